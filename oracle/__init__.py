@@ -1,0 +1,199 @@
+"""CPU oracle for the SQAP-VLA hot path: TEST INFRASTRUCTURE ONLY.
+
+Thin numpy/ctypes marshalling around ``sqap_oracle.c`` (plain C, written from
+the paper, arXiv 2509.09090).  Nothing here is imported by the product package
+and nothing here imports it.  Allowed callers: ``tests/``, the smoke check and
+the benchmark's ``cpu_baseline`` leg.
+
+Half-precision arrays are ``numpy.float16``; they cross into C as their uint16
+bit patterns.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sqap_oracle.c")
+_LIB = os.path.join(_HERE, "libsqap_oracle.so")
+
+ROTATE_HADAMARD = 1
+
+
+def build(force=False):
+    """Compile the oracle with the host C compiler (no GPU code involved)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC",
+           "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_f16_to_f32.restype = ctypes.c_float
+        _lib.oracle_f16_to_f32.argtypes = [ctypes.c_uint16]
+        _lib.oracle_f32_to_f16.restype = ctypes.c_uint16
+        _lib.oracle_f32_to_f16.argtypes = [ctypes.c_float]
+        _lib.oracle_int_gemm.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def set_threads(n):
+    """Number of OpenMP threads the row loops may use (returns the old value)."""
+    omp = ctypes.CDLL("libgomp.so.1")
+    old = omp.omp_get_max_threads()
+    omp.omp_set_num_threads(int(n))
+    return old
+
+
+def f16_to_f32(bits):
+    return float(lib().oracle_f16_to_f32(int(bits)))
+
+
+def f32_to_f16(x):
+    return int(lib().oracle_f32_to_f16(ctypes.c_float(x)))
+
+
+def prune_topk(scores, keep_k):
+    """Eq. 1: indices of the keep_k largest scores of each row, ascending."""
+    s = _c(scores, np.float32)
+    one = s.ndim == 1
+    s2 = s.reshape(1, -1) if one else s
+    b, n = s2.shape
+    out = np.empty((b, keep_k), dtype=np.int32)
+    rc = lib().oracle_prune_topk(_p(s2), b, n, int(keep_k), _p(out))
+    if rc != 0:
+        raise ValueError("oracle_prune_topk: status %d" % rc)
+    return out[0] if one else out
+
+
+def kept_rows(idx, seq_len, vis_begin, n_vis):
+    """Surviving sequence rows (global over the batch) in original order."""
+    i2 = _c(idx, np.int32)
+    if i2.ndim == 1:
+        i2 = i2.reshape(1, -1)
+    b, k = i2.shape
+    out = np.empty(b * (seq_len - n_vis + k), dtype=np.int32)
+    rc = lib().oracle_kept_rows(_p(i2), b, k, int(seq_len), int(vis_begin), int(n_vis),
+                                _p(out))
+    if rc != 0:
+        raise ValueError("oracle_kept_rows: status %d" % rc)
+    return out
+
+
+def gather_rows(X, rows):
+    X = _c(X, np.float16)
+    rows = _c(rows, np.int32)
+    out = np.empty((rows.size, X.shape[1]), dtype=np.float16)
+    lib().oracle_gather_rows(_p(X), ctypes.c_int64(X.shape[1]), _p(rows), rows.size,
+                             X.shape[1], _p(out), ctypes.c_int64(X.shape[1]))
+    return out
+
+
+def fwht(v):
+    """Eq. 6 rotation of one binary32 vector (copy)."""
+    v = np.array(v, dtype=np.float32, copy=True)
+    rc = lib().oracle_fwht_f32(_p(v), v.size)
+    if rc != 0:
+        raise ValueError("oracle_fwht_f32: status %d" % rc)
+    return v
+
+
+def quantize_rows(X, rows=None, rotate=False):
+    """Per-row symmetric int4: returns (packed [M,K/2] u8, scale [M] f16, rowsum [M] i32)."""
+    X = _c(X, np.float16)
+    K = X.shape[1]
+    r = None if rows is None else _c(rows, np.int32)
+    M = X.shape[0] if r is None else r.size
+    q = np.empty((M, K // 2), dtype=np.uint8)
+    s = np.empty(M, dtype=np.float16)
+    rs = np.empty(M, dtype=np.int32)
+    rc = lib().oracle_quantize_rows(_p(X), ctypes.c_int64(K), _p(r), M, K,
+                                    1 if rotate else 0, _p(q), _p(s), _p(rs))
+    if rc != 0:
+        raise ValueError("oracle_quantize_rows: status %d" % rc)
+    return q, s, rs
+
+
+def unpack_int4(Q):
+    Q = _c(Q, np.uint8)
+    R, half = Q.shape
+    out = np.empty((R, 2 * half), dtype=np.int8)
+    lib().oracle_unpack_int4(_p(Q), R, 2 * half, _p(out))
+    return out
+
+
+def int_gemm(Xq, Wq):
+    """Exact acc[m,n] = sum_k xq[m,k]*wq[n,k]; raises if int32 != int64 anywhere."""
+    Xq = _c(Xq, np.uint8)
+    Wq = _c(Wq, np.uint8)
+    M, half = Xq.shape
+    N = Wq.shape[0]
+    assert Wq.shape[1] == half
+    acc = np.empty((M, N), dtype=np.int32)
+    bad = lib().oracle_int_gemm(_p(Xq), _p(Wq), M, N, 2 * half, _p(acc))
+    if bad != 0:
+        raise ArithmeticError("int32 and int64 accumulators differ (%d)" % bad)
+    return acc
+
+
+def dequant(acc, sx, sw):
+    acc = _c(acc, np.int32)
+    sx = _c(sx, np.float16)
+    sw = _c(sw, np.float16)
+    M, N = acc.shape
+    Y = np.empty((M, N), dtype=np.float16)
+    lib().oracle_dequant(_p(acc), _p(sx), _p(sw), M, N, _p(Y), ctypes.c_int64(N))
+    return Y
+
+
+def w4a4_linear(Xq, sx, Wq, sw):
+    """Returns (Y fp16 [M,N], acc int32 [M,N])."""
+    acc = int_gemm(Xq, Wq)
+    return dequant(acc, sx, sw), acc
+
+
+def linear_samples(Xq, sx, Wq, sw, ms, ns):
+    """acc and Y at chosen (m, n) positions only."""
+    Xq = _c(Xq, np.uint8)
+    Wq = _c(Wq, np.uint8)
+    sx = _c(sx, np.float16)
+    sw = _c(sw, np.float16)
+    ms = _c(ms, np.int32)
+    ns = _c(ns, np.int32)
+    acc = np.empty(ms.size, dtype=np.int32)
+    y = np.empty(ms.size, dtype=np.float16)
+    lib().oracle_linear_samples(_p(Xq), _p(sx), _p(Wq), _p(sw), 2 * Xq.shape[1],
+                                _p(ms), _p(ns), ms.size, _p(acc), _p(y))
+    return acc, y
+
+
+def attn_scores(q, k, vis_begin, n_vis):
+    """Retention score a_q of the visual span: q [H,d], k [S,H,d] (fp16)."""
+    q = _c(q, np.float16)
+    k = _c(k, np.float16)
+    S, H, d = k.shape
+    out = np.empty(n_vis, dtype=np.float32)
+    rc = lib().oracle_attn_scores(_p(q), _p(k), S, H, d, int(vis_begin), int(n_vis),
+                                  _p(out))
+    if rc != 0:
+        raise ValueError("oracle_attn_scores: status %d" % rc)
+    return out

@@ -1,0 +1,395 @@
+/*
+ * CPU oracle for the SQAP-VLA hot path: TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain C, one loop nest per definition, no blocking, no fusion.  It exists so
+ * that the HIP library can be checked element by element; it shares no code,
+ * header, table or helper with that library and must never be called by it.
+ * Only the test-suite, the smoke check and the benchmark's cpu_baseline leg
+ * may load this object.
+ *
+ * Every function names the passage of the paper (arXiv 2509.09090) it follows.
+ * Where the paper leaves arithmetic open (int4 range, rounding, scale format)
+ * the reading taken is written next to the code.
+ *
+ * Half-precision values cross this interface as IEEE binary16 bit patterns in
+ * uint16_t, because the host compiler has no half type.
+ *
+ * Parity pins: every function below is pinned by tests that do not re-type its
+ * formula (stable library sort, numpy integer matmul, numpy half conversion,
+ * dense Sylvester matrix product, closed forms, brute force).  The one
+ * exception is oracle_attn_scores: its arithmetic is pinned (generic softmax
+ * attention row), but WHICH layer, query token and head aggregation define
+ * the retention score is not fixed by the paper: "parity unpinned" for that
+ * choice.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* binary16 <-> binary32, written out bit by bit                       */
+/* ------------------------------------------------------------------ */
+
+float oracle_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    uint32_t exp = (uint32_t)(h >> 10) & 0x1fu;
+    uint32_t man = (uint32_t)h & 0x3ffu;
+    double v;
+    if (exp == 0x1fu) {
+        if (man != 0) return sign ? -NAN : NAN;
+        v = INFINITY;
+    } else if (exp == 0) {
+        v = ldexp((double)man, -24);            /* subnormal: man * 2^-24 */
+    } else {
+        v = ldexp((double)(man + 1024u), (int)exp - 25);
+    }
+    return (float)(sign ? -v : v);              /* exact: 11 significant bits */
+}
+
+/* round-to-nearest-even conversion, subnormals kept, overflow to infinity */
+uint16_t oracle_f32_to_f16(float f)
+{
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    uint16_t sign = (uint16_t)((bits >> 16) & 0x8000u);
+    if (isnan(f)) return (uint16_t)(sign | 0x7e00u);
+    double a = fabs((double)f);
+    if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u);   /* rounds to inf */
+    if (a == 0.0) return sign;
+    int e;
+    (void)frexp(a, &e);                         /* a = m * 2^e, m in [0.5,1) */
+    int ulp_exp = e - 11;                       /* 11 significant bits        */
+    if (ulp_exp < -24) ulp_exp = -24;           /* subnormal spacing          */
+    double q = ldexp(a, -ulp_exp);              /* exact scaling              */
+    double r = nearbyint(q);                    /* default mode: ties to even */
+    double rounded = ldexp(r, ulp_exp);
+    /* re-encode the rounded value (it is representable by construction) */
+    if (rounded >= 65520.0) return (uint16_t)(sign | 0x7c00u);
+    if (rounded < ldexp(1.0, -14)) {
+        return (uint16_t)(sign | (uint16_t)ldexp(rounded, 24));
+    }
+    int e2;
+    double m2 = frexp(rounded, &e2);            /* m2 in [0.5,1) */
+    uint32_t man = (uint32_t)ldexp(m2, 11) - 1024u;
+    uint32_t ex = (uint32_t)(e2 - 1 + 15);
+    return (uint16_t)(sign | (ex << 10) | man);
+}
+
+/* ------------------------------------------------------------------ */
+/* Strategy 1, Eq. 1: K_attn = Top_k(a_q, k)                           */
+/* ------------------------------------------------------------------ */
+/*
+ * Reading of what Eq. 1 leaves open: the set is made unique by the total
+ * order "larger score first, equal scores: lower index first"; -0 equals +0;
+ * NaN ranks below every number; the kept indices are returned ascending.
+ */
+static int ranks_before(float sa, int ia, float sb, int ib)
+{
+    int na = isnan(sa), nb = isnan(sb);
+    if (na || nb) {
+        if (na && nb) return ia < ib;
+        return nb;                     /* a number ranks before a NaN */
+    }
+    if (sa > sb) return 1;
+    if (sa < sb) return 0;
+    return ia < ib;
+}
+
+int oracle_prune_topk(const float *scores, int batch, int n_tokens, int keep_k,
+                      int32_t *idx_out)
+{
+    if (batch < 0 || n_tokens < 0 || keep_k < 0 || keep_k > n_tokens) return -1;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n_tokens > 0 ? n_tokens : 1));
+    if (!order) return -4;
+    for (int b = 0; b < batch; ++b) {
+        const float *s = scores + (size_t)b * n_tokens;
+        /* full insertion sort into descending rank order */
+        for (int i = 0; i < n_tokens; ++i) {
+            int j = i;
+            while (j > 0 && ranks_before(s[i], i, s[order[j - 1]], order[j - 1])) {
+                order[j] = order[j - 1];
+                --j;
+            }
+            order[j] = i;
+        }
+        /* first keep_k of that order, reported by ascending index */
+        int32_t *out = idx_out + (size_t)b * keep_k;
+        for (int i = 0; i < keep_k; ++i) {
+            int j = i;
+            while (j > 0 && out[j - 1] > order[i]) {
+                out[j] = out[j - 1];
+                --j;
+            }
+            out[j] = order[i];
+        }
+    }
+    free(order);
+    return 0;
+}
+
+/*
+ * Section 3.2, last paragraph: the kept visual tokens shorten the sequence.
+ * Reading: the surviving sequence keeps the original order; every token
+ * outside the visual span [vis_begin, vis_begin+n_vis) is kept.  Row numbers
+ * are global over the batch: observation b starts at row b*seq_len.
+ * rows_out has batch*(seq_len-n_vis+keep_k) entries.
+ */
+int oracle_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
+                     int vis_begin, int n_vis, int32_t *rows_out)
+{
+    if (batch < 0 || keep_k < 0 || keep_k > n_vis || vis_begin < 0 ||
+        vis_begin + n_vis > seq_len)
+        return -1;
+    size_t o = 0;
+    for (int b = 0; b < batch; ++b) {
+        for (int s = 0; s < seq_len; ++s) {
+            int keep = 1;
+            if (s >= vis_begin && s < vis_begin + n_vis) {
+                keep = 0;
+                for (int i = 0; i < keep_k; ++i)
+                    if (idx[(size_t)b * keep_k + i] == s - vis_begin) keep = 1;
+            }
+            if (keep) rows_out[o++] = b * seq_len + s;
+        }
+    }
+    return 0;
+}
+
+/* gather: out[i,:] = X[rows[i],:], a bit copy of half-precision rows */
+int oracle_gather_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, int M,
+                       int K, uint16_t *out, int64_t ldo)
+{
+    for (int i = 0; i < M; ++i)
+        for (int k = 0; k < K; ++k)
+            out[(size_t)i * ldo + k] = X[(size_t)rows[i] * ldx + k];
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 3.3, Eq. 6: rotation by the Hadamard matrix H               */
+/* ------------------------------------------------------------------ */
+/*
+ * Reading: H is the Sylvester (natural-order) Walsh-Hadamard matrix scaled by
+ * 1/sqrt(K) so that H^T H = I as Eq. 6 needs.  Arithmetic fixed so that a
+ * parallel implementation can agree to the bit: binary32 butterflies, stage
+ * distance h = 1, 2, 4, ..., K/2 in that order, (a,b) -> (a+b, a-b) with a
+ * the lower index, then one multiply by (float)(1/sqrt(K)).
+ */
+int oracle_fwht_f32(float *v, int K)
+{
+    if (K <= 0 || (K & (K - 1)) != 0) return -2;
+    for (int h = 1; h < K; h *= 2) {
+        for (int base = 0; base < K; base += 2 * h) {
+            for (int j = base; j < base + h; ++j) {
+                float a = v[j], b = v[j + h];
+                v[j] = a + b;
+                v[j + h] = a - b;
+            }
+        }
+    }
+    float c = (float)(1.0 / sqrt((double)K));
+    for (int j = 0; j < K; ++j) v[j] = v[j] * c;
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* 4-bit symmetric quantizer, one scale per row                        */
+/* (Section 3.3 / Implementation Details: W4A4; the arithmetic is a    */
+/* reading: divisor 7, ties-to-even, binary16 scale, no zero point)    */
+/* ------------------------------------------------------------------ */
+/*
+ * For each output row i (a token for activations, an output channel for
+ * weights), taken from source row rows[i] (or i when rows is NULL):
+ *   v      = binary32 of the row, rotated by oracle_fwht_f32 when rotate != 0
+ *   amax   = max_k |v_k|
+ *   scale  = binary16(amax / 7), raised to the smallest subnormal 2^-24 if 0
+ *   q_k    = clamp(rint(v_k / (float)scale), -8, 7)
+ *   byte j = (q_{2j} & 15) | (q_{2j+1} & 15) << 4        (two's complement)
+ *   rowsum = sum_k q_k
+ */
+int oracle_quantize_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, int M,
+                         int K, int rotate, uint8_t *Xq, uint16_t *scale_out,
+                         int32_t *rowsum_out)
+{
+    if (M < 0 || K <= 0 || (K & 1)) return -1;
+    if (rotate && (K & (K - 1)) != 0) return -2;
+    int status = 0;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i) {
+        float *v = (float *)malloc(sizeof(float) * (size_t)K);
+        if (!v) {
+            status = -4;
+            continue;
+        }
+        size_t src = rows ? (size_t)rows[i] : (size_t)i;
+        for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
+        if (rotate) oracle_fwht_f32(v, K);
+        float amax = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            float a = fabsf(v[k]);
+            if (a > amax) amax = a;
+        }
+        uint16_t sh = oracle_f32_to_f16(amax / 7.0f);
+        if (sh == 0) sh = 1;                     /* 2^-24: keeps the scale positive */
+        float sf = oracle_f16_to_f32(sh);
+        int32_t sum = 0;
+        for (int k = 0; k < K; k += 2) {
+            int q[2];
+            for (int t = 0; t < 2; ++t) {
+                float r = rintf(v[k + t] / sf);
+                if (r > 7.0f) r = 7.0f;
+                if (r < -8.0f) r = -8.0f;
+                q[t] = (int)r;
+                sum += q[t];
+            }
+            Xq[(size_t)i * (K / 2) + k / 2] =
+                (uint8_t)((q[0] & 15) | ((q[1] & 15) << 4));
+        }
+        scale_out[i] = sh;
+        if (rowsum_out) rowsum_out[i] = sum;
+        free(v);
+    }
+    return status;
+}
+
+/* signed value of nibble number k of a packed row */
+static inline int nibble(const uint8_t *row, int k)
+{
+    int b = row[k >> 1];
+    int u = (k & 1) ? (b >> 4) : (b & 15);
+    return u >= 8 ? u - 16 : u;
+}
+
+/* unpack a packed row matrix to one int8 per code (helper for the GEMM) */
+int oracle_unpack_int4(const uint8_t *Q, int R, int K, int8_t *out)
+{
+    for (int r = 0; r < R; ++r)
+        for (int k = 0; k < K; ++k)
+            out[(size_t)r * K + k] = (int8_t)nibble(Q + (size_t)r * (K / 2), k);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* W4A4 linear: exact integer contraction, then dequantisation         */
+/* ------------------------------------------------------------------ */
+/*
+ * acc[m,n] = sum_k xq[m,k] * wq[n,k], accumulated both in int32 and in int64;
+ * returns the number of entries where the two disagree (must be 0).
+ */
+int64_t oracle_int_gemm(const uint8_t *Xq, const uint8_t *Wq, int M, int N, int K,
+                        int32_t *acc)
+{
+    int8_t *x = (int8_t *)malloc((size_t)(M > 0 ? M : 1) * K);
+    int8_t *w = (int8_t *)malloc((size_t)(N > 0 ? N : 1) * K);
+    if (!x || !w) {
+        free(x);
+        free(w);
+        return -4;
+    }
+    oracle_unpack_int4(Xq, M, K, x);
+    oracle_unpack_int4(Wq, N, K, w);
+    int64_t bad = 0;
+#pragma omp parallel for schedule(static) reduction(+ : bad)
+    for (int n = 0; n < N; ++n) {
+        for (int m = 0; m < M; ++m) {
+            int32_t s32 = 0;
+            int64_t s64 = 0;
+            const int8_t *xr = x + (size_t)m * K, *wr = w + (size_t)n * K;
+            for (int k = 0; k < K; ++k) {
+                int p = (int)xr[k] * (int)wr[k];
+                s32 += p;
+                s64 += p;
+            }
+            if ((int64_t)s32 != s64) ++bad;
+            acc[(size_t)m * N + n] = s32;
+        }
+    }
+    free(x);
+    free(w);
+    return bad;
+}
+
+/* Y[m,n] = binary16( ((float)acc * sx[m]) * sw[n] ), two binary32 products */
+int oracle_dequant(const int32_t *acc, const uint16_t *sx, const uint16_t *sw, int M,
+                   int N, uint16_t *Y, int64_t ldy)
+{
+    for (int m = 0; m < M; ++m) {
+        float a = oracle_f16_to_f32(sx[m]);
+        for (int n = 0; n < N; ++n) {
+            float t = (float)acc[(size_t)m * N + n] * a;
+            float y = t * oracle_f16_to_f32(sw[n]);
+            Y[(size_t)m * ldy + n] = oracle_f32_to_f16(y);
+        }
+    }
+    return 0;
+}
+
+/*
+ * The same two definitions evaluated only at chosen output positions
+ * (ms[i], ns[i]); used where the full product is too slow to form.
+ */
+int oracle_linear_samples(const uint8_t *Xq, const uint16_t *sx, const uint8_t *Wq,
+                          const uint16_t *sw, int K, const int32_t *ms,
+                          const int32_t *ns, int count, int32_t *acc_out,
+                          uint16_t *y_out)
+{
+    for (int i = 0; i < count; ++i) {
+        const uint8_t *xr = Xq + (size_t)ms[i] * (K / 2);
+        const uint8_t *wr = Wq + (size_t)ns[i] * (K / 2);
+        int64_t s = 0;
+        for (int k = 0; k < K; ++k) s += (int64_t)nibble(xr, k) * nibble(wr, k);
+        acc_out[i] = (int32_t)s;
+        float t = (float)(int32_t)s * oracle_f16_to_f32(sx[ms[i]]);
+        y_out[i] = oracle_f32_to_f16(t * oracle_f16_to_f32(sw[ns[i]]));
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Retention score a_q (Strategy 1 text; Section 3.3: Q, K from X)     */
+/* ------------------------------------------------------------------ */
+/*
+ * Reading: the task-query token is one query vector per head q[h,:]; the
+ * score of visual token j is its softmax attention weight over all S keys,
+ * averaged over the H heads.  Double precision throughout.
+ *   l[h,s] = (q[h,:] . k[s,h,:]) / sqrt(d)
+ *   p[h,:] = softmax_s(l[h,:])
+ *   score[j] = (1/H) sum_h p[h, vis_begin + j]
+ */
+int oracle_attn_scores(const uint16_t *q, const uint16_t *k, int S, int H, int d,
+                       int vis_begin, int n_vis, float *scores_out)
+{
+    if (S <= 0 || H <= 0 || d <= 0 || vis_begin < 0 || n_vis < 0 ||
+        vis_begin + n_vis > S)
+        return -1;
+    double *p = (double *)malloc(sizeof(double) * (size_t)S);
+    double *acc = (double *)calloc((size_t)(n_vis > 0 ? n_vis : 1), sizeof(double));
+    if (!p || !acc) {
+        free(p);
+        free(acc);
+        return -4;
+    }
+    for (int h = 0; h < H; ++h) {
+        double lmax = -INFINITY;
+        for (int s = 0; s < S; ++s) {
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i)
+                dot += (double)oracle_f16_to_f32(q[(size_t)h * d + i]) *
+                       (double)oracle_f16_to_f32(k[((size_t)s * H + h) * d + i]);
+            p[s] = dot / sqrt((double)d);
+            if (p[s] > lmax) lmax = p[s];
+        }
+        double z = 0.0;
+        for (int s = 0; s < S; ++s) {
+            p[s] = exp(p[s] - lmax);
+            z += p[s];
+        }
+        for (int j = 0; j < n_vis; ++j) acc[j] += p[vis_begin + j] / z;
+    }
+    for (int j = 0; j < n_vis; ++j) scores_out[j] = (float)(acc[j] / (double)H);
+    free(p);
+    free(acc);
+    return 0;
+}

@@ -1,0 +1,441 @@
+"""Pins for the CPU oracle: it is checked against things other than itself
+(library routines, closed forms, brute force, fixed values) so that a dropped
+term, a wrong sign or index, or a transposed operand fails here.  No GPU."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import scipy.linalg
+import scipy.special
+
+from paper_2509_09090_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+# ------------------------------------------------------------------ half
+def test_f16_to_f32_all_bit_patterns(oracle):
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float32)
+    got = np.array([oracle.f16_to_f32(int(b)) for b in bits], dtype=np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+
+
+def test_f32_to_f16_golden_cases(oracle):
+    with open(os.path.join(GOLDEN, "half_rounding_cases.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            a, b = line.split()[:2]
+            x = np.array([int(a, 16)], dtype=np.uint32).view(np.float32)[0]
+            assert oracle.f32_to_f16(float(x)) == int(b, 16), line
+
+
+def test_f32_to_f16_matches_numpy(oracle):
+    rng = np.random.default_rng(1)
+    # random bit patterns around the half range plus every half value +- 1 float ulp
+    xs = [rng.standard_normal(20000).astype(np.float32) * np.float32(s)
+          for s in (1e-7, 1e-5, 1e-3, 1.0, 300.0, 40000.0)]
+    h = np.arange(0x7c00, dtype=np.uint16).view(np.float16).astype(np.float32)
+    mids = ((h[:-1].astype(np.float64) + h[1:].astype(np.float64)) / 2).astype(np.float32)
+    xs += [h, -h, mids, np.nextafter(mids, np.float32(np.inf)),
+           np.nextafter(mids, np.float32(-np.inf))]
+    x = np.concatenate(xs)
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.f32_to_f16(float(v)) for v in x], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ top-k
+def _library_topk(s, k):
+    """Stable library sort on descending score: ties keep the lower index first,
+    NaN sorts last."""
+    order = np.argsort(-s.astype(np.float64), kind="stable")
+    return np.sort(order[:k]).astype(np.int32)
+
+
+def _rank_brute(s, k):
+    """Brute force from the definition of the total order (O(n^2))."""
+    n = len(s)
+    kept = []
+    for i in range(n):
+        ahead = 0
+        for j in range(n):
+            if j == i:
+                continue
+            si, sj = s[i], s[j]
+            if np.isnan(sj):
+                before = np.isnan(si) and j < i
+            elif np.isnan(si):
+                before = True
+            else:
+                before = sj > si or (sj == si and j < i)
+            ahead += bool(before)
+        if ahead < k:
+            kept.append(i)
+    return np.array(kept, dtype=np.int32)
+
+
+@pytest.mark.parametrize("n,k", [(1, 0), (1, 1), (7, 3), (64, 32), (256, 128), (256, 64),
+                                 (256, 0), (256, 256), (255, 254), (300, 1), (1000, 17)])
+def test_topk_random_vs_stable_sort(oracle, n, k):
+    rng = np.random.default_rng(n * 1000 + k)
+    s = rng.random((5, n), dtype=np.float32)
+    got = oracle.prune_topk(s, k)
+    assert got.shape == (5, k)
+    for b in range(5):
+        assert np.array_equal(got[b], _library_topk(s[b], k))
+
+
+def test_topk_adversarial(oracle):
+    n = 64
+    cases = {
+        "all_equal": np.full(n, 0.5, np.float32),
+        "two_valued": np.tile(np.array([1.0, 0.0], np.float32), n // 2),
+        "descending": np.linspace(1, 0, n).astype(np.float32),
+        "ascending": np.linspace(0, 1, n).astype(np.float32),
+        "dups_at_cut": np.repeat(np.arange(n // 4, dtype=np.float32), 4),
+        "signed_zero": np.array([0.0, -0.0] * (n // 2), np.float32),
+        "with_nan": np.where(np.arange(n) % 5 == 0, np.nan, np.arange(n) % 7).astype(np.float32),
+        "all_nan": np.full(n, np.nan, np.float32),
+        "infs": np.array([np.inf, -np.inf, 1.0, np.inf] * (n // 4), np.float32),
+        "negatives": -np.arange(n, dtype=np.float32),
+    }
+    for name, s in cases.items():
+        for k in (0, 1, 2, 31, 32, 33, n - 1, n):
+            got = oracle.prune_topk(s, k)
+            assert np.array_equal(got, _library_topk(s, k)), (name, k)
+            assert np.array_equal(got, _rank_brute(s, k)), (name, k)
+
+
+def test_topk_invariants(oracle):
+    rng = np.random.default_rng(3)
+    s = np.round(rng.random((8, 256)) * 20).astype(np.float32) / 20   # many duplicates
+    k = 100
+    got = oracle.prune_topk(s, k)
+    for b in range(8):
+        idx = got[b]
+        assert len(idx) == k and np.all(np.diff(idx) > 0)
+        dropped = np.setdiff1d(np.arange(256), idx)
+        assert s[b, idx].min() >= s[b, dropped].max()
+        cut = s[b, idx].min()
+        kept_at_cut = idx[s[b, idx] == cut]
+        dropped_at_cut = dropped[s[b, dropped] == cut]
+        if len(dropped_at_cut):
+            assert kept_at_cut.max() < dropped_at_cut.min()
+
+
+def test_topk_all_equal_keeps_prefix(oracle):
+    assert np.array_equal(oracle.prune_topk(np.zeros(10, np.float32), 4), np.arange(4))
+
+
+def test_topk_rejects_keep_above_n(oracle):
+    with pytest.raises(ValueError):
+        oracle.prune_topk(np.zeros(4, np.float32), 5)
+
+
+# ------------------------------------------------------------------ rows / gather
+def test_kept_rows_and_gather(oracle):
+    rng = np.random.default_rng(4)
+    B, S, v0, nv, k = 3, 30, 4, 16, 5
+    idx = np.stack([np.sort(rng.choice(nv, k, replace=False)) for _ in range(B)]).astype(np.int32)
+    rows = oracle.kept_rows(idx, S, v0, nv)
+    assert rows.size == B * (S - nv + k)
+    assert np.all(np.diff(rows) > 0)                      # original order kept
+    for b in range(B):
+        mine = rows[(rows >= b * S) & (rows < (b + 1) * S)] - b * S
+        text = np.concatenate([np.arange(0, v0), np.arange(v0 + nv, S)])
+        want = np.sort(np.concatenate([text, idx[b] + v0]))
+        assert np.array_equal(mine, want)
+    X = rng.standard_normal((B * S, 12)).astype(np.float16)
+    out = oracle.gather_rows(X, rows)
+    assert np.array_equal(out.view(np.uint16), X[rows].view(np.uint16))
+
+
+# ------------------------------------------------------------------ Hadamard
+def test_sylvester_fixture_is_what_scipy_builds():
+    H = np.loadtxt(os.path.join(GOLDEN, "sylvester_h8.txt"))
+    assert np.array_equal(H, scipy.linalg.hadamard(8))
+
+
+def test_fwht_matches_fixture_matrix(oracle):
+    H = np.loadtxt(os.path.join(GOLDEN, "sylvester_h8.txt"))
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal(8)
+    got = oracle.fwht(x)
+    assert np.allclose(got, H @ x.astype(np.float32).astype(np.float64) / np.sqrt(8), atol=1e-6)
+
+
+@pytest.mark.parametrize("K", [1, 2, 4, 16, 64, 512, 4096])
+def test_fwht_vs_dense_product(oracle, K):
+    rng = np.random.default_rng(K)
+    x = rng.standard_normal(K).astype(np.float32)
+    want = scipy.linalg.hadamard(K).astype(np.float64) @ x.astype(np.float64) / np.sqrt(K)
+    got = oracle.fwht(x)
+    assert np.allclose(got, want, atol=2e-5 * np.sqrt(np.log2(K) + 1))
+    # involution (H/sqrt K is symmetric orthogonal) and Parseval
+    assert np.allclose(oracle.fwht(got), x, atol=1e-4)
+    assert np.isclose(np.linalg.norm(got.astype(np.float64)), np.linalg.norm(x.astype(np.float64)),
+                      rtol=1e-5)
+
+
+def test_fwht_unit_vectors(oracle):
+    K = 64
+    H = scipy.linalg.hadamard(K)
+    for j in (0, 1, 5, 63):
+        e = np.zeros(K, np.float32)
+        e[j] = 1
+        assert np.array_equal(oracle.fwht(e), (H[:, j] / 8.0).astype(np.float32))
+
+
+def test_fwht_rejects_non_power_of_two(oracle):
+    with pytest.raises(ValueError):
+        oracle.fwht(np.zeros(12, np.float32))
+
+
+def test_rotation_leaves_the_linear_unchanged(oracle):
+    """Eq. 6: (W H^T)(H x) = W x with the orthonormal H."""
+    rng = np.random.default_rng(6)
+    K, N = 256, 8
+    x = rng.standard_normal(K).astype(np.float32)
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    xr = oracle.fwht(x).astype(np.float64)
+    Wr = np.stack([oracle.fwht(W[n]) for n in range(N)]).astype(np.float64)
+    assert np.allclose(Wr @ xr, W.astype(np.float64) @ x.astype(np.float64), atol=1e-3)
+
+
+# ------------------------------------------------------------------ quantizer
+def _codes(oracle, q):
+    return oracle.unpack_int4(q).astype(np.int32)
+
+
+def test_unpack_layout_low_nibble_first(oracle):
+    q = np.array([[0x21, 0xF8, 0x7F]], dtype=np.uint8)
+    assert np.array_equal(oracle.unpack_int4(q), [[1, 2, -8, -1, -1, 7]])
+
+
+def test_quantizer_error_bound_and_range(oracle):
+    X, _ = wl.activations(64, 512, 4, 20.0, np.random.default_rng(7))
+    q, s, rs = oracle.quantize_rows(X)
+    c = _codes(oracle, q)
+    sf = s.astype(np.float64)[:, None]
+    err = np.abs(c * sf - X.astype(np.float64))
+    assert np.all(err <= sf / 2 * (1 + 1e-6))
+    assert c.min() >= -7 and c.max() <= 7
+    amax_pos = np.argmax(np.abs(X.astype(np.float32)), axis=1)
+    assert np.all(np.abs(c[np.arange(64), amax_pos]) == 7)
+    assert np.array_equal(rs, c.sum(axis=1))
+    # the scale is the half nearest to amax/7
+    amax = np.abs(X.astype(np.float32)).max(axis=1)
+    assert np.array_equal(s.view(np.uint16), (amax / np.float32(7)).astype(np.float16).view(np.uint16))
+
+
+def test_quantizer_sign_symmetry_and_power_of_two_scaling(oracle):
+    X, _ = wl.activations(16, 128, 2, 20.0, np.random.default_rng(8))
+    q, s, _ = oracle.quantize_rows(X)
+    qn, sn, _ = oracle.quantize_rows(-X)
+    assert np.array_equal(_codes(oracle, qn), -_codes(oracle, q))
+    assert np.array_equal(sn, s)
+    for p in (-4, 3):                       # stays in the normal half range
+        Xs = (X.astype(np.float32) * np.float32(2.0 ** p)).astype(np.float16)
+        qs, ss, _ = oracle.quantize_rows(Xs)
+        assert np.array_equal(_codes(oracle, qs), _codes(oracle, q))
+        assert np.array_equal(ss.astype(np.float32), s.astype(np.float32) * np.float32(2.0 ** p))
+
+
+def test_quantizer_every_finite_half_as_a_row(oracle):
+    """Rows (x, 0) for every finite half x: error bound, +-7 mapping, symmetry."""
+    bits = np.arange(0x7c00, dtype=np.uint16)
+    x = bits.view(np.float16)
+    X = np.stack([x, np.zeros_like(x)], axis=1)
+    q, s, _ = oracle.quantize_rows(X)
+    c = _codes(oracle, q)
+    assert np.all(c[:, 1] == 0)
+    sf = s.astype(np.float64)
+    assert np.all(sf > 0)
+    normal_scale = sf >= 2.0 ** -14
+    assert np.all(c[normal_scale, 0] == 7)
+    err = np.abs(c[:, 0] * sf - x.astype(np.float64))
+    assert np.all(err[normal_scale] <= sf[normal_scale] / 2)
+    # below the normal range the scale has few bits; the code is then clamped at 7
+    assert np.all((c[:, 0] >= 0) & (c[:, 0] <= 7))
+    assert c[0, 0] == 0 and bits[0] == 0 and s.view(np.uint16)[0] == 1   # all-zero row
+    qn, sn, _ = oracle.quantize_rows(-X)
+    # (the clamp range [-8, 7] is not symmetric, so only where no clamp bites)
+    assert np.array_equal(_codes(oracle, qn)[normal_scale], -c[normal_scale])
+    assert np.array_equal(sn, s)
+    assert _codes(oracle, qn).min() >= -8
+
+
+def test_quantizer_pairs_of_halves(oracle):
+    """Rows (x, y) for sampled pairs: the smaller element obeys the error bound."""
+    rng = np.random.default_rng(9)
+    b = rng.integers(0x0400, 0x7bff, size=(20000, 2)).astype(np.uint16)
+    b |= (rng.integers(0, 2, size=b.shape).astype(np.uint16) << 15)
+    X = b.view(np.float16)
+    q, s, _ = oracle.quantize_rows(X)
+    c = _codes(oracle, q)
+    sf = s.astype(np.float64)[:, None]
+    ok = sf[:, 0] >= 2.0 ** -14
+    err = np.abs(c * sf - X.astype(np.float64))
+    assert np.all(err[ok] <= sf[ok] / 2 * (1 + 1e-6))
+    assert np.all(np.abs(c).max(axis=1)[ok] == 7)
+
+
+def test_quantizer_half_way_cases_round_to_even(oracle):
+    # scale exactly 1 (amax 7): 0.5 -> 0, 1.5 -> 2, 2.5 -> 2, -3.5 -> -4, 6.5 -> 6
+    X = np.array([[7, 0.5, 1.5, 2.5, -3.5, 6.5, -0.5, 4.5]], dtype=np.float16)
+    q, s, _ = oracle.quantize_rows(X)
+    assert float(s[0]) == 1.0
+    assert np.array_equal(_codes(oracle, q), [[7, 0, 2, 2, -4, 6, 0, 4]])
+
+
+def test_quantizer_rows_argument_is_a_gather(oracle):
+    X, _ = wl.activations(40, 64, 1, 20.0, np.random.default_rng(10))
+    rows = np.array([5, 3, 39, 0, 5], dtype=np.int32)
+    q1, s1, r1 = oracle.quantize_rows(X, rows=rows)
+    q2, s2, r2 = oracle.quantize_rows(X[rows])
+    assert np.array_equal(q1, q2) and np.array_equal(s1, s2) and np.array_equal(r1, r2)
+
+
+def test_rotation_reduces_quantisation_error_on_outlier_channels(oracle):
+    """Section 3.3: rotating spreads the outlier energy, so int4 error falls."""
+    X, _ = wl.activations(32, 1024, 10, 30.0, np.random.default_rng(11))
+    xf = X.astype(np.float64)
+    q0, s0, _ = oracle.quantize_rows(X)
+    e0 = np.linalg.norm(_codes(oracle, q0) * s0.astype(np.float64)[:, None] - xf)
+    q1, s1, _ = oracle.quantize_rows(X, rotate=True)
+    xr = np.stack([oracle.fwht(X[i].astype(np.float32)) for i in range(32)]).astype(np.float64)
+    e1 = np.linalg.norm(_codes(oracle, q1) * s1.astype(np.float64)[:, None] - xr)
+    assert e1 < 0.6 * e0        # norms are equal (orthonormal H), so errors compare directly
+    with pytest.raises(ValueError):
+        oracle.quantize_rows(X[:, :1000], rotate=True)
+
+
+# ------------------------------------------------------------------ GEMM + epilogue
+def test_int_gemm_vs_numpy_int64(oracle):
+    rng = np.random.default_rng(12)
+    M, N, K = 13, 21, 96
+    Xq = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    Wq = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    acc = oracle.int_gemm(Xq, Wq)
+    want = oracle.unpack_int4(Xq).astype(np.int64) @ oracle.unpack_int4(Wq).astype(np.int64).T
+    assert np.array_equal(acc.astype(np.int64), want)
+    # not symmetric in its operands: a transposed read would fail here
+    assert acc.shape == (M, N)
+
+
+def test_int_gemm_hand_cases(oracle):
+    K = 64
+    p7 = np.full((1, K // 2), 0x77, np.uint8)          # all +7
+    m7 = np.full((1, K // 2), 0x99, np.uint8)          # all -7
+    m8 = np.full((1, K // 2), 0x88, np.uint8)          # all -8
+    assert oracle.int_gemm(p7, m7)[0, 0] == -49 * K
+    assert oracle.int_gemm(m8, m8)[0, 0] == 64 * K
+    # W picks single codes: row n has a 1 at k = n only
+    W = np.zeros((4, K // 2), np.uint8)
+    for n in range(4):
+        W[n, n // 2] = 1 << (4 * (n % 2))
+    X = np.zeros((1, K // 2), np.uint8)
+    X[0, 0] = 0x2F          # k0 = -1, k1 = 2
+    X[0, 1] = 0x93          # k2 = 3, k3 = -7
+    assert np.array_equal(oracle.int_gemm(X, W), [[-1, 2, 3, -7]])
+
+
+def test_dequant_against_numpy_half_conversion(oracle):
+    rng = np.random.default_rng(13)
+    M, N = 9, 33
+    acc = rng.integers(-700000, 700000, size=(M, N)).astype(np.int32)
+    sx = (rng.random(M) * 3 + 0.01).astype(np.float16)
+    sw = (rng.random(N) * 0.02 + 1e-4).astype(np.float16)
+    Y = oracle.dequant(acc, sx, sw)
+    with np.errstate(over="ignore"):
+        want = ((acc.astype(np.float32) * sx.astype(np.float32)[:, None])
+                * sw.astype(np.float32)[None, :]).astype(np.float16)
+    assert np.array_equal(Y.view(np.uint16), want.view(np.uint16))
+
+
+def test_linear_samples_agree_with_full_product(oracle):
+    rng = np.random.default_rng(14)
+    M, N, K = 10, 12, 64
+    Xq = rng.integers(0, 256, size=(M, K // 2), dtype=np.uint8)
+    Wq = rng.integers(0, 256, size=(N, K // 2), dtype=np.uint8)
+    sx = (rng.random(M) + 0.1).astype(np.float16)
+    sw = (rng.random(N) * 0.01 + 1e-3).astype(np.float16)
+    want_acc = oracle.unpack_int4(Xq).astype(np.int64) @ oracle.unpack_int4(Wq).astype(np.int64).T
+    ms, ns = np.meshgrid(np.arange(M), np.arange(N), indexing="ij")
+    acc, y = oracle.linear_samples(Xq, sx, Wq, sw, ms.ravel(), ns.ravel())
+    assert np.array_equal(acc.reshape(M, N), want_acc)
+    Y, _ = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    assert np.array_equal(y.reshape(M, N).view(np.uint16), Y.view(np.uint16))
+
+
+def test_w4a4_linear_approximates_the_fp_linear(oracle):
+    """End to end on configuration 0: the W4A4 output tracks the fp32 linear, and
+    tracks it better once the rotation of Eq. 6 is applied to both operands."""
+    c = wl.toy_config()
+    X, W = c["X"], c["W"]
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+
+    def run(rotate):
+        if rotate:
+            Wr = np.stack([oracle.fwht(W[n].astype(np.float32)) for n in range(W.shape[0])])
+            Wq, sw, _ = oracle.quantize_rows(Wr.astype(np.float16))
+        else:
+            Wq, sw, _ = oracle.quantize_rows(W)
+        Xq, sx, _ = oracle.quantize_rows(X, rotate=rotate)
+        Y, _ = oracle.w4a4_linear(Xq, sx, Wq, sw)
+        return np.linalg.norm(Y.astype(np.float64) - ref) / np.linalg.norm(ref)
+
+    e_plain, e_rot = run(False), run(True)
+    assert e_plain < 1.0
+    assert e_rot < 0.35 and e_rot < e_plain
+
+
+# ------------------------------------------------------------------ score
+def test_attn_scores_vs_library_softmax(oracle):
+    rng = np.random.default_rng(15)
+    S, H, d, v0, nv = 37, 4, 16, 3, 20
+    q, k = wl.query_and_keys(S, H, d, rng)
+    got = oracle.attn_scores(q, k, v0, nv)
+    logits = np.einsum("hd,shd->hs", q.astype(np.float64), k.astype(np.float64)) / np.sqrt(d)
+    p = scipy.special.softmax(logits, axis=1)
+    assert np.allclose(got, p[:, v0:v0 + nv].mean(axis=0), rtol=1e-6, atol=1e-9)
+    full = oracle.attn_scores(q, k, 0, S)
+    assert np.isclose(full.sum(), 1.0, atol=1e-6)
+
+
+def test_attn_scores_uniform_and_shift_invariance(oracle):
+    S, H, d = 10, 2, 8
+    q = np.ones((H, d), np.float16)
+    k = np.ones((S, H, d), np.float16)
+    assert np.allclose(oracle.attn_scores(q, k, 0, S), 1.0 / S)
+    rng = np.random.default_rng(16)
+    q, k = wl.query_and_keys(S, H, d, rng)
+    q = np.round(q * 4) / 4
+    k = np.round(k * 4) / 4
+    base = oracle.attn_scores(q, k, 2, 5)
+    # adding one vector to every key adds a per-head constant to all logits
+    shifted = oracle.attn_scores(q, (k + np.float16(0.5)).astype(np.float16), 2, 5)
+    assert np.allclose(base, shifted, rtol=1e-5)
+
+
+# ------------------------------------------------------------------ brute force, tiny
+def test_tiny_linear_by_python_loops(oracle):
+    rng = np.random.default_rng(17)
+    M, N, K = 3, 4, 8
+    X = (rng.standard_normal((M, K)) * 2).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    Xq, sx, _ = oracle.quantize_rows(X)
+    Wq, sw, _ = oracle.quantize_rows(W)
+    xc, wc = _codes(oracle, Xq), _codes(oracle, Wq)
+    Y, acc = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    for m, n in itertools.product(range(M), range(N)):
+        s = sum(int(xc[m, k]) * int(wc[n, k]) for k in range(K))
+        assert acc[m, n] == s
+        approx = s * float(sx[m]) * float(sw[n])
+        assert abs(float(Y[m, n]) - approx) <= 1e-3 * abs(approx) + 1e-7
