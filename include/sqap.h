@@ -1,0 +1,178 @@
+/*
+ * sqap.h: C ABI of the MI355X (gfx950) library for the hot path of SQAP-VLA
+ * (arXiv 2509.09090): W4A4 linear layers run over the tokens that survive the
+ * paper's pruning criterion.
+ *
+ *   prune_topk -> kept_rows -> (gather) -> quantize_act -> w4a4_linear
+ *
+ * Conventions that hold for every call unless stated otherwise
+ *   - Data pointers are DEVICE pointers owned by the caller.  The library
+ *     never frees or keeps them.  The only library-owned objects are
+ *     sqap_weight handles.
+ *   - Half precision crosses the ABI as IEEE binary16 bit patterns (sqap_f16).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work on it and return; they never synchronise the host.
+ *   - Arguments are validated on the host before any device work.  A failed
+ *     validation returns a negative status, enqueues nothing, and leaves a
+ *     message for sqap_last_error().
+ *   - Sizes of zero (M = 0, keep_k = 0, batch = 0) are legal and do nothing.
+ *   - Packed int4 ("canonical") layout: row-major, K/2 bytes per row; byte j
+ *     holds element 2j in bits 0-3 and element 2j+1 in bits 4-7, each a 4-bit
+ *     two's-complement code in [-8, 7].
+ *   - No C++ exception crosses this boundary.
+ */
+#ifndef SQAP_H
+#define SQAP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t sqap_status;
+typedef uint16_t sqap_f16; /* IEEE binary16 bit pattern */
+
+enum {
+    SQAP_OK = 0,
+    SQAP_EINVAL = -1,       /* null pointer, negative size, odd K, keep_k > n, ld < K ... */
+    SQAP_EUNSUPPORTED = -2, /* legal request outside what the kernels cover */
+    SQAP_EDEVICE = -3,      /* a HIP call failed; message holds hipGetErrorString */
+    SQAP_ENOMEM = -4
+};
+
+/* flags */
+enum {
+    SQAP_ROTATE_HADAMARD = 1u /* rotate each row by the orthonormal Hadamard matrix first */
+};
+
+/* Opaque packed weight: device-resident, library-private layout. */
+typedef struct sqap_weight sqap_weight;
+
+/* Message of the last failed call on this thread (static storage, never NULL). */
+const char *sqap_last_error(void);
+
+/* Library version string (static storage). */
+const char *sqap_version(void);
+
+/*
+ * Retention score a_q (Strategy 1, text under Eq. 1; Section 3.3 defines the
+ * Q and K it is computed from).  For a task-query token with per-head query
+ * q[H,d] and the key cache k[S,H,d] (both half, row-major), computes for each
+ * head the softmax over all S keys of (q.k)/sqrt(d) and writes the mean over
+ * heads of the weights of the visual span:
+ *   scores_out[j] = (1/H) sum_h softmax_s(l[h,:])[vis_begin + j],  j < n_vis.
+ * Arithmetic in binary32.  scores_out: n_vis floats.
+ * EINVAL: null pointer, S/H/d <= 0, span outside [0,S).  EUNSUPPORTED: d > 256
+ * or S > 16384.
+ */
+sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
+                             int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
+                             void *stream);
+
+/*
+ * Eq. 1: K_attn = Top_k(a_q, k).  For each of `batch` rows of `scores`
+ * ([batch, n_tokens] floats) writes the indices of the keep_k largest values
+ * to idx_out ([batch, keep_k] int32), in ascending index order.  The kept set
+ * is unique: larger score first, equal scores -> lower index first, -0 == +0,
+ * NaN ranks below every number (lower index first among NaN).
+ * EINVAL: null pointer (when the size is non-zero), negative size,
+ * keep_k > n_tokens.  EUNSUPPORTED: n_tokens > 65536.
+ */
+sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens,
+                            int32_t keep_k, int32_t *idx_out, void *stream);
+
+/*
+ * Section 3.2 (final paragraph: the retained tokens form the shortened
+ * sequence).  Turns kept visual indices into row numbers of the token matrix:
+ * every token outside the visual span [vis_begin, vis_begin + n_vis) survives,
+ * visual token v survives iff v is in idx[b,:]; original order is preserved.
+ * idx: [batch, keep_k] ascending (as sqap_prune_topk writes it).
+ * rows_out: [batch * (seq_len - n_vis + keep_k)] int32; observation b's rows
+ * are offset by b * seq_len.
+ * EINVAL: null pointer, negative size, keep_k > n_vis, span outside the sequence.
+ */
+sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, int32_t seq_len,
+                           int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream);
+
+/*
+ * Token gather (same passage): out[i, 0..K) = X[rows[i], 0..K), a bit copy of
+ * half rows.  ldx / ldo are row pitches in elements (>= K).  K must be a
+ * multiple of 8 and both base pointers and pitches 16-byte aligned
+ * (EUNSUPPORTED otherwise).  Row numbers are not range-checked.
+ */
+sqap_status sqap_gather_rows(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                             int32_t K, sqap_f16 *out, int64_t ldo, void *stream);
+
+/*
+ * 4-bit activation quantizer, one scale per token (Section 3.3; Implementation
+ * Details: W4A4).  For output row i, taken from X[rows[i], :] (or X[i, :] when
+ * rows is NULL, which fuses the gather):
+ *   v     = the row in binary32; with SQAP_ROTATE_HADAMARD, v <- (H/sqrt(K)) v
+ *           (Eq. 6; butterflies at distance 1, 2, 4, ... in that order)
+ *   sx[i] = binary16(max|v| / 7), raised to 2^-24 when that rounds to 0
+ *   code  = clamp(rint(v / sx[i]), -8, 7), round-half-even, IEEE division
+ * Xq: [M, K/2] canonical packed int4.  sx: [M] half.
+ * EINVAL: null pointer, M < 0, K <= 0, K odd, ldx < K.
+ * EUNSUPPORTED: K not a multiple of 8, K > 16384, X/ldx not 16-byte aligned,
+ * rotation with K not a power of two or K < 16.
+ */
+sqap_status sqap_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                              int32_t K, uint32_t flags, uint8_t *Xq, sqap_f16 *sx,
+                              void *stream);
+
+/*
+ * 4-bit weight quantizer, one scale per output channel, round to nearest
+ * (the paper's "tensor-wise", i.e. not group-wise, W4; offline step).  Same
+ * arithmetic as sqap_quantize_act applied to the rows of W [N, K] (dense,
+ * pitch K).  With SQAP_ROTATE_HADAMARD the rows are rotated first, which is
+ * the (W^T H^T) factor of Eq. 6.  Wq: [N, K/2] canonical.  sw: [N] half.
+ */
+sqap_status sqap_quantize_weight(const sqap_f16 *W, int32_t N, int32_t K, uint32_t flags,
+                                 uint8_t *Wq, sqap_f16 *sw, void *stream);
+
+/*
+ * Re-lays canonical packed weights [N, K/2] and their scales [N] into the
+ * library's streaming layout and returns a handle that owns a device copy
+ * (allocated with hipMalloc on the current device).  The inputs may be freed
+ * once the stream has run past this call.  K must be a multiple of 32.
+ * EINVAL: null pointer, N/K <= 0.  EUNSUPPORTED: K % 32 != 0.  ENOMEM.
+ */
+sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, int32_t K,
+                             sqap_weight **out, void *stream);
+
+/* Frees a handle (NULL is allowed).  The caller makes sure no kernel still uses it. */
+sqap_status sqap_weight_free(sqap_weight *w);
+
+/* Shape and device footprint of a handle; any out pointer may be NULL. */
+sqap_status sqap_weight_info(const sqap_weight *w, int32_t *N, int32_t *K, size_t *device_bytes);
+
+/*
+ * Bytes of device workspace sqap_w4a4_linear needs for this shape (may be 0).
+ * The workspace is scratch: contents before and after a call are unspecified.
+ */
+size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K);
+
+/*
+ * W4A4 linear (the q/k/v/o, gate/up/down and lm_head layers of the quantized
+ * backbone; Section 4.3 names them as where the time goes):
+ *   acc[m,n] = sum_k xq[m,k] * wq[n,k]          exact, int32
+ *   Y[m,n]   = binary16( ((float)acc * sx[m]) * sw[n] )
+ * Xq: [M, K/2] canonical (pitch K/2, 16-byte aligned), sx: [M] half, W: a packed
+ * handle with the same K, Y: [M, N] half with pitch ldy >= N elements.
+ * acc_out: NULL, or [M, N] int32 (pitch N) that receives the accumulators.
+ * workspace: at least sqap_workspace_bytes(M, N, K) bytes, 256-byte aligned
+ * (may be NULL when that is 0).  Calls that share a workspace must be ordered
+ * on one stream.  One entry point serves prefill (large M) and decode (M <= 8);
+ * the kernel is chosen from M inside.
+ * EINVAL: null pointer, M < 0, ldy < N, workspace too small.
+ */
+sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
+                             const sqap_weight *W, sqap_f16 *Y, int64_t ldy, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQAP_H */

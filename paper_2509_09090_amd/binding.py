@@ -1,0 +1,165 @@
+"""ctypes binding of libsqap.so: argument marshalling only.
+
+Every function has the name of the C entry point it wraps (see include/sqap.h)
+and takes torch CUDA tensors, which are used purely as device memory; work is
+enqueued on torch's current stream unless `stream` is given.  Nothing here
+computes: there is no fallback when the library is missing (loading raises).
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsqap.so")
+
+OK, EINVAL, EUNSUPPORTED, EDEVICE, ENOMEM = 0, -1, -2, -3, -4
+ROTATE_HADAMARD = 1
+
+EXPORTS = (
+    "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_prune_topk", "sqap_kept_rows",
+    "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
+    "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
+)
+
+
+class SqapError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("sqap status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libsqap.so is not built: run `python -m paper_2509_09090_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u32, sz = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                                 ctypes.c_size_t)
+        L.sqap_last_error.restype = ctypes.c_char_p
+        L.sqap_last_error.argtypes = []
+        L.sqap_version.restype = ctypes.c_char_p
+        L.sqap_version.argtypes = []
+        L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
+        L.sqap_prune_topk.argtypes = [vp, i32, i32, i32, vp, vp]
+        L.sqap_kept_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+        L.sqap_gather_rows.argtypes = [vp, i64, vp, i32, i32, vp, i64, vp]
+        L.sqap_quantize_act.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp]
+        L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
+        L.sqap_weight_pack.argtypes = [vp, vp, i32, i32, ctypes.POINTER(vp), vp]
+        L.sqap_weight_free.argtypes = [vp]
+        L.sqap_weight_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(sz)]
+        L.sqap_workspace_bytes.restype = sz
+        L.sqap_workspace_bytes.argtypes = [i32, i32, i32]
+        L.sqap_w4a4_linear.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        for name in EXPORTS:
+            if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
+                getattr(L, name).restype = ctypes.c_int32
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != OK:
+        raise SqapError(status, lib().sqap_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is not None:
+        return ctypes.c_void_p(int(stream))
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def sqap_version():
+    return lib().sqap_version().decode()
+
+
+def sqap_attn_scores(q, k, vis_begin, n_vis, scores_out, stream=None):
+    """q [H,d] fp16, k [S,H,d] fp16 -> scores_out [n_vis] fp32."""
+    S, H, d = k.shape
+    _check(lib().sqap_attn_scores(_ptr(q), _ptr(k), S, H, d, vis_begin, n_vis, _ptr(scores_out),
+                                  _stream(stream)))
+
+
+def sqap_prune_topk(scores, keep_k, idx_out, stream=None):
+    """scores [batch, n] fp32 -> idx_out [batch, keep_k] int32 (ascending)."""
+    batch, n = scores.shape
+    _check(lib().sqap_prune_topk(_ptr(scores), batch, n, keep_k, _ptr(idx_out), _stream(stream)))
+
+
+def sqap_kept_rows(idx, seq_len, vis_begin, n_vis, rows_out, stream=None):
+    """idx [batch, keep_k] int32 -> rows_out [batch * (seq_len - n_vis + keep_k)] int32."""
+    batch, keep_k = idx.shape
+    _check(lib().sqap_kept_rows(_ptr(idx), batch, keep_k, seq_len, vis_begin, n_vis, _ptr(rows_out),
+                                _stream(stream)))
+
+
+def sqap_gather_rows(X, rows, out, stream=None):
+    M, K = rows.numel(), X.shape[1]
+    _check(lib().sqap_gather_rows(_ptr(X), X.stride(0), _ptr(rows), M, K, _ptr(out), out.stride(0),
+                                  _stream(stream)))
+
+
+def sqap_quantize_act(X, rows, Xq, sx, flags=0, stream=None):
+    """X [S,K] fp16, rows int32 [M] or None -> Xq [M,K/2] u8, sx [M] fp16."""
+    K = X.shape[1]
+    M = X.shape[0] if rows is None else rows.numel()
+    _check(lib().sqap_quantize_act(_ptr(X), X.stride(0), _ptr(rows), M, K, flags, _ptr(Xq), _ptr(sx),
+                                   _stream(stream)))
+
+
+def sqap_quantize_weight(W, Wq, sw, flags=0, stream=None):
+    N, K = W.shape
+    _check(lib().sqap_quantize_weight(_ptr(W), N, K, flags, _ptr(Wq), _ptr(sw), _stream(stream)))
+
+
+class Weight:
+    """Owns a sqap_weight handle."""
+
+    def __init__(self, handle, N, K):
+        self.handle, self.N, self.K = handle, N, K
+
+    def free(self):
+        if self.handle:
+            _check(lib().sqap_weight_free(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+    @property
+    def device_bytes(self):
+        b = ctypes.c_size_t()
+        _check(lib().sqap_weight_info(self.handle, None, None, ctypes.byref(b)))
+        return b.value
+
+
+def sqap_weight_pack(Wq, sw, stream=None):
+    N, half = Wq.shape
+    h = ctypes.c_void_p()
+    _check(lib().sqap_weight_pack(_ptr(Wq), _ptr(sw), N, 2 * half, ctypes.byref(h), _stream(stream)))
+    return Weight(h, N, 2 * half)
+
+
+def sqap_workspace_bytes(M, N, K):
+    return int(lib().sqap_workspace_bytes(M, N, K))
+
+
+def sqap_w4a4_linear(Xq, sx, W, Y, acc_out=None, workspace=None, stream=None):
+    """Xq [M,K/2] u8, sx [M] fp16, W: Weight -> Y [M,N] fp16 (+ acc_out [M,N] int32)."""
+    M = Xq.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().sqap_w4a4_linear(_ptr(Xq), _ptr(sx), M, W.handle, _ptr(Y), Y.stride(0), _ptr(acc_out),
+                                  _ptr(workspace), ws_bytes, _stream(stream)))

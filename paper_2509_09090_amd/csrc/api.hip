@@ -1,0 +1,234 @@
+// C ABI of the library: argument validation on the host, then kernel launches.
+// Declarations and the meaning of every argument are in include/sqap.h.
+#include <stdarg.h>
+#include <stdio.h>
+#include <new>
+
+#include "common.h"
+
+namespace sqap {
+
+static thread_local char g_error[512] = "";
+
+sqap_status fail(sqap_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static const Weight *check_weight(const sqap_weight *w)
+{
+    const Weight *ww = reinterpret_cast<const Weight *>(w);
+    if (!ww || ww->magic != kWeightMagic) return nullptr;
+    return ww;
+}
+
+}  // namespace sqap
+
+using namespace sqap;
+
+extern "C" {
+
+const char *sqap_last_error(void) { return g_error; }
+
+const char *sqap_version(void) { return "sqap-gfx950 0.1"; }
+
+sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
+                             int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
+                             void *stream)
+{
+    if (S <= 0 || H <= 0 || d <= 0)
+        return fail(SQAP_EINVAL, "sqap_attn_scores: S, H, d must be positive (%d, %d, %d)", S, H, d);
+    if (vis_begin < 0 || n_vis < 0 || (int64_t)vis_begin + n_vis > S)
+        return fail(SQAP_EINVAL, "sqap_attn_scores: visual span [%d, %d+%d) outside [0, %d)",
+                    vis_begin, vis_begin, n_vis, S);
+    if (!q || !k) return fail(SQAP_EINVAL, "sqap_attn_scores: null q or k");
+    if (n_vis == 0) return SQAP_OK;
+    if (!scores_out) return fail(SQAP_EINVAL, "sqap_attn_scores: null scores_out");
+    if (d > 256 || (d & 1)) return fail(SQAP_EUNSUPPORTED, "sqap_attn_scores: d = %d (even, <= 256)", d);
+    if (S > 16384) return fail(SQAP_EUNSUPPORTED, "sqap_attn_scores: S = %d > 16384", S);
+    return launch_attn_scores(reinterpret_cast<const __half *>(q),
+                              reinterpret_cast<const __half *>(k), S, H, d, vis_begin, n_vis,
+                              scores_out, as_stream(stream));
+}
+
+sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens,
+                            int32_t keep_k, int32_t *idx_out, void *stream)
+{
+    if (batch < 0 || n_tokens < 0 || keep_k < 0)
+        return fail(SQAP_EINVAL, "sqap_prune_topk: negative size (batch %d, n %d, keep %d)", batch,
+                    n_tokens, keep_k);
+    if (keep_k > n_tokens)
+        return fail(SQAP_EINVAL, "sqap_prune_topk: keep_k %d > n_tokens %d", keep_k, n_tokens);
+    if (batch == 0 || keep_k == 0) return SQAP_OK;
+    if (!scores || !idx_out) return fail(SQAP_EINVAL, "sqap_prune_topk: null pointer");
+    if (n_tokens > 65536)
+        return fail(SQAP_EUNSUPPORTED, "sqap_prune_topk: n_tokens %d > 65536", n_tokens);
+    return launch_prune_topk(scores, batch, n_tokens, keep_k, idx_out, as_stream(stream));
+}
+
+sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, int32_t seq_len,
+                           int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream)
+{
+    if (batch < 0 || keep_k < 0 || seq_len < 0 || n_vis < 0 || vis_begin < 0)
+        return fail(SQAP_EINVAL, "sqap_kept_rows: negative size");
+    if (keep_k > n_vis) return fail(SQAP_EINVAL, "sqap_kept_rows: keep_k %d > n_vis %d", keep_k, n_vis);
+    if ((int64_t)vis_begin + n_vis > seq_len)
+        return fail(SQAP_EINVAL, "sqap_kept_rows: visual span [%d, %d+%d) outside [0, %d)",
+                    vis_begin, vis_begin, n_vis, seq_len);
+    int64_t per = (int64_t)seq_len - n_vis + keep_k;
+    if ((int64_t)batch * seq_len > INT32_MAX)
+        return fail(SQAP_EINVAL, "sqap_kept_rows: batch * seq_len overflows int32");
+    if (batch == 0 || per == 0) return SQAP_OK;
+    if (!rows_out || (keep_k > 0 && !idx)) return fail(SQAP_EINVAL, "sqap_kept_rows: null pointer");
+    return launch_kept_rows(idx, batch, keep_k, seq_len, vis_begin, n_vis, rows_out,
+                            as_stream(stream));
+}
+
+sqap_status sqap_gather_rows(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                             int32_t K, sqap_f16 *out, int64_t ldo, void *stream)
+{
+    if (M < 0 || K <= 0) return fail(SQAP_EINVAL, "sqap_gather_rows: M %d, K %d", M, K);
+    if (ldx < K || ldo < K) return fail(SQAP_EINVAL, "sqap_gather_rows: pitch below K");
+    if (M == 0) return SQAP_OK;
+    if (!X || !rows || !out) return fail(SQAP_EINVAL, "sqap_gather_rows: null pointer");
+    if ((K & 7) || (ldx & 7) || (ldo & 7) || !aligned16(X) || !aligned16(out))
+        return fail(SQAP_EUNSUPPORTED, "sqap_gather_rows: K and pitches must be multiples of 8, "
+                                       "pointers 16-byte aligned");
+    return launch_gather_rows(reinterpret_cast<const __half *>(X), ldx, rows, M, K,
+                              reinterpret_cast<__half *>(out), ldo, as_stream(stream));
+}
+
+static sqap_status quantize_common(const char *who, const sqap_f16 *X, int64_t ldx,
+                                   const int32_t *rows, int32_t M, int32_t K, uint32_t flags,
+                                   uint8_t *Xq, sqap_f16 *sx, void *stream)
+{
+    if (M < 0 || K <= 0) return fail(SQAP_EINVAL, "%s: M %d, K %d", who, M, K);
+    if (K & 1) return fail(SQAP_EINVAL, "%s: K = %d is odd", who, K);
+    if (ldx < K) return fail(SQAP_EINVAL, "%s: pitch %lld below K %d", who, (long long)ldx, K);
+    if (flags & ~(uint32_t)SQAP_ROTATE_HADAMARD) return fail(SQAP_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    if (M == 0) return SQAP_OK;
+    if (!X || !Xq || !sx) return fail(SQAP_EINVAL, "%s: null pointer", who);
+    bool rotate = (flags & SQAP_ROTATE_HADAMARD) != 0;
+    if (rotate && ((K & (K - 1)) != 0 || K < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if ((K & 7) || K > 16384)
+        return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
+    if ((ldx & 7) || !aligned16(X) || (reinterpret_cast<uintptr_t>(Xq) & 3u))
+        return fail(SQAP_EUNSUPPORTED, "%s: X and its pitch must be 16-byte aligned, Xq 4-byte", who);
+    return launch_quantize_rows(reinterpret_cast<const __half *>(X), ldx, rows, M, K, rotate, Xq,
+                                reinterpret_cast<__half *>(sx), as_stream(stream));
+}
+
+sqap_status sqap_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                              int32_t K, uint32_t flags, uint8_t *Xq, sqap_f16 *sx, void *stream)
+{
+    return quantize_common("sqap_quantize_act", X, ldx, rows, M, K, flags, Xq, sx, stream);
+}
+
+sqap_status sqap_quantize_weight(const sqap_f16 *W, int32_t N, int32_t K, uint32_t flags,
+                                 uint8_t *Wq, sqap_f16 *sw, void *stream)
+{
+    return quantize_common("sqap_quantize_weight", W, K, nullptr, N, K, flags, Wq, sw, stream);
+}
+
+sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, int32_t K,
+                             sqap_weight **out, void *stream)
+{
+    if (out) *out = nullptr;
+    if (N <= 0 || K <= 0) return fail(SQAP_EINVAL, "sqap_weight_pack: N %d, K %d", N, K);
+    if (!Wq || !sw || !out) return fail(SQAP_EINVAL, "sqap_weight_pack: null pointer");
+    if (K % 32 != 0) return fail(SQAP_EUNSUPPORTED, "sqap_weight_pack: K = %d is not a multiple of 32", K);
+    if (!aligned16(Wq)) return fail(SQAP_EUNSUPPORTED, "sqap_weight_pack: Wq must be 16-byte aligned");
+    Weight *w = new (std::nothrow) Weight();
+    if (!w) return fail(SQAP_ENOMEM, "sqap_weight_pack: host allocation failed");
+    w->magic = kWeightMagic;
+    w->N = N;
+    w->K = K;
+    w->n_groups = (N + 31) / 32;
+    w->chunks = K / 32;
+    size_t data_bytes = (size_t)w->n_groups * w->chunks * 512;
+    size_t scale_bytes = (size_t)w->n_groups * 32 * sizeof(__half);
+    w->bytes = data_bytes + scale_bytes;
+    w->data = nullptr;
+    w->scales = nullptr;
+    hipError_t e = hipGetDevice(&w->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&w->data), data_bytes);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&w->scales), scale_bytes);
+    if (e != hipSuccess) {
+        if (w->data) (void)hipFree(w->data);
+        delete w;
+        return fail(e == hipErrorOutOfMemory ? SQAP_ENOMEM : SQAP_EDEVICE, "sqap_weight_pack: %s",
+                    hipGetErrorString(e));
+    }
+    sqap_status st = launch_weight_pack(Wq, reinterpret_cast<const __half *>(sw), *w, as_stream(stream));
+    if (st != SQAP_OK) {
+        (void)hipFree(w->data);
+        (void)hipFree(w->scales);
+        delete w;
+        return st;
+    }
+    *out = reinterpret_cast<sqap_weight *>(w);
+    return SQAP_OK;
+}
+
+sqap_status sqap_weight_free(sqap_weight *w)
+{
+    if (!w) return SQAP_OK;
+    Weight *ww = reinterpret_cast<Weight *>(w);
+    if (ww->magic != kWeightMagic) return fail(SQAP_EINVAL, "sqap_weight_free: not a weight handle");
+    ww->magic = 0;
+    hipError_t e1 = hipFree(ww->data);
+    hipError_t e2 = hipFree(ww->scales);
+    delete ww;
+    if (e1 != hipSuccess) return fail(SQAP_EDEVICE, "sqap_weight_free: %s", hipGetErrorString(e1));
+    if (e2 != hipSuccess) return fail(SQAP_EDEVICE, "sqap_weight_free: %s", hipGetErrorString(e2));
+    return SQAP_OK;
+}
+
+sqap_status sqap_weight_info(const sqap_weight *w, int32_t *N, int32_t *K, size_t *device_bytes)
+{
+    const Weight *ww = check_weight(w);
+    if (!ww) return fail(SQAP_EINVAL, "sqap_weight_info: not a weight handle");
+    if (N) *N = ww->N;
+    if (K) *K = ww->K;
+    if (device_bytes) *device_bytes = ww->bytes;
+    return SQAP_OK;
+}
+
+size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return linear_workspace_bytes(M, N, K);
+}
+
+sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
+                             const sqap_weight *W, sqap_f16 *Y, int64_t ldy, int32_t *acc_out,
+                             void *workspace, size_t workspace_bytes, void *stream)
+{
+    const Weight *w = check_weight(W);
+    if (!w) return fail(SQAP_EINVAL, "sqap_w4a4_linear: W is not a weight handle");
+    if (M < 0) return fail(SQAP_EINVAL, "sqap_w4a4_linear: M = %d", M);
+    if (ldy < w->N) return fail(SQAP_EINVAL, "sqap_w4a4_linear: ldy %lld below N %d", (long long)ldy, w->N);
+    if (M == 0) return SQAP_OK;
+    if (!Xq || !sx || !Y) return fail(SQAP_EINVAL, "sqap_w4a4_linear: null pointer");
+    if (!aligned16(Xq)) return fail(SQAP_EUNSUPPORTED, "sqap_w4a4_linear: Xq must be 16-byte aligned");
+    size_t need = linear_workspace_bytes(M, w->N, w->K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need)
+            return fail(SQAP_EINVAL, "sqap_w4a4_linear: workspace of %zu bytes needed, %zu given", need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u)
+            return fail(SQAP_EINVAL, "sqap_w4a4_linear: workspace must be 256-byte aligned");
+    }
+    return launch_w4a4_linear(Xq, reinterpret_cast<const __half *>(sx), M, *w,
+                              reinterpret_cast<__half *>(Y), ldy, acc_out, workspace,
+                              as_stream(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,63 @@
+// Internal helpers of the gfx950 library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "sqap.h"
+
+namespace sqap {
+
+// Records the message returned by sqap_last_error() and passes the status through.
+sqap_status fail(sqap_status st, const char *fmt, ...);
+
+// Packed weight: device copy in the streaming layout used by the GEMM kernels.
+//
+// Layout of `data`: rows are grouped by 32 and the reduction axis by chunks of
+// 32 codes (16 bytes).  For row group g (rows 32g .. 32g+31) and chunk c the
+// 512 bytes at ((g * chunks + c) * 512) hold, for r = 0..31, the 16 packed
+// bytes of row 32g + r, codes 32c .. 32c+31, unchanged from the canonical
+// layout.  Rows past N are zero.  A wavefront that reads 1 KiB contiguous gets
+// two chunks of one row group, which is exactly the B operand of two
+// 32x32x32 int8 MFMAs once nibbles are split (low nibbles -> one, high -> other).
+struct Weight {
+    uint32_t magic;
+    int32_t N, K;
+    int32_t n_groups;   // ceil(N / 32)
+    int32_t chunks;     // K / 32
+    uint8_t *data;      // n_groups * chunks * 512 bytes
+    __half *scales;     // n_groups * 32 halves (zero padded)
+    size_t bytes;
+    int device;
+};
+constexpr uint32_t kWeightMagic = 0x53514150u;  // "SQAP"
+
+static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+#define SQAP_HIP_CHECK(expr)                                                          \
+    do {                                                                              \
+        hipError_t e_ = (expr);                                                       \
+        if (e_ != hipSuccess)                                                         \
+            return ::sqap::fail(SQAP_EDEVICE, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// kernel launchers (defined in the .hip files); all validation is done by the caller
+sqap_status launch_attn_scores(const __half *q, const __half *k, int S, int H, int d,
+                               int vis_begin, int n_vis, float *scores, hipStream_t st);
+sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
+                              hipStream_t st);
+sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
+                             int vis_begin, int n_vis, int32_t *rows, hipStream_t st);
+sqap_status launch_gather_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                               __half *out, int64_t ldo, hipStream_t st);
+sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                 bool rotate, uint8_t *Xq, __half *sx, hipStream_t st);
+sqap_status launch_weight_pack(const uint8_t *Wq, const __half *sw, const Weight &w,
+                               hipStream_t st);
+size_t linear_workspace_bytes(int M, int N, int K);
+sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const Weight &w,
+                               __half *Y, int64_t ldy, int32_t *acc_out, void *workspace,
+                               hipStream_t st);
+
+}  // namespace sqap

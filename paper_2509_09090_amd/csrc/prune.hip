@@ -1,0 +1,285 @@
+// Token selection kernels: retention score, top-k (Eq. 1 of the paper), the
+// surviving row list and the row gather.
+#include "common.h"
+
+namespace sqap {
+
+// Monotone map from a score to an unsigned key: larger score <=> larger key,
+// -0 and +0 share a key, every NaN maps to 0 (below -inf, whose key is 0x007fffff).
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t b = __float_as_uint(s);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return 0u;
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Exclusive prefix sum of one 0/1 flag per thread over a 256-thread block.
+// Returns the thread's offset; *total receives the block sum.  `wave_sums`
+// is 4 ints of LDS.  Contains two barriers.
+__device__ __forceinline__ int block_scan_flags(bool flag, int *wave_sums, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long m = __ballot(flag);
+    int before = __popcll(m & ((1ull << lane) - 1ull));
+    __syncthreads();                       // previous users of wave_sums are done
+    if (lane == 0) wave_sums[wave] = __popcll(m);
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        int c = wave_sums[w];
+        if (w < wave) off += c;
+        tot += c;
+    }
+    *total = tot;
+    return off + before;
+}
+
+constexpr int kTopkSmallMax = 2048;
+
+// n <= 2048: every element counts how many rank ahead of it (larger key, or the
+// same key at a lower index); it is kept iff that count is below keep_k.
+__global__ __launch_bounds__(256) void topk_rank_kernel(const float *__restrict__ scores, int n,
+                                                        int keep_k, int32_t *__restrict__ idx_out)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t keys[kTopkSmallMax];
+    __shared__ int wave_sums[4];
+    const int t = threadIdx.x;
+    const float *s = scores + (size_t)blockIdx.x * n;
+    int32_t *out = idx_out + (size_t)blockIdx.x * keep_k;
+    const int n4 = (n + 3) & ~3;
+    for (int i = t; i < n4; i += 256) keys[i] = i < n ? score_key(s[i]) : 0u;
+    __syncthreads();
+    int base = 0;
+    for (int c = 0; c < n; c += 256) {
+        const int i = c + t;
+        bool keep = false;
+        if (i < n) {
+            const uint32_t ki = keys[i];
+            int ahead = 0;
+            for (int j = 0; j < n4; j += 4) {
+                uint4 kj = *reinterpret_cast<const uint4 *>(&keys[j]);
+                ahead += (kj.x > ki) || (kj.x == ki && j + 0 < i);
+                ahead += (kj.y > ki) || (kj.y == ki && j + 1 < i);
+                ahead += (kj.z > ki) || (kj.z == ki && j + 2 < i);
+                ahead += (kj.w > ki) || (kj.w == ki && j + 3 < i);
+            }
+            keep = ahead < keep_k;
+        }
+        int total;
+        int pos = block_scan_flags(keep, wave_sums, &total);
+        if (keep) out[base + pos] = i;
+        base += total;
+    }
+}
+
+// Any n: radix select, 8 bits per pass from the top, finds the key T of the
+// keep_k-th ranked element and how many elements equal to T are kept; a last
+// pass in index order keeps key > T and the first `need_eq` with key == T.
+__global__ __launch_bounds__(256) void topk_radix_kernel(const float *__restrict__ scores, int n,
+                                                         int keep_k, int32_t *__restrict__ idx_out)
+{
+    __shared__ int hist[256];
+    __shared__ int wave_sums[4];
+    __shared__ int sel_digit, sel_remaining;
+    const int t = threadIdx.x;
+    const float *s = scores + (size_t)blockIdx.x * n;
+    int32_t *out = idx_out + (size_t)blockIdx.x * keep_k;
+    uint32_t prefix = 0, mask = 0;
+    int remaining = keep_k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[t] = 0;
+        __syncthreads();
+        for (int i = t; i < n; i += 256) {
+            uint32_t k = score_key(s[i]);
+            if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        int above = 0;
+        for (int d = t + 1; d < 256; ++d) above += hist[d];
+        if (above < remaining && above + hist[t] >= remaining) {
+            sel_digit = t;
+            sel_remaining = remaining - above;
+        }
+        __syncthreads();
+        prefix |= (uint32_t)sel_digit << shift;
+        mask |= 0xffu << shift;
+        remaining = sel_remaining;
+        __syncthreads();
+    }
+    const uint32_t T = prefix;
+    const int need_eq = remaining;
+    int base = 0, eq_seen = 0;
+    for (int c = 0; c < n; c += 256) {
+        const int i = c + t;
+        uint32_t k = i < n ? score_key(s[i]) : 0u;
+        bool gt = i < n && k > T, eq = i < n && k == T;
+        int eq_total;
+        int eq_rank = eq_seen + block_scan_flags(eq, wave_sums, &eq_total);
+        bool keep = gt || (eq && eq_rank < need_eq);
+        int total;
+        int pos = block_scan_flags(keep, wave_sums, &total);
+        if (keep) out[base + pos] = i;
+        base += total;
+        eq_seen += eq_total;
+    }
+}
+
+sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
+                              hipStream_t st)
+{
+    if (n <= kTopkSmallMax)
+        hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx);
+    else
+        hipLaunchKernelGGL(topk_radix_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// One block per observation: walks the sequence in order, keeps every token
+// outside the visual span and the visual tokens listed (ascending) in idx.
+__global__ __launch_bounds__(256) void kept_rows_kernel(const int32_t *__restrict__ idx, int keep_k,
+                                                        int seq_len, int vis_begin, int n_vis,
+                                                        int32_t *__restrict__ rows)
+{
+    __shared__ int wave_sums[4];
+    const int b = blockIdx.x, t = threadIdx.x;
+    const int32_t *my = idx + (size_t)b * keep_k;
+    int32_t *out = rows + (size_t)b * (seq_len - n_vis + keep_k);
+    int base = 0;
+    for (int c = 0; c < seq_len; c += 256) {
+        const int s = c + t;
+        bool keep = false;
+        if (s < seq_len) {
+            const int v = s - vis_begin;
+            if (v < 0 || v >= n_vis) {
+                keep = true;
+            } else {                     // binary search in the ascending list
+                int lo = 0, hi = keep_k;
+                while (lo < hi) {
+                    int mid = (lo + hi) >> 1;
+                    if (my[mid] < v) lo = mid + 1; else hi = mid;
+                }
+                keep = lo < keep_k && my[lo] == v;
+            }
+        }
+        int total;
+        int pos = block_scan_flags(keep, wave_sums, &total);
+        if (keep) out[base + pos] = b * seq_len + s;
+        base += total;
+    }
+}
+
+sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
+                             int vis_begin, int n_vis, int32_t *rows, hipStream_t st)
+{
+    hipLaunchKernelGGL(kept_rows_kernel, dim3(batch), dim3(256), 0, st, idx, keep_k, seq_len,
+                       vis_begin, n_vis, rows);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// out[i,:] = X[rows[i],:]; one 16-byte piece per thread, rows of a block contiguous.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                          const int32_t *__restrict__ rows, int M,
+                                                          int pieces, __half *__restrict__ out,
+                                                          int64_t ldo)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t row = gid / pieces;
+    const int p = (int)(gid % pieces);
+    if (row >= M) return;
+    const uint4 *src = reinterpret_cast<const uint4 *>(X + (int64_t)rows[row] * ldx) + p;
+    uint4 *dst = reinterpret_cast<uint4 *>(out + row * ldo) + p;
+    *dst = *src;
+}
+
+sqap_status launch_gather_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                               __half *out, int64_t ldo, hipStream_t st)
+{
+    const int pieces = K / 8;
+    const int64_t total = (int64_t)M * pieces;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_gather_rows: too large");
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, st, X, ldx, rows, M,
+                       pieces, out, ldo);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// Retention score.  One block of 8 wavefronts; wavefront w takes heads w, w+8, ...
+// For its head every lane owns keys lane, lane+64, ...: pass 1 builds the
+// running (max, sum) of the softmax, pass 2 recomputes the logits of the
+// visual span and turns them into weights.  Heads are then added into the
+// LDS accumulator in wavefront order, so the sum order is fixed.
+__device__ __forceinline__ float dot_qk(const __half *__restrict__ qh, const __half *__restrict__ kh, int d)
+{
+    float acc = 0.f;
+    for (int i = 0; i < d; i += 2) {
+        float2 a = __half22float2(*reinterpret_cast<const __half2 *>(qh + i));
+        float2 b = __half22float2(*reinterpret_cast<const __half2 *>(kh + i));
+        acc = fmaf(a.x, b.x, acc);
+        acc = fmaf(a.y, b.y, acc);
+    }
+    return acc;
+}
+
+constexpr int kScoreWaves = 8;
+
+__global__ __launch_bounds__(64 * kScoreWaves) void attn_scores_kernel(
+    const __half *__restrict__ q, const __half *__restrict__ k, int S, int H, int d, int vis_begin,
+    int n_vis, float *__restrict__ scores)
+{
+    extern __shared__ float acc_lds[];   // n_vis floats
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int j = threadIdx.x; j < n_vis; j += blockDim.x) acc_lds[j] = 0.f;
+    __syncthreads();
+    const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+    const int rounds = (H + kScoreWaves - 1) / kScoreWaves;
+    for (int r = 0; r < rounds; ++r) {
+        const int h = r * kScoreWaves + wave;
+        float m = -INFINITY, z = 0.f;
+        if (h < H) {
+            const __half *qh = q + (size_t)h * d;
+            for (int s = lane; s < S; s += 64) {
+                float l = dot_qk(qh, k + ((size_t)s * H + h) * d, d) * inv_sqrt_d;
+                float mn = fmaxf(m, l);
+                z = z * expf(m - mn) + expf(l - mn);
+                m = mn;
+            }
+            for (int o = 32; o > 0; o >>= 1) {
+                float m2 = __shfl_xor(m, o), z2 = __shfl_xor(z, o);
+                float mn = fmaxf(m, m2);
+                float za = (m == -INFINITY) ? 0.f : z * expf(m - mn);
+                float zb = (m2 == -INFINITY) ? 0.f : z2 * expf(m2 - mn);
+                z = za + zb;
+                m = mn;
+            }
+        }
+        // add this round's heads in wavefront order
+        for (int w = 0; w < kScoreWaves; ++w) {
+            if (w == wave && h < H) {
+                const __half *qh = q + (size_t)h * d;
+                for (int j = lane; j < n_vis; j += 64) {
+                    const int s = vis_begin + j;
+                    float l = dot_qk(qh, k + ((size_t)s * H + h) * d, d) * inv_sqrt_d;
+                    acc_lds[j] += expf(l - m) / z;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int j = threadIdx.x; j < n_vis; j += blockDim.x) scores[j] = acc_lds[j] / (float)H;
+}
+
+sqap_status launch_attn_scores(const __half *q, const __half *k, int S, int H, int d,
+                               int vis_begin, int n_vis, float *scores, hipStream_t st)
+{
+    hipLaunchKernelGGL(attn_scores_kernel, dim3(1), dim3(64 * kScoreWaves), n_vis * sizeof(float), st,
+                       q, k, S, H, d, vis_begin, n_vis, scores);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+}  // namespace sqap

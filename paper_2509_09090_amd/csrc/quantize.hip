@@ -1,0 +1,175 @@
+// Per-row symmetric int4 quantizer (activations: one row per token; weights:
+// one row per output channel), with the optional Hadamard rotation of Eq. 6,
+// and the re-layout of canonical packed weights into the streaming layout.
+#include "common.h"
+
+namespace sqap {
+
+constexpr int kQuantMaxGroups = 8;   // 8 groups of 8 elements per thread: K <= 16384
+
+// One block per output row.  Each thread owns groups t, t+256, ... of 8
+// consecutive elements, held in registers from the single read of the row to
+// the packed store.  Arithmetic (all binary32, IEEE, no contraction possible):
+//   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
+template <bool ROTATE>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                            const int32_t *__restrict__ rows, int K,
+                                                            uint8_t *__restrict__ Xq,
+                                                            __half *__restrict__ scale_out)
+{
+    extern __shared__ float rot[];       // K floats when ROTATE
+    __shared__ float wave_max[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int row = blockIdx.x;
+    const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
+    const uint4 *xrow = reinterpret_cast<const uint4 *>(X + src * ldx);
+    const int groups = K >> 3;
+
+    float v[kQuantMaxGroups][8];
+#pragma unroll
+    for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+            uint4 raw = xrow[g];
+            const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                float2 f = __half22float2(h2[p]);
+                v[gi][2 * p] = f.x;
+                v[gi][2 * p + 1] = f.y;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
+        }
+    }
+
+    if (ROTATE) {
+        // Butterfly stages at distance 1, 2, 4 stay inside a group of 8: registers.
+#pragma unroll
+        for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+#pragma unroll
+            for (int h = 1; h < 8; h <<= 1) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if ((e & h) == 0) {
+                        float a = v[gi][e], b = v[gi][e + h];
+                        v[gi][e] = a + b;
+                        v[gi][e + h] = a - b;
+                    }
+                }
+            }
+            const int g = t + gi * 256;
+            if (g < groups) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) rot[g * 8 + e] = v[gi][e];
+            }
+        }
+        __syncthreads();
+        // Remaining stages, distance 8 .. K/2, in LDS in the same order.
+        const int half_k = K >> 1;
+        for (int h = 8; h < K; h <<= 1) {
+            for (int p = t; p < half_k; p += 256) {
+                const int j = ((p / h) * 2 * h) + (p % h);
+                float a = rot[j], b = rot[j + h];
+                rot[j] = a + b;
+                rot[j + h] = a - b;
+            }
+            __syncthreads();
+        }
+        const float c = (float)(1.0 / sqrt((double)K));
+#pragma unroll
+        for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+            const int g = t + gi * 256;
+            if (g < groups) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[gi][e] = rot[g * 8 + e] * c;
+            }
+        }
+    }
+
+    float amax = 0.f;
+#pragma unroll
+    for (int gi = 0; gi < kQuantMaxGroups; ++gi)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
+    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    if (lane == 0) wave_max[wave] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
+
+    __half sh = __float2half_rn(amax / 7.0f);
+    if (__half_as_ushort(sh) == 0) sh = __ushort_as_half((unsigned short)1);
+    const float sf = __half2float(sh);
+    if (t == 0) scale_out[row] = sh;
+
+    uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
+#pragma unroll
+    for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+            uint32_t packed = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float r = rintf(v[gi][e] / sf);
+                r = fminf(fmaxf(r, -8.f), 7.f);
+                packed |= ((uint32_t)(int)r & 15u) << (4 * e);
+            }
+            qrow[g] = packed;
+        }
+    }
+}
+
+sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                 bool rotate, uint8_t *Xq, __half *sx, hipStream_t st)
+{
+    if (rotate) {
+        size_t lds = (size_t)K * sizeof(float);
+        static bool configured = false;
+        if (!configured) {
+            SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
+            configured = true;
+        }
+        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(M), dim3(256), lds, st, X, ldx, rows, K, Xq,
+                           sx);
+    } else {
+        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(M), dim3(256), 0, st, X, ldx, rows, K, Xq,
+                           sx);
+    }
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// canonical [N, K/2] -> streaming layout (see Weight in common.h); one 16-byte
+// piece per thread; rows past N and their scales are written as zero.
+__global__ __launch_bounds__(256) void weight_pack_kernel(const uint8_t *__restrict__ Wq,
+                                                          const __half *__restrict__ sw, int N, int chunks,
+                                                          int n_groups, uint4 *__restrict__ data,
+                                                          __half *__restrict__ scales)
+{
+    const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)n_groups * chunks * 32;
+    if (gid < (int64_t)n_groups * 32) scales[gid] = gid < N ? sw[gid] : __ushort_as_half((unsigned short)0);
+    if (gid >= total) return;
+    const int r = (int)(gid & 31);
+    const int64_t gc = gid >> 5;
+    const int c = (int)(gc % chunks);
+    const int64_t n = (gc / chunks) * 32 + r;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (n < N) val = reinterpret_cast<const uint4 *>(Wq + n * ((int64_t)chunks * 16))[c];
+    data[gid] = val;
+}
+
+sqap_status launch_weight_pack(const uint8_t *Wq, const __half *sw, const Weight &w, hipStream_t st)
+{
+    const int64_t total = (int64_t)w.n_groups * w.chunks * 32;
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_weight_pack: too large");
+    hipLaunchKernelGGL(weight_pack_kernel, dim3((unsigned)blocks), dim3(256), 0, st, Wq, sw, w.N, w.chunks,
+                       w.n_groups, reinterpret_cast<uint4 *>(w.data), w.scales);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+}  // namespace sqap

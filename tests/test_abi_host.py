@@ -1,0 +1,105 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2509_09090_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "sqap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sqap_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    L = B.lib()
+    names = _declared()
+    assert len(names) >= 13
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version_and_error_strings():
+    assert "gfx950" in B.sqap_version()
+    assert isinstance(B.lib().sqap_last_error(), bytes)
+
+
+def _err():
+    return B.lib().sqap_last_error().decode()
+
+
+def test_prune_topk_validation():
+    L = B.lib()
+    assert L.sqap_prune_topk(None, 1, 4, 5, None, None) == B.EINVAL and "keep_k" in _err()
+    assert L.sqap_prune_topk(None, -1, 4, 1, None, None) == B.EINVAL
+    assert L.sqap_prune_topk(None, 1, 4, 2, None, None) == B.EINVAL      # null with work to do
+    assert L.sqap_prune_topk(None, 0, 4, 2, None, None) == B.OK          # empty batch
+    assert L.sqap_prune_topk(None, 3, 4, 0, None, None) == B.OK          # keep nothing
+    one = ctypes.c_void_p(16)
+    assert L.sqap_prune_topk(one, 1, 70000, 5, one, None) == B.EUNSUPPORTED
+
+
+def test_kept_rows_validation():
+    L = B.lib()
+    assert L.sqap_kept_rows(None, 1, 5, 10, 0, 4, None, None) == B.EINVAL    # keep_k > n_vis
+    assert L.sqap_kept_rows(None, 1, 2, 10, 8, 4, None, None) == B.EINVAL    # span outside
+    assert L.sqap_kept_rows(None, 0, 2, 10, 0, 4, None, None) == B.OK
+
+
+def test_quantize_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.sqap_quantize_act(p, 5, None, 1, 5, 0, p, p, None) == B.EINVAL and "odd" in _err()
+    assert L.sqap_quantize_act(p, 8, None, 1, 16, 0, p, p, None) == B.EINVAL          # ldx < K
+    assert L.sqap_quantize_act(p, 16, None, -1, 16, 0, p, p, None) == B.EINVAL
+    assert L.sqap_quantize_act(None, 16, None, 1, 16, 0, p, p, None) == B.EINVAL
+    assert L.sqap_quantize_act(p, 16, None, 1, 16, 2, p, p, None) == B.EINVAL         # unknown flag
+    assert L.sqap_quantize_act(None, 16, None, 0, 16, 0, None, None, None) == B.OK    # M = 0
+    assert L.sqap_quantize_act(p, 11008, None, 1, 11008, 1, p, p, None) == B.EUNSUPPORTED
+    assert "power of two" in _err()
+    assert L.sqap_quantize_act(p, 12, None, 1, 12, 0, p, p, None) == B.EUNSUPPORTED   # K % 8
+    assert L.sqap_quantize_act(p, 32768, None, 1, 32768, 0, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_quantize_act(ctypes.c_void_p(4098), 16, None, 1, 16, 0, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_quantize_weight(p, 4, 7, 0, p, p, None) == B.EINVAL
+
+
+def test_gather_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.sqap_gather_rows(p, 8, p, 1, 16, p, 16, None) == B.EINVAL
+    assert L.sqap_gather_rows(p, 16, None, 1, 16, p, 16, None) == B.EINVAL
+    assert L.sqap_gather_rows(p, 12, p, 1, 12, p, 12, None) == B.EUNSUPPORTED
+    assert L.sqap_gather_rows(p, 16, p, 0, 16, p, 16, None) == B.OK
+
+
+def test_weight_and_linear_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    h = ctypes.c_void_p()
+    assert L.sqap_weight_pack(p, p, 0, 32, ctypes.byref(h), None) == B.EINVAL
+    assert L.sqap_weight_pack(p, p, 4, 48, ctypes.byref(h), None) == B.EUNSUPPORTED
+    assert L.sqap_weight_pack(None, p, 4, 32, ctypes.byref(h), None) == B.EINVAL
+    assert h.value is None
+    assert L.sqap_weight_free(None) == B.OK
+    assert L.sqap_weight_info(None, None, None, None) == B.EINVAL
+    assert L.sqap_w4a4_linear(p, p, 1, None, p, 32, None, None, 0, None) == B.EINVAL
+    fake = (ctypes.c_uint32 * 32)()          # wrong magic: rejected without a device call
+    assert L.sqap_w4a4_linear(p, p, 1, ctypes.cast(fake, ctypes.c_void_p), p, 32, None, None, 0,
+                              None) == B.EINVAL
+    assert B.sqap_workspace_bytes(0, 10, 32) == 0
+
+
+def test_attn_scores_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.sqap_attn_scores(p, p, 0, 1, 8, 0, 0, p, None) == B.EINVAL
+    assert L.sqap_attn_scores(p, p, 10, 2, 8, 5, 6, p, None) == B.EINVAL
+    assert L.sqap_attn_scores(p, p, 10, 2, 512, 0, 4, p, None) == B.EUNSUPPORTED
+    assert L.sqap_attn_scores(p, p, 10, 2, 8, 0, 0, None, None) == B.OK

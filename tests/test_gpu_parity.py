@@ -1,0 +1,190 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on
+the same seeded inputs, through the C ABI.  Integer outputs (indices, int4
+codes, int32 accumulators, scales' bit patterns) must be identical; fp16
+outputs must be within 1e-2 + 1e-3|ref| (and are expected to be bit-equal,
+since the epilogue arithmetic is pinned)."""
+import numpy as np
+import pytest
+
+from paper_2509_09090_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from tests import gpu_util
+    return gpu_util
+
+
+# ------------------------------------------------------------------ top-k / rows / gather
+@pytest.mark.parametrize("batch,n,k", [(1, 64, 32), (1, 256, 128), (1, 256, 64), (16, 256, 128),
+                                       (3, 1, 1), (2, 7, 3), (2, 255, 254), (2, 300, 1),
+                                       (2, 1000, 17), (2, 2048, 1000), (2, 2049, 5), (3, 5000, 2500),
+                                       (1, 65536, 4097), (2, 4096, 4096), (4, 256, 256)])
+def test_topk_random(G, oracle, batch, n, k):
+    s = wl.scores(batch, n, wl.rng_for(90, n, wl.T_SCORES, k))
+    assert np.array_equal(G.gpu_prune_topk(s, k), oracle.prune_topk(s, k))
+
+
+@pytest.mark.parametrize("n", [64, 256, 4096])
+def test_topk_adversarial(G, oracle, n):
+    rng = np.random.default_rng(n)
+    cases = {
+        "all_equal": np.full(n, 0.5, np.float32),
+        "two_valued": np.tile(np.array([1.0, 0.0], np.float32), n // 2),
+        "descending": np.linspace(1, 0, n).astype(np.float32),
+        "ascending": np.linspace(0, 1, n).astype(np.float32),
+        "dups": (np.round(rng.random(n) * 10) / 10).astype(np.float32),
+        "signed_zero": np.array([0.0, -0.0] * (n // 2), np.float32),
+        "with_nan": np.where(np.arange(n) % 5 == 0, np.nan, np.arange(n) % 7).astype(np.float32),
+        "all_nan": np.full(n, np.nan, np.float32),
+        "infs": np.array([np.inf, -np.inf, 1.0, np.inf] * (n // 4), np.float32),
+        "negatives": -np.arange(n, dtype=np.float32),
+        "denormals": (np.arange(n) % 9).astype(np.float32) * np.float32(1e-45),
+    }
+    for name, s in cases.items():
+        for k in (1, 2, n // 2 - 1, n // 2, n // 2 + 1, n - 1, n):
+            got = G.gpu_prune_topk(s[None, :], k)
+            assert np.array_equal(got, oracle.prune_topk(s[None, :], k)), (name, k)
+
+
+def test_topk_zero_sizes(G):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    s = torch.zeros((2, 8), dtype=torch.float32, device="cuda")
+    out = torch.zeros((2, 0), dtype=torch.int32, device="cuda")
+    B.sqap_prune_topk(s, 0, out)          # keep_k = 0: legal no-op
+    with pytest.raises(B.SqapError):
+        B.sqap_prune_topk(s, 9, torch.zeros((2, 9), dtype=torch.int32, device="cuda"))
+
+
+@pytest.mark.parametrize("batch,S,v0,nv,k", [(1, 276, 0, 256, 128), (16, 276, 0, 256, 128),
+                                             (3, 30, 4, 16, 5), (2, 700, 100, 500, 123),
+                                             (2, 20, 0, 20, 0), (2, 20, 3, 0, 0), (1, 64, 0, 64, 32)])
+def test_kept_rows_and_gather(G, oracle, batch, S, v0, nv, k):
+    s = wl.scores(batch, max(nv, 1), wl.rng_for(91, S, wl.T_SCORES, k))[:, :nv]
+    idx = oracle.prune_topk(s, k) if nv else np.zeros((batch, 0), np.int32)
+    rows = oracle.kept_rows(idx, S, v0, nv)
+    assert np.array_equal(G.gpu_kept_rows(idx, S, v0, nv), rows)
+    X, _ = wl.activations(batch * S, 64, 2, 20.0, wl.rng_for(91, S, wl.T_X, k))
+    assert np.array_equal(G.gpu_gather(X, rows).view(np.uint16), X[rows].view(np.uint16))
+
+
+# ------------------------------------------------------------------ quantizer
+@pytest.mark.parametrize("M,K", [(64, 512), (148, 4096), (37, 11008), (5, 8), (3, 16), (9, 2056),
+                                 (2, 16384), (1, 4096), (8, 11008)])
+def test_quantize_act(G, oracle, M, K):
+    X, _ = wl.activations(M, K, max(1, wl.n_outliers_for(K)), 30.0, wl.rng_for(92, M, wl.T_X, K))
+    q, s = G.gpu_quantize(X)
+    qo, so, _ = oracle.quantize_rows(X)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16))
+    assert np.array_equal(q, qo)
+
+
+def test_quantize_act_fused_gather(G, oracle):
+    X, _ = wl.activations(276, 4096, 41, 30.0, wl.rng_for(92, 1, wl.T_X, 1))
+    rows = np.sort(np.random.default_rng(5).choice(276, 148, replace=False)).astype(np.int32)
+    q, s = G.gpu_quantize(X, rows=rows)
+    qo, so, _ = oracle.quantize_rows(X, rows=rows)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
+
+
+@pytest.mark.parametrize("M,K", [(7, 16), (5, 64), (33, 512), (148, 4096), (3, 16384)])
+def test_quantize_act_rotated(G, oracle, M, K):
+    X, _ = wl.activations(M, K, max(1, wl.n_outliers_for(K)), 30.0, wl.rng_for(93, M, wl.T_X, K))
+    q, s = G.gpu_quantize(X, rotate=True)
+    qo, so, _ = oracle.quantize_rows(X, rotate=True)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16))
+    assert np.array_equal(q, qo)
+
+
+def test_quantize_special_rows(G, oracle):
+    K = 64
+    X = np.zeros((6, K), np.float16)
+    X[1, 3] = np.float16(6e-8)            # smallest subnormal: scale floor path
+    X[2] = np.float16(65504.0)
+    X[3, ::2] = np.float16(-1.5)
+    X[4] = np.linspace(-7, 7, K).astype(np.float16)   # exact .5 ties with scale 1
+    X[5, 0], X[5, 1] = np.float16(7.0), np.float16(2.5)
+    q, s = G.gpu_quantize(X)
+    qo, so, _ = oracle.quantize_rows(X)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
+
+
+def test_quantize_weight(G, oracle):
+    W = wl.weights(512, 512, wl.rng_for(94, 0, wl.T_W))
+    q, s = G.gpu_quantize(W, weight=True)
+    qo, so, _ = oracle.quantize_rows(W)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
+    q, s = G.gpu_quantize(W, weight=True, rotate=True)
+    qo, so, _ = oracle.quantize_rows(W, rotate=True)
+    assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
+
+
+# ------------------------------------------------------------------ linear
+def _random_packed(rng, R, K):
+    return rng.integers(0, 256, size=(R, K // 2), dtype=np.uint8)
+
+
+@pytest.mark.parametrize("M,N,K", [(32, 512, 512), (1, 32, 32), (8, 4096, 4096), (148, 512, 1024),
+                                   (300, 700, 352), (70, 33, 96), (257, 300, 128), (5, 1000, 11008),
+                                   (148, 1024, 11008), (513, 544, 640)])
+def test_linear_random_codes(G, oracle, M, N, K):
+    """Uniform random codes (including -8) exercise every tile edge and the exact int32 sum."""
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
+    sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+    sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+    Y, acc = G.gpu_linear(Xq, sx, Wq, sw)
+    Yo, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    assert np.array_equal(acc, acco)
+    assert G.assert_fp16_close(Y, Yo) == 0
+
+
+def test_linear_extreme_codes(G, oracle):
+    """All codes -8 on both sides: the largest accumulator the format allows (64 K)."""
+    M, N, K = 40, 64, 11008
+    Xq = np.full((M, K // 2), 0x88, np.uint8)
+    Wq = np.full((N, K // 2), 0x88, np.uint8)
+    sx = np.full(M, 1.0, np.float16)
+    sw = np.full(N, 2.0 ** -10, np.float16)
+    Y, acc = G.gpu_linear(Xq, sx, Wq, sw)
+    assert np.all(acc == 64 * K)
+    Yo, _ = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    assert G.assert_fp16_close(Y, Yo) == 0
+
+
+def test_config0_end_to_end(G, oracle):
+    """Configuration 0: prune 64 -> 32 tokens, quantize, one 512x512 W4A4 linear."""
+    c = wl.toy_config()
+    idx = G.gpu_prune_topk(c["scores"], c["keep_k"])
+    idx_o = oracle.prune_topk(c["scores"], c["keep_k"])
+    assert np.array_equal(idx, idx_o)
+    rows = G.gpu_kept_rows(idx, 64, 0, 64)
+    assert np.array_equal(rows, oracle.kept_rows(idx_o, 64, 0, 64))
+    Xq, sx = G.gpu_quantize(c["X"], rows=rows)
+    Xq_o, sx_o, _ = oracle.quantize_rows(c["X"], rows=rows)
+    assert np.array_equal(Xq, Xq_o) and np.array_equal(sx.view(np.uint16), sx_o.view(np.uint16))
+    Wq, sw = G.gpu_quantize(c["W"], weight=True)
+    Wq_o, sw_o, _ = oracle.quantize_rows(c["W"])
+    assert np.array_equal(Wq, Wq_o) and np.array_equal(sw.view(np.uint16), sw_o.view(np.uint16))
+    Y, acc = G.gpu_linear(Xq, sx, Wq, sw)
+    Yo, acco = oracle.w4a4_linear(Xq_o, sx_o, Wq_o, sw_o)
+    assert Y.shape == (32, 512)
+    assert np.array_equal(acc, acco)
+    assert G.assert_fp16_close(Y, Yo) == 0
+
+
+def test_attn_scores(G, oracle):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    for (S, H, d, v0, nv) in [(276, 32, 128, 0, 256), (37, 4, 16, 3, 20), (1000, 5, 64, 10, 990)]:
+        q, k = wl.query_and_keys(S, H, d, wl.rng_for(95, S, wl.T_Q))
+        out = torch.zeros(nv, dtype=torch.float32, device="cuda")
+        B.sqap_attn_scores(G.to_dev(q), G.to_dev(k), v0, nv, out)
+        torch.cuda.synchronize()
+        ref = oracle.attn_scores(q, k, v0, nv)
+        assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7)
