@@ -150,7 +150,7 @@ sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, i
     w->magic = kWeightMagic;
     w->N = N;
     w->K = K;
-    w->n_groups = (N + 31) / 32;
+    w->n_groups = ((N + 255) / 256) * 8;
     w->chunks = K / 32;
     size_t data_bytes = (size_t)w->n_groups * w->chunks * 512;
     size_t scale_bytes = (size_t)w->n_groups * 32 * sizeof(__half);

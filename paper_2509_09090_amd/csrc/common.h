@@ -18,13 +18,14 @@ sqap_status fail(sqap_status st, const char *fmt, ...);
 // 32 codes (16 bytes).  For row group g (rows 32g .. 32g+31) and chunk c the
 // 512 bytes at ((g * chunks + c) * 512) hold, for r = 0..31, the 16 packed
 // bytes of row 32g + r, codes 32c .. 32c+31, unchanged from the canonical
-// layout.  Rows past N are zero.  A wavefront that reads 1 KiB contiguous gets
+// layout.  The number of row groups is rounded up to a multiple of 8 (256 rows)
+// so that a GEMM tile never needs a guard in N; rows past N are zero.  A wavefront that reads 1 KiB contiguous gets
 // two chunks of one row group, which is exactly the B operand of two
 // 32x32x32 int8 MFMAs once nibbles are split (low nibbles -> one, high -> other).
 struct Weight {
     uint32_t magic;
     int32_t N, K;
-    int32_t n_groups;   // ceil(N / 32)
+    int32_t n_groups;   // ceil(N / 256) * 8
     int32_t chunks;     // K / 32
     uint8_t *data;      // n_groups * chunks * 512 bytes
     __half *scales;     // n_groups * 32 halves (zero padded)

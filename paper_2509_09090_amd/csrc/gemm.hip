@@ -5,11 +5,16 @@
 // piece of a packed row holds 32 codes; `(x << 4) & 0xF0F0F0F0` turns the 16
 // low nibbles into 16 int8 values equal to 16 * code (the nibble's sign bit
 // lands on the byte's sign bit) and `x & 0xF0F0F0F0` does the same for the high
-// nibbles.  The low-nibble bytes feed lanes 0-31 of a 32x32x32 MFMA operand and
-// the high-nibble bytes feed lanes 32-63; the activation rows are split the
-// same way, so every product pairs codes of the same k.  The accumulator is
-// then 256 * sum(x*w), |.| <= 256 * 64 * K < 2^31 for K <= 131071, and the
-// epilogue shifts it back: the integer result is exact.
+// nibbles.  The low-nibble bytes feed one 32x32x32 MFMA and the high-nibble
+// bytes a second one; the activation rows are split the same way, so every
+// product pairs codes of the same k.  The accumulator is then 256 * sum(x*w),
+// |.| <= 256 * 64 * K < 2^31 for K <= 131071, and the epilogue shifts it back:
+// the integer result is exact.
+#include <stdlib.h>
+
+#include <atomic>
+#include <random>
+
 #include "common.h"
 
 namespace sqap {
@@ -20,6 +25,14 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 constexpr int kBK = 128;            // codes of the reduction axis per main-loop step
 constexpr int kChunksPerStep = 4;   // = kBK / 32, 16-byte packed pieces per row per step
 constexpr int kMaxK = 131040;       // keeps 256 * 64 * K below 2^31
+
+// Persistent (stream-K) launch: at most this many workgroups, 8 XCDs.
+constexpr int kMaxPersistentBlocks = 256;
+constexpr int kXcds = 8;
+constexpr size_t kFlagBytes = 4096;         // workspace header: one flag per workgroup + error word
+constexpr int kErrWord = 500;               // index (in 64-bit words) of the error word in the header
+constexpr int kStreamKMinM = 512;           // from this M on the persistent kernel is used
+constexpr long long kSpinLimit = 200000000; // bounded wait (about a minute of polling)
 
 struct GemmParams {
     const uint8_t *Xq;     // [M, K/2] canonical
@@ -32,18 +45,19 @@ struct GemmParams {
     int M, N, K;
     int n_groups, chunks;
     int m_tiles, n_tiles;
+    bool y_vec_ok;         // Y and its pitch are 16-byte aligned
+    // persistent kernel only
+    unsigned long long *flags;   // workspace header: one 64-bit flag per workgroup
+    unsigned long long epoch;    // value that marks a flag as set by THIS launch
+    uint8_t *partials;     // one BM x BN int32 slot per workgroup
+    int blocks_per_xcd;
 };
 
-__device__ __forceinline__ void widen(const uint4 &p, v4i &lo, v4i &hi)
+__device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
 {
-    lo.x = (int)((p.x << 4) & 0xF0F0F0F0u);
-    lo.y = (int)((p.y << 4) & 0xF0F0F0F0u);
-    lo.z = (int)((p.z << 4) & 0xF0F0F0F0u);
-    lo.w = (int)((p.w << 4) & 0xF0F0F0F0u);
-    hi.x = (int)(p.x & 0xF0F0F0F0u);
-    hi.y = (int)(p.y & 0xF0F0F0F0u);
-    hi.z = (int)(p.z & 0xF0F0F0F0u);
-    hi.w = (int)(p.w & 0xF0F0F0F0u);
+    const v4i mask = {(int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0};
+    lo = (p << 4) & mask;
+    hi = p & mask;
 }
 
 // Y = half((float(acc) * sx) * sw): two binary32 products, then one rounding to
@@ -57,188 +71,528 @@ __device__ __forceinline__ __half dequant(int acc, float sx, float sw)
     return __float2half_rn(y);
 }
 
-// Block tile BM x BN, four wavefronts as 2 x 2, each owning (BM/2) x (BN/2) as
-// 32x32 MFMA tiles.  LDS holds two stages of widened operands in "fragment
-// order": for row group rg (32 rows) and k-step ks (32 codes) the 1 KiB at
-// ((rg * 4 + ks) * 1024) is exactly what the 64 lanes of a wavefront read with
-// one ds_read_b128 (lane l at l * 16): rows in lanes 0-31 (even codes), the
-// same rows in lanes 32-63 (odd codes).
-template <int BM, int BN>
-__global__ __launch_bounds__(256, 1) void gemm_tiled_kernel(const GemmParams p)
+// Static shape of one tile configuration: block tile BM x BN, WAVES_M x WAVES_N
+// wavefronts, each owning (BM/WAVES_M) x (BN/WAVES_N) as 32x32 MFMA tiles.
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_>
+struct Cfg {
+    static constexpr int BM = BM_, BN = BN_, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_;
+    static constexpr int NW = WAVES_M * WAVES_N, THREADS = NW * 64;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int CP = kChunksPerStep / 2;                 // chunk pairs per step
+    static constexpr int A_FRAGS = (BM / 32) * CP, B_FRAGS = (BN / 32) * CP;
+    static constexpr int A_BYTES = A_FRAGS * 1024, B_BYTES = B_FRAGS * 1024;
+    static constexpr int STAGE = A_BYTES + B_BYTES;
+    static constexpr int A_LOADS = (A_FRAGS + NW - 1) / NW, B_LOADS = (B_FRAGS + NW - 1) / NW;
+    static_assert(B_FRAGS % NW == 0, "weight fragments divide over the wavefronts");
+    static_assert(A_FRAGS % NW == 0 || A_FRAGS < NW, "activation fragments divide over the wavefronts");
+    // epilogue staging: 32 rows of each wavefront's tile in halves (+16 bytes of
+    // padding per row) followed by BM token scales and BN channel scales as floats
+    static constexpr int EP_PITCH = WN * 2 + 16;
+    static constexpr int EP_BYTES = NW * 32 * EP_PITCH + (BM + BN) * 4;
+    static constexpr int LDS_BYTES = 2 * STAGE > EP_BYTES ? 2 * STAGE : EP_BYTES;
+};
+
+// Main loop over steps [step_begin, step_end) of one tile (one step = 128
+// codes of K), accumulating into acc.
+//
+// Operands stay PACKED in LDS (half the LDS traffic of int8) and are widened
+// in registers right before the MFMAs.  LDS holds two stages in "fragment
+// order": for row group rg (32 rows) and chunk pair cp (2 x 32 codes) the 1 KiB
+// at ((rg * 2 + cp) * 1024) is what one ds_read_b128 of a wavefront fetches
+// (lane l at l * 16): lanes 0-31 hold rows 0-31 of chunk 2cp, lanes 32-63 the
+// same rows of chunk 2cp+1.  Widening a lane's 16 bytes gives its operand for
+// two MFMAs: the even codes (both chunks, across the two lane halves) and the
+// odd codes.  The weight layout in global memory is already in this order, so
+// its path global -> register -> LDS is a straight 1 KiB copy per wavefront.
+//
+// The MFMAs take the WEIGHT fragment first, so an accumulator tile is the
+// transpose of the output tile (see the epilogue).
+//
+// Loads are unguarded in M and N: rows past M re-read row M-1 and row groups
+// past the end exist as zero padding in the weight layout; what they produce
+// lands in accumulators that are never stored.  RAGGED_K = true guards the
+// reduction axis (K not a multiple of 128) and is the slow, general variant.
+//
+// Pipeline: while stage `cur` feeds the MFMAs, the registers loaded one step
+// ago are copied into the other stage and the loads for two steps ahead are
+// issued.  One barrier per step; a trailing barrier leaves LDS free.
+template <class C, bool RAGGED_K>
+__device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int m0, int ng0, int step_begin,
+                                         int step_end, v16i (&acc)[C::TM][C::TN])
 {
-    constexpr int WM = BM / 2, WN = BN / 2;
-    constexpr int TM = WM / 32, TN = WN / 32;
-    constexpr int A_BYTES = BM * kBK, B_BYTES = BN * kBK;      // per stage, widened
-    constexpr int STAGE = A_BYTES + B_BYTES;
-    constexpr int A_UNITS = BM * kChunksPerStep, B_UNITS = BN * kChunksPerStep;
-    constexpr int A_LOADS = (A_UNITS + 255) / 256, B_LOADS = (B_UNITS + 255) / 256;
-    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int TM = C::TM, TN = C::TN, CP = C::CP;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int Kh = p.K >> 1;
 
+    // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand
+    // (with fewer A fragments than wavefronts, the first A_FRAGS wavefronts move one each).
+    const v4i *a_src[C::A_LOADS];
+    int a_dst[C::A_LOADS], a_chunk[C::A_LOADS];
+    const bool a_mover = wave * C::A_LOADS < C::A_FRAGS;
+#pragma unroll
+    for (int i = 0; i < C::A_LOADS; ++i) {
+        const int f = min(wave * C::A_LOADS + i, C::A_FRAGS - 1), rg = f / CP, cp = f % CP;
+        const int grow = min(m0 + rg * 32 + (lane & 31), p.M - 1);
+        a_chunk[i] = 2 * cp + (lane >> 5);
+        a_src[i] = reinterpret_cast<const v4i *>(p.Xq + (size_t)grow * Kh) + a_chunk[i];
+        a_dst[i] = (f << 10) + (lane << 4);
+    }
+    const v4i *b_src[C::B_LOADS];
+    int b_dst[C::B_LOADS], b_chunk[C::B_LOADS];
+#pragma unroll
+    for (int i = 0; i < C::B_LOADS; ++i) {
+        const int f = wave * C::B_LOADS + i, rg = f / CP, cp = f % CP;
+        b_chunk[i] = 2 * cp + (lane >> 5);
+        b_src[i] = reinterpret_cast<const v4i *>(p.Wd + ((size_t)(ng0 + rg) * p.chunks + 2 * cp) * 512) + lane;
+        b_dst[i] = C::A_BYTES + (f << 10) + (lane << 4);
+    }
+
+    v4i ga[C::A_LOADS], gb[C::B_LOADS];
+
+    auto load_global = [&](int step) {
+        const v4i zero4 = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < C::A_LOADS; ++i) {
+            if (!RAGGED_K || step * kChunksPerStep + a_chunk[i] < p.chunks)
+                ga[i] = a_src[i][step * kChunksPerStep];
+            else
+                ga[i] = zero4;
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_LOADS; ++i) {
+            if (!RAGGED_K || step * kChunksPerStep + b_chunk[i] < p.chunks)
+                gb[i] = b_src[i][step * kChunksPerStep * 32];
+            else
+                gb[i] = zero4;
+        }
+    };
+    auto store_lds = [&](int stage) {
+        uint8_t *base = smem + stage * C::STAGE;
+        if (C::A_FRAGS % C::NW == 0 || a_mover) {
+#pragma unroll
+            for (int i = 0; i < C::A_LOADS; ++i) *reinterpret_cast<v4i *>(base + a_dst[i]) = ga[i];
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + b_dst[i]) = gb[i];
+    };
+    auto compute = [&](int stage) {
+        const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
+        const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+            v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                widen(*reinterpret_cast<const v4i *>(sa + ((i * CP + cp) << 10)), alo[i], ahi[i]);
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+                widen(*reinterpret_cast<const v4i *>(sb + ((jn * CP + cp) << 10)), blo[jn], bhi[jn]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn)
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[jn], alo[i], acc[i][jn], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn)
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
+        }
+    };
+
+    load_global(step_begin);
+    store_lds(0);
+    if (step_begin + 1 < step_end) load_global(step_begin + 1);
+    __syncthreads();
+    int it = step_begin, stage = 0;
+    for (; it + 2 < step_end; ++it) {
+        store_lds(stage ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_global(it + 2);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(stage);
+        __syncthreads();
+        stage ^= 1;
+    }
+    if (it + 1 < step_end) {
+        store_lds(stage ^ 1);
+        compute(stage);
+        __syncthreads();
+        stage ^= 1;
+    }
+    compute(stage);
+    __syncthreads();
+}
+
+// Epilogue: dequantise and store one wavefront's accumulators.  Called by every
+// wavefront of the block (it contains barriers); LDS must be free on entry and
+// is free again on return.
+//
+// An accumulator tile is the transpose of the output tile: lane l holds token
+// row l%32 and, in register e, channel 8*(e/4) + 4*(l/32) + (e%4).  Four
+// consecutive registers are four consecutive channels of one token: 8 bytes of
+// halves, written to LDS in one piece and read back 16 bytes per lane so that
+// a wavefront's global store covers whole rows of its tile.
+template <class C>
+__device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM][C::TN], uint8_t *smem, int m0,
+                                         int ng0)
+{
+    constexpr int TM = C::TM, TN = C::TN, WM = C::WM, WN = C::WN, PITCH = C::EP_PITCH;
+    constexpr int LANES_PER_ROW = WN * 2 / 16;
+    constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const int tok = lane & 31, ch4 = (lane >> 5) * 4;
+    const int wave_col0 = (ng0 << 5) + wn * WN;
 
-    // Tile order: the hardware deals consecutive workgroups to the 8 XCDs in
-    // turn; give each XCD a contiguous run of tiles (n-tile major, m-tile minor)
-    // so that the tiles sharing a weight panel sit behind one L2.
+    if (p.acc_out) {
+        const bool vec = (p.N & 3) == 0 && (reinterpret_cast<uintptr_t>(p.acc_out) & 15u) == 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row = m0 + wm * WM + i * 32 + tok;
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = wave_col0 + jn * 32 + q * 8 + ch4;
+                    if (row < p.M && col < p.N) {
+                        int32_t *dst = p.acc_out + (size_t)row * p.N + col;
+                        v4i v = {acc[i][jn][4 * q] >> 8, acc[i][jn][4 * q + 1] >> 8, acc[i][jn][4 * q + 2] >> 8,
+                                 acc[i][jn][4 * q + 3] >> 8};
+                        if (vec) {
+                            *reinterpret_cast<v4i *>(dst) = v;
+                        } else {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x)
+                                if (col + x < p.N) dst[x] = v[x];
+                        }
+                    }
+                }
+        }
+    }
+
+    float *sxs = reinterpret_cast<float *>(smem + C::NW * 32 * PITCH);   // BM token scales
+    float *sws = sxs + C::BM;                                            // BN channel scales
+    for (int r = t; r < C::BM; r += C::THREADS) sxs[r] = __half2float(p.sx[min(m0 + r, p.M - 1)]);
+    for (int c = t; c < C::BN; c += C::THREADS) sws[c] = __half2float(p.sw[(ng0 << 5) + c]);   // zero padded past N
+    __syncthreads();
+    uint8_t *ep = smem + wave * (32 * PITCH);
+    const bool vec_ok = p.y_vec_ok;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row0 = m0 + wm * WM + i * 32;
+        const float sxf = sxs[wm * WM + i * 32 + tok];
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cin = jn * 32 + q * 8 + ch4;
+                const float4 s4 = *reinterpret_cast<const float4 *>(&sws[wn * WN + cin]);
+                union { __half h[4]; uint2 u; } pk;
+                pk.h[0] = dequant(acc[i][jn][4 * q + 0] >> 8, sxf, s4.x);
+                pk.h[1] = dequant(acc[i][jn][4 * q + 1] >> 8, sxf, s4.y);
+                pk.h[2] = dequant(acc[i][jn][4 * q + 2] >> 8, sxf, s4.z);
+                pk.h[3] = dequant(acc[i][jn][4 * q + 3] >> 8, sxf, s4.w);
+                *reinterpret_cast<uint2 *>(ep + tok * PITCH + cin * 2) = pk.u;
+            }
+        // The staging area is private to the wavefront and LDS operations of one
+        // wavefront complete in order, so no block barrier is needed around it.
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
+            const int rin = ps * ROWS_PER_PASS + lane / LANES_PER_ROW;
+            const int cb = (lane % LANES_PER_ROW) * 16;
+            const int row = row0 + rin, col = wave_col0 + (cb >> 1);
+            if (row < p.M && col < p.N) {
+                const v4i v = *reinterpret_cast<const v4i *>(ep + rin * PITCH + cb);
+                __half *dst = p.Y + (size_t)row * p.ldy + col;
+                if (vec_ok && col + 8 <= p.N) {
+                    *reinterpret_cast<v4i *>(dst) = v;
+                } else {
+                    const __half *h = reinterpret_cast<const __half *>(&v);
+#pragma unroll
+                    for (int x = 0; x < 8; ++x)
+                        if (col + x < p.N) dst[x] = h[x];
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();                                   // LDS is free again
+}
+
+template <class C>
+__device__ __forceinline__ void zero_acc(v16i (&acc)[C::TM][C::TN])
+{
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < C::TN; ++jn)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][jn][e] = 0;
+}
+
+// One tile per workgroup.  Tile order: the hardware deals consecutive
+// workgroups to the 8 XCDs in turn; each XCD gets a contiguous run of tiles
+// (n-tile major, m-tile minor) so that the tiles sharing a weight panel sit
+// behind one L2.
+template <class C, bool RAGGED_K>
+__global__ __launch_bounds__(C::THREADS, 1) void gemm_tiled_kernel(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int tiles = p.m_tiles * p.n_tiles;
     const int bid = blockIdx.x;
     const int xcd = bid & 7, j = bid >> 3;
     const int q = tiles >> 3, r = tiles & 7;
     const int tile = xcd * q + (xcd < r ? xcd : r) + j;
     const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
-    const int m0 = mt * BM, ng0 = nt * (BN / 32);
-    const int Kh = p.K >> 1;
+    const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
+    v16i acc[C::TM][C::TN];
+    zero_acc<C>(acc);
+    const int steps = (p.chunks + kChunksPerStep - 1) / kChunksPerStep;
+    mainloop<C, RAGGED_K>(p, smem, m0, ng0, 0, steps, acc);
+    epilogue<C>(p, acc, smem, m0, ng0);
+}
 
-    // per-thread load slots
-    const uint4 *a_src[A_LOADS];
-    int a_dst[A_LOADS], a_chunk[A_LOADS];
-    bool a_ok[A_LOADS];
-#pragma unroll
-    for (int i = 0; i < A_LOADS; ++i) {
-        const int u = i * 256 + t;
-        const int row = (u >> 6) * 16 + (u & 15), chunk = (u & 63) >> 4;
-        a_ok[i] = (u < A_UNITS) && (m0 + row < p.M);
-        a_chunk[i] = chunk;
-        a_src[i] = reinterpret_cast<const uint4 *>(p.Xq + (size_t)(m0 + row) * Kh) + chunk;
-        a_dst[i] = (((row >> 5) * 4 + chunk) << 10) + ((row & 31) << 4);
-        if (u >= A_UNITS) a_dst[i] = -1;
-    }
-    const uint4 *b_src[B_LOADS];
-    int b_dst[B_LOADS], b_chunk[B_LOADS];
-    bool b_ok[B_LOADS];
-#pragma unroll
-    for (int i = 0; i < B_LOADS; ++i) {
-        const int u = i * 256 + t;
-        const int ngl = u >> 7, rem = u & 127;
-        b_ok[i] = (u < B_UNITS) && (ng0 + ngl < p.n_groups);
-        b_chunk[i] = rem >> 5;
-        b_src[i] = reinterpret_cast<const uint4 *>(p.Wd + ((size_t)(ng0 + ngl) * p.chunks) * 512) + rem;
-        b_dst[i] = A_BYTES + ((ngl * 4 + (rem >> 5)) << 10) + ((rem & 31) << 4);
-        if (u >= B_UNITS) b_dst[i] = -1;
-    }
+// Persistent stream-K kernel.  The tiles are dealt to the 8 XCDs in whole
+// tiles (contiguous runs, as above); inside an XCD the run's main-loop steps
+// are split evenly over that XCD's workgroups, so a tile may be shared by
+// several workgroups.  The workgroup holding the LAST steps of a tile finishes
+// it: it adds the partial accumulators the others left in the workspace (exact:
+// integer sums commute) and runs the epilogue.  A workgroup computes a
+// segment it does not finish FIRST and publishes it at once; the segment it
+// finishes comes LAST.  A finisher therefore only ever waits for workgroups of
+// its own XCD with a lower index, which were dispatched before it and publish
+// before doing anything else, so the wait cannot deadlock; it is bounded all
+// the same, and a timeout raises the error word in the workspace header.
+template <class C>
+__global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int t = threadIdx.x;
+    const int tiles = p.m_tiles * p.n_tiles;
+    const int steps = p.chunks / kChunksPerStep;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, nb = p.blocks_per_xcd;
+    // whole tiles of this XCD
+    const int q = tiles >> 3, r = tiles & 7;
+    const int tile0 = xcd * q + (xcd < r ? xcd : r);
+    const int ntile = q + (xcd < r ? 1 : 0);
+    // this workgroup's share of the XCD's steps: [begin, end)
+    const long long total = (long long)ntile * steps;
+    const long long begin = total * j / nb, end = total * (j + 1) / nb;
+    if (begin >= end) return;
+    const int t_first = (int)(begin / steps), t_last = (int)((end - 1) / steps);
+    const int slot = blockIdx.x;
 
-    v16i acc[TM][TN];
+    // Visit order: downwards from t_last.  Only t_last can be left unfinished by
+    // this workgroup (its steps end before the tile does), and only t_first can
+    // need partial sums from others, so "publish first, finish last" holds.
+    // The two cases are separate code regions (each with its own copy of the main
+    // loop) because one region serving both needs more registers than there are.
+    //
+    // Slot layout: wavefront w, accumulator tile a, quarter q, lane l at
+    // ((w * TM*TN + a) * 4 + q) * 1024 + l * 16 bytes: every store and load of a
+    // wavefront is 1 KiB contiguous, and a tile's four pieces share one base.
+    constexpr int SLOT_BYTES = C::BM * C::BN * 4;
+    const int lane = t & 63, wave = t >> 6;
+    const int my_off = wave * (C::TM * C::TN * 4096) + lane * 16;
+    int tl = t_last;
+    if (end < (long long)(t_last + 1) * steps) {
+        // not the finisher of t_last: compute the head segment and publish it
+        const long long tb = (long long)tl * steps;
+        const int s0 = (int)((begin > tb ? begin : tb) - tb);
+        const int s1 = (int)(end - tb);
+        const int tile = tile0 + tl;
+        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        v16i acc[C::TM][C::TN];
+        zero_acc<C>(acc);
+        mainloop<C, false>(p, smem, mt * C::BM, nt * (C::BN / 32), s0, s1, acc);
+        uint8_t *dst = p.partials + (size_t)slot * SLOT_BYTES + my_off;
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-        for (int jn = 0; jn < TN; ++jn)
+            for (int jn = 0; jn < C::TN; ++jn) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][jn][e] = 0;
-
-    uint4 ga[A_LOADS], gb[B_LOADS];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    const int steps = (p.chunks + kChunksPerStep - 1) / kChunksPerStep;   // a ragged last step reads zeros
-
-    auto load_global = [&](int step) {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i)
-            ga[i] = (a_ok[i] && step * kChunksPerStep + a_chunk[i] < p.chunks) ? a_src[i][step * kChunksPerStep]
-                                                                              : zero4;
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i)
-            gb[i] = (b_ok[i] && step * kChunksPerStep + b_chunk[i] < p.chunks)
-                        ? b_src[i][step * kChunksPerStep * 32]
-                        : zero4;
-    };
-    auto store_lds = [&](int stage) {
-        uint8_t *base = smem + stage * STAGE;
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) {
-            if (a_dst[i] >= 0) {
-                v4i lo, hi;
-                widen(ga[i], lo, hi);
-                *reinterpret_cast<v4i *>(base + a_dst[i]) = lo;
-                *reinterpret_cast<v4i *>(base + a_dst[i] + 512) = hi;
+                for (int qd = 0; qd < 4; ++qd) {
+                    v4i v = {acc[i][jn][4 * qd], acc[i][jn][4 * qd + 1], acc[i][jn][4 * qd + 2],
+                             acc[i][jn][4 * qd + 3]};
+                    *reinterpret_cast<v4i *>(dst + qd * 1024) = v;
+                }
+                dst += 4096;
             }
-        }
-#pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) {
-            if (b_dst[i] >= 0) {
-                v4i lo, hi;
-                widen(gb[i], lo, hi);
-                *reinterpret_cast<v4i *>(base + b_dst[i]) = lo;
-                *reinterpret_cast<v4i *>(base + b_dst[i] + 512) = hi;
-            }
-        }
-    };
-
-    load_global(0);
-    store_lds(0);
-    if (steps > 1) load_global(1);
-    __syncthreads();
-
-    for (int it = 0; it < steps; ++it) {
-        const int cur = it & 1;
-        if (it + 1 < steps) store_lds(cur ^ 1);
-        if (it + 2 < steps) load_global(it + 2);
-        const uint8_t *sa = smem + cur * STAGE + ((wm * TM * 4) << 10) + (lane << 4);
-        const uint8_t *sb = smem + cur * STAGE + A_BYTES + ((wn * TN * 4) << 10) + (lane << 4);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            v4i af[TM], bf[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) af[i] = *reinterpret_cast<const v4i *>(sa + ((i * 4 + ks) << 10));
-#pragma unroll
-            for (int jn = 0; jn < TN; ++jn) bf[jn] = *reinterpret_cast<const v4i *>(sb + ((jn * 4 + ks) << 10));
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[i], bf[jn], acc[i][jn], 0, 0, 0);
-        }
+        // The consumers sit behind the same L2 (same XCD); the stores are complete
+        // there once the vector-memory counter drains, and the flag goes out after that.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        if (t == 0) __hip_atomic_store(&p.flags[slot], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        --tl;
     }
-
-    // Epilogue.  In a 32x32 accumulator tile lane l, register e holds
-    // row 8*(e/4) + 4*(l/32) + (e%4), column l%32.
-    const int col_in = lane & 31, row_half = (lane >> 5) * 4;
+    for (; tl >= t_first; --tl) {
+        const long long tb = (long long)tl * steps;
+        const int s0 = (int)((begin > tb ? begin : tb) - tb);
+        const int tile = tile0 + tl;
+        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
+        v16i acc[C::TM][C::TN];
+        zero_acc<C>(acc);
+        mainloop<C, false>(p, smem, m0, ng0, s0, steps, acc);
+        if (s0 > 0) {
+            // finisher of a shared tile: steps [0, s0) were done by lower workgroups of this XCD
+            int first = (int)((tb * nb) / total);            // candidate for the workgroup holding step tb
+            while (total * (first + 1) / nb <= tb) ++first;  // (integer division: settle exactly)
+            while (total * first / nb > tb) --first;
+            if (t == 0) {
+                for (int jj = first; jj < j; ++jj) {
+                    if (total * jj / nb >= total * (jj + 1) / nb) continue;   // that workgroup had no steps
+                    const unsigned long long *f = &p.flags[jj * 8 + xcd];
+                    long long spins = 0;
+                    while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
+                        __builtin_amdgcn_s_sleep(8);
+                        if (++spins > kSpinLimit) {
+                            p.flags[kErrWord] = p.epoch;      // give up: the result of this tile is wrong
+                            break;
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            // Partials are read with agent-scope loads (sc1): they bypass this CU's L1 and
+            // are served by the L2 the producer wrote through.
+            for (int jj = first; jj < j; ++jj) {
+                if (total * jj / nb >= total * (jj + 1) / nb) continue;
+                __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    p.partials + (size_t)(jj * 8 + xcd) * SLOT_BYTES, 0, SLOT_BYTES, 0x00020000);
+                // half of the accumulator at a time: 16 loads in flight per thread
 #pragma unroll
-    for (int jn = 0; jn < TN; ++jn) {
-        const int col = (ng0 << 5) + wn * WN + jn * 32 + col_in;
-        const bool col_ok = col < p.N;
-        const float swf = col_ok ? __half2float(p.sw[col]) : 0.f;
+                for (int h = 0; h < 2; ++h) {
+                    constexpr int TILES = C::TM * C::TN, HALF = TILES / 2;
+                    v4i tmp[HALF * 4];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+                    for (int a = 0; a < HALF; ++a)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = m0 + wm * WM + i * 32 + ((e >> 2) << 3) + row_half + (e & 3);
-                if (col_ok && row < p.M) {
-                    const int a = acc[i][jn][e] >> 8;
-                    const float sxf = __half2float(p.sx[row]);
-                    p.Y[(size_t)row * p.ldy + col] = dequant(a, sxf, swf);
-                    if (p.acc_out) p.acc_out[(size_t)row * p.N + col] = a;
+                        for (int qd = 0; qd < 4; ++qd) {
+                            const auto v = __builtin_amdgcn_raw_buffer_load_b128(
+                                rsrc, my_off + (h * HALF + a) * 4096 + qd * 1024, 0, 16);
+                            tmp[a * 4 + qd] = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+                        }
+#pragma unroll
+                    for (int a = 0; a < HALF; ++a) {
+                        const int ta = h * HALF + a, i = ta / C::TN, jn = ta % C::TN;
+#pragma unroll
+                        for (int qd = 0; qd < 4; ++qd) {
+                            acc[i][jn][4 * qd] += tmp[a * 4 + qd].x;
+                            acc[i][jn][4 * qd + 1] += tmp[a * 4 + qd].y;
+                            acc[i][jn][4 * qd + 2] += tmp[a * 4 + qd].z;
+                            acc[i][jn][4 * qd + 3] += tmp[a * 4 + qd].w;
+                        }
+                    }
                 }
             }
         }
+        epilogue<C>(p, acc, smem, m0, ng0);
     }
 }
 
-size_t linear_workspace_bytes(int, int, int) { return 0; }
-
-template <int BM, int BN>
-static sqap_status launch_tiled(GemmParams &p, hipStream_t st)
+// Flags need no clearing between launches: a flag counts as set only when it
+// holds the launch's own epoch, a 64-bit value never used before in this
+// process (a per-process random upper half and a counter).  Whatever an earlier
+// launch or another owner of the memory left there differs from it.
+static unsigned long long next_epoch()
 {
-    p.m_tiles = (p.M + BM - 1) / BM;
-    p.n_tiles = (p.n_groups * 32 + BN - 1) / BN;
-    const size_t lds = (size_t)2 * (BM + BN) * kBK;
+    static std::atomic<unsigned long long> counter{0};
+    static const unsigned long long salt = [] {
+        std::random_device rd;
+        unsigned long long s = ((unsigned long long)rd() << 32) ^ (unsigned long long)rd();
+        return (s | 1ull) << 32;
+    }();
+    return salt + (++counter);
+}
+
+static int persistent_blocks()
+{
+    static int blocks = 0;
+    if (blocks == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kXcds)
+            cus = kMaxPersistentBlocks;
+        if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
+        blocks = (cus / kXcds) * kXcds;
+    }
+    return blocks;
+}
+
+using CfgBig = Cfg<256, 256, 2, 4>;
+
+size_t linear_workspace_bytes(int M, int, int K)
+{
+    if (M >= kStreamKMinM && K % kBK == 0)
+        return kFlagBytes + (size_t)kMaxPersistentBlocks * CfgBig::BM * CfgBig::BN * sizeof(int32_t);
+    return 0;
+}
+
+template <class C, class K>
+static sqap_status set_lds(K kernel)
+{
+    SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+    return SQAP_OK;
+}
+
+template <class C, bool RAGGED_K>
+static sqap_status launch_tiled_k(GemmParams &p, hipStream_t st)
+{
+    p.m_tiles = (p.M + C::BM - 1) / C::BM;
+    p.n_tiles = (p.N + C::BN - 1) / C::BN;
     static bool configured = false;
     if (!configured) {
-        SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_tiled_kernel<BM, BN>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        sqap_status s = set_lds<C>(&gemm_tiled_kernel<C, RAGGED_K>);
+        if (s != SQAP_OK) return s;
         configured = true;
     }
     const int64_t blocks = (int64_t)p.m_tiles * p.n_tiles;
     if (blocks > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_w4a4_linear: too many tiles");
-    hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN>), dim3((unsigned)blocks), dim3(256), lds, st, p);
+    hipLaunchKernelGGL((gemm_tiled_kernel<C, RAGGED_K>), dim3((unsigned)blocks), dim3(C::THREADS), C::LDS_BYTES, st,
+                       p);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+template <class C>
+static sqap_status launch_tiled(GemmParams &p, hipStream_t st)
+{
+    if (p.chunks % kChunksPerStep) return launch_tiled_k<C, true>(p, st);
+    return launch_tiled_k<C, false>(p, st);
+}
+
+template <class C>
+static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st)
+{
+    p.m_tiles = (p.M + C::BM - 1) / C::BM;
+    p.n_tiles = (p.N + C::BN - 1) / C::BN;
+    const int blocks = persistent_blocks();
+    p.blocks_per_xcd = blocks / kXcds;
+    p.flags = reinterpret_cast<unsigned long long *>(workspace);
+    p.epoch = next_epoch();
+    p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;
+    static bool configured = false;
+    if (!configured) {
+        sqap_status s = set_lds<C>(&gemm_streamk_kernel<C>);
+        if (s != SQAP_OK) return s;
+        configured = true;
+    }
+    hipLaunchKernelGGL((gemm_streamk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
 
 sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const Weight &w,
-                               __half *Y, int64_t ldy, int32_t *acc_out, void *, hipStream_t st)
+                               __half *Y, int64_t ldy, int32_t *acc_out, void *workspace, hipStream_t st)
 {
     if (w.K > kMaxK) return fail(SQAP_EUNSUPPORTED, "sqap_w4a4_linear: K = %d above %d", w.K, kMaxK);
-    GemmParams p;
+    GemmParams p = {};
     p.Xq = Xq;
     p.sx = sx;
     p.Wd = w.data;
@@ -251,9 +605,12 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
     p.K = w.K;
     p.n_groups = w.n_groups;
     p.chunks = w.chunks;
-    if (M <= 64) return launch_tiled<64, 256>(p, st);
-    if (M <= 128) return launch_tiled<128, 256>(p, st);
-    return launch_tiled<256, 256>(p, st);
+    p.y_vec_ok = (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (ldy & 7) == 0;
+    if (M <= 64) return launch_tiled<Cfg<64, 256, 1, 4>>(p, st);
+    if (M <= 128) return launch_tiled<Cfg<128, 256, 2, 4>>(p, st);
+    static const int v = getenv("SQAP_V") ? atoi(getenv("SQAP_V")) : 0;
+    if (M >= kStreamKMinM && w.K % kBK == 0 && v == 0) return launch_streamk<CfgBig>(p, workspace, st);
+    return launch_tiled<CfgBig>(p, st);
 }
 
 }  // namespace sqap
