@@ -11,9 +11,10 @@ the batched-prefill workload (16 observations x 276 tokens, each pruned to
 
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 `value` is 2*M*N*K of the two linears divided by the whole step time (TOPS).
-The `roofline` object is for the prefill GEMM kernel (int8 MFMA bound), timed
-with HIP events around its launches; `decode` reports the small-M path
-(HBM bound); `cpu_baseline` times the CPU oracle on a bounded sample.
+`roofline` is for the prefill GEMM kernel (int8 MFMA bound), timed with HIP
+events recorded on the launch stream around its launches.  `decode` reports the
+small-M path over the 32-layer stack + lm_head (HBM bound), with its own
+roofline object.  `cpu_baseline` times the CPU oracle on the same step.
 """
 import argparse
 import json
@@ -25,7 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-INT8_MFMA_PEAK_TOPS = 5033.0      # 8192 op/clk/CU x 256 CU x 2.4 GHz (dense)
+INT8_MFMA_PEAK_TOPS = 5033.0      # 8192 op/clk/CU x 256 CU x 2.4 GHz (dense), = 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
 
 
@@ -36,8 +37,19 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--only", default="", help="run only the main loop this many times (for profilers)")
+    ap.add_argument("--no-layers", action="store_true")
+    ap.add_argument("--only", default="", help="prefill|decode: run just that loop --steps times (for profilers)")
     return ap.parse_args()
+
+
+def quantize_and_pack(torch, B, W):
+    N, K = W.shape
+    Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
+    sw = torch.empty((N,), dtype=torch.float16, device=W.device)
+    B.sqap_quantize_weight(W, Wq, sw)
+    h = B.sqap_weight_pack(Wq, sw)
+    torch.cuda.synchronize()
+    return h
 
 
 class Prefill:
@@ -55,8 +67,8 @@ class Prefill:
         self.scores = t(wl.scores(self.batch, self.nv, wl.rng_for(3, 0, wl.T_SCORES)))
         self.X = t(wl.layer_input(3, 0, 4, self.batch * self.S))          # gate/up input, all tokens
         self.Xd = t(wl.layer_input(3, 0, 6, self.M))                       # down input, kept tokens
-        self.W_gate = self._weight(t(wl.layer_weight(3, 0, 4)))
-        self.W_down = self._weight(t(wl.layer_weight(3, 0, 6)))
+        self.W_gate = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 4)))
+        self.W_down = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 6)))
         i32, u8, f16 = torch.int32, torch.uint8, torch.float16
         self.idx = torch.empty((self.batch, self.keep), dtype=i32, device=dev)
         self.rows = torch.empty((self.M,), dtype=i32, device=dev)
@@ -67,19 +79,9 @@ class Prefill:
         self.Yg = torch.empty((self.M, F), dtype=f16, device=dev)
         self.Yd = torch.empty((self.M, H), dtype=f16, device=dev)
         nws = max(B.sqap_workspace_bytes(self.M, F, H), B.sqap_workspace_bytes(self.M, H, F), 256)
-        self.ws = torch.empty((nws,), dtype=u8, device=dev)
+        self.ws = torch.zeros((nws,), dtype=u8, device=dev)
         self.ops = 2.0 * self.M * (F * H + H * F)
         self.gemm_events = None
-
-    def _weight(self, W):
-        torch, B = self.torch, self.B
-        N, K = W.shape
-        Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
-        sw = torch.empty((N,), dtype=torch.float16, device=W.device)
-        B.sqap_quantize_weight(W, Wq, sw)
-        h = B.sqap_weight_pack(Wq, sw)
-        torch.cuda.synchronize()
-        return h
 
     def step(self):
         B, ev = self.B, self.gemm_events
@@ -118,15 +120,159 @@ def time_gemm_launches(torch, wk, steps):
     return total_ms / launches, {k: v / steps for k, v in per.items()}
 
 
-def cpu_baseline(wl, wk_M_per_obs, n_obs=4):
-    """The oracle, as it stands, on 4 of the 16 observations of the same workload."""
-    import numpy as np
+class Stack:
+    """The 32-layer linear stack + lm_head as packed W4 weights (3.30 GB), from a seeded
+    GPU generator (host generation of 6.6 G normals would take minutes)."""
+
+    def __init__(self, torch, B, wl, dev, layers=None):
+        self.torch, self.B, self.wl, self.dev = torch, B, wl, dev
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.BASE_SEED)
+        self.g = g
+        self.layers = wl.N_LAYERS if layers is None else layers
+        self.weights = []
+        for _ in range(self.layers):
+            row = []
+            for (_, N, K) in wl.LAYER_LINEARS:
+                W = (torch.randn((N, K), generator=g, device=dev, dtype=torch.float32) * 0.02).half()
+                row.append(quantize_and_pack(torch, B, W))
+                del W
+            self.weights.append(row)
+        _, V, Hd = wl.LM_HEAD
+        W = (torch.randn((V, Hd), generator=g, device=dev, dtype=torch.float32) * 0.02).half()
+        self.lm_head = quantize_and_pack(torch, B, W)
+        del W
+        self.weight_bytes = self.layers * sum(N * K // 2 for (_, N, K) in wl.LAYER_LINEARS) + V * Hd // 2
+        self.scale_bytes = 2 * (self.layers * sum(N for (_, N, K) in wl.LAYER_LINEARS) + V)
+
+    def activation(self, M, K):
+        """Quantized [M, K] input: N(0,1) with 1 % outlier channels x30 (fixed channels)."""
+        torch, B, wl = self.torch, self.B, self.wl
+        x = torch.randn((M, K), generator=self.g, device=self.dev, dtype=torch.float32)
+        ch = torch.randperm(K, generator=self.g, device=self.dev)[: wl.n_outliers_for(K)]
+        x[:, ch] *= 30.0
+        x = x.half()
+        Xq = torch.empty((M, K // 2), dtype=torch.uint8, device=self.dev)
+        sx = torch.empty((M,), dtype=torch.float16, device=self.dev)
+        B.sqap_quantize_act(x, None, Xq, sx)
+        return Xq, sx
+
+
+def decode_leg(torch, B, wl, stack, steps_per_m=7):
+    """Configuration 4: M in {1, 8} through every linear of the stack + lm_head.  Each linear
+    has its own input (the workload has no glue between linears), so a whole step is one
+    group launch; the dependency-respecting variant (4 launches per layer) is timed too."""
+    out = {}
+    dev = stack.dev
+    H, F = wl.HIDDEN, wl.FFN
+    for M in (1, 8):
+        xq_h = [stack.activation(M, H) for _ in range(3)]      # qkv input, o input, gate/up input
+        xq_f = stack.activation(M, F)
+        problems, levels = [], []
+        for l in range(stack.layers):
+            ys = []
+            for i, (name, N, K) in enumerate(wl.LAYER_LINEARS):
+                src = xq_f if K == F else (xq_h[0] if i < 3 else xq_h[1] if i == 3 else xq_h[2])
+                Y = torch.empty((M, N), dtype=torch.float16, device=dev)
+                ys.append((src[0], src[1], stack.weights[l][i], Y))
+            problems += ys
+            levels += [ys[0:3], ys[3:4], ys[4:6], ys[6:7]]
+        _, V, _ = wl.LM_HEAD
+        lm = (xq_h[0][0], xq_h[0][1], stack.lm_head, torch.empty((M, V), dtype=torch.float16, device=dev))
+        problems.append(lm)
+        levels.append([lm])
+        whole = B.sqap_group_create(problems)
+        per_level = [B.sqap_group_create(lv) for lv in levels]
+
+        def timed(fn):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps_per_m):            # 7 sequential action tokens
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps_per_m
+
+        ms_whole = timed(whole.run)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for gq in per_level:
+                gq.run()
+        ms_levels = timed(graph.replay)
+        alg_bytes = stack.weight_bytes + stack.scale_bytes + M * sum(
+            K // 2 + 2 * N for (_, N, K) in wl.LAYER_LINEARS) * stack.layers
+        out["M%d" % M] = {
+            "us_per_step": ms_whole * 1e3, "GBps": alg_bytes / (ms_whole * 1e-3) / 1e9,
+            "frac_of_hbm_peak": alg_bytes / (ms_whole * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "launches": 1,
+            "per_level": {"launches": len(per_level), "us_per_step": ms_levels * 1e3,
+                          "GBps": alg_bytes / (ms_levels * 1e-3) / 1e9},
+        }
+        whole.free()
+        for gq in per_level:
+            gq.free()
+    best = out["M1"]
+    out["roofline"] = {"bound": "hbm", "kernel": "skinny_kernel<1>", "achieved": best["GBps"],
+                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["GBps"] / HBM_PEAK_GBS,
+                       "traffic": None, "algorithmic_bytes_per_launch": stack.weight_bytes + stack.scale_bytes}
+    out["weights_GB"] = stack.weight_bytes / 1e9
+    return out
+
+
+def layer_leg(torch, B, wl, stack):
+    """Configurations 1 and 2: per-layer latency of the 7 linears at M = 148 (one layer) and the
+    32-layer stack at M = 276 for 2 layers then M = 84; one launch per linear, distinct weights."""
+    dev = stack.dev
+    H, F = wl.HIDDEN, wl.FFN
+    res = {}
+
+    def run_layers(M, layer_ids):
+        xh, xf = stack.activation(M, H), stack.activation(M, F)
+        ys = {N: torch.empty((M, N), dtype=torch.float16, device=dev) for N in (H, F)}
+        nws = max([B.sqap_workspace_bytes(M, N, K) for (_, N, K) in wl.LAYER_LINEARS] + [256])
+        ws = torch.zeros((nws,), dtype=torch.uint8, device=dev)
+
+        def go():
+            for l in layer_ids:
+                for i, (_, N, K) in enumerate(wl.LAYER_LINEARS):
+                    x = xf if K == F else xh
+                    B.sqap_w4a4_linear(x[0], x[1], stack.weights[l][i], ys[N], None, ws)
+        go()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 3
+        e0.record()
+        for _ in range(reps):
+            go()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3        # us for all the listed layers
+
+    n = stack.layers
+    ops_layer = lambda M: 2.0 * M * sum(N * K for (_, N, K) in wl.LAYER_LINEARS)
+    us148 = run_layers(148, range(n)) / n
+    res["cfg1_M148"] = {"us_per_layer": us148, "TOPS": ops_layer(148) / us148 / 1e6,
+                        "floor_us": 14.6, "note": "average over %d distinct layers (no cache reuse)" % n}
+    us276 = run_layers(276, range(min(2, n))) / min(2, n)
+    us84 = run_layers(84, range(min(2, n), n)) / max(1, n - 2)
+    total = 2 * us276 + 30 * us84
+    res["cfg2_stack"] = {"us_per_layer_M276": us276, "us_per_layer_M84": us84, "us_total_32_layers": total,
+                         "floor_us": 456.0, "TOPS": (2 * ops_layer(276) + 30 * ops_layer(84)) / total / 1e6}
+    return res
+
+
+def cpu_baseline(wl):
+    """The oracle, as it stands, on the same step (all 16 observations)."""
+    import ctypes
     import oracle
-    H, F, S, nv, keep = wl.HIDDEN, wl.FFN, wl.SEQ_LEN, wl.N_VISUAL, wl.CONFIGS[3]["keep_k"]
-    scores = wl.scores(16, nv, wl.rng_for(3, 0, wl.T_SCORES))[:n_obs]
-    X = wl.layer_input(3, 0, 4, 16 * S)[: n_obs * S]
-    M = n_obs * wk_M_per_obs
-    Xd = wl.layer_input(3, 0, 6, 16 * wk_M_per_obs)[:M]
+    H, F, S, nv = wl.HIDDEN, wl.FFN, wl.SEQ_LEN, wl.N_VISUAL
+    keep, batch = wl.CONFIGS[3]["keep_k"], wl.CONFIGS[3]["batch"]
+    M = batch * (keep + wl.N_TEXT)
+    scores = wl.scores(batch, nv, wl.rng_for(3, 0, wl.T_SCORES))
+    X = wl.layer_input(3, 0, 4, batch * S)
+    Xd = wl.layer_input(3, 0, 6, M)
     Wg, sg, _ = oracle.quantize_rows(wl.layer_weight(3, 0, 4))       # offline step, not timed
     Wd, sd, _ = oracle.quantize_rows(wl.layer_weight(3, 0, 6))
     t0 = time.perf_counter()
@@ -138,12 +284,20 @@ def cpu_baseline(wl, wk_M_per_obs, n_obs=4):
     oracle.w4a4_linear(Xdq, sxd, Wd, sd)
     dt = time.perf_counter() - t0
     ops = 2.0 * M * (F * H + H * F)
-    import ctypes
     threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
     return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
-            "seconds": dt,
-            "sample": "%d of 16 observations (M=%d) through the same prune/quantize/gate-up/down path"
-                      % (n_obs, M)}
+            "seconds": dt, "sample": "one whole step of the same workload (16 observations, M=%d): "
+                                     "prune, rows, quantize, gate/up, quantize, down" % M}
+
+
+def stored_traffic(kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (see profiles/); None if not recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(kernel)
+    except (OSError, ValueError):
+        return None
 
 
 def main():
@@ -158,10 +312,15 @@ def main():
     B.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    wk = Prefill(torch, B, wl, dev)
 
-    if args.only:
-        for _ in range(int(args.only)):
+    if args.only == "decode":
+        stack = Stack(torch, B, wl, dev)
+        print(json.dumps(decode_leg(torch, B, wl, stack, steps_per_m=args.steps)))
+        return
+
+    wk = Prefill(torch, B, wl, dev)
+    if args.only == "prefill":
+        for _ in range(args.steps):
             wk.step()
         torch.cuda.synchronize()
         return
@@ -182,20 +341,32 @@ def main():
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
 
     out = {
-        "metric": "W4A4 linear TOPS (prefill, pruned tokens)",
+        "metric": "W4A4 linear TOPS (prefill, pruned tokens) + decode GB/s, fraction of peak",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int4 codes -> int8 MFMA -> int32 acc -> fp16",
+        "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": "configs[3]: batched prefill, 16 obs x 276 tokens pruned to 148, M=2368; "
-                               "gate/up 4096->11008 and down 11008->4096",
+                               "gate/up 4096->11008 and down 11008->4096, int4 codes widened to int8 MFMA",
                    "M": wk.M, "step": "prune_topk+kept_rows+quantize_act+linear+quantize_act+linear"},
-        "roofline": {"bound": "mfma", "kernel": "gemm_tiled_kernel<256,256>", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": "gemm_streamk_kernel<Cfg<256,256,2,4>>", "achieved": achieved,
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS,
-                     "avg_launch_ms": gemm_ms, "per_gemm_ms": per_gemm, "traffic": None},
+                     "avg_launch_ms": gemm_ms, "per_gemm_ms": per_gemm,
+                     "algorithmic_ops_per_launch": gemm_ops,
+                     "traffic": stored_traffic("gemm_streamk_kernel")},
     }
+    del wk
+    torch.cuda.empty_cache()
+    if not (args.no_decode and args.no_layers):
+        stack = Stack(torch, B, wl, dev)
+        if not args.no_decode:
+            out["decode"] = decode_leg(torch, B, wl, stack)
+            out["decode"]["roofline"]["traffic"] = stored_traffic("skinny_kernel")
+        if not args.no_layers:
+            out["layers"] = layer_leg(torch, B, wl, stack)
+        del stack
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, wk.keep + wl.N_TEXT)
+        out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 
 

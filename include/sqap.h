@@ -172,6 +172,41 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
                              const sqap_weight *W, sqap_f16 *Y, int64_t ldy, int32_t *acc_out,
                              void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Grouped small-M linears (autoregressive decode, M <= 8).  Decode streams
+ * every weight once per step and a single linear moves only a few megabytes,
+ * so launching linears one by one leaves the memory system idle between them.
+ * A group is a device-resident table of INDEPENDENT problems (for example
+ * q/k/v of one layer, which share an input, or gate/up) that one launch
+ * streams through back to back; each problem computes exactly what
+ * sqap_w4a4_linear computes.  Build the group once, run it every step.
+ *
+ * descs is a HOST array; the device pointers inside it are captured, not
+ * copied, and must stay valid while the group is used.  Outputs of different
+ * problems must not overlap.
+ * EINVAL: null pointers, count <= 0, M < 1, ldy < N, bad weight handle.
+ * EUNSUPPORTED: some M > 8 or some K not a multiple of 64.  ENOMEM / EDEVICE.
+ */
+typedef struct sqap_linear_desc {
+    const uint8_t *Xq;      /* [M, K/2] canonical, 16-byte aligned */
+    const sqap_f16 *sx;     /* [M] */
+    int32_t M;
+    const sqap_weight *W;
+    sqap_f16 *Y;            /* [M, N], pitch ldy */
+    int64_t ldy;
+    int32_t *acc_out;       /* NULL or [M, N] int32 */
+} sqap_linear_desc;
+
+typedef struct sqap_group sqap_group;
+
+sqap_status sqap_group_create(const sqap_linear_desc *descs, int32_t count, sqap_group **out);
+
+/* Enqueues the whole group on `stream` as one launch.  No host synchronisation. */
+sqap_status sqap_group_run(const sqap_group *g, void *stream);
+
+/* Frees a group (NULL allowed); the caller makes sure no launch still uses it. */
+sqap_status sqap_group_free(sqap_group *g);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,15 @@ EXPORTS = (
     "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_prune_topk", "sqap_kept_rows",
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
+    "sqap_group_create", "sqap_group_run", "sqap_group_free",
 )
+
+
+class LinearDesc(ctypes.Structure):
+    """Mirror of sqap_linear_desc."""
+    _fields_ = [("Xq", ctypes.c_void_p), ("sx", ctypes.c_void_p), ("M", ctypes.c_int32),
+                ("W", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("ldy", ctypes.c_int64),
+                ("acc_out", ctypes.c_void_p)]
 
 
 class SqapError(RuntimeError):
@@ -57,6 +65,9 @@ def lib():
         L.sqap_workspace_bytes.restype = sz
         L.sqap_workspace_bytes.argtypes = [i32, i32, i32]
         L.sqap_w4a4_linear.argtypes = [vp, vp, i32, vp, vp, i64, vp, vp, sz, vp]
+        L.sqap_group_create.argtypes = [ctypes.POINTER(LinearDesc), i32, ctypes.POINTER(vp)]
+        L.sqap_group_run.argtypes = [vp, vp]
+        L.sqap_group_free.argtypes = [vp]
         for name in EXPORTS:
             if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
@@ -163,3 +174,43 @@ def sqap_w4a4_linear(Xq, sx, W, Y, acc_out=None, workspace=None, stream=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().sqap_w4a4_linear(_ptr(Xq), _ptr(sx), M, W.handle, _ptr(Y), Y.stride(0), _ptr(acc_out),
                                   _ptr(workspace), ws_bytes, _stream(stream)))
+
+
+class Group:
+    """Owns a sqap_group handle; keeps the tensors it points to alive."""
+
+    def __init__(self, handle, keep):
+        self.handle, self._keep = handle, keep
+
+    def run(self, stream=None):
+        _check(lib().sqap_group_run(self.handle, _stream(stream)))
+
+    def free(self):
+        if self.handle:
+            _check(lib().sqap_group_free(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def sqap_group_create(problems):
+    """problems: list of (Xq, sx, Weight, Y) or (Xq, sx, Weight, Y, acc_out) with M <= 8."""
+    n = len(problems)
+    arr = (LinearDesc * n)()
+    for i, pr in enumerate(problems):
+        Xq, sx, W, Y = pr[:4]
+        acc = pr[4] if len(pr) > 4 else None
+        arr[i].Xq, arr[i].sx, arr[i].M = Xq.data_ptr(), sx.data_ptr(), Xq.shape[0]
+        arr[i].W, arr[i].Y, arr[i].ldy = W.handle.value, Y.data_ptr(), Y.stride(0)
+        arr[i].acc_out = None if acc is None else acc.data_ptr()
+    h = ctypes.c_void_p()
+    _check(lib().sqap_group_create(arr, n, ctypes.byref(h)))
+    return Group(h, list(problems))
+
+
+def sqap_group_run(group, stream=None):
+    group.run(stream)

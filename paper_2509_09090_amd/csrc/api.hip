@@ -226,9 +226,120 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
         if (reinterpret_cast<uintptr_t>(workspace) & 255u)
             return fail(SQAP_EINVAL, "sqap_w4a4_linear: workspace must be 256-byte aligned");
     }
+    if (M <= kSkinnyMaxM && w->K % 64 == 0) {
+        SkinnyArgs a = {};
+        a.table = nullptr;
+        a.count = 1;
+        a.total_items = (w->N + 31) / 32;
+        SkinnyEntry &e = a.inline_entries[0];
+        e.Xq = Xq;
+        e.sx = reinterpret_cast<const __half *>(sx);
+        e.Wd = w->data;
+        e.sw = w->scales;
+        e.Y = reinterpret_cast<__half *>(Y);
+        e.acc_out = acc_out;
+        e.ldy = ldy;
+        e.M = M;
+        e.N = w->N;
+        e.chunks = w->chunks;
+        e.rg_begin = 0;
+        e.cost_begin = 0;
+        a.total_cost = (long long)a.total_items * w->chunks;
+        return launch_skinny(a, w->chunks, as_stream(stream));
+    }
     return launch_w4a4_linear(Xq, reinterpret_cast<const __half *>(sx), M, *w,
                               reinterpret_cast<__half *>(Y), ldy, acc_out, workspace,
                               as_stream(stream));
+}
+
+sqap_status sqap_group_create(const sqap_linear_desc *descs, int32_t count, sqap_group **out)
+{
+    if (out) *out = nullptr;
+    if (!descs || !out) return fail(SQAP_EINVAL, "sqap_group_create: null pointer");
+    if (count <= 0) return fail(SQAP_EINVAL, "sqap_group_create: count = %d", count);
+    SkinnyEntry *host = new (std::nothrow) SkinnyEntry[count];
+    if (!host) return fail(SQAP_ENOMEM, "sqap_group_create: host allocation failed");
+    int total = 0, max_chunks = 0;
+    long long cost = 0;
+    for (int i = 0; i < count; ++i) {
+        const sqap_linear_desc &d = descs[i];
+        const Weight *w = check_weight(d.W);
+        sqap_status st = SQAP_OK;
+        if (!w) st = fail(SQAP_EINVAL, "sqap_group_create: problem %d: W is not a weight handle", i);
+        else if (!d.Xq || !d.sx || !d.Y) st = fail(SQAP_EINVAL, "sqap_group_create: problem %d: null pointer", i);
+        else if (d.M < 1) st = fail(SQAP_EINVAL, "sqap_group_create: problem %d: M = %d", i, d.M);
+        else if (d.ldy < w->N) st = fail(SQAP_EINVAL, "sqap_group_create: problem %d: ldy below N", i);
+        else if (d.M > kSkinnyMaxM) st = fail(SQAP_EUNSUPPORTED, "sqap_group_create: problem %d: M = %d > %d", i, d.M, kSkinnyMaxM);
+        else if (w->K % 64 != 0) st = fail(SQAP_EUNSUPPORTED, "sqap_group_create: problem %d: K = %d is not a multiple of 64", i, w->K);
+        else if (!aligned16(d.Xq)) st = fail(SQAP_EUNSUPPORTED, "sqap_group_create: problem %d: Xq must be 16-byte aligned", i);
+        if (st != SQAP_OK) {
+            delete[] host;
+            return st;
+        }
+        SkinnyEntry &e = host[i];
+        e.Xq = d.Xq;
+        e.sx = reinterpret_cast<const __half *>(d.sx);
+        e.Wd = w->data;
+        e.sw = w->scales;
+        e.Y = reinterpret_cast<__half *>(d.Y);
+        e.acc_out = d.acc_out;
+        e.ldy = d.ldy;
+        e.M = d.M;
+        e.N = w->N;
+        e.chunks = w->chunks;
+        e.rg_begin = total;
+        e.cost_begin = cost;
+        total += (w->N + 31) / 32;
+        cost += (long long)((w->N + 31) / 32) * w->chunks;
+        if (w->chunks > max_chunks) max_chunks = w->chunks;
+    }
+    Group *g = new (std::nothrow) Group();
+    if (!g) {
+        delete[] host;
+        return fail(SQAP_ENOMEM, "sqap_group_create: host allocation failed");
+    }
+    g->magic = kGroupMagic;
+    g->count = count;
+    g->total_items = total;
+    g->max_chunks = max_chunks;
+    g->total_cost = cost;
+    g->table = nullptr;
+    hipError_t e = hipGetDevice(&g->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&g->table), sizeof(SkinnyEntry) * count);
+    if (e == hipSuccess) e = hipMemcpy(g->table, host, sizeof(SkinnyEntry) * count, hipMemcpyHostToDevice);
+    delete[] host;
+    if (e != hipSuccess) {
+        if (g->table) (void)hipFree(g->table);
+        delete g;
+        return fail(e == hipErrorOutOfMemory ? SQAP_ENOMEM : SQAP_EDEVICE, "sqap_group_create: %s",
+                    hipGetErrorString(e));
+    }
+    *out = reinterpret_cast<sqap_group *>(g);
+    return SQAP_OK;
+}
+
+sqap_status sqap_group_run(const sqap_group *g, void *stream)
+{
+    const Group *gg = reinterpret_cast<const Group *>(g);
+    if (!gg || gg->magic != kGroupMagic) return fail(SQAP_EINVAL, "sqap_group_run: not a group handle");
+    SkinnyArgs a = {};
+    a.table = gg->table;
+    a.count = gg->count;
+    a.total_items = gg->total_items;
+    a.total_cost = gg->total_cost;
+    return launch_skinny(a, gg->max_chunks, as_stream(stream));
+}
+
+sqap_status sqap_group_free(sqap_group *g)
+{
+    if (!g) return SQAP_OK;
+    Group *gg = reinterpret_cast<Group *>(g);
+    if (gg->magic != kGroupMagic) return fail(SQAP_EINVAL, "sqap_group_free: not a group handle");
+    gg->magic = 0;
+    hipError_t e = hipFree(gg->table);
+    delete gg;
+    if (e != hipSuccess) return fail(SQAP_EDEVICE, "sqap_group_free: %s", hipGetErrorString(e));
+    return SQAP_OK;
 }
 
 }  // extern "C"

@@ -34,6 +34,38 @@ struct Weight {
 };
 constexpr uint32_t kWeightMagic = 0x53514150u;  // "SQAP"
 
+// One problem of a small-M launch (see skinny.hip).  rg_begin is the index of the
+// problem's first work item (row group) in the launch-wide numbering.
+struct SkinnyEntry {
+    const uint8_t *Xq;
+    const __half *sx;
+    const uint8_t *Wd;
+    const __half *sw;
+    __half *Y;
+    int32_t *acc_out;   // nullable
+    int64_t ldy;
+    int M, N, chunks, rg_begin;
+    long long cost_begin;   // sum over earlier problems of row groups * chunks
+};
+constexpr int kSkinnyInline = 4;
+struct SkinnyArgs {
+    const SkinnyEntry *table;   // device table, or null to use inline_entries
+    int count, total_items, xs_bytes;
+    long long total_cost;
+    SkinnyEntry inline_entries[kSkinnyInline];
+};
+constexpr int kSkinnyMaxM = 8;
+
+// Device-resident table of small-M problems, run by one launch.
+struct Group {
+    uint32_t magic;
+    int count, total_items, max_chunks;
+    long long total_cost;
+    SkinnyEntry *table;   // device
+    int device;
+};
+constexpr uint32_t kGroupMagic = 0x53514752u;  // "SQGR"
+
 static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
 #define SQAP_HIP_CHECK(expr)                                                          \
@@ -60,5 +92,7 @@ size_t linear_workspace_bytes(int M, int N, int K);
 sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const Weight &w,
                                __half *Y, int64_t ldy, int32_t *acc_out, void *workspace,
                                hipStream_t st);
+
+sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 
 }  // namespace sqap

@@ -1,0 +1,287 @@
+// Small-M (decode) W4A4 linear: M <= 8 token rows against a weight matrix that
+// is streamed from HBM exactly once.  The work is memory bound, so the kernel
+// is organised around keeping many 1 KiB weight loads in flight per wavefront;
+// the arithmetic (same int8 MFMA and dequantisation as the prefill GEMM) rides
+// along.
+//
+// One launch serves a whole table of independent problems (a "group"): q/k/v
+// of a layer, gate/up, or every linear of a benchmark step.  A work item is one
+// row group (32 output channels) of one problem and belongs to ONE wavefront,
+// which walks the item's whole reduction axis with a ring of loads in flight:
+// no cross-wavefront reduction, no barrier per item.  Each block owns a
+// contiguous run of items holding an equal share of the launch's weight bytes,
+// so it keeps streaming across problem boundaries instead of paying a launch
+// per linear; the block re-stages the (tiny) activations in LDS only when its
+// run enters another problem.
+#include "common.h"
+
+namespace sqap {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kSkinnyWaves = 8;
+constexpr int kSkinnyThreads = kSkinnyWaves * 64;
+constexpr int kSkinnyDepth = 8;          // 1 KiB weight loads in flight per wavefront
+constexpr int kSkinnyZeroBytes = 16;
+
+__device__ __forceinline__ void widen4(const v4i p, v4i &lo, v4i &hi)
+{
+    const v4i mask = {(int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0};
+    lo = (p << 4) & mask;
+    hi = p & mask;
+}
+
+// same two-step rounding as the prefill epilogue (see gemm.hip)
+__device__ __forceinline__ __half dequant2(int acc, float sx, float sw)
+{
+    float y = ((float)acc * sx) * sw;
+    asm volatile("" : "+v"(y));
+    return __float2half_rn(y);
+}
+
+// The problem table is read with vector loads, so the compiler treats what it
+// reads as per-lane values.  Everything below IS wavefront-uniform; saying so
+// keeps the bookkeeping in scalar registers and the hot loop free of lane masks.
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ long long uni(long long v)
+{
+    const unsigned lo = __builtin_amdgcn_readfirstlane((int)(v & 0xffffffffll));
+    const unsigned hi = __builtin_amdgcn_readfirstlane((int)(v >> 32));
+    return (long long)(((unsigned long long)hi << 32) | lo);
+}
+template <class T>
+__device__ __forceinline__ T *uni(T *p)
+{
+    return reinterpret_cast<T *>(uni((long long)reinterpret_cast<uintptr_t>(p)));
+}
+
+// First item whose cumulative cost (in 16-byte weight pieces per row) reaches `target`.
+__device__ __forceinline__ int item_at_cost(const SkinnyEntry *table, int count, int total_items, long long target)
+{
+    int p = 0;
+    while (p + 1 < count && uni(table[p + 1].cost_begin) <= target) ++p;
+    const long long into = target - uni(table[p].cost_begin);
+    const int ch = uni(table[p].chunks);
+    long long it = uni(table[p].rg_begin) + (into + ch - 1) / ch;
+    return it < total_items ? (int)it : total_items;
+}
+
+// LDS: [0, 16): zeros; then the packed activations of the current problem,
+// 256 bytes per chunk pair cp: [k-half h][row r < 8][16 bytes]; then (S > 1)
+// 1 KiB per wavefront for the partial sums.
+//
+// S = number of wavefronts that share one item, each taking a slice of the
+// reduction axis.  S = 1 is the streaming configuration for large groups.  A
+// launch with few items (one linear, one layer) would otherwise run on a few
+// hundred wavefronts, each latency bound on its own ring; S > 1 spreads the same
+// bytes over up to 8 times as many wavefronts and adds their partial
+// accumulators through LDS.
+template <int S>
+__global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyArgs a)
+{
+    constexpr int R = kSkinnyWaves / S;          // items a block works on at a time
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int t = threadIdx.x, lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // uniform: keeps item bookkeeping scalar
+    uint8_t *xs = smem + kSkinnyZeroBytes;
+    if (t < 4) reinterpret_cast<int *>(smem)[t] = 0;
+
+    const SkinnyEntry *table = a.table ? a.table : a.inline_entries;
+    const int beg = item_at_cost(table, a.count, a.total_items, a.total_cost * blockIdx.x / gridDim.x);
+    const int end = blockIdx.x + 1 == gridDim.x
+                        ? a.total_items
+                        : item_at_cost(table, a.count, a.total_items, a.total_cost * (blockIdx.x + 1) / gridDim.x);
+    const int r = lane & 31, h = lane >> 5;
+    int prob = 0;
+    for (int cur = beg; cur < end;) {
+        while (prob + 1 < a.count && cur >= uni(table[prob + 1].rg_begin)) ++prob;
+        SkinnyEntry e = table[prob];
+        e.Xq = uni(e.Xq);
+        e.sx = uni(e.sx);
+        e.Wd = uni(e.Wd);
+        e.sw = uni(e.sw);
+        e.Y = uni(e.Y);
+        e.acc_out = uni(e.acc_out);
+        e.ldy = uni((long long)e.ldy);
+        e.M = uni(e.M);
+        e.N = uni(e.N);
+        e.chunks = uni(e.chunks);
+        e.rg_begin = uni(e.rg_begin);
+        const int next_begin = prob + 1 < a.count ? uni(table[prob + 1].rg_begin) : end;
+        const int seg_end = next_begin < end ? next_begin : end;
+        const int cps = e.chunks >> 1;
+
+        // this wavefront's first item and slice [c0, c0 + cn) of its chunk pairs: start the
+        // weight stream before staging the activations
+        const int sub = wave / S, ks = wave % S;
+        int item = cur + sub;
+        const int c0 = (int)((long long)cps * ks / S);
+        const int cn = (int)((long long)cps * (ks + 1) / S) - c0;
+        const int rounds = (cn + kSkinnyDepth - 1) / kSkinnyDepth;
+        const size_t item_stride = (size_t)R * e.chunks * 32;     // in v4i: R row groups on
+        const v4i *wsrc =
+            reinterpret_cast<const v4i *>(e.Wd + ((size_t)(item - e.rg_begin) * e.chunks + 2 * c0) * 512) + lane;
+        v4i wbuf[kSkinnyDepth];
+        if (item < seg_end) {
+#pragma unroll
+            for (int d = 0; d < kSkinnyDepth; ++d) wbuf[d] = wsrc[(size_t)(d < cn ? d : 0) * 64];
+        }
+
+        __syncthreads();                           // every wavefront is done with the previous problem's xs
+        const int Kh = e.chunks * 16;
+        for (int u = t; u < cps * 16; u += kSkinnyThreads) {
+            const int cp = u >> 4, hh = (u >> 3) & 1, rr = u & 7;
+            v4i v = {0, 0, 0, 0};
+            if (rr < e.M) v = reinterpret_cast<const v4i *>(e.Xq + (size_t)rr * Kh)[2 * cp + hh];
+            *reinterpret_cast<v4i *>(xs + cp * 256 + hh * 128 + rr * 16) = v;
+        }
+        __syncthreads();
+        // lanes whose token row does not exist read the zero block, with stride 0
+        const bool has_row = r < e.M;
+        const int xoff = has_row ? (kSkinnyZeroBytes + c0 * 256 + h * 128 + r * 16) : 0;
+        const int xstride = has_row ? 256 : 0;
+        const float sxf = has_row ? __half2float(e.sx[r]) : 0.f;
+        const bool y_vec = (e.N & 3) == 0 && (e.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(e.Y) & 7u) == 0;
+
+        for (int base = cur; base < seg_end; base += R, item += R) {
+            const int rg = item - e.rg_begin;
+            const bool active = item < seg_end;
+            const bool has_next = item + R < seg_end;
+            const v4i *wnext = has_next ? wsrc + item_stride : wsrc;
+            v16i acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0;
+            if (active) {
+            // The loop body is branch free: every step consumes ring slot d and refills it
+            // with exactly one load.  The reduction axis is padded to whole rounds; a
+            // padding step multiplies by the zero block and its refill re-reads piece 0.
+            for (int rd = 0; rd < rounds; ++rd) {
+#pragma unroll
+                for (int d = 0; d < kSkinnyDepth; ++d) {
+                    const int cp = rd * kSkinnyDepth + d;
+                    const bool valid = cp < cn;
+                    v4i wlo, whi, xlo, xhi;
+                    widen4(wbuf[d], wlo, whi);
+                    const int p2 = cp + kSkinnyDepth;
+                    const v4i *src = p2 < cn ? wsrc + (size_t)p2 * 64
+                                             : (rd + 1 == rounds ? wnext + (size_t)(d < cn ? d : 0) * 64 : wsrc);
+                    wbuf[d] = *src;
+                    widen4(*reinterpret_cast<const v4i *>(smem + (valid ? xoff + cp * xstride : 0)), xlo, xhi);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wlo, xlo, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(whi, xhi, acc, 0, 0, 0);
+                    // keep the steps apart: otherwise the compiler gathers all eight slots at
+                    // the top of a round and drains the ring before refilling it
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            }
+            wsrc = wnext;
+            // Accumulator layout: lane l holds token l%32 and, in register i, channel
+            // 8*(i/4) + 4*(l/32) + (i%4) of the row group: four consecutive channels per quad.
+            if (S > 1) {
+                // add the S slices: token lanes park their 16 registers in LDS (64 bytes per
+                // lane slot r + 8h), the slice-0 wavefront of each item collects them
+                int *red = reinterpret_cast<int *>(smem + kSkinnyZeroBytes + a.xs_bytes);
+                if (has_row && ks != 0) {
+                    int *dst = red + wave * 256 + (r + 8 * h) * 16;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        *reinterpret_cast<v4i *>(dst + 4 * q) =
+                            v4i{acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
+                }
+                __syncthreads();
+                if (has_row && ks == 0) {
+#pragma unroll
+                    for (int o = 1; o < S; ++o) {
+                        const int *src = red + (wave + o) * 256 + (r + 8 * h) * 16;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const v4i v = *reinterpret_cast<const v4i *>(src + 4 * q);
+                            acc[4 * q] += v.x;
+                            acc[4 * q + 1] += v.y;
+                            acc[4 * q + 2] += v.z;
+                            acc[4 * q + 3] += v.w;
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+            if (has_row && active && ks == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = rg * 32 + q * 8 + h * 4;
+                    if (n < e.N) {
+                        union { __half hv[4]; uint2 u; } pk;
+                        int v[4];
+#pragma unroll
+                        for (int x = 0; x < 4; ++x) {
+                            v[x] = acc[4 * q + x] >> 8;
+                            pk.hv[x] = dequant2(v[x], sxf, __half2float(e.sw[n + x]));   // scales are zero padded
+                        }
+                        __half *dst = e.Y + (size_t)r * e.ldy + n;
+                        if (y_vec) {
+                            *reinterpret_cast<uint2 *>(dst) = pk.u;
+                        } else {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x)
+                                if (n + x < e.N) dst[x] = pk.hv[x];
+                        }
+                        if (e.acc_out) {
+#pragma unroll
+                            for (int x = 0; x < 4; ++x)
+                                if (n + x < e.N) e.acc_out[(size_t)r * e.N + n + x] = v[x];
+                        }
+                    }
+                }
+            }
+        }
+        cur = seg_end;
+    }
+}
+
+size_t skinny_lds_bytes(int max_chunks)
+{
+    return kSkinnyZeroBytes + (size_t)(max_chunks / 2) * 256 + kSkinnyWaves * 1024;
+}
+
+template <int S>
+static sqap_status launch_skinny_s(SkinnyArgs &a, size_t lds, int grid_cap, hipStream_t st)
+{
+    static size_t configured = 0;
+    if (lds > configured) {
+        SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_kernel<S>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        configured = lds;
+    }
+    constexpr int R = kSkinnyWaves / S;
+    const int want = (a.total_items + R - 1) / R;
+    const int grid = want < grid_cap ? want : grid_cap;
+    hipLaunchKernelGGL(skinny_kernel<S>, dim3(grid), dim3(kSkinnyThreads), lds, st, a);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st)
+{
+    const size_t lds = skinny_lds_bytes(max_chunks);
+    if (lds > 160 * 1024) return fail(SQAP_EUNSUPPORTED, "small-M linear: K too large for the LDS staging");
+    static int grid_cap = 0;
+    if (grid_cap == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        grid_cap = 2 * cus;
+    }
+    SkinnyArgs a = args;
+    a.xs_bytes = (max_chunks / 2) * 256;
+    // aim at about 4096 wavefronts: share an item between S of them when items are few
+    const int waves = grid_cap * kSkinnyWaves;
+    if (a.total_items * 8 <= waves) return launch_skinny_s<8>(a, lds, grid_cap, st);
+    if (a.total_items * 4 <= waves) return launch_skinny_s<4>(a, lds, grid_cap, st);
+    if (a.total_items * 2 <= waves) return launch_skinny_s<2>(a, lds, grid_cap, st);
+    return launch_skinny_s<1>(a, lds, grid_cap, st);
+}
+
+}  // namespace sqap

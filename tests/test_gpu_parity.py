@@ -188,3 +188,54 @@ def test_attn_scores(G, oracle):
         torch.cuda.synchronize()
         ref = oracle.attn_scores(q, k, v0, nv)
         assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7)
+
+
+# ------------------------------------------------------------------ small-M (decode) path
+@pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (2, 544, 640), (3, 33, 64), (4, 11008, 4096),
+                                   (7, 4096, 11008), (8, 1000, 11008), (8, 32000, 4096), (1, 32, 128),
+                                   (8, 64, 64), (5, 96, 1088)])
+def test_small_m_linear(G, oracle, M, N, K):
+    rng = np.random.default_rng(M * 11 + N * 5 + K)
+    Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
+    sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+    sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+    Y, acc = G.gpu_linear(Xq, sx, Wq, sw)
+    Yo, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    assert np.array_equal(acc, acco)
+    assert G.assert_fp16_close(Y, Yo) == 0
+
+
+def test_group_of_small_m_linears(G, oracle):
+    """One launch over several independent problems of different shapes, two of them sharing an input."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(77)
+    shapes = [(8, 4096, 4096), (8, 4096, 4096), (1, 11008, 4096), (3, 4096, 11008), (8, 96, 64), (5, 1000, 640)]
+    keep, problems, refs = [], [], []
+    shared_x = None
+    for i, (M, N, K) in enumerate(shapes):
+        if i == 1:
+            Xq, sx = shared_x
+        else:
+            Xq = _random_packed(rng, M, K)
+            sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+        if i == 0:
+            shared_x = (Xq, sx)
+        Wq = _random_packed(rng, N, K)
+        sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+        xq_d, sx_d = G.to_dev(Xq), G.to_dev(sx)
+        W = B.sqap_weight_pack(G.to_dev(Wq), G.to_dev(sw))
+        Y = torch.full((M, N + 8), float("nan"), dtype=torch.float16, device="cuda")[:, :N]   # pitch > N
+        acc = torch.full((M, N), -1, dtype=torch.int32, device="cuda")
+        problems.append((xq_d, sx_d, W, Y, acc))
+        refs.append(oracle.w4a4_linear(Xq, sx, Wq, sw))
+    g = B.sqap_group_create(problems)
+    for _ in range(2):                       # a group is reusable
+        g.run()
+    torch.cuda.synchronize()
+    for (xq_d, sx_d, W, Y, acc), (Yo, acco) in zip(problems, refs):
+        assert np.array_equal(acc.cpu().numpy(), acco)
+        assert G.assert_fp16_close(Y.cpu().numpy(), Yo) == 0
+    g.free()
+    for pr in problems:
+        pr[2].free()
