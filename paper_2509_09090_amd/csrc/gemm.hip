@@ -10,8 +10,6 @@
 // product pairs codes of the same k.  The accumulator is then 256 * sum(x*w),
 // |.| <= 256 * 64 * K < 2^31 for K <= 131071, and the epilogue shifts it back:
 // the integer result is exact.
-#include <stdlib.h>
-
 #include <atomic>
 #include <random>
 
@@ -85,7 +83,7 @@ struct Cfg {
     static constexpr int STAGE = A_BYTES + B_BYTES;
     static constexpr int A_LOADS = (A_FRAGS + NW - 1) / NW, B_LOADS = (B_FRAGS + NW - 1) / NW;
     static_assert(B_FRAGS % NW == 0, "weight fragments divide over the wavefronts");
-    static_assert(A_FRAGS % NW == 0 || A_FRAGS < NW, "activation fragments divide over the wavefronts");
+    static constexpr bool A_EVEN = A_FRAGS % NW == 0;           // else the last slots of some wavefronts are idle
     // epilogue staging: 32 rows of each wavefront's tile in halves (+16 bytes of
     // padding per row) followed by BM token scales and BN channel scales as floats
     static constexpr int EP_PITCH = WN * 2 + 16;
@@ -126,13 +124,15 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
     const int Kh = p.K >> 1;
 
-    // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand
-    // (with fewer A fragments than wavefronts, the first A_FRAGS wavefronts move one each).
+    // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand (when the
+    // A fragments do not divide evenly, slots past the last fragment load it again and
+    // are not stored).
     const v4i *a_src[C::A_LOADS];
     int a_dst[C::A_LOADS], a_chunk[C::A_LOADS];
-    const bool a_mover = wave * C::A_LOADS < C::A_FRAGS;
+    bool a_live[C::A_LOADS];
 #pragma unroll
     for (int i = 0; i < C::A_LOADS; ++i) {
+        a_live[i] = wave * C::A_LOADS + i < C::A_FRAGS;
         const int f = min(wave * C::A_LOADS + i, C::A_FRAGS - 1), rg = f / CP, cp = f % CP;
         const int grow = min(m0 + rg * 32 + (lane & 31), p.M - 1);
         a_chunk[i] = 2 * cp + (lane >> 5);
@@ -170,10 +170,9 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     };
     auto store_lds = [&](int stage) {
         uint8_t *base = smem + stage * C::STAGE;
-        if (C::A_FRAGS % C::NW == 0 || a_mover) {
 #pragma unroll
-            for (int i = 0; i < C::A_LOADS; ++i) *reinterpret_cast<v4i *>(base + a_dst[i]) = ga[i];
-        }
+        for (int i = 0; i < C::A_LOADS; ++i)
+            if (C::A_EVEN || a_live[i]) *reinterpret_cast<v4i *>(base + a_dst[i]) = ga[i];
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + b_dst[i]) = gb[i];
     };
@@ -464,21 +463,23 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
                 if (total * jj / nb >= total * (jj + 1) / nb) continue;
                 __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
                     p.partials + (size_t)(jj * 8 + xcd) * SLOT_BYTES, 0, SLOT_BYTES, 0x00020000);
-                // half of the accumulator at a time: 16 loads in flight per thread
+                // half of the accumulator at a time: up to 16 loads in flight per thread
+                constexpr int TILES = C::TM * C::TN, HALF = (TILES + 1) / 2;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    constexpr int TILES = C::TM * C::TN, HALF = TILES / 2;
                     v4i tmp[HALF * 4];
 #pragma unroll
                     for (int a = 0; a < HALF; ++a)
 #pragma unroll
                         for (int qd = 0; qd < 4; ++qd) {
+                            if (h * HALF + a >= TILES) continue;
                             const auto v = __builtin_amdgcn_raw_buffer_load_b128(
                                 rsrc, my_off + (h * HALF + a) * 4096 + qd * 1024, 0, 16);
                             tmp[a * 4 + qd] = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
                         }
 #pragma unroll
                     for (int a = 0; a < HALF; ++a) {
+                        if (h * HALF + a >= TILES) continue;
                         const int ta = h * HALF + a, i = ta / C::TN, jn = ta % C::TN;
 #pragma unroll
                         for (int qd = 0; qd < 4; ++qd) {
@@ -524,13 +525,21 @@ static int persistent_blocks()
     return blocks;
 }
 
+// Tile shapes.  Large M: 256 x 256, eight wavefronts.  Below that the output is too
+// small to fill the machine with whole tiles (M = 148, N = 4096 is 19 x 128 MFMA tiles
+// for 1024 SIMDs), so narrow 128-column tiles of 96 or 160 rows are split along K by the
+// same stream-K kernel.
 using CfgBig = Cfg<256, 256, 2, 4>;
+using CfgMid = Cfg<160, 128, 1, 4>;
+using CfgLow = Cfg<96, 128, 1, 4>;
 
 size_t linear_workspace_bytes(int M, int, int K)
 {
-    if (M >= kStreamKMinM && K % kBK == 0)
-        return kFlagBytes + (size_t)kMaxPersistentBlocks * CfgBig::BM * CfgBig::BN * sizeof(int32_t);
-    return 0;
+    if (K % kBK != 0 || M <= kSkinnyMaxM) return 0;
+    const size_t slot = M >= kStreamKMinM ? (size_t)CfgBig::BM * CfgBig::BN
+                                          : (M > CfgLow::BM ? (size_t)CfgMid::BM * CfgMid::BN
+                                                            : (size_t)CfgLow::BM * CfgLow::BN);
+    return kFlagBytes + (size_t)kMaxPersistentBlocks * slot * sizeof(int32_t);
 }
 
 template <class C, class K>
@@ -606,10 +615,14 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
     p.n_groups = w.n_groups;
     p.chunks = w.chunks;
     p.y_vec_ok = (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (ldy & 7) == 0;
-    if (M <= 64) return launch_tiled<Cfg<64, 256, 1, 4>>(p, st);
-    if (M <= 128) return launch_tiled<Cfg<128, 256, 2, 4>>(p, st);
-    static const int v = getenv("SQAP_V") ? atoi(getenv("SQAP_V")) : 0;
-    if (M >= kStreamKMinM && w.K % kBK == 0 && v == 0) return launch_streamk<CfgBig>(p, workspace, st);
+    if (w.K % kBK == 0) {
+        if (M >= kStreamKMinM) return launch_streamk<CfgBig>(p, workspace, st);
+        if (M > CfgLow::BM) return launch_streamk<CfgMid>(p, workspace, st);
+        return launch_streamk<CfgLow>(p, workspace, st);
+    }
+    // K not a multiple of 128: one tile per workgroup, reduction axis guarded
+    if (M <= CfgLow::BM) return launch_tiled<CfgLow>(p, st);
+    if (M <= CfgMid::BM) return launch_tiled<CfgMid>(p, st);
     return launch_tiled<CfgBig>(p, st);
 }
 
