@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-layers", action="store_true")
-    ap.add_argument("--only", default="", help="prefill|decode: run just that loop --steps times (for profilers)")
+    ap.add_argument("--only", default="", help="prefill|decode|calib: run just that loop --steps times (for profilers)")
     return ap.parse_args()
 
 
@@ -313,6 +313,15 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.only == "calib":
+        # plain copy of known size: reference reading for the FETCH_SIZE / WRITE_SIZE counters
+        n = 1 << 30
+        src = torch.ones((n,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        return
     if args.only == "decode":
         stack = Stack(torch, B, wl, dev)
         print(json.dumps(decode_leg(torch, B, wl, stack, steps_per_m=args.steps)))

@@ -8,7 +8,7 @@
  * Conventions that hold for every call unless stated otherwise
  *   - Data pointers are DEVICE pointers owned by the caller.  The library
  *     never frees or keeps them.  The only library-owned objects are
- *     sqap_weight handles.
+ *     sqap_weight and sqap_group handles.
  *   - Half precision crosses the ABI as IEEE binary16 bit patterns (sqap_f16).
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls enqueue work on it and return; they never synchronise the host.
@@ -163,8 +163,10 @@ size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K);
  * handle with the same K, Y: [M, N] half with pitch ldy >= N elements.
  * acc_out: NULL, or [M, N] int32 (pitch N) that receives the accumulators.
  * workspace: at least sqap_workspace_bytes(M, N, K) bytes, 256-byte aligned
- * (may be NULL when that is 0).  Calls that share a workspace must be ordered
- * on one stream.  One entry point serves prefill (large M) and decode (M <= 8);
+ * (may be NULL when that is 0); its contents need no initialisation.  Calls
+ * that share a workspace must be ordered on one stream.  The large- and mid-M
+ * kernels are persistent: they assume the whole device (one workgroup per
+ * compute unit resident at once).  One entry point serves prefill (large M) and decode (M <= 8);
  * the kernel is chosen from M inside.
  * EINVAL: null pointer, M < 0, ldy < N, workspace too small.
  */
