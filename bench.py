@@ -5,7 +5,7 @@ One "step" is one pass of the whole path over one batch of synthetic input of
 the batched-prefill workload (16 observations x 276 tokens, each pruned to
 128 + 20 = 148 tokens, M = 2368):
 
-    prune_topk -> kept_rows -> quantize_act (gather fused) -> W4A4 gate/up
+    prune_rows (top-k + kept rows) -> quantize_act (gather fused) -> W4A4 gate/up
     linear (4096 -> 11008) -> quantize_act (K = 11008) -> W4A4 down linear
     (11008 -> 4096)
 
@@ -85,8 +85,7 @@ class Prefill:
 
     def step(self):
         B, ev = self.B, self.gemm_events
-        B.sqap_prune_topk(self.scores, self.keep, self.idx)
-        B.sqap_kept_rows(self.idx, self.S, 0, self.nv, self.rows)
+        B.sqap_prune_rows(self.scores, self.keep, self.S, 0, self.idx, self.rows)
         B.sqap_quantize_act(self.X, self.rows, self.Xq, self.sx)
         if ev is not None:
             ev[0].record()
@@ -357,7 +356,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "configs[3]: batched prefill, 16 obs x 276 tokens pruned to 148, M=2368; "
                                "gate/up 4096->11008 and down 11008->4096, int4 codes widened to int8 MFMA",
-                   "M": wk.M, "step": "prune_topk+kept_rows+quantize_act+linear+quantize_act+linear"},
+                   "M": wk.M, "step": "prune_rows(top-k+kept rows)+quantize_act+linear+quantize_act+linear"},
         "roofline": {"bound": "mfma", "kernel": "gemm_streamk_kernel<Cfg<256,256,2,4>>", "achieved": achieved,
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS,
                      "avg_launch_ms": gemm_ms, "per_gemm_ms": per_gemm,

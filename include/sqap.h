@@ -97,6 +97,16 @@ sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, in
                            int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream);
 
 /*
+ * sqap_prune_topk followed by sqap_kept_rows in one launch (Eq. 1 and the
+ * shortened sequence of Section 3.2): scores [batch, n_vis] -> idx_out
+ * [batch, keep_k] and rows_out [batch * (seq_len - n_vis + keep_k)], both exactly
+ * as the two separate calls write them.  Same errors as those calls.
+ */
+sqap_status sqap_prune_rows(const float *scores, int32_t batch, int32_t n_vis, int32_t keep_k,
+                            int32_t seq_len, int32_t vis_begin, int32_t *idx_out, int32_t *rows_out,
+                            void *stream);
+
+/*
  * Token gather (same passage): out[i, 0..K) = X[rows[i], 0..K), a bit copy of
  * half rows.  ldx / ldo are row pitches in elements (>= K).  K must be a
  * multiple of 8 and both base pointers and pitches 16-byte aligned
@@ -173,6 +183,17 @@ size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K);
 sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
                              const sqap_weight *W, sqap_f16 *Y, int64_t ldy, int32_t *acc_out,
                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Self-test of the quantizer's arithmetic.  The quantizer divides every element
+ * of a row by the same scale; it does so with a reciprocal and two fused
+ * corrections that give the correctly rounded binary32 quotient.  This call
+ * checks that claim on the device for every pair (v, s) of finite half values,
+ * s > 0, both signs of v, against the division operator, and ADDS the number of
+ * differing bit patterns to *mismatches_out (a device uint64 the caller has
+ * zeroed).  Expected result: 0.  EINVAL: null pointer.
+ */
+sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream);
 
 /*
  * Grouped small-M linears (autoregressive decode, M <= 8).  Decode streams

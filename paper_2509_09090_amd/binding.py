@@ -20,7 +20,8 @@ EXPORTS = (
     "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_prune_topk", "sqap_kept_rows",
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
-    "sqap_group_create", "sqap_group_run", "sqap_group_free",
+    "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient",
+    "sqap_prune_rows",
 )
 
 
@@ -56,6 +57,7 @@ def lib():
         L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_prune_topk.argtypes = [vp, i32, i32, i32, vp, vp]
         L.sqap_kept_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
+        L.sqap_prune_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.sqap_gather_rows.argtypes = [vp, i64, vp, i32, i32, vp, i64, vp]
         L.sqap_quantize_act.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
@@ -68,6 +70,7 @@ def lib():
         L.sqap_group_create.argtypes = [ctypes.POINTER(LinearDesc), i32, ctypes.POINTER(vp)]
         L.sqap_group_run.argtypes = [vp, vp]
         L.sqap_group_free.argtypes = [vp]
+        L.sqap_selftest_quotient.argtypes = [vp, vp]
         for name in EXPORTS:
             if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
@@ -112,6 +115,13 @@ def sqap_kept_rows(idx, seq_len, vis_begin, n_vis, rows_out, stream=None):
     batch, keep_k = idx.shape
     _check(lib().sqap_kept_rows(_ptr(idx), batch, keep_k, seq_len, vis_begin, n_vis, _ptr(rows_out),
                                 _stream(stream)))
+
+
+def sqap_prune_rows(scores, keep_k, seq_len, vis_begin, idx_out, rows_out, stream=None):
+    """Fused sqap_prune_topk + sqap_kept_rows."""
+    batch, n = scores.shape
+    _check(lib().sqap_prune_rows(_ptr(scores), batch, n, keep_k, seq_len, vis_begin, _ptr(idx_out),
+                                 _ptr(rows_out), _stream(stream)))
 
 
 def sqap_gather_rows(X, rows, out, stream=None):
@@ -162,6 +172,11 @@ def sqap_weight_pack(Wq, sw, stream=None):
     h = ctypes.c_void_p()
     _check(lib().sqap_weight_pack(_ptr(Wq), _ptr(sw), N, 2 * half, ctypes.byref(h), _stream(stream)))
     return Weight(h, N, 2 * half)
+
+
+def sqap_selftest_quotient(counter, stream=None):
+    """counter: zeroed int64 device tensor of one element; receives the number of mismatches."""
+    _check(lib().sqap_selftest_quotient(_ptr(counter), _stream(stream)))
 
 
 def sqap_workspace_bytes(M, N, K):

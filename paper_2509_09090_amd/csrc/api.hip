@@ -72,6 +72,27 @@ sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens
     return launch_prune_topk(scores, batch, n_tokens, keep_k, idx_out, as_stream(stream));
 }
 
+sqap_status sqap_prune_rows(const float *scores, int32_t batch, int32_t n_vis, int32_t keep_k,
+                            int32_t seq_len, int32_t vis_begin, int32_t *idx_out, int32_t *rows_out,
+                            void *stream)
+{
+    if (batch < 0 || n_vis < 0 || keep_k < 0 || seq_len < 0 || vis_begin < 0)
+        return fail(SQAP_EINVAL, "sqap_prune_rows: negative size");
+    if (keep_k > n_vis) return fail(SQAP_EINVAL, "sqap_prune_rows: keep_k %d > n_vis %d", keep_k, n_vis);
+    if ((int64_t)vis_begin + n_vis > seq_len)
+        return fail(SQAP_EINVAL, "sqap_prune_rows: visual span [%d, %d+%d) outside [0, %d)", vis_begin,
+                    vis_begin, n_vis, seq_len);
+    if ((int64_t)batch * seq_len > INT32_MAX)
+        return fail(SQAP_EINVAL, "sqap_prune_rows: batch * seq_len overflows int32");
+    if (n_vis > 65536) return fail(SQAP_EUNSUPPORTED, "sqap_prune_rows: n_vis %d > 65536", n_vis);
+    if (batch == 0 || (int64_t)seq_len - n_vis + keep_k == 0) return SQAP_OK;
+    if (!rows_out || (keep_k > 0 && (!scores || !idx_out))) return fail(SQAP_EINVAL, "sqap_prune_rows: null pointer");
+    if (keep_k == 0 || n_vis == 0)      // nothing to rank: only the non-visual rows survive
+        return launch_kept_rows(idx_out, batch, 0, seq_len, vis_begin, n_vis, rows_out, as_stream(stream));
+    return launch_prune_rows(scores, batch, n_vis, keep_k, seq_len, vis_begin, idx_out, rows_out,
+                             as_stream(stream));
+}
+
 sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, int32_t seq_len,
                            int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream)
 {
@@ -199,6 +220,12 @@ sqap_status sqap_weight_info(const sqap_weight *w, int32_t *N, int32_t *K, size_
     if (K) *K = ww->K;
     if (device_bytes) *device_bytes = ww->bytes;
     return SQAP_OK;
+}
+
+sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream)
+{
+    if (!mismatches_out) return fail(SQAP_EINVAL, "sqap_selftest_quotient: null pointer");
+    return launch_quotient_selftest(reinterpret_cast<unsigned long long *>(mismatches_out), as_stream(stream));
 }
 
 size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K)

@@ -80,6 +80,8 @@ sqap_status launch_attn_scores(const __half *q, const __half *k, int S, int H, i
                                int vis_begin, int n_vis, float *scores, hipStream_t st);
 sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
                               hipStream_t st);
+sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,
+                              int32_t *idx, int32_t *rows, hipStream_t st);
 sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
                              int vis_begin, int n_vis, int32_t *rows, hipStream_t st);
 sqap_status launch_gather_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
@@ -93,6 +95,7 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
                                __half *Y, int64_t ldy, int32_t *acc_out, void *workspace,
                                hipStream_t st);
 
+sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t st);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 
 }  // namespace sqap

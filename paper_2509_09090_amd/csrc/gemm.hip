@@ -49,6 +49,7 @@ struct GemmParams {
     unsigned long long epoch;    // value that marks a flag as set by THIS launch
     uint8_t *partials;     // one BM x BN int32 slot per workgroup
     int blocks_per_xcd;
+    int epi_steps;         // cost of one epilogue, in main-loop steps (work split)
 };
 
 __device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
@@ -89,6 +90,10 @@ struct Cfg {
     static constexpr int EP_PITCH = WN * 2 + 16;
     static constexpr int EP_BYTES = NW * 32 * EP_PITCH + (BM + BN) * 4;
     static constexpr int LDS_BYTES = 2 * STAGE > EP_BYTES ? 2 * STAGE : EP_BYTES;
+    // Steps charged per epilogue when the work is split.  0 = split the steps evenly:
+    // charging the measured cost (about 5 steps at 256 x 256) made the launch slower,
+    // the tail is not set by the epilogue count.
+    static constexpr int EPI_STEPS = 0;
 };
 
 // Main loop over steps [step_begin, step_end) of one tile (one step = 128
@@ -176,6 +181,10 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + b_dst[i]) = gb[i];
     };
+#ifndef SQAP_COMPUTE_VARIANT
+#define SQAP_COMPUTE_VARIANT 0
+#endif
+#if SQAP_COMPUTE_VARIANT == 0
     auto compute = [&](int stage) {
         const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
         const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
@@ -200,6 +209,70 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
                     acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
         }
     };
+#else
+    // Half-phase pipeline: all LDS reads of the step up front, then each group of
+    // TM*TN MFMAs is issued interleaved with the widening of the NEXT group's operands.
+    auto compute = [&](int stage) {
+        const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
+        const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
+        const v4i mask = {(int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0};
+        v4i ra[CP][TM], rb[CP][TN];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) ra[cp][i] = *reinterpret_cast<const v4i *>(sa + ((i * CP + cp) << 10));
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn) rb[cp][jn] = *reinterpret_cast<const v4i *>(sb + ((jn * CP + cp) << 10));
+        }
+        v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) alo[i] = (ra[0][i] << 4) & mask;
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) blo[jn] = (rb[0][jn] << 4) & mask;
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) ahi[i] = ra[cp][i] & mask;
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn) bhi[jn] = rb[cp][jn] & mask;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn)
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[jn], alo[i], acc[i][jn], 0, 0, 0);
+            if (cp + 1 < CP) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) alo[i] = (ra[cp + 1][i] << 4) & mask;
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn) blo[jn] = (rb[cp + 1][jn] << 4) & mask;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn)
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
+        }
+        // order template: reads, first widening, then MFMAs with the next widening in their shadow
+        constexpr int G = TM * TN, FR = TM + TN;
+        __builtin_amdgcn_sched_group_barrier(0x100, CP * FR, 0);             // all ds_read
+        __builtin_amdgcn_sched_group_barrier(0x002, FR * 8, 0);              // widen lo(0)
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {                                    // MFMA lo(cp) | widen hi(cp)
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, (FR * 4 + G - 1) / G, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {                                    // MFMA hi(cp) | widen lo(cp+1)
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (cp + 1 < CP) __builtin_amdgcn_sched_group_barrier(0x002, (FR * 8 + G - 1) / G, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#endif
 
     load_global(step_begin);
     store_lds(0);
@@ -378,11 +451,16 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
     const int q = tiles >> 3, r = tiles & 7;
     const int tile0 = xcd * q + (xcd < r ? xcd : r);
     const int ntile = q + (xcd < r ? 1 : 0);
-    // this workgroup's share of the XCD's steps: [begin, end)
-    const long long total = (long long)ntile * steps;
+    // This workgroup's share [begin, end) of the XCD's work, measured in steps, with every
+    // tile counted as steps + epi_steps: the tail of each tile stands for its epilogue, so a
+    // workgroup that finishes more tiles gets fewer main-loop steps.  Positions of tile tl:
+    // [tl*V, tl*V + steps) are its steps, the rest is the epilogue share of whoever holds
+    // the last step.
+    const int V = steps + p.epi_steps;
+    const long long total = (long long)ntile * V;
     const long long begin = total * j / nb, end = total * (j + 1) / nb;
     if (begin >= end) return;
-    const int t_first = (int)(begin / steps), t_last = (int)((end - 1) / steps);
+    const int t_first = (int)(begin / V), t_last = (int)((end - 1) / V);
     const int slot = blockIdx.x;
 
     // Visit order: downwards from t_last.  Only t_last can be left unfinished by
@@ -398,9 +476,9 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
     const int lane = t & 63, wave = t >> 6;
     const int my_off = wave * (C::TM * C::TN * 4096) + lane * 16;
     int tl = t_last;
-    if (end < (long long)(t_last + 1) * steps) {
+    if (end < (long long)t_last * V + steps) {
         // not the finisher of t_last: compute the head segment and publish it
-        const long long tb = (long long)tl * steps;
+        const long long tb = (long long)tl * V;
         const int s0 = (int)((begin > tb ? begin : tb) - tb);
         const int s1 = (int)(end - tb);
         const int tile = tile0 + tl;
@@ -429,8 +507,9 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
         --tl;
     }
     for (; tl >= t_first; --tl) {
-        const long long tb = (long long)tl * steps;
+        const long long tb = (long long)tl * V;
         const int s0 = (int)((begin > tb ? begin : tb) - tb);
+        if (s0 >= steps) continue;          // only the epilogue share of this tile falls in the range
         const int tile = tile0 + tl;
         const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
         const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
@@ -529,7 +608,10 @@ static int persistent_blocks()
 // small to fill the machine with whole tiles (M = 148, N = 4096 is 19 x 128 MFMA tiles
 // for 1024 SIMDs), so narrow 128-column tiles of 96 or 160 rows are split along K by the
 // same stream-K kernel.
-using CfgBig = Cfg<256, 256, 2, 4>;
+#ifndef SQAP_BIG_WN
+#define SQAP_BIG_WN 4
+#endif
+using CfgBig = Cfg<256, 256, 2, SQAP_BIG_WN>;
 using CfgMid = Cfg<160, 128, 1, 4>;
 using CfgLow = Cfg<96, 128, 1, 4>;
 
@@ -583,6 +665,7 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     p.n_tiles = (p.N + C::BN - 1) / C::BN;
     const int blocks = persistent_blocks();
     p.blocks_per_xcd = blocks / kXcds;
+    p.epi_steps = C::EPI_STEPS;
     p.flags = reinterpret_cast<unsigned long long *>(workspace);
     p.epoch = next_epoch();
     p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;

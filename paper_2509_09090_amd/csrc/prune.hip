@@ -40,10 +40,15 @@ constexpr int kTopkSmallMax = 2048;
 
 // n <= 2048: every element counts how many rank ahead of it (larger key, or the
 // same key at a lower index); it is kept iff that count is below keep_k.
+// With rows_out the same launch also writes the surviving sequence rows (see
+// kept_rows_kernel), saving a dependent launch.
 __global__ __launch_bounds__(256) void topk_rank_kernel(const float *__restrict__ scores, int n,
-                                                        int keep_k, int32_t *__restrict__ idx_out)
+                                                        int keep_k, int32_t *__restrict__ idx_out,
+                                                        int seq_len, int vis_begin,
+                                                        int32_t *__restrict__ rows_out)
 {
     __shared__ __attribute__((aligned(16))) uint32_t keys[kTopkSmallMax];
+    __shared__ uint8_t kept[kTopkSmallMax];
     __shared__ int wave_sums[4];
     const int t = threadIdx.x;
     const float *s = scores + (size_t)blockIdx.x * n;
@@ -66,11 +71,25 @@ __global__ __launch_bounds__(256) void topk_rank_kernel(const float *__restrict_
                 ahead += (kj.w > ki) || (kj.w == ki && j + 3 < i);
             }
             keep = ahead < keep_k;
+            kept[i] = keep;
         }
         int total;
         int pos = block_scan_flags(keep, wave_sums, &total);
         if (keep) out[base + pos] = i;
         base += total;
+    }
+    if (rows_out) {
+        int32_t *rows = rows_out + (size_t)blockIdx.x * (seq_len - n + keep_k);
+        __syncthreads();
+        base = 0;
+        for (int c = 0; c < seq_len; c += 256) {
+            const int sq = c + t, v = sq - vis_begin;
+            const bool keep = sq < seq_len && (v < 0 || v >= n || kept[v]);
+            int total;
+            int pos = block_scan_flags(keep, wave_sums, &total);
+            if (keep) rows[base + pos] = blockIdx.x * seq_len + sq;
+            base += total;
+        }
     }
 }
 
@@ -130,11 +149,30 @@ sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k,
                               hipStream_t st)
 {
     if (n <= kTopkSmallMax)
-        hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx);
+        hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx, 0, 0,
+                           (int32_t *)nullptr);
     else
         hipLaunchKernelGGL(topk_radix_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
+}
+
+sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
+                             int vis_begin, int n_vis, int32_t *rows, hipStream_t st);
+
+// top-k and the surviving rows; one launch when the scores fit the rank kernel
+sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,
+                              int32_t *idx, int32_t *rows, hipStream_t st)
+{
+    if (n <= kTopkSmallMax) {
+        hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx, seq_len,
+                           vis_begin, rows);
+        SQAP_HIP_CHECK(hipGetLastError());
+        return SQAP_OK;
+    }
+    sqap_status stt = launch_prune_topk(scores, batch, n, keep_k, idx, st);
+    if (stt != SQAP_OK) return stt;
+    return launch_kept_rows(idx, batch, keep_k, seq_len, vis_begin, n, rows, st);
 }
 
 // One block per observation: walks the sequence in order, keeps every token

@@ -5,13 +5,28 @@
 
 namespace sqap {
 
-constexpr int kQuantMaxGroups = 8;   // 8 groups of 8 elements per thread: K <= 16384
+constexpr int kQuantMaxGroups = 8;   // up to 8 groups of 8 elements per thread: K <= 16384
+
+// Correctly rounded binary32 quotient v / s for a divisor whose reciprocal r = RN(1/s)
+// was formed once per row (IEEE division).  q0 = RN(v r) is within one ulp of v/s, the
+// FMA gives the exact remainder, and the second FMA rounds q0 + rem * r to the
+// correctly rounded quotient (Markstein's correction; it can fail only for divisors whose
+// significand is all ones, which a half-precision scale widened to binary32 never is).
+// Three instructions instead of the ~15 of a full IEEE division per element; every
+// half / half pair is compared against the division operator by sqap_selftest_quotient.
+__device__ __forceinline__ float quotient(float v, float s, float r)
+{
+    const float q0 = v * r;
+    const float rem = fmaf(-q0, s, v);
+    return fmaf(rem, r, q0);
+}
 
 // One block per output row.  Each thread owns groups t, t+256, ... of 8
 // consecutive elements, held in registers from the single read of the row to
 // the packed store.  Arithmetic (all binary32, IEEE, no contraction possible):
 //   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
-template <bool ROTATE>
+// GPT = groups per thread the instance is compiled for (registers, hence occupancy).
+template <bool ROTATE, int GPT>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
                                                             const int32_t *__restrict__ rows, int K,
                                                             uint8_t *__restrict__ Xq,
@@ -25,9 +40,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     const uint4 *xrow = reinterpret_cast<const uint4 *>(X + src * ldx);
     const int groups = K >> 3;
 
-    float v[kQuantMaxGroups][8];
+    float v[GPT][8];
 #pragma unroll
-    for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+    for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
         if (g < groups) {
             uint4 raw = xrow[g];
@@ -47,7 +62,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     if (ROTATE) {
         // Butterfly stages at distance 1, 2, 4 stay inside a group of 8: registers.
 #pragma unroll
-        for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+        for (int gi = 0; gi < GPT; ++gi) {
 #pragma unroll
             for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
@@ -79,7 +94,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
         }
         const float c = (float)(1.0 / sqrt((double)K));
 #pragma unroll
-        for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+        for (int gi = 0; gi < GPT; ++gi) {
             const int g = t + gi * 256;
             if (g < groups) {
 #pragma unroll
@@ -90,7 +105,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
 
     float amax = 0.f;
 #pragma unroll
-    for (int gi = 0; gi < kQuantMaxGroups; ++gi)
+    for (int gi = 0; gi < GPT; ++gi)
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
     for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
@@ -103,15 +118,18 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     const float sf = __half2float(sh);
     if (t == 0) scale_out[row] = sh;
 
+    // Inputs that were not rotated are half values, for which the fast quotient is
+    // verified exhaustively; rotated rows take the division operator.
+    const float rcp = 1.0f / sf;
     uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
 #pragma unroll
-    for (int gi = 0; gi < kQuantMaxGroups; ++gi) {
+    for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
         if (g < groups) {
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float r = rintf(v[gi][e] / sf);
+                float r = rintf(ROTATE ? v[gi][e] / sf : quotient(v[gi][e], sf, rcp));
                 r = fminf(fmaxf(r, -8.f), 7.f);
                 packed |= ((uint32_t)(int)r & 15u) << (4 * e);
             }
@@ -120,23 +138,69 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     }
 }
 
+template <bool ROTATE, int GPT>
+static void launch_quantize_inst(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, size_t lds,
+                                 uint8_t *Xq, __half *sx, hipStream_t st)
+{
+    hipLaunchKernelGGL((quantize_rows_kernel<ROTATE, GPT>), dim3(M), dim3(256), lds, st, X, ldx, rows, K, Xq, sx);
+}
+
+template <bool ROTATE>
+static void launch_quantize_gpt(int gpt, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                size_t lds, uint8_t *Xq, __half *sx, hipStream_t st)
+{
+    if (gpt <= 1) launch_quantize_inst<ROTATE, 1>(X, ldx, rows, M, K, lds, Xq, sx, st);
+    else if (gpt <= 2) launch_quantize_inst<ROTATE, 2>(X, ldx, rows, M, K, lds, Xq, sx, st);
+    else if (gpt <= 4) launch_quantize_inst<ROTATE, 4>(X, ldx, rows, M, K, lds, Xq, sx, st);
+    else if (gpt <= 6) launch_quantize_inst<ROTATE, 6>(X, ldx, rows, M, K, lds, Xq, sx, st);
+    else launch_quantize_inst<ROTATE, 8>(X, ldx, rows, M, K, lds, Xq, sx, st);
+}
+
 sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                  bool rotate, uint8_t *Xq, __half *sx, hipStream_t st)
 {
+    const int gpt = (K / 8 + 255) / 256;
     if (rotate) {
         size_t lds = (size_t)K * sizeof(float);
-        static bool configured = false;
-        if (!configured) {
-            SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
-            configured = true;
+        if (lds > 48 * 1024) {
+            static bool configured = false;
+            if (!configured) {
+                SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true, 8>),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
+                configured = true;
+            }
         }
-        hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(M), dim3(256), lds, st, X, ldx, rows, K, Xq,
-                           sx);
+        launch_quantize_gpt<true>(gpt, X, ldx, rows, M, K, lds, Xq, sx, st);
     } else {
-        hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(M), dim3(256), 0, st, X, ldx, rows, K, Xq,
-                           sx);
+        launch_quantize_gpt<false>(gpt, X, ldx, rows, M, K, 0, Xq, sx, st);
     }
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// Self-test: for every pair (v, s) of finite half values with s > 0, compares the fast
+// quotient with the division operator, bit for bit.  Counts the differences.
+__global__ __launch_bounds__(256) void quotient_selftest_kernel(unsigned long long *mismatches)
+{
+    const unsigned s_bits = blockIdx.x + 1;                    // 1 .. 0x7bff
+    const float s = __half2float(__ushort_as_half((unsigned short)s_bits));
+    const float r = 1.0f / s;
+    unsigned bad = 0;
+    for (unsigned v_bits = threadIdx.x; v_bits < 0x7c00u; v_bits += 256) {
+        const float v = __half2float(__ushort_as_half((unsigned short)v_bits));
+        const float a = v / s, b = quotient(v, s, r);
+        const float an = (-v) / s, bn = quotient(-v, s, r);
+        // (a zero quotient may differ in sign: -0 / s is -0, the corrected form gives +0;
+        // both become code 0)
+        bad += (__float_as_uint(a) != __float_as_uint(b) && !(a == 0.f && b == 0.f)) +
+               (__float_as_uint(an) != __float_as_uint(bn) && !(an == 0.f && bn == 0.f));
+    }
+    if (bad) atomicAdd(mismatches, (unsigned long long)bad);
+}
+
+sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t st)
+{
+    hipLaunchKernelGGL(quotient_selftest_kernel, dim3(0x7bff), dim3(256), 0, st, mismatches);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }

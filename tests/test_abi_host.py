@@ -48,6 +48,9 @@ def test_prune_topk_validation():
 
 def test_kept_rows_validation():
     L = B.lib()
+    assert L.sqap_prune_rows(None, 1, 4, 5, 10, 0, None, None, None) == B.EINVAL    # keep_k > n_vis
+    assert L.sqap_prune_rows(None, 1, 4, 2, 10, 8, None, None, None) == B.EINVAL    # span outside
+    assert L.sqap_prune_rows(None, 0, 4, 2, 10, 0, None, None, None) == B.OK
     assert L.sqap_kept_rows(None, 1, 5, 10, 0, 4, None, None) == B.EINVAL    # keep_k > n_vis
     assert L.sqap_kept_rows(None, 1, 2, 10, 8, 4, None, None) == B.EINVAL    # span outside
     assert L.sqap_kept_rows(None, 0, 2, 10, 0, 4, None, None) == B.OK

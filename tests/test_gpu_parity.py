@@ -73,6 +73,22 @@ def test_kept_rows_and_gather(G, oracle, batch, S, v0, nv, k):
     assert np.array_equal(G.gpu_gather(X, rows).view(np.uint16), X[rows].view(np.uint16))
 
 
+@pytest.mark.parametrize("batch,S,v0,nv,k", [(16, 276, 0, 256, 128), (1, 276, 0, 256, 64), (3, 30, 4, 16, 5),
+                                             (2, 700, 100, 500, 123), (2, 20, 0, 20, 0), (2, 2500, 7, 2048, 1000),
+                                             (2, 5000, 100, 4096, 77), (2, 40, 5, 30, 30)])
+def test_prune_rows_fused(G, oracle, batch, S, v0, nv, k):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    s = wl.scores(batch, nv, wl.rng_for(96, S, wl.T_SCORES, k))
+    idx = torch.full((batch, k), -1, dtype=torch.int32, device="cuda")
+    rows = torch.full((batch * (S - nv + k),), -1, dtype=torch.int32, device="cuda")
+    B.sqap_prune_rows(G.to_dev(s), k, S, v0, idx, rows)
+    torch.cuda.synchronize()
+    idx_o = oracle.prune_topk(s, k)
+    assert np.array_equal(idx.cpu().numpy(), idx_o)
+    assert np.array_equal(rows.cpu().numpy(), oracle.kept_rows(idx_o, S, v0, nv))
+
+
 # ------------------------------------------------------------------ quantizer
 @pytest.mark.parametrize("M,K", [(64, 512), (148, 4096), (37, 11008), (5, 8), (3, 16), (9, 2056),
                                  (2, 16384), (1, 4096), (8, 11008)])
@@ -112,6 +128,16 @@ def test_quantize_special_rows(G, oracle):
     q, s = G.gpu_quantize(X)
     qo, so, _ = oracle.quantize_rows(X)
     assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
+
+
+def test_quantizer_quotient_is_the_ieee_quotient(G):
+    """Every (half, half) pair: the fast quotient of the quantizer equals the division operator."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    c = torch.zeros((1,), dtype=torch.int64, device="cuda")
+    B.sqap_selftest_quotient(c)
+    torch.cuda.synchronize()
+    assert int(c.item()) == 0
 
 
 def test_quantize_weight(G, oracle):
