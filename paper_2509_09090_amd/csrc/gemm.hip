@@ -49,7 +49,7 @@ struct GemmParams {
     unsigned long long epoch;    // value that marks a flag as set by THIS launch
     uint8_t *partials;     // one BM x BN int32 slot per workgroup
     int blocks_per_xcd;
-    int epi_steps;         // cost of one epilogue, in main-loop steps (work split)
+    int epi_steps;         // cost of one epilogue, in main-loop steps (work split); 0 = even split
 };
 
 __device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
@@ -59,15 +59,25 @@ __device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
     hi = p & mask;
 }
 
-// Y = half((float(acc) * sx) * sw): two binary32 products, then one rounding to
-// half.  The empty asm keeps the compiler from folding the second product and
-// the conversion into v_fma_mixlo_f16, which rounds the exact product once and
-// so differs from the two-step definition in about one result in 2^13.
-__device__ __forceinline__ __half dequant(int acc, float sx, float sw)
+// Y = half((float(acc >> 8) * sx) * sw): two binary32 products, then one rounding to
+// half.  The accumulator is 256 * v with |v| < 2^23, so float(acc) = 256 * float(v)
+// exactly, and with the token scale pre-multiplied by 2^-8 (exact: it is at least 2^-24)
+// the first product is the same real number, hence the same float, without the shift.
+// The empty asm keeps the compiler from folding the second product and the conversion
+// into v_fma_mixlo_f16, which rounds the exact product once and so differs from the
+// two-step definition in about one result in 2^13.  Two results are converted at a time
+// (v_cvt_pk_f16_f32, round to nearest even).
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t dequant2(int acc0, int acc1, float sx_over_256, float sw0, float sw1)
 {
-    float y = ((float)acc * sx) * sw;
-    asm volatile("" : "+v"(y));
-    return __float2half_rn(y);
+    float y0 = ((float)acc0 * sx_over_256) * sw0;
+    float y1 = ((float)acc1 * sx_over_256) * sw1;
+    asm volatile("" : "+v"(y0), "+v"(y1));
+    const v2f y = {y0, y1};
+    union { v2h h; uint32_t u; } r;
+    r.h = __builtin_convertvector(y, v2h);
+    return r.u;
 }
 
 // Static shape of one tile configuration: block tile BM x BN, WAVES_M x WAVES_N
@@ -89,11 +99,8 @@ struct Cfg {
     // padding per row) followed by BM token scales and BN channel scales as floats
     static constexpr int EP_PITCH = WN * 2 + 16;
     static constexpr int EP_BYTES = NW * 32 * EP_PITCH + (BM + BN) * 4;
-    static constexpr int LDS_BYTES = 2 * STAGE > EP_BYTES ? 2 * STAGE : EP_BYTES;
-    // Steps charged per epilogue when the work is split.  0 = split the steps evenly:
-    // charging the measured cost (about 5 steps at 256 x 256) made the launch slower,
-    // the tail is not set by the epilogue count.
-    static constexpr int EPI_STEPS = 0;
+    static constexpr int PIPE_BYTES = 2 * STAGE;                  // two stages
+    static constexpr int LDS_BYTES = PIPE_BYTES > EP_BYTES ? PIPE_BYTES : EP_BYTES;
 };
 
 // Main loop over steps [step_begin, step_end) of one tile (one step = 128
@@ -181,10 +188,6 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + b_dst[i]) = gb[i];
     };
-#ifndef SQAP_COMPUTE_VARIANT
-#define SQAP_COMPUTE_VARIANT 0
-#endif
-#if SQAP_COMPUTE_VARIANT == 0
     auto compute = [&](int stage) {
         const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
         const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
@@ -209,70 +212,6 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
                     acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
         }
     };
-#else
-    // Half-phase pipeline: all LDS reads of the step up front, then each group of
-    // TM*TN MFMAs is issued interleaved with the widening of the NEXT group's operands.
-    auto compute = [&](int stage) {
-        const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
-        const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
-        const v4i mask = {(int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0};
-        v4i ra[CP][TM], rb[CP][TN];
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int cp = 0; cp < CP; ++cp) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) ra[cp][i] = *reinterpret_cast<const v4i *>(sa + ((i * CP + cp) << 10));
-#pragma unroll
-            for (int jn = 0; jn < TN; ++jn) rb[cp][jn] = *reinterpret_cast<const v4i *>(sb + ((jn * CP + cp) << 10));
-        }
-        v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) alo[i] = (ra[0][i] << 4) & mask;
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn) blo[jn] = (rb[0][jn] << 4) & mask;
-#pragma unroll
-        for (int cp = 0; cp < CP; ++cp) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) ahi[i] = ra[cp][i] & mask;
-#pragma unroll
-            for (int jn = 0; jn < TN; ++jn) bhi[jn] = rb[cp][jn] & mask;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[jn], alo[i], acc[i][jn], 0, 0, 0);
-            if (cp + 1 < CP) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) alo[i] = (ra[cp + 1][i] << 4) & mask;
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn) blo[jn] = (rb[cp + 1][jn] << 4) & mask;
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jn = 0; jn < TN; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
-        }
-        // order template: reads, first widening, then MFMAs with the next widening in their shadow
-        constexpr int G = TM * TN, FR = TM + TN;
-        __builtin_amdgcn_sched_group_barrier(0x100, CP * FR, 0);             // all ds_read
-        __builtin_amdgcn_sched_group_barrier(0x002, FR * 8, 0);              // widen lo(0)
-#pragma unroll
-        for (int cp = 0; cp < CP; ++cp) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) {                                    // MFMA lo(cp) | widen hi(cp)
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, (FR * 4 + G - 1) / G, 0);
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g) {                                    // MFMA hi(cp) | widen lo(cp+1)
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (cp + 1 < CP) __builtin_amdgcn_sched_group_barrier(0x002, (FR * 8 + G - 1) / G, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
-#endif
 
     load_global(step_begin);
     store_lds(0);
@@ -345,9 +284,9 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
         }
     }
 
-    float *sxs = reinterpret_cast<float *>(smem + C::NW * 32 * PITCH);   // BM token scales
+    float *sxs = reinterpret_cast<float *>(smem + C::NW * 32 * PITCH);   // BM token scales, times 2^-8
     float *sws = sxs + C::BM;                                            // BN channel scales
-    for (int r = t; r < C::BM; r += C::THREADS) sxs[r] = __half2float(p.sx[min(m0 + r, p.M - 1)]);
+    for (int r = t; r < C::BM; r += C::THREADS) sxs[r] = __half2float(p.sx[min(m0 + r, p.M - 1)]) * 0.00390625f;
     for (int c = t; c < C::BN; c += C::THREADS) sws[c] = __half2float(p.sw[(ng0 << 5) + c]);   // zero padded past N
     __syncthreads();
     uint8_t *ep = smem + wave * (32 * PITCH);
@@ -362,12 +301,10 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
             for (int q = 0; q < 4; ++q) {
                 const int cin = jn * 32 + q * 8 + ch4;
                 const float4 s4 = *reinterpret_cast<const float4 *>(&sws[wn * WN + cin]);
-                union { __half h[4]; uint2 u; } pk;
-                pk.h[0] = dequant(acc[i][jn][4 * q + 0] >> 8, sxf, s4.x);
-                pk.h[1] = dequant(acc[i][jn][4 * q + 1] >> 8, sxf, s4.y);
-                pk.h[2] = dequant(acc[i][jn][4 * q + 2] >> 8, sxf, s4.z);
-                pk.h[3] = dequant(acc[i][jn][4 * q + 3] >> 8, sxf, s4.w);
-                *reinterpret_cast<uint2 *>(ep + tok * PITCH + cin * 2) = pk.u;
+                uint2 pk;
+                pk.x = dequant2(acc[i][jn][4 * q + 0], acc[i][jn][4 * q + 1], sxf, s4.x, s4.y);
+                pk.y = dequant2(acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3], sxf, s4.z, s4.w);
+                *reinterpret_cast<uint2 *>(ep + tok * PITCH + cin * 2) = pk;
             }
         // The staging area is private to the wavefront and LDS operations of one
         // wavefront complete in order, so no block barrier is needed around it.
@@ -608,10 +545,7 @@ static int persistent_blocks()
 // small to fill the machine with whole tiles (M = 148, N = 4096 is 19 x 128 MFMA tiles
 // for 1024 SIMDs), so narrow 128-column tiles of 96 or 160 rows are split along K by the
 // same stream-K kernel.
-#ifndef SQAP_BIG_WN
-#define SQAP_BIG_WN 4
-#endif
-using CfgBig = Cfg<256, 256, 2, SQAP_BIG_WN>;
+using CfgBig = Cfg<256, 256, 2, 4>;
 using CfgMid = Cfg<160, 128, 1, 4>;
 using CfgLow = Cfg<96, 128, 1, 4>;
 
@@ -665,7 +599,8 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     p.n_tiles = (p.N + C::BN - 1) / C::BN;
     const int blocks = persistent_blocks();
     p.blocks_per_xcd = blocks / kXcds;
-    p.epi_steps = C::EPI_STEPS;
+    p.epi_steps = 0;       // charging the measured cost (4 to 8 steps) did not shorten the launch: the tail is set by
+                           // the chain publish -> wait -> reduce -> epilogue, not by the epilogue count
     p.flags = reinterpret_cast<unsigned long long *>(workspace);
     p.epoch = next_epoch();
     p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;
