@@ -461,7 +461,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
             if (t == 0) {
                 for (int jj = first; jj < j; ++jj) {
                     if (total * jj / nb >= total * (jj + 1) / nb) continue;   // that workgroup had no steps
-                    const unsigned long long *f = &p.flags[jj * 8 + xcd];
+                    unsigned long long *f = &p.flags[jj * 8 + xcd];
                     long long spins = 0;
                     while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
                         __builtin_amdgcn_s_sleep(8);
@@ -470,6 +470,9 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
                             break;
                         }
                     }
+                    // A flag has exactly one consumer.  Taking it down again makes a replay of
+                    // a captured launch (same epoch argument) start from clear flags.
+                    __hip_atomic_store(f, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
             __syncthreads();
@@ -515,7 +518,10 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
 // Flags need no clearing between launches: a flag counts as set only when it
 // holds the launch's own epoch, a 64-bit value never used before in this
 // process (a per-process random upper half and a counter).  Whatever an earlier
-// launch or another owner of the memory left there differs from it.
+// launch or another owner of the memory left there differs from it.  A launch
+// replayed from a captured graph carries the epoch it was captured with; that
+// is safe because every flag a launch raises is taken down by its one consumer
+// before the launch ends.
 static unsigned long long next_epoch()
 {
     static std::atomic<unsigned long long> counter{0};

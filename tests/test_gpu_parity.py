@@ -216,6 +216,52 @@ def test_attn_scores(G, oracle):
         assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7)
 
 
+def test_linear_replayed_from_a_graph(G, oracle):
+    """A captured launch of the split (persistent) kernel carries the launch epoch it was captured with:
+    every replay, with new operands and eager launches on the same workspace in between, must still
+    give the exact result."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(4242)
+    M, N, K = 600, 768, 1024            # 3 x 3 tiles of 256 x 256 over 256 workgroups: every tile is shared
+    Wq = _random_packed(rng, N, K)
+    sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+    W = B.sqap_weight_pack(G.to_dev(Wq), G.to_dev(sw))
+    xq = torch.zeros((M, K // 2), dtype=torch.uint8, device="cuda")
+    sxd = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    Y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+    acc = torch.zeros((M, N), dtype=torch.int32, device="cuda")
+    ws = torch.empty((B.sqap_workspace_bytes(M, N, K),), dtype=torch.uint8, device="cuda")
+    ws.random_(0, 256)                  # the workspace needs no initialisation
+    side = torch.cuda.Stream()          # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.sqap_w4a4_linear(xq, sxd, W, Y, acc, ws)          # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.sqap_w4a4_linear(xq, sxd, W, Y, acc, ws)
+    for rep in range(4):
+        Xq = _random_packed(rng, M, K)
+        sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+        xq.copy_(G.to_dev(Xq))
+        sxd.copy_(G.to_dev(sx))
+        Y.fill_(float("nan"))
+        acc.fill_(-1)
+        graph.replay()
+        torch.cuda.synchronize()
+        Yo, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
+        assert np.array_equal(acc.cpu().numpy(), acco), rep
+        assert G.assert_fp16_close(Y.cpu().numpy(), Yo) == 0
+        # eager launch on the same workspace between replays
+        Y2 = torch.zeros_like(Y)
+        B.sqap_w4a4_linear(xq, sxd, W, Y2, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(Y2, Y)
+    W.free()
+
+
 # ------------------------------------------------------------------ small-M (decode) path
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (2, 544, 640), (3, 33, 64), (4, 11008, 4096),
                                    (7, 4096, 11008), (8, 1000, 11008), (8, 32000, 4096), (1, 32, 128),
