@@ -85,6 +85,46 @@ def prune_topk(scores, keep_k):
     return out[0] if one else out
 
 
+def project_token(Kmat, Rt, xyz, patch_w, patch_h):
+    """Eq. 2-3: world point -> token coordinates (t_u, t_v), or None if there is no valid projection."""
+    Km, R, p = _c(Kmat, np.float64).reshape(9), _c(Rt, np.float64).reshape(12), _c(xyz, np.float64).reshape(3)
+    tu, tv = ctypes.c_int32(0), ctypes.c_int32(0)
+    ok = lib().oracle_project_token(_p(Km), _p(R), _p(p), ctypes.c_double(patch_w), ctypes.c_double(patch_h),
+                                    ctypes.byref(tu), ctypes.byref(tv))
+    return (tu.value, tv.value) if ok else None
+
+
+def ring(grid_w, grid_h, cu, cv, radius):
+    """Eq. 4: membership flags of the Chebyshev ball around token (cu, cv), clipped to the grid."""
+    flags = np.zeros(grid_w * grid_h, dtype=np.uint8)
+    rc = lib().oracle_ring(int(grid_w), int(grid_h), int(cu), int(cv), int(radius), _p(flags))
+    if rc != 0:
+        raise ValueError("oracle_ring: status %d" % rc)
+    return flags
+
+
+def fps(grid_w, grid_h, kept, m):
+    """Eq. 5: m farthest-point picks (in pick order) given the 0/1 array of tokens already kept."""
+    k = np.array(kept, dtype=np.uint8).reshape(grid_w * grid_h).copy()
+    picks = np.empty(m, dtype=np.int32)
+    rc = lib().oracle_fps(int(grid_w), int(grid_h), _p(k), int(m), _p(picks))
+    if rc != 0:
+        raise ValueError("oracle_fps: status %d" % rc)
+    return picks
+
+
+def prune_select(scores, grid_w, grid_h, k_attn, keep_total, centre=None, radius=0):
+    """K_attn + K_ring + K_fps for one observation: ascending token indices."""
+    s = _c(scores, np.float32).reshape(grid_w * grid_h)
+    out = np.empty(grid_w * grid_h, dtype=np.int32)
+    cu, cv = centre if centre is not None else (0, 0)
+    n = lib().oracle_prune_select(_p(s), int(grid_w), int(grid_h), int(k_attn), int(keep_total),
+                                  int(centre is not None), int(cu), int(cv), int(radius), _p(out))
+    if n < 0:
+        raise ValueError("oracle_prune_select: status %d" % n)
+    return out[:n].copy()
+
+
 def kept_rows(idx, seq_len, vis_begin, n_vis):
     """Surviving sequence rows (global over the batch) in original order."""
     i2 = _c(idx, np.int32)

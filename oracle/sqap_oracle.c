@@ -20,8 +20,12 @@
  * exception is oracle_attn_scores: its arithmetic is pinned (generic softmax
  * attention row), but WHICH layer, query token and head aggregation define
  * the retention score is not fixed by the paper: "parity unpinned" for that
- * choice.
+ * choice.  Likewise for Eq. 5: farthest point sampling itself is pinned (a
+ * hand-worked sequence, the max-min property step by step, a running-minimum
+ * formulation), but the set it starts from, the metric and the tie-break are
+ * readings the paper does not fix: "parity unpinned" for those choices.
  */
+#include <limits.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -127,6 +131,137 @@ int oracle_prune_topk(const float *scores, int batch, int n_tokens, int keep_k,
     }
     free(order);
     return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Section 3.2, strategies 2 and 3: Eq. 2-5 and the final union         */
+/* ------------------------------------------------------------------ */
+/*
+ * Eq. 2 and Eq. 3: a world point is taken into the camera frame by [R|t],
+ * onto the image plane by K, and the pixel is mapped to its patch.
+ * cam = R p + t, h = K cam, (u, v) = (h0/h2, h1/h2), t_u = floor(u/P_w),
+ * t_v = floor(v/P_h).  Reading (the paper fixes no precision): binary64,
+ * every dot product summed left to right, no fused multiply-add.  Kmat is
+ * 3x3 and Rt is 3x4, both row-major.  Returns 1 and the token coordinates if
+ * the point is in front of the camera (h2 > 0) and u, v are finite and within
+ * +-2^30 patches; 0 otherwise (then there is no ring).
+ */
+int oracle_project_token(const double *Kmat, const double *Rt, const double *xyz,
+                         double patch_w, double patch_h, int32_t *tu, int32_t *tv)
+{
+    double cam[3], h[3];
+    for (int i = 0; i < 3; ++i)
+        cam[i] = ((Rt[4 * i] * xyz[0] + Rt[4 * i + 1] * xyz[1]) + Rt[4 * i + 2] * xyz[2]) + Rt[4 * i + 3];
+    for (int i = 0; i < 3; ++i)
+        h[i] = (Kmat[3 * i] * cam[0] + Kmat[3 * i + 1] * cam[1]) + Kmat[3 * i + 2] * cam[2];
+    if (!(h[2] > 0.0)) return 0;
+    double fu = floor((h[0] / h[2]) / patch_w), fv = floor((h[1] / h[2]) / patch_h);
+    if (!(fabs(fu) <= 1073741824.0) || !(fabs(fv) <= 1073741824.0)) return 0;
+    *tu = (int32_t)fu;
+    *tv = (int32_t)fv;
+    return 1;
+}
+
+/*
+ * Eq. 4: the protected set is every token of the grid whose Chebyshev distance
+ * from the centre token is at most R_t.  Reading: a filled square, clipped to
+ * the grid (the centre itself may lie outside the image).  Token (t_u, t_v)
+ * has index t_v * grid_w + t_u.  flags[i] = 1 for members.
+ */
+int oracle_ring(int grid_w, int grid_h, int cu, int cv, int radius, uint8_t *flags)
+{
+    if (grid_w <= 0 || grid_h <= 0 || radius < 0) return -1;
+    for (int v = 0; v < grid_h; ++v)
+        for (int u = 0; u < grid_w; ++u) {
+            long du = labs((long)u - cu), dv = labs((long)v - cv);
+            flags[v * grid_w + u] = (uint8_t)((du > dv ? du : dv) <= radius);
+        }
+    return 0;
+}
+
+/*
+ * Eq. 5: farthest point sampling of m tokens from the tokens not yet kept.
+ * Reading (the paper names FPS only): points are the token coordinates on the
+ * grid, distance is squared Euclidean in integers, a candidate's distance is
+ * its minimum over the tokens kept so far, the set it starts from being
+ * K_attn + K_ring (so that the FINAL set is spread out, as the text asks),
+ * and each step takes the candidate with the largest such distance, the lowest
+ * index among equals.  With nothing kept yet every distance is infinite and
+ * the first pick is token 0.  kept[] is updated; picks_out gets the m picks in
+ * the order they were made.  Written as the definition: every step recomputes
+ * every minimum from scratch.
+ */
+int oracle_fps(int grid_w, int grid_h, uint8_t *kept, int m, int32_t *picks_out)
+{
+    const int n = grid_w * grid_h;
+    if (grid_w <= 0 || grid_h <= 0 || m < 0) return -1;
+    for (int step = 0; step < m; ++step) {
+        long best_d = -1;
+        int best = -1;
+        for (int c = 0; c < n; ++c) {
+            if (kept[c]) continue;
+            long dmin = LONG_MAX;
+            for (int s = 0; s < n; ++s) {
+                if (!kept[s]) continue;
+                long du = (c % grid_w) - (s % grid_w), dv = (c / grid_w) - (s / grid_w);
+                long d = du * du + dv * dv;
+                if (d < dmin) dmin = d;
+            }
+            if (dmin > best_d) {          /* strict: the lowest index among equals stays */
+                best_d = dmin;
+                best = c;
+            }
+        }
+        if (best < 0) return -2;          /* fewer than m candidates */
+        kept[best] = 1;
+        picks_out[step] = best;
+    }
+    return 0;
+}
+
+/*
+ * Final set: K_attn + K_ring + K_fps.  K_attn = Top_k(scores, k_attn) over all
+ * tokens (Eq. 1), K_ring as above (absent when have_ring = 0), and the quota
+ * left, m = keep_total - |K_attn + K_ring|, is filled by FPS (none if the two
+ * sets already reach the total: the union is never cut).  idx_out receives the
+ * members in ascending order (capacity: grid_w * grid_h); returns their number,
+ * or a negative status.
+ */
+int oracle_prune_select(const float *scores, int grid_w, int grid_h, int k_attn, int keep_total,
+                        int have_ring, int cu, int cv, int radius, int32_t *idx_out)
+{
+    const int n = grid_w * grid_h;
+    if (grid_w <= 0 || grid_h <= 0 || k_attn < 0 || k_attn > n || keep_total < 0 || keep_total > n ||
+        radius < 0)
+        return -1;
+    uint8_t *kept = (uint8_t *)calloc((size_t)n, 1);
+    int32_t *tmp = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
+    if (!kept || !tmp) {
+        free(kept);
+        free(tmp);
+        return -4;
+    }
+    int rc = oracle_prune_topk(scores, 1, n, k_attn, tmp);
+    for (int i = 0; rc == 0 && i < k_attn; ++i) kept[tmp[i]] = 1;
+    if (rc == 0 && have_ring) {
+        uint8_t *ring = (uint8_t *)malloc((size_t)n);
+        if (!ring) rc = -4;
+        if (rc == 0) rc = oracle_ring(grid_w, grid_h, cu, cv, radius, ring);
+        for (int i = 0; rc == 0 && i < n; ++i) kept[i] |= ring[i];
+        free(ring);
+    }
+    int count = 0;
+    for (int i = 0; i < n; ++i) count += kept[i];
+    if (rc == 0 && keep_total > count) {
+        rc = oracle_fps(grid_w, grid_h, kept, keep_total - count, tmp);
+        count = keep_total;
+    }
+    int o = 0;
+    for (int i = 0; rc == 0 && i < n; ++i)
+        if (kept[i]) idx_out[o++] = i;
+    free(kept);
+    free(tmp);
+    return rc == 0 ? count : rc;
 }
 
 /*

@@ -138,6 +138,173 @@ def test_topk_rejects_keep_above_n(oracle):
         oracle.prune_topk(np.zeros(4, np.float32), 5)
 
 
+# ------------------------------------------------------------------ ring, FPS, final set (Eq. 2-5)
+def _fixture_rows(name):
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                yield [int(v) for v in line.split()]
+
+
+def test_ring_counts_match_the_hand_counted_fixture(oracle):
+    for cx, cy, R, count in _fixture_rows("chebyshev_ball_counts.txt"):
+        assert int(oracle.ring(16, 16, cx, cy, R).sum()) == count, (cx, cy, R)
+
+
+def test_ring_membership_is_the_chebyshev_ball(oracle):
+    """Every cell, against max(|du|, |dv|) written with numpy broadcasting; non-square grids and
+    centres outside the grid included (a transposed grid or an L1/L2 ball fails here)."""
+    for gw, gh, cu, cv, R in [(16, 16, 5, 9, 3), (7, 3, 6, 0, 2), (3, 7, 0, 6, 2), (16, 16, -2, 4, 3),
+                              (16, 16, 20, 20, 5), (4, 4, 1, 1, 0), (5, 9, 2, 4, 50)]:
+        u, v = np.meshgrid(np.arange(gw), np.arange(gh))              # row-major: index = v * gw + u
+        want = (np.maximum(np.abs(u - cu), np.abs(v - cv)) <= R).astype(np.uint8).reshape(-1)
+        assert np.array_equal(oracle.ring(gw, gh, cu, cv, R), want), (gw, gh, cu, cv, R)
+    # a diagonal neighbour is in the radius-1 ball (it is not in the L1 ball)
+    assert oracle.ring(16, 16, 8, 8, 1)[9 * 16 + 9] == 1
+
+
+def test_fps_hand_worked_sequence(oracle):
+    rows = list(_fixture_rows("fps_4x4_worked.txt"))
+    kept = np.zeros(16, np.uint8)
+    kept[0] = 1
+    picks = oracle.fps(4, 4, kept, len(rows))
+    assert [int(p) for p in picks] == [r[1] for r in rows]
+
+
+def _fps_numpy(gw, gh, kept, m):
+    """Independent statement of farthest point sampling: a running minimum-distance array
+    updated after every pick (the oracle recomputes all minima from scratch instead)."""
+    n = gw * gh
+    xy = np.stack([np.arange(n) % gw, np.arange(n) // gw], axis=1).astype(np.int64)
+    kept = kept.astype(bool).copy()
+    big = np.iinfo(np.int64).max
+    mind = np.full(n, big)
+    for s in np.flatnonzero(kept):
+        mind = np.minimum(mind, ((xy - xy[s]) ** 2).sum(axis=1))
+    picks = []
+    for _ in range(m):
+        cand = np.where(kept, -1, mind)
+        best = int(np.argmax(cand))                 # argmax returns the first (lowest) index among equals
+        picks.append(best)
+        kept[best] = True
+        mind = np.minimum(mind, ((xy - xy[best]) ** 2).sum(axis=1))
+    return picks
+
+
+def test_fps_vs_running_minimum_formulation(oracle):
+    rng = np.random.default_rng(5)
+    for gw, gh in [(4, 4), (8, 8), (5, 3), (3, 6), (16, 16), (1, 9)]:
+        n = gw * gh
+        for trial in range(4):
+            kept = (rng.random(n) < (0.0, 0.1, 0.3, 0.6)[trial]).astype(np.uint8)
+            free = int(n - kept.sum())
+            for m in sorted({0, 1, free // 2, free}):
+                got = [int(p) for p in oracle.fps(gw, gh, kept, m)]
+                assert got == _fps_numpy(gw, gh, kept, m), (gw, gh, trial, m)
+
+
+def test_fps_each_pick_maximises_the_distance_to_the_kept_set(oracle):
+    """The defining property, checked pick by pick with brute-force distances."""
+    rng = np.random.default_rng(6)
+    gw, gh = 6, 5
+    n = gw * gh
+    kept = np.zeros(n, bool)
+    kept[rng.choice(n, 4, replace=False)] = True
+    picks = oracle.fps(gw, gh, kept.astype(np.uint8), 10)
+    assert len(set(int(p) for p in picks)) == 10 and not kept[picks].any()
+    cur = kept.copy()
+    for p in picks:
+        dist = {c: min((c % gw - s % gw) ** 2 + (c // gw - s // gw) ** 2 for s in np.flatnonzero(cur))
+                for c in np.flatnonzero(~cur)}
+        top = max(dist.values())
+        assert dist[int(p)] == top and int(p) == min(c for c, d in dist.items() if d == top)
+        cur[p] = True
+
+
+def test_fps_from_an_empty_set_starts_at_token_zero_and_rejects_too_many(oracle):
+    assert [int(p) for p in oracle.fps(4, 4, np.zeros(16, np.uint8), 2)] == [0, 15]
+    with pytest.raises(ValueError):
+        oracle.fps(2, 2, np.array([1, 1, 1, 0], np.uint8), 2)
+
+
+def test_projection_closed_forms(oracle):
+    """Eq. 2-3 on cases whose answer is known without multiplying matrices by machine."""
+    Kmat = np.array([[100.0, 0, 112], [0, 100, 112], [0, 0, 1]])
+    ident = np.hstack([np.eye(3), np.zeros((3, 1))])
+    # pinhole, identity pose: u = fx x/z + cx, v = fy y/z + cy
+    assert oracle.project_token(Kmat, ident, [1, 2, 4], 14, 14) == ((25 + 112) // 14, (50 + 112) // 14)
+    # the optical axis lands on the principal point, patch (8, 8) of a 16 x 16 grid of 14-pixel patches
+    assert oracle.project_token(Kmat, ident, [0, 0, 3], 14, 14) == (8, 8)
+    # a quarter turn about the optical axis takes (x, y, z) to (-y, x, z)
+    rot = np.hstack([np.array([[0.0, -1, 0], [1, 0, 0], [0, 0, 1]]), np.zeros((3, 1))])
+    assert oracle.project_token(Kmat, rot, [1, 2, 4], 14, 14) == ((-50 + 112) // 14, (25 + 112) // 14)
+    # a translation adds to the camera-frame point before the division
+    tr = np.hstack([np.eye(3), np.array([[0.5], [0.0], [1.0]])])
+    assert oracle.project_token(Kmat, tr, [1, 2, 4], 14, 14) == (int(np.floor((100 * 1.5 / 5 + 112) / 14)),
+                                                                  int(np.floor((100 * 2 / 5 + 112) / 14)))
+    # unequal patch sizes, and floor (not truncation) left of / above the image
+    assert oracle.project_token(Kmat, ident, [1, 2, 4], 7, 28) == ((25 + 112) // 7, (50 + 112) // 28)
+    assert oracle.project_token(np.array([[100.0, 0, 0], [0, 100, 0], [0, 0, 1]]), ident, [-0.01, -3, 2], 14, 14) \
+        == (-1, -11)
+    # behind or on the camera plane: no token
+    assert oracle.project_token(Kmat, ident, [1, 2, -4], 14, 14) is None
+    assert oracle.project_token(Kmat, ident, [1, 2, 0], 14, 14) is None
+
+
+def test_projection_matches_homogeneous_matrix_product(oracle):
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        Kmat = np.array([[rng.uniform(50, 400), 0, rng.uniform(50, 200)], [0, rng.uniform(50, 400), rng.uniform(50, 200)],
+                         [0, 0, 1]])
+        q, _ = np.linalg.qr(rng.standard_normal((3, 3)))
+        Rt = np.hstack([q, rng.standard_normal((3, 1))])
+        p = rng.standard_normal(3) * 2
+        h = Kmat @ Rt @ np.append(p, 1.0)
+        got = oracle.project_token(Kmat, Rt, p, 14.0, 14.0)
+        if h[2] <= 0:
+            assert got is None
+            continue
+        u, v = h[0] / h[2] / 14.0, h[1] / h[2] / 14.0
+        if min(abs(u - round(u)), abs(v - round(v))) < 1e-9:       # too close to a patch border to call
+            continue
+        assert got == (int(np.floor(u)), int(np.floor(v)))
+
+
+def test_final_set_is_the_union_with_the_quota_filled_by_fps(oracle):
+    rng = np.random.default_rng(9)
+    for gw, gh, k_attn, total, centre, R in [(16, 16, 64, 128, (5, 9), 2), (16, 16, 0, 40, (0, 0), 1),
+                                             (16, 16, 100, 128, None, 0), (8, 8, 10, 30, (7, 7), 3),
+                                             (16, 16, 128, 128, (8, 8), 1), (6, 4, 5, 24, (2, 2), 1)]:
+        n = gw * gh
+        s = rng.random(n).astype(np.float32)
+        attn = _library_topk(s, k_attn)
+        kept = np.zeros(n, np.uint8)
+        kept[attn] = 1
+        if centre is not None:
+            u, v = np.meshgrid(np.arange(gw), np.arange(gh))
+            kept |= (np.maximum(np.abs(u - centre[0]), np.abs(v - centre[1])) <= R).astype(np.uint8).reshape(-1)
+        base = int(kept.sum())
+        m = max(0, total - base)
+        want = set(np.flatnonzero(kept)) | set(_fps_numpy(gw, gh, kept, m))
+        got = oracle.prune_select(s, gw, gh, k_attn, total, centre, R)
+        assert list(got) == sorted(want)
+        assert len(got) == max(total, base)            # the union is never cut; the quota only adds
+
+
+def test_final_set_special_cases(oracle):
+    s = np.linspace(1, 0, 256).astype(np.float32)
+    # no ring, no quota left: exactly Eq. 1
+    assert np.array_equal(oracle.prune_select(s, 16, 16, 128, 128), np.arange(128))
+    # ring overlapping the attention set is not counted twice
+    got = oracle.prune_select(s, 16, 16, 16, 16, (0, 0), 1)            # ring {0,1,16,17}; 0 and 1 already in the top row
+    assert list(got) == list(range(16)) + [16, 17]
+    # everything kept
+    assert np.array_equal(oracle.prune_select(s, 16, 16, 0, 256), np.arange(256))
+    with pytest.raises(ValueError):
+        oracle.prune_select(s, 16, 16, 257, 128)
+
+
 # ------------------------------------------------------------------ rows / gather
 def test_kept_rows_and_gather(oracle):
     rng = np.random.default_rng(4)
