@@ -97,6 +97,43 @@ sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, in
                            int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream);
 
 /*
+ * The full selection rule of Section 3.2: K_final = K_attn + K_ring + K_fps.
+ *
+ * The visual tokens form a grid_w x grid_h grid, token (t_u, t_v) has index
+ * t_v * grid_w + t_u (at most 1024 tokens).  For each of `batch` observations:
+ *   K_attn = the k_attn highest scores (Eq. 1, same ranking as sqap_prune_topk);
+ *   K_ring = tokens within Chebyshev distance ring_radius of the token that the
+ *            observation's world point projects to (Eq. 2-4): a filled square
+ *            clipped to the grid; empty if `camera` is null or the point is not
+ *            in front of the camera;
+ *   K_fps  = farthest point sampling (Eq. 5) of m = keep_total - |K_attn + K_ring|
+ *            further tokens (none if that is not positive: the union is never
+ *            cut), on token coordinates with squared Euclidean distance, the
+ *            distance of a candidate being its minimum over everything kept so
+ *            far, starting from K_attn + K_ring; largest distance first, lowest
+ *            index among equals.
+ *
+ * scores    device, [batch, grid_w * grid_h] binary32.
+ * camera    device or null, [batch, 26] binary64 per observation: the intrinsic
+ *           matrix K (3 x 3, row-major), the extrinsic [R|t] (3 x 4, row-major),
+ *           the world point (x, y, z), the patch width and height in pixels.
+ *           The projection is evaluated in binary64: cam = R p + t, h = K cam
+ *           (each dot product summed left to right), u = h0 / h2, v = h1 / h2,
+ *           t_u = floor(u / patch_w), t_v = floor(v / patch_h).
+ * idx_out   device, [batch, cap] int32: the members in ascending order, then -1.
+ * cap       row pitch of idx_out; must hold the largest possible set:
+ *           max(keep_total, min(tokens, k_attn + (2 ring_radius + 1)^2)).
+ * count_out device or null, [batch] int32: size of each final set (keep_total
+ *           whenever the union did not already exceed it).
+ * EINVAL: null pointer, negative size, k_attn or keep_total above the token
+ * count, cap too small.  EUNSUPPORTED: more than 1024 tokens.
+ */
+sqap_status sqap_prune_select(const float *scores, int32_t batch, int32_t grid_w, int32_t grid_h,
+                              int32_t k_attn, int32_t keep_total, const double *camera,
+                              int32_t ring_radius, int32_t *idx_out, int32_t cap, int32_t *count_out,
+                              void *stream);
+
+/*
  * sqap_prune_topk followed by sqap_kept_rows in one launch (Eq. 1 and the
  * shortened sequence of Section 3.2): scores [batch, n_vis] -> idx_out
  * [batch, keep_k] and rows_out [batch * (seq_len - n_vis + keep_k)], both exactly

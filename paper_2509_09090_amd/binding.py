@@ -21,7 +21,7 @@ EXPORTS = (
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient",
-    "sqap_prune_rows",
+    "sqap_prune_rows", "sqap_prune_select",
 )
 
 
@@ -122,6 +122,15 @@ def sqap_prune_rows(scores, keep_k, seq_len, vis_begin, idx_out, rows_out, strea
     batch, n = scores.shape
     _check(lib().sqap_prune_rows(_ptr(scores), batch, n, keep_k, seq_len, vis_begin, _ptr(idx_out),
                                  _ptr(rows_out), _stream(stream)))
+
+
+def sqap_prune_select(scores, grid_w, grid_h, k_attn, keep_total, camera, ring_radius, idx_out, count_out=None,
+                      stream=None):
+    """K_attn + K_ring + K_fps: scores [batch, grid_w*grid_h] fp32, camera [batch, 26] fp64 or None,
+    idx_out [batch, cap] int32 (ascending members, then -1), count_out [batch] int32 or None."""
+    batch = scores.shape[0]
+    _check(lib().sqap_prune_select(_ptr(scores), batch, grid_w, grid_h, k_attn, keep_total, _ptr(camera),
+                                   ring_radius, _ptr(idx_out), idx_out.shape[1], _ptr(count_out), _stream(stream)))
 
 
 def sqap_gather_rows(X, rows, out, stream=None):

@@ -93,6 +93,30 @@ sqap_status sqap_prune_rows(const float *scores, int32_t batch, int32_t n_vis, i
                              as_stream(stream));
 }
 
+sqap_status sqap_prune_select(const float *scores, int32_t batch, int32_t grid_w, int32_t grid_h,
+                              int32_t k_attn, int32_t keep_total, const double *camera, int32_t ring_radius,
+                              int32_t *idx_out, int32_t cap, int32_t *count_out, void *stream)
+{
+    if (batch < 0 || grid_w < 1 || grid_h < 1 || k_attn < 0 || keep_total < 0 || ring_radius < 0 || cap < 0)
+        return fail(SQAP_EINVAL, "sqap_prune_select: negative size");
+    const int64_t n = (int64_t)grid_w * grid_h;
+    if (n > 1024) return fail(SQAP_EUNSUPPORTED, "sqap_prune_select: %lld tokens > 1024", (long long)n);
+    if (k_attn > n || keep_total > n)
+        return fail(SQAP_EINVAL, "sqap_prune_select: k_attn %d or keep_total %d above %lld tokens", k_attn,
+                    keep_total, (long long)n);
+    // the union K_attn + K_ring is never cut, so the output must be able to hold it
+    const int64_t side = 2 * (int64_t)(ring_radius > 1024 ? 1024 : ring_radius) + 1;
+    int64_t most = camera ? (int64_t)k_attn + side * side : k_attn;
+    if (most > n) most = n;
+    if (most < keep_total) most = keep_total;
+    if (cap < most)
+        return fail(SQAP_EINVAL, "sqap_prune_select: cap %d below the largest possible set %lld", cap, (long long)most);
+    if (batch == 0) return SQAP_OK;
+    if (!scores || (cap > 0 && !idx_out)) return fail(SQAP_EINVAL, "sqap_prune_select: null pointer");
+    return launch_prune_select(scores, batch, grid_w, grid_h, k_attn, keep_total, camera, ring_radius, idx_out,
+                               cap, count_out, as_stream(stream));
+}
+
 sqap_status sqap_kept_rows(const int32_t *idx, int32_t batch, int32_t keep_k, int32_t seq_len,
                            int32_t vis_begin, int32_t n_vis, int32_t *rows_out, void *stream)
 {

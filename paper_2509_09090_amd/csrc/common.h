@@ -82,6 +82,9 @@ sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k,
                               hipStream_t st);
 sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,
                               int32_t *idx, int32_t *rows, hipStream_t st);
+sqap_status launch_prune_select(const float *scores, int batch, int gw, int gh, int k_attn, int keep_total,
+                                const double *camera, int radius, int32_t *idx, int cap, int32_t *count,
+                                hipStream_t st);
 sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_len,
                              int vis_begin, int n_vis, int32_t *rows, hipStream_t st);
 sqap_status launch_gather_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,

@@ -175,6 +175,156 @@ sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k,
     return launch_kept_rows(idx, batch, keep_k, seq_len, vis_begin, n, rows, st);
 }
 
+// ---------------------------------------------------------------------------
+// Full selection rule of Section 3.2: K_attn (Eq. 1) + K_ring (Eq. 2-4) + K_fps
+// (Eq. 5).  One wavefront per observation; lane l owns tokens l, l + 64, ...
+// (at most 1024 tokens, 16 per lane).  Everything after the projection is
+// integer work, so the result is exact.
+constexpr int kSelectMaxTokens = 1024;
+constexpr int kSelectPerLane = kSelectMaxTokens / 64;
+constexpr int kSelectCamera = 26;          // doubles per observation: K (9), [R|t] (12), point (3), patch w, h
+constexpr uint32_t kFarAway = 1u << 20;    // above any squared distance on a grid of <= 1024 tokens
+
+// Eq. 2-3 in binary64, dot products summed left to right, no contraction.
+__device__ __forceinline__ bool project_token(const double *c, int &tu, int &tv)
+{
+    const double *Km = c, *Rt = c + 9, *p = c + 21;
+    double cam[3], h[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+        cam[i] = ((Rt[4 * i] * p[0] + Rt[4 * i + 1] * p[1]) + Rt[4 * i + 2] * p[2]) + Rt[4 * i + 3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) h[i] = (Km[3 * i] * cam[0] + Km[3 * i + 1] * cam[1]) + Km[3 * i + 2] * cam[2];
+    if (!(h[2] > 0.0)) return false;
+    const double fu = floor((h[0] / h[2]) / c[24]), fv = floor((h[1] / h[2]) / c[25]);
+    if (!(fabs(fu) <= 1073741824.0) || !(fabs(fv) <= 1073741824.0)) return false;
+    tu = (int)fu;
+    tv = (int)fv;
+    return true;
+}
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+__global__ __launch_bounds__(64) void prune_select_kernel(const float *__restrict__ scores, int gw, int gh,
+                                                          int k_attn, int keep_total,
+                                                          const double *__restrict__ camera, int radius,
+                                                          int32_t *__restrict__ idx_out, int cap,
+                                                          int32_t *__restrict__ count_out)
+{
+    __shared__ __attribute__((aligned(16))) uint32_t keys[kSelectMaxTokens];
+    __shared__ uint8_t keptf[kSelectMaxTokens];
+    const int lane = threadIdx.x, b = blockIdx.x;
+    const int n = gw * gh, n4 = (n + 3) & ~3;
+    const float *s = scores + (size_t)b * n;
+    for (int i = lane; i < n4; i += 64) keys[i] = i < n ? score_key(s[i]) : 0u;
+
+    int cu = 0, cv = 0;
+    bool have_ring = false;
+    if (camera) have_ring = project_token(camera + (size_t)b * kSelectCamera, cu, cv);
+    __syncthreads();
+
+    // Eq. 1 by ranking, Eq. 4 by the distance itself
+    bool kept[kSelectPerLane];
+    int tu[kSelectPerLane], tv[kSelectPerLane];
+#pragma unroll
+    for (int r = 0; r < kSelectPerLane; ++r) {
+        const int i = lane + 64 * r;
+        kept[r] = false;
+        tu[r] = i % gw;
+        tv[r] = i / gw;
+        if (i < n) {
+            const uint32_t ki = keys[i];
+            int ahead = 0;
+            for (int j = 0; j < n4; j += 4) {
+                const uint4 kj = *reinterpret_cast<const uint4 *>(&keys[j]);
+                ahead += (kj.x > ki) || (kj.x == ki && j + 0 < i);
+                ahead += (kj.y > ki) || (kj.y == ki && j + 1 < i);
+                ahead += (kj.z > ki) || (kj.z == ki && j + 2 < i);
+                ahead += (kj.w > ki) || (kj.w == ki && j + 3 < i);
+            }
+            bool keep = ahead < k_attn;
+            if (have_ring) {
+                const int du = abs(tu[r] - cu), dv = abs(tv[r] - cv);
+                keep = keep || (du > dv ? du : dv) <= radius;
+            }
+            kept[r] = keep;
+            keptf[i] = keep;
+        }
+    }
+    int count = 0;
+#pragma unroll
+    for (int r = 0; r < kSelectPerLane; ++r) count += __popcll(__ballot(kept[r]));
+    __syncthreads();
+
+    // Eq. 5: distance of every candidate to the set kept so far, then one pick per step
+    const int m = keep_total > count ? keep_total - count : 0;
+    uint32_t mind[kSelectPerLane];
+#pragma unroll
+    for (int r = 0; r < kSelectPerLane; ++r) mind[r] = kFarAway;
+    if (m > 0) {
+        for (int j = 0; j < n; ++j) {
+            if (!keptf[j]) continue;                      // uniform: every lane reads the same flag
+            const int ju = j % gw, jv = j / gw;
+#pragma unroll
+            for (int r = 0; r < kSelectPerLane; ++r) {
+                const int du = tu[r] - ju, dv = tv[r] - jv;
+                const uint32_t d = (uint32_t)(du * du + dv * dv);
+                mind[r] = d < mind[r] ? d : mind[r];
+            }
+        }
+    }
+    for (int step = 0; step < m; ++step) {
+        // largest distance, lowest index among equals: the index enters the key inverted
+        uint32_t best = 0;
+#pragma unroll
+        for (int r = 0; r < kSelectPerLane; ++r) {
+            const int i = lane + 64 * r;
+            const uint32_t key = (i < n && !kept[r]) ? (mind[r] << 11) + (uint32_t)(2047 - i) : 0u;
+            best = key > best ? key : best;
+        }
+        best = wave_max_u32(best);
+        const int w = 2047 - (int)(best & 2047u);
+        const int wu = w % gw, wv = w / gw;
+#pragma unroll
+        for (int r = 0; r < kSelectPerLane; ++r) {
+            if (lane + 64 * r == w) kept[r] = true;
+            const int du = tu[r] - wu, dv = tv[r] - wv;
+            const uint32_t d = (uint32_t)(du * du + dv * dv);
+            mind[r] = d < mind[r] ? d : mind[r];
+        }
+    }
+
+    // ascending output: tokens 64r .. 64r+63 sit in lane order
+    int32_t *out = idx_out + (size_t)b * cap;
+    int base = 0;
+#pragma unroll
+    for (int r = 0; r < kSelectPerLane; ++r) {
+        const unsigned long long mk = __ballot(kept[r]);
+        if (kept[r]) out[base + __popcll(mk & ((1ull << lane) - 1ull))] = lane + 64 * r;
+        base += __popcll(mk);
+    }
+    for (int i = base + lane; i < cap; i += 64) out[i] = -1;
+    if (count_out && lane == 0) count_out[b] = base;
+}
+
+sqap_status launch_prune_select(const float *scores, int batch, int gw, int gh, int k_attn, int keep_total,
+                                const double *camera, int radius, int32_t *idx, int cap, int32_t *count,
+                                hipStream_t st)
+{
+    hipLaunchKernelGGL(prune_select_kernel, dim3(batch), dim3(64), 0, st, scores, gw, gh, k_attn, keep_total,
+                       camera, radius, idx, cap, count);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
 // One block per observation: walks the sequence in order, keeps every token
 // outside the visual span and the visual tokens listed (ascending) in idx.
 __global__ __launch_bounds__(256) void kept_rows_kernel(const int32_t *__restrict__ idx, int keep_k,

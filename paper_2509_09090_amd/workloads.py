@@ -28,7 +28,7 @@ N_TEXT = 20
 SEQ_LEN = N_VISUAL + N_TEXT
 
 # tensor ids used to key the generator
-T_SCORES, T_X, T_W, T_Q, T_KCACHE = 0, 1, 2, 3, 4
+T_SCORES, T_X, T_W, T_Q, T_KCACHE, T_CAMERA = 0, 1, 2, 3, 4, 5
 
 # name -> (N = out features, K = in features) of one decoder layer's linears
 LAYER_LINEARS = (
@@ -72,6 +72,31 @@ def weights(N, K, rng, std=0.02):
 def scores(batch, n_tokens, rng):
     """[batch, n_tokens] fp32 ~ U(0,1)."""
     return rng.random((batch, n_tokens), dtype=np.float32)
+
+
+def cameras(batch, grid_w, grid_h, patch, rng):
+    """[batch, 26] fp64 camera records for the robot-aware ring: intrinsics K (3x3), extrinsics [R|t]
+    (3x4), a world point, patch width and height.  A pinhole camera looking at a point whose image
+    falls on or near the grid_w x grid_h patch grid; about one record in eight has the point behind
+    the camera.  Only data: the projection itself is done by whoever consumes the record."""
+    out = np.empty((batch, 26), dtype=np.float64)
+    W, H = grid_w * patch, grid_h * patch
+    for b in range(batch):
+        f = rng.uniform(0.8, 1.6) * W
+        Kmat = np.array([[f, 0.0, W / 2 + rng.uniform(-4, 4)], [0.0, f * rng.uniform(0.95, 1.05), H / 2 + rng.uniform(-4, 4)],
+                         [0.0, 0.0, 1.0]])
+        q, _ = np.linalg.qr(rng.standard_normal((3, 3)))
+        if np.linalg.det(q) < 0:
+            q[:, 0] = -q[:, 0]
+        t = rng.standard_normal(3)
+        depth = rng.uniform(0.5, 2.0) * (-1.0 if rng.random() < 0.125 else 1.0)
+        cam = np.array([rng.uniform(-0.6, 0.6) * depth * W / f, rng.uniform(-0.6, 0.6) * depth * H / f, depth])
+        world = q.T @ (cam - t)                 # so that R world + t lands where intended (up to rounding)
+        out[b, 0:9] = Kmat.reshape(-1)
+        out[b, 9:21] = np.hstack([q, t.reshape(3, 1)]).reshape(-1)
+        out[b, 21:24] = world
+        out[b, 24:26] = patch
+    return out
 
 
 def query_and_keys(S, H, d, rng):

@@ -106,3 +106,17 @@ def test_attn_scores_validation():
     assert L.sqap_attn_scores(p, p, 10, 2, 8, 5, 6, p, None) == B.EINVAL
     assert L.sqap_attn_scores(p, p, 10, 2, 512, 0, 4, p, None) == B.EUNSUPPORTED
     assert L.sqap_attn_scores(p, p, 10, 2, 8, 0, 0, None, None) == B.OK
+
+
+def test_prune_select_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.sqap_prune_select(p, 1, 16, 16, 300, 128, None, 1, p, 256, None, None) == B.EINVAL      # k_attn > tokens
+    assert L.sqap_prune_select(p, 1, 16, 16, 64, 300, None, 1, p, 300, None, None) == B.EINVAL       # total > tokens
+    assert L.sqap_prune_select(p, 1, 16, 16, 64, 128, None, 1, p, 100, None, None) == B.EINVAL and "cap" in _err()
+    assert L.sqap_prune_select(p, 1, 16, 16, 64, 70, p, 2, p, 70, None, None) == B.EINVAL            # ring may not fit
+    assert L.sqap_prune_select(p, 1, 40, 40, 64, 128, None, 1, p, 1600, None, None) == B.EUNSUPPORTED
+    assert L.sqap_prune_select(p, 1, 0, 16, 0, 0, None, 1, p, 16, None, None) == B.EINVAL
+    assert L.sqap_prune_select(p, 1, 16, 16, 64, 128, None, -1, p, 256, None, None) == B.EINVAL
+    assert L.sqap_prune_select(None, 1, 16, 16, 64, 128, None, 1, p, 256, None, None) == B.EINVAL
+    assert L.sqap_prune_select(None, 0, 16, 16, 64, 128, None, 1, None, 256, None, None) == B.OK     # empty batch

@@ -150,6 +150,82 @@ def test_quantize_weight(G, oracle):
     assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
 
 
+# ------------------------------------------------------------------ full selection rule (Eq. 1-5)
+def _gpu_select(G, s, gw, gh, k_attn, total, cam, radius, cap=None):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    s2 = np.atleast_2d(s).astype(np.float32)
+    cap = gw * gh if cap is None else cap
+    idx = torch.full((s2.shape[0], cap), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((s2.shape[0],), -7, dtype=torch.int32, device="cuda")
+    B.sqap_prune_select(G.to_dev(s2), gw, gh, k_attn, total, None if cam is None else G.to_dev(cam), radius, idx, cnt)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cnt.cpu().numpy()
+
+
+def _oracle_select(oracle, s, gw, gh, k_attn, total, cam, radius):
+    out = []
+    for b, row in enumerate(np.atleast_2d(s)):
+        centre = None
+        if cam is not None:
+            centre = oracle.project_token(cam[b, 0:9], cam[b, 9:21], cam[b, 21:24], cam[b, 24], cam[b, 25])
+        out.append(oracle.prune_select(row, gw, gh, k_attn, total, centre, radius))
+    return out
+
+
+@pytest.mark.parametrize("gw,gh,batch,k_attn,total,radius,with_cam", [
+    (16, 16, 16, 64, 128, 2, True),       # the workload's grid: 256 visual tokens, half kept
+    (16, 16, 3, 100, 128, 0, False),      # no ring
+    (16, 16, 4, 0, 60, 1, True),          # no attention set
+    (16, 16, 4, 128, 128, 3, True),       # the union exceeds the total: it is not cut
+    (16, 16, 2, 10, 256, 1, True),        # keep everything
+    (32, 32, 3, 300, 700, 4, True),       # the largest grid, 16 tokens per lane
+    (5, 3, 6, 2, 9, 1, True),             # ragged small grid
+    (1, 9, 2, 1, 5, 0, False),            # one column
+    (16, 16, 2, 20, 40, 1000, True),      # a ring that covers the grid
+    (7, 11, 5, 0, 0, 0, False),           # nothing kept
+])
+def test_prune_select(G, oracle, gw, gh, batch, k_attn, total, radius, with_cam):
+    rng = wl.rng_for(96, gw * 100 + gh, wl.T_SCORES, extra=k_attn)
+    s = wl.scores(batch, gw * gh, rng)
+    s[0, : (gw * gh) // 2] = 0.5                       # a run of equal scores: ties by index
+    cam = wl.cameras(batch, gw, gh, 14.0, wl.rng_for(96, gw * 100 + gh, wl.T_CAMERA)) if with_cam else None
+    idx, cnt = _gpu_select(G, s, gw, gh, k_attn, total, cam, radius)
+    want = _oracle_select(oracle, s, gw, gh, k_attn, total, cam, radius)
+    for b in range(batch):
+        assert cnt[b] == len(want[b]), b
+        assert np.array_equal(idx[b, : cnt[b]], want[b]), b
+        assert np.all(idx[b, cnt[b]:] == -1)
+
+
+def test_prune_select_projection_edge_cases(G, oracle):
+    """Points on patch borders, outside the image, behind the camera: the token is decided in binary64
+    on both sides, so the sets agree exactly."""
+    gw = gh = 16
+    s = wl.scores(8, 256, wl.rng_for(97, 0, wl.T_SCORES))
+    cam = np.zeros((8, 26))
+    cam[:, 0:9] = np.array([[100.0, 0, 112], [0, 100, 112], [0, 0, 1]]).reshape(-1)
+    cam[:, 9:21] = np.hstack([np.eye(3), np.zeros((3, 1))]).reshape(-1)
+    cam[:, 24:26] = 14.0
+    pts = [(0, 0, 1), (0.14, 0.28, 1), (-1.12, -1.12, 1), (-1.1201, 0, 1), (5, 5, 1), (0, 0, -1), (0, 0, 0),
+           (1.0 / 3, 2.0 / 3, 7.0 / 9)]
+    cam[:, 21:24] = np.array(pts)
+    idx, cnt = _gpu_select(G, s, gw, gh, 32, 96, cam, 2)
+    want = _oracle_select(oracle, s, gw, gh, 32, 96, cam, 2)
+    for b in range(8):
+        assert cnt[b] == len(want[b]) and np.array_equal(idx[b, : cnt[b]], want[b]), b
+
+
+def test_prune_select_feeds_the_row_list(G, oracle):
+    """The selected tokens shorten the sequence exactly as the top-k tokens do."""
+    s = wl.scores(4, 256, wl.rng_for(98, 0, wl.T_SCORES))
+    cam = wl.cameras(4, 16, 16, 14.0, wl.rng_for(98, 0, wl.T_CAMERA))
+    idx, cnt = _gpu_select(G, s, 16, 16, 64, 128, cam, 1, cap=128)
+    assert np.all(cnt == 128)
+    rows = G.gpu_kept_rows(idx, 276, 0, 256)
+    assert np.array_equal(rows, oracle.kept_rows(np.stack(_oracle_select(oracle, s, 16, 16, 64, 128, cam, 1)), 276, 0, 256))
+
+
 # ------------------------------------------------------------------ linear
 def _random_packed(rng, R, K):
     return rng.integers(0, 256, size=(R, K // 2), dtype=np.uint8)
