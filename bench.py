@@ -262,6 +262,27 @@ def layer_leg(torch, B, wl, stack):
     return res
 
 
+def selection_leg(torch, B, wl, dev, iters=50):
+    """The full selection rule (top-k + projected ring + farthest point sampling) at configuration 3's
+    batch: 16 observations of a 16 x 16 token grid, 64 attention tokens, ring radius 2, 128 kept."""
+    batch, gw, gh, k_attn, total, radius = 16, 16, 16, 64, 128, 2
+    s = torch.from_numpy(wl.scores(batch, gw * gh, wl.rng_for(3, 0, wl.T_SCORES))).to(dev)
+    cam = torch.from_numpy(wl.cameras(batch, gw, gh, 14.0, wl.rng_for(3, 0, wl.T_CAMERA))).to(dev)
+    idx = torch.empty((batch, total + (2 * radius + 1) ** 2), dtype=torch.int32, device=dev)
+    cnt = torch.empty((batch,), dtype=torch.int32, device=dev)
+    for _ in range(5):
+        B.sqap_prune_select(s, gw, gh, k_attn, total, cam, radius, idx, cnt)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        B.sqap_prune_select(s, gw, gh, k_attn, total, cam, radius, idx, cnt)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"us_per_call": e0.elapsed_time(e1) * 1e3 / iters, "batch": batch, "grid": [gw, gh], "k_attn": k_attn,
+            "keep_total": total, "ring_radius": radius, "note": "back-to-back launches, includes launch overhead"}
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, on the same step (all 16 observations)."""
     import ctypes
@@ -373,6 +394,7 @@ def main():
         if not args.no_layers:
             out["layers"] = layer_leg(torch, B, wl, stack)
         del stack
+    out["selection"] = selection_leg(torch, B, wl, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

@@ -181,7 +181,6 @@ sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k,
 // (at most 1024 tokens, 16 per lane).  Everything after the projection is
 // integer work, so the result is exact.
 constexpr int kSelectMaxTokens = 1024;
-constexpr int kSelectPerLane = kSelectMaxTokens / 64;
 constexpr int kSelectCamera = 26;          // doubles per observation: K (9), [R|t] (12), point (3), patch w, h
 constexpr uint32_t kFarAway = 1u << 20;    // above any squared distance on a grid of <= 1024 tokens
 
@@ -203,81 +202,107 @@ __device__ __forceinline__ bool project_token(const double *c, int &tu, int &tv)
     return true;
 }
 
+// Maximum over the 64 lanes, returned in every lane.  Row-shift steps fold each row of 16
+// lanes into its lane 15, two row broadcasts fold the four rows into lane 63; lanes whose
+// source does not exist take 0, the identity here.
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const uint32_t o = (uint32_t)__shfl_xor((int)v, off, 64);
-        v = o > v ? o : v;
+#define SQAP_DPP_MAX(ctrl, row_mask, bank_mask)                                                      \
+    {                                                                                                \
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ctrl, row_mask, bank_mask, false); \
+        v = o > v ? o : v;                                                                           \
     }
-    return v;
+    SQAP_DPP_MAX(0x111, 0xf, 0xf)    // row_shr:1
+    SQAP_DPP_MAX(0x112, 0xf, 0xf)    // row_shr:2
+    SQAP_DPP_MAX(0x114, 0xf, 0xe)    // row_shr:4, lanes 4-15 of a row
+    SQAP_DPP_MAX(0x118, 0xf, 0xc)    // row_shr:8, lanes 8-15 of a row
+    SQAP_DPP_MAX(0x142, 0xa, 0xf)    // lane 15 of rows 0 and 2 into rows 1 and 3
+    SQAP_DPP_MAX(0x143, 0xc, 0xf)    // lane 31 into rows 2 and 3
+#undef SQAP_DPP_MAX
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+template <int PL>     // tokens per lane: at most 64 * PL tokens
 __global__ __launch_bounds__(64) void prune_select_kernel(const float *__restrict__ scores, int gw, int gh,
                                                           int k_attn, int keep_total,
                                                           const double *__restrict__ camera, int radius,
                                                           int32_t *__restrict__ idx_out, int cap,
                                                           int32_t *__restrict__ count_out)
 {
-    __shared__ __attribute__((aligned(16))) uint32_t keys[kSelectMaxTokens];
-    __shared__ uint8_t keptf[kSelectMaxTokens];
     const int lane = threadIdx.x, b = blockIdx.x;
-    const int n = gw * gh, n4 = (n + 3) & ~3;
+    const int n = gw * gh;
     const float *s = scores + (size_t)b * n;
-    for (int i = lane; i < n4; i += 64) keys[i] = i < n ? score_key(s[i]) : 0u;
+    const unsigned long long below = (1ull << lane) - 1ull;      // lanes with a lower number
 
     int cu = 0, cv = 0;
     bool have_ring = false;
     if (camera) have_ring = project_token(camera + (size_t)b * kSelectCamera, cu, cv);
-    __syncthreads();
 
-    // Eq. 1 by ranking, Eq. 4 by the distance itself
-    bool kept[kSelectPerLane];
-    int tu[kSelectPerLane], tv[kSelectPerLane];
+    // own tokens: lane + 64 r.  Tokens 64 r .. 64 r + 63 sit in lane order, so "lower index
+    // first" is "lower row first, then lower lane".
+    bool valid[PL], kept[PL];
+    uint32_t key[PL];
+    int tu[PL], tv[PL];
 #pragma unroll
-    for (int r = 0; r < kSelectPerLane; ++r) {
+    for (int r = 0; r < PL; ++r) {
         const int i = lane + 64 * r;
-        kept[r] = false;
-        tu[r] = i % gw;
-        tv[r] = i / gw;
-        if (i < n) {
-            const uint32_t ki = keys[i];
-            int ahead = 0;
-            for (int j = 0; j < n4; j += 4) {
-                const uint4 kj = *reinterpret_cast<const uint4 *>(&keys[j]);
-                ahead += (kj.x > ki) || (kj.x == ki && j + 0 < i);
-                ahead += (kj.y > ki) || (kj.y == ki && j + 1 < i);
-                ahead += (kj.z > ki) || (kj.z == ki && j + 2 < i);
-                ahead += (kj.w > ki) || (kj.w == ki && j + 3 < i);
-            }
-            bool keep = ahead < k_attn;
-            if (have_ring) {
-                const int du = abs(tu[r] - cu), dv = abs(tv[r] - cv);
-                keep = keep || (du > dv ? du : dv) <= radius;
-            }
-            kept[r] = keep;
-            keptf[i] = keep;
+        valid[r] = i < n;
+        key[r] = valid[r] ? score_key(s[i]) : 0u;
+        tu[r] = valid[r] ? i % gw : 0;
+        tv[r] = valid[r] ? i / gw : 0;
+    }
+
+    // Eq. 1: the k_attn-th largest key T, found bit by bit from the top (T is the largest value
+    // that at least k_attn keys reach), then keys above T and the first tokens equal to T.
+    uint32_t T = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int reach = 0;
+#pragma unroll
+        for (int r = 0; r < PL; ++r) reach += __popcll(__ballot(valid[r] && key[r] >= cand));
+        if (reach >= k_attn) T = cand;
+    }
+    int above = 0;
+#pragma unroll
+    for (int r = 0; r < PL; ++r) above += __popcll(__ballot(valid[r] && key[r] > T));
+    const int need_eq = k_attn - above;          // (k_attn = 0 ends with T = all ones: nothing above, nothing needed)
+    int eq_seen = 0;
+#pragma unroll
+    for (int r = 0; r < PL; ++r) {
+        const bool eq = valid[r] && key[r] == T;
+        const unsigned long long mk = __ballot(eq);
+        bool keep = valid[r] && (key[r] > T || (eq && eq_seen + __popcll(mk & below) < need_eq));
+        eq_seen += __popcll(mk);
+        // Eq. 4 by the distance itself
+        if (have_ring && valid[r]) {
+            const int du = abs(tu[r] - cu), dv = abs(tv[r] - cv);
+            keep = keep || (du > dv ? du : dv) <= radius;
         }
+        kept[r] = keep;
     }
     int count = 0;
 #pragma unroll
-    for (int r = 0; r < kSelectPerLane; ++r) count += __popcll(__ballot(kept[r]));
-    __syncthreads();
+    for (int r = 0; r < PL; ++r) count += __popcll(__ballot(kept[r]));
 
     // Eq. 5: distance of every candidate to the set kept so far, then one pick per step
     const int m = keep_total > count ? keep_total - count : 0;
-    uint32_t mind[kSelectPerLane];
+    uint32_t mind[PL];
 #pragma unroll
-    for (int r = 0; r < kSelectPerLane; ++r) mind[r] = kFarAway;
+    for (int r = 0; r < PL; ++r) mind[r] = kFarAway;
     if (m > 0) {
-        for (int j = 0; j < n; ++j) {
-            if (!keptf[j]) continue;                      // uniform: every lane reads the same flag
-            const int ju = j % gw, jv = j / gw;
 #pragma unroll
-            for (int r = 0; r < kSelectPerLane; ++r) {
-                const int du = tu[r] - ju, dv = tv[r] - jv;
-                const uint32_t d = (uint32_t)(du * du + dv * dv);
-                mind[r] = d < mind[r] ? d : mind[r];
+        for (int rr = 0; rr < PL; ++rr) {
+            unsigned long long mk = __ballot(kept[rr]);     // kept tokens 64 rr .. 64 rr + 63, one at a time
+            while (mk) {
+                const int src = __builtin_ctzll(mk);
+                mk &= mk - 1;
+                const int ju = __builtin_amdgcn_readlane(tu[rr], src), jv = __builtin_amdgcn_readlane(tv[rr], src);
+#pragma unroll
+                for (int r = 0; r < PL; ++r) {
+                    const int du = tu[r] - ju, dv = tv[r] - jv;
+                    const uint32_t d = (uint32_t)(du * du + dv * dv);
+                    mind[r] = d < mind[r] ? d : mind[r];
+                }
             }
         }
     }
@@ -285,16 +310,22 @@ __global__ __launch_bounds__(64) void prune_select_kernel(const float *__restric
         // largest distance, lowest index among equals: the index enters the key inverted
         uint32_t best = 0;
 #pragma unroll
-        for (int r = 0; r < kSelectPerLane; ++r) {
-            const int i = lane + 64 * r;
-            const uint32_t key = (i < n && !kept[r]) ? (mind[r] << 11) + (uint32_t)(2047 - i) : 0u;
-            best = key > best ? key : best;
+        for (int r = 0; r < PL; ++r) {
+            const uint32_t k2 = (valid[r] && !kept[r]) ? (mind[r] << 11) + (uint32_t)(2047 - (lane + 64 * r)) : 0u;
+            best = k2 > best ? k2 : best;
         }
         best = wave_max_u32(best);
         const int w = 2047 - (int)(best & 2047u);
-        const int wu = w % gw, wv = w / gw;
+        const int wl = w & 63, wr = w >> 6;
+        int wu = 0, wv = 0;
 #pragma unroll
-        for (int r = 0; r < kSelectPerLane; ++r) {
+        for (int r = 0; r < PL; ++r)
+            if (r == wr) {                                   // uniform
+                wu = __builtin_amdgcn_readlane(tu[r], wl);
+                wv = __builtin_amdgcn_readlane(tv[r], wl);
+            }
+#pragma unroll
+        for (int r = 0; r < PL; ++r) {
             if (lane + 64 * r == w) kept[r] = true;
             const int du = tu[r] - wu, dv = tv[r] - wv;
             const uint32_t d = (uint32_t)(du * du + dv * dv);
@@ -302,13 +333,13 @@ __global__ __launch_bounds__(64) void prune_select_kernel(const float *__restric
         }
     }
 
-    // ascending output: tokens 64r .. 64r+63 sit in lane order
+    // ascending output
     int32_t *out = idx_out + (size_t)b * cap;
     int base = 0;
 #pragma unroll
-    for (int r = 0; r < kSelectPerLane; ++r) {
+    for (int r = 0; r < PL; ++r) {
         const unsigned long long mk = __ballot(kept[r]);
-        if (kept[r]) out[base + __popcll(mk & ((1ull << lane) - 1ull))] = lane + 64 * r;
+        if (kept[r]) out[base + __popcll(mk & below)] = lane + 64 * r;
         base += __popcll(mk);
     }
     for (int i = base + lane; i < cap; i += 64) out[i] = -1;
@@ -319,8 +350,16 @@ sqap_status launch_prune_select(const float *scores, int batch, int gw, int gh, 
                                 const double *camera, int radius, int32_t *idx, int cap, int32_t *count,
                                 hipStream_t st)
 {
-    hipLaunchKernelGGL(prune_select_kernel, dim3(batch), dim3(64), 0, st, scores, gw, gh, k_attn, keep_total,
-                       camera, radius, idx, cap, count);
+    const int n = gw * gh;
+    if (n <= 256)
+        hipLaunchKernelGGL(prune_select_kernel<4>, dim3(batch), dim3(64), 0, st, scores, gw, gh, k_attn, keep_total,
+                           camera, radius, idx, cap, count);
+    else if (n <= 512)
+        hipLaunchKernelGGL(prune_select_kernel<8>, dim3(batch), dim3(64), 0, st, scores, gw, gh, k_attn, keep_total,
+                           camera, radius, idx, cap, count);
+    else
+        hipLaunchKernelGGL(prune_select_kernel<16>, dim3(batch), dim3(64), 0, st, scores, gw, gh, k_attn,
+                           keep_total, camera, radius, idx, cap, count);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
