@@ -173,6 +173,50 @@ def quantize_rows(X, rows=None, rotate=False):
     return q, s, rs
 
 
+def channel_scales(X, rows=None, rotate=False):
+    """Section 3.3, channel-wise activations: static scale per input channel from calibration rows, [K] f16."""
+    X = _c(X, np.float16)
+    K = X.shape[1]
+    r = None if rows is None else _c(rows, np.int32)
+    M = X.shape[0] if r is None else r.size
+    c = np.empty(K, dtype=np.float16)
+    rc = lib().oracle_channel_scales(_p(X), ctypes.c_int64(K), _p(r), M, K, 1 if rotate else 0, _p(c))
+    if rc != 0:
+        raise ValueError("oracle_channel_scales: status %d" % rc)
+    return c
+
+
+def quantize_rows_channelwise(X, col_scales, rows=None, rotate=False):
+    """Codes with one static scale per channel; returns (packed [M,K/2] u8, per-token scale [M] f16 = 1)."""
+    X = _c(X, np.float16)
+    K = X.shape[1]
+    c = _c(col_scales, np.float16)
+    assert c.shape == (K,)
+    r = None if rows is None else _c(rows, np.int32)
+    M = X.shape[0] if r is None else r.size
+    q = np.empty((M, K // 2), dtype=np.uint8)
+    s = np.empty(M, dtype=np.float16)
+    rc = lib().oracle_quantize_rows_channelwise(_p(X), ctypes.c_int64(K), _p(r), M, K, 1 if rotate else 0,
+                                                _p(c), _p(q), _p(s))
+    if rc != 0:
+        raise ValueError("oracle_quantize_rows_channelwise: status %d" % rc)
+    return q, s
+
+
+def quantize_rows_folded(W, col_scales, rotate=False):
+    """Weight rows times the activation channel scales, then per-row int4: (packed [N,K/2] u8, scale [N] f16)."""
+    W = _c(W, np.float16)
+    N, K = W.shape
+    c = _c(col_scales, np.float16)
+    assert c.shape == (K,)
+    q = np.empty((N, K // 2), dtype=np.uint8)
+    s = np.empty(N, dtype=np.float16)
+    rc = lib().oracle_quantize_rows_folded(_p(W), ctypes.c_int64(K), N, K, 1 if rotate else 0, _p(c), _p(q), _p(s))
+    if rc != 0:
+        raise ValueError("oracle_quantize_rows_folded: status %d" % rc)
+    return q, s
+
+
 def unpack_int4(Q):
     Q = _c(Q, np.uint8)
     R, half = Q.shape

@@ -389,6 +389,130 @@ int oracle_quantize_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, in
     return status;
 }
 
+/* ------------------------------------------------------------------ */
+/* Section 3.3: channel-wise quantization of activations               */
+/* ------------------------------------------------------------------ */
+/*
+ * The paper proposes one activation scale per input channel instead of one per
+ * token, so that a few large channels do not flatten all the others.  Reading
+ * (the paper gives no formula): the scales are static, taken from calibration
+ * rows,
+ *   c_k = binary16(max_rows |v_k| / 7), raised to 2^-24 if 0,
+ * with v the row in binary32, rotated first when rotate != 0.  A scale that
+ * varies along the reduction axis cannot leave an integer dot product, so it
+ * is folded into the weight before the weight is quantized:
+ *   x_k ~ c_k q_k,   y_n = sum_k x_k W_nk ~ sum_k q_k (c_k W_nk).
+ */
+int oracle_channel_scales(const uint16_t *X, int64_t ldx, const int32_t *rows, int M, int K,
+                          int rotate, uint16_t *scales_out)
+{
+    if (M < 0 || K <= 0) return -1;
+    if (rotate && (K & (K - 1)) != 0) return -2;
+    float *amax = (float *)calloc((size_t)K, sizeof(float));
+    float *v = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!amax || !v) {
+        free(amax);
+        free(v);
+        return -4;
+    }
+    for (int i = 0; i < M; ++i) {
+        size_t src = rows ? (size_t)rows[i] : (size_t)i;
+        for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
+        if (rotate) oracle_fwht_f32(v, K);
+        for (int k = 0; k < K; ++k)
+            if (fabsf(v[k]) > amax[k]) amax[k] = fabsf(v[k]);
+    }
+    for (int k = 0; k < K; ++k) {
+        uint16_t sh = oracle_f32_to_f16(amax[k] / 7.0f);
+        scales_out[k] = sh == 0 ? 1 : sh;
+    }
+    free(amax);
+    free(v);
+    return 0;
+}
+
+/*
+ * Activations with the static channel scales: q_k = clamp(rint(v_k / (float)c_k), -8, 7),
+ * packed as in oracle_quantize_rows.  The per-token scale that the linear's
+ * epilogue multiplies by is 1 for every token (binary16 0x3c00).
+ */
+int oracle_quantize_rows_channelwise(const uint16_t *X, int64_t ldx, const int32_t *rows, int M,
+                                     int K, int rotate, const uint16_t *col_scales, uint8_t *Xq,
+                                     uint16_t *scale_out)
+{
+    if (M < 0 || K <= 0 || (K & 1)) return -1;
+    if (rotate && (K & (K - 1)) != 0) return -2;
+    int status = 0;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i) {
+        float *v = (float *)malloc(sizeof(float) * (size_t)K);
+        if (!v) {
+            status = -4;
+            continue;
+        }
+        size_t src = rows ? (size_t)rows[i] : (size_t)i;
+        for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
+        if (rotate) oracle_fwht_f32(v, K);
+        for (int k = 0; k < K; k += 2) {
+            int q[2];
+            for (int t = 0; t < 2; ++t) {
+                float r = rintf(v[k + t] / oracle_f16_to_f32(col_scales[k + t]));
+                if (r > 7.0f) r = 7.0f;
+                if (r < -8.0f) r = -8.0f;
+                q[t] = (int)r;
+            }
+            Xq[(size_t)i * (K / 2) + k / 2] = (uint8_t)((q[0] & 15) | ((q[1] & 15) << 4));
+        }
+        scale_out[i] = 0x3c00;
+        free(v);
+    }
+    return status;
+}
+
+/*
+ * Weight with the channel scales folded in: row n of W (rotated first when
+ * rotate != 0) is multiplied elementwise by (float)c_k in binary32, then
+ * quantized per output channel exactly as oracle_quantize_rows does.
+ */
+int oracle_quantize_rows_folded(const uint16_t *W, int64_t ldw, int N, int K, int rotate,
+                                const uint16_t *col_scales, uint8_t *Wq, uint16_t *scale_out)
+{
+    if (N < 0 || K <= 0 || (K & 1)) return -1;
+    if (rotate && (K & (K - 1)) != 0) return -2;
+    int status = 0;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < N; ++i) {
+        float *v = (float *)malloc(sizeof(float) * (size_t)K);
+        if (!v) {
+            status = -4;
+            continue;
+        }
+        for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(W[(size_t)i * ldw + k]);
+        if (rotate) oracle_fwht_f32(v, K);
+        float amax = 0.0f;
+        for (int k = 0; k < K; ++k) {
+            v[k] = v[k] * oracle_f16_to_f32(col_scales[k]);
+            if (fabsf(v[k]) > amax) amax = fabsf(v[k]);
+        }
+        uint16_t sh = oracle_f32_to_f16(amax / 7.0f);
+        if (sh == 0) sh = 1;
+        float sf = oracle_f16_to_f32(sh);
+        for (int k = 0; k < K; k += 2) {
+            int q[2];
+            for (int t = 0; t < 2; ++t) {
+                float r = rintf(v[k + t] / sf);
+                if (r > 7.0f) r = 7.0f;
+                if (r < -8.0f) r = -8.0f;
+                q[t] = (int)r;
+            }
+            Wq[(size_t)i * (K / 2) + k / 2] = (uint8_t)((q[0] & 15) | ((q[1] & 15) << 4));
+        }
+        scale_out[i] = sh;
+        free(v);
+    }
+    return status;
+}
+
 /* signed value of nibble number k of a packed row */
 static inline int nibble(const uint8_t *row, int k)
 {

@@ -483,6 +483,94 @@ def test_rotation_reduces_quantisation_error_on_outlier_channels(oracle):
         oracle.quantize_rows(X[:, :1000], rotate=True)
 
 
+# ------------------------------------------------------------------ channel-wise activations (Section 3.3)
+def test_channel_scales_are_the_column_maxima(oracle):
+    """numpy's own half conversion and column reduction; a row-wise (per-token) maximum fails here."""
+    rng = np.random.default_rng(21)
+    X = (rng.standard_normal((37, 64)) * rng.uniform(0.01, 50, 64)).astype(np.float16)
+    X[:, 5] = 0                                            # an all-zero channel gets the smallest scale
+    want = (np.abs(X.astype(np.float32)).max(axis=0) / np.float32(7)).astype(np.float16)
+    want[5] = np.float16(2.0 ** -24)
+    assert np.array_equal(oracle.channel_scales(X).view(np.uint16), want.view(np.uint16))
+    rows = np.array([3, 3, 20, 7], np.int32)
+    want_r = (np.abs(X[rows].astype(np.float32)).max(axis=0) / np.float32(7)).astype(np.float16)
+    want_r[5] = np.float16(2.0 ** -24)
+    assert np.array_equal(oracle.channel_scales(X, rows=rows).view(np.uint16), want_r.view(np.uint16))
+
+
+def test_channelwise_codes_error_bound_and_unit_token_scale(oracle):
+    rng = np.random.default_rng(22)
+    X, _ = wl.activations(64, 256, 3, 30.0, rng)
+    c = oracle.channel_scales(X)
+    q, s = oracle.quantize_rows_channelwise(X, c)
+    assert np.all(s.view(np.uint16) == 0x3c00)             # the linear's epilogue multiplies by exactly 1
+    codes = oracle.unpack_int4(q).astype(np.float64)
+    assert codes.min() >= -7 and codes.max() <= 7          # calibration rows never reach the clamp
+    cf = c.astype(np.float64)
+    assert np.all(np.abs(codes * cf - X.astype(np.float64)) <= cf / 2 * (1 + 1e-3))
+    # every channel uses its range: the largest |code| of each column is 7 (6 only through the half rounding of c)
+    assert np.all(np.abs(codes).max(axis=0) >= 6)
+
+
+def test_channelwise_by_python_loops(oracle):
+    X = np.array([[1.0, -2.0, 0.5, 100.0], [0.25, 7.0, -0.5, -50.0]], np.float16)
+    c = np.array([0.5, 1.0, 0.125, 16.0], np.float16)
+    want = [[2, -2, 4, 6], [0, 7, -4, -3]]       # 1/.5, -2/1, .5/.125, 100/16=6.25->6 ; .25/.5=.5->0 (even), 7, -4, -3.125->-3
+    q, _ = oracle.quantize_rows_channelwise(X, c)
+    assert oracle.unpack_int4(q).tolist() == want
+    # out-of-calibration values are clamped, not wrapped
+    q2, _ = oracle.quantize_rows_channelwise(np.array([[9.0, -20.0, 3.0, 0.0]], np.float16), c)
+    assert oracle.unpack_int4(q2).tolist() == [[7, -8, 7, 0]]
+
+
+def test_folding_power_of_two_scales_changes_only_the_weight_scale(oracle):
+    """c_k = 2^-3 for every k: W * c is exact, the codes cannot change and the row scale is divided by 8."""
+    rng = np.random.default_rng(23)
+    W = wl.weights(24, 128, rng)
+    c = np.full(128, 0.125, np.float16)
+    q0, s0, _ = oracle.quantize_rows(W)
+    q1, s1 = oracle.quantize_rows_folded(W, c)
+    assert np.array_equal(q0, q1)
+    assert np.array_equal(s1.astype(np.float32) * 8, s0.astype(np.float32))
+    # a single large channel scale pulls that column's codes up and the others down
+    c2 = c.copy()
+    c2[7] = 8.0
+    q2, _ = oracle.quantize_rows_folded(W, c2)
+    codes0, codes2 = oracle.unpack_int4(q0).astype(int), oracle.unpack_int4(q2).astype(int)
+    assert np.abs(codes2[:, 7]).sum() > np.abs(codes0[:, 7]).sum()
+    assert np.abs(np.delete(codes2, 7, axis=1)).sum() < np.abs(np.delete(codes0, 7, axis=1)).sum()
+
+
+def test_channelwise_linear_reproduces_the_fp_linear_and_beats_per_token_on_outliers(oracle):
+    """y = x W^T with x ~ c q and c folded into W.  On activations with a few huge channels the per-token
+    quantizer zeroes the ordinary channels (the failure Section 3.3 describes); the channel-wise one does not.
+    A missing or doubled fold, or scales applied along the wrong axis, breaks the first assertion."""
+    rng = np.random.default_rng(24)
+    M, K, N = 48, 512, 40
+    X, ch = wl.activations(M, K, 5, 30.0, rng)
+    W = wl.weights(N, K, rng)
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    c = oracle.channel_scales(X)
+    xq, sx1 = oracle.quantize_rows_channelwise(X, c)
+    wq, sw = oracle.quantize_rows_folded(W, c)
+    y_cw, _ = oracle.w4a4_linear(xq, sx1, wq, sw)
+    xq_t, sx_t, _ = oracle.quantize_rows(X)
+    wq_t, sw_t, _ = oracle.quantize_rows(W)
+    y_tok, _ = oracle.w4a4_linear(xq_t, sx_t, wq_t, sw_t)
+    err = lambda y: np.linalg.norm(y.astype(np.float64) - ref) / np.linalg.norm(ref)
+    # the outlier channels carry most of the output energy and both quantizers resolve them; what is left is
+    # the ordinary channels, which only the channel-wise activations keep
+    keep = np.ones(K, bool)
+    keep[ch] = False
+    ref_ord = X[:, keep].astype(np.float64) @ W[:, keep].astype(np.float64).T
+    codes_cw = oracle.unpack_int4(xq).astype(np.float64) * c.astype(np.float64)
+    codes_tok = oracle.unpack_int4(xq_t).astype(np.float64) * sx_t.astype(np.float64)[:, None]
+    act_err = lambda xh: np.linalg.norm(xh[:, keep] - X[:, keep].astype(np.float64)) / np.linalg.norm(X[:, keep])
+    assert err(y_cw) < 0.35
+    assert act_err(codes_cw) < 0.2 < 0.9 < act_err(codes_tok)
+    assert np.linalg.norm(ref_ord) > 0
+
+
 # ------------------------------------------------------------------ GEMM + epilogue
 def test_int_gemm_vs_numpy_int64(oracle):
     rng = np.random.default_rng(12)
