@@ -180,6 +180,42 @@ sqap_status sqap_quantize_weight(const sqap_f16 *W, int32_t N, int32_t K, uint32
                                  uint8_t *Wq, sqap_f16 *sw, void *stream);
 
 /*
+ * Channel-wise activation quantization (Section 3.3: one activation scale per
+ * input channel instead of one per token, so that a few large channels do not
+ * flatten the others).  The scales are static: taken once from calibration
+ * rows and folded into the weight, since a scale that varies along the
+ * reduction axis cannot leave an integer dot product:
+ *   x_k ~ c_k q_k,   y_n = sum_k x_k W_nk ~ sw_n sum_k q_k qw_nk,
+ *   with qw, sw the per-output-channel quantization of W_nk * c_k.
+ *
+ * sqap_channel_scales: c_k = binary16(max over the M rows of |v_k| / 7), raised
+ * to 2^-24 when that rounds to 0; v as in sqap_quantize_act (rotated first with
+ * SQAP_ROTATE_HADAMARD).  amax: device, [K] binary32 running maxima, cleared by
+ * the call unless accumulate != 0 (several calibration batches); scales_out:
+ * device, [K] half, 16-byte aligned.
+ *
+ * sqap_quantize_act_channelwise: code = clamp(rint(v_k / c_k), -8, 7) (IEEE
+ * division, round-half-even); Xq as sqap_quantize_act; sx[i] = 1 for every row,
+ * so that sqap_w4a4_linear applies unchanged.
+ *
+ * sqap_quantize_weight_folded: the rows of W [N, K] (rotated first with the
+ * flag), multiplied elementwise by c_k in binary32, then quantized per output
+ * channel exactly as sqap_quantize_weight does.
+ *
+ * Errors as sqap_quantize_act; col_scales / scales_out must be 16-byte aligned.
+ */
+sqap_status sqap_channel_scales(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                                int32_t K, uint32_t flags, float *amax, int32_t accumulate,
+                                sqap_f16 *scales_out, void *stream);
+sqap_status sqap_quantize_act_channelwise(const sqap_f16 *X, int64_t ldx, const int32_t *rows,
+                                          int32_t M, int32_t K, uint32_t flags,
+                                          const sqap_f16 *col_scales, uint8_t *Xq, sqap_f16 *sx,
+                                          void *stream);
+sqap_status sqap_quantize_weight_folded(const sqap_f16 *W, int32_t N, int32_t K, uint32_t flags,
+                                        const sqap_f16 *col_scales, uint8_t *Wq, sqap_f16 *sw,
+                                        void *stream);
+
+/*
  * Re-lays canonical packed weights [N, K/2] and their scales [N] into the
  * library's streaming layout and returns a handle that owns a device copy
  * (allocated with hipMalloc on the current device).  The inputs may be freed

@@ -21,7 +21,8 @@ EXPORTS = (
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient",
-    "sqap_prune_rows", "sqap_prune_select",
+    "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
+    "sqap_quantize_weight_folded",
 )
 
 
@@ -59,6 +60,10 @@ def lib():
         L.sqap_kept_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_prune_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.sqap_gather_rows.argtypes = [vp, i64, vp, i32, i32, vp, i64, vp]
+        L.sqap_prune_select.argtypes = [vp, i32, i32, i32, i32, i32, vp, i32, vp, i32, vp, vp]
+        L.sqap_channel_scales.argtypes = [vp, i64, vp, i32, i32, u32, vp, i32, vp, vp]
+        L.sqap_quantize_act_channelwise.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp, vp]
+        L.sqap_quantize_weight_folded.argtypes = [vp, i32, i32, u32, vp, vp, vp, vp]
         L.sqap_quantize_act.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
         L.sqap_weight_pack.argtypes = [vp, vp, i32, i32, ctypes.POINTER(vp), vp]
@@ -174,6 +179,25 @@ class Weight:
         b = ctypes.c_size_t()
         _check(lib().sqap_weight_info(self.handle, None, None, ctypes.byref(b)))
         return b.value
+
+
+def sqap_channel_scales(X, rows, amax, scales_out, flags=0, accumulate=False, stream=None):
+    """Static per-channel activation scales from calibration rows: X [S,K] fp16 -> scales_out [K] fp16."""
+    M = X.shape[0] if rows is None else rows.numel()
+    _check(lib().sqap_channel_scales(_ptr(X), X.stride(0), _ptr(rows), M, X.shape[1], flags, _ptr(amax),
+                                     1 if accumulate else 0, _ptr(scales_out), _stream(stream)))
+
+
+def sqap_quantize_act_channelwise(X, rows, col_scales, Xq, sx, flags=0, stream=None):
+    M = X.shape[0] if rows is None else rows.numel()
+    _check(lib().sqap_quantize_act_channelwise(_ptr(X), X.stride(0), _ptr(rows), M, X.shape[1], flags,
+                                               _ptr(col_scales), _ptr(Xq), _ptr(sx), _stream(stream)))
+
+
+def sqap_quantize_weight_folded(W, col_scales, Wq, sw, flags=0, stream=None):
+    N, K = W.shape
+    _check(lib().sqap_quantize_weight_folded(_ptr(W), N, K, flags, _ptr(col_scales), _ptr(Wq), _ptr(sw),
+                                             _stream(stream)))
 
 
 def sqap_weight_pack(Wq, sw, stream=None):

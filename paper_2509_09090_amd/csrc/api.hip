@@ -182,6 +182,66 @@ sqap_status sqap_quantize_weight(const sqap_f16 *W, int32_t N, int32_t K, uint32
     return quantize_common("sqap_quantize_weight", W, K, nullptr, N, K, flags, Wq, sw, stream);
 }
 
+// shared checks of the entry points that take per-channel scales
+static sqap_status scaled_common(const char *who, const sqap_f16 *X, int64_t ldx, int32_t M, int32_t K,
+                                 uint32_t flags, const void *col_scales)
+{
+    if (M < 0 || K <= 0) return fail(SQAP_EINVAL, "%s: M %d, K %d", who, M, K);
+    if (K & 1) return fail(SQAP_EINVAL, "%s: K = %d is odd", who, K);
+    if (ldx < K) return fail(SQAP_EINVAL, "%s: pitch %lld below K %d", who, (long long)ldx, K);
+    if (flags & ~(uint32_t)SQAP_ROTATE_HADAMARD) return fail(SQAP_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    if ((flags & SQAP_ROTATE_HADAMARD) && ((K & (K - 1)) != 0 || K < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if ((K & 7) || K > 16384) return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
+    if (M > 0 && (!X || !col_scales)) return fail(SQAP_EINVAL, "%s: null pointer", who);
+    if (M > 0 && ((ldx & 7) || !aligned16(X) || !aligned16(col_scales)))
+        return fail(SQAP_EUNSUPPORTED, "%s: X, its pitch and the channel scales must be 16-byte aligned", who);
+    return SQAP_OK;
+}
+
+sqap_status sqap_channel_scales(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M, int32_t K,
+                                uint32_t flags, float *amax, int32_t accumulate, sqap_f16 *scales_out,
+                                void *stream)
+{
+    if (!amax || !scales_out) return fail(SQAP_EINVAL, "sqap_channel_scales: null pointer");
+    sqap_status st = scaled_common("sqap_channel_scales", X, ldx, M, K, flags, scales_out);
+    if (st != SQAP_OK) return st;
+    return launch_channel_scales(reinterpret_cast<const __half *>(X), ldx, rows, M, K,
+                                 (flags & SQAP_ROTATE_HADAMARD) != 0, amax, accumulate != 0,
+                                 reinterpret_cast<__half *>(scales_out), as_stream(stream));
+}
+
+sqap_status sqap_quantize_act_channelwise(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                                          int32_t K, uint32_t flags, const sqap_f16 *col_scales, uint8_t *Xq,
+                                          sqap_f16 *sx, void *stream)
+{
+    sqap_status st = scaled_common("sqap_quantize_act_channelwise", X, ldx, M, K, flags, col_scales);
+    if (st != SQAP_OK) return st;
+    if (M == 0) return SQAP_OK;
+    if (!Xq || !sx) return fail(SQAP_EINVAL, "sqap_quantize_act_channelwise: null pointer");
+    if (reinterpret_cast<uintptr_t>(Xq) & 3u)
+        return fail(SQAP_EUNSUPPORTED, "sqap_quantize_act_channelwise: Xq must be 4-byte aligned");
+    return launch_quantize_rows_scaled(reinterpret_cast<const __half *>(X), ldx, rows, M, K,
+                                       (flags & SQAP_ROTATE_HADAMARD) != 0, false,
+                                       reinterpret_cast<const __half *>(col_scales), Xq,
+                                       reinterpret_cast<__half *>(sx), as_stream(stream));
+}
+
+sqap_status sqap_quantize_weight_folded(const sqap_f16 *W, int32_t N, int32_t K, uint32_t flags,
+                                        const sqap_f16 *col_scales, uint8_t *Wq, sqap_f16 *sw, void *stream)
+{
+    sqap_status st = scaled_common("sqap_quantize_weight_folded", W, K, N, K, flags, col_scales);
+    if (st != SQAP_OK) return st;
+    if (N == 0) return SQAP_OK;
+    if (!Wq || !sw) return fail(SQAP_EINVAL, "sqap_quantize_weight_folded: null pointer");
+    if (reinterpret_cast<uintptr_t>(Wq) & 3u)
+        return fail(SQAP_EUNSUPPORTED, "sqap_quantize_weight_folded: Wq must be 4-byte aligned");
+    return launch_quantize_rows_scaled(reinterpret_cast<const __half *>(W), K, nullptr, N, K,
+                                       (flags & SQAP_ROTATE_HADAMARD) != 0, true,
+                                       reinterpret_cast<const __half *>(col_scales), Wq,
+                                       reinterpret_cast<__half *>(sw), as_stream(stream));
+}
+
 sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, int32_t K,
                              sqap_weight **out, void *stream)
 {

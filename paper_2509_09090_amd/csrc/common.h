@@ -91,6 +91,11 @@ sqap_status launch_gather_rows(const __half *X, int64_t ldx, const int32_t *rows
                                __half *out, int64_t ldo, hipStream_t st);
 sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                  bool rotate, uint8_t *Xq, __half *sx, hipStream_t st);
+sqap_status launch_quantize_rows_scaled(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                        bool rotate, bool folded, const __half *col_scales, uint8_t *Xq,
+                                        __half *sx, hipStream_t st);
+sqap_status launch_channel_scales(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, bool rotate,
+                                  float *amax, bool accumulate, __half *scales, hipStream_t st);
 sqap_status launch_weight_pack(const uint8_t *Wq, const __half *sw, const Weight &w,
                                hipStream_t st);
 size_t linear_workspace_bytes(int M, int N, int K);

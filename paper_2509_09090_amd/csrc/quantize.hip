@@ -21,26 +21,22 @@ __device__ __forceinline__ float quotient(float v, float s, float r)
     return fmaf(rem, r, q0);
 }
 
-// One block per output row.  Each thread owns groups t, t+256, ... of 8
-// consecutive elements, held in registers from the single read of the row to
-// the packed store.  Arithmetic (all binary32, IEEE, no contraction possible):
-//   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
-// GPT = groups per thread the instance is compiled for (registers, hence occupancy).
-template <bool ROTATE, int GPT>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
-                                                            const int32_t *__restrict__ rows, int K,
-                                                            uint8_t *__restrict__ Xq,
-                                                            __half *__restrict__ scale_out)
-{
-    extern __shared__ float rot[];       // K floats when ROTATE
-    __shared__ float wave_max[4];
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-    const int row = blockIdx.x;
-    const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
-    const uint4 *xrow = reinterpret_cast<const uint4 *>(X + src * ldx);
-    const int groups = K >> 3;
+// How the scale enters (Section 3.3):
+//   kPerRow      one scale per row, from the row's own maximum (per token / per output channel)
+//   kChannelwise static scale per input channel given by the caller; the per-row scale written is 1
+//   kFolded      the row is first multiplied by the per-channel scales (the activation scales folded
+//                into a weight), then quantized per row
+enum QuantMode { kPerRow = 0, kChannelwise = 1, kFolded = 2 };
 
-    float v[GPT][8];
+// Reads one row into registers (thread t owns groups t, t+256, ... of 8 consecutive
+// elements) and applies the rotation of Eq. 6 when ROTATE: butterfly stages at distance 1, 2,
+// 4 inside a group of 8 in registers, the remaining stages in LDS in the same order, then one
+// multiply by (float)(1/sqrt(K)).  Contains barriers when ROTATE.
+template <bool ROTATE, int GPT>
+__device__ __forceinline__ void load_row(const uint4 *xrow, int K, float (&v)[GPT][8], float *rot)
+{
+    const int t = threadIdx.x;
+    const int groups = K >> 3;
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
@@ -58,9 +54,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
             for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
         }
     }
-
     if (ROTATE) {
-        // Butterfly stages at distance 1, 2, 4 stay inside a group of 8: registers.
 #pragma unroll
         for (int gi = 0; gi < GPT; ++gi) {
 #pragma unroll
@@ -81,7 +75,6 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
             }
         }
         __syncthreads();
-        // Remaining stages, distance 8 .. K/2, in LDS in the same order.
         const int half_k = K >> 1;
         for (int h = 8; h < K; h <<= 1) {
             for (int p = t; p < half_k; p += 256) {
@@ -102,6 +95,76 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
             }
         }
     }
+}
+
+// The eight per-channel scales of group g as floats.
+__device__ __forceinline__ void load_col_scales(const __half *col_scales, int g, float (&c)[8])
+{
+    const uint4 raw = reinterpret_cast<const uint4 *>(col_scales)[g];
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float2 f = __half22float2(h2[p]);
+        c[2 * p] = f.x;
+        c[2 * p + 1] = f.y;
+    }
+}
+
+// One block per output row; the row stays in registers from its single read to the packed
+// store.  Arithmetic (all binary32, IEEE, no contraction possible):
+//   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
+// GPT = groups per thread the instance is compiled for (registers, hence occupancy).
+template <bool ROTATE, int GPT, int MODE>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                            const int32_t *__restrict__ rows, int K,
+                                                            const __half *__restrict__ col_scales,
+                                                            uint8_t *__restrict__ Xq,
+                                                            __half *__restrict__ scale_out)
+{
+    extern __shared__ float rot[];       // K floats when ROTATE
+    __shared__ float wave_max[4];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int row = blockIdx.x;
+    const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
+    const uint4 *xrow = reinterpret_cast<const uint4 *>(X + src * ldx);
+    const int groups = K >> 3;
+
+    float v[GPT][8];
+    load_row<ROTATE, GPT>(xrow, K, v, rot);
+    uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
+
+    if (MODE == kChannelwise) {
+        if (t == 0) scale_out[row] = __ushort_as_half((unsigned short)0x3c00);      // 1.0
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = t + gi * 256;
+            if (g < groups) {
+                float c[8];
+                load_col_scales(col_scales, g, c);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float r = rintf(v[gi][e] / c[e]);
+                    r = fminf(fmaxf(r, -8.f), 7.f);
+                    packed |= ((uint32_t)(int)r & 15u) << (4 * e);
+                }
+                qrow[g] = packed;
+            }
+        }
+        return;
+    }
+    if (MODE == kFolded) {
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = t + gi * 256;
+            if (g < groups) {
+                float c[8];
+                load_col_scales(col_scales, g, c);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[gi][e] = v[gi][e] * c[e];
+            }
+        }
+    }
 
     float amax = 0.f;
 #pragma unroll
@@ -118,10 +181,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     const float sf = __half2float(sh);
     if (t == 0) scale_out[row] = sh;
 
-    // Inputs that were not rotated are half values, for which the fast quotient is
-    // verified exhaustively; rotated rows take the division operator.
+    // Inputs that were neither rotated nor multiplied by channel scales are half values, for
+    // which the fast quotient is verified exhaustively; the others take the division operator.
     const float rcp = 1.0f / sf;
-    uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
@@ -129,7 +191,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float r = rintf(ROTATE ? v[gi][e] / sf : quotient(v[gi][e], sf, rcp));
+                float r = rintf((ROTATE || MODE == kFolded) ? v[gi][e] / sf : quotient(v[gi][e], sf, rcp));
                 r = fminf(fmaxf(r, -8.f), 7.f);
                 packed |= ((uint32_t)(int)r & 15u) << (4 * e);
             }
@@ -138,42 +200,152 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     }
 }
 
+// Static channel scales from calibration rows: each block walks rows blockIdx.x, + gridDim.x,
+// ... keeping the running maximum of its threads' columns in registers (the column layout of
+// load_row is the same for every row), then merges into amax[] with an integer atomic maximum
+// on the bit pattern (non-negative floats order like their bits; a maximum is order independent).
 template <bool ROTATE, int GPT>
-static void launch_quantize_inst(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, size_t lds,
-                                 uint8_t *Xq, __half *sx, hipStream_t st)
+__global__ __launch_bounds__(256) void channel_absmax_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                             const int32_t *__restrict__ rows, int M, int K,
+                                                             float *__restrict__ amax)
 {
-    hipLaunchKernelGGL((quantize_rows_kernel<ROTATE, GPT>), dim3(M), dim3(256), lds, st, X, ldx, rows, K, Xq, sx);
+    extern __shared__ float rot[];
+    const int t = threadIdx.x, groups = K >> 3;
+    float best[GPT][8];
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) best[gi][e] = 0.f;
+    for (int row = blockIdx.x; row < M; row += gridDim.x) {
+        const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
+        float v[GPT][8];
+        load_row<ROTATE, GPT>(reinterpret_cast<const uint4 *>(X + src * ldx), K, v, rot);
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) best[gi][e] = fmaxf(best[gi][e], fabsf(v[gi][e]));
+        if (ROTATE) __syncthreads();          // the next row reuses rot[]
+    }
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                atomicMax(reinterpret_cast<unsigned int *>(amax) + g * 8 + e, __float_as_uint(best[gi][e]));
+        }
+    }
 }
 
-template <bool ROTATE>
-static void launch_quantize_gpt(int gpt, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
-                                size_t lds, uint8_t *Xq, __half *sx, hipStream_t st)
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *p, int n)
 {
-    if (gpt <= 1) launch_quantize_inst<ROTATE, 1>(X, ldx, rows, M, K, lds, Xq, sx, st);
-    else if (gpt <= 2) launch_quantize_inst<ROTATE, 2>(X, ldx, rows, M, K, lds, Xq, sx, st);
-    else if (gpt <= 4) launch_quantize_inst<ROTATE, 4>(X, ldx, rows, M, K, lds, Xq, sx, st);
-    else if (gpt <= 6) launch_quantize_inst<ROTATE, 6>(X, ldx, rows, M, K, lds, Xq, sx, st);
-    else launch_quantize_inst<ROTATE, 8>(X, ldx, rows, M, K, lds, Xq, sx, st);
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+// c_k = half(amax_k / 7), 2^-24 if that is zero
+__global__ __launch_bounds__(256) void channel_scales_kernel(const float *__restrict__ amax, int K,
+                                                             __half *__restrict__ scales)
+{
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k < K) {
+        __half sh = __float2half_rn(amax[k] / 7.0f);
+        if (__half_as_ushort(sh) == 0) sh = __ushort_as_half((unsigned short)1);
+        scales[k] = sh;
+    }
+}
+
+template <bool ROTATE, int GPT, int MODE>
+static void launch_quantize_inst(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, size_t lds,
+                                 const __half *col_scales, uint8_t *Xq, __half *sx, hipStream_t st)
+{
+    hipLaunchKernelGGL((quantize_rows_kernel<ROTATE, GPT, MODE>), dim3(M), dim3(256), lds, st, X, ldx, rows, K,
+                       col_scales, Xq, sx);
+}
+
+template <bool ROTATE, int MODE>
+static void launch_quantize_gpt(int gpt, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                size_t lds, const __half *col_scales, uint8_t *Xq, __half *sx, hipStream_t st)
+{
+    if (gpt <= 1) launch_quantize_inst<ROTATE, 1, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    else if (gpt <= 2) launch_quantize_inst<ROTATE, 2, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    else if (gpt <= 4) launch_quantize_inst<ROTATE, 4, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    else if (gpt <= 6) launch_quantize_inst<ROTATE, 6, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    else launch_quantize_inst<ROTATE, 8, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+}
+
+// Rotation keeps the row in LDS: K floats, above the 64 KiB default for the widest rows.
+template <class Kern>
+static sqap_status allow_rotation_lds(Kern kernel, size_t lds)
+{
+    if (lds > 48 * 1024)
+        SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
+    return SQAP_OK;
+}
+
+template <int MODE>
+static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                        bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
+                                        hipStream_t st)
+{
+    const int gpt = (K / 8 + 255) / 256;
+    if (rotate) {
+        const size_t lds = (size_t)K * sizeof(float);
+        sqap_status s = allow_rotation_lds(&quantize_rows_kernel<true, 8, MODE>, lds);
+        if (s != SQAP_OK) return s;
+        launch_quantize_gpt<true, MODE>(gpt, X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    } else {
+        launch_quantize_gpt<false, MODE>(gpt, X, ldx, rows, M, K, 0, col_scales, Xq, sx, st);
+    }
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
 }
 
 sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                  bool rotate, uint8_t *Xq, __half *sx, hipStream_t st)
 {
-    const int gpt = (K / 8 + 255) / 256;
-    if (rotate) {
-        size_t lds = (size_t)K * sizeof(float);
-        if (lds > 48 * 1024) {
-            static bool configured = false;
-            if (!configured) {
-                SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&quantize_rows_kernel<true, 8>),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
-                configured = true;
-            }
+    return launch_quantize_mode<kPerRow>(X, ldx, rows, M, K, rotate, nullptr, Xq, sx, st);
+}
+
+sqap_status launch_quantize_rows_scaled(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                        bool rotate, bool folded, const __half *col_scales, uint8_t *Xq,
+                                        __half *sx, hipStream_t st)
+{
+    if (folded) return launch_quantize_mode<kFolded>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, st);
+    return launch_quantize_mode<kChannelwise>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, st);
+}
+
+template <bool ROTATE>
+static void launch_absmax_gpt(int gpt, int grid, size_t lds, const __half *X, int64_t ldx, const int32_t *rows,
+                              int M, int K, float *amax, hipStream_t st)
+{
+    if (gpt <= 2)
+        hipLaunchKernelGGL((channel_absmax_kernel<ROTATE, 2>), dim3(grid), dim3(256), lds, st, X, ldx, rows, M, K, amax);
+    else if (gpt <= 4)
+        hipLaunchKernelGGL((channel_absmax_kernel<ROTATE, 4>), dim3(grid), dim3(256), lds, st, X, ldx, rows, M, K, amax);
+    else
+        hipLaunchKernelGGL((channel_absmax_kernel<ROTATE, 8>), dim3(grid), dim3(256), lds, st, X, ldx, rows, M, K, amax);
+}
+
+sqap_status launch_channel_scales(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, bool rotate,
+                                  float *amax, bool accumulate, __half *scales, hipStream_t st)
+{
+    const int kblocks = (K + 255) / 256;
+    if (!accumulate) hipLaunchKernelGGL(fill_zero_kernel, dim3(kblocks), dim3(256), 0, st, amax, K);
+    if (M > 0) {
+        const int gpt = (K / 8 + 255) / 256;
+        const int grid = M < 256 ? M : 256;
+        if (rotate) {
+            const size_t lds = (size_t)K * sizeof(float);
+            sqap_status s = allow_rotation_lds(&channel_absmax_kernel<true, 8>, lds);
+            if (s != SQAP_OK) return s;
+            launch_absmax_gpt<true>(gpt, grid, lds, X, ldx, rows, M, K, amax, st);
+        } else {
+            launch_absmax_gpt<false>(gpt, grid, 0, X, ldx, rows, M, K, amax, st);
         }
-        launch_quantize_gpt<true>(gpt, X, ldx, rows, M, K, lds, Xq, sx, st);
-    } else {
-        launch_quantize_gpt<false>(gpt, X, ldx, rows, M, K, 0, Xq, sx, st);
     }
+    hipLaunchKernelGGL(channel_scales_kernel, dim3(kblocks), dim3(256), 0, st, amax, K, scales);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }

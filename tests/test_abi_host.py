@@ -120,3 +120,19 @@ def test_prune_select_validation():
     assert L.sqap_prune_select(p, 1, 16, 16, 64, 128, None, -1, p, 256, None, None) == B.EINVAL
     assert L.sqap_prune_select(None, 1, 16, 16, 64, 128, None, 1, p, 256, None, None) == B.EINVAL
     assert L.sqap_prune_select(None, 0, 16, 16, 64, 128, None, 1, None, 256, None, None) == B.OK     # empty batch
+
+
+def test_channelwise_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    assert L.sqap_channel_scales(p, 16, None, 4, 16, 0, None, 0, p, None) == B.EINVAL             # no amax buffer
+    assert L.sqap_channel_scales(p, 8, None, 4, 16, 0, p, 0, p, None) == B.EINVAL                 # pitch < K
+    assert L.sqap_channel_scales(p, 24, None, 4, 24, 1, p, 0, p, None) == B.EUNSUPPORTED          # rotate, K not 2^n
+    assert L.sqap_channel_scales(None, 16, None, 4, 16, 0, p, 0, p, None) == B.EINVAL
+    assert L.sqap_quantize_act_channelwise(p, 16, None, 4, 16, 0, None, p, p, None) == B.EINVAL   # no scales
+    assert L.sqap_quantize_act_channelwise(p, 16, None, 4, 16, 4, p, p, p, None) == B.EINVAL      # unknown flag
+    assert L.sqap_quantize_act_channelwise(p, 16, None, 4, 16, 0, ctypes.c_void_p(4104), p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_quantize_act_channelwise(p, 16, None, 0, 16, 0, p, None, None, None) == B.OK    # no rows
+    assert L.sqap_quantize_weight_folded(p, 4, 15, 0, p, p, p, None) == B.EINVAL                  # odd K
+    assert L.sqap_quantize_weight_folded(p, 4, 16, 0, p, None, p, None) == B.EINVAL
+    assert L.sqap_quantize_weight_folded(p, 0, 16, 0, p, None, None, None) == B.OK

@@ -226,6 +226,71 @@ def test_prune_select_feeds_the_row_list(G, oracle):
     assert np.array_equal(rows, oracle.kept_rows(np.stack(_oracle_select(oracle, s, 16, 16, 64, 128, cam, 1)), 276, 0, 256))
 
 
+# ------------------------------------------------------------------ channel-wise activations (Section 3.3)
+def _gpu_channelwise(G, X, W, rows=None, rotate=False, batches=1):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    flags = B.ROTATE_HADAMARD if rotate else 0
+    x, w = G.to_dev(X), G.to_dev(W)
+    r = None if rows is None else G.to_dev(rows.astype(np.int32))
+    K, N = X.shape[1], W.shape[0]
+    M = X.shape[0] if rows is None else rows.size
+    amax = torch.full((K,), 123.0, dtype=torch.float32, device="cuda")         # cleared by the call
+    c = torch.zeros((K,), dtype=torch.float16, device="cuda")
+    if batches == 1:
+        B.sqap_channel_scales(x, r, amax, c, flags)
+    else:                                                                       # same rows in several calls
+        order = np.arange(M) if rows is None else rows
+        parts = np.array_split(order, batches)
+        for i, part in enumerate(parts):
+            B.sqap_channel_scales(x, G.to_dev(part.astype(np.int32)), amax, c, flags, accumulate=i > 0)
+    xq = torch.zeros((M, K // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    B.sqap_quantize_act_channelwise(x, r, c, xq, sx, flags)
+    wq = torch.zeros((N, K // 2), dtype=torch.uint8, device="cuda")
+    sw = torch.zeros((N,), dtype=torch.float16, device="cuda")
+    B.sqap_quantize_weight_folded(w, c, wq, sw, flags)
+    torch.cuda.synchronize()
+    return c.cpu().numpy(), xq.cpu().numpy(), sx.cpu().numpy(), wq.cpu().numpy(), sw.cpu().numpy()
+
+
+@pytest.mark.parametrize("M,K,N,rotate,gather,batches", [
+    (148, 4096, 96, False, False, 1),      # the workload's hidden size
+    (300, 11008, 40, False, True, 3),      # the FFN width, gathered rows, calibration in three calls
+    (64, 512, 64, True, False, 1),         # rotated first
+    (37, 2048, 33, True, True, 2),
+    (5, 64, 3, False, False, 1),           # a single group of eight per thread, most threads idle
+    (700, 16384, 8, True, False, 1),       # the widest rows, more rows than calibration blocks
+])
+def test_channelwise_quantization(G, oracle, M, K, N, rotate, gather, batches):
+    rng = wl.rng_for(99, M, wl.T_X, extra=K)
+    S = M + 9 if gather else M
+    X, _ = wl.activations(S, K, max(1, wl.n_outliers_for(K)), 30.0, rng)
+    X[:, 3] = 0                                                  # a dead channel: smallest scale, codes 0
+    W = wl.weights(N, K, rng)
+    rows = rng.permutation(S)[:M].astype(np.int32) if gather else None
+    c, xq, sx, wq, sw = _gpu_channelwise(G, X, W, rows, rotate, batches)
+    co = oracle.channel_scales(X, rows=rows, rotate=rotate)
+    assert np.array_equal(c.view(np.uint16), co.view(np.uint16))
+    xqo, sxo = oracle.quantize_rows_channelwise(X, co, rows=rows, rotate=rotate)
+    assert np.array_equal(xq, xqo) and np.array_equal(sx.view(np.uint16), sxo.view(np.uint16))
+    wqo, swo = oracle.quantize_rows_folded(W, co, rotate=rotate)
+    assert np.array_equal(wq, wqo) and np.array_equal(sw.view(np.uint16), swo.view(np.uint16))
+
+
+def test_channelwise_linear_end_to_end(G, oracle):
+    """Calibrate, quantize both sides, run the W4A4 linear: exact accumulators, outputs at the parity bar."""
+    rng = wl.rng_for(99, 1, wl.T_W)
+    X, _ = wl.activations(148, 4096, 41, 30.0, rng)
+    W = wl.weights(256, 4096, rng)
+    c, xq, sx, wq, sw = _gpu_channelwise(G, X, W)
+    Y, acc = G.gpu_linear(xq, sx, wq, sw)
+    Yo, acco = oracle.w4a4_linear(xq, sx, wq, sw)
+    assert np.array_equal(acc, acco) and G.assert_fp16_close(Y, Yo) == 0
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.linalg.norm(Y.astype(np.float64) - ref) / np.linalg.norm(ref) < 0.35
+
+
 # ------------------------------------------------------------------ linear
 def _random_packed(rng, R, K):
     return rng.integers(0, 256, size=(R, K // 2), dtype=np.uint8)
