@@ -259,6 +259,41 @@ def layer_leg(torch, B, wl, stack):
     total = 2 * us276 + 30 * us84
     res["cfg2_stack"] = {"us_per_layer_M276": us276, "us_per_layer_M84": us84, "us_total_32_layers": total,
                          "floor_us": 456.0, "TOPS": (2 * ops_layer(276) + 30 * ops_layer(84)) / total / 1e6}
+
+    # pruning-ratio sweep on the same layers: 256 visual tokens pruned by 0.3 .. 0.6, plus 20 text tokens
+    few = range(min(4, n))
+    res["ratio_sweep"] = {"M%d" % M: run_layers(M, few) / len(few) for M in (199, 174, 148, 122)}
+    res["ratio_sweep"]["note"] = "us per layer (7 launches), pruning ratio 0.3 / 0.4 / 0.5 / 0.6 of 256 visual tokens"
+
+    # the same layer with q/k/v and gate/up packed as single weights: 4 launches instead of 7
+    g = stack.g
+    mk = lambda N, K: quantize_and_pack(torch, B, (torch.randn((N, K), generator=g, device=dev,
+                                                               dtype=torch.float32) * 0.02).half())
+    fused = [[mk(3 * H, H), mk(H, H), mk(2 * F, H), mk(H, F)] for _ in few]
+    shapes = [(3 * H, H), (H, H), (2 * F, H), (H, F)]
+    M = 148
+    xh, xf = stack.activation(M, H), stack.activation(M, F)
+    ys = [torch.empty((M, N), dtype=torch.float16, device=dev) for (N, _) in shapes]
+    nws = max([B.sqap_workspace_bytes(M, N, K) for (N, K) in shapes] + [256])
+    ws = torch.zeros((nws,), dtype=torch.uint8, device=dev)
+
+    def go_fused():
+        for row in fused:
+            for i, (N, K) in enumerate(shapes):
+                x = xf if K == F else xh
+                B.sqap_w4a4_linear(x[0], x[1], row[i], ys[i], None, ws)
+    go_fused()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        go_fused()
+    e1.record()
+    torch.cuda.synchronize()
+    res["cfg1_M148"]["us_per_layer_fused_qkv_gateup"] = e0.elapsed_time(e1) / 3 * 1e3 / len(fused)
+    for row in fused:
+        for w in row:
+            w.free()
     return res
 
 

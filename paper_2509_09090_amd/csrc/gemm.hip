@@ -27,8 +27,13 @@ constexpr int kMaxK = 131040;       // keeps 256 * 64 * K below 2^31
 // Persistent (stream-K) launch: at most this many workgroups, 8 XCDs.
 constexpr int kMaxPersistentBlocks = 256;
 constexpr int kXcds = 8;
-constexpr size_t kFlagBytes = 4096;         // workspace header: one flag per workgroup + error word
-constexpr int kErrWord = 500;               // index (in 64-bit words) of the error word in the header
+// Workspace header, in 64-bit words: [0, 256) one flag per workgroup (256 x 256 tiles), 500 the
+// error word, [512, 1024) arrival and [1024, 1536) departure flags of the narrow-tile kernel
+// (one per partial slot: 2 x 256).
+constexpr size_t kFlagBytes = 16384;
+constexpr int kErrWord = 500;
+constexpr int kArriveWord = 512;
+constexpr int kDepartWord = 1024;
 constexpr int kStreamKMinM = 512;           // from this M on the persistent kernel is used
 constexpr long long kSpinLimit = 200000000; // bounded wait (about a minute of polling)
 
@@ -458,9 +463,13 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
             int first = (int)((tb * nb) / total);            // candidate for the workgroup holding step tb
             while (total * (first + 1) / nb <= tb) ++first;  // (integer division: settle exactly)
             while (total * first / nb > tb) --first;
-            if (t == 0) {
-                for (int jj = first; jj < j; ++jj) {
-                    if (total * jj / nb >= total * (jj + 1) / nb) continue;   // that workgroup had no steps
+            // One lane per contributor (at most 31 of them) waits for that contributor's flag: the
+            // waits overlap instead of costing one memory round trip each.
+            unsigned *share = reinterpret_cast<unsigned *>(smem);       // LDS is free between main loop and epilogue
+            if (t < 64) {
+                const int jj = first + t;
+                const bool live = jj < j && total * jj / nb < total * (jj + 1) / nb;   // else: no such workgroup, or no steps
+                if (live) {
                     unsigned long long *f = &p.flags[jj * 8 + xcd];
                     long long spins = 0;
                     while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
@@ -474,44 +483,291 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
                     // a captured launch (same epoch argument) start from clear flags.
                     __hip_atomic_store(f, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
+                const unsigned long long mk = __ballot(live);
+                if (t == 0) *share = (unsigned)mk;
             }
+            __syncthreads();
+            const unsigned live_mask = *share;                // bit u: workgroup first + u left a partial
             __syncthreads();
             // Partials are read with agent-scope loads (sc1): they bypass this CU's L1 and
             // are served by the L2 the producer wrote through.
-            for (int jj = first; jj < j; ++jj) {
-                if (total * jj / nb >= total * (jj + 1) / nb) continue;
-                __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                    p.partials + (size_t)(jj * 8 + xcd) * SLOT_BYTES, 0, SLOT_BYTES, 0x00020000);
-                // half of the accumulator at a time: up to 16 loads in flight per thread
-                constexpr int TILES = C::TM * C::TN, HALF = (TILES + 1) / 2;
+            constexpr int TILES = C::TM * C::TN;
+            {
+                for (int jj = first; jj < j; ++jj) {
+                    if (!((live_mask >> (jj - first)) & 1u)) continue;
+                    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                        p.partials + (size_t)(jj * 8 + xcd) * SLOT_BYTES, 0, SLOT_BYTES, 0x00020000);
+                    // half of the accumulator at a time: up to 16 loads in flight per thread
+                    constexpr int HALF = (TILES + 1) / 2;
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    v4i tmp[HALF * 4];
+                    for (int h = 0; h < 2; ++h) {
+                        v4i tmp[HALF * 4];
 #pragma unroll
-                    for (int a = 0; a < HALF; ++a)
+                        for (int a = 0; a < HALF; ++a)
 #pragma unroll
-                        for (int qd = 0; qd < 4; ++qd) {
+                            for (int qd = 0; qd < 4; ++qd) {
+                                if (h * HALF + a >= TILES) continue;
+                                const auto v = __builtin_amdgcn_raw_buffer_load_b128(
+                                    rsrc, my_off + (h * HALF + a) * 4096 + qd * 1024, 0, 16);
+                                tmp[a * 4 + qd] = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+                            }
+#pragma unroll
+                        for (int a = 0; a < HALF; ++a) {
                             if (h * HALF + a >= TILES) continue;
-                            const auto v = __builtin_amdgcn_raw_buffer_load_b128(
-                                rsrc, my_off + (h * HALF + a) * 4096 + qd * 1024, 0, 16);
-                            tmp[a * 4 + qd] = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
-                        }
+                            const int ta = h * HALF + a, i = ta / C::TN, jn = ta % C::TN;
 #pragma unroll
-                    for (int a = 0; a < HALF; ++a) {
-                        if (h * HALF + a >= TILES) continue;
-                        const int ta = h * HALF + a, i = ta / C::TN, jn = ta % C::TN;
-#pragma unroll
-                        for (int qd = 0; qd < 4; ++qd) {
-                            acc[i][jn][4 * qd] += tmp[a * 4 + qd].x;
-                            acc[i][jn][4 * qd + 1] += tmp[a * 4 + qd].y;
-                            acc[i][jn][4 * qd + 2] += tmp[a * 4 + qd].z;
-                            acc[i][jn][4 * qd + 3] += tmp[a * 4 + qd].w;
+                            for (int qd = 0; qd < 4; ++qd) {
+                                acc[i][jn][4 * qd] += tmp[a * 4 + qd].x;
+                                acc[i][jn][4 * qd + 1] += tmp[a * 4 + qd].y;
+                                acc[i][jn][4 * qd + 2] += tmp[a * 4 + qd].z;
+                                acc[i][jn][4 * qd + 3] += tmp[a * 4 + qd].w;
+                            }
                         }
                     }
                 }
             }
         }
         epilogue<C>(p, acc, smem, m0, ng0);
+    }
+}
+
+// Split-K kernel for the narrow tile shapes (a few hundred token rows).  Same persistent
+// launch and the same division of every XCD's main-loop steps as above, but a tile is then
+// shared by many workgroups (eight at M = 148, N = K = 4096), and one finisher pulling every
+// partial through its own CU is bound by that CU's load path (560 KB: 9 us measured).  Here
+// the contributors of a tile finish it together:
+//   every contributor stores its accumulators and raises its arrival flag as soon as its
+//   steps of the tile are done, and goes on with its other main-loop work;
+//   at the end, once all flags of the tile are up, contributor number r adds the r-th slice
+//   of ALL the partials (its own included), dequantises that slice and stores it;
+//   it then raises its departure flag; contributor 0 waits for all departures and takes every
+//   flag of the tile down again, so that a replay of a captured launch, which carries the
+//   same epoch, starts clean.  Every flag has one writer: no read-modify-write atomics (a
+//   contended compare-and-swap costs about 1.7 us here).
+// A workgroup waits for workgroups with higher numbers too.  That cannot deadlock because
+// the launch has at most one workgroup per compute unit and each fits one, so all of them
+// are resident at the same time; the wait is bounded all the same (error word).
+// A workgroup can be part of two shared tiles (where its share ends: slot 0, and where it
+// begins: slot 1).
+template <class C>
+__global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int TILES = C::TM * C::TN;
+    constexpr int SLOT_BYTES = C::BM * C::BN * 4, UNITS = SLOT_BYTES / 16;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int tiles = p.m_tiles * p.n_tiles;
+    const int steps = p.chunks / kChunksPerStep;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, nb = p.blocks_per_xcd;
+    const int q = tiles >> 3, r = tiles & 7;
+    const int tile0 = xcd * q + (xcd < r ? xcd : r);
+    const int ntile = q + (xcd < r ? 1 : 0);
+    const long long total = (long long)ntile * steps;
+    const long long begin = total * j / nb, end = total * (j + 1) / nb;
+    if (begin >= end) return;
+    const int t_first = (int)(begin / steps), t_last = (int)((end - 1) / steps);
+    const int my_off = wave * (TILES * 4096) + lane * 16;
+    int *cslot = reinterpret_cast<int *>(smem);            // [0, 32): slot numbers of the tile's contributors
+    int *cinfo = cslot + 32;                               // [0]: how many, [1]: this workgroup's number among them
+    int *ckeep = cslot + 64;                               // [0, 64): slots whose flags this workgroup takes down at the end
+
+    // Phase 1: all the main-loop work.  A shared tile's partial sums are stored and this
+    // workgroup is counted in, without waiting for anybody: a workgroup that waited here would
+    // make its neighbour wait for everything the workgroup still has to do.
+    for (int tl = t_last; tl >= t_first; --tl) {
+        const long long tb = (long long)tl * steps;
+        const int s0 = (int)((begin > tb ? begin : tb) - tb);
+        const int s1 = (int)((end < tb + steps ? end : tb + steps) - tb);
+        const int tile = tile0 + tl;
+        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
+        v16i acc[C::TM][C::TN];
+        zero_acc<C>(acc);
+        mainloop<C, false>(p, smem, m0, ng0, s0, s1, acc);
+        if (s0 == 0 && s1 == steps) {
+            epilogue<C>(p, acc, smem, m0, ng0);            // the whole tile is this workgroup's
+            continue;
+        }
+        const int which = tl == t_last ? 0 : 1;
+        uint8_t *dst = p.partials + ((size_t)which * kMaxPersistentBlocks + blockIdx.x) * SLOT_BYTES + my_off;
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int jn = 0; jn < C::TN; ++jn) {
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd) {
+                    v4i v = {acc[i][jn][4 * qd], acc[i][jn][4 * qd + 1], acc[i][jn][4 * qd + 2],
+                             acc[i][jn][4 * qd + 3]};
+                    *reinterpret_cast<v4i *>(dst + qd * 1024) = v;
+                }
+                dst += 4096;
+            }
+        // The others sit behind the same L2 (same XCD); the stores are complete there once the
+        // vector-memory counter drains, and only then is this workgroup counted in.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (t == 0)
+            __hip_atomic_store(&p.flags[kArriveWord + which * kMaxPersistentBlocks + blockIdx.x], p.epoch,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // Phase 2: finish the shared tiles (at most two: where the share ends and where it begins).
+    if (t < 64) ckeep[t] = -1;                             // (LDS is free: the last main loop ended with a barrier)
+    for (int pass = 0; pass < 2; ++pass) {
+        const int tl = pass == 0 ? t_last : t_first;
+        if (pass == 1 && t_first == t_last) break;
+        const long long tb = (long long)tl * steps;
+        const int s0 = (int)((begin > tb ? begin : tb) - tb);
+        const int s1 = (int)((end < tb + steps ? end : tb + steps) - tb);
+        if (s0 == 0 && s1 == steps) continue;              // was a whole tile
+        const int tile = tile0 + tl;
+        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
+        // who shares this tile: the workgroups of this XCD from the holder of its first step to
+        // the holder of its last step (those with an empty share excepted)
+        int first = (int)((tb * nb) / total);
+        while (total * (first + 1) / nb <= tb) ++first;
+        while (total * first / nb > tb) --first;
+        __syncthreads();                                   // cslot / cinfo of the previous pass are no longer read
+        if (t < 64) {
+            const int jj = first + t;
+            const long long jb = jj < nb ? total * jj / nb : 0, je = jj < nb ? total * (jj + 1) / nb : 0;
+            const bool live = jj < nb && jb < je && jb < tb + steps;          // has steps, and they start inside the tile
+            const unsigned long long mk = __ballot(live);
+            if (live) {
+                const int rank = __popcll(mk & ((1ull << t) - 1ull));
+                const int w2 = tl == (int)((je - 1) / steps) ? 0 : 1;          // the slot that workgroup used for this tile
+                cslot[rank] = w2 * kMaxPersistentBlocks + jj * 8 + xcd;
+                if (jj == j) cinfo[1] = rank;
+            }
+            if (t == 0) cinfo[0] = __popcll(mk);
+        }
+        __syncthreads();
+        const int nc = cinfo[0], rank = cinfo[1];
+        // one lane per contributor waits for that contributor's arrival
+        if (t < nc) {
+            const unsigned long long *f = &p.flags[kArriveWord + cslot[t]];
+            long long spins = 0;
+            while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
+                __builtin_amdgcn_s_sleep(8);
+                if (++spins > kSpinLimit) {
+                    p.flags[kErrWord] = p.epoch;          // give up: the result of this tile is wrong
+                    break;
+                }
+            }
+        }
+        __syncthreads();
+
+        // this workgroup's slice of the tile, 16 bytes (4 channels of one token) per thread at a time;
+        // partials are read with agent-scope loads (sc1): they bypass this CU's L1
+        const int ub = (int)((long long)UNITS * rank / nc), ue = (int)((long long)UNITS * (rank + 1) / nc);
+        const bool y_vec = (p.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(p.Y) & 7u) == 0;
+        constexpr int UPT = 4;                             // units per thread per trip
+        for (int u0 = ub + t; u0 < ue; u0 += UPT * C::THREADS) {
+            // where each unit goes, and its scales: issued before the partial sums so that the
+            // two kinds of load overlap.  unit u = ((w * TILES + a) * 4 + qd) * 64 + l
+            int row[UPT], col[UPT];
+            bool live[UPT];
+            float sxf[UPT];
+            uint2 swr[UPT];
+#pragma unroll
+            for (int x = 0; x < UPT; ++x) {
+                const int u = u0 + x * C::THREADS;
+                const int l = u & 63, qd = (u >> 6) & 3, a = (u >> 8) % TILES, w = (u >> 8) / TILES;
+                row[x] = m0 + (w / C::WAVES_N) * C::WM + (a / C::TN) * 32 + (l & 31);
+                col[x] = (ng0 << 5) + (w % C::WAVES_N) * C::WN + (a % C::TN) * 32 + qd * 8 + (l >> 5) * 4;
+                live[x] = u < ue && row[x] < p.M && col[x] < p.N;
+                sxf[x] = 0.f;
+                swr[x] = uint2{0u, 0u};
+                if (live[x]) {
+                    sxf[x] = __half2float(p.sx[row[x]]) * 0.00390625f;
+                    swr[x] = *reinterpret_cast<const uint2 *>(p.sw + col[x]);        // zero padded past N
+                }
+            }
+            // four contributors at a time: up to 16 loads in flight
+            v4i sums[UPT];
+#pragma unroll
+            for (int x = 0; x < UPT; ++x) sums[x] = v4i{0, 0, 0, 0};
+            for (int c0 = 0; c0 < nc; c0 += 4) {
+                v4i tmp[4][UPT];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (c0 + k < nc) {
+                        __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                            p.partials + (size_t)__builtin_amdgcn_readfirstlane(cslot[c0 + k]) * SLOT_BYTES, 0,
+                            SLOT_BYTES, 0x00020000);
+#pragma unroll
+                        for (int x = 0; x < UPT; ++x) {
+                            if (live[x]) {
+                                const auto v = __builtin_amdgcn_raw_buffer_load_b128(
+                                    rsrc, (u0 + x * C::THREADS) * 16, 0, 16);
+                                tmp[k][x] = v4i{(int)v[0], (int)v[1], (int)v[2], (int)v[3]};
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+                    if (c0 + k < nc) {
+#pragma unroll
+                        for (int x = 0; x < UPT; ++x)
+                            if (live[x]) sums[x] += tmp[k][x];
+                    }
+            }
+#pragma unroll
+            for (int x = 0; x < UPT; ++x) {
+                if (!live[x]) continue;
+                const v4i sum = sums[x];
+                const __half2 *sw2 = reinterpret_cast<const __half2 *>(&swr[x]);
+                const float2 s01 = __half22float2(sw2[0]), s23 = __half22float2(sw2[1]);
+                uint2 pk;
+                pk.x = dequant2(sum.x, sum.y, sxf[x], s01.x, s01.y);
+                pk.y = dequant2(sum.z, sum.w, sxf[x], s23.x, s23.y);
+                __half *dst = p.Y + (size_t)row[x] * p.ldy + col[x];
+                if (y_vec && col[x] + 4 <= p.N) {
+                    *reinterpret_cast<uint2 *>(dst) = pk;
+                } else {
+                    const __half *h = reinterpret_cast<const __half *>(&pk);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col[x] + e < p.N) dst[e] = h[e];
+                }
+                if (p.acc_out) {
+                    int32_t *ad = p.acc_out + (size_t)row[x] * p.N + col[x];
+                    const int v4[4] = {sum.x >> 8, sum.y >> 8, sum.z >> 8, sum.w >> 8};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (col[x] + e < p.N) ad[e] = v4[e];
+                }
+            }
+        }
+        // every load of the others' partials has been consumed above: count out
+        __syncthreads();
+        if (t == 0)
+            __hip_atomic_store(&p.flags[kDepartWord + cslot[rank]], p.epoch, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        // contributor 0 takes the tile's flags down once everybody is out: phase 3
+        if (rank == 0 && t < nc) ckeep[pass * 32 + t] = cslot[t];
+    }
+
+    // Phase 3: flags of the tiles this workgroup is contributor 0 of.  Waiting for the others'
+    // departures here, after this workgroup's own, keeps the waits from forming a chain.
+    __syncthreads();
+    if (t < 64) {
+        const int slot = ckeep[t];
+        if (slot >= 0) {
+            unsigned long long *d = &p.flags[kDepartWord + slot];
+            long long spins = 0;
+            while (__hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
+                __builtin_amdgcn_s_sleep(8);
+                if (++spins > kSpinLimit) {
+                    p.flags[kErrWord] = p.epoch;
+                    break;
+                }
+            }
+            __hip_atomic_store(d, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&p.flags[kArriveWord + slot], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -558,10 +814,10 @@ using CfgLow = Cfg<96, 128, 1, 4>;
 size_t linear_workspace_bytes(int M, int, int K)
 {
     if (K % kBK != 0 || M <= kSkinnyMaxM) return 0;
-    const size_t slot = M >= kStreamKMinM ? (size_t)CfgBig::BM * CfgBig::BN
-                                          : (M > CfgLow::BM ? (size_t)CfgMid::BM * CfgMid::BN
-                                                            : (size_t)CfgLow::BM * CfgLow::BN);
-    return kFlagBytes + (size_t)kMaxPersistentBlocks * slot * sizeof(int32_t);
+    // one tile-sized int32 slot per workgroup; the narrow shapes need two (see gemm_splitk_kernel)
+    if (M >= kStreamKMinM) return kFlagBytes + (size_t)kMaxPersistentBlocks * CfgBig::BM * CfgBig::BN * sizeof(int32_t);
+    const size_t slot = M > CfgLow::BM ? (size_t)CfgMid::BM * CfgMid::BN : (size_t)CfgLow::BM * CfgLow::BN;
+    return kFlagBytes + 2 * (size_t)kMaxPersistentBlocks * slot * sizeof(int32_t);
 }
 
 template <class C, class K>
@@ -598,7 +854,7 @@ static sqap_status launch_tiled(GemmParams &p, hipStream_t st)
     return launch_tiled_k<C, false>(p, st);
 }
 
-template <class C>
+template <class C, bool SPLITK>
 static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st)
 {
     p.m_tiles = (p.M + C::BM - 1) / C::BM;
@@ -612,11 +868,16 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;
     static bool configured = false;
     if (!configured) {
-        sqap_status s = set_lds<C>(&gemm_streamk_kernel<C>);
+        sqap_status s;
+        if constexpr (SPLITK) s = set_lds<C>(&gemm_splitk_kernel<C>);
+        else s = set_lds<C>(&gemm_streamk_kernel<C>);
         if (s != SQAP_OK) return s;
         configured = true;
     }
-    hipLaunchKernelGGL((gemm_streamk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
+    if constexpr (SPLITK)
+        hipLaunchKernelGGL((gemm_splitk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
+    else
+        hipLaunchKernelGGL((gemm_streamk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
@@ -640,9 +901,17 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
     p.chunks = w.chunks;
     p.y_vec_ok = (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (ldy & 7) == 0;
     if (w.K % kBK == 0) {
-        if (M >= kStreamKMinM) return launch_streamk<CfgBig>(p, workspace, st);
-        if (M > CfgLow::BM) return launch_streamk<CfgMid>(p, workspace, st);
-        return launch_streamk<CfgLow>(p, workspace, st);
+        if (M >= kStreamKMinM) return launch_streamk<CfgBig, false>(p, workspace, st);
+        // Narrow tiles.  With few tiles, each is shared by many workgroups (256 / tiles of them) and
+        // the contributors finish it together; with many tiles a single finisher has only two or
+        // three partials to add, which measured faster than the joint finish (23.6 vs 28.6 us at
+        // M = 148, N = 11008, K = 4096; the other way round, 21.6 vs 15.2 us, at N = 4096).
+        const bool mid = M > CfgLow::BM;
+        const int64_t tiles = (int64_t)((M + (mid ? CfgMid::BM : CfgLow::BM) - 1) / (mid ? CfgMid::BM : CfgLow::BM)) *
+                              ((w.N + CfgMid::BN - 1) / CfgMid::BN);
+        const bool joint = tiles * 4 <= kMaxPersistentBlocks;
+        if (mid) return joint ? launch_streamk<CfgMid, true>(p, workspace, st) : launch_streamk<CfgMid, false>(p, workspace, st);
+        return joint ? launch_streamk<CfgLow, true>(p, workspace, st) : launch_streamk<CfgLow, false>(p, workspace, st);
     }
     // K not a multiple of 128: one tile per workgroup, reduction axis guarded
     if (M <= CfgLow::BM) return launch_tiled<CfgLow>(p, st);

@@ -357,14 +357,16 @@ def test_attn_scores(G, oracle):
         assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7)
 
 
-def test_linear_replayed_from_a_graph(G, oracle):
-    """A captured launch of the split (persistent) kernel carries the launch epoch it was captured with:
+@pytest.mark.parametrize("M,N,K", [(600, 768, 1024),     # 3 x 3 tiles of 256 x 256 over 256 workgroups: every tile is shared
+                                   (148, 1024, 2048),    # narrow tiles, finished together by their contributors
+                                   (84, 512, 11008)])
+def test_linear_replayed_from_a_graph(G, oracle, M, N, K):
+    """A captured launch of the split (persistent) kernels carries the launch epoch it was captured with:
     every replay, with new operands and eager launches on the same workspace in between, must still
     give the exact result."""
     import torch
     from paper_2509_09090_amd import binding as B
-    rng = np.random.default_rng(4242)
-    M, N, K = 600, 768, 1024            # 3 x 3 tiles of 256 x 256 over 256 workgroups: every tile is shared
+    rng = np.random.default_rng(4242 + M)
     Wq = _random_packed(rng, N, K)
     sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
     W = B.sqap_weight_pack(G.to_dev(Wq), G.to_dev(sw))
