@@ -56,15 +56,32 @@ __device__ __forceinline__ T *uni(T *p)
     return reinterpret_cast<T *>(uni((long long)reinterpret_cast<uintptr_t>(p)));
 }
 
-// First item whose cumulative cost (in 16-byte weight pieces per row) reaches `target`.
-__device__ __forceinline__ int item_at_cost(const SkinnyEntry *table, int count, int total_items, long long target)
+// A block's run of items: the first item whose cumulative cost (in 16-byte weight pieces per
+// row) reaches the block's share boundary, for both of its boundaries at once.  The problem
+// holding a boundary is found by counting, across the lanes, the problems that start at or
+// before it (cost_begin is nondecreasing): one round of loads for both boundaries instead of
+// a scan with one dependent load per problem, which used to cost the last blocks of a 225-problem
+// launch tens of microseconds before their first weight load.
+__device__ __forceinline__ void block_run(const SkinnyEntry *table, int count, int total_items, long long lo,
+                                          long long hi, bool to_the_end, int lane, int *beg, int *end, int *problem)
 {
-    int p = 0;
-    while (p + 1 < count && uni(table[p + 1].cost_begin) <= target) ++p;
-    const long long into = target - uni(table[p].cost_begin);
-    const int ch = uni(table[p].chunks);
-    long long it = uni(table[p].rg_begin) + (into + ch - 1) / ch;
-    return it < total_items ? (int)it : total_items;
+    int n_lo = 0, n_hi = 0;
+#pragma unroll 4
+    for (int base = 0; base < count; base += 64) {
+        const int e = base + lane;
+        const long long c = e < count ? table[e].cost_begin : 0x7fffffffffffffffll;
+        n_lo += __popcll(__ballot(c <= lo));
+        n_hi += __popcll(__ballot(c <= hi));
+    }
+    auto item_of = [&](int p, long long target) {
+        const long long into = target - uni(table[p].cost_begin);
+        const int ch = uni(table[p].chunks);
+        const long long it = uni(table[p].rg_begin) + (into + ch - 1) / ch;
+        return it < total_items ? (int)it : total_items;
+    };
+    *problem = n_lo - 1;                          // cost_begin of problem 0 is 0: at least one counted
+    *beg = item_of(n_lo - 1, lo);
+    *end = to_the_end ? total_items : item_of(n_hi - 1, hi);
 }
 
 // LDS: [0, 16): zeros; then the packed activations of the current problem,
@@ -88,12 +105,10 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
     if (t < 4) reinterpret_cast<int *>(smem)[t] = 0;
 
     const SkinnyEntry *table = a.table ? a.table : a.inline_entries;
-    const int beg = item_at_cost(table, a.count, a.total_items, a.total_cost * blockIdx.x / gridDim.x);
-    const int end = blockIdx.x + 1 == gridDim.x
-                        ? a.total_items
-                        : item_at_cost(table, a.count, a.total_items, a.total_cost * (blockIdx.x + 1) / gridDim.x);
+    int prob, beg, end;                            // prob: the problem the first item belongs to (or the one before it)
+    block_run(table, a.count, a.total_items, a.total_cost * blockIdx.x / gridDim.x,
+              a.total_cost * (blockIdx.x + 1) / gridDim.x, blockIdx.x + 1 == gridDim.x, lane, &beg, &end, &prob);
     const int r = lane & 31, h = lane >> 5;
-    int prob = 0;
     for (int cur = beg; cur < end;) {
         while (prob + 1 < a.count && cur >= uni(table[prob + 1].rg_begin)) ++prob;
         SkinnyEntry e = table[prob];
