@@ -811,12 +811,21 @@ using CfgBig = Cfg<256, 256, 2, 4>;
 using CfgMid = Cfg<160, 128, 1, 4>;
 using CfgLow = Cfg<96, 128, 1, 4>;
 
+// Below kStreamKMinM rows: 160- or 96-row tiles, whichever pads M less (148 -> one tile of 160;
+// 84 -> one of 96; 174, 199 or 276 -> two or three of 96 rather than two of 160).
+static bool narrow_tile_is_mid(int M)
+{
+    const int pad_mid = (M + CfgMid::BM - 1) / CfgMid::BM * CfgMid::BM;
+    const int pad_low = (M + CfgLow::BM - 1) / CfgLow::BM * CfgLow::BM;
+    return pad_mid <= pad_low;
+}
+
 size_t linear_workspace_bytes(int M, int, int K)
 {
     if (K % kBK != 0 || M <= kSkinnyMaxM) return 0;
     // one tile-sized int32 slot per workgroup; the narrow shapes need two (see gemm_splitk_kernel)
     if (M >= kStreamKMinM) return kFlagBytes + (size_t)kMaxPersistentBlocks * CfgBig::BM * CfgBig::BN * sizeof(int32_t);
-    const size_t slot = M > CfgLow::BM ? (size_t)CfgMid::BM * CfgMid::BN : (size_t)CfgLow::BM * CfgLow::BN;
+    const size_t slot = narrow_tile_is_mid(M) ? (size_t)CfgMid::BM * CfgMid::BN : (size_t)CfgLow::BM * CfgLow::BN;
     return kFlagBytes + 2 * (size_t)kMaxPersistentBlocks * slot * sizeof(int32_t);
 }
 
@@ -906,7 +915,7 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
         // the contributors finish it together; with many tiles a single finisher has only two or
         // three partials to add, which measured faster than the joint finish (23.6 vs 28.6 us at
         // M = 148, N = 11008, K = 4096; the other way round, 21.6 vs 15.2 us, at N = 4096).
-        const bool mid = M > CfgLow::BM;
+        const bool mid = narrow_tile_is_mid(M);
         const int64_t tiles = (int64_t)((M + (mid ? CfgMid::BM : CfgLow::BM) - 1) / (mid ? CfgMid::BM : CfgLow::BM)) *
                               ((w.N + CfgMid::BN - 1) / CfgMid::BN);
         const bool joint = tiles * 4 <= kMaxPersistentBlocks;
