@@ -248,9 +248,14 @@ size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K);
  * workspace: at least sqap_workspace_bytes(M, N, K) bytes, 256-byte aligned
  * (may be NULL when that is 0); its contents need no initialisation.  Calls
  * that share a workspace must be ordered on one stream.  The large- and mid-M
- * kernels are persistent: they assume the whole device (one workgroup per
- * compute unit resident at once).  One entry point serves prefill (large M) and decode (M <= 8);
- * the kernel is chosen from M inside.
+ * kernels are persistent (one workgroup per compute unit) and split tiles
+ * between workgroups, which exchange partial sums through the workspace; a
+ * wait that does not end within about a minute gives up and writes a nonzero
+ * value to the 64-bit word at byte 4000 of the workspace (the result is then
+ * wrong).  A launch may be captured in a HIP graph and replayed: every flag it
+ * raises in the workspace is cleared again before it ends.  One entry point
+ * serves prefill (large M) and decode (M <= 8); the kernel is chosen from M
+ * inside.
  * EINVAL: null pointer, M < 0, ldy < N, workspace too small.
  */
 sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
