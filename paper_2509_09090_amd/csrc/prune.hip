@@ -93,6 +93,85 @@ __global__ __launch_bounds__(256) void topk_rank_kernel(const float *__restrict_
     }
 }
 
+// n <= 1024 and a sequence of at most 2048 positions: one wavefront per observation, no
+// barriers and no LDS traffic in the ranking.  Lane l owns tokens l, l + 64, ...: tokens
+// 64 r .. 64 r + 63 sit in lane order, so "lower index first" is "lower row, then lower lane".
+// The keep_k-th largest key T is built bit by bit from the top (T is the largest value that at
+// least keep_k keys reach) with wave ballots; keys above T are kept, and of the keys equal to T
+// the first ones by index.  Outputs are compacted with ballot prefixes.  PL = tokens per lane.
+template <int PL>
+__global__ __launch_bounds__(64) void topk_wave_kernel(const float *__restrict__ scores, int n, int keep_k,
+                                                       int32_t *__restrict__ idx_out, int seq_len, int vis_begin,
+                                                       int32_t *__restrict__ rows_out)
+{
+    __shared__ uint8_t keptf[1024];
+    const int lane = threadIdx.x, b = blockIdx.x;
+    const float *s = scores + (size_t)b * n;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    bool valid[PL], kept[PL];
+    uint32_t key[PL];
+#pragma unroll
+    for (int r = 0; r < PL; ++r) {
+        const int i = lane + 64 * r;
+        valid[r] = i < n;
+        key[r] = valid[r] ? score_key(s[i]) : 0u;
+    }
+    uint32_t T = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        int reach = 0;
+#pragma unroll
+        for (int r = 0; r < PL; ++r) reach += __popcll(__ballot(valid[r] && key[r] >= cand));
+        if (reach >= keep_k) T = cand;
+    }
+    int above = 0;
+#pragma unroll
+    for (int r = 0; r < PL; ++r) above += __popcll(__ballot(valid[r] && key[r] > T));
+    const int need_eq = keep_k - above;
+    int32_t *out = idx_out + (size_t)b * keep_k;
+    int eq_seen = 0, base = 0;
+#pragma unroll
+    for (int r = 0; r < PL; ++r) {
+        const bool eq = valid[r] && key[r] == T;
+        const unsigned long long me = __ballot(eq);
+        kept[r] = valid[r] && (key[r] > T || (eq && eq_seen + __popcll(me & below) < need_eq));
+        eq_seen += __popcll(me);
+        const unsigned long long mk = __ballot(kept[r]);
+        if (kept[r]) out[base + __popcll(mk & below)] = lane + 64 * r;
+        base += __popcll(mk);
+        if (rows_out && valid[r]) keptf[lane + 64 * r] = kept[r];
+    }
+    if (rows_out) {
+        // LDS operations of one wavefront complete in order: the flags written above are visible
+        __builtin_amdgcn_wave_barrier();
+        int32_t *rows = rows_out + (size_t)b * (seq_len - n + keep_k);
+        int rbase = 0;
+        for (int c = 0; c < seq_len; c += 64) {
+            const int sq = c + lane, v = sq - vis_begin;
+            const bool keep = sq < seq_len && (v < 0 || v >= n || keptf[v]);
+            const unsigned long long mk = __ballot(keep);
+            if (keep) rows[rbase + __popcll(mk & below)] = b * seq_len + sq;
+            rbase += __popcll(mk);
+        }
+    }
+}
+
+static bool launch_topk_wave(const float *scores, int batch, int n, int keep_k, int32_t *idx, int seq_len,
+                             int vis_begin, int32_t *rows, hipStream_t st)
+{
+    if (n > 1024 || seq_len > 2048) return false;
+    if (n <= 256)
+        hipLaunchKernelGGL(topk_wave_kernel<4>, dim3(batch), dim3(64), 0, st, scores, n, keep_k, idx, seq_len,
+                           vis_begin, rows);
+    else if (n <= 512)
+        hipLaunchKernelGGL(topk_wave_kernel<8>, dim3(batch), dim3(64), 0, st, scores, n, keep_k, idx, seq_len,
+                           vis_begin, rows);
+    else
+        hipLaunchKernelGGL(topk_wave_kernel<16>, dim3(batch), dim3(64), 0, st, scores, n, keep_k, idx, seq_len,
+                           vis_begin, rows);
+    return true;
+}
+
 // Any n: radix select, 8 bits per pass from the top, finds the key T of the
 // keep_k-th ranked element and how many elements equal to T are kept; a last
 // pass in index order keeps key > T and the first `need_eq` with key == T.
@@ -148,7 +227,8 @@ __global__ __launch_bounds__(256) void topk_radix_kernel(const float *__restrict
 sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
                               hipStream_t st)
 {
-    if (n <= kTopkSmallMax)
+    if (launch_topk_wave(scores, batch, n, keep_k, idx, 0, 0, nullptr, st)) {
+    } else if (n <= kTopkSmallMax)
         hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx, 0, 0,
                            (int32_t *)nullptr);
     else
@@ -164,6 +244,10 @@ sqap_status launch_kept_rows(const int32_t *idx, int batch, int keep_k, int seq_
 sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,
                               int32_t *idx, int32_t *rows, hipStream_t st)
 {
+    if (launch_topk_wave(scores, batch, n, keep_k, idx, seq_len, vis_begin, rows, st)) {
+        SQAP_HIP_CHECK(hipGetLastError());
+        return SQAP_OK;
+    }
     if (n <= kTopkSmallMax) {
         hipLaunchKernelGGL(topk_rank_kernel, dim3(batch), dim3(256), 0, st, scores, n, keep_k, idx, seq_len,
                            vis_begin, rows);

@@ -75,7 +75,8 @@ def test_kept_rows_and_gather(G, oracle, batch, S, v0, nv, k):
 
 @pytest.mark.parametrize("batch,S,v0,nv,k", [(16, 276, 0, 256, 128), (1, 276, 0, 256, 64), (3, 30, 4, 16, 5),
                                              (2, 700, 100, 500, 123), (2, 20, 0, 20, 0), (2, 2500, 7, 2048, 1000),
-                                             (2, 5000, 100, 4096, 77), (2, 40, 5, 30, 30)])
+                                             (2, 5000, 100, 4096, 77), (2, 40, 5, 30, 30),
+                                             (2, 1500, 3, 1000, 400), (2, 2100, 0, 900, 10), (3, 600, 88, 512, 511)])
 def test_prune_rows_fused(G, oracle, batch, S, v0, nv, k):
     import torch
     from paper_2509_09090_amd import binding as B
