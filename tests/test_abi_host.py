@@ -136,3 +136,20 @@ def test_channelwise_validation():
     assert L.sqap_quantize_weight_folded(p, 4, 15, 0, p, p, p, None) == B.EINVAL                  # odd K
     assert L.sqap_quantize_weight_folded(p, 4, 16, 0, p, None, p, None) == B.EINVAL
     assert L.sqap_quantize_weight_folded(p, 0, 16, 0, p, None, None, None) == B.OK
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_package_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import or load it."""
+    pkg = os.path.join(ROOT, "paper_2509_09090_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "sqap_oracle" not in text, f
