@@ -318,6 +318,47 @@ def selection_leg(torch, B, wl, dev, iters=50):
             "keep_total": total, "ring_radius": radius, "note": "back-to-back launches, includes launch overhead"}
 
 
+def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
+    """Microseconds per call of the selection and quantization kernels at configuration 3's sizes
+    (back-to-back launches on one stream, HIP events around the run)."""
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    q, k = wl.query_and_keys(wl.SEQ_LEN, wl.N_HEADS, wl.HEAD_DIM, wl.rng_for(3, 2, wl.T_Q))
+    q, k = torch.from_numpy(q).to(dev), torch.from_numpy(k).to(dev)
+    a_q = torch.empty((wl.N_VISUAL,), dtype=torch.float32, device=dev)
+    gathered = torch.empty((wk.M, wk.H), dtype=torch.float16, device=dev)
+    nb = 16
+    qb = q.unsqueeze(0).repeat(nb, 1, 1).contiguous()
+    kb = k.unsqueeze(0).repeat(nb, 1, 1, 1).contiguous()
+    a_qb = torch.empty((nb, wl.N_VISUAL), dtype=torch.float32, device=dev)
+    out = {
+        "attn_scores_S276_H32_d128": timed(lambda: B.sqap_attn_scores(q, k, 0, wl.N_VISUAL, a_q)),
+        "attn_scores_batch16_S276_H32_d128": timed(lambda: B.sqap_attn_scores_batch(qb, kb, 0, wl.N_VISUAL, a_qb)),
+        "prune_rows_16x256_to_128": timed(lambda: B.sqap_prune_rows(wk.scores, wk.keep, wk.S, 0, wk.idx, wk.rows)),
+        "gather_rows_2368x4096": timed(lambda: B.sqap_gather_rows(wk.X, wk.rows, gathered)),
+        "quantize_act_2368x4096_fused_gather": timed(lambda: B.sqap_quantize_act(wk.X, wk.rows, wk.Xq, wk.sx)),
+        "quantize_act_2368x11008": timed(lambda: B.sqap_quantize_act(wk.Xd, None, wk.Xdq, wk.sxd)),
+        "quantize_act_2368x4096_rotated": timed(
+            lambda: B.sqap_quantize_act(wk.X, wk.rows, wk.Xq, wk.sx, flags=B.ROTATE_HADAMARD)),
+    }
+    # algorithmic bytes: 2 B read + 0.5 B written per element (+ scales)
+    for name, (rows_, cols) in (("quantize_act_2368x4096_fused_gather", (wk.M, wk.H)),
+                                ("quantize_act_2368x11008", (wk.M, wk.F))):
+        out[name + "_GBps"] = rows_ * cols * 2.5 / out[name] / 1e3
+    out["note"] = "us per call, back-to-back launches (includes launch overhead)"
+    return out
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, on the same step (all 16 observations)."""
     import ctypes
@@ -419,6 +460,7 @@ def main():
                      "algorithmic_ops_per_launch": gemm_ops,
                      "traffic": stored_traffic("gemm_streamk_kernel")},
     }
+    out["kernels_us"] = small_kernel_leg(torch, B, wl, wk, dev)
     del wk
     torch.cuda.empty_cache()
     if not (args.no_decode and args.no_layers):

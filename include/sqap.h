@@ -63,13 +63,29 @@ const char *sqap_version(void);
  * head the softmax over all S keys of (q.k)/sqrt(d) and writes the mean over
  * heads of the weights of the visual span:
  *   scores_out[j] = (1/H) sum_h softmax_s(l[h,:])[vis_begin + j],  j < n_vis.
- * Arithmetic in binary32.  scores_out: n_vis floats.
- * EINVAL: null pointer, S/H/d <= 0, span outside [0,S).  EUNSUPPORTED: d > 256
- * or S > 16384.
+ * Arithmetic in binary32.  scores_out: n_vis floats.  All pointers are device
+ * pointers owned by the caller.  The heads are added in head order, so the
+ * result is the same bits on every call.
+ * The kernel keeps per-head weights in a scratch array that belongs to the
+ * device (no workspace argument): calls of this function and of
+ * sqap_attn_scores_batch that overlap in time on one device (two streams, two
+ * host threads) race; calls in one stream do not.
+ * EINVAL: null pointer, S/H/d <= 0, span outside [0,S).  EUNSUPPORTED: d > 256,
+ * d odd or S > 16384.
  */
 sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
                              int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
                              void *stream);
+
+/*
+ * The same score for `batch` observations in one launch: q[batch,H,d],
+ * k[batch,S,H,d], scores_out[batch,n_vis] (row-major, dense); observation b
+ * gets exactly what sqap_attn_scores gives for q[b], k[b].  batch = 0 is a
+ * no-op.  Errors as above; EINVAL for batch < 0, EUNSUPPORTED for batch > 4096.
+ */
+sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S,
+                                   int32_t H, int32_t d, int32_t vis_begin, int32_t n_vis,
+                                   float *scores_out, void *stream);
 
 /*
  * Eq. 1: K_attn = Top_k(a_q, k).  For each of `batch` rows of `scores`

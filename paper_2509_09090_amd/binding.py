@@ -17,7 +17,7 @@ OK, EINVAL, EUNSUPPORTED, EDEVICE, ENOMEM = 0, -1, -2, -3, -4
 ROTATE_HADAMARD = 1
 
 EXPORTS = (
-    "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_prune_topk", "sqap_kept_rows",
+    "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_attn_scores_batch", "sqap_prune_topk", "sqap_kept_rows",
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient",
@@ -56,6 +56,7 @@ def lib():
         L.sqap_version.restype = ctypes.c_char_p
         L.sqap_version.argtypes = []
         L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
+        L.sqap_attn_scores_batch.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_prune_topk.argtypes = [vp, i32, i32, i32, vp, vp]
         L.sqap_kept_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_prune_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -107,6 +108,13 @@ def sqap_attn_scores(q, k, vis_begin, n_vis, scores_out, stream=None):
     S, H, d = k.shape
     _check(lib().sqap_attn_scores(_ptr(q), _ptr(k), S, H, d, vis_begin, n_vis, _ptr(scores_out),
                                   _stream(stream)))
+
+
+def sqap_attn_scores_batch(q, k, vis_begin, n_vis, scores_out, stream=None):
+    """q [batch,H,d] fp16, k [batch,S,H,d] fp16 -> scores_out [batch,n_vis] fp32."""
+    batch, S, H, d = k.shape
+    _check(lib().sqap_attn_scores_batch(_ptr(q), _ptr(k), batch, S, H, d, vis_begin, n_vis, _ptr(scores_out),
+                                        _stream(stream)))
 
 
 def sqap_prune_topk(scores, keep_k, idx_out, stream=None):

@@ -38,23 +38,38 @@ const char *sqap_last_error(void) { return g_error; }
 
 const char *sqap_version(void) { return "sqap-gfx950 0.1"; }
 
+static sqap_status attn_scores_checked(const char *who, const sqap_f16 *q, const sqap_f16 *k, int32_t batch,
+                                       int32_t S, int32_t H, int32_t d, int32_t vis_begin, int32_t n_vis,
+                                       float *scores_out, void *stream)
+{
+    if (batch < 0) return fail(SQAP_EINVAL, "%s: batch %d < 0", who, batch);
+    if (S <= 0 || H <= 0 || d <= 0)
+        return fail(SQAP_EINVAL, "%s: S, H, d must be positive (%d, %d, %d)", who, S, H, d);
+    if (vis_begin < 0 || n_vis < 0 || (int64_t)vis_begin + n_vis > S)
+        return fail(SQAP_EINVAL, "%s: visual span [%d, %d+%d) outside [0, %d)", who, vis_begin, vis_begin, n_vis, S);
+    if (batch == 0) return SQAP_OK;
+    if (!q || !k) return fail(SQAP_EINVAL, "%s: null q or k", who);
+    if (n_vis == 0) return SQAP_OK;
+    if (!scores_out) return fail(SQAP_EINVAL, "%s: null scores_out", who);
+    if (d > 256 || (d & 1)) return fail(SQAP_EUNSUPPORTED, "%s: d = %d (even, <= 256)", who, d);
+    if (S > 16384) return fail(SQAP_EUNSUPPORTED, "%s: S = %d > 16384", who, S);
+    if (batch > 4096) return fail(SQAP_EUNSUPPORTED, "%s: batch = %d > 4096", who, batch);
+    return launch_attn_scores(reinterpret_cast<const __half *>(q), reinterpret_cast<const __half *>(k), batch, S, H,
+                              d, vis_begin, n_vis, scores_out, as_stream(stream));
+}
+
 sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
                              int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
                              void *stream)
 {
-    if (S <= 0 || H <= 0 || d <= 0)
-        return fail(SQAP_EINVAL, "sqap_attn_scores: S, H, d must be positive (%d, %d, %d)", S, H, d);
-    if (vis_begin < 0 || n_vis < 0 || (int64_t)vis_begin + n_vis > S)
-        return fail(SQAP_EINVAL, "sqap_attn_scores: visual span [%d, %d+%d) outside [0, %d)",
-                    vis_begin, vis_begin, n_vis, S);
-    if (!q || !k) return fail(SQAP_EINVAL, "sqap_attn_scores: null q or k");
-    if (n_vis == 0) return SQAP_OK;
-    if (!scores_out) return fail(SQAP_EINVAL, "sqap_attn_scores: null scores_out");
-    if (d > 256 || (d & 1)) return fail(SQAP_EUNSUPPORTED, "sqap_attn_scores: d = %d (even, <= 256)", d);
-    if (S > 16384) return fail(SQAP_EUNSUPPORTED, "sqap_attn_scores: S = %d > 16384", S);
-    return launch_attn_scores(reinterpret_cast<const __half *>(q),
-                              reinterpret_cast<const __half *>(k), S, H, d, vis_begin, n_vis,
-                              scores_out, as_stream(stream));
+    return attn_scores_checked("sqap_attn_scores", q, k, 1, S, H, d, vis_begin, n_vis, scores_out, stream);
+}
+
+sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S, int32_t H,
+                                   int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
+                                   void *stream)
+{
+    return attn_scores_checked("sqap_attn_scores_batch", q, k, batch, S, H, d, vis_begin, n_vis, scores_out, stream);
 }
 
 sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens,

@@ -76,7 +76,7 @@ static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream
     } while (0)
 
 // kernel launchers (defined in the .hip files); all validation is done by the caller
-sqap_status launch_attn_scores(const __half *q, const __half *k, int S, int H, int d,
+sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int S, int H, int d,
                                int vis_begin, int n_vis, float *scores, hipStream_t st);
 sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
                               hipStream_t st);

@@ -584,11 +584,136 @@ __global__ __launch_bounds__(64 * kScoreWaves) void attn_scores_kernel(
     for (int j = threadIdx.x; j < n_vis; j += blockDim.x) scores[j] = acc_lds[j] / (float)H;
 }
 
-sqap_status launch_attn_scores(const __half *q, const __half *k, int S, int H, int d,
+// Fast path of the retention score: one workgroup per head.  A group of d/8 lanes reads one
+// key row piece (16 bytes per lane: a coalesced run of 2d bytes), the logits of the head go to
+// LDS, the workgroup takes their maximum and the sum of exponentials, and writes the head's
+// softmax weights of the visual span to a device-resident scratch array.  The workgroup that
+// finishes last (a device counter tells) adds the heads in head order, so the result does not
+// depend on the order in which the workgroups ran.  The scratch array and the counter belong to
+// the device: calls that overlap on one device race.
+// A batch of observations runs as one launch (grid: heads x observations); each observation has
+// its own counter and its own piece of the scratch array.
+constexpr int kScoreMaxHeads = 128, kScoreMaxSpan = 4096, kScoreMaxSeq = 4096, kScoreMaxBatch = 1024;
+constexpr size_t kScoreScratchFloats = (size_t)kScoreMaxHeads * kScoreMaxSpan;
+__device__ float g_head_weights[kScoreScratchFloats];
+constexpr int kCounterStride = 64;                // one 256-byte line per counter: atomics on one line serialise
+__device__ unsigned int g_heads_done[kScoreMaxBatch * kCounterStride];
+
+__device__ __forceinline__ float block_reduce_256(float v, bool take_max, float *scratch4)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int o = 32; o > 0; o >>= 1) {
+        const float u = __shfl_xor(v, o);
+        v = take_max ? fmaxf(v, u) : v + u;
+    }
+    __syncthreads();                              // previous users of scratch4 are done
+    if (lane == 0) scratch4[wave] = v;
+    __syncthreads();
+    return take_max ? fmaxf(fmaxf(scratch4[0], scratch4[1]), fmaxf(scratch4[2], scratch4[3]))
+                    : (scratch4[0] + scratch4[1]) + (scratch4[2] + scratch4[3]);
+}
+
+__global__ __launch_bounds__(256) void attn_head_kernel(const __half *__restrict__ q, const __half *__restrict__ k,
+                                                        int S, int H, int d, int vis_begin, int n_vis,
+                                                        float *__restrict__ scores)
+{
+    __shared__ float logits[kScoreMaxSeq];
+    __shared__ float red[4];
+    __shared__ bool is_last;
+    const int t = threadIdx.x, h = blockIdx.x, b = blockIdx.y;
+    q += (size_t)b * H * d;
+    k += (size_t)b * S * H * d;
+    scores += (size_t)b * n_vis;
+    float *head_weights = g_head_weights + (size_t)b * H * n_vis;
+    const int lp = d >> 3;                        // lanes per key row: a power of two, 1 .. 32
+    const int sub = t & (lp - 1), grp = t / lp, groups = 256 / lp;
+    float qf[8];
+    {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(q + (size_t)h * d + sub * 8);
+        const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float2 f = __half22float2(h2[i]);
+            qf[2 * i] = f.x;
+            qf[2 * i + 1] = f.y;
+        }
+    }
+    const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+    constexpr int kRowsInFlight = 8;              // key rows a lane group loads before it reduces any
+    for (int s0 = 0; s0 < S; s0 += groups * kRowsInFlight) {
+        uint4 raw[kRowsInFlight];
+#pragma unroll
+        for (int r = 0; r < kRowsInFlight; ++r) {
+            const int s = s0 + r * groups + grp;
+            raw[r] = make_uint4(0u, 0u, 0u, 0u);
+            if (s < S) raw[r] = *reinterpret_cast<const uint4 *>(k + ((size_t)s * H + h) * d + sub * 8);
+        }
+#pragma unroll
+        for (int r = 0; r < kRowsInFlight; ++r) {
+            const int s = s0 + r * groups + grp;
+            const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw[r]);
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float2 f = __half22float2(h2[i]);
+                acc = fmaf(qf[2 * i], f.x, acc);
+                acc = fmaf(qf[2 * i + 1], f.y, acc);
+            }
+            for (int o = lp >> 1; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+            if (s < S && sub == 0) logits[s] = acc * inv_sqrt_d;
+        }
+    }
+    __syncthreads();
+    float m = -INFINITY;
+    for (int s = t; s < S; s += 256) m = fmaxf(m, logits[s]);
+    m = block_reduce_256(m, true, red);
+    float z = 0.f;
+    for (int s = t; s < S; s += 256) z += expf(logits[s] - m);
+    z = block_reduce_256(z, false, red);
+    // The weights go out as agent-scope stores (written through this XCD's L2, since the workgroup that
+    // adds the heads may sit behind another one); they are complete once the vector-memory counter
+    // drains, and only then does the workgroup count itself as done.  A full release fence here would
+    // write back the whole L2 once per workgroup.
+    for (int j = t; j < n_vis; j += 256)
+        __hip_atomic_store(&head_weights[(size_t)h * n_vis + j], expf(logits[vis_begin + j] - m) / z, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t == 0) {
+        const unsigned done = __hip_atomic_fetch_add(&g_heads_done[b * kCounterStride], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        is_last = done + 1 == (unsigned)H;
+        if (is_last)                              // ready for the next call
+            __hip_atomic_store(&g_heads_done[b * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (is_last) {
+        // agent-scope loads: they do not hit stale lines of an earlier call in this XCD's caches
+        for (int j = t; j < n_vis; j += 256) {
+            float a = 0.f;
+#pragma unroll 16
+            for (int hh = 0; hh < H; ++hh)
+                a += __hip_atomic_load(&head_weights[(size_t)hh * n_vis + j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            scores[j] = a / (float)H;
+        }
+    }
+}
+
+sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int S, int H, int d,
                                int vis_begin, int n_vis, float *scores, hipStream_t st)
 {
-    hipLaunchKernelGGL(attn_scores_kernel, dim3(1), dim3(64 * kScoreWaves), n_vis * sizeof(float), st,
-                       q, k, S, H, d, vis_begin, n_vis, scores);
+    const bool pow2 = (d & (d - 1)) == 0;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15u) == 0;
+    const bool fits = H <= kScoreMaxHeads && n_vis <= kScoreMaxSpan && S <= kScoreMaxSeq && batch <= kScoreMaxBatch &&
+                      (size_t)batch * H * n_vis <= kScoreScratchFloats;
+    if (pow2 && d >= 8 && d <= 256 && aligned && fits) {
+        hipLaunchKernelGGL(attn_head_kernel, dim3(H, batch), dim3(256), 0, st, q, k, S, H, d, vis_begin, n_vis, scores);
+    } else {
+        for (int b = 0; b < batch; ++b)
+            hipLaunchKernelGGL(attn_scores_kernel, dim3(1), dim3(64 * kScoreWaves), n_vis * sizeof(float), st,
+                               q + (size_t)b * H * d, k + (size_t)b * S * H * d, S, H, d, vis_begin, n_vis,
+                               scores + (size_t)b * n_vis);
+    }
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }

@@ -106,6 +106,11 @@ def test_attn_scores_validation():
     assert L.sqap_attn_scores(p, p, 10, 2, 8, 5, 6, p, None) == B.EINVAL
     assert L.sqap_attn_scores(p, p, 10, 2, 512, 0, 4, p, None) == B.EUNSUPPORTED
     assert L.sqap_attn_scores(p, p, 10, 2, 8, 0, 0, None, None) == B.OK
+    assert L.sqap_attn_scores_batch(p, p, -1, 10, 2, 8, 0, 4, p, None) == B.EINVAL
+    assert L.sqap_attn_scores_batch(None, None, 0, 10, 2, 8, 0, 4, None, None) == B.OK
+    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 8, 8, 4, p, None) == B.EINVAL
+    assert L.sqap_attn_scores_batch(p, p, 5000, 10, 2, 8, 0, 4, p, None) == B.EUNSUPPORTED
+    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 7, 0, 4, p, None) == B.EUNSUPPORTED
 
 
 def test_prune_select_validation():

@@ -349,13 +349,45 @@ def test_config0_end_to_end(G, oracle):
 def test_attn_scores(G, oracle):
     import torch
     from paper_2509_09090_amd import binding as B
-    for (S, H, d, v0, nv) in [(276, 32, 128, 0, 256), (37, 4, 16, 3, 20), (1000, 5, 64, 10, 990)]:
+    # the last three take the general kernel: head size not a power of two, a long sequence, many heads
+    for (S, H, d, v0, nv) in [(276, 32, 128, 0, 256), (37, 4, 16, 3, 20), (1000, 5, 64, 10, 990), (300, 128, 8, 1, 299),
+                              (4096, 2, 256, 0, 4096), (100, 3, 24, 5, 60), (5000, 2, 32, 100, 4000), (50, 130, 16, 0, 50)]:
         q, k = wl.query_and_keys(S, H, d, wl.rng_for(95, S, wl.T_Q))
+        qd, kd = G.to_dev(q), G.to_dev(k)
         out = torch.zeros(nv, dtype=torch.float32, device="cuda")
-        B.sqap_attn_scores(G.to_dev(q), G.to_dev(k), v0, nv, out)
+        B.sqap_attn_scores(qd, kd, v0, nv, out)
         torch.cuda.synchronize()
         ref = oracle.attn_scores(q, k, v0, nv)
-        assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7)
+        assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7), (S, H, d)
+        again = torch.zeros(nv, dtype=torch.float32, device="cuda")      # same bits on every call
+        B.sqap_attn_scores(qd, kd, v0, nv, again)
+        torch.cuda.synchronize()
+        assert torch.equal(out, again), (S, H, d)
+
+
+@pytest.mark.gpu
+def test_attn_scores_batch(G, oracle):
+    """One launch for a batch of observations gives each what the single call gives, and the oracle's values."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    # (batch, S, H, d, vis_begin, n_vis); the third does not fit the device scratch and takes the general kernel
+    for (nb, S, H, d, v0, nv) in [(16, 276, 32, 128, 0, 256), (3, 61, 5, 32, 7, 40), (5, 4096, 32, 16, 0, 4096)]:
+        qs, ks = [], []
+        for b in range(nb):
+            q, k = wl.query_and_keys(S, H, d, wl.rng_for(96, S, wl.T_Q, b))
+            qs.append(q)
+            ks.append(k)
+        qd, kd = G.to_dev(np.stack(qs)), G.to_dev(np.stack(ks))
+        out = torch.zeros(nb, nv, dtype=torch.float32, device="cuda")
+        B.sqap_attn_scores_batch(qd, kd, v0, nv, out)
+        torch.cuda.synchronize()
+        one = torch.zeros(nv, dtype=torch.float32, device="cuda")
+        for b in ([0, nb - 1] if S > 1000 else range(nb)):
+            ref = oracle.attn_scores(qs[b], ks[b], v0, nv)
+            assert np.allclose(out[b].cpu().numpy(), ref, rtol=2e-4, atol=1e-7), (nb, S, H, d, b)
+            B.sqap_attn_scores(qd[b], kd[b], v0, nv, one)
+            torch.cuda.synchronize()
+            assert np.allclose(out[b].cpu().numpy(), one.cpu().numpy(), rtol=1e-6, atol=1e-9), (nb, S, H, d, b)
 
 
 @pytest.mark.parametrize("M,N,K", [(600, 768, 1024),     # 3 x 3 tiles of 256 x 256 over 256 workgroups: every tile is shared
