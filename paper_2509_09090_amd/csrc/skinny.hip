@@ -172,6 +172,15 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
             v16i acc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0;
+            // this lane's 16 channel scales (4 runs of 4 halves), asked for before the weights are
+            // walked so that the epilogue does not wait for them; the scale array is padded to whole
+            // row groups and 8-byte aligned
+            uint2 swraw[4] = {};
+            if (active && ks == 0) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    swraw[q] = *reinterpret_cast<const uint2 *>(e.sw + rg * 32 + q * 8 + h * 4);
+            }
             if (active) {
             // The loop body is branch free: every step consumes ring slot d and refills it
             // with exactly one load.  The reduction axis is padded to whole rounds; a
@@ -232,12 +241,13 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
                 for (int q = 0; q < 4; ++q) {
                     const int n = rg * 32 + q * 8 + h * 4;
                     if (n < e.N) {
-                        union { __half hv[4]; uint2 u; } pk;
+                        union { __half hv[4]; uint2 u; } pk, swq;
+                        swq.u = swraw[q];
                         int v[4];
 #pragma unroll
                         for (int x = 0; x < 4; ++x) {
                             v[x] = acc[4 * q + x] >> 8;
-                            pk.hv[x] = dequant2(v[x], sxf, __half2float(e.sw[n + x]));   // scales are zero padded
+                            pk.hv[x] = dequant2(v[x], sxf, __half2float(swq.hv[x]));
                         }
                         __half *dst = e.Y + (size_t)r * e.ldy + n;
                         if (y_vec) {
