@@ -290,6 +290,21 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
 sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream);
 
 /*
+ * Self-test of the dispatch order the persistent GEMM kernels rely on.  They
+ * pass partial sums between workgroups b and b' of one launch with
+ * b % 8 == b' % 8 through ordinary stores, which requires both to run behind
+ * the same L2 (workgroup b on XCD b % 8, or a device with one L2).  The library
+ * checks this once per device, in the first sqap_weight_pack on it, and uses
+ * one-tile-per-workgroup kernels on a device where it does not hold.  This call
+ * repeats the probe and writes the XCC id of each of the 256 workgroups of a
+ * probe launch to xcc_of_block_out (HOST memory, 256 words); it synchronises
+ * the stream.  Expected: out[b] == out[b % 8] for every b.  EINVAL: null.
+ * Setting SQAP_DISABLE_PERSISTENT=1 in the environment selects the fallback
+ * kernels on any device (read at every sqap_w4a4_linear call).
+ */
+sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream);
+
+/*
  * Grouped small-M linears (autoregressive decode, M <= 8).  Decode streams
  * every weight once per step and a single linear moves only a few megabytes,
  * so launching linears one by one leaves the memory system idle between them.

@@ -20,7 +20,7 @@ EXPORTS = (
     "sqap_last_error", "sqap_version", "sqap_attn_scores", "sqap_attn_scores_batch", "sqap_prune_topk", "sqap_kept_rows",
     "sqap_gather_rows", "sqap_quantize_act", "sqap_quantize_weight", "sqap_weight_pack",
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
-    "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient",
+    "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded",
 )
@@ -77,6 +77,7 @@ def lib():
         L.sqap_group_run.argtypes = [vp, vp]
         L.sqap_group_free.argtypes = [vp]
         L.sqap_selftest_quotient.argtypes = [vp, vp]
+        L.sqap_selftest_dispatch.argtypes = [ctypes.POINTER(u32), vp]
         for name in EXPORTS:
             if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
@@ -218,6 +219,13 @@ def sqap_weight_pack(Wq, sw, stream=None):
 def sqap_selftest_quotient(counter, stream=None):
     """counter: zeroed int64 device tensor of one element; receives the number of mismatches."""
     _check(lib().sqap_selftest_quotient(_ptr(counter), _stream(stream)))
+
+
+def sqap_selftest_dispatch(stream=None):
+    """XCC id of each of the 256 workgroups of a probe launch (list of int)."""
+    table = (ctypes.c_uint32 * 256)()
+    _check(lib().sqap_selftest_dispatch(table, _stream(stream)))
+    return list(table)
 
 
 def sqap_workspace_bytes(M, N, K):

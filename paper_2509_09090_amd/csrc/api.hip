@@ -293,6 +293,14 @@ sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, i
         delete w;
         return st;
     }
+    // first weight on this device: find out whether the persistent GEMM kernels may be used on it
+    st = probe_dispatch(w->device, as_stream(stream), nullptr);
+    if (st != SQAP_OK) {
+        (void)hipFree(w->data);
+        (void)hipFree(w->scales);
+        delete w;
+        return st;
+    }
     *out = reinterpret_cast<sqap_weight *>(w);
     return SQAP_OK;
 }
@@ -319,6 +327,14 @@ sqap_status sqap_weight_info(const sqap_weight *w, int32_t *N, int32_t *K, size_
     if (K) *K = ww->K;
     if (device_bytes) *device_bytes = ww->bytes;
     return SQAP_OK;
+}
+
+sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream)
+{
+    if (!xcc_of_block_out) return fail(SQAP_EINVAL, "sqap_selftest_dispatch: null pointer");
+    int dev = 0;
+    SQAP_HIP_CHECK(hipGetDevice(&dev));
+    return probe_dispatch(dev, as_stream(stream), xcc_of_block_out);
 }
 
 sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream)

@@ -104,6 +104,9 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
                                hipStream_t st);
 
 sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t st);
+// Checks once per device how a launch's workgroups are dealt to the XCDs (see gemm.hip); table_out
+// (host, 256 words, nullable) receives the XCC id of every workgroup and forces a fresh probe.
+sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 
 }  // namespace sqap

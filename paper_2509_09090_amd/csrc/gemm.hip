@@ -11,6 +11,7 @@
 // |.| <= 256 * 64 * K < 2^31 for K <= 131071, and the epilogue shifts it back:
 // the integer result is exact.
 #include <atomic>
+#include <cstdlib>
 #include <random>
 
 #include "common.h"
@@ -789,6 +790,49 @@ static unsigned long long next_epoch()
     return salt + (++counter);
 }
 
+// The persistent kernels hand partial sums from workgroup b to a workgroup b' with b' % 8 == b % 8
+// through ordinary stores, which is valid only when the two sit behind one L2: the dispatcher has to
+// deal workgroup b of a launch to XCD b % 8 (or the device has a single L2).  The probe reads the
+// XCC_ID register in every workgroup of a launch shaped like the persistent ones; a device where the
+// rule does not hold gets the one-tile-per-workgroup kernels, which share nothing.
+__device__ unsigned int g_xcc_of_block[kMaxPersistentBlocks];
+
+__global__ __launch_bounds__(512) void xcc_probe_kernel()
+{
+    unsigned int x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(x));
+    if (threadIdx.x == 0) g_xcc_of_block[blockIdx.x] = x & 15u;
+}
+
+constexpr int kMaxDevices = 64;
+static std::atomic<int> g_dealing[kMaxDevices];      // 0 not probed, 1 the rule holds, 2 it does not
+
+sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(SQAP_EUNSUPPORTED, "device ordinal %d above %d", device, kMaxDevices - 1);
+    if (g_dealing[device].load() != 0 && !table_out) return SQAP_OK;
+    unsigned int host[kMaxPersistentBlocks];
+    hipLaunchKernelGGL(xcc_probe_kernel, dim3(kMaxPersistentBlocks), dim3(512), 0, st);
+    SQAP_HIP_CHECK(hipGetLastError());
+    SQAP_HIP_CHECK(hipStreamSynchronize(st));
+    SQAP_HIP_CHECK(hipMemcpyFromSymbol(host, HIP_SYMBOL(g_xcc_of_block), sizeof(host), 0, hipMemcpyDeviceToHost));
+    bool ok = true;
+    for (int b = 0; b < kMaxPersistentBlocks; ++b) ok = ok && host[b] == host[b % kXcds];
+    g_dealing[device].store(ok ? 1 : 2);
+    if (table_out)
+        for (int b = 0; b < kMaxPersistentBlocks; ++b) table_out[b] = host[b];
+    return SQAP_OK;
+}
+
+static bool persistent_allowed()
+{
+    // SQAP_DISABLE_PERSISTENT=1 in the environment selects the fallback kernels (read at every call)
+    const char *off = getenv("SQAP_DISABLE_PERSISTENT");
+    if (off && off[0] == '1') return false;
+    int dev = 0;
+    return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_dealing[dev].load() == 1;
+}
+
 static int persistent_blocks()
 {
     static int blocks = 0;
@@ -909,7 +953,7 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
     p.n_groups = w.n_groups;
     p.chunks = w.chunks;
     p.y_vec_ok = (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (ldy & 7) == 0;
-    if (w.K % kBK == 0) {
+    if (w.K % kBK == 0 && persistent_allowed()) {
         if (M >= kStreamKMinM) return launch_streamk<CfgBig, false>(p, workspace, st);
         // Narrow tiles.  With few tiles, each is shared by many workgroups (256 / tiles of them) and
         // the contributors finish it together; with many tiles a single finisher has only two or
@@ -922,7 +966,8 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
         if (mid) return joint ? launch_streamk<CfgMid, true>(p, workspace, st) : launch_streamk<CfgMid, false>(p, workspace, st);
         return joint ? launch_streamk<CfgLow, true>(p, workspace, st) : launch_streamk<CfgLow, false>(p, workspace, st);
     }
-    // K not a multiple of 128: one tile per workgroup, reduction axis guarded
+    // K not a multiple of 128 (or a device whose dispatch order the persistent kernels cannot rely on):
+    // one tile per workgroup, reduction axis guarded
     if (M <= CfgLow::BM) return launch_tiled<CfgLow>(p, st);
     if (M <= CfgMid::BM) return launch_tiled<CfgMid>(p, st);
     return launch_tiled<CfgBig>(p, st);

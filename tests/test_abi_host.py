@@ -113,6 +113,10 @@ def test_attn_scores_validation():
     assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 7, 0, 4, p, None) == B.EUNSUPPORTED
 
 
+def test_selftest_dispatch_validation():
+    assert B.lib().sqap_selftest_dispatch(None, None) == B.EINVAL
+
+
 def test_prune_select_validation():
     L = B.lib()
     p = ctypes.c_void_p(4096)

@@ -312,6 +312,29 @@ def test_linear_random_codes(G, oracle, M, N, K):
     assert G.assert_fp16_close(Y, Yo) == 0
 
 
+def test_dispatch_order_selftest(G):
+    """Workgroup b of a launch runs on XCD b % 8: what the persistent GEMM kernels rely on."""
+    from paper_2509_09090_amd import binding as B
+    table = B.sqap_selftest_dispatch()
+    assert len(table) == 256 and all(table[b] == table[b % 8] for b in range(256)), table
+
+
+@pytest.mark.parametrize("M,N,K", [(600, 768, 1024), (148, 1024, 2048), (84, 512, 1024)])
+def test_linear_fallback_kernels(G, oracle, M, N, K, monkeypatch):
+    """With the persistent kernels switched off the one-tile-per-workgroup kernels give the same bits."""
+    rng = np.random.default_rng(M + N + K)
+    Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
+    sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+    sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+    Y1, acc1 = G.gpu_linear(Xq, sx, Wq, sw)
+    monkeypatch.setenv("SQAP_DISABLE_PERSISTENT", "1")
+    Y2, acc2 = G.gpu_linear(Xq, sx, Wq, sw)
+    monkeypatch.delenv("SQAP_DISABLE_PERSISTENT")
+    _, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    assert np.array_equal(acc1, acco) and np.array_equal(acc2, acco)
+    assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
+
+
 def test_linear_extreme_codes(G, oracle):
     """All codes -8 on both sides: the largest accumulator the format allows (64 K)."""
     M, N, K = 40, 64, 11008
