@@ -281,3 +281,64 @@ def attn_scores(q, k, vis_begin, n_vis):
     if rc != 0:
         raise ValueError("oracle_attn_scores: status %d" % rc)
     return out
+
+
+def rmsnorm_rows(X, gamma, eps, rows=None, delta=None):
+    """RMSNorm (with an optional residual update first): returns (x' fp16 [M,K], y fp16 [M,K])."""
+    X = _c(X, np.float16)
+    gamma = _c(gamma, np.float16)
+    K = X.shape[1]
+    rows_c = None if rows is None else _c(rows, np.int32)
+    M = X.shape[0] if rows is None else len(rows_c)
+    delta_c = None if delta is None else _c(delta, np.float16)
+    xs = np.empty((M, K), dtype=np.float16)
+    y = np.empty((M, K), dtype=np.float16)
+    rc = lib().oracle_rmsnorm_rows(_p(X), ctypes.c_int64(X.strides[0] // 2), _p(rows_c), M, K, _p(delta_c),
+                                   _p(gamma), ctypes.c_float(eps), _p(xs), _p(y))
+    if rc:
+        raise ValueError("oracle_rmsnorm_rows: %d" % rc)
+    return xs, y
+
+
+def swiglu(G, U):
+    """h = fp16(silu(g) * u), elementwise over [M, F] halves."""
+    G = _c(G, np.float16)
+    U = _c(U, np.float16)
+    M, F = G.shape
+    out = np.empty((M, F), dtype=np.float16)
+    rc = lib().oracle_swiglu(_p(G), ctypes.c_int64(F), _p(U), ctypes.c_int64(F), M, F, _p(out))
+    if rc:
+        raise ValueError("oracle_swiglu: %d" % rc)
+    return out
+
+
+def rope(X, pos, base=10000.0):
+    """Rotary embedding of [S, H, d] halves at integer positions pos[S]; returns a new array."""
+    out = _c(X, np.float16).copy()
+    S, H, d = out.shape
+    pos = _c(pos, np.int32)
+    rc = lib().oracle_rope(_p(out), _p(pos), S, H, d, ctypes.c_double(base))
+    if rc:
+        raise ValueError("oracle_rope: %d" % rc)
+    return out
+
+
+def attention(Q, K, V):
+    """Causal softmax attention over [S, H, d] halves -> [S, H, d] halves."""
+    Q, K, V = _c(Q, np.float16), _c(K, np.float16), _c(V, np.float16)
+    S, H, d = Q.shape
+    out = np.empty((S, H, d), dtype=np.float16)
+    rc = lib().oracle_attention(_p(Q), _p(K), _p(V), S, H, d, _p(out))
+    if rc:
+        raise ValueError("oracle_attention: %d" % rc)
+    return out
+
+
+def residual_add(X, delta):
+    out = _c(X, np.float16).copy()
+    delta = _c(delta, np.float16)
+    M, K = out.shape
+    rc = lib().oracle_residual_add(_p(out), _p(delta), M, K)
+    if rc:
+        raise ValueError("oracle_residual_add: %d" % rc)
+    return out

@@ -24,6 +24,12 @@
  * hand-worked sequence, the max-min property step by step, a running-minimum
  * formulation), but the set it starts from, the metric and the tie-break are
  * readings the paper does not fix: "parity unpinned" for those choices.
+ * The decoder glue at the end of the file (RMSNorm, rotary embedding, causal
+ * attention, SwiGLU, residual add) is not described by the paper at all; it
+ * follows the published Llama-2 architecture and is pinned by closed forms
+ * (constant rows, zero queries, position 0), exact rational arithmetic for the
+ * sum of squares, 50-digit decimal evaluation of silu, complex multiplication
+ * for the rotation and a matrix formulation of attention with library softmax.
  */
 #include <limits.h>
 #include <math.h>
@@ -650,5 +656,164 @@ int oracle_attn_scores(const uint16_t *q, const uint16_t *k, int S, int H, int d
     for (int j = 0; j < n_vis; ++j) scores_out[j] = (float)(acc[j] / (double)H);
     free(p);
     free(acc);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Decoder glue between the linears                                    */
+/* ------------------------------------------------------------------ */
+/*
+ * The paper runs its W4A4 linears inside a Llama-2-7B decoder (Implementation
+ * Details; Section 3.3 takes Q = W_q^T X and K = W_k^T X from it) and does not
+ * restate that architecture.  What follows is the published one, written out:
+ * pre-normalisation by RMSNorm (Zhang & Sennrich 2019), rotary position
+ * embedding in the half-split pairing (Su et al. 2021 as used by Llama),
+ * causal softmax attention, and the SwiGLU feed-forward (Shazeer 2020).  Each
+ * result that a later quantizer consumes is rounded to binary16 here, so that
+ * the fused device kernels (norm + quantize, SwiGLU + quantize) are the
+ * composition of one of these functions with oracle_quantize_rows.
+ */
+
+/*
+ * RMSNorm of rows of halves, with an optional residual update first:
+ *   x'_k = binary16(float(x_k) + float(delta_k))          (delta != NULL)
+ *   S    = sum_k x'_k^2                                    exactly
+ *   r    = (float)(1 / sqrt(S / K + eps))                  binary64, one rounding
+ *   y_k  = binary16((float(x'_k) * r) * float(gamma_k))    two binary32 products
+ * S is exact: a half is an integer m (|m| < 2^11) times 2^e with e >= -24, so
+ * x^2 * 2^48 is an integer below 2^80 and the row sum fits 128 bits; it is
+ * rounded to binary64 once.  Source row rows[i] (or i); delta, xsum_out and y_out
+ * are dense [M, K] indexed by the output row.  xsum_out (nullable) receives x'.
+ */
+int oracle_rmsnorm_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, int M, int K,
+                        const uint16_t *delta, const uint16_t *gamma, float eps,
+                        uint16_t *xsum_out, uint16_t *y_out)
+{
+    if (M < 0 || K <= 0 || !(eps >= 0.0f)) return -1;
+    for (int i = 0; i < M; ++i) {
+        size_t src = rows ? (size_t)rows[i] : (size_t)i;
+        unsigned __int128 S = 0;
+        for (int k = 0; k < K; ++k) {
+            uint16_t h = X[src * ldx + k];
+            if (delta) {
+                float s = oracle_f16_to_f32(h) + oracle_f16_to_f32(delta[(size_t)i * K + k]);
+                h = oracle_f32_to_f16(s);
+            }
+            if (xsum_out) xsum_out[(size_t)i * K + k] = h;
+            y_out[(size_t)i * K + k] = h;                    /* parked: x' */
+            uint32_t ex = (h >> 10) & 0x1fu, man = h & 0x3ffu;
+            if (ex == 0x1fu) return -3;                       /* infinity or NaN in the row */
+            uint32_t m = ex ? man + 1024u : man;
+            int e = ex ? (int)ex - 25 : -24;                  /* |x| = m * 2^e */
+            S += (unsigned __int128)((uint64_t)m * m) << (2 * e + 48);
+        }
+        double Sd = ldexp((double)S, -48);                    /* one rounding to nearest even */
+        float r = (float)(1.0 / sqrt(Sd / (double)K + (double)eps));
+        for (int k = 0; k < K; ++k) {
+            float xv = oracle_f16_to_f32(y_out[(size_t)i * K + k]);
+            float t = xv * r;
+            float y = t * oracle_f16_to_f32(gamma[k]);
+            y_out[(size_t)i * K + k] = oracle_f32_to_f16(y);
+        }
+    }
+    return 0;
+}
+
+/*
+ * SwiGLU gate: h = binary16(silu(g) * float(u)),
+ *   silu(g) = (float)(g / (1 + exp(-g)))   evaluated in binary64, one rounding,
+ * then one binary32 product and one rounding to half.  G, U: [M, F] halves
+ * with row pitches ldg, ldu; H_out dense [M, F].
+ */
+int oracle_swiglu(const uint16_t *G, int64_t ldg, const uint16_t *U, int64_t ldu, int M, int F,
+                  uint16_t *H_out)
+{
+    if (M < 0 || F < 0) return -1;
+    for (int i = 0; i < M; ++i)
+        for (int k = 0; k < F; ++k) {
+            double g = (double)oracle_f16_to_f32(G[(size_t)i * ldg + k]);
+            float s = (float)(g / (1.0 + exp(-g)));
+            float h = s * oracle_f16_to_f32(U[(size_t)i * ldu + k]);
+            H_out[(size_t)i * F + k] = oracle_f32_to_f16(h);
+        }
+    return 0;
+}
+
+/*
+ * Rotary position embedding, half-split pairing: for a head vector v of even
+ * size d at position p and i < d/2, with angle a = p * base^(-2i/d),
+ *   v'_i       = v_i cos a - v_{i+d/2} sin a
+ *   v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a
+ * in binary64, rounded to binary16.  X: [S, H, d] halves, in place.
+ */
+int oracle_rope(uint16_t *X, const int32_t *pos, int S, int H, int d, double base)
+{
+    if (S < 0 || H <= 0 || d <= 0 || (d & 1)) return -1;
+    for (int s = 0; s < S; ++s)
+        for (int h = 0; h < H; ++h) {
+            uint16_t *v = X + ((size_t)s * H + h) * d;
+            for (int i = 0; i < d / 2; ++i) {
+                double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+                double lo = (double)oracle_f16_to_f32(v[i]);
+                double hi = (double)oracle_f16_to_f32(v[i + d / 2]);
+                v[i] = oracle_f32_to_f16((float)(lo * cos(a) - hi * sin(a)));
+                v[i + d / 2] = oracle_f32_to_f16((float)(hi * cos(a) + lo * sin(a)));
+            }
+        }
+    return 0;
+}
+
+/*
+ * Causal softmax attention, one head at a time, binary64 throughout:
+ *   l[s,t] = (q[s,h,:] . k[t,h,:]) / sqrt(d)   for t <= s  (keys after the query are masked)
+ *   p[s,:] = softmax_t(l[s,:]),   o[s,h,:] = sum_t p[s,t] v[t,h,:]  -> binary16.
+ * Q, K, V, O: [S, H, d] halves.  Queries and keys are taken as given (rotate
+ * them with oracle_rope first).
+ */
+int oracle_attention(const uint16_t *Q, const uint16_t *Kc, const uint16_t *V, int S, int H, int d,
+                     uint16_t *O)
+{
+    if (S < 0 || H <= 0 || d <= 0) return -1;
+    double *p = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1));
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!p || !o) {
+        free(p);
+        free(o);
+        return -4;
+    }
+    for (int h = 0; h < H; ++h)
+        for (int s = 0; s < S; ++s) {
+            double lmax = -INFINITY;
+            for (int t = 0; t <= s; ++t) {
+                double dot = 0.0;
+                for (int i = 0; i < d; ++i)
+                    dot += (double)oracle_f16_to_f32(Q[((size_t)s * H + h) * d + i]) *
+                           (double)oracle_f16_to_f32(Kc[((size_t)t * H + h) * d + i]);
+                p[t] = dot / sqrt((double)d);
+                if (p[t] > lmax) lmax = p[t];
+            }
+            double z = 0.0;
+            for (int t = 0; t <= s; ++t) {
+                p[t] = exp(p[t] - lmax);
+                z += p[t];
+            }
+            for (int i = 0; i < d; ++i) o[i] = 0.0;
+            for (int t = 0; t <= s; ++t)
+                for (int i = 0; i < d; ++i)
+                    o[i] += (p[t] / z) * (double)oracle_f16_to_f32(V[((size_t)t * H + h) * d + i]);
+            for (int i = 0; i < d; ++i)
+                O[((size_t)s * H + h) * d + i] = oracle_f32_to_f16((float)o[i]);
+        }
+    free(p);
+    free(o);
+    return 0;
+}
+
+/* Residual update of the hidden state: x_k <- binary16(float(x_k) + float(delta_k)), [M, K] dense. */
+int oracle_residual_add(uint16_t *X, const uint16_t *delta, int M, int K)
+{
+    if (M < 0 || K < 0) return -1;
+    for (size_t j = 0; j < (size_t)M * (size_t)K; ++j)
+        X[j] = oracle_f32_to_f16(oracle_f16_to_f32(X[j]) + oracle_f16_to_f32(delta[j]));
     return 0;
 }

@@ -694,3 +694,164 @@ def test_tiny_linear_by_python_loops(oracle):
         assert acc[m, n] == s
         approx = s * float(sx[m]) * float(sw[n])
         assert abs(float(Y[m, n]) - approx) <= 1e-3 * abs(approx) + 1e-7
+
+
+# ------------------------------------------------------------------ decoder glue
+def _exact_inv_rms(row_f16, eps):
+    """1/sqrt(mean square + eps) from exact rational arithmetic on the half values."""
+    from fractions import Fraction
+    S = sum(Fraction(float(v)) ** 2 for v in row_f16)          # a half converts to Fraction exactly
+    Sd = float(S)                                              # correctly rounded to binary64
+    return np.float32(1.0 / np.sqrt(Sd / len(row_f16) + float(np.float32(eps))))
+
+
+def test_rmsnorm_constant_row_and_unit_rms(oracle):
+    K = 96
+    for c in (0.5, -3.0, 100.0, 6.1e-5):
+        X = np.full((1, K), c, dtype=np.float16)
+        _, y = oracle.rmsnorm_rows(X, np.ones(K, np.float16), 0.0)
+        assert np.all(y == np.float16(np.sign(c))), c              # x / |x|
+    rng = np.random.default_rng(5)
+    X = (rng.standard_normal((7, 512)) * 3).astype(np.float16)
+    _, y = oracle.rmsnorm_rows(X, np.ones(512, np.float16), 0.0)
+    rms = np.sqrt((y.astype(np.float64) ** 2).mean(axis=1))
+    assert np.all(np.abs(rms - 1.0) < 1e-3)                        # only the rounding to half is left
+    gamma = (1 + 0.2 * rng.standard_normal(512)).astype(np.float16)
+    _, yg = oracle.rmsnorm_rows(X, gamma, 1e-5)
+    x = X.astype(np.float64)
+    ref = x / np.sqrt((x * x).mean(axis=1, keepdims=True) + 1e-5) * gamma.astype(np.float64)
+    assert np.all(np.abs(yg.astype(np.float64) - ref) <= 2.0 ** -11 * np.abs(ref) + 1e-7 + 2e-7 * np.abs(ref))
+
+
+def test_rmsnorm_power_of_two_scaling_changes_nothing(oracle):
+    rng = np.random.default_rng(6)
+    X = rng.standard_normal((5, 200)).astype(np.float16)
+    gamma = (1 + 0.1 * rng.standard_normal(200)).astype(np.float16)
+    _, y0 = oracle.rmsnorm_rows(X, gamma, 0.0)
+    for j in (-3, 2, 5):
+        Xs = (X.astype(np.float32) * np.float32(2.0 ** j)).astype(np.float16)
+        assert np.array_equal(Xs.astype(np.float32), X.astype(np.float32) * np.float32(2.0 ** j))  # exact scaling
+        _, y = oracle.rmsnorm_rows(Xs, gamma, 0.0)
+        assert np.array_equal(y.view(np.uint16), y0.view(np.uint16)), j
+
+
+def test_rmsnorm_sum_of_squares_is_exact(oracle):
+    """Rows whose squares span 80 binary orders: any floating-point running sum loses the small terms."""
+    K = 4096
+    rows = []
+    r = np.full(K, 2.0 ** -24, dtype=np.float16)               # smallest subnormal everywhere ...
+    r[7] = np.float16(65504.0)                                 # ... and the largest half once
+    rows.append(r)
+    r = np.full(K, 2.0 ** -14, dtype=np.float16)
+    r[::5] = np.float16(1.0009765625)
+    rows.append(r)
+    rng = np.random.default_rng(7)
+    r = (rng.standard_normal(K) * np.exp(rng.uniform(-15, 8, K))).astype(np.float16)
+    rows.append(np.clip(r, -60000, 60000).astype(np.float16))
+    X = np.stack(rows)
+    gamma = np.ones(K, np.float16)
+    for eps in (0.0, 1e-6, 1e-12):
+        _, y = oracle.rmsnorm_rows(X, gamma, eps)
+        for i in range(X.shape[0]):
+            inv = _exact_inv_rms(X[i], eps)
+            want = (X[i].astype(np.float32) * inv).astype(np.float16)     # gamma = 1: second product is exact
+            assert np.array_equal(y[i].view(np.uint16), want.view(np.uint16)), (i, eps)
+    # the tiny terms matter: with eps = 0 the row of 2^-24 alone normalises to 1
+    _, y = oracle.rmsnorm_rows(np.full((1, K), 2.0 ** -24, np.float16), gamma, 0.0)
+    assert np.all(y == np.float16(1.0))
+
+
+def test_rmsnorm_gather_and_residual_update(oracle):
+    rng = np.random.default_rng(8)
+    X = rng.standard_normal((9, 64)).astype(np.float16)
+    D = rng.standard_normal((4, 64)).astype(np.float16)
+    gamma = (1 + 0.1 * rng.standard_normal(64)).astype(np.float16)
+    rows = np.array([8, 0, 3, 3], np.int32)
+    xs, y = oracle.rmsnorm_rows(X, gamma, 1e-5, rows=rows, delta=D)
+    want_x = (X[rows].astype(np.float32) + D.astype(np.float32)).astype(np.float16)    # numpy's own conversions
+    assert np.array_equal(xs.view(np.uint16), want_x.view(np.uint16))
+    assert np.array_equal(oracle.residual_add(X[rows], D).view(np.uint16), want_x.view(np.uint16))
+    _, y2 = oracle.rmsnorm_rows(want_x, gamma, 1e-5)
+    assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))
+    with pytest.raises(ValueError):
+        oracle.rmsnorm_rows(np.array([[np.inf, 1.0]], np.float16), np.ones(2, np.float16), 0.0)
+
+
+def test_swiglu_against_high_precision_and_identities(oracle):
+    import decimal
+    decimal.getcontext().prec = 50
+    gs = np.array([0.0, 1.0, -1.0, 0.5, 3.140625, -2.71875, 8.0, -8.0, 11.0, -17.0, 6.1e-5, -6.1e-5, 60000.0, -60000.0,
+                   30.0, -30.0], dtype=np.float16)
+    one = np.ones_like(gs)
+    h = oracle.swiglu(gs[None, :], one[None, :])[0]
+    for g, got in zip(gs, h):
+        gd = decimal.Decimal(float(g))
+        true = gd / (1 + (-gd).exp())
+        want = np.float16(np.float32(float(true)))               # silu to float, product with 1, to half
+        assert got.view(np.uint16) == want.view(np.uint16) or abs(float(got) - float(true)) <= 2.0 ** -11 * abs(float(true)) + 2.0 ** -25, g
+    assert h[0] == 0 and float(h[12]) == 60000.0 and float(h[13]) == 0.0       # silu(0) = 0, silu(+big) = big, silu(-big) = -0
+    rng = np.random.default_rng(9)
+    G = (rng.standard_normal((3, 500)) * 4).astype(np.float16)
+    U = (rng.standard_normal((3, 500)) * 2).astype(np.float16)
+    H = oracle.swiglu(G, U).astype(np.float64)
+    ref = scipy.special.expit(G.astype(np.float64)) * G.astype(np.float64) * U.astype(np.float64)   # library logistic
+    assert np.all(np.abs(H - ref) <= 2.0 ** -11 * np.abs(ref) + 1e-7 + 3e-7 * np.abs(ref))
+    # silu(g) - silu(-g) = g: the u factor and the sign of the exponent are where a slip would show
+    plus = oracle.swiglu(G, np.ones_like(G)).astype(np.float64)
+    minus = oracle.swiglu(-G, np.ones_like(G)).astype(np.float64)
+    assert np.all(np.abs(plus - minus - G.astype(np.float64)) <= 2.0 ** -9 * np.maximum(np.abs(G.astype(np.float64)), 1e-3))
+    # operands are not swapped: silu acts on the first argument only
+    assert not np.array_equal(oracle.swiglu(G, U), oracle.swiglu(U, G))
+    h1, h2 = oracle.swiglu(G, U).astype(np.float32), oracle.swiglu(G, 2 * U).astype(np.float32)
+    normal = np.abs(h1) >= 2.0 ** -13                            # doubling is exact away from the subnormal halves
+    assert np.array_equal(h2[normal], 2 * h1[normal])
+
+
+def test_rope_is_a_rotation_by_position_times_frequency(oracle):
+    rng = np.random.default_rng(10)
+    S, H, d, base = 11, 3, 16, 10000.0
+    X = rng.standard_normal((S, H, d)).astype(np.float16)
+    pos = np.array([0, 1, 2, 3, 5, 8, 13, 21, 34, 147, 275], np.int32)
+    Y = oracle.rope(X, pos, base).astype(np.float64)
+    assert np.array_equal(Y[0], X[0].astype(np.float64))                       # position 0: identity
+    z = X[..., :d // 2].astype(np.float64) + 1j * X[..., d // 2:].astype(np.float64)
+    freq = base ** (-np.arange(d // 2) * 2.0 / d)
+    zr = z * np.exp(1j * pos[:, None, None] * freq[None, None, :])             # complex multiplication
+    want = np.concatenate([zr.real, zr.imag], axis=-1)
+    assert np.all(np.abs(Y - want) <= 2.0 ** -11 * np.abs(want) + 1e-6)
+    # the defining property: rotated dot products depend on the position difference only
+    q = rng.standard_normal((1, 1, d)).astype(np.float16)
+    k = rng.standard_normal((1, 1, d)).astype(np.float16)
+    dots = []
+    for (m, n) in ((3, 1), (10, 8), (102, 100)):
+        qm = oracle.rope(q, np.array([m], np.int32), base).astype(np.float64).ravel()
+        kn = oracle.rope(k, np.array([n], np.int32), base).astype(np.float64).ravel()
+        dots.append(qm @ kn)
+    assert np.ptp(dots) < 2e-2 * max(1.0, abs(dots[0]))
+
+
+def test_attention_closed_forms_and_matrix_form(oracle):
+    rng = np.random.default_rng(11)
+    S, H, d = 13, 2, 8
+    V = rng.standard_normal((S, H, d)).astype(np.float16)
+    K = rng.standard_normal((S, H, d)).astype(np.float16)
+    # zero queries: uniform weights over the keys up to and including the query's own position
+    O = oracle.attention(np.zeros((S, H, d), np.float16), K, V).astype(np.float64)
+    run = np.cumsum(V.astype(np.float64), axis=0) / np.arange(1, S + 1)[:, None, None]
+    assert np.all(np.abs(O - run) <= 2.0 ** -11 * np.abs(run) + 1e-7)
+    assert np.array_equal(O[0], V[0].astype(np.float64))                       # a single key: its value
+    # a query that singles out one key returns that key's value
+    Kb = np.zeros((S, H, d), np.float16)
+    Kb[:, :, 0] = np.arange(S)[:, None]                                        # key t has first coordinate t
+    Qb = np.zeros((S, H, d), np.float16)
+    Qb[:, :, 0] = 200.0                                                        # prefers the largest visible t = s
+    O = oracle.attention(Qb, Kb, V)
+    assert np.array_equal(O.view(np.uint16), V.view(np.uint16))
+    # matrix formulation with library routines
+    Q = rng.standard_normal((S, H, d)).astype(np.float16)
+    L = np.einsum("shi,thi->hst", Q.astype(np.float64), K.astype(np.float64)) / np.sqrt(d)
+    L = np.where(np.tril(np.ones((S, S), bool))[None], L, -np.inf)
+    P = scipy.special.softmax(L, axis=-1)
+    want = np.einsum("hst,thi->shi", P, V.astype(np.float64))
+    got = oracle.attention(Q, K, V).astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2.0 ** -11 * np.abs(want) + 1e-7)
