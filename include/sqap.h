@@ -279,6 +279,68 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
                              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Decoder glue between the linears.  The paper runs its W4A4 linears inside a
+ * Llama-2-7B decoder (Implementation Details; Section 3.3 takes Q and K from
+ * it) and does not restate that architecture; the calls below follow the
+ * published one: RMSNorm in front of each group of linears, rotary position
+ * embedding, causal softmax attention, SwiGLU feed-forward, residual adds.
+ * Every result that a quantizer consumes is rounded to binary16 first, so each
+ * fused call equals the unfused sequence bit for bit.
+ *
+ * sqap_rmsnorm_quantize_act: for output row i taken from X[rows[i], :] (or
+ * X[i, :] when rows is NULL):
+ *   x' = binary16(x + delta[i, :])      when delta is given ([M, K] dense);
+ *                                        xsum_out[i, :] = x' when asked for
+ *   S  = sum_k x'_k^2, exact (128-bit integer arithmetic on the half values)
+ *   r  = (float)(1 / sqrt(S / K + eps)) in binary64, S rounded to binary64 once
+ *   y  = binary16((float(x') * r) * float(gamma))     two binary32 products
+ * y_out[i, :] = y when asked for; then, when Xq is given, y is quantized as by
+ * sqap_quantize_act (col_scales NULL: one scale per token, written to sx) or as
+ * by sqap_quantize_act_channelwise (col_scales given).  flags as there.  Rows
+ * must be finite.  delta, xsum_out, y_out: [M, K] dense halves, 16-byte
+ * aligned; gamma: [K].  EINVAL: null X/gamma, neither Xq nor y_out, eps < 0.
+ *
+ * sqap_swiglu_quantize_act: h = binary16(silu(g) * float(u)) elementwise over
+ * G, U [M, F] (pitches ldg, ldu), silu(g) = (float)(g / (1 + exp(-g)))
+ * evaluated in binary64; h_out[i, :] = h when asked for; then quantized as
+ * above (no rotation).
+ */
+sqap_status sqap_rmsnorm_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
+                                      int32_t K, const sqap_f16 *delta, const sqap_f16 *gamma, float eps,
+                                      uint32_t flags, const sqap_f16 *col_scales, sqap_f16 *xsum_out,
+                                      sqap_f16 *y_out, uint8_t *Xq, sqap_f16 *sx, void *stream);
+sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_f16 *U, int64_t ldu,
+                                     int32_t M, int32_t F, const sqap_f16 *col_scales, sqap_f16 *h_out,
+                                     uint8_t *Xq, sqap_f16 *sx, void *stream);
+
+/*
+ * Rotary position embedding, in place, half-split pairing: for token s, head h
+ * and i < d/2, with a = pos[s] * base^(-2i/d),
+ *   v'_i = v_i cos a - v_{i+d/2} sin a,   v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a,
+ * evaluated in binary64 and rounded to half.  X: [S, H*d] with row pitch ld
+ * (elements), so a slice of a fused q/k/v output can be rotated where it lies.
+ * pos: [S] int32 device.  EINVAL: null pointer, d odd, ld < H*d, base <= 0.
+ *
+ * sqap_attention: causal softmax attention.  Query i (of Sq) sits at position
+ * Sk - Sq + i of the key sequence and sees keys 0 .. Sk - Sq + i:
+ *   o[i,h,:] = sum_t softmax_t((q[i,h,:] . k[t,h,:]) / sqrt(d)) v[t,h,:]
+ * in binary32 (online softmax over tiles of 64 keys), rounded to half.
+ * Q [Sq, H*d], K, V [Sk, H*d], O [Sq, H*d] with row pitches in elements.
+ * EINVAL: null pointer, Sk < Sq, pitch < H*d.  EUNSUPPORTED: d not in
+ * {16, 32, 64, 128}, operands or pitches not 16-byte aligned.
+ *
+ * sqap_residual_add: X[i, :] <- binary16(float(X[i, :]) + float(delta[i, :])),
+ * K a multiple of 8, 16-byte aligned rows.
+ */
+sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d,
+                      double base, void *stream);
+sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk,
+                           const sqap_f16 *V, int64_t ldv, int32_t Sq, int32_t Sk, int32_t H, int32_t d,
+                           sqap_f16 *O, int64_t ldo, void *stream);
+sqap_status sqap_residual_add(sqap_f16 *X, int64_t ldx, const sqap_f16 *delta, int64_t ldd, int32_t M,
+                              int32_t K, void *stream);
+
+/*
  * Self-test of the quantizer's arithmetic.  The quantizer divides every element
  * of a row by the same scale; it does so with a reciprocal and two fused
  * corrections that give the correctly rounded binary32 quotient.  This call

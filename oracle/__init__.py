@@ -324,11 +324,12 @@ def rope(X, pos, base=10000.0):
 
 
 def attention(Q, K, V):
-    """Causal softmax attention over [S, H, d] halves -> [S, H, d] halves."""
+    """Causal softmax attention: Q [Sq, H, d] (the last Sq positions), K, V [Sk, H, d] -> [Sq, H, d] halves."""
     Q, K, V = _c(Q, np.float16), _c(K, np.float16), _c(V, np.float16)
-    S, H, d = Q.shape
-    out = np.empty((S, H, d), dtype=np.float16)
-    rc = lib().oracle_attention(_p(Q), _p(K), _p(V), S, H, d, _p(out))
+    Sq, H, d = Q.shape
+    Sk = K.shape[0]
+    out = np.empty((Sq, H, d), dtype=np.float16)
+    rc = lib().oracle_attention(_p(Q), _p(K), _p(V), Sq, Sk, H, d, _p(out))
     if rc:
         raise ValueError("oracle_attention: %d" % rc)
     return out

@@ -764,17 +764,19 @@ int oracle_rope(uint16_t *X, const int32_t *pos, int S, int H, int d, double bas
 }
 
 /*
- * Causal softmax attention, one head at a time, binary64 throughout:
- *   l[s,t] = (q[s,h,:] . k[t,h,:]) / sqrt(d)   for t <= s  (keys after the query are masked)
- *   p[s,:] = softmax_t(l[s,:]),   o[s,h,:] = sum_t p[s,t] v[t,h,:]  -> binary16.
- * Q, K, V, O: [S, H, d] halves.  Queries and keys are taken as given (rotate
- * them with oracle_rope first).
+ * Causal softmax attention, one head at a time, binary64 throughout.  The Sq
+ * queries are the last Sq positions of a sequence of Sk keys: query s sits at
+ * position Sk - Sq + s and sees keys t <= Sk - Sq + s.
+ *   l[s,t] = (q[s,h,:] . k[t,h,:]) / sqrt(d),   p[s,:] = softmax_t(l[s,:]),
+ *   o[s,h,:] = sum_t p[s,t] v[t,h,:]  -> binary16.
+ * Q, O: [Sq, H, d] halves; K, V: [Sk, H, d].  Queries and keys are taken as
+ * given (rotate them with oracle_rope first).
  */
-int oracle_attention(const uint16_t *Q, const uint16_t *Kc, const uint16_t *V, int S, int H, int d,
-                     uint16_t *O)
+int oracle_attention(const uint16_t *Q, const uint16_t *Kc, const uint16_t *V, int Sq, int Sk, int H,
+                     int d, uint16_t *O)
 {
-    if (S < 0 || H <= 0 || d <= 0) return -1;
-    double *p = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1));
+    if (Sq < 0 || Sk < Sq || H <= 0 || d <= 0) return -1;
+    double *p = (double *)malloc(sizeof(double) * (size_t)(Sk > 0 ? Sk : 1));
     double *o = (double *)malloc(sizeof(double) * (size_t)d);
     if (!p || !o) {
         free(p);
@@ -782,9 +784,10 @@ int oracle_attention(const uint16_t *Q, const uint16_t *Kc, const uint16_t *V, i
         return -4;
     }
     for (int h = 0; h < H; ++h)
-        for (int s = 0; s < S; ++s) {
+        for (int s = 0; s < Sq; ++s) {
+            int last = Sk - Sq + s;
             double lmax = -INFINITY;
-            for (int t = 0; t <= s; ++t) {
+            for (int t = 0; t <= last; ++t) {
                 double dot = 0.0;
                 for (int i = 0; i < d; ++i)
                     dot += (double)oracle_f16_to_f32(Q[((size_t)s * H + h) * d + i]) *
@@ -793,12 +796,12 @@ int oracle_attention(const uint16_t *Q, const uint16_t *Kc, const uint16_t *V, i
                 if (p[t] > lmax) lmax = p[t];
             }
             double z = 0.0;
-            for (int t = 0; t <= s; ++t) {
+            for (int t = 0; t <= last; ++t) {
                 p[t] = exp(p[t] - lmax);
                 z += p[t];
             }
             for (int i = 0; i < d; ++i) o[i] = 0.0;
-            for (int t = 0; t <= s; ++t)
+            for (int t = 0; t <= last; ++t)
                 for (int i = 0; i < d; ++i)
                     o[i] += (p[t] / z) * (double)oracle_f16_to_f32(V[((size_t)t * H + h) * d + i]);
             for (int i = 0; i < d; ++i)

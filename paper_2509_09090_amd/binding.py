@@ -22,7 +22,8 @@ EXPORTS = (
     "sqap_weight_free", "sqap_weight_info", "sqap_workspace_bytes", "sqap_w4a4_linear",
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
-    "sqap_quantize_weight_folded",
+    "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
+    "sqap_attention", "sqap_residual_add",
 )
 
 
@@ -66,6 +67,11 @@ def lib():
         L.sqap_quantize_act_channelwise.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp, vp]
         L.sqap_quantize_weight_folded.argtypes = [vp, i32, i32, u32, vp, vp, vp, vp]
         L.sqap_quantize_act.argtypes = [vp, i64, vp, i32, i32, u32, vp, vp, vp]
+        L.sqap_rmsnorm_quantize_act.argtypes = [vp, i64, vp, i32, i32, vp, vp, ctypes.c_float, u32, vp, vp, vp, vp, vp, vp]
+        L.sqap_swiglu_quantize_act.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
+        L.sqap_rope.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp]
+        L.sqap_attention.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, vp, i64, vp]
+        L.sqap_residual_add.argtypes = [vp, i64, vp, i64, i32, i32, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
         L.sqap_weight_pack.argtypes = [vp, vp, i32, i32, ctypes.POINTER(vp), vp]
         L.sqap_weight_free.argtypes = [vp]
@@ -214,6 +220,39 @@ def sqap_weight_pack(Wq, sw, stream=None):
     h = ctypes.c_void_p()
     _check(lib().sqap_weight_pack(_ptr(Wq), _ptr(sw), N, 2 * half, ctypes.byref(h), _stream(stream)))
     return Weight(h, N, 2 * half)
+
+
+def sqap_rmsnorm_quantize_act(X, rows, gamma, eps, Xq, sx, delta=None, flags=0, col_scales=None, xsum_out=None,
+                              y_out=None, stream=None):
+    """RMSNorm (after an optional residual update) fused into the activation quantizer."""
+    K = X.shape[1]
+    M = X.shape[0] if rows is None else rows.numel()
+    _check(lib().sqap_rmsnorm_quantize_act(_ptr(X), X.stride(0), _ptr(rows), M, K, _ptr(delta), _ptr(gamma), eps,
+                                           flags, _ptr(col_scales), _ptr(xsum_out), _ptr(y_out), _ptr(Xq),
+                                           _ptr(sx), _stream(stream)))
+
+
+def sqap_swiglu_quantize_act(G, U, Xq, sx, col_scales=None, h_out=None, stream=None):
+    """h = silu(G) * U fused into the activation quantizer; G, U may be column slices of one tensor."""
+    M, F = G.shape
+    _check(lib().sqap_swiglu_quantize_act(_ptr(G), G.stride(0), _ptr(U), U.stride(0), M, F, _ptr(col_scales),
+                                          _ptr(h_out), _ptr(Xq), _ptr(sx), _stream(stream)))
+
+
+def sqap_rope(X, pos, H, d, base=10000.0, stream=None):
+    """X [S, >= H*d] fp16 (row pitch = X.stride(0)), rotated in place at positions pos [S] int32."""
+    _check(lib().sqap_rope(_ptr(X), X.stride(0), _ptr(pos), X.shape[0], H, d, base, _stream(stream)))
+
+
+def sqap_attention(Q, K, V, H, d, O, stream=None):
+    """Causal attention; Q [Sq, H*d], K, V [Sk, H*d], O [Sq, H*d] (row pitches from the strides)."""
+    _check(lib().sqap_attention(_ptr(Q), Q.stride(0), _ptr(K), K.stride(0), _ptr(V), V.stride(0), Q.shape[0],
+                                K.shape[0], H, d, _ptr(O), O.stride(0), _stream(stream)))
+
+
+def sqap_residual_add(X, delta, stream=None):
+    M, K = X.shape
+    _check(lib().sqap_residual_add(_ptr(X), X.stride(0), _ptr(delta), delta.stride(0), M, K, _stream(stream)))
 
 
 def sqap_selftest_quotient(counter, stream=None):

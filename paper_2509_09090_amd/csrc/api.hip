@@ -197,6 +197,115 @@ sqap_status sqap_quantize_weight(const sqap_f16 *W, int32_t N, int32_t K, uint32
     return quantize_common("sqap_quantize_weight", W, K, nullptr, N, K, flags, Wq, sw, stream);
 }
 
+// shared checks of the quantizers with an operation fused in front
+static sqap_status fused_common(const char *who, const void *X, int64_t ldx, int32_t M, int32_t K, uint32_t flags,
+                                const void *col_scales, const void *y_out, const uint8_t *Xq, const void *sx)
+{
+    if (M < 0 || K <= 0) return fail(SQAP_EINVAL, "%s: M %d, K %d", who, M, K);
+    if (ldx < K) return fail(SQAP_EINVAL, "%s: pitch %lld below K %d", who, (long long)ldx, K);
+    if (flags & ~(uint32_t)SQAP_ROTATE_HADAMARD) return fail(SQAP_EINVAL, "%s: unknown flags 0x%x", who, flags);
+    if (!Xq && !y_out && M > 0) return fail(SQAP_EINVAL, "%s: neither Xq nor a half-precision output asked for", who);
+    if (Xq && !sx) return fail(SQAP_EINVAL, "%s: null sx", who);
+    if (M > 0 && !X) return fail(SQAP_EINVAL, "%s: null input", who);
+    const bool rotate = (flags & SQAP_ROTATE_HADAMARD) != 0;
+    if (rotate && ((K & (K - 1)) != 0 || K < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if ((K & 7) || K > 16384) return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
+    if ((ldx & 7) || !aligned16(X) || !aligned16(col_scales) || !aligned16(y_out) ||
+        (reinterpret_cast<uintptr_t>(Xq) & 3u))
+        return fail(SQAP_EUNSUPPORTED, "%s: half operands and pitches must be 16-byte aligned, Xq 4-byte", who);
+    return SQAP_OK;
+}
+
+sqap_status sqap_rmsnorm_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M, int32_t K,
+                                      const sqap_f16 *delta, const sqap_f16 *gamma, float eps, uint32_t flags,
+                                      const sqap_f16 *col_scales, sqap_f16 *xsum_out, sqap_f16 *y_out,
+                                      uint8_t *Xq, sqap_f16 *sx, void *stream)
+{
+    const char *who = "sqap_rmsnorm_quantize_act";
+    sqap_status s = fused_common(who, X, ldx, M, K, flags, col_scales, y_out, Xq, sx);
+    if (s != SQAP_OK) return s;
+    if (!(eps >= 0.0f)) return fail(SQAP_EINVAL, "%s: eps must be >= 0", who);
+    if (M == 0) return SQAP_OK;
+    if (!gamma) return fail(SQAP_EINVAL, "%s: null gamma", who);
+    if (!aligned16(gamma) || !aligned16(delta) || !aligned16(xsum_out))
+        return fail(SQAP_EUNSUPPORTED, "%s: gamma, delta and xsum_out must be 16-byte aligned", who);
+    PreArgs pre = {};
+    pre.delta = reinterpret_cast<const __half *>(delta);
+    pre.xsum_out = reinterpret_cast<__half *>(xsum_out);
+    pre.gamma = reinterpret_cast<const __half *>(gamma);
+    pre.eps = eps;
+    pre.y_out = reinterpret_cast<__half *>(y_out);
+    return launch_fused_quantize(kPreNorm, reinterpret_cast<const __half *>(X), ldx, rows, M, K,
+                                 (flags & SQAP_ROTATE_HADAMARD) != 0, reinterpret_cast<const __half *>(col_scales),
+                                 Xq, reinterpret_cast<__half *>(sx), pre, as_stream(stream));
+}
+
+sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_f16 *U, int64_t ldu, int32_t M,
+                                     int32_t F, const sqap_f16 *col_scales, sqap_f16 *h_out, uint8_t *Xq,
+                                     sqap_f16 *sx, void *stream)
+{
+    const char *who = "sqap_swiglu_quantize_act";
+    sqap_status s = fused_common(who, G, ldg, M, F, 0, col_scales, h_out, Xq, sx);
+    if (s != SQAP_OK) return s;
+    if (ldu < F) return fail(SQAP_EINVAL, "%s: pitch %lld below F %d", who, (long long)ldu, F);
+    if (M == 0) return SQAP_OK;
+    if (!U) return fail(SQAP_EINVAL, "%s: null U", who);
+    if ((ldu & 7) || !aligned16(U)) return fail(SQAP_EUNSUPPORTED, "%s: U and its pitch must be 16-byte aligned", who);
+    PreArgs pre = {};
+    pre.U = reinterpret_cast<const __half *>(U);
+    pre.ldu = ldu;
+    pre.y_out = reinterpret_cast<__half *>(h_out);
+    return launch_fused_quantize(kPreSwiglu, reinterpret_cast<const __half *>(G), ldg, nullptr, M, F, false,
+                                 reinterpret_cast<const __half *>(col_scales), Xq, reinterpret_cast<__half *>(sx), pre,
+                                 as_stream(stream));
+}
+
+sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d, double base,
+                      void *stream)
+{
+    if (S < 0 || H <= 0 || d <= 0 || (d & 1)) return fail(SQAP_EINVAL, "sqap_rope: S %d, H %d, d %d", S, H, d);
+    if (ld < (int64_t)H * d) return fail(SQAP_EINVAL, "sqap_rope: pitch %lld below H * d", (long long)ld);
+    if (!(base > 0.0)) return fail(SQAP_EINVAL, "sqap_rope: base must be positive");
+    if (S == 0) return SQAP_OK;
+    if (!X || !pos) return fail(SQAP_EINVAL, "sqap_rope: null pointer");
+    return launch_rope(reinterpret_cast<__half *>(X), ld, pos, S, H, d, base, as_stream(stream));
+}
+
+sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk, const sqap_f16 *V,
+                           int64_t ldv, int32_t Sq, int32_t Sk, int32_t H, int32_t d, sqap_f16 *O, int64_t ldo,
+                           void *stream)
+{
+    if (Sq < 0 || Sk < Sq || H <= 0 || d <= 0)
+        return fail(SQAP_EINVAL, "sqap_attention: Sq %d, Sk %d (>= Sq), H %d, d %d", Sq, Sk, H, d);
+    const int64_t width = (int64_t)H * d;
+    if (ldq < width || ldk < width || ldv < width || ldo < width)
+        return fail(SQAP_EINVAL, "sqap_attention: a pitch is below H * d");
+    if (d != 16 && d != 32 && d != 64 && d != 128)
+        return fail(SQAP_EUNSUPPORTED, "sqap_attention: head size %d (16, 32, 64 or 128)", d);
+    if (H > 65535) return fail(SQAP_EUNSUPPORTED, "sqap_attention: H = %d", H);
+    if (Sq == 0) return SQAP_OK;
+    if (!Q || !K || !V || !O) return fail(SQAP_EINVAL, "sqap_attention: null pointer");
+    if (((ldq | ldk | ldv | ldo) & 7) || !aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
+        return fail(SQAP_EUNSUPPORTED, "sqap_attention: operands and pitches must be 16-byte aligned");
+    return launch_attention(reinterpret_cast<const __half *>(Q), ldq, reinterpret_cast<const __half *>(K), ldk,
+                            reinterpret_cast<const __half *>(V), ldv, Sq, Sk, H, d, reinterpret_cast<__half *>(O), ldo,
+                            as_stream(stream));
+}
+
+sqap_status sqap_residual_add(sqap_f16 *X, int64_t ldx, const sqap_f16 *delta, int64_t ldd, int32_t M, int32_t K,
+                              void *stream)
+{
+    if (M < 0 || K < 0) return fail(SQAP_EINVAL, "sqap_residual_add: M %d, K %d", M, K);
+    if (ldx < K || ldd < K) return fail(SQAP_EINVAL, "sqap_residual_add: pitch below K");
+    if (M == 0 || K == 0) return SQAP_OK;
+    if (!X || !delta) return fail(SQAP_EINVAL, "sqap_residual_add: null pointer");
+    if ((K & 7) || (ldx & 7) || (ldd & 7) || !aligned16(X) || !aligned16(delta))
+        return fail(SQAP_EUNSUPPORTED, "sqap_residual_add: K and pitches multiples of 8, pointers 16-byte aligned");
+    return launch_residual_add(reinterpret_cast<__half *>(X), ldx, reinterpret_cast<const __half *>(delta), ldd, M, K,
+                               as_stream(stream));
+}
+
 // shared checks of the entry points that take per-channel scales
 static sqap_status scaled_common(const char *who, const sqap_f16 *X, int64_t ldx, int32_t M, int32_t K,
                                  uint32_t flags, const void *col_scales)

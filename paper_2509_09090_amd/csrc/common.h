@@ -94,6 +94,20 @@ sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *ro
 sqap_status launch_quantize_rows_scaled(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                         bool rotate, bool folded, const __half *col_scales, uint8_t *Xq,
                                         __half *sx, hipStream_t st);
+// Operation fused in front of the quantizer (quantize.hip) and its operands.
+enum PreOp { kPreNone = 0, kPreNorm = 1, kPreSwiglu = 2 };
+struct PreArgs {
+    const __half *delta;    // kPreNorm: residual update [M, K], nullable
+    __half *xsum_out;       // kPreNorm: x + delta [M, K], nullable
+    const __half *gamma;    // kPreNorm: [K]
+    float eps;              // kPreNorm
+    const __half *U;        // kPreSwiglu: up rows, pitch ldu
+    int64_t ldu;
+    __half *y_out;          // the half-precision result the quantizer sees, [M, K], nullable
+};
+sqap_status launch_fused_quantize(int pre_op, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                  bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
+                                  const PreArgs &pre, hipStream_t st);
 sqap_status launch_channel_scales(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, bool rotate,
                                   float *amax, bool accumulate, __half *scales, hipStream_t st);
 sqap_status launch_weight_pack(const uint8_t *Wq, const __half *sw, const Weight &w,
@@ -103,6 +117,10 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
                                __half *Y, int64_t ldy, int32_t *acc_out, void *workspace,
                                hipStream_t st);
 
+sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H, int d, double base, hipStream_t st);
+sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int64_t ldk, const __half *V,
+                             int64_t ldv, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st);
+sqap_status launch_residual_add(__half *X, int64_t ldx, const __half *Dl, int64_t ldd, int M, int K, hipStream_t st);
 sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t st);
 // Checks once per device how a launch's workgroups are dealt to the XCDs (see gemm.hip); table_out
 // (host, 256 words, nullable) receives the XCC id of every workgroup and forces a fresh probe.

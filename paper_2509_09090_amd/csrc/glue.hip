@@ -1,0 +1,221 @@
+// Decoder glue between the W4A4 linears of a Llama-shaped layer: rotary position embedding,
+// causal softmax attention over a short prefix, residual add.  (RMSNorm and the SwiGLU gate are
+// fused into the activation quantizer, quantize.hip.)  The paper does not restate the decoder;
+// these follow the published architecture (Su et al. 2021 in the half-split pairing used by
+// Llama; Vaswani et al. 2017).  Sequences here are a few hundred tokens (276 before pruning, 148
+// after), so attention is a small fraction of a layer and is written for low latency, not for
+// matrix-core throughput: binary32 FMAs over LDS tiles with an online softmax.
+#include "common.h"
+
+namespace sqap {
+
+// v'_i = v_i cos a - v_{i+d/2} sin a,  v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a,
+// a = pos * base^(-2i/d); angle, sine and cosine in binary64, products in binary64, one rounding
+// to half.  One thread per (token, head, i); consecutive threads take consecutive i.
+__global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ X, int64_t ld, const int32_t *__restrict__ pos,
+                                                   int S, int H, int d, double base)
+{
+    const int half_d = d >> 1;
+    const int64_t total = (int64_t)S * H * half_d;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half_d);
+    const int64_t sh = idx / half_d;
+    const int h = (int)(sh % H);
+    const int s = (int)(sh / H);
+    __half *v = X + (int64_t)s * ld + (int64_t)h * d;
+    const double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+    double sn, cs;
+    sincos(a, &sn, &cs);
+    const double lo = (double)__half2float(v[i]), hi = (double)__half2float(v[i + half_d]);
+    v[i] = __float2half_rn((float)(lo * cs - hi * sn));
+    v[i + half_d] = __float2half_rn((float)(hi * cs + lo * sn));
+}
+
+sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H, int d, double base, hipStream_t st)
+{
+    const int64_t total = (int64_t)S * H * (d / 2);
+    if (total == 0) return SQAP_OK;
+    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, X, ld, pos, S, H, d, base);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// Causal attention.  Query i (of Sq) sits at sequence position Sk - Sq + i and sees keys 0 ..
+// Sk - Sq + i.  One workgroup per (head, block of 32 queries); keys and values pass through LDS
+// in tiles of 64.  Thread t works for query t/8: in the score phase on keys 8(t%8) .. +7 of the
+// tile, in the output phase on the D/8 consecutive head-dimension columns from (t%8) D/8 on.
+// Running maximum m, running sum l and the output row are
+// rescaled when a tile raises the maximum (the usual online softmax); all in binary32.
+constexpr int kAttQ = 32, kAttK = 64;
+
+template <int D>
+__global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict__ Q, int64_t ldq,
+                                                        const __half *__restrict__ Kc, int64_t ldk,
+                                                        const __half *__restrict__ V, int64_t ldv, int Sq, int Sk,
+                                                        int H, __half *__restrict__ O, int64_t ldo)
+{
+    constexpr int PITCH = D + 8;                 // halves per LDS row: keeps 16-byte alignment, staggers the banks
+    constexpr int CPT = D / 8;                   // output columns per thread
+    __shared__ __attribute__((aligned(16))) __half qs[kAttQ * PITCH];
+    __shared__ __attribute__((aligned(16))) __half ks[kAttK * PITCH];
+    __shared__ __attribute__((aligned(16))) __half vs[kAttK * PITCH];
+    __shared__ float ps[kAttQ * (kAttK + 1)];
+    const int t = threadIdx.x, h = blockIdx.x, q0 = blockIdx.y * kAttQ;
+    const int qi = t >> 3, sub = t & 7;
+    const int shift = Sk - Sq;                   // query i sees keys <= i + shift
+    const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+
+    for (int u = t; u < kAttQ * (D / 8); u += 256) {
+        const int r = u / (D / 8), c = u % (D / 8);
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (q0 + r < Sq) raw = *reinterpret_cast<const uint4 *>(Q + (int64_t)(q0 + r) * ldq + (int64_t)h * D + c * 8);
+        *reinterpret_cast<uint4 *>(qs + r * PITCH + c * 8) = raw;
+    }
+    float o[CPT];
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) o[c] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    const int my_q = q0 + qi;
+    const int last_key = min(Sk - 1, min(q0 + kAttQ - 1, Sq - 1) + shift);      // of the whole block
+    for (int k0 = 0; k0 <= last_key; k0 += kAttK) {
+        __syncthreads();                                                        // previous tile consumed (and qs written)
+        for (int u = t; u < kAttK * (D / 8); u += 256) {
+            const int r = u / (D / 8), c = u % (D / 8);
+            uint4 kr = make_uint4(0u, 0u, 0u, 0u), vr = kr;
+            if (k0 + r < Sk) {
+                kr = *reinterpret_cast<const uint4 *>(Kc + (int64_t)(k0 + r) * ldk + (int64_t)h * D + c * 8);
+                vr = *reinterpret_cast<const uint4 *>(V + (int64_t)(k0 + r) * ldv + (int64_t)h * D + c * 8);
+            }
+            *reinterpret_cast<uint4 *>(ks + r * PITCH + c * 8) = kr;
+            *reinterpret_cast<uint4 *>(vs + r * PITCH + c * 8) = vr;
+        }
+        __syncthreads();
+        // scores of this thread's 8 keys
+        float sc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sc[j] = 0.f;
+        for (int c = 0; c < D; c += 8) {
+            const uint4 qraw = *reinterpret_cast<const uint4 *>(qs + qi * PITCH + c);
+            const __half2 *q2 = reinterpret_cast<const __half2 *>(&qraw);
+            float qf[8];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const float2 f = __half22float2(q2[p]);
+                qf[2 * p] = f.x;
+                qf[2 * p + 1] = f.y;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint4 kraw = *reinterpret_cast<const uint4 *>(ks + (sub * 8 + j) * PITCH + c);
+                const __half2 *k2 = reinterpret_cast<const __half2 *>(&kraw);
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const float2 f = __half22float2(k2[p]);
+                    sc[j] = fmaf(qf[2 * p], f.x, sc[j]);
+                    sc[j] = fmaf(qf[2 * p + 1], f.y, sc[j]);
+                }
+            }
+        }
+        float tile_max = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int key = k0 + sub * 8 + j;
+            const bool seen = key < Sk && key <= my_q + shift && my_q < Sq;
+            sc[j] = seen ? sc[j] * inv_sqrt_d : -INFINITY;
+            tile_max = fmaxf(tile_max, sc[j]);
+        }
+        for (int x = 1; x < 8; x <<= 1) tile_max = fmaxf(tile_max, __shfl_xor(tile_max, x));
+        const float m_new = fmaxf(m, tile_max);
+        // a query that has seen no key yet keeps m = -inf; exp(-inf - -inf) is avoided
+        const float rescale = m_new == -INFINITY ? 1.f : expf(m - m_new);
+        float tile_sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float pj = sc[j] == -INFINITY ? 0.f : expf(sc[j] - m_new);
+            ps[qi * (kAttK + 1) + sub * 8 + j] = pj;
+            tile_sum += pj;
+        }
+        for (int x = 1; x < 8; x <<= 1) tile_sum += __shfl_xor(tile_sum, x);
+        l = l * rescale + tile_sum;
+        m = m_new;
+        __syncthreads();                                                        // ps complete
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) o[c] *= rescale;
+        const int kmax = min(kAttK, Sk - k0);
+        for (int j = 0; j < kmax; ++j) {
+            const float pj = ps[qi * (kAttK + 1) + j];
+            const __half *vrow = vs + j * PITCH + sub * CPT;
+#pragma unroll
+            for (int c = 0; c < CPT; c += 2) {
+                const float2 f = __half22float2(*reinterpret_cast<const __half2 *>(vrow + c));
+                o[c] = fmaf(pj, f.x, o[c]);
+                o[c + 1] = fmaf(pj, f.y, o[c + 1]);
+            }
+        }
+    }
+    if (my_q < Sq) {
+        __half *dst = O + (int64_t)my_q * ldo + (int64_t)h * D + sub * CPT;
+        const float inv_l = 1.0f / l;
+#pragma unroll
+        for (int c = 0; c < CPT; c += 2)
+            *reinterpret_cast<__half2 *>(dst + c) = __floats2half2_rn(o[c] * inv_l, o[c + 1] * inv_l);
+    }
+}
+
+sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int64_t ldk, const __half *V,
+                             int64_t ldv, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st)
+{
+    if (Sq == 0) return SQAP_OK;
+    const dim3 grid(H, (Sq + kAttQ - 1) / kAttQ);
+#define SQAP_ATT_CASE(DD)                                                                                          \
+    case DD:                                                                                                       \
+        hipLaunchKernelGGL(attention_kernel<DD>, grid, dim3(256), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo); \
+        break;
+    switch (d) {
+        SQAP_ATT_CASE(16)
+        SQAP_ATT_CASE(32)
+        SQAP_ATT_CASE(64)
+        SQAP_ATT_CASE(128)
+    default:
+        return fail(SQAP_EUNSUPPORTED, "attention: head size %d (16, 32, 64 or 128)", d);
+    }
+#undef SQAP_ATT_CASE
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// x <- half(float(x) + float(delta)), rows of K halves with pitches; 8 elements per thread
+__global__ __launch_bounds__(256) void residual_add_kernel(__half *__restrict__ X, int64_t ldx,
+                                                           const __half *__restrict__ Dl, int64_t ldd, int M, int K)
+{
+    const int groups = K >> 3;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)M * groups) return;
+    const int g = (int)(idx % groups);
+    const int64_t r = idx / groups;
+    uint4 *xp = reinterpret_cast<uint4 *>(X + r * ldx) + g;
+    uint4 a = *xp;
+    const uint4 b = reinterpret_cast<const uint4 *>(Dl + r * ldd)[g];
+    __half2 *a2 = reinterpret_cast<__half2 *>(&a);
+    const __half2 *b2 = reinterpret_cast<const __half2 *>(&b);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float2 x = __half22float2(a2[p]), y = __half22float2(b2[p]);
+        float s0 = x.x + y.x, s1 = x.y + y.y;
+        asm volatile("" : "+v"(s0), "+v"(s1));       // binary32 sums first, then one conversion each
+        a2[p] = __floats2half2_rn(s0, s1);
+    }
+    *xp = a;
+}
+
+sqap_status launch_residual_add(__half *X, int64_t ldx, const __half *Dl, int64_t ldd, int M, int K, hipStream_t st)
+{
+    const int64_t total = (int64_t)M * (K >> 3);
+    if (total == 0) return SQAP_OK;
+    hipLaunchKernelGGL(residual_add_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, X, ldx, Dl, ldd, M, K);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+}  // namespace sqap

@@ -28,12 +28,9 @@ __device__ __forceinline__ float quotient(float v, float s, float r)
 //                into a weight), then quantized per row
 enum QuantMode { kPerRow = 0, kChannelwise = 1, kFolded = 2 };
 
-// Reads one row into registers (thread t owns groups t, t+256, ... of 8 consecutive
-// elements) and applies the rotation of Eq. 6 when ROTATE: butterfly stages at distance 1, 2,
-// 4 inside a group of 8 in registers, the remaining stages in LDS in the same order, then one
-// multiply by (float)(1/sqrt(K)).  Contains barriers when ROTATE.
-template <bool ROTATE, int GPT>
-__device__ __forceinline__ void load_row(const uint4 *xrow, int K, float (&v)[GPT][8], float *rot)
+// Reads one row into registers: thread t owns groups t, t+256, ... of 8 consecutive elements.
+template <int GPT>
+__device__ __forceinline__ void load_halves(const uint4 *xrow, int K, float (&v)[GPT][8])
 {
     const int t = threadIdx.x;
     const int groups = K >> 3;
@@ -54,45 +51,200 @@ __device__ __forceinline__ void load_row(const uint4 *xrow, int K, float (&v)[GP
             for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
         }
     }
-    if (ROTATE) {
+}
+
+// The rotation of Eq. 6 on a row held in registers: butterfly stages at distance 1, 2, 4 inside
+// a group of 8 in registers, the remaining stages in LDS in the same order, then one multiply
+// by (float)(1/sqrt(K)).  Contains barriers.
+template <int GPT>
+__device__ __forceinline__ void rotate_row(int K, float (&v)[GPT][8], float *rot)
+{
+    const int t = threadIdx.x;
+    const int groups = K >> 3;
 #pragma unroll
-        for (int gi = 0; gi < GPT; ++gi) {
+    for (int gi = 0; gi < GPT; ++gi) {
 #pragma unroll
-            for (int h = 1; h < 8; h <<= 1) {
+        for (int h = 1; h < 8; h <<= 1) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    if ((e & h) == 0) {
-                        float a = v[gi][e], b = v[gi][e + h];
-                        v[gi][e] = a + b;
-                        v[gi][e + h] = a - b;
-                    }
+            for (int e = 0; e < 8; ++e) {
+                if ((e & h) == 0) {
+                    float a = v[gi][e], b = v[gi][e + h];
+                    v[gi][e] = a + b;
+                    v[gi][e + h] = a - b;
                 }
             }
-            const int g = t + gi * 256;
-            if (g < groups) {
+        }
+        const int g = t + gi * 256;
+        if (g < groups) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) rot[g * 8 + e] = v[gi][e];
-            }
+            for (int e = 0; e < 8; ++e) rot[g * 8 + e] = v[gi][e];
+        }
+    }
+    __syncthreads();
+    const int half_k = K >> 1;
+    for (int h = 8; h < K; h <<= 1) {
+        for (int p = t; p < half_k; p += 256) {
+            const int j = ((p / h) * 2 * h) + (p % h);
+            float a = rot[j], b = rot[j + h];
+            rot[j] = a + b;
+            rot[j + h] = a - b;
         }
         __syncthreads();
-        const int half_k = K >> 1;
-        for (int h = 8; h < K; h <<= 1) {
-            for (int p = t; p < half_k; p += 256) {
-                const int j = ((p / h) * 2 * h) + (p % h);
-                float a = rot[j], b = rot[j + h];
-                rot[j] = a + b;
-                rot[j + h] = a - b;
-            }
-            __syncthreads();
+    }
+    const float c = (float)(1.0 / sqrt((double)K));
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[gi][e] = rot[g * 8 + e] * c;
         }
-        const float c = (float)(1.0 / sqrt((double)K));
+    }
+}
+
+template <bool ROTATE, int GPT>
+__device__ __forceinline__ void load_row(const uint4 *xrow, int K, float (&v)[GPT][8], float *rot)
+{
+    load_halves<GPT>(xrow, K, v);
+    if (ROTATE) rotate_row<GPT>(K, v, rot);
+}
+
+// ---- operations fused in front of the quantizer (the decoder's glue between two linears) ----
+
+// The empty asm makes x exist as a binary32 value: otherwise the compiler folds the operation that
+// produced it and the conversion into one mixed-precision instruction that rounds only once.
+__device__ __forceinline__ float round_to_half(float x)
+{
+    asm volatile("" : "+v"(x));
+    return __half2float(__float2half_rn(x));
+}
+
+__device__ __forceinline__ void unpack8(const uint4 raw, float (&f)[8])
+{
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
-        for (int gi = 0; gi < GPT; ++gi) {
-            const int g = t + gi * 256;
-            if (g < groups) {
+    for (int p = 0; p < 4; ++p) {
+        const float2 x = __half22float2(h2[p]);
+        f[2 * p] = x.x;
+        f[2 * p + 1] = x.y;
+    }
+}
+
+__device__ __forceinline__ uint4 pack8(const float (&f)[8])
+{
+    uint4 raw;
+    __half2 *h2 = reinterpret_cast<__half2 *>(&raw);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) v[gi][e] = rot[g * 8 + e] * c;
+    for (int p = 0; p < 4; ++p) h2[p] = __floats2half2_rn(f[2 * p], f[2 * p + 1]);
+    return raw;
+}
+
+// RMSNorm of the row in v (Zhang & Sennrich 2019, as used in front of every linear group of a
+// Llama decoder), after an optional residual update x' = half(x + delta):
+//   S = sum x'^2 exactly;  r = (float)(1 / sqrt(S / K + eps)) in binary64;
+//   v = half((x' * r) * gamma)
+// The sum is exact and therefore independent of the order in which lanes add: a half is an
+// integer m < 2^11 times 2^e, e >= -24, so x^2 * 2^48 is an integer below 2^80; every thread
+// adds its elements into a 128-bit integer, wavefronts and the block add those.  The sum is
+// rounded to binary64 once (top 64 bits with a sticky last bit, then the hardware's u64 -> f64
+// conversion, which rounds to nearest even).  Rows are assumed finite.
+template <int GPT>
+__device__ __forceinline__ void norm_row(float (&v)[GPT][8], int row, int K, const PreArgs &pre,
+                                         unsigned long long *wsum)
+{
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, groups = K >> 3;
+    unsigned long long hi = 0, lo = 0;
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+            if (pre.delta) {
+                float d[8];
+                unpack8(reinterpret_cast<const uint4 *>(pre.delta + (size_t)row * K)[g], d);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[gi][e] = round_to_half(v[gi][e] + d[e]);
             }
+            if (pre.xsum_out) reinterpret_cast<uint4 *>(pre.xsum_out + (size_t)row * K)[g] = pack8(v[gi]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned bits = __half_as_ushort(__float2half_rn(v[gi][e]));      // exact: v is a half value
+                const unsigned ex = (bits >> 10) & 31u, man = bits & 1023u;
+                const unsigned long long m = ex ? man + 1024u : man;
+                const int sh = ex ? 2 * (int)ex - 2 : 0;                                // 2e + 48, at most 58
+                const unsigned long long m2 = m * m;                                    // below 2^22
+                const unsigned long long add_lo = m2 << sh;
+                const unsigned long long add_hi = sh > 42 ? m2 >> (64 - sh) : 0ull;
+                lo += add_lo;
+                hi += add_hi + (lo < add_lo ? 1ull : 0ull);
+            }
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long ohi = __shfl_xor(hi, o), olo = __shfl_xor(lo, o);
+        lo += olo;
+        hi += ohi + (lo < olo ? 1ull : 0ull);
+    }
+    if (lane == 0) {
+        wsum[2 * wave] = hi;
+        wsum[2 * wave + 1] = lo;
+    }
+    __syncthreads();
+    hi = wsum[0];
+    lo = wsum[1];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+        const unsigned long long olo = wsum[2 * w + 1];
+        lo += olo;
+        hi += wsum[2 * w] + (lo < olo ? 1ull : 0ull);
+    }
+    double Sd;
+    if (hi == 0) {
+        Sd = (double)lo;
+    } else {
+        const int lz = __clzll((long long)hi);
+        unsigned long long top = lz ? (hi << lz) | (lo >> (64 - lz)) : hi;
+        const unsigned long long rest = lz ? lo << lz : lo;
+        top |= rest != 0 ? 1ull : 0ull;
+        Sd = ldexp((double)top, 64 - lz);
+    }
+    Sd = ldexp(Sd, -48);
+    const float r = (float)(1.0 / sqrt(Sd / (double)K + (double)pre.eps));
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+            float gm[8];
+            unpack8(reinterpret_cast<const uint4 *>(pre.gamma)[g], gm);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float xr = v[gi][e] * r;
+                v[gi][e] = round_to_half(xr * gm[e]);
+            }
+            if (pre.y_out) reinterpret_cast<uint4 *>(pre.y_out + (size_t)row * K)[g] = pack8(v[gi]);
+        }
+    }
+}
+
+// SwiGLU (Shazeer 2020; the feed-forward of a Llama decoder): v holds the gate row g, pre.U the
+// up row;  v = half(silu(g) * u),  silu(g) = (float)(g / (1 + exp(-g))) evaluated in binary64.
+// silu is a function of a half value: a GPU test walks all 2^16 of them against the host's.
+template <int GPT>
+__device__ __forceinline__ void swiglu_row(float (&v)[GPT][8], int row, int K, const PreArgs &pre)
+{
+    const int t = threadIdx.x, groups = K >> 3;
+#pragma unroll
+    for (int gi = 0; gi < GPT; ++gi) {
+        const int g = t + gi * 256;
+        if (g < groups) {
+            float u[8];
+            unpack8(reinterpret_cast<const uint4 *>(pre.U + (size_t)row * pre.ldu)[g], u);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const double gd = (double)v[gi][e];
+                const float s = (float)(gd / (1.0 + exp(-gd)));
+                v[gi][e] = round_to_half(s * u[e]);
+            }
+            if (pre.y_out) reinterpret_cast<uint4 *>(pre.y_out + (size_t)row * K)[g] = pack8(v[gi]);
         }
     }
 }
@@ -114,15 +266,17 @@ __device__ __forceinline__ void load_col_scales(const __half *col_scales, int g,
 // store.  Arithmetic (all binary32, IEEE, no contraction possible):
 //   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
 // GPT = groups per thread the instance is compiled for (registers, hence occupancy).
-template <bool ROTATE, int GPT, int MODE>
+// PRE selects an operation applied to the row between its read and the quantizer (see above).
+template <bool ROTATE, int GPT, int MODE, int PRE>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
                                                             const int32_t *__restrict__ rows, int K,
                                                             const __half *__restrict__ col_scales,
                                                             uint8_t *__restrict__ Xq,
-                                                            __half *__restrict__ scale_out)
+                                                            __half *__restrict__ scale_out, const PreArgs pre)
 {
     extern __shared__ float rot[];       // K floats when ROTATE
     __shared__ float wave_max[4];
+    __shared__ unsigned long long wave_sum[8];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int row = blockIdx.x;
     const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
@@ -130,7 +284,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__rest
     const int groups = K >> 3;
 
     float v[GPT][8];
-    load_row<ROTATE, GPT>(xrow, K, v, rot);
+    load_halves<GPT>(xrow, K, v);
+    if (PRE == kPreNorm) norm_row<GPT>(v, row, K, pre, wave_sum);
+    if (PRE == kPreSwiglu) swiglu_row<GPT>(v, row, K, pre);
+    if (ROTATE) rotate_row<GPT>(K, v, rot);
+    if (!Xq) return;                     // the caller wanted the half-precision result only (uniform)
     uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
 
     if (MODE == kChannelwise) {
@@ -255,23 +413,25 @@ __global__ __launch_bounds__(256) void channel_scales_kernel(const float *__rest
     }
 }
 
-template <bool ROTATE, int GPT, int MODE>
+template <bool ROTATE, int GPT, int MODE, int PRE>
 static void launch_quantize_inst(const __half *X, int64_t ldx, const int32_t *rows, int M, int K, size_t lds,
-                                 const __half *col_scales, uint8_t *Xq, __half *sx, hipStream_t st)
+                                 const __half *col_scales, uint8_t *Xq, __half *sx, const PreArgs &pre,
+                                 hipStream_t st)
 {
-    hipLaunchKernelGGL((quantize_rows_kernel<ROTATE, GPT, MODE>), dim3(M), dim3(256), lds, st, X, ldx, rows, K,
-                       col_scales, Xq, sx);
+    hipLaunchKernelGGL((quantize_rows_kernel<ROTATE, GPT, MODE, PRE>), dim3(M), dim3(256), lds, st, X, ldx, rows, K,
+                       col_scales, Xq, sx, pre);
 }
 
-template <bool ROTATE, int MODE>
+template <bool ROTATE, int MODE, int PRE>
 static void launch_quantize_gpt(int gpt, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
-                                size_t lds, const __half *col_scales, uint8_t *Xq, __half *sx, hipStream_t st)
+                                size_t lds, const __half *col_scales, uint8_t *Xq, __half *sx, const PreArgs &pre,
+                                hipStream_t st)
 {
-    if (gpt <= 1) launch_quantize_inst<ROTATE, 1, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
-    else if (gpt <= 2) launch_quantize_inst<ROTATE, 2, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
-    else if (gpt <= 4) launch_quantize_inst<ROTATE, 4, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
-    else if (gpt <= 6) launch_quantize_inst<ROTATE, 6, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
-    else launch_quantize_inst<ROTATE, 8, MODE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+    if (gpt <= 1) launch_quantize_inst<ROTATE, 1, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
+    else if (gpt <= 2) launch_quantize_inst<ROTATE, 2, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
+    else if (gpt <= 4) launch_quantize_inst<ROTATE, 4, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
+    else if (gpt <= 6) launch_quantize_inst<ROTATE, 6, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
+    else launch_quantize_inst<ROTATE, 8, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
 }
 
 // Rotation keeps the row in LDS: K floats, above the 64 KiB default for the widest rows.
@@ -284,19 +444,23 @@ static sqap_status allow_rotation_lds(Kern kernel, size_t lds)
     return SQAP_OK;
 }
 
-template <int MODE>
+template <int MODE, int PRE>
 static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                         bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
-                                        hipStream_t st)
+                                        const PreArgs &pre, hipStream_t st)
 {
     const int gpt = (K / 8 + 255) / 256;
     if (rotate) {
-        const size_t lds = (size_t)K * sizeof(float);
-        sqap_status s = allow_rotation_lds(&quantize_rows_kernel<true, 8, MODE>, lds);
-        if (s != SQAP_OK) return s;
-        launch_quantize_gpt<true, MODE>(gpt, X, ldx, rows, M, K, lds, col_scales, Xq, sx, st);
+        if constexpr (PRE == kPreSwiglu) {
+            return fail(SQAP_EUNSUPPORTED, "rotation is not available behind the SwiGLU gate");
+        } else {
+            const size_t lds = (size_t)K * sizeof(float);
+            sqap_status s = allow_rotation_lds(&quantize_rows_kernel<true, 8, MODE, PRE>, lds);
+            if (s != SQAP_OK) return s;
+            launch_quantize_gpt<true, MODE, PRE>(gpt, X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
+        }
     } else {
-        launch_quantize_gpt<false, MODE>(gpt, X, ldx, rows, M, K, 0, col_scales, Xq, sx, st);
+        launch_quantize_gpt<false, MODE, PRE>(gpt, X, ldx, rows, M, K, 0, col_scales, Xq, sx, pre, st);
     }
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
@@ -305,15 +469,30 @@ static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int3
 sqap_status launch_quantize_rows(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                  bool rotate, uint8_t *Xq, __half *sx, hipStream_t st)
 {
-    return launch_quantize_mode<kPerRow>(X, ldx, rows, M, K, rotate, nullptr, Xq, sx, st);
+    return launch_quantize_mode<kPerRow, kPreNone>(X, ldx, rows, M, K, rotate, nullptr, Xq, sx, PreArgs{}, st);
 }
 
 sqap_status launch_quantize_rows_scaled(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                         bool rotate, bool folded, const __half *col_scales, uint8_t *Xq,
                                         __half *sx, hipStream_t st)
 {
-    if (folded) return launch_quantize_mode<kFolded>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, st);
-    return launch_quantize_mode<kChannelwise>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, st);
+    if (folded)
+        return launch_quantize_mode<kFolded, kPreNone>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, PreArgs{}, st);
+    return launch_quantize_mode<kChannelwise, kPreNone>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, PreArgs{}, st);
+}
+
+sqap_status launch_fused_quantize(int pre_op, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
+                                  bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
+                                  const PreArgs &pre, hipStream_t st)
+{
+    if (pre_op == kPreNorm) {
+        if (col_scales)
+            return launch_quantize_mode<kChannelwise, kPreNorm>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, pre, st);
+        return launch_quantize_mode<kPerRow, kPreNorm>(X, ldx, rows, M, K, rotate, nullptr, Xq, sx, pre, st);
+    }
+    if (col_scales)
+        return launch_quantize_mode<kChannelwise, kPreSwiglu>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, pre, st);
+    return launch_quantize_mode<kPerRow, kPreSwiglu>(X, ldx, rows, M, K, rotate, nullptr, Xq, sx, pre, st);
 }
 
 template <bool ROTATE>

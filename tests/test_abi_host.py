@@ -113,6 +113,30 @@ def test_attn_scores_validation():
     assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 7, 0, 4, p, None) == B.EUNSUPPORTED
 
 
+def test_glue_validation():
+    L = B.lib()
+    p = ctypes.c_void_p(4096)
+    f = ctypes.c_float
+    assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 64, None, None, f(1e-5), 0, None, None, None, p, p, None) == B.EINVAL
+    assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 64, None, p, f(-1.0), 0, None, None, None, p, p, None) == B.EINVAL
+    assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 64, None, p, f(1e-5), 0, None, None, None, None, None, None) == B.EINVAL
+    assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 60, None, p, f(1e-5), 0, None, None, None, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_rmsnorm_quantize_act(p, 96, None, 2, 96, None, p, f(1e-5), 1, None, None, None, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_rmsnorm_quantize_act(None, 64, None, 0, 64, None, None, f(0.0), 0, None, None, None, None, None, None) == B.OK
+    assert L.sqap_swiglu_quantize_act(p, 64, p, 32, 2, 64, None, None, p, p, None) == B.EINVAL
+    assert L.sqap_swiglu_quantize_act(p, 64, None, 64, 2, 64, None, None, p, p, None) == B.EINVAL
+    assert L.sqap_swiglu_quantize_act(p, 64, ctypes.c_void_p(4100), 64, 2, 64, None, None, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_rope(p, 64, p, 2, 2, 33, ctypes.c_double(1e4), None) == B.EINVAL
+    assert L.sqap_rope(p, 32, p, 2, 2, 32, ctypes.c_double(1e4), None) == B.EINVAL
+    assert L.sqap_rope(None, 64, None, 0, 2, 32, ctypes.c_double(1e4), None) == B.OK
+    assert L.sqap_attention(p, 64, p, 64, p, 64, 5, 4, 1, 64, p, 64, None) == B.EINVAL
+    assert L.sqap_attention(p, 64, p, 64, p, 64, 4, 4, 1, 48, p, 64, None) == B.EINVAL       # pitch below H * d
+    assert L.sqap_attention(p, 48, p, 48, p, 48, 4, 4, 1, 48, p, 48, None) == B.EUNSUPPORTED
+    assert L.sqap_attention(None, 64, None, 64, None, 64, 0, 4, 1, 64, None, 64, None) == B.OK
+    assert L.sqap_residual_add(p, 64, p, 32, 2, 64, None) == B.EINVAL
+    assert L.sqap_residual_add(p, 68, p, 68, 2, 68, None) == B.EUNSUPPORTED
+
+
 def test_selftest_dispatch_validation():
     assert B.lib().sqap_selftest_dispatch(None, None) == B.EINVAL
 

@@ -1,0 +1,199 @@
+"""GPU parity of the decoder glue (RMSNorm / SwiGLU fused into the quantizer, rotary embedding,
+attention, residual add) against the CPU oracle, through the C-ABI."""
+import numpy as np
+import pytest
+
+from paper_2509_09090_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _acts(rng, M, K, outliers=True):
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    if outliers and K >= 100:
+        ch = rng.choice(K, size=max(1, K // 100), replace=False)
+        X[:, ch] *= 30.0
+    return X.astype(np.float16)
+
+
+@pytest.mark.parametrize("M,K,rotate,gather,with_delta,channelwise", [
+    (5, 64, False, False, False, False), (148, 4096, False, True, True, False), (37, 11008, False, False, True, False),
+    (33, 512, True, False, False, False), (148, 4096, True, True, True, False), (20, 2056, False, False, True, True),
+    (64, 4096, True, False, False, True), (3, 16384, False, False, True, False)])
+def test_rmsnorm_quantize(G, oracle, M, K, rotate, gather, with_delta, channelwise):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(M * 13 + K)
+    src_rows = M + 9 if gather else M
+    X = _acts(rng, src_rows, K)
+    rows = np.sort(rng.choice(src_rows, size=M, replace=False)).astype(np.int32) if gather else None
+    delta = _acts(rng, M, K, outliers=False) if with_delta else None
+    gamma = (1 + 0.2 * rng.standard_normal(K)).astype(np.float16)
+    eps = 1e-5
+    xs_o, y_o = oracle.rmsnorm_rows(X, gamma, eps, rows=rows, delta=delta)
+    cs = None
+    if channelwise:
+        cs = oracle.channel_scales(y_o, rotate=rotate)
+        q_o, s_o = oracle.quantize_rows_channelwise(y_o, cs, rotate=rotate)
+    else:
+        q_o, s_o, _ = oracle.quantize_rows(y_o, rotate=rotate)
+    dev = lambda a: None if a is None else G.to_dev(a)
+    Xq = torch.zeros((M, K // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    xs = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    y = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    B.sqap_rmsnorm_quantize_act(dev(X), dev(rows), dev(gamma), eps, Xq, sx, delta=dev(delta),
+                                flags=B.ROTATE_HADAMARD if rotate else 0, col_scales=dev(cs), xsum_out=xs, y_out=y)
+    torch.cuda.synchronize()
+    assert np.array_equal(xs.cpu().numpy().view(np.uint16), xs_o.view(np.uint16))
+    assert np.array_equal(y.cpu().numpy().view(np.uint16), y_o.view(np.uint16))
+    assert np.array_equal(sx.cpu().numpy().view(np.uint16), np.asarray(s_o).view(np.uint16))
+    assert np.array_equal(Xq.cpu().numpy(), q_o)
+    # the half-precision result alone (no quantizer), and the quantizer without the optional outputs
+    y2 = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    B.sqap_rmsnorm_quantize_act(dev(X), dev(rows), dev(gamma), eps, None, None, delta=dev(delta), y_out=y2)
+    Xq2 = torch.zeros_like(Xq)
+    B.sqap_rmsnorm_quantize_act(dev(X), dev(rows), dev(gamma), eps, Xq2, sx, delta=dev(delta),
+                                flags=B.ROTATE_HADAMARD if rotate else 0, col_scales=dev(cs))
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y) and torch.equal(Xq2, Xq)
+
+
+def test_rmsnorm_sum_of_squares_is_exact_on_the_device(G, oracle):
+    """Rows whose squares span 80 binary orders and rows of extreme values: the exact sum decides r."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    K = 4096
+    rng = np.random.default_rng(77)
+    rows = []
+    r = np.full(K, 2.0 ** -24, dtype=np.float16)
+    r[7] = np.float16(65504.0)
+    rows.append(r)
+    rows.append(np.full(K, 2.0 ** -24, dtype=np.float16))
+    rows.append(np.full(K, 65504.0, dtype=np.float16))
+    rows.append(np.zeros(K, dtype=np.float16))
+    for _ in range(12):
+        r = (rng.standard_normal(K) * np.exp(rng.uniform(-15, 8, K))).astype(np.float64)
+        rows.append(np.clip(r, -60000, 60000).astype(np.float16))
+    X = np.stack(rows)
+    gamma = np.ones(K, np.float16)
+    for eps in (0.0, 1e-6):
+        if eps == 0.0:
+            Xe = np.delete(X, 3, axis=0)          # a zero row with eps = 0 has no finite norm
+        else:
+            Xe = X
+        _, y_o = oracle.rmsnorm_rows(Xe, gamma, eps)
+        y = torch.zeros(Xe.shape, dtype=torch.float16, device="cuda")
+        B.sqap_rmsnorm_quantize_act(G.to_dev(Xe), None, G.to_dev(gamma), eps, None, None, y_out=y)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), y_o.view(np.uint16)), eps
+
+
+def test_silu_of_every_half_value(G, oracle):
+    """silu is a function of one half value: all 63488 finite ones, against the oracle, bit for bit."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    bits = np.arange(65536, dtype=np.uint16)
+    g = bits.view(np.float16)
+    g = g[np.isfinite(g)]
+    assert len(g) == 63488
+    g = g.reshape(62, 1024)
+    Gm = np.concatenate([g, g, g])
+    Um = np.concatenate([np.ones_like(g), np.full_like(g, 0.333), np.full_like(g, -7.5)])
+    h_o = oracle.swiglu(Gm, Um)
+    h = torch.zeros(Gm.shape, dtype=torch.float16, device="cuda")
+    B.sqap_swiglu_quantize_act(G.to_dev(Gm), G.to_dev(Um), None, None, h_out=h)
+    torch.cuda.synchronize()
+    got = h.cpu().numpy()
+    assert np.array_equal(got.view(np.uint16), h_o.view(np.uint16)), int(np.count_nonzero(got.view(np.uint16) != h_o.view(np.uint16)))
+
+
+@pytest.mark.parametrize("M,F,channelwise,sliced", [(148, 11008, False, True), (7, 64, False, False), (33, 2056, True, False),
+                                                     (8, 11008, False, True)])
+def test_swiglu_quantize(G, oracle, M, F, channelwise, sliced):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(M + F)
+    GU = (rng.standard_normal((M, 2 * F)) * 2.5).astype(np.float16)     # gate | up as a fused linear writes them
+    Gn, Un = GU[:, :F], GU[:, F:]
+    h_o = oracle.swiglu(Gn, Un)
+    cs = None
+    if channelwise:
+        cs = oracle.channel_scales(h_o)
+        q_o, s_o = oracle.quantize_rows_channelwise(h_o, cs)
+    else:
+        q_o, s_o, _ = oracle.quantize_rows(h_o)
+    gu = G.to_dev(GU)
+    if sliced:
+        Gd, Ud = gu[:, :F], gu[:, F:]
+    else:
+        Gd, Ud = G.to_dev(np.ascontiguousarray(Gn)), G.to_dev(np.ascontiguousarray(Un))
+    Xq = torch.zeros((M, F // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    h = torch.zeros((M, F), dtype=torch.float16, device="cuda")
+    B.sqap_swiglu_quantize_act(Gd, Ud, Xq, sx, col_scales=None if cs is None else G.to_dev(cs), h_out=h)
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy().view(np.uint16), h_o.view(np.uint16))
+    assert np.array_equal(sx.cpu().numpy().view(np.uint16), np.asarray(s_o).view(np.uint16))
+    assert np.array_equal(Xq.cpu().numpy(), q_o)
+
+
+@pytest.mark.parametrize("S,H,d", [(276, 32, 128), (5, 3, 16), (148, 4, 64)])
+def test_rope(G, oracle, S, H, d):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(S + H + d)
+    width = 3 * H * d                                           # rotated where it lies inside a fused q|k|v row
+    Y = rng.standard_normal((S, width)).astype(np.float16)
+    pos = np.sort(rng.choice(400, size=S, replace=False)).astype(np.int32)
+    want = Y.copy()
+    want[:, :H * d] = oracle.rope(Y[:, :H * d].reshape(S, H, d), pos).reshape(S, H * d)
+    want[:, H * d:2 * H * d] = oracle.rope(Y[:, H * d:2 * H * d].reshape(S, H, d), pos).reshape(S, H * d)
+    y = G.to_dev(Y)
+    p = G.to_dev(pos)
+    B.sqap_rope(y[:, :H * d], p, H, d)
+    B.sqap_rope(y[:, H * d:2 * H * d], p, H, d)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    assert np.array_equal(got[:, 2 * H * d:].view(np.uint16), Y[:, 2 * H * d:].view(np.uint16))      # v untouched
+    g, w = got.astype(np.float64), want.astype(np.float64)
+    assert np.all(np.abs(g - w) <= 1e-2 + 1e-3 * np.abs(w))
+    assert np.count_nonzero(got.view(np.uint16) != want.view(np.uint16)) <= got.size // 200          # both are binary64 -> half
+
+
+@pytest.mark.parametrize("Sq,Sk,H,d", [(276, 276, 32, 128), (148, 148, 8, 128), (1, 149, 32, 128), (8, 156, 4, 64),
+                                       (70, 70, 3, 16), (33, 97, 2, 32), (1, 1, 1, 16)])
+def test_attention(G, oracle, Sq, Sk, H, d):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(Sq * 3 + Sk + H + d)
+    width = H * d
+    QKV = rng.standard_normal((Sk, 3 * width)).astype(np.float16)
+    QKV[:, :width] *= 2.0                                      # sharper softmax rows
+    Qn = QKV[Sk - Sq:, :width].reshape(Sq, H, d)
+    Kn = QKV[:, width:2 * width].reshape(Sk, H, d)
+    Vn = QKV[:, 2 * width:].reshape(Sk, H, d)
+    want = oracle.attention(Qn, Kn, Vn).reshape(Sq, width)
+    qkv = G.to_dev(QKV)
+    O = torch.full((Sq, width), float("nan"), dtype=torch.float16, device="cuda")
+    B.sqap_attention(qkv[Sk - Sq:, :width], qkv[:, width:2 * width], qkv[:, 2 * width:], H, d, O)
+    torch.cuda.synchronize()
+    assert G.assert_fp16_close(O.cpu().numpy(), want) >= 0
+
+
+def test_residual_add(G, oracle):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(4)
+    X = _acts(rng, 37, 4096)
+    D = _acts(rng, 37, 4096, outliers=False)
+    x = G.to_dev(X)
+    B.sqap_residual_add(x, G.to_dev(D))
+    torch.cuda.synchronize()
+    assert np.array_equal(x.cpu().numpy().view(np.uint16), oracle.residual_add(X, D).view(np.uint16))

@@ -855,3 +855,9 @@ def test_attention_closed_forms_and_matrix_form(oracle):
     want = np.einsum("hst,thi->shi", P, V.astype(np.float64))
     got = oracle.attention(Q, K, V).astype(np.float64)
     assert np.all(np.abs(got - want) <= 2.0 ** -11 * np.abs(want) + 1e-7)
+    # fewer queries than keys: they are the last positions, so the result is the tail of the square case
+    tail = oracle.attention(Q[-3:], K, V)
+    assert np.array_equal(tail.view(np.uint16), oracle.attention(Q, K, V)[-3:].view(np.uint16))
+    assert np.all(np.abs(tail.astype(np.float64) - want[-3:]) <= 2.0 ** -11 * np.abs(want[-3:]) + 1e-7)
+    with pytest.raises(ValueError):
+        oracle.attention(Q, K[:5], V[:5])
