@@ -298,7 +298,8 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
  * sqap_quantize_act (col_scales NULL: one scale per token, written to sx) or as
  * by sqap_quantize_act_channelwise (col_scales given).  flags as there.  Rows
  * must be finite.  delta, xsum_out, y_out: [M, K] dense halves, 16-byte
- * aligned; gamma: [K].  EINVAL: null X/gamma, neither Xq nor y_out, eps < 0.
+ * aligned; gamma: [K].  xsum_out may be X itself when rows is NULL and
+ * ldx = K (update in place).  EINVAL: null X/gamma, neither Xq nor y_out, eps < 0.
  *
  * sqap_swiglu_quantize_act: h = binary16(silu(g) * float(u)) elementwise over
  * G, U [M, F] (pitches ldg, ldu), silu(g) = (float)(g / (1 + exp(-g)))
@@ -325,7 +326,9 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
  * Sk - Sq + i of the key sequence and sees keys 0 .. Sk - Sq + i:
  *   o[i,h,:] = sum_t softmax_t((q[i,h,:] . k[t,h,:]) / sqrt(d)) v[t,h,:]
  * in binary32 (online softmax over tiles of 64 keys), rounded to half.
- * Q [Sq, H*d], K, V [Sk, H*d], O [Sq, H*d] with row pitches in elements.
+ * Q [Sq, H*d], K, V [Sk, H*d], O [Sq, H*d] with row pitches in elements; a
+ * batch of independent sequences is a stack of such row blocks (sequence b
+ * owns rows b*Sq .. of Q and O and rows b*Sk .. of K and V).
  * EINVAL: null pointer, Sk < Sq, pitch < H*d.  EUNSUPPORTED: d not in
  * {16, 32, 64, 128}, operands or pitches not 16-byte aligned.
  *
@@ -335,8 +338,8 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
 sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d,
                       double base, void *stream);
 sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk,
-                           const sqap_f16 *V, int64_t ldv, int32_t Sq, int32_t Sk, int32_t H, int32_t d,
-                           sqap_f16 *O, int64_t ldo, void *stream);
+                           const sqap_f16 *V, int64_t ldv, int32_t batch, int32_t Sq, int32_t Sk, int32_t H,
+                           int32_t d, sqap_f16 *O, int64_t ldo, void *stream);
 sqap_status sqap_residual_add(sqap_f16 *X, int64_t ldx, const sqap_f16 *delta, int64_t ldd, int32_t M,
                               int32_t K, void *stream);
 

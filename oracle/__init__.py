@@ -343,3 +343,42 @@ def residual_add(X, delta):
     if rc:
         raise ValueError("oracle_residual_add: %d" % rc)
     return out
+
+
+def decoder_layer(x, pending, pos, batch, weights, gamma_attn, gamma_mlp, n_heads, head_dim, eps=1e-5,
+                  rotate=False, attn_override=None):
+    """One pre-normalisation Llama layer as a chain of the functions above; every stage is returned.
+
+    x [M, hidden] fp16 residual stream, pending [M, hidden] or None, pos [M] positions, batch
+    sequences of M / batch rows.  weights: dict name -> (packed int4 [N, K/2], scales [N]) for
+    'qkv' (N = 3 hidden), 'o', 'gate_up' (N = 2 ffn), 'down'.  attn_override replaces the attention
+    output (lets a test continue from another implementation's result).
+    """
+    M, hidden = x.shape
+    S = M // batch
+    st = {}
+    st["x1"], y1 = rmsnorm_rows(x, gamma_attn, eps, delta=pending)
+    q1, s1, _ = quantize_rows(y1, rotate=rotate)
+    st["q1"], st["s1"] = q1, s1
+    st["qkv"], _ = w4a4_linear(q1, s1, *weights["qkv"])
+    qkv = st["qkv"]
+    q = rope(qkv[:, :hidden].reshape(M, n_heads, head_dim), pos)
+    k = rope(qkv[:, hidden:2 * hidden].reshape(M, n_heads, head_dim), pos)
+    v = np.ascontiguousarray(qkv[:, 2 * hidden:]).reshape(M, n_heads, head_dim)
+    st["q_rot"], st["k_rot"] = q.reshape(M, hidden), k.reshape(M, hidden)
+    a = np.concatenate([attention(q[b * S:(b + 1) * S], k[b * S:(b + 1) * S], v[b * S:(b + 1) * S])
+                        for b in range(batch)]).reshape(M, hidden)
+    st["attn"] = a
+    if attn_override is not None:
+        a = attn_override
+    q2, s2, _ = quantize_rows(a)
+    st["o"], _ = w4a4_linear(q2, s2, *weights["o"])
+    st["x2"], y2 = rmsnorm_rows(st["x1"], gamma_mlp, eps, delta=st["o"])
+    q3, s3, _ = quantize_rows(y2)
+    st["gu"], _ = w4a4_linear(q3, s3, *weights["gate_up"])
+    ffn = st["gu"].shape[1] // 2
+    h = swiglu(st["gu"][:, :ffn], st["gu"][:, ffn:])
+    q4, s4, _ = quantize_rows(h)
+    st["hq"], st["sh"] = q4, s4
+    st["d"], _ = w4a4_linear(q4, s4, *weights["down"])
+    return st

@@ -70,7 +70,7 @@ def lib():
         L.sqap_rmsnorm_quantize_act.argtypes = [vp, i64, vp, i32, i32, vp, vp, ctypes.c_float, u32, vp, vp, vp, vp, vp, vp]
         L.sqap_swiglu_quantize_act.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
         L.sqap_rope.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp]
-        L.sqap_attention.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, vp, i64, vp]
+        L.sqap_attention.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sqap_residual_add.argtypes = [vp, i64, vp, i64, i32, i32, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
         L.sqap_weight_pack.argtypes = [vp, vp, i32, i32, ctypes.POINTER(vp), vp]
@@ -244,10 +244,11 @@ def sqap_rope(X, pos, H, d, base=10000.0, stream=None):
     _check(lib().sqap_rope(_ptr(X), X.stride(0), _ptr(pos), X.shape[0], H, d, base, _stream(stream)))
 
 
-def sqap_attention(Q, K, V, H, d, O, stream=None):
-    """Causal attention; Q [Sq, H*d], K, V [Sk, H*d], O [Sq, H*d] (row pitches from the strides)."""
-    _check(lib().sqap_attention(_ptr(Q), Q.stride(0), _ptr(K), K.stride(0), _ptr(V), V.stride(0), Q.shape[0],
-                                K.shape[0], H, d, _ptr(O), O.stride(0), _stream(stream)))
+def sqap_attention(Q, K, V, H, d, O, batch=1, stream=None):
+    """Causal attention; Q, O [batch*Sq, H*d], K, V [batch*Sk, H*d] (row pitches from the strides)."""
+    _check(lib().sqap_attention(_ptr(Q), Q.stride(0), _ptr(K), K.stride(0), _ptr(V), V.stride(0), batch,
+                                Q.shape[0] // batch, K.shape[0] // batch, H, d, _ptr(O), O.stride(0),
+                                _stream(stream)))
 
 
 def sqap_residual_add(X, delta, stream=None):

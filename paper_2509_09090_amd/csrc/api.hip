@@ -273,23 +273,23 @@ sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, in
 }
 
 sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk, const sqap_f16 *V,
-                           int64_t ldv, int32_t Sq, int32_t Sk, int32_t H, int32_t d, sqap_f16 *O, int64_t ldo,
-                           void *stream)
+                           int64_t ldv, int32_t batch, int32_t Sq, int32_t Sk, int32_t H, int32_t d, sqap_f16 *O,
+                           int64_t ldo, void *stream)
 {
-    if (Sq < 0 || Sk < Sq || H <= 0 || d <= 0)
-        return fail(SQAP_EINVAL, "sqap_attention: Sq %d, Sk %d (>= Sq), H %d, d %d", Sq, Sk, H, d);
+    if (batch < 0 || Sq < 0 || Sk < Sq || H <= 0 || d <= 0)
+        return fail(SQAP_EINVAL, "sqap_attention: batch %d, Sq %d, Sk %d (>= Sq), H %d, d %d", batch, Sq, Sk, H, d);
     const int64_t width = (int64_t)H * d;
     if (ldq < width || ldk < width || ldv < width || ldo < width)
         return fail(SQAP_EINVAL, "sqap_attention: a pitch is below H * d");
     if (d != 16 && d != 32 && d != 64 && d != 128)
         return fail(SQAP_EUNSUPPORTED, "sqap_attention: head size %d (16, 32, 64 or 128)", d);
-    if (H > 65535) return fail(SQAP_EUNSUPPORTED, "sqap_attention: H = %d", H);
-    if (Sq == 0) return SQAP_OK;
+    if (batch > 65535) return fail(SQAP_EUNSUPPORTED, "sqap_attention: batch = %d", batch);
+    if (Sq == 0 || batch == 0) return SQAP_OK;
     if (!Q || !K || !V || !O) return fail(SQAP_EINVAL, "sqap_attention: null pointer");
     if (((ldq | ldk | ldv | ldo) & 7) || !aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O))
         return fail(SQAP_EUNSUPPORTED, "sqap_attention: operands and pitches must be 16-byte aligned");
     return launch_attention(reinterpret_cast<const __half *>(Q), ldq, reinterpret_cast<const __half *>(K), ldk,
-                            reinterpret_cast<const __half *>(V), ldv, Sq, Sk, H, d, reinterpret_cast<__half *>(O), ldo,
+                            reinterpret_cast<const __half *>(V), ldv, batch, Sq, Sk, H, d, reinterpret_cast<__half *>(O), ldo,
                             as_stream(stream));
 }
 

@@ -42,7 +42,8 @@ sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H,
 }
 
 // Causal attention.  Query i (of Sq) sits at sequence position Sk - Sq + i and sees keys 0 ..
-// Sk - Sq + i.  One workgroup per (head, block of 32 queries); keys and values pass through LDS
+// Sk - Sq + i.  A batch of sequences is a stack of row blocks (Sq rows of Q and O, Sk rows of K
+// and V per sequence).  One workgroup per (head, block of 32 queries, sequence); keys and values pass through LDS
 // in tiles of 64.  Thread t works for query t/8: in the score phase on keys 8(t%8) .. +7 of the
 // tile, in the output phase on the D/8 consecutive head-dimension columns from (t%8) D/8 on.
 // Running maximum m, running sum l and the output row are
@@ -63,6 +64,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
     __shared__ float ps[kAttQ * (kAttK + 1)];
     const int t = threadIdx.x, h = blockIdx.x, q0 = blockIdx.y * kAttQ;
     const int qi = t >> 3, sub = t & 7;
+    Q += (int64_t)blockIdx.z * Sq * ldq;
+    O += (int64_t)blockIdx.z * Sq * ldo;
+    Kc += (int64_t)blockIdx.z * Sk * ldk;
+    V += (int64_t)blockIdx.z * Sk * ldv;
     const int shift = Sk - Sq;                   // query i sees keys <= i + shift
     const float inv_sqrt_d = 1.0f / sqrtf((float)D);
 
@@ -164,10 +169,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
 }
 
 sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int64_t ldk, const __half *V,
-                             int64_t ldv, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st)
+                             int64_t ldv, int batch, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st)
 {
-    if (Sq == 0) return SQAP_OK;
-    const dim3 grid(H, (Sq + kAttQ - 1) / kAttQ);
+    if (Sq == 0 || batch == 0) return SQAP_OK;
+    const dim3 grid(H, (Sq + kAttQ - 1) / kAttQ, batch);
 #define SQAP_ATT_CASE(DD)                                                                                          \
     case DD:                                                                                                       \
         hipLaunchKernelGGL(attention_kernel<DD>, grid, dim3(256), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo); \

@@ -268,7 +268,7 @@ __device__ __forceinline__ void load_col_scales(const __half *col_scales, int g,
 // GPT = groups per thread the instance is compiled for (registers, hence occupancy).
 // PRE selects an operation applied to the row between its read and the quantizer (see above).
 template <bool ROTATE, int GPT, int MODE, int PRE>
-__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *__restrict__ X, int64_t ldx,
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int64_t ldx,      // may alias pre.xsum_out
                                                             const int32_t *__restrict__ rows, int K,
                                                             const __half *__restrict__ col_scales,
                                                             uint8_t *__restrict__ Xq,

@@ -1,0 +1,79 @@
+"""One Llama-shaped decoder layer as a sequence of library calls (argument marshalling only: every
+step runs in the HIP kernels).  The paper runs its W4A4 linears inside such a decoder
+(Implementation Details; Section 3.3) without restating it; the order of operations here is the
+published pre-normalisation layer:
+
+    y1 = RMSNorm(x + pending) -> int4        sqap_rmsnorm_quantize_act   (also writes x + pending)
+    q|k|v = W_qkv y1                         sqap_w4a4_linear            (one GEMM, N = 3 * hidden)
+    q, k <- rotary(q, k)                     sqap_rope
+    a = causal attention(q, k, v)            sqap_attention
+    o = W_o quant(a)                         sqap_quantize_act + sqap_w4a4_linear
+    y2 = RMSNorm(x + o) -> int4              sqap_rmsnorm_quantize_act   (residual add fused)
+    g|u = W_gu y2                            sqap_w4a4_linear            (N = 2 * ffn)
+    h = silu(g) * u -> int4                  sqap_swiglu_quantize_act
+    d = W_down h                             sqap_w4a4_linear
+The last residual add (x + d) is left pending and fused into the next layer's first call.
+"""
+import torch
+
+from . import binding as B
+
+
+class LayerWeights:
+    """Packed weights and norm gains of one layer (device resident)."""
+
+    def __init__(self, qkv, o, gate_up, down, gamma_attn, gamma_mlp):
+        self.qkv, self.o, self.gate_up, self.down = qkv, o, gate_up, down
+        self.gamma_attn, self.gamma_mlp = gamma_attn, gamma_mlp
+
+    def free(self):
+        for w in (self.qkv, self.o, self.gate_up, self.down):
+            w.free()
+
+
+class LayerBuffers:
+    """Scratch tensors for up to max_rows token rows of one layer call (reused by every layer)."""
+
+    def __init__(self, max_rows, hidden, ffn, device="cuda"):
+        f16, u8 = torch.float16, torch.uint8
+        self.hidden, self.ffn = hidden, ffn
+        self.xq = torch.empty((max_rows, hidden // 2), dtype=u8, device=device)
+        self.sx = torch.empty((max_rows,), dtype=f16, device=device)
+        self.qkv = torch.empty((max_rows, 3 * hidden), dtype=f16, device=device)
+        self.attn = torch.empty((max_rows, hidden), dtype=f16, device=device)
+        self.o = torch.empty((max_rows, hidden), dtype=f16, device=device)
+        self.gu = torch.empty((max_rows, 2 * ffn), dtype=f16, device=device)
+        self.hq = torch.empty((max_rows, ffn // 2), dtype=u8, device=device)
+        self.sh = torch.empty((max_rows,), dtype=f16, device=device)
+        nbytes = max(B.sqap_workspace_bytes(max_rows, n, k)
+                     for (n, k) in ((3 * hidden, hidden), (hidden, hidden), (2 * ffn, hidden), (hidden, ffn)))
+        self.ws = torch.zeros((max(nbytes, 256),), dtype=u8, device=device)
+
+
+def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_out, eps=1e-5, rows=None,
+                  rotate=False, stream=None):
+    """Runs one layer on M token rows (batch sequences of M / batch tokens each).
+
+    x: residual stream [*, hidden] fp16 (rows picks the M rows when given: the token gather is fused);
+    pending: [M, hidden] update not yet added to x, or None; pos: [M] int32 positions.
+    x_out [M, hidden] receives the residual stream after the attention block, d_out [M, hidden] the
+    feed-forward output still to be added to it (the next call's `pending`).
+    """
+    M = pos.numel()
+    hidden = buf.hidden
+    flags = B.ROTATE_HADAMARD if rotate else 0
+    xq, sx, qkv, attn, o = buf.xq[:M], buf.sx[:M], buf.qkv[:M], buf.attn[:M], buf.o[:M]
+    gu, hq, sh = buf.gu[:M], buf.hq[:M], buf.sh[:M]
+    B.sqap_rmsnorm_quantize_act(x, rows, w.gamma_attn, eps, xq, sx, delta=pending, flags=flags, xsum_out=x_out,
+                                stream=stream)
+    B.sqap_w4a4_linear(xq, sx, w.qkv, qkv, None, buf.ws, stream=stream)
+    B.sqap_rope(qkv[:, :hidden], pos, n_heads, head_dim, stream=stream)
+    B.sqap_rope(qkv[:, hidden:2 * hidden], pos, n_heads, head_dim, stream=stream)
+    B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
+                     batch=batch, stream=stream)
+    B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
+    B.sqap_w4a4_linear(xq, sx, w.o, o, None, buf.ws, stream=stream)
+    B.sqap_rmsnorm_quantize_act(x_out, None, w.gamma_mlp, eps, xq, sx, delta=o, xsum_out=x_out, stream=stream)
+    B.sqap_w4a4_linear(xq, sx, w.gate_up, gu, None, buf.ws, stream=stream)
+    B.sqap_swiglu_quantize_act(gu[:, :buf.ffn], gu[:, buf.ffn:], hq, sh, stream=stream)
+    B.sqap_w4a4_linear(hq, sh, w.down, d_out, None, buf.ws, stream=stream)

@@ -129,10 +129,11 @@ def test_glue_validation():
     assert L.sqap_rope(p, 64, p, 2, 2, 33, ctypes.c_double(1e4), None) == B.EINVAL
     assert L.sqap_rope(p, 32, p, 2, 2, 32, ctypes.c_double(1e4), None) == B.EINVAL
     assert L.sqap_rope(None, 64, None, 0, 2, 32, ctypes.c_double(1e4), None) == B.OK
-    assert L.sqap_attention(p, 64, p, 64, p, 64, 5, 4, 1, 64, p, 64, None) == B.EINVAL
-    assert L.sqap_attention(p, 64, p, 64, p, 32, 4, 4, 1, 64, p, 64, None) == B.EINVAL       # pitch below H * d
-    assert L.sqap_attention(p, 48, p, 48, p, 48, 4, 4, 1, 48, p, 48, None) == B.EUNSUPPORTED
-    assert L.sqap_attention(None, 64, None, 64, None, 64, 0, 4, 1, 64, None, 64, None) == B.OK
+    assert L.sqap_attention(p, 64, p, 64, p, 64, 1, 5, 4, 1, 64, p, 64, None) == B.EINVAL
+    assert L.sqap_attention(p, 64, p, 64, p, 32, 1, 4, 4, 1, 64, p, 64, None) == B.EINVAL       # pitch below H * d
+    assert L.sqap_attention(p, 48, p, 48, p, 48, 1, 4, 4, 1, 48, p, 48, None) == B.EUNSUPPORTED
+    assert L.sqap_attention(None, 64, None, 64, None, 64, 2, 0, 4, 1, 64, None, 64, None) == B.OK
+    assert L.sqap_attention(p, 64, p, 64, p, 64, -1, 4, 4, 1, 64, p, 64, None) == B.EINVAL
     assert L.sqap_residual_add(p, 64, p, 32, 2, 64, None) == B.EINVAL
     assert L.sqap_residual_add(p, 68, p, 68, 2, 68, None) == B.EUNSUPPORTED
 

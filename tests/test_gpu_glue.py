@@ -187,6 +187,26 @@ def test_attention(G, oracle, Sq, Sk, H, d):
     assert G.assert_fp16_close(O.cpu().numpy(), want) >= 0
 
 
+def test_attention_batch(G, oracle):
+    """Sequences stacked as row blocks: each gets what a single call gives."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    nb, S, H, d = 5, 41, 3, 64
+    rng = np.random.default_rng(12)
+    width = H * d
+    QKV = rng.standard_normal((nb * S, 3 * width)).astype(np.float16)
+    qkv = G.to_dev(QKV)
+    O = torch.full((nb * S, width), float("nan"), dtype=torch.float16, device="cuda")
+    B.sqap_attention(qkv[:, :width], qkv[:, width:2 * width], qkv[:, 2 * width:], H, d, O, batch=nb)
+    torch.cuda.synchronize()
+    got = O.cpu().numpy()
+    for b in range(nb):
+        blk = QKV[b * S:(b + 1) * S]
+        want = oracle.attention(blk[:, :width].reshape(S, H, d), blk[:, width:2 * width].reshape(S, H, d),
+                                blk[:, 2 * width:].reshape(S, H, d)).reshape(S, width)
+        assert G.assert_fp16_close(got[b * S:(b + 1) * S], want) >= 0
+
+
 def test_residual_add(G, oracle):
     import torch
     from paper_2509_09090_amd import binding as B
@@ -197,3 +217,55 @@ def test_residual_add(G, oracle):
     B.sqap_residual_add(x, G.to_dev(D))
     torch.cuda.synchronize()
     assert np.array_equal(x.cpu().numpy().view(np.uint16), oracle.residual_add(X, D).view(np.uint16))
+
+
+def _layer_case(oracle, G, seed, hidden, H, d, F, batch, S, rotate):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    from paper_2509_09090_amd import decoder
+    rng = np.random.default_rng(seed)
+    M = batch * S
+    x = _acts(rng, M, hidden)
+    pend = (0.5 * rng.standard_normal((M, hidden))).astype(np.float16)
+    pos = np.tile(np.arange(S) * 2 + 1, batch).astype(np.int32)        # pruned sequences keep their old positions
+    ws, packed = {}, {}
+    for name, (N, K) in dict(qkv=(3 * hidden, hidden), o=(hidden, hidden), gate_up=(2 * F, hidden), down=(hidden, F)).items():
+        W = (rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float16)
+        q, s, _ = oracle.quantize_rows(W, rotate=rotate and name == "qkv")
+        ws[name] = (q, s)
+        packed[name] = B.sqap_weight_pack(G.to_dev(q), G.to_dev(s))
+    g1 = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16)
+    g2 = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16)
+    w = decoder.LayerWeights(packed["qkv"], packed["o"], packed["gate_up"], packed["down"], G.to_dev(g1), G.to_dev(g2))
+    return x, pend, pos, ws, w, g1, g2, M
+
+
+@pytest.mark.parametrize("hidden,H,d,F,batch,S,rotate", [(256, 4, 64, 512, 2, 19, False), (512, 4, 128, 1024, 1, 70, True)])
+def test_decoder_layer(G, oracle, hidden, H, d, F, batch, S, rotate):
+    """One layer through decoder.layer_forward against the oracle's chain.  Everything up to the
+    rotary embedding is exact; attention is compared within the fp16 tolerance; the rest of the
+    layer is then continued on both sides from the DEVICE's attention output and is exact again."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    from paper_2509_09090_amd import decoder
+    x, pend, pos, ws, w, g1, g2, M = _layer_case(oracle, G, 21 + hidden, hidden, H, d, F, batch, S, rotate)
+    buf = decoder.LayerBuffers(M, hidden, F)
+    x_out = torch.zeros((M, hidden), dtype=torch.float16, device="cuda")
+    d_out = torch.zeros((M, hidden), dtype=torch.float16, device="cuda")
+    decoder.layer_forward(w, buf, G.to_dev(x), G.to_dev(pend), G.to_dev(pos), batch, H, d, x_out, d_out, rotate=rotate)
+    torch.cuda.synchronize()
+    attn_dev = buf.attn[:M].cpu().numpy()
+    qkv_dev = buf.qkv[:M].cpu().numpy()
+    st = oracle.decoder_layer(x, pend, pos, batch, ws, g1, g2, H, d, rotate=rotate, attn_override=attn_dev)
+    # value part of the fused q|k|v output is untouched by the rotation: exact
+    assert np.array_equal(qkv_dev[:, 2 * hidden:].view(np.uint16), st["qkv"][:, 2 * hidden:].view(np.uint16))
+    assert G.assert_fp16_close(qkv_dev[:, :hidden], st["q_rot"]) >= 0
+    assert G.assert_fp16_close(qkv_dev[:, hidden:2 * hidden], st["k_rot"]) >= 0
+    # the device's attention is within tolerance of the oracle's on the oracle's own q, k, v ...
+    assert G.assert_fp16_close(attn_dev, st["attn"]) >= 0
+    # ... and from the device's attention output on, both sides agree bit for bit
+    assert np.array_equal(x_out.cpu().numpy().view(np.uint16), st["x2"].view(np.uint16))
+    assert np.array_equal(buf.hq[:M].cpu().numpy(), st["hq"])
+    assert np.array_equal(buf.sh[:M].cpu().numpy().view(np.uint16), np.asarray(st["sh"]).view(np.uint16))
+    assert G.assert_fp16_close(d_out.cpu().numpy(), st["d"]) == 0
+    w.free()
