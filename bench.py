@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-layers", action="store_true")
-    ap.add_argument("--only", default="", help="prefill|decode|calib: run just that loop --steps times (for profilers)")
+    ap.add_argument("--only", default="", help="prefill|decode|decoder|calib: run just that loop --steps times (for profilers)")
     return ap.parse_args()
 
 
@@ -297,6 +297,102 @@ def layer_leg(torch, B, wl, stack):
     return res
 
 
+def decoder_leg(torch, B, wl, dev, distinct_layers=8):
+    """Configuration 2 as a real forward: 32 Llama-2-7B-shaped layers at batch 1 (RMSNorm, fused q|k|v,
+    rotary embedding, causal attention, o, RMSNorm, fused gate|up, SwiGLU, down, residuals; every linear
+    W4A4), 276 tokens for two layers, then the retention score of the last text token from that layer's
+    own rotated queries and keys, top-k 256 -> 64 visual tokens, and 84 tokens for the other 30 layers.
+    Weights: 8 distinct random layers used in turn (0.8 GB, more than the caches hold)."""
+    from paper_2509_09090_amd import decoder
+    H, F, nh, hd = wl.HIDDEN, wl.FFN, wl.N_HEADS, wl.HEAD_DIM
+    S, nv, keep = wl.SEQ_LEN, wl.N_VISUAL, 64
+    Mk = S - nv + keep
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.BASE_SEED + 2)
+    mk = lambda N, K: quantize_and_pack(torch, B, (torch.randn((N, K), generator=g, device=dev,
+                                                               dtype=torch.float32) * 0.02).half())
+    gain = lambda: (1 + 0.1 * torch.randn((H,), generator=g, device=dev, dtype=torch.float32)).half()
+    layers = [decoder.LayerWeights(mk(3 * H, H), mk(H, H), mk(2 * F, H), mk(H, F), gain(), gain())
+              for _ in range(distinct_layers)]
+    buf = decoder.LayerBuffers(S, H, F, device=dev)
+    x0 = torch.randn((S, H), generator=g, device=dev, dtype=torch.float32)
+    ch = torch.randperm(H, generator=g, device=dev)[: wl.n_outliers_for(H)]
+    x0[:, ch] *= 30.0
+    x0 = x0.half()
+    x = torch.empty_like(x0)
+    xa, xb = torch.empty((S, H), dtype=torch.float16, device=dev), torch.empty((S, H), dtype=torch.float16, device=dev)
+    da, db = torch.empty_like(xa), torch.empty_like(xa)
+    pos_full = torch.arange(S, dtype=torch.int32, device=dev)
+    kdense = torch.empty((S, H), dtype=torch.float16, device=dev)
+    scores = torch.empty((1, nv), dtype=torch.float32, device=dev)
+    idx = torch.empty((1, keep), dtype=torch.int32, device=dev)
+    rows = torch.empty((Mk,), dtype=torch.int32, device=dev)
+
+    def forward():
+        x.copy_(x0)
+        # layers 0, 1 on the full sequence
+        decoder.layer_forward(layers[0], buf, x, None, pos_full, 1, nh, hd, xa, da)
+        decoder.layer_forward(layers[1 % distinct_layers], buf, xa, da, pos_full, 1, nh, hd, xb, db)
+        # retention score of the last (text) token from this layer's rotated q and k, then the kept rows
+        B.sqap_gather_rows(buf.qkv[:S, H:2 * H], pos_full, kdense)
+        B.sqap_attn_scores(buf.qkv[S - 1, :H], kdense.view(S, nh, hd), 0, nv, scores[0])
+        B.sqap_prune_rows(scores, keep, S, 0, idx, rows)
+        B.sqap_residual_add(xb, db)                       # the pending update lands before the gather
+        src, pend, use_rows, pos = xb, None, rows, rows
+        outs = ((xa[:Mk], da[:Mk]), (xb[:Mk], db[:Mk]))
+        for l in range(2, wl.N_LAYERS):
+            xo, do = outs[l & 1]
+            if use_rows is not None:                      # first pruned layer: gather fused into its first call
+                xo, do = xa[:Mk], da[:Mk]
+            decoder.layer_forward(layers[l % distinct_layers], buf, src, pend, pos, 1, nh, hd, xo, do, rows=use_rows)
+            src, pend, use_rows = xo, do, None
+        B.sqap_residual_add(src, pend)
+        return src
+
+    forward()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 3
+    e0.record()
+    for _ in range(reps):
+        forward()
+    e1.record()
+    torch.cuda.synchronize()
+    eager_us = e0.elapsed_time(e1) / reps * 1e3
+    res = {"us_forward_eager": eager_us, "launches": 2 * 11 + 4 + 30 * 11 + 2,
+           "note": "32 layers, 276 tokens for 2 layers then 84; includes the pruning step"}
+    # the same forward replayed from a HIP graph (no host launch cost)
+    try:
+        sidestream = torch.cuda.Stream()
+        sidestream.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(sidestream):
+            forward()
+        torch.cuda.current_stream().wait_stream(sidestream)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            out_ref = forward()
+        graph.replay()
+        torch.cuda.synchronize()
+        first = out_ref.clone()
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res["us_forward_graph"] = e0.elapsed_time(e1) / reps * 1e3
+        eager_out = forward().clone()
+        torch.cuda.synchronize()
+        res["graph_matches_eager"] = bool(torch.equal(first, eager_out) and torch.equal(out_ref, eager_out))
+    except Exception as exc:                              # report, never hide: the eager number stands on its own
+        res["graph_error"] = repr(exc)[:200]
+    ops = lambda M: 2.0 * M * (3 * H * H + H * H + 2 * F * H + H * F)
+    total_ops = 2 * ops(S) + 30 * ops(Mk)
+    res["TOPS_eager"] = total_ops / eager_us / 1e6
+    for lw in layers:
+        lw.free()
+    return res
+
+
 def selection_leg(torch, B, wl, dev, iters=50):
     """The full selection rule (top-k + projected ring + farthest point sampling) at configuration 3's
     batch: 16 observations of a 16 x 16 token grid, 64 attention tokens, ring radius 2, 128 kept."""
@@ -418,6 +514,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         return
+    if args.only == "decoder":
+        print(json.dumps(decoder_leg(torch, B, wl, dev)))
+        return
     if args.only == "decode":
         stack = Stack(torch, B, wl, dev)
         print(json.dumps(decode_leg(torch, B, wl, stack, steps_per_m=args.steps)))
@@ -471,6 +570,9 @@ def main():
         if not args.no_layers:
             out["layers"] = layer_leg(torch, B, wl, stack)
         del stack
+        torch.cuda.empty_cache()
+    if not args.no_layers:
+        out["decoder_forward"] = decoder_leg(torch, B, wl, dev)
     out["selection"] = selection_leg(torch, B, wl, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

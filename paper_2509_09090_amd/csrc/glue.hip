@@ -168,10 +168,166 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
     }
 }
 
+// The same attention on the matrix cores, for head sizes 64 and 128: one wavefront per (head, block of
+// 32 queries, sequence), key tiles of 32.  Everything is kept transposed so that no accumulator ever has
+// to change lanes:
+//   S^T = K Q^T      v_mfma_f32_32x32x8_f16 with A = key rows, B = query rows: lane l holds query l%32,
+//                    register i key 8(i/4) + 4(l/32) + i%4 of the tile;
+//   softmax          over registers and the two lane halves (one cross-lane exchange);
+//   O^T += V^T P^T   registers 4b .. 4b+3 of exp(S^T - m), converted to half, ARE the B operand of key
+//                    block b (keys 8b + 4(l/32) + 0..3); A = V^T comes from a transposed copy of the value
+//                    tile in LDS.
+// The running maximum, the running sum and the rescaling of O^T are per query, i.e. per lane.  The reduction
+// over the head dimension may visit it in any order as long as A and B agree: MFMA j takes elements
+// 16(j/2) + 8(l/32) + 4(j%2) + 0..3, so that each lane fetches 16 contiguous bytes per pair of MFMAs.
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+template <int D>
+__global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__restrict__ Q, int64_t ldq,
+                                                            const __half *__restrict__ Kc, int64_t ldk,
+                                                            const __half *__restrict__ V, int64_t ldv, int Sq, int Sk,
+                                                            int H, __half *__restrict__ O, int64_t ldo)
+{
+    constexpr int NP = D / 16;                   // 16-byte pieces of a head row per lane half
+    constexpr int CT = D / 32;                   // 32-column tiles of the head dimension
+    constexpr int VP = 36;                       // halves per row of the transposed value tile (8-byte aligned rows)
+    __shared__ __attribute__((aligned(16))) __half vt[D * VP];
+    const int l = threadIdx.x, c = l & 31, h = l >> 5;
+    const int head = blockIdx.x, q0 = blockIdx.y * 32;
+    Q += (int64_t)blockIdx.z * Sq * ldq + (int64_t)head * D;
+    O += (int64_t)blockIdx.z * Sq * ldo + (int64_t)head * D;
+    Kc += (int64_t)blockIdx.z * Sk * ldk + (int64_t)head * D;
+    V += (int64_t)blockIdx.z * Sk * ldv + (int64_t)head * D;
+    const int shift = Sk - Sq;
+    const int my_q = q0 + c;
+    const bool q_ok = my_q < Sq;
+    const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+    union Piece { uint4 u; v4h v[2]; };
+
+    Piece qf[NP];
+#pragma unroll
+    for (int m = 0; m < NP; ++m) {
+        qf[m].u = make_uint4(0u, 0u, 0u, 0u);
+        if (q_ok) qf[m].u = *reinterpret_cast<const uint4 *>(Q + (int64_t)my_q * ldq + 16 * m + 8 * h);
+    }
+    v16f ot[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) ot[ct][i] = 0.f;
+    float mrun = -INFINITY, lrun = 0.f;
+    const int last_key = min(Sk - 1, min(q0 + 31, Sq - 1) + shift);
+    const int n_tiles = last_key / 32 + 1;
+
+    Piece kf[NP];
+    auto load_keys = [&](int k0) {
+        const int key = k0 + c;
+#pragma unroll
+        for (int m = 0; m < NP; ++m) {
+            kf[m].u = make_uint4(0u, 0u, 0u, 0u);
+            if (key < Sk) kf[m].u = *reinterpret_cast<const uint4 *>(Kc + (int64_t)key * ldk + 16 * m + 8 * h);
+        }
+    };
+    // keys and values of the next tile are asked for while the current one is worked on: these rows were
+    // just written by another kernel and come from memory, two microseconds away
+    uint4 vraw[D / 16];
+    auto load_values = [&](int k0) {
+#pragma unroll
+        for (int n = 0; n < D / 16; ++n) {
+            const int u = l + 64 * n, key = u / (D / 8), dp = u % (D / 8);
+            vraw[n] = make_uint4(0u, 0u, 0u, 0u);
+            if (k0 + key < Sk) vraw[n] = *reinterpret_cast<const uint4 *>(V + (int64_t)(k0 + key) * ldv + dp * 8);
+        }
+    };
+    load_keys(0);
+    load_values(0);
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int k0 = kt * 32;
+        v16f st;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) st[i] = 0.f;
+#pragma unroll
+        for (int m = 0; m < NP; ++m) {
+            st = __builtin_amdgcn_mfma_f32_32x32x8f16(kf[m].v[0], qf[m].v[0], st, 0, 0, 0);
+            st = __builtin_amdgcn_mfma_f32_32x32x8f16(kf[m].v[1], qf[m].v[1], st, 0, 0, 0);
+        }
+        if (kt + 1 < n_tiles) load_keys(k0 + 32);           // in flight during the softmax and the second product
+        __builtin_amdgcn_wave_barrier();
+        // value tile, transposed into LDS (the previous tile's readers are this same wavefront: LDS operations
+        // of one wavefront complete in order)
+#pragma unroll
+        for (int n = 0; n < D / 16; ++n) {
+            const int u = l + 64 * n, key = u / (D / 8), dp = u % (D / 8);
+            const __half *hv = reinterpret_cast<const __half *>(&vraw[n]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vt[(dp * 8 + e) * VP + key] = hv[e];
+        }
+        if (kt + 1 < n_tiles) load_values(k0 + 32);
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int key = k0 + 8 * (i >> 2) + 4 * h + (i & 3);
+            const bool seen = q_ok && key < Sk && key <= my_q + shift;
+            st[i] = seen ? st[i] * inv_sqrt_d : -INFINITY;
+            tmax = fmaxf(tmax, st[i]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(mrun, tmax);
+        const float rescale = m_new == -INFINITY ? 1.f : expf(mrun - m_new);
+        float tsum = 0.f;
+        v4h pb[4];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pi = st[i] == -INFINITY ? 0.f : expf(st[i] - m_new);
+            tsum += pi;
+            pb[i >> 2][i & 3] = (_Float16)pi;
+        }
+        tsum += __shfl_xor(tsum, 32);
+        lrun = lrun * rescale + tsum;
+        mrun = m_new;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) ot[ct][i] *= rescale;
+        __builtin_amdgcn_wave_barrier();                     // the transposed tile is written (same wavefront, in order)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                union { uint2 u; v4h v; } va;
+                va.u = *reinterpret_cast<const uint2 *>(vt + (32 * ct + c) * VP + 8 * b + 4 * h);
+                ot[ct] = __builtin_amdgcn_mfma_f32_32x32x8f16(va.v, pb[b], ot[ct], 0, 0, 0);
+            }
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (q_ok) {
+        const float inv_l = 1.0f / lrun;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                union { uint2 u; __half2 p[2]; } out;
+                out.p[0] = __floats2half2_rn(ot[ct][4 * g] * inv_l, ot[ct][4 * g + 1] * inv_l);
+                out.p[1] = __floats2half2_rn(ot[ct][4 * g + 2] * inv_l, ot[ct][4 * g + 3] * inv_l);
+                *reinterpret_cast<uint2 *>(O + (int64_t)my_q * ldo + 32 * ct + 8 * g + 4 * h) = out.u;
+            }
+    }
+}
+
 sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int64_t ldk, const __half *V,
                              int64_t ldv, int batch, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st)
 {
     if (Sq == 0 || batch == 0) return SQAP_OK;
+    if (d == 64 || d == 128) {
+        const dim3 wgrid(H, (Sq + 31) / 32, batch);
+        if (d == 64)
+            hipLaunchKernelGGL(attention_mfma_kernel<64>, wgrid, dim3(64), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
+        else
+            hipLaunchKernelGGL(attention_mfma_kernel<128>, wgrid, dim3(64), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
+        SQAP_HIP_CHECK(hipGetLastError());
+        return SQAP_OK;
+    }
     const dim3 grid(H, (Sq + kAttQ - 1) / kAttQ, batch);
 #define SQAP_ATT_CASE(DD)                                                                                          \
     case DD:                                                                                                       \
@@ -180,8 +336,6 @@ sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int
     switch (d) {
         SQAP_ATT_CASE(16)
         SQAP_ATT_CASE(32)
-        SQAP_ATT_CASE(64)
-        SQAP_ATT_CASE(128)
     default:
         return fail(SQAP_EUNSUPPORTED, "attention: head size %d (16, 32, 64 or 128)", d);
     }

@@ -5,7 +5,7 @@ published pre-normalisation layer:
 
     y1 = RMSNorm(x + pending) -> int4        sqap_rmsnorm_quantize_act   (also writes x + pending)
     q|k|v = W_qkv y1                         sqap_w4a4_linear            (one GEMM, N = 3 * hidden)
-    q, k <- rotary(q, k)                     sqap_rope
+    q, k <- rotary(q, k)                     sqap_rope                   (one launch: 2 * heads columns)
     a = causal attention(q, k, v)            sqap_attention
     o = W_o quant(a)                         sqap_quantize_act + sqap_w4a4_linear
     y2 = RMSNorm(x + o) -> int4              sqap_rmsnorm_quantize_act   (residual add fused)
@@ -67,8 +67,7 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
     B.sqap_rmsnorm_quantize_act(x, rows, w.gamma_attn, eps, xq, sx, delta=pending, flags=flags, xsum_out=x_out,
                                 stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.qkv, qkv, None, buf.ws, stream=stream)
-    B.sqap_rope(qkv[:, :hidden], pos, n_heads, head_dim, stream=stream)
-    B.sqap_rope(qkv[:, hidden:2 * hidden], pos, n_heads, head_dim, stream=stream)
+    B.sqap_rope(qkv[:, :2 * hidden], pos, 2 * n_heads, head_dim, stream=stream)      # queries and keys in one launch
     B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
                      batch=batch, stream=stream)
     B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
