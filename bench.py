@@ -401,33 +401,43 @@ def selection_leg(torch, B, wl, dev, iters=50):
     cam = torch.from_numpy(wl.cameras(batch, gw, gh, 14.0, wl.rng_for(3, 0, wl.T_CAMERA))).to(dev)
     idx = torch.empty((batch, total + (2 * radius + 1) ** 2), dtype=torch.int32, device=dev)
     cnt = torch.empty((batch,), dtype=torch.int32, device=dev)
-    for _ in range(5):
-        B.sqap_prune_select(s, gw, gh, k_attn, total, cam, radius, idx, cnt)
+    us = graph_time_us(torch, lambda: B.sqap_prune_select(s, gw, gh, k_attn, total, cam, radius, idx, cnt), iters)
+    return {"us_per_call": us, "batch": batch, "grid": [gw, gh], "k_attn": k_attn, "keep_total": total,
+            "ring_radius": radius, "note": "GPU time, back-to-back launches replayed from a HIP graph"}
+
+
+def graph_time_us(torch, fn, iters, per_graph=10):
+    """Microseconds of GPU time per call of fn: per_graph calls captured into a HIP graph and replayed, so
+    that the host's launch cost (several microseconds per call through Python) does not count."""
+    for _ in range(3):
+        fn()
     torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(per_graph):
+            fn()
+    graph.replay()
+    torch.cuda.synchronize()
+    reps = max(1, iters // per_graph)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for _ in range(iters):
-        B.sqap_prune_select(s, gw, gh, k_attn, total, cam, radius, idx, cnt)
+    for _ in range(reps):
+        graph.replay()
     e1.record()
     torch.cuda.synchronize()
-    return {"us_per_call": e0.elapsed_time(e1) * 1e3 / iters, "batch": batch, "grid": [gw, gh], "k_attn": k_attn,
-            "keep_total": total, "ring_radius": radius, "note": "back-to-back launches, includes launch overhead"}
+    return e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
 
 
 def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
     """Microseconds per call of the selection and quantization kernels at configuration 3's sizes
     (back-to-back launches on one stream, HIP events around the run)."""
     def timed(fn):
-        for _ in range(5):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(iters):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / iters
+        return graph_time_us(torch, fn, iters)
 
     q, k = wl.query_and_keys(wl.SEQ_LEN, wl.N_HEADS, wl.HEAD_DIM, wl.rng_for(3, 2, wl.T_Q))
     q, k = torch.from_numpy(q).to(dev), torch.from_numpy(k).to(dev)
@@ -451,7 +461,7 @@ def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
     for name, (rows_, cols) in (("quantize_act_2368x4096_fused_gather", (wk.M, wk.H)),
                                 ("quantize_act_2368x11008", (wk.M, wk.F))):
         out[name + "_GBps"] = rows_ * cols * 2.5 / out[name] / 1e3
-    out["note"] = "us per call, back-to-back launches (includes launch overhead)"
+    out["note"] = "us of GPU time per call, back-to-back launches replayed from a HIP graph"
     return out
 
 

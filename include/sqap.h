@@ -304,9 +304,7 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
  * sqap_swiglu_quantize_act: h = binary16(silu(g) * float(u)) elementwise over
  * G, U [M, F] (pitches ldg, ldu), silu(g) = (float)(g / (1 + exp(-g)))
  * evaluated in binary64; h_out[i, :] = h when asked for; then quantized as
- * above (no rotation).  The first call on a device tabulates silu for all
- * 2^16 half values and synchronises the stream once (make it before a stream
- * capture).
+ * above (no rotation).
  */
 sqap_status sqap_rmsnorm_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
                                       int32_t K, const sqap_f16 *delta, const sqap_f16 *gamma, float eps,

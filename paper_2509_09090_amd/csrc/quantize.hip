@@ -1,8 +1,6 @@
 // Per-row symmetric int4 quantizer (activations: one row per token; weights:
 // one row per output channel), with the optional Hadamard rotation of Eq. 6,
 // and the re-layout of canonical packed weights into the streaming layout.
-#include <mutex>
-
 #include "common.h"
 
 namespace sqap {
@@ -229,19 +227,9 @@ __device__ __forceinline__ void norm_row(float (&v)[GPT][8], int row, int K, con
 
 // SwiGLU (Shazeer 2020; the feed-forward of a Llama decoder): v holds the gate row g, pre.U the
 // up row;  v = half(silu(g) * u),  silu(g) = (float)(g / (1 + exp(-g))) evaluated in binary64.
-// silu is a function of a half value, so it is tabulated once per device (2^16 floats, built by
-// silu_table_kernel with exactly that expression) and looked up by bit pattern: a row of a few
-// thousand binary64 exponentials per thread would otherwise set the kernel's latency.  A GPU
-// test walks all 2^16 inputs against the host's evaluation.
-__device__ float g_silu_table[65536];
-
-__global__ __launch_bounds__(256) void silu_table_kernel()
-{
-    const unsigned bits = blockIdx.x * 256 + threadIdx.x;
-    const double gd = (double)__half2float(__ushort_as_half((unsigned short)bits));
-    g_silu_table[bits] = (float)(gd / (1.0 + exp(-gd)));
-}
-
+// silu is a function of a half value: a GPU test walks all 2^16 of them against the host's.
+// (A per-device table of the 2^16 results was slower than computing: 13 against 10 us at 84 x 11008,
+// 48 scattered 4-byte loads per thread.)
 template <int GPT>
 __device__ __forceinline__ void swiglu_row(float (&v)[GPT][8], int row, int K, const PreArgs &pre)
 {
@@ -254,7 +242,8 @@ __device__ __forceinline__ void swiglu_row(float (&v)[GPT][8], int row, int K, c
             unpack8(reinterpret_cast<const uint4 *>(pre.U + (size_t)row * pre.ldu)[g], u);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float s = g_silu_table[__half_as_ushort(__float2half_rn(v[gi][e]))];     // exact: v is a half value
+                const double gd = (double)v[gi][e];
+                const float s = (float)(gd / (1.0 + exp(-gd)));
                 v[gi][e] = round_to_half(s * u[e]);
             }
             if (pre.y_out) reinterpret_cast<uint4 *>(pre.y_out + (size_t)row * K)[g] = pack8(v[gi]);
@@ -494,32 +483,10 @@ sqap_status launch_quantize_rows_scaled(const __half *X, int64_t ldx, const int3
     return launch_quantize_mode<kChannelwise, kPreNone>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, PreArgs{}, st);
 }
 
-// Builds the silu table of the current device on first use and waits for it, so that a later call on
-// any stream finds it complete.
-static sqap_status ensure_silu_table(hipStream_t st)
-{
-    static std::mutex lock;
-    static bool built[64];
-    int dev = 0;
-    SQAP_HIP_CHECK(hipGetDevice(&dev));
-    if (dev < 0 || dev >= 64) return fail(SQAP_EUNSUPPORTED, "device ordinal %d above 63", dev);
-    std::lock_guard<std::mutex> guard(lock);
-    if (built[dev]) return SQAP_OK;
-    hipLaunchKernelGGL(silu_table_kernel, dim3(256), dim3(256), 0, st);
-    SQAP_HIP_CHECK(hipGetLastError());
-    SQAP_HIP_CHECK(hipStreamSynchronize(st));
-    built[dev] = true;
-    return SQAP_OK;
-}
-
 sqap_status launch_fused_quantize(int pre_op, const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                   bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
                                   const PreArgs &pre, hipStream_t st)
 {
-    if (pre_op == kPreSwiglu) {
-        sqap_status s = ensure_silu_table(st);
-        if (s != SQAP_OK) return s;
-    }
     if (pre_op == kPreNorm) {
         if (col_scales)
             return launch_quantize_mode<kChannelwise, kPreNorm>(X, ldx, rows, M, K, rotate, col_scales, Xq, sx, pre, st);
