@@ -53,9 +53,41 @@ __device__ __forceinline__ void load_halves(const uint4 *xrow, int K, float (&v)
     }
 }
 
-// The rotation of Eq. 6 on a row held in registers: butterfly stages at distance 1, 2, 4 inside
-// a group of 8 in registers, the remaining stages in LDS in the same order, then one multiply
-// by (float)(1/sqrt(K)).  Contains barriers.
+// The rotation of Eq. 6 on a row held in registers: butterfly stages at distance 1, 2, 4 inside a
+// group of 8 in registers, then passes over LDS that each apply up to three further stages (distance
+// s, 2s, 4s) to sets of 8 elements {base + j s} owned by one thread, so a pass costs one read, one
+// write and one barrier for three stages; then one multiply by (float)(1/sqrt(K)).  The stages come
+// in the order 1, 2, 4, ..., K/2 and every butterfly is (a, b) -> (a + b, a - b) with a the lower
+// index, as the definition has it, so the result is the same bits whatever the pass structure.
+// LDS index i lives at i + 8 (i / 64): with that padding the lanes of a wavefront hit distinct
+// banks in every pass.  Contains barriers.
+__device__ __forceinline__ int rot_at(int i) { return i + ((i >> 6) << 3); }
+constexpr size_t rot_lds_bytes(int K) { return ((size_t)K + (size_t)K / 8) * sizeof(float); }
+
+template <int W>
+__device__ __forceinline__ void rotate_pass(float *rot, int K, int s)
+{
+    for (int o = threadIdx.x; o < K / W; o += 256) {
+        const int base = (o / s) * (W * s) + (o % s);
+        float x[W];
+#pragma unroll
+        for (int j = 0; j < W; ++j) x[j] = rot[rot_at(base + j * s)];
+#pragma unroll
+        for (int hh = 1; hh < W; hh <<= 1) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                if ((j & hh) == 0) {
+                    const float a = x[j], b = x[j + hh];
+                    x[j] = a + b;
+                    x[j + hh] = a - b;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < W; ++j) rot[rot_at(base + j * s)] = x[j];
+    }
+}
+
 template <int GPT>
 __device__ __forceinline__ void rotate_row(int K, float (&v)[GPT][8], float *rot)
 {
@@ -75,20 +107,17 @@ __device__ __forceinline__ void rotate_row(int K, float (&v)[GPT][8], float *rot
             }
         }
         const int g = t + gi * 256;
-        if (g < groups) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) rot[g * 8 + e] = v[gi][e];
+        if (g < groups) {                      // a group of 8 never straddles a padded block of 64
+            float4 *dst = reinterpret_cast<float4 *>(rot + rot_at(g * 8));
+            dst[0] = make_float4(v[gi][0], v[gi][1], v[gi][2], v[gi][3]);
+            dst[1] = make_float4(v[gi][4], v[gi][5], v[gi][6], v[gi][7]);
         }
     }
     __syncthreads();
-    const int half_k = K >> 1;
-    for (int h = 8; h < K; h <<= 1) {
-        for (int p = t; p < half_k; p += 256) {
-            const int j = ((p / h) * 2 * h) + (p % h);
-            float a = rot[j], b = rot[j + h];
-            rot[j] = a + b;
-            rot[j + h] = a - b;
-        }
+    for (int s = 8; s < K; s <<= 3) {
+        if (s * 8 <= K) rotate_pass<8>(rot, K, s);
+        else if (s * 4 <= K) rotate_pass<4>(rot, K, s);
+        else rotate_pass<2>(rot, K, s);
         __syncthreads();
     }
     const float c = (float)(1.0 / sqrt((double)K));
@@ -96,8 +125,10 @@ __device__ __forceinline__ void rotate_row(int K, float (&v)[GPT][8], float *rot
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
         if (g < groups) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[gi][e] = rot[g * 8 + e] * c;
+            const float4 *src = reinterpret_cast<const float4 *>(rot + rot_at(g * 8));
+            const float4 lo = src[0], hi = src[1];
+            v[gi][0] = lo.x * c; v[gi][1] = lo.y * c; v[gi][2] = lo.z * c; v[gi][3] = lo.w * c;
+            v[gi][4] = hi.x * c; v[gi][5] = hi.y * c; v[gi][6] = hi.z * c; v[gi][7] = hi.w * c;
         }
     }
 }
@@ -276,7 +307,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
                                                             uint8_t *__restrict__ Xq,
                                                             __half *__restrict__ scale_out, const PreArgs pre)
 {
-    extern __shared__ float rot[];       // K floats when ROTATE
+    extern __shared__ __attribute__((aligned(16))) float rot[];       // the padded row when ROTATE
     __shared__ float wave_max[4];
     __shared__ unsigned long long wave_sum[8];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -369,7 +400,7 @@ __global__ __launch_bounds__(256) void channel_absmax_kernel(const __half *__res
                                                              const int32_t *__restrict__ rows, int M, int K,
                                                              float *__restrict__ amax)
 {
-    extern __shared__ float rot[];
+    extern __shared__ __attribute__((aligned(16))) float rot[];
     const int t = threadIdx.x, groups = K >> 3;
     float best[GPT][8];
 #pragma unroll
@@ -436,13 +467,13 @@ static void launch_quantize_gpt(int gpt, const __half *X, int64_t ldx, const int
     else launch_quantize_inst<ROTATE, 8, MODE, PRE>(X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
 }
 
-// Rotation keeps the row in LDS: K floats, above the 64 KiB default for the widest rows.
+// Rotation keeps the row in LDS: K floats plus padding, above the 64 KiB default for the widest rows.
 template <class Kern>
 static sqap_status allow_rotation_lds(Kern kernel, size_t lds)
 {
     if (lds > 48 * 1024)
         SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)rot_lds_bytes(16384)));
     return SQAP_OK;
 }
 
@@ -456,7 +487,7 @@ static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int3
         if constexpr (PRE == kPreSwiglu) {
             return fail(SQAP_EUNSUPPORTED, "rotation is not available behind the SwiGLU gate");
         } else {
-            const size_t lds = (size_t)K * sizeof(float);
+            const size_t lds = rot_lds_bytes(K);
             sqap_status s = allow_rotation_lds(&quantize_rows_kernel<true, 8, MODE, PRE>, lds);
             if (s != SQAP_OK) return s;
             launch_quantize_gpt<true, MODE, PRE>(gpt, X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
@@ -518,7 +549,7 @@ sqap_status launch_channel_scales(const __half *X, int64_t ldx, const int32_t *r
         const int gpt = (K / 8 + 255) / 256;
         const int grid = M < 256 ? M : 256;
         if (rotate) {
-            const size_t lds = (size_t)K * sizeof(float);
+            const size_t lds = rot_lds_bytes(K);
             sqap_status s = allow_rotation_lds(&channel_absmax_kernel<true, 8>, lds);
             if (s != SQAP_OK) return s;
             launch_absmax_gpt<true>(gpt, grid, lds, X, ldx, rows, M, K, amax, st);
