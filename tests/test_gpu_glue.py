@@ -269,3 +269,51 @@ def test_decoder_layer(G, oracle, hidden, H, d, F, batch, S, rotate):
     assert np.array_equal(buf.sh[:M].cpu().numpy().view(np.uint16), np.asarray(st["sh"]).view(np.uint16))
     assert G.assert_fp16_close(d_out.cpu().numpy(), st["d"]) == 0
     w.free()
+
+
+def test_glue_at_full_size_on_sampled_rows(G, oracle):
+    """Configuration 3's sizes (16 observations x 148 tokens = 2368 rows): the fused quantizers on sampled
+    rows bit for bit, attention on sampled (observation, head) pairs within the fp16 tolerance."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(2368)
+    M, K, F, nb, S, H, d = 2368, wl.HIDDEN, wl.FFN, 16, 148, wl.N_HEADS, wl.HEAD_DIM
+    sample = np.sort(rng.choice(M, size=24, replace=False))
+    # RMSNorm + residual + quantize, K = 4096
+    X = _acts(rng, M, K)
+    D = _acts(rng, M, K, outliers=False)
+    gamma = (1 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    Xq = torch.zeros((M, K // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    xs = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+    B.sqap_rmsnorm_quantize_act(G.to_dev(X), None, G.to_dev(gamma), 1e-5, Xq, sx, delta=G.to_dev(D), xsum_out=xs)
+    torch.cuda.synchronize()
+    xs_o, y_o = oracle.rmsnorm_rows(X[sample], gamma, 1e-5, delta=D[sample])
+    q_o, s_o, _ = oracle.quantize_rows(y_o)
+    assert np.array_equal(xs.cpu().numpy()[sample].view(np.uint16), xs_o.view(np.uint16))
+    assert np.array_equal(Xq.cpu().numpy()[sample], q_o)
+    assert np.array_equal(sx.cpu().numpy()[sample].view(np.uint16), np.asarray(s_o).view(np.uint16))
+    # SwiGLU + quantize, F = 11008, gate | up as one fused output
+    GU = (rng.standard_normal((M, 2 * F)) * 2).astype(np.float16)
+    gu = G.to_dev(GU)
+    Hq = torch.zeros((M, F // 2), dtype=torch.uint8, device="cuda")
+    sh = torch.zeros((M,), dtype=torch.float16, device="cuda")
+    B.sqap_swiglu_quantize_act(gu[:, :F], gu[:, F:], Hq, sh)
+    torch.cuda.synchronize()
+    h_o = oracle.swiglu(GU[sample, :F], GU[sample, F:])
+    q_o, s_o, _ = oracle.quantize_rows(h_o)
+    assert np.array_equal(Hq.cpu().numpy()[sample], q_o)
+    assert np.array_equal(sh.cpu().numpy()[sample].view(np.uint16), np.asarray(s_o).view(np.uint16))
+    # attention over 16 sequences of 148 tokens, 32 heads of 128
+    QKV = rng.standard_normal((nb * S, 3 * H * d)).astype(np.float16)
+    qkv = G.to_dev(QKV)
+    O = torch.full((nb * S, H * d), float("nan"), dtype=torch.float16, device="cuda")
+    B.sqap_attention(qkv[:, :H * d], qkv[:, H * d:2 * H * d], qkv[:, 2 * H * d:], H, d, O, batch=nb)
+    torch.cuda.synchronize()
+    got = O.cpu().numpy()
+    assert not np.isnan(got).any()
+    for (b, h) in ((0, 0), (7, 13), (15, 31)):
+        blk = QKV[b * S:(b + 1) * S]
+        cut = lambda part: np.ascontiguousarray(blk[:, part * H * d + h * d: part * H * d + (h + 1) * d]).reshape(S, 1, d)
+        want = oracle.attention(cut(0), cut(1), cut(2)).reshape(S, d)
+        assert G.assert_fp16_close(got[b * S:(b + 1) * S, h * d:(h + 1) * d], want) >= 0
