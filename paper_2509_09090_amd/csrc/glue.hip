@@ -177,14 +177,19 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
 //   O^T += V^T P^T   registers 4b .. 4b+3 of exp(S^T - m), converted to half, ARE the B operand of key
 //                    block b (keys 8b + 4(l/32) + 0..3); A = V^T comes from a transposed copy of the value
 //                    tile in LDS.
-// The running maximum, the running sum and the rescaling of O^T are per query, i.e. per lane.  The reduction
+// The running maximum, the running sum and the rescaling of O^T are per query, i.e. per lane.  The four
+// wavefronts of a workgroup take the key tiles in turn (tile t belongs to wavefront t % 4), so a sequence of
+// up to 128 keys costs one round of loads, and merge their partial (m, l, O^T) through LDS at the end: wavefront
+// w collects column tile w of the output from the other three.  The reduction
 // over the head dimension may visit it in any order as long as A and B agree: MFMA j takes elements
 // 16(j/2) + 8(l/32) + 4(j%2) + 0..3, so that each lane fetches 16 contiguous bytes per pair of MFMAs.
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
+constexpr int kAttWaves = 4;
+
 template <int D>
-__global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__restrict__ Q, int64_t ldq,
+__global__ __launch_bounds__(64 * kAttWaves) void attention_mfma_kernel(const __half *__restrict__ Q, int64_t ldq,
                                                             const __half *__restrict__ Kc, int64_t ldk,
                                                             const __half *__restrict__ V, int64_t ldv, int Sq, int Sk,
                                                             int H, __half *__restrict__ O, int64_t ldo)
@@ -192,8 +197,13 @@ __global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__rest
     constexpr int NP = D / 16;                   // 16-byte pieces of a head row per lane half
     constexpr int CT = D / 32;                   // 32-column tiles of the head dimension
     constexpr int VP = 36;                       // halves per row of the transposed value tile (8-byte aligned rows)
-    __shared__ __attribute__((aligned(16))) __half vt[D * VP];
-    const int l = threadIdx.x, c = l & 31, h = l >> 5;
+    constexpr int NW = kAttWaves;
+    constexpr int VT_BYTES = NW * D * VP * 2;
+    constexpr int MERGE_BYTES = CT * NW * 4096 + NW * 64 * 8;      // O^T pieces [ct][wave][16 regs][64 lanes] + (m, l)
+    __shared__ __attribute__((aligned(16))) uint8_t lds[VT_BYTES > MERGE_BYTES ? VT_BYTES : MERGE_BYTES];
+    const int l = threadIdx.x & 63, c = l & 31, h = l >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __half *vt = reinterpret_cast<__half *>(lds) + wave * (D * VP);
     const int head = blockIdx.x, q0 = blockIdx.y * 32;
     Q += (int64_t)blockIdx.z * Sq * ldq + (int64_t)head * D;
     O += (int64_t)blockIdx.z * Sq * ldo + (int64_t)head * D;
@@ -240,9 +250,11 @@ __global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__rest
             if (k0 + key < Sk) vraw[n] = *reinterpret_cast<const uint4 *>(V + (int64_t)(k0 + key) * ldv + dp * 8);
         }
     };
-    load_keys(0);
-    load_values(0);
-    for (int kt = 0; kt < n_tiles; ++kt) {
+    if (wave < n_tiles) {
+        load_keys(wave * 32);
+        load_values(wave * 32);
+    }
+    for (int kt = wave; kt < n_tiles; kt += NW) {
         const int k0 = kt * 32;
         v16f st;
 #pragma unroll
@@ -252,7 +264,7 @@ __global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__rest
             st = __builtin_amdgcn_mfma_f32_32x32x8f16(kf[m].v[0], qf[m].v[0], st, 0, 0, 0);
             st = __builtin_amdgcn_mfma_f32_32x32x8f16(kf[m].v[1], qf[m].v[1], st, 0, 0, 0);
         }
-        if (kt + 1 < n_tiles) load_keys(k0 + 32);           // in flight during the softmax and the second product
+        if (kt + NW < n_tiles) load_keys(k0 + 32 * NW);      // in flight during the softmax and the second product
         __builtin_amdgcn_wave_barrier();
         // value tile, transposed into LDS (the previous tile's readers are this same wavefront: LDS operations
         // of one wavefront complete in order)
@@ -263,7 +275,7 @@ __global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__rest
 #pragma unroll
             for (int e = 0; e < 8; ++e) vt[(dp * 8 + e) * VP + key] = hv[e];
         }
-        if (kt + 1 < n_tiles) load_values(k0 + 32);
+        if (kt + NW < n_tiles) load_values(k0 + 32 * NW);
         float tmax = -INFINITY;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -301,17 +313,58 @@ __global__ __launch_bounds__(64) void attention_mfma_kernel(const __half *__rest
             }
         __builtin_amdgcn_wave_barrier();
     }
-    if (q_ok) {
-        const float inv_l = 1.0f / lrun;
+    // merge: every wavefront publishes its (m, l) and, for each column tile it does not own, its piece of O^T
+    __syncthreads();                                         // the value tiles are no longer needed
+    float *ml = reinterpret_cast<float *>(lds + CT * NW * 4096);
+    ml[(wave * 64 + l) * 2] = mrun;
+    ml[(wave * 64 + l) * 2 + 1] = lrun;
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) {
+        if (ct != wave) {
+            float *dst = reinterpret_cast<float *>(lds + (ct * NW + wave) * 4096);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dst[i * 64 + l] = ot[ct][i];
+        }
+    }
+    __syncthreads();
+    if (wave < CT) {
+        float mall = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) mall = fmaxf(mall, ml[(w * 64 + l) * 2]);
+        float lall = 0.f, f[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float mw = ml[(w * 64 + l) * 2];
+            f[w] = mw == -INFINITY ? 0.f : expf(mw - mall);
+            lall += ml[(w * 64 + l) * 2 + 1] * f[w];
+        }
+        v16f acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
+            if (ct == wave) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = ot[ct][i] * f[ct];         // static indices after unrolling
+            }
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            if (w != wave) {
+                const float *src = reinterpret_cast<const float *>(lds + (wave * NW + w) * 4096);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = fmaf(src[i * 64 + l], f[w], acc[i]);
+            }
+        }
+        if (q_ok) {
+            const float inv_l = 1.0f / lall;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 union { uint2 u; __half2 p[2]; } out;
-                out.p[0] = __floats2half2_rn(ot[ct][4 * g] * inv_l, ot[ct][4 * g + 1] * inv_l);
-                out.p[1] = __floats2half2_rn(ot[ct][4 * g + 2] * inv_l, ot[ct][4 * g + 3] * inv_l);
-                *reinterpret_cast<uint2 *>(O + (int64_t)my_q * ldo + 32 * ct + 8 * g + 4 * h) = out.u;
+                out.p[0] = __floats2half2_rn(acc[4 * g] * inv_l, acc[4 * g + 1] * inv_l);
+                out.p[1] = __floats2half2_rn(acc[4 * g + 2] * inv_l, acc[4 * g + 3] * inv_l);
+                *reinterpret_cast<uint2 *>(O + (int64_t)my_q * ldo + 32 * wave + 8 * g + 4 * h) = out.u;
             }
+        }
     }
 }
 
@@ -322,9 +375,9 @@ sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int
     if (d == 64 || d == 128) {
         const dim3 wgrid(H, (Sq + 31) / 32, batch);
         if (d == 64)
-            hipLaunchKernelGGL(attention_mfma_kernel<64>, wgrid, dim3(64), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
+            hipLaunchKernelGGL(attention_mfma_kernel<64>, wgrid, dim3(64 * kAttWaves), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
         else
-            hipLaunchKernelGGL(attention_mfma_kernel<128>, wgrid, dim3(64), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
+            hipLaunchKernelGGL(attention_mfma_kernel<128>, wgrid, dim3(64 * kAttWaves), 0, st, Q, ldq, Kc, ldk, V, ldv, Sq, Sk, H, O, ldo);
         SQAP_HIP_CHECK(hipGetLastError());
         return SQAP_OK;
     }
