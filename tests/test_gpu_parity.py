@@ -120,7 +120,8 @@ def test_quantize_act_rotated(G, oracle, M, K):
 
 def test_quantize_special_rows(G, oracle):
     K = 64
-    X = np.zeros((6, K), np.float16)
+    X = np.zeros((7, K), np.float16)
+    X[6, :4] = np.array([-10, 10, -7, 3], np.float16) * np.float16(2.0 ** -24)   # the only way to code -8: the clamp
     X[1, 3] = np.float16(6e-8)            # smallest subnormal: scale floor path
     X[2] = np.float16(65504.0)
     X[3, ::2] = np.float16(-1.5)

@@ -401,6 +401,20 @@ def test_quantizer_error_bound_and_range(oracle):
     assert np.array_equal(s.view(np.uint16), (amax / np.float32(7)).astype(np.float16).view(np.uint16))
 
 
+def test_quantizer_clamp_reaches_minus_eight_only_below_the_normal_scales(oracle):
+    """Code -8 exists in the format but the divisor 7 never asks for it; it appears only where the scale has
+    too few bits: amax = 10 * 2^-24 gives the scale 2^-24 (10/7 rounds to one subnormal unit), v / s = -10."""
+    u = 2.0 ** -24
+    X = np.array([[-10 * u, 10 * u, -7 * u, 3 * u]], dtype=np.float16)
+    q, s, _ = oracle.quantize_rows(X)
+    assert s.view(np.uint16)[0] == 1
+    assert list(oracle.unpack_int4(q)[0]) == [-8, 7, -7, 3]
+    # in the normal range of scales the most negative code is -7
+    rng = np.random.default_rng(17)
+    Xn = (rng.standard_normal((64, 256)) * np.exp(rng.uniform(-6, 6, (64, 1)))).astype(np.float16)
+    assert oracle.unpack_int4(oracle.quantize_rows(Xn)[0]).min() == -7
+
+
 def test_quantizer_sign_symmetry_and_power_of_two_scaling(oracle):
     X, _ = wl.activations(16, 128, 2, 20.0, np.random.default_rng(8))
     q, s, _ = oracle.quantize_rows(X)
@@ -711,6 +725,11 @@ def test_rmsnorm_constant_row_and_unit_rms(oracle):
         X = np.full((1, K), c, dtype=np.float16)
         _, y = oracle.rmsnorm_rows(X, np.ones(K, np.float16), 0.0)
         assert np.all(y == np.float16(np.sign(c))), c              # x / |x|
+    # eps equal to the mean square halves the normalised power: x / sqrt(2 x^2) = 1 / sqrt(2)
+    for c in (0.5, -0.03125, 16.0):
+        X = np.full((1, K), c, dtype=np.float16)
+        _, y = oracle.rmsnorm_rows(X, np.ones(K, np.float16), c * c)
+        assert np.all(y == np.float16(np.sign(c) * np.sqrt(0.5))), c
     rng = np.random.default_rng(5)
     X = (rng.standard_normal((7, 512)) * 3).astype(np.float16)
     _, y = oracle.rmsnorm_rows(X, np.ones(512, np.float16), 0.0)
