@@ -38,7 +38,10 @@ __device__ __forceinline__ void load_halves(const uint4 *xrow, int K, float (&v)
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
         if (g < groups) {
-            uint4 raw = xrow[g];
+            typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+            union { v4u v; uint4 u; } ld;
+            ld.v = __builtin_nontemporal_load(reinterpret_cast<const v4u *>(xrow) + g);   // a row is read once
+            uint4 raw = ld.u;
             const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
