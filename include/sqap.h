@@ -173,13 +173,16 @@ sqap_status sqap_gather_rows(const sqap_f16 *X, int64_t ldx, const int32_t *rows
  * Details: W4A4).  For output row i, taken from X[rows[i], :] (or X[i, :] when
  * rows is NULL, which fuses the gather):
  *   v     = the row in binary32; with SQAP_ROTATE_HADAMARD, v <- (H/sqrt(K)) v
- *           (Eq. 6; butterflies at distance 1, 2, 4, ... in that order)
+ *           (Eq. 6; butterflies at distance 1, 2, 4, ... in that order); when
+ *           K is not a power of two, H is block diagonal with one matrix of
+ *           order B per aligned run of B channels, B the largest power of two
+ *           dividing K (256 for K = 11008), scaled by 1/sqrt(B)
  *   sx[i] = binary16(max|v| / 7), raised to 2^-24 when that rounds to 0
  *   code  = clamp(rint(v / sx[i]), -8, 7), round-half-even, IEEE division
  * Xq: [M, K/2] canonical packed int4.  sx: [M] half.
  * EINVAL: null pointer, M < 0, K <= 0, K odd, ldx < K.
  * EUNSUPPORTED: K not a multiple of 8, K > 16384, X/ldx not 16-byte aligned,
- * rotation with K not a power of two or K < 16.
+ * rotation with K not a multiple of 16.
  */
 sqap_status sqap_quantize_act(const sqap_f16 *X, int64_t ldx, const int32_t *rows, int32_t M,
                               int32_t K, uint32_t flags, uint8_t *Xq, sqap_f16 *sx,

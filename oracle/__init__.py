@@ -157,6 +157,19 @@ def fwht(v):
     return v
 
 
+def rotate(v):
+    """Eq. 6 rotation of one binary32 vector of any length: blocks of the largest power-of-two divisor (copy)."""
+    v = np.array(v, dtype=np.float32, copy=True)
+    rc = lib().oracle_rotate_f32(_p(v), v.size)
+    if rc != 0:
+        raise ValueError("oracle_rotate_f32: status %d" % rc)
+    return v
+
+
+def rotation_block(K):
+    return int(lib().oracle_rotation_block(int(K)))
+
+
 def quantize_rows(X, rows=None, rotate=False):
     """Per-row symmetric int4: returns (packed [M,K/2] u8, scale [M] f16, rowsum [M] i32)."""
     X = _c(X, np.float16)

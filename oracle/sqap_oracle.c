@@ -335,6 +335,32 @@ int oracle_fwht_f32(float *v, int K)
     return 0;
 }
 
+/*
+ * Rotation of a row whose length is not a power of two (the feed-forward width
+ * 11008 = 43 * 256).  Eq. 6 only needs H orthogonal.  Reading: H is block
+ * diagonal, one orthonormal Sylvester matrix of order B per aligned block of B
+ * consecutive channels, B the largest power of two that divides K (for a power
+ * of two this is the single matrix above).  Outlier energy is then spread over
+ * the 256 channels of its block instead of over the whole row.
+ */
+int oracle_rotation_block(int K)
+{
+    int B = 1;
+    while (K > 0 && (K % (2 * B)) == 0) B *= 2;
+    return B;
+}
+
+int oracle_rotate_f32(float *v, int K)
+{
+    if (K <= 0) return -2;
+    int B = oracle_rotation_block(K);
+    for (int base = 0; base < K; base += B) {
+        int rc = oracle_fwht_f32(v + base, B);
+        if (rc) return rc;
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------ */
 /* 4-bit symmetric quantizer, one scale per row                        */
 /* (Section 3.3 / Implementation Details: W4A4; the arithmetic is a    */
@@ -343,7 +369,7 @@ int oracle_fwht_f32(float *v, int K)
 /*
  * For each output row i (a token for activations, an output channel for
  * weights), taken from source row rows[i] (or i when rows is NULL):
- *   v      = binary32 of the row, rotated by oracle_fwht_f32 when rotate != 0
+ *   v      = binary32 of the row, rotated by oracle_rotate_f32 when rotate != 0
  *   amax   = max_k |v_k|
  *   scale  = binary16(amax / 7), raised to the smallest subnormal 2^-24 if 0
  *   q_k    = clamp(rint(v_k / (float)scale), -8, 7)
@@ -355,7 +381,7 @@ int oracle_quantize_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, in
                          int32_t *rowsum_out)
 {
     if (M < 0 || K <= 0 || (K & 1)) return -1;
-    if (rotate && (K & (K - 1)) != 0) return -2;
+    if (rotate && oracle_rotation_block(K) < 16) return -2;
     int status = 0;
 #pragma omp parallel for schedule(static)
     for (int i = 0; i < M; ++i) {
@@ -366,7 +392,7 @@ int oracle_quantize_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, in
         }
         size_t src = rows ? (size_t)rows[i] : (size_t)i;
         for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
-        if (rotate) oracle_fwht_f32(v, K);
+        if (rotate) oracle_rotate_f32(v, K);
         float amax = 0.0f;
         for (int k = 0; k < K; ++k) {
             float a = fabsf(v[k]);
@@ -413,7 +439,7 @@ int oracle_channel_scales(const uint16_t *X, int64_t ldx, const int32_t *rows, i
                           int rotate, uint16_t *scales_out)
 {
     if (M < 0 || K <= 0) return -1;
-    if (rotate && (K & (K - 1)) != 0) return -2;
+    if (rotate && oracle_rotation_block(K) < 16) return -2;
     float *amax = (float *)calloc((size_t)K, sizeof(float));
     float *v = (float *)malloc(sizeof(float) * (size_t)K);
     if (!amax || !v) {
@@ -424,7 +450,7 @@ int oracle_channel_scales(const uint16_t *X, int64_t ldx, const int32_t *rows, i
     for (int i = 0; i < M; ++i) {
         size_t src = rows ? (size_t)rows[i] : (size_t)i;
         for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
-        if (rotate) oracle_fwht_f32(v, K);
+        if (rotate) oracle_rotate_f32(v, K);
         for (int k = 0; k < K; ++k)
             if (fabsf(v[k]) > amax[k]) amax[k] = fabsf(v[k]);
     }
@@ -447,7 +473,7 @@ int oracle_quantize_rows_channelwise(const uint16_t *X, int64_t ldx, const int32
                                      uint16_t *scale_out)
 {
     if (M < 0 || K <= 0 || (K & 1)) return -1;
-    if (rotate && (K & (K - 1)) != 0) return -2;
+    if (rotate && oracle_rotation_block(K) < 16) return -2;
     int status = 0;
 #pragma omp parallel for schedule(static)
     for (int i = 0; i < M; ++i) {
@@ -458,7 +484,7 @@ int oracle_quantize_rows_channelwise(const uint16_t *X, int64_t ldx, const int32
         }
         size_t src = rows ? (size_t)rows[i] : (size_t)i;
         for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(X[src * ldx + k]);
-        if (rotate) oracle_fwht_f32(v, K);
+        if (rotate) oracle_rotate_f32(v, K);
         for (int k = 0; k < K; k += 2) {
             int q[2];
             for (int t = 0; t < 2; ++t) {
@@ -484,7 +510,7 @@ int oracle_quantize_rows_folded(const uint16_t *W, int64_t ldw, int N, int K, in
                                 const uint16_t *col_scales, uint8_t *Wq, uint16_t *scale_out)
 {
     if (N < 0 || K <= 0 || (K & 1)) return -1;
-    if (rotate && (K & (K - 1)) != 0) return -2;
+    if (rotate && oracle_rotation_block(K) < 16) return -2;
     int status = 0;
 #pragma omp parallel for schedule(static)
     for (int i = 0; i < N; ++i) {
@@ -494,7 +520,7 @@ int oracle_quantize_rows_folded(const uint16_t *W, int64_t ldw, int N, int K, in
             continue;
         }
         for (int k = 0; k < K; ++k) v[k] = oracle_f16_to_f32(W[(size_t)i * ldw + k]);
-        if (rotate) oracle_fwht_f32(v, K);
+        if (rotate) oracle_rotate_f32(v, K);
         float amax = 0.0f;
         for (int k = 0; k < K; ++k) {
             v[k] = v[k] * oracle_f16_to_f32(col_scales[k]);

@@ -175,8 +175,8 @@ static sqap_status quantize_common(const char *who, const sqap_f16 *X, int64_t l
     if (M == 0) return SQAP_OK;
     if (!X || !Xq || !sx) return fail(SQAP_EINVAL, "%s: null pointer", who);
     bool rotate = (flags & SQAP_ROTATE_HADAMARD) != 0;
-    if (rotate && ((K & (K - 1)) != 0 || K < 16))
-        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if (rotate && ((K & -K) < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a multiple of 16 (K = %d)", who, K);
     if ((K & 7) || K > 16384)
         return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
     if ((ldx & 7) || !aligned16(X) || (reinterpret_cast<uintptr_t>(Xq) & 3u))
@@ -208,8 +208,8 @@ static sqap_status fused_common(const char *who, const void *X, int64_t ldx, int
     if (Xq && !sx) return fail(SQAP_EINVAL, "%s: null sx", who);
     if (M > 0 && !X) return fail(SQAP_EINVAL, "%s: null input", who);
     const bool rotate = (flags & SQAP_ROTATE_HADAMARD) != 0;
-    if (rotate && ((K & (K - 1)) != 0 || K < 16))
-        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if (rotate && ((K & -K) < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a multiple of 16 (K = %d)", who, K);
     if ((K & 7) || K > 16384) return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
     if ((ldx & 7) || !aligned16(X) || !aligned16(col_scales) || !aligned16(y_out) ||
         (reinterpret_cast<uintptr_t>(Xq) & 3u))
@@ -314,8 +314,8 @@ static sqap_status scaled_common(const char *who, const sqap_f16 *X, int64_t ldx
     if (K & 1) return fail(SQAP_EINVAL, "%s: K = %d is odd", who, K);
     if (ldx < K) return fail(SQAP_EINVAL, "%s: pitch %lld below K %d", who, (long long)ldx, K);
     if (flags & ~(uint32_t)SQAP_ROTATE_HADAMARD) return fail(SQAP_EINVAL, "%s: unknown flags 0x%x", who, flags);
-    if ((flags & SQAP_ROTATE_HADAMARD) && ((K & (K - 1)) != 0 || K < 16))
-        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a power of two >= 16 (K = %d)", who, K);
+    if ((flags & SQAP_ROTATE_HADAMARD) && ((K & -K) < 16))
+        return fail(SQAP_EUNSUPPORTED, "%s: rotation needs K a multiple of 16 (K = %d)", who, K);
     if ((K & 7) || K > 16384) return fail(SQAP_EUNSUPPORTED, "%s: K = %d (multiple of 8, <= 16384)", who, K);
     if (M > 0 && (!X || !col_scales)) return fail(SQAP_EINVAL, "%s: null pointer", who);
     if (M > 0 && ((ldx & 7) || !aligned16(X) || !aligned16(col_scales)))

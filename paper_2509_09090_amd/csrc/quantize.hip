@@ -59,8 +59,8 @@ __device__ __forceinline__ void load_halves(const uint4 *xrow, int K, float (&v)
 // The rotation of Eq. 6 on a row held in registers: butterfly stages at distance 1, 2, 4 inside a
 // group of 8 in registers, then passes over LDS that each apply up to three further stages (distance
 // s, 2s, 4s) to sets of 8 elements {base + j s} owned by one thread, so a pass costs one read, one
-// write and one barrier for three stages; then one multiply by (float)(1/sqrt(K)).  The stages come
-// in the order 1, 2, 4, ..., K/2 and every butterfly is (a, b) -> (a + b, a - b) with a the lower
+// write and one barrier for three stages; then one multiply by (float)(1/sqrt(B)), B = K for a power
+// of two.  The stages come in the order 1, 2, 4, ..., B/2 and every butterfly is (a, b) -> (a + b, a - b) with a the lower
 // index, as the definition has it, so the result is the same bits whatever the pass structure.
 // LDS index i lives at i + 8 (i / 64): with that padding the lanes of a wavefront hit distinct
 // banks in every pass.  Contains barriers.
@@ -117,13 +117,16 @@ __device__ __forceinline__ void rotate_row(int K, float (&v)[GPT][8], float *rot
         }
     }
     __syncthreads();
-    for (int s = 8; s < K; s <<= 3) {
-        if (s * 8 <= K) rotate_pass<8>(rot, K, s);
-        else if (s * 4 <= K) rotate_pass<4>(rot, K, s);
+    // a row whose length is not a power of two is rotated block by block: one matrix of order B per
+    // aligned run of B channels, B the largest power of two dividing K (the stages simply stop at B/2)
+    const int B = K & -K;
+    for (int s = 8; s < B; s <<= 3) {
+        if (s * 8 <= B) rotate_pass<8>(rot, K, s);
+        else if (s * 4 <= B) rotate_pass<4>(rot, K, s);
         else rotate_pass<2>(rot, K, s);
         __syncthreads();
     }
-    const float c = (float)(1.0 / sqrt((double)K));
+    const float c = (float)(1.0 / sqrt((double)B));
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;

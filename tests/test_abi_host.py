@@ -65,8 +65,8 @@ def test_quantize_validation():
     assert L.sqap_quantize_act(None, 16, None, 1, 16, 0, p, p, None) == B.EINVAL
     assert L.sqap_quantize_act(p, 16, None, 1, 16, 2, p, p, None) == B.EINVAL         # unknown flag
     assert L.sqap_quantize_act(None, 16, None, 0, 16, 0, None, None, None) == B.OK    # M = 0
-    assert L.sqap_quantize_act(p, 11008, None, 1, 11008, 1, p, p, None) == B.EUNSUPPORTED
-    assert "power of two" in _err()
+    assert L.sqap_quantize_act(p, 2056, None, 1, 2056, 1, p, p, None) == B.EUNSUPPORTED   # 2056 = 8 * 257
+    assert "multiple of 16" in _err()
     assert L.sqap_quantize_act(p, 12, None, 1, 12, 0, p, p, None) == B.EUNSUPPORTED   # K % 8
     assert L.sqap_quantize_act(p, 32768, None, 1, 32768, 0, p, p, None) == B.EUNSUPPORTED
     assert L.sqap_quantize_act(ctypes.c_void_p(4098), 16, None, 1, 16, 0, p, p, None) == B.EUNSUPPORTED
@@ -121,7 +121,7 @@ def test_glue_validation():
     assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 64, None, p, f(-1.0), 0, None, None, None, p, p, None) == B.EINVAL
     assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 64, None, p, f(1e-5), 0, None, None, None, None, None, None) == B.EINVAL
     assert L.sqap_rmsnorm_quantize_act(p, 64, None, 2, 60, None, p, f(1e-5), 0, None, None, None, p, p, None) == B.EUNSUPPORTED
-    assert L.sqap_rmsnorm_quantize_act(p, 96, None, 2, 96, None, p, f(1e-5), 1, None, None, None, p, p, None) == B.EUNSUPPORTED
+    assert L.sqap_rmsnorm_quantize_act(p, 72, None, 2, 72, None, p, f(1e-5), 1, None, None, None, p, p, None) == B.EUNSUPPORTED
     assert L.sqap_rmsnorm_quantize_act(None, 64, None, 0, 64, None, None, f(0.0), 0, None, None, None, None, None, None) == B.OK
     assert L.sqap_swiglu_quantize_act(p, 64, p, 32, 2, 64, None, None, p, p, None) == B.EINVAL
     assert L.sqap_swiglu_quantize_act(p, 64, None, 64, 2, 64, None, None, p, p, None) == B.EINVAL

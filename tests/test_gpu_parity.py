@@ -109,7 +109,8 @@ def test_quantize_act_fused_gather(G, oracle):
     assert np.array_equal(s.view(np.uint16), so.view(np.uint16)) and np.array_equal(q, qo)
 
 
-@pytest.mark.parametrize("M,K", [(7, 16), (5, 64), (33, 512), (148, 4096), (3, 16384)])
+@pytest.mark.parametrize("M,K", [(7, 16), (5, 64), (33, 512), (148, 4096), (3, 16384), (37, 11008), (9, 1536), (4, 48),
+                                 (6, 10240)])
 def test_quantize_act_rotated(G, oracle, M, K):
     X, _ = wl.activations(M, K, max(1, wl.n_outliers_for(K)), 30.0, wl.rng_for(93, M, wl.T_X, K))
     q, s = G.gpu_quantize(X, rotate=True)

@@ -364,6 +364,41 @@ def test_fwht_rejects_non_power_of_two(oracle):
         oracle.fwht(np.zeros(12, np.float32))
 
 
+def test_rotation_of_other_lengths_is_block_diagonal(oracle):
+    """Lengths that are not a power of two: one orthonormal Sylvester block per aligned run of B channels, B the
+    largest power of two dividing K; the whole matrix for a power of two."""
+    assert [oracle.rotation_block(K) for K in (4096, 11008, 1536, 2056, 96, 7)] == [4096, 256, 512, 8, 32, 1]
+    rng = np.random.default_rng(31)
+    v = rng.standard_normal(512).astype(np.float32)
+    assert np.array_equal(oracle.rotate(v).view(np.uint32), oracle.fwht(v).view(np.uint32))
+    for K in (96, 192, 1536):
+        B = oracle.rotation_block(K)
+        v = (rng.standard_normal(K) * 3).astype(np.float32)
+        dense = scipy.linalg.block_diag(*([scipy.linalg.hadamard(B) / np.sqrt(B)] * (K // B)))
+        want = dense @ v.astype(np.float64)
+        got = oracle.rotate(v).astype(np.float64)
+        assert np.all(np.abs(got - want) <= 1e-5 * np.abs(v).max() * np.log2(B))
+        assert abs(np.linalg.norm(got) - np.linalg.norm(v.astype(np.float64))) <= 1e-5 * np.linalg.norm(v)   # orthonormal
+        # an impulse stays inside its block
+        e = np.zeros(K, np.float32)
+        e[B + 3] = 1.0
+        out = oracle.rotate(e)
+        assert np.all(out[:B] == 0) and np.all(out[2 * B:] == 0) and np.all(np.abs(out[B:2 * B]) == np.float32(1 / np.sqrt(B)))
+    # Eq. 6: rotating the weight rows and the activation row leaves the product unchanged
+    K, N = 192, 7
+    W = rng.standard_normal((N, K)).astype(np.float32)
+    x = rng.standard_normal(K).astype(np.float32)
+    Wr = np.stack([oracle.rotate(w) for w in W]).astype(np.float64)
+    assert np.allclose(Wr @ oracle.rotate(x).astype(np.float64), W.astype(np.float64) @ x.astype(np.float64), atol=1e-4)
+    # the quantizer takes such rows, and refuses blocks too small to rotate in registers (B < 16)
+    X = (rng.standard_normal((3, 192))).astype(np.float16)
+    q, s, _ = oracle.quantize_rows(X, rotate=True)
+    vr = oracle.rotate(X[1].astype(np.float32))
+    assert s[1] == np.float16(np.abs(vr).max() / np.float32(7.0))
+    with pytest.raises(ValueError):
+        oracle.quantize_rows(np.zeros((1, 2056), np.float16), rotate=True)
+
+
 def test_rotation_leaves_the_linear_unchanged(oracle):
     """Eq. 6: (W H^T)(H x) = W x with the orthonormal H."""
     rng = np.random.default_rng(6)
