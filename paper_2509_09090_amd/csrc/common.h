@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
@@ -67,6 +69,30 @@ struct Group {
 constexpr uint32_t kGroupMagic = 0x53514752u;  // "SQGR"
 
 static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Launcher state that belongs to a device (function attributes set, CU count): one slot per device
+// ordinal, atomics so that host threads may race to initialise it (every racer writes the same value).
+constexpr int kMaxDeviceSlots = 64;
+static inline int device_slot()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0) dev = 0;
+    return dev % kMaxDeviceSlots;
+}
+static inline int device_cu_count()
+{
+    static std::atomic<int> cus[kMaxDeviceSlots];
+    const int slot = device_slot();
+    int v = cus[slot].load(std::memory_order_relaxed);
+    if (v == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+            v = 256;
+        cus[slot].store(v, std::memory_order_relaxed);
+    }
+    return v;
+}
 
 #define SQAP_HIP_CHECK(expr)                                                          \
     do {                                                                              \

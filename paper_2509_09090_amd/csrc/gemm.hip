@@ -804,7 +804,7 @@ __global__ __launch_bounds__(512) void xcc_probe_kernel()
     if (threadIdx.x == 0) g_xcc_of_block[blockIdx.x] = x & 15u;
 }
 
-constexpr int kMaxDevices = 64;
+constexpr int kMaxDevices = kMaxDeviceSlots;
 static std::atomic<int> g_dealing[kMaxDevices];      // 0 not probed, 1 the rule holds, 2 it does not
 
 sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out)
@@ -835,16 +835,10 @@ static bool persistent_allowed()
 
 static int persistent_blocks()
 {
-    static int blocks = 0;
-    if (blocks == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < kXcds)
-            cus = kMaxPersistentBlocks;
-        if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
-        blocks = (cus / kXcds) * kXcds;
-    }
-    return blocks;
+    int cus = device_cu_count();
+    if (cus < kXcds) cus = kMaxPersistentBlocks;
+    if (cus > kMaxPersistentBlocks) cus = kMaxPersistentBlocks;
+    return (cus / kXcds) * kXcds;
 }
 
 // Tile shapes.  Large M: 256 x 256, eight wavefronts.  Below that the output is too
@@ -886,11 +880,12 @@ static sqap_status launch_tiled_k(GemmParams &p, hipStream_t st)
 {
     p.m_tiles = (p.M + C::BM - 1) / C::BM;
     p.n_tiles = (p.N + C::BN - 1) / C::BN;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured[kMaxDeviceSlots];
+    const int dslot = device_slot();
+    if (!configured[dslot].load(std::memory_order_acquire)) {
         sqap_status s = set_lds<C>(&gemm_tiled_kernel<C, RAGGED_K>);
         if (s != SQAP_OK) return s;
-        configured = true;
+        configured[dslot].store(true, std::memory_order_release);
     }
     const int64_t blocks = (int64_t)p.m_tiles * p.n_tiles;
     if (blocks > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_w4a4_linear: too many tiles");
@@ -919,13 +914,14 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     p.flags = reinterpret_cast<unsigned long long *>(workspace);
     p.epoch = next_epoch();
     p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;
-    static bool configured = false;
-    if (!configured) {
+    static std::atomic<bool> configured[kMaxDeviceSlots];
+    const int dslot = device_slot();
+    if (!configured[dslot].load(std::memory_order_acquire)) {
         sqap_status s;
         if constexpr (SPLITK) s = set_lds<C>(&gemm_splitk_kernel<C>);
         else s = set_lds<C>(&gemm_streamk_kernel<C>);
         if (s != SQAP_OK) return s;
-        configured = true;
+        configured[dslot].store(true, std::memory_order_release);
     }
     if constexpr (SPLITK)
         hipLaunchKernelGGL((gemm_splitk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);

@@ -278,11 +278,12 @@ size_t skinny_lds_bytes(int max_chunks)
 template <int S>
 static sqap_status launch_skinny_s(SkinnyArgs &a, size_t lds, int grid_cap, hipStream_t st)
 {
-    static size_t configured = 0;
-    if (lds > configured) {
+    static std::atomic<size_t> configured[kMaxDeviceSlots];
+    const int dslot = device_slot();
+    if (lds > configured[dslot].load(std::memory_order_acquire)) {
         SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_kernel<S>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        configured = lds;
+        configured[dslot].store(lds, std::memory_order_release);
     }
     constexpr int R = kSkinnyWaves / S;
     const int want = (a.total_items + R - 1) / R;
@@ -296,14 +297,7 @@ sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st
 {
     const size_t lds = skinny_lds_bytes(max_chunks);
     if (lds > 160 * 1024) return fail(SQAP_EUNSUPPORTED, "small-M linear: K too large for the LDS staging");
-    static int grid_cap = 0;
-    if (grid_cap == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            cus = 256;
-        grid_cap = 2 * cus;
-    }
+    const int grid_cap = 2 * device_cu_count();
     SkinnyArgs a = args;
     a.xs_bytes = (max_chunks / 2) * 256;
     // aim at about 4096 wavefronts: share an item between S of them when items are few
