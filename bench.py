@@ -388,8 +388,68 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
     ops = lambda M: 2.0 * M * (3 * H * H + H * H + 2 * F * H + H * F)
     total_ops = 2 * ops(S) + 30 * ops(Mk)
     res["TOPS_eager"] = total_ops / eager_us / 1e6
+    res["decode"] = decode_forward_leg(torch, B, wl, dev, layers, buf, g)
     for lw in layers:
         lw.free()
+    return res
+
+
+def decode_forward_leg(torch, B, wl, dev, layers, buf, g, prefix=148, new_tokens=7):
+    """Configuration 4 as a real decode: the 148 pruned tokens are prefilled into per-layer key/value caches,
+    then action tokens are generated one at a time at batch 1: 32 layers (norm, q|k|v, rotary, cache append,
+    attention over the cache, o, norm, gate|up, SwiGLU, down; every linear W4A4 through the small-M kernel),
+    final norm and the 4096 -> 32000 head.  Time per generated token."""
+    from paper_2509_09090_amd import decoder
+    H, F, nh, hd, V = wl.HIDDEN, wl.FFN, wl.N_HEADS, wl.HEAD_DIM, wl.LM_HEAD[1]
+    nl, nd = wl.N_LAYERS, len(layers)
+    head = quantize_and_pack(torch, B, (torch.randn((V, H), generator=g, device=dev, dtype=torch.float32) * 0.02).half())
+    gamma_f = (1 + 0.1 * torch.randn((H,), generator=g, device=dev, dtype=torch.float32)).half()
+    caches = [torch.zeros((prefix + new_tokens, 2 * H), dtype=torch.float16, device=dev) for _ in range(nl)]
+    x0 = torch.randn((prefix, H), generator=g, device=dev, dtype=torch.float32).half()
+    pos = torch.arange(prefix, dtype=torch.int32, device=dev)
+    xa, xb = (torch.empty((prefix, H), dtype=torch.float16, device=dev) for _ in range(2))
+    da, db = (torch.empty((prefix, H), dtype=torch.float16, device=dev) for _ in range(2))
+    src, pend = x0, None
+    for l in range(nl):                                  # prefill (not timed): fills the caches
+        xo, do = (xa, da) if l % 2 == 0 else (xb, db)
+        decoder.layer_forward(layers[l % nd], buf, src, pend, pos, 1, nh, hd, xo, do, kv=caches[l], past=0)
+        src, pend = xo, do
+    tok = torch.randn((1, H), generator=g, device=dev, dtype=torch.float32).half()
+    logits = torch.empty((1, V), dtype=torch.float16, device=dev)
+    x1a, x1b, d1a, d1b = (torch.empty((1, H), dtype=torch.float16, device=dev) for _ in range(4))
+    p1 = [torch.tensor([prefix + i], dtype=torch.int32, device=dev) for i in range(new_tokens)]
+
+    def step(i):
+        src, pend = tok, None
+        for l in range(nl):
+            xo, do = (x1a, d1a) if l % 2 == 0 else (x1b, d1b)
+            decoder.layer_forward(layers[l % nd], buf, src, pend, p1[i], 1, nh, hd, xo, do, kv=caches[l], past=prefix + i)
+            src, pend = xo, do
+        B.sqap_rmsnorm_quantize_act(src, None, gamma_f, 1e-5, buf.xq[:1], buf.sx[:1], delta=pend)
+        B.sqap_w4a4_linear(buf.xq[:1], buf.sx[:1], head, logits, None, buf.ws)
+
+    def generate():
+        for i in range(new_tokens):
+            step(i)
+
+    generate()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        generate()
+    e1.record()
+    torch.cuda.synchronize()
+    us_eager = e0.elapsed_time(e1) * 1e3 / (3 * new_tokens)
+    res = {"us_per_token_eager": us_eager, "launches_per_token": nl * 11 + 2, "prefix": prefix,
+           "new_tokens": new_tokens}
+    try:
+        res["us_per_token_graph"] = graph_time_us(torch, generate, 3, per_graph=1) / new_tokens
+    except Exception as exc:
+        res["graph_error"] = repr(exc)[:200]
+    weight_bytes = nl * (3 * H * H + H * H + 2 * F * H + H * F) // 2 + V * H // 2
+    res["GBps_weights_graph"] = weight_bytes / res.get("us_per_token_graph", us_eager) / 1e3
+    head.free()
     return res
 
 

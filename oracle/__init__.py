@@ -359,13 +359,14 @@ def residual_add(X, delta):
 
 
 def decoder_layer(x, pending, pos, batch, weights, gamma_attn, gamma_mlp, n_heads, head_dim, eps=1e-5,
-                  rotate=False, attn_override=None):
+                  rotate=False, attn_override=None, past_k=None, past_v=None):
     """One pre-normalisation Llama layer as a chain of the functions above; every stage is returned.
 
     x [M, hidden] fp16 residual stream, pending [M, hidden] or None, pos [M] positions, batch
     sequences of M / batch rows.  weights: dict name -> (packed int4 [N, K/2], scales [N]) for
     'qkv' (N = 3 hidden), 'o', 'gate_up' (N = 2 ffn), 'down'.  attn_override replaces the attention
-    output (lets a test continue from another implementation's result).
+    output (lets a test continue from another implementation's result).  past_k, past_v [P, hidden]:
+    rotated keys and values of P earlier positions of the (single) sequence, placed in front of the new ones.
     """
     M, hidden = x.shape
     S = M // batch
@@ -379,8 +380,14 @@ def decoder_layer(x, pending, pos, batch, weights, gamma_attn, gamma_mlp, n_head
     k = rope(qkv[:, hidden:2 * hidden].reshape(M, n_heads, head_dim), pos)
     v = np.ascontiguousarray(qkv[:, 2 * hidden:]).reshape(M, n_heads, head_dim)
     st["q_rot"], st["k_rot"] = q.reshape(M, hidden), k.reshape(M, hidden)
-    a = np.concatenate([attention(q[b * S:(b + 1) * S], k[b * S:(b + 1) * S], v[b * S:(b + 1) * S])
-                        for b in range(batch)]).reshape(M, hidden)
+    if past_k is not None:
+        assert batch == 1
+        kk = np.concatenate([_c(past_k, np.float16).reshape(-1, n_heads, head_dim), k])
+        vv = np.concatenate([_c(past_v, np.float16).reshape(-1, n_heads, head_dim), v])
+        a = attention(q, kk, vv).reshape(M, hidden)
+    else:
+        a = np.concatenate([attention(q[b * S:(b + 1) * S], k[b * S:(b + 1) * S], v[b * S:(b + 1) * S])
+                            for b in range(batch)]).reshape(M, hidden)
     st["attn"] = a
     if attn_override is not None:
         a = attn_override

@@ -45,19 +45,24 @@ class LayerBuffers:
         self.gu = torch.empty((max_rows, 2 * ffn), dtype=f16, device=device)
         self.hq = torch.empty((max_rows, ffn // 2), dtype=u8, device=device)
         self.sh = torch.empty((max_rows,), dtype=f16, device=device)
-        nbytes = max(B.sqap_workspace_bytes(max_rows, n, k)
+        # the workspace a linear needs is not monotonic in M (the tile shape changes with M): take the largest
+        nbytes = max(B.sqap_workspace_bytes(m, n, k) for m in range(1, max_rows + 1)
                      for (n, k) in ((3 * hidden, hidden), (hidden, hidden), (2 * ffn, hidden), (hidden, ffn)))
         self.ws = torch.zeros((max(nbytes, 256),), dtype=u8, device=device)
+        self.iota = torch.arange(max_rows, dtype=torch.int32, device=device)
 
 
 def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_out, eps=1e-5, rows=None,
-                  rotate=False, stream=None):
+                  rotate=False, kv=None, past=0, stream=None):
     """Runs one layer on M token rows (batch sequences of M / batch tokens each).
 
     x: residual stream [*, hidden] fp16 (rows picks the M rows when given: the token gather is fused);
     pending: [M, hidden] update not yet added to x, or None; pos: [M] int32 positions.
     x_out [M, hidden] receives the residual stream after the attention block, d_out [M, hidden] the
     feed-forward output still to be added to it (the next call's `pending`).
+    kv: this layer's key/value cache of ONE sequence, [capacity, 2 * hidden] fp16 (rotated key | value per
+    position), holding `past` positions: the M new rows are appended and attention runs over past + M
+    keys (prefill fills the cache with past = 0; a decode step has M = 1).  Needs batch == 1.
     """
     M = pos.numel()
     hidden = buf.hidden
@@ -68,8 +73,15 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
                                 stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.qkv, qkv, None, buf.ws, stream=stream)
     B.sqap_rope(qkv[:, :2 * hidden], pos, 2 * n_heads, head_dim, stream=stream)      # queries and keys in one launch
-    B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
-                     batch=batch, stream=stream)
+    if kv is None:
+        B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
+                         batch=batch, stream=stream)
+    else:
+        if batch != 1:
+            raise ValueError("a key/value cache belongs to one sequence")
+        B.sqap_gather_rows(qkv[:, hidden:], buf.iota[:M], kv[past:past + M], stream=stream)   # key | value rows
+        B.sqap_attention(qkv[:, :hidden], kv[:past + M, :hidden], kv[:past + M, hidden:], n_heads, head_dim, attn,
+                         stream=stream)
     B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.o, o, None, buf.ws, stream=stream)
     B.sqap_rmsnorm_quantize_act(x_out, None, w.gamma_mlp, eps, xq, sx, delta=o, xsum_out=x_out, stream=stream)

@@ -317,3 +317,45 @@ def test_glue_at_full_size_on_sampled_rows(G, oracle):
         cut = lambda part: np.ascontiguousarray(blk[:, part * H * d + h * d: part * H * d + (h + 1) * d]).reshape(S, 1, d)
         want = oracle.attention(cut(0), cut(1), cut(2)).reshape(S, d)
         assert G.assert_fp16_close(got[b * S:(b + 1) * S, h * d:(h + 1) * d], want) >= 0
+
+
+def test_decoder_layer_with_a_key_value_cache(G, oracle):
+    """Prefill 21 tokens into the cache, then three single-token steps: the cache rows are what the prefill and
+    the steps wrote, attention runs over all of them, and everything downstream of it is exact."""
+    import torch
+    from paper_2509_09090_amd import decoder
+    hidden, H, d, F, S, steps = 256, 4, 64, 512, 21, 3
+    x, pend, pos, ws, w, g1, g2, M = _layer_case(oracle, G, 77, hidden, H, d, F, 1, S, False)
+    rng = np.random.default_rng(78)
+    buf = decoder.LayerBuffers(S, hidden, F)
+    kv = torch.zeros((S + steps, 2 * hidden), dtype=torch.float16, device="cuda")
+    x_out = torch.zeros((S, hidden), dtype=torch.float16, device="cuda")
+    d_out = torch.zeros((S, hidden), dtype=torch.float16, device="cuda")
+    decoder.layer_forward(w, buf, G.to_dev(x), G.to_dev(pend), G.to_dev(pos), 1, H, d, x_out, d_out, kv=kv, past=0)
+    torch.cuda.synchronize()
+    st = oracle.decoder_layer(x, pend, pos, 1, ws, g1, g2, H, d, attn_override=buf.attn[:S].cpu().numpy())
+    cache = kv.cpu().numpy()
+    assert G.assert_fp16_close(cache[:S, :hidden], st["k_rot"]) >= 0
+    assert np.array_equal(cache[:S, hidden:].view(np.uint16), st["qkv"][:, 2 * hidden:].view(np.uint16))
+    assert G.assert_fp16_close(buf.attn[:S].cpu().numpy(), st["attn"]) >= 0
+    assert G.assert_fp16_close(d_out.cpu().numpy(), st["d"]) == 0
+    past = S
+    for step in range(steps):
+        xt = _acts(rng, 1, hidden)
+        pt = np.array([int(pos[-1]) + 1 + step], np.int32)
+        x1 = torch.zeros((1, hidden), dtype=torch.float16, device="cuda")
+        d1 = torch.zeros((1, hidden), dtype=torch.float16, device="cuda")
+        before = kv.cpu().numpy()[:past]
+        decoder.layer_forward(w, buf, G.to_dev(xt), None, G.to_dev(pt), 1, H, d, x1, d1, kv=kv, past=past)
+        torch.cuda.synchronize()
+        after = kv.cpu().numpy()
+        assert np.array_equal(after[:past].view(np.uint16), before.view(np.uint16))          # earlier rows untouched
+        st = oracle.decoder_layer(xt, None, pt, 1, ws, g1, g2, H, d, attn_override=buf.attn[:1].cpu().numpy(),
+                                  past_k=before[:, :hidden], past_v=before[:, hidden:])
+        assert G.assert_fp16_close(after[past:past + 1, :hidden], st["k_rot"]) >= 0
+        assert np.array_equal(after[past:past + 1, hidden:].view(np.uint16), st["qkv"][:, 2 * hidden:].view(np.uint16))
+        assert G.assert_fp16_close(buf.attn[:1].cpu().numpy(), st["attn"]) >= 0               # over the device's own cache
+        assert np.array_equal(x1.cpu().numpy().view(np.uint16), st["x2"].view(np.uint16))
+        assert G.assert_fp16_close(d1.cpu().numpy(), st["d"]) == 0
+        past += 1
+    w.free()
