@@ -84,6 +84,37 @@ __device__ __forceinline__ void block_run(const SkinnyEntry *table, int count, i
     *end = to_the_end ? total_items : item_of(n_hi - 1, hi);
 }
 
+// A launch with at most kSkinnyInline problems carries them in the kernel arguments.  They are read
+// with constant indices only: taking the address of a kernel argument would make the compiler copy the
+// whole argument block (368 bytes) into every lane's scratch memory at kernel start.
+#define SQAP_INLINE_FIELD(a, p, field) \
+    ((p) == 0 ? (a).inline_entries[0].field : (p) == 1 ? (a).inline_entries[1].field : \
+     (p) == 2 ? (a).inline_entries[2].field : (a).inline_entries[3].field)
+
+// block_run for inline problems (count <= 4): the same boundaries, from scalar arithmetic.
+__device__ __forceinline__ void inline_run(const SkinnyArgs &a, long long lo, long long hi, bool to_the_end, int *beg,
+                                           int *end, int *problem)
+{
+    int n_lo = 0, n_hi = 0;
+#pragma unroll
+    for (int p = 0; p < kSkinnyInline; ++p) {
+        if (p < a.count) {
+            const long long c = SQAP_INLINE_FIELD(a, p, cost_begin);
+            n_lo += c <= lo ? 1 : 0;
+            n_hi += c <= hi ? 1 : 0;
+        }
+    }
+    auto item_of = [&](int p, long long target) {
+        const long long into = target - SQAP_INLINE_FIELD(a, p, cost_begin);
+        const int ch = SQAP_INLINE_FIELD(a, p, chunks);
+        const long long it = SQAP_INLINE_FIELD(a, p, rg_begin) + (into + ch - 1) / ch;
+        return it < a.total_items ? (int)it : a.total_items;
+    };
+    *problem = n_lo - 1;
+    *beg = item_of(n_lo - 1, lo);
+    *end = to_the_end ? a.total_items : item_of(n_hi - 1, hi);
+}
+
 // LDS: [0, 16): zeros; then the packed activations of the current problem,
 // 256 bytes per chunk pair cp: [k-half h][row r < 8][16 bytes]; then (S > 1)
 // 1 KiB per wavefront for the partial sums.
@@ -109,26 +140,47 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
     uint8_t *xs = smem + kSkinnyZeroBytes;
     if (t < 4) reinterpret_cast<int *>(smem)[t] = 0;
 
-    const SkinnyEntry *table = a.table ? a.table : a.inline_entries;
+    const SkinnyEntry *table = a.table;
+    const bool inl = table == nullptr;             // the problems are in the kernel arguments
     int prob, beg, end;                            // prob: the problem the first item belongs to (or the one before it)
-    block_run(table, a.count, a.total_items, a.total_cost * blockIdx.x / gridDim.x,
-              a.total_cost * (blockIdx.x + 1) / gridDim.x, blockIdx.x + 1 == gridDim.x, lane, &beg, &end, &prob);
+    if (inl)
+        inline_run(a, a.total_cost * blockIdx.x / gridDim.x, a.total_cost * (blockIdx.x + 1) / gridDim.x,
+                   blockIdx.x + 1 == gridDim.x, &beg, &end, &prob);
+    else
+        block_run(table, a.count, a.total_items, a.total_cost * blockIdx.x / gridDim.x,
+                  a.total_cost * (blockIdx.x + 1) / gridDim.x, blockIdx.x + 1 == gridDim.x, lane, &beg, &end, &prob);
+    auto rg_begin_of = [&](int p) { return inl ? SQAP_INLINE_FIELD(a, p, rg_begin) : uni(table[p].rg_begin); };
     const int r = lane & 31, h = lane >> 5;
     for (int cur = beg; cur < end;) {
-        while (prob + 1 < a.count && cur >= uni(table[prob + 1].rg_begin)) ++prob;
-        SkinnyEntry e = table[prob];
-        e.Xq = uni(e.Xq);
-        e.sx = uni(e.sx);
-        e.Wd = uni(e.Wd);
-        e.sw = uni(e.sw);
-        e.Y = uni(e.Y);
-        e.acc_out = uni(e.acc_out);
-        e.ldy = uni((long long)e.ldy);
-        e.M = uni(e.M);
-        e.N = uni(e.N);
-        e.chunks = uni(e.chunks);
-        e.rg_begin = uni(e.rg_begin);
-        const int next_begin = prob + 1 < a.count ? uni(table[prob + 1].rg_begin) : end;
+        while (prob + 1 < a.count && cur >= rg_begin_of(prob + 1)) ++prob;
+        SkinnyEntry e;
+        if (inl) {
+            e.Xq = SQAP_INLINE_FIELD(a, prob, Xq);
+            e.sx = SQAP_INLINE_FIELD(a, prob, sx);
+            e.Wd = SQAP_INLINE_FIELD(a, prob, Wd);
+            e.sw = SQAP_INLINE_FIELD(a, prob, sw);
+            e.Y = SQAP_INLINE_FIELD(a, prob, Y);
+            e.acc_out = SQAP_INLINE_FIELD(a, prob, acc_out);
+            e.ldy = SQAP_INLINE_FIELD(a, prob, ldy);
+            e.M = SQAP_INLINE_FIELD(a, prob, M);
+            e.N = SQAP_INLINE_FIELD(a, prob, N);
+            e.chunks = SQAP_INLINE_FIELD(a, prob, chunks);
+            e.rg_begin = SQAP_INLINE_FIELD(a, prob, rg_begin);
+        } else {
+            e = table[prob];
+            e.Xq = uni(e.Xq);
+            e.sx = uni(e.sx);
+            e.Wd = uni(e.Wd);
+            e.sw = uni(e.sw);
+            e.Y = uni(e.Y);
+            e.acc_out = uni(e.acc_out);
+            e.ldy = uni((long long)e.ldy);
+            e.M = uni(e.M);
+            e.N = uni(e.N);
+            e.chunks = uni(e.chunks);
+            e.rg_begin = uni(e.rg_begin);
+        }
+        const int next_begin = prob + 1 < a.count ? rg_begin_of(prob + 1) : end;
         const int seg_end = next_begin < end ? next_begin : end;
         const int cps = e.chunks >> 1;
 
