@@ -144,14 +144,14 @@ def test_swiglu_quantize(G, oracle, M, F, channelwise, sliced):
     assert np.array_equal(Xq.cpu().numpy(), q_o)
 
 
-@pytest.mark.parametrize("S,H,d", [(276, 32, 128), (5, 3, 16), (148, 4, 64)])
+@pytest.mark.parametrize("S,H,d", [(276, 32, 128), (5, 3, 16), (148, 4, 64), (700, 6, 64)])
 def test_rope(G, oracle, S, H, d):
     import torch
     from paper_2509_09090_amd import binding as B
     rng = np.random.default_rng(S + H + d)
     width = 3 * H * d                                           # rotated where it lies inside a fused q|k|v row
     Y = rng.standard_normal((S, width)).astype(np.float16)
-    pos = np.sort(rng.choice(400, size=S, replace=False)).astype(np.int32)
+    pos = np.sort(rng.choice(max(400, 2 * S), size=S, replace=False)).astype(np.int32)
     want = Y.copy()
     want[:, :H * d] = oracle.rope(Y[:, :H * d].reshape(S, H, d), pos).reshape(S, H * d)
     want[:, H * d:2 * H * d] = oracle.rope(Y[:, H * d:2 * H * d].reshape(S, H, d), pos).reshape(S, H * d)
