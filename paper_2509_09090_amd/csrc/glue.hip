@@ -247,7 +247,8 @@ __global__ __launch_bounds__(64 * kAttWaves) void attention_mfma_kernel(const __
     const int shift = Sk - Sq;
     const int my_q = q0 + c;
     const bool q_ok = my_q < Sq;
-    const float inv_sqrt_d = 1.0f / sqrtf((float)D);
+    // scores are kept in units of ln 2, so that the exponentials are single v_exp_f32 instructions
+    const float inv_sqrt_d = 1.4426950408889634f / sqrtf((float)D);
     union Piece { uint4 u; v4h v[2]; };
 
     Piece qf[NP];
@@ -320,12 +321,12 @@ __global__ __launch_bounds__(64 * kAttWaves) void attention_mfma_kernel(const __
         }
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float m_new = fmaxf(mrun, tmax);
-        const float rescale = m_new == -INFINITY ? 1.f : expf(mrun - m_new);
+        const float rescale = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(mrun - m_new);
         float tsum = 0.f;
         v4h pb[4];
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const float pi = st[i] == -INFINITY ? 0.f : expf(st[i] - m_new);
+            const float pi = st[i] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(st[i] - m_new);
             tsum += pi;
             pb[i >> 2][i & 3] = (_Float16)pi;
         }
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(64 * kAttWaves) void attention_mfma_kernel(const __
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
             for (int i = 0; i < 16; ++i) ot[ct][i] *= rescale;
-        __builtin_amdgcn_wave_barrier();                     // the transposed tile is written (same wavefront, in order)
+        __builtin_amdgcn_wave_barrier();                     // the value tile is written (same wavefront, in order)
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(64 * kAttWaves) void attention_mfma_kernel(const __
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const float mw = ml[(w * 64 + l) * 2];
-            f[w] = mw == -INFINITY ? 0.f : expf(mw - mall);
+            f[w] = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - mall);
             lall += ml[(w * 64 + l) * 2 + 1] * f[w];
         }
         v16f acc;
