@@ -389,6 +389,16 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
     total_ops = 2 * ops(S) + 30 * ops(Mk)
     res["TOPS_eager"] = total_ops / eager_us / 1e6
     res["decode"] = decode_forward_leg(torch, B, wl, dev, layers, buf, g)
+    # one layer at configuration 3's batch: 16 observations x 148 tokens = 2368 rows
+    nb, Sp = 16, 148
+    big = decoder.LayerBuffers(nb * Sp, H, F, device=dev)
+    xb3 = torch.randn((nb * Sp, H), generator=g, device=dev, dtype=torch.float32).half()
+    pend3 = torch.randn((nb * Sp, H), generator=g, device=dev, dtype=torch.float32).half()
+    pos3 = torch.arange(Sp, dtype=torch.int32, device=dev).repeat(nb)
+    xo3, do3 = torch.empty_like(xb3), torch.empty_like(xb3)
+    res["us_layer_cfg3_batch16"] = graph_time_us(
+        torch, lambda: decoder.layer_forward(layers[0], big, xb3, pend3, pos3, nb, nh, hd, xo3, do3), 10, per_graph=2)
+    del big
     for lw in layers:
         lw.free()
     return res
