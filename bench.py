@@ -406,7 +406,7 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
 
 def decode_forward_leg(torch, B, wl, dev, layers, buf, g, prefix=148, new_tokens=7):
     """Configuration 4 as a real decode: the 148 pruned tokens are prefilled into per-layer key/value caches,
-    then action tokens are generated one at a time at batch 1: 32 layers (norm, q|k|v, rotary, cache append,
+    then action tokens are generated one at a time at batch 1: 32 layers (norm, q|k|v, rotary + cache append,
     attention over the cache, o, norm, gate|up, SwiGLU, down; every linear W4A4 through the small-M kernel),
     final norm and the 4096 -> 32000 head.  Time per generated token."""
     from paper_2509_09090_amd import decoder
@@ -451,7 +451,7 @@ def decode_forward_leg(torch, B, wl, dev, layers, buf, g, prefix=148, new_tokens
     e1.record()
     torch.cuda.synchronize()
     us_eager = e0.elapsed_time(e1) * 1e3 / (3 * new_tokens)
-    res = {"us_per_token_eager": us_eager, "launches_per_token": nl * 11 + 2, "prefix": prefix,
+    res = {"us_per_token_eager": us_eager, "launches_per_token": nl * 10 + 2, "prefix": prefix,
            "new_tokens": new_tokens}
     try:
         res["us_per_token_graph"] = graph_time_us(torch, generate, 3, per_graph=1) / new_tokens

@@ -325,6 +325,12 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
  * (elements), so a slice of a fused q/k/v output can be rotated where it lies.
  * pos: [S] int32 device.  EINVAL: null pointer, d odd, ld < H*d, base <= 0.
  *
+ * sqap_rope_append: the same rotation for a block of fused q|k|v rows [S, 3*H*d] (pitch ld) with the
+ * key/value cache append folded in: queries are rotated in place; keys are rotated into KV[s, 0 .. H*d) and
+ * values copied into KV[s, H*d .. 2*H*d) (KV: the cache rows these S tokens occupy, pitch ldkv >= 2*H*d); the
+ * key and value columns of QKV are left as they were.  Bit-identical to sqap_rope on the q and k slices
+ * followed by a row copy.  EINVAL: null pointer, d odd, a pitch too small, base <= 0.
+ *
  * sqap_attention: causal softmax attention.  Query i (of Sq) sits at position
  * Sk - Sq + i of the key sequence and sees keys 0 .. Sk - Sq + i:
  *   o[i,h,:] = sum_t softmax_t((q[i,h,:] . k[t,h,:]) / sqrt(d)) v[t,h,:]
@@ -340,6 +346,8 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
  */
 sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d,
                       double base, void *stream);
+sqap_status sqap_rope_append(sqap_f16 *QKV, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d,
+                             double base, sqap_f16 *KV, int64_t ldkv, void *stream);
 sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk,
                            const sqap_f16 *V, int64_t ldv, int32_t batch, int32_t Sq, int32_t Sk, int32_t H,
                            int32_t d, sqap_f16 *O, int64_t ldo, void *stream);

@@ -23,7 +23,7 @@ EXPORTS = (
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
-    "sqap_attention", "sqap_residual_add",
+    "sqap_attention", "sqap_residual_add", "sqap_rope_append",
 )
 
 
@@ -70,6 +70,7 @@ def lib():
         L.sqap_rmsnorm_quantize_act.argtypes = [vp, i64, vp, i32, i32, vp, vp, ctypes.c_float, u32, vp, vp, vp, vp, vp, vp]
         L.sqap_swiglu_quantize_act.argtypes = [vp, i64, vp, i64, i32, i32, vp, vp, vp, vp, vp]
         L.sqap_rope.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp]
+        L.sqap_rope_append.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp, i64, vp]
         L.sqap_attention.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, i64, vp]
         L.sqap_residual_add.argtypes = [vp, i64, vp, i64, i32, i32, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
@@ -242,6 +243,12 @@ def sqap_swiglu_quantize_act(G, U, Xq, sx, col_scales=None, h_out=None, stream=N
 def sqap_rope(X, pos, H, d, base=10000.0, stream=None):
     """X [S, >= H*d] fp16 (row pitch = X.stride(0)), rotated in place at positions pos [S] int32."""
     _check(lib().sqap_rope(_ptr(X), X.stride(0), _ptr(pos), X.shape[0], H, d, base, _stream(stream)))
+
+
+def sqap_rope_append(QKV, pos, H, d, KV, base=10000.0, stream=None):
+    """QKV [S, 3*H*d] fused rows: q rotated in place, rotated k | v written to the cache rows KV [S, 2*H*d]."""
+    _check(lib().sqap_rope_append(_ptr(QKV), QKV.stride(0), _ptr(pos), QKV.shape[0], H, d, base, _ptr(KV),
+                                  KV.stride(0), _stream(stream)))
 
 
 def sqap_attention(Q, K, V, H, d, O, batch=1, stream=None):

@@ -272,6 +272,19 @@ sqap_status sqap_rope(sqap_f16 *X, int64_t ld, const int32_t *pos, int32_t S, in
     return launch_rope(reinterpret_cast<__half *>(X), ld, pos, S, H, d, base, as_stream(stream));
 }
 
+sqap_status sqap_rope_append(sqap_f16 *QKV, int64_t ld, const int32_t *pos, int32_t S, int32_t H, int32_t d,
+                             double base, sqap_f16 *KV, int64_t ldkv, void *stream)
+{
+    if (S < 0 || H <= 0 || d <= 0 || (d & 1)) return fail(SQAP_EINVAL, "sqap_rope_append: S %d, H %d, d %d", S, H, d);
+    if (ld < (int64_t)3 * H * d || ldkv < (int64_t)2 * H * d)
+        return fail(SQAP_EINVAL, "sqap_rope_append: pitch below 3 H d (q|k|v) or 2 H d (cache)");
+    if (!(base > 0.0)) return fail(SQAP_EINVAL, "sqap_rope_append: base must be positive");
+    if (S == 0) return SQAP_OK;
+    if (!QKV || !pos || !KV) return fail(SQAP_EINVAL, "sqap_rope_append: null pointer");
+    return launch_rope_append(reinterpret_cast<__half *>(QKV), ld, pos, S, H, d, base, reinterpret_cast<__half *>(KV),
+                              ldkv, as_stream(stream));
+}
+
 sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk, const sqap_f16 *V,
                            int64_t ldv, int32_t batch, int32_t Sq, int32_t Sk, int32_t H, int32_t d, sqap_f16 *O,
                            int64_t ldo, void *stream)

@@ -32,6 +32,51 @@ __global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ X, int64
     v[i + half_d] = __float2half_rn((float)(hi * cs + lo * sn));
 }
 
+// Rotary embedding of a fused q|k|v row block with the key/value cache append folded in: queries are rotated
+// in place, keys are rotated on their way into the cache row (the copy in the q|k|v buffer stays as it was),
+// values are copied.  Same arithmetic as rope_kernel; one launch instead of a rotation and a row copy.
+// One thread per (token, head-or-value slot, i): slots 0 .. H-1 queries, H .. 2H-1 keys, 2H .. 3H-1 values.
+__global__ __launch_bounds__(256) void rope_append_kernel(__half *__restrict__ QKV, int64_t ld,
+                                                          const int32_t *__restrict__ pos, int S, int H, int d,
+                                                          double base, __half *__restrict__ KV, int64_t ldkv)
+{
+    const int half_d = d >> 1;
+    const int64_t total = (int64_t)S * 3 * H * half_d;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half_d);
+    const int64_t sh = idx / half_d;
+    const int slot = (int)(sh % (3 * H));
+    const int s = (int)(sh / (3 * H));
+    const __half *src = QKV + (int64_t)s * ld + (int64_t)slot * d;
+    if (slot >= 2 * H) {                                      // value: plain copy of the pair
+        __half *dst = KV + (int64_t)s * ldkv + (int64_t)(slot - H) * d;
+        dst[i] = src[i];
+        dst[i + half_d] = src[i + half_d];
+        return;
+    }
+    const double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+    double sn, cs;
+    sincos(a, &sn, &cs);
+    const double lo = (double)__half2float(src[i]), hi = (double)__half2float(src[i + half_d]);
+    const __half r0 = __float2half_rn((float)(lo * cs - hi * sn));
+    const __half r1 = __float2half_rn((float)(hi * cs + lo * sn));
+    __half *dst = slot < H ? QKV + (int64_t)s * ld + (int64_t)slot * d : KV + (int64_t)s * ldkv + (int64_t)(slot - H) * d;
+    dst[i] = r0;
+    dst[i + half_d] = r1;
+}
+
+sqap_status launch_rope_append(__half *QKV, int64_t ld, const int32_t *pos, int S, int H, int d, double base,
+                               __half *KV, int64_t ldkv, hipStream_t st)
+{
+    const int64_t total = (int64_t)S * 3 * H * (d / 2);
+    if (total == 0) return SQAP_OK;
+    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, QKV, ld, pos, S, H, d,
+                       base, KV, ldkv);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
 // The same for many tokens: one workgroup per token evaluates the d/2 angles of its position once (the
 // binary64 power, sine and cosine are a few hundred instructions per pair) and shares them between the
 // heads through LDS.  With few tokens the per-pair kernel is faster (more threads in flight: 6.7 against

@@ -5,7 +5,8 @@ published pre-normalisation layer:
 
     y1 = RMSNorm(x + pending) -> int4        sqap_rmsnorm_quantize_act   (also writes x + pending)
     q|k|v = W_qkv y1                         sqap_w4a4_linear            (one GEMM, N = 3 * hidden)
-    q, k <- rotary(q, k)                     sqap_rope                   (one launch: 2 * heads columns)
+    q, k <- rotary(q, k)                     sqap_rope                   (one launch: 2 * heads columns;
+                                             sqap_rope_append with a key/value cache: append folded in)
     a = causal attention(q, k, v)            sqap_attention
     o = W_o quant(a)                         sqap_quantize_act + sqap_w4a4_linear
     y2 = RMSNorm(x + o) -> int4              sqap_rmsnorm_quantize_act   (residual add fused)
@@ -72,14 +73,15 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
     B.sqap_rmsnorm_quantize_act(x, rows, w.gamma_attn, eps, xq, sx, delta=pending, flags=flags, xsum_out=x_out,
                                 stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.qkv, qkv, None, buf.ws, stream=stream)
-    B.sqap_rope(qkv[:, :2 * hidden], pos, 2 * n_heads, head_dim, stream=stream)      # queries and keys in one launch
     if kv is None:
+        B.sqap_rope(qkv[:, :2 * hidden], pos, 2 * n_heads, head_dim, stream=stream)  # queries and keys in one launch
         B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
                          batch=batch, stream=stream)
     else:
         if batch != 1:
             raise ValueError("a key/value cache belongs to one sequence")
-        B.sqap_gather_rows(qkv[:, hidden:], buf.iota[:M], kv[past:past + M], stream=stream)   # key | value rows
+        # rotation and cache append in one launch: rotated key | value rows land in the cache
+        B.sqap_rope_append(qkv, pos, n_heads, head_dim, kv[past:past + M], stream=stream)
         B.sqap_attention(qkv[:, :hidden], kv[:past + M, :hidden], kv[:past + M, hidden:], n_heads, head_dim, attn,
                          stream=stream)
     B.sqap_quantize_act(attn, None, xq, sx, stream=stream)

@@ -129,6 +129,10 @@ def test_glue_validation():
     assert L.sqap_rope(p, 64, p, 2, 2, 33, ctypes.c_double(1e4), None) == B.EINVAL
     assert L.sqap_rope(p, 32, p, 2, 2, 32, ctypes.c_double(1e4), None) == B.EINVAL
     assert L.sqap_rope(None, 64, None, 0, 2, 32, ctypes.c_double(1e4), None) == B.OK
+    assert L.sqap_rope_append(p, 64, p, 2, 2, 32, ctypes.c_double(1e4), p, 128, None) == B.EINVAL      # q|k|v pitch below 3 H d
+    assert L.sqap_rope_append(p, 192, p, 2, 2, 32, ctypes.c_double(1e4), p, 64, None) == B.EINVAL      # cache pitch below 2 H d
+    assert L.sqap_rope_append(p, 192, p, 2, 2, 32, ctypes.c_double(1e4), None, 128, None) == B.EINVAL
+    assert L.sqap_rope_append(None, 192, None, 0, 2, 32, ctypes.c_double(1e4), None, 128, None) == B.OK
     assert L.sqap_attention(p, 64, p, 64, p, 64, 1, 5, 4, 1, 64, p, 64, None) == B.EINVAL
     assert L.sqap_attention(p, 64, p, 64, p, 32, 1, 4, 4, 1, 64, p, 64, None) == B.EINVAL       # pitch below H * d
     assert L.sqap_attention(p, 48, p, 48, p, 48, 1, 4, 4, 1, 48, p, 48, None) == B.EUNSUPPORTED

@@ -167,6 +167,31 @@ def test_rope(G, oracle, S, H, d):
     assert np.count_nonzero(got.view(np.uint16) != want.view(np.uint16)) <= got.size // 200          # both are binary64 -> half
 
 
+def test_rope_append_equals_rotation_plus_row_copy(G, oracle):
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(41)
+    S, H, d, past = 9, 4, 64, 5
+    width = H * d
+    QKV = rng.standard_normal((S, 3 * width)).astype(np.float16)
+    pos = (np.arange(S) * 3 + 2).astype(np.int32)
+    a = G.to_dev(QKV)
+    b = G.to_dev(QKV)
+    p = G.to_dev(pos)
+    cache = torch.full((past + S + 2, 2 * width + 16), 7.0, dtype=torch.float16, device="cuda")    # wider pitch, guard rows
+    B.sqap_rope_append(a, p, H, d, cache[past:past + S, :2 * width])
+    B.sqap_rope(b[:, :2 * width], p, 2 * H, d)
+    torch.cuda.synchronize()
+    an, bn, cn = a.cpu().numpy(), b.cpu().numpy(), cache.cpu().numpy()
+    assert np.array_equal(an[:, :width].view(np.uint16), bn[:, :width].view(np.uint16))                  # q rotated in place
+    assert np.array_equal(an[:, width:].view(np.uint16), QKV[:, width:].view(np.uint16))                 # k, v columns untouched
+    assert np.array_equal(cn[past:past + S, :width].view(np.uint16), bn[:, width:2 * width].view(np.uint16))
+    assert np.array_equal(cn[past:past + S, width:2 * width].view(np.uint16), QKV[:, 2 * width:].view(np.uint16))
+    assert np.all(cn[:past] == 7.0) and np.all(cn[past + S:] == 7.0) and np.all(cn[:, 2 * width:] == 7.0)
+    want_q = oracle.rope(QKV[:, :width].reshape(S, H, d), pos).reshape(S, width)
+    assert G.assert_fp16_close(an[:, :width], want_q) >= 0
+
+
 @pytest.mark.parametrize("Sq,Sk,H,d", [(276, 276, 32, 128), (148, 148, 8, 128), (1, 149, 32, 128), (8, 156, 4, 64),
                                        (70, 70, 3, 16), (33, 97, 2, 32), (1, 1, 1, 16)])
 def test_attention(G, oracle, Sq, Sk, H, d):
