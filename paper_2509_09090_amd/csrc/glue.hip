@@ -123,11 +123,12 @@ sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H,
 
 // Causal attention.  Query i (of Sq) sits at sequence position Sk - Sq + i and sees keys 0 ..
 // Sk - Sq + i.  A batch of sequences is a stack of row blocks (Sq rows of Q and O, Sk rows of K
-// and V per sequence).  One workgroup per (head, block of 32 queries, sequence); keys and values pass through LDS
-// in tiles of 64.  Thread t works for query t/8: in the score phase on keys 8(t%8) .. +7 of the
-// tile, in the output phase on the D/8 consecutive head-dimension columns from (t%8) D/8 on.
-// Running maximum m, running sum l and the output row are
-// rescaled when a tile raises the maximum (the usual online softmax); all in binary32.
+// and V per sequence).  This scalar form serves the small head sizes (16 and 32): one workgroup per
+// (head, block of 32 queries, sequence); keys and values pass through LDS in tiles of 64.  Thread t
+// works for query t/8: in the score phase on keys 8(t%8) .. +7 of the tile, in the output phase on
+// the D/8 consecutive head-dimension columns from (t%8) D/8 on.  Running maximum m, running sum l
+// and the output row are rescaled when a tile raises the maximum (the usual online softmax); all in
+// binary32.
 constexpr int kAttQ = 32, kAttK = 64;
 
 template <int D>
@@ -248,9 +249,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
     }
 }
 
-// The same attention on the matrix cores, for head sizes 64 and 128: one wavefront per (head, block of
-// 32 queries, sequence), key tiles of 32.  Everything is kept transposed so that no accumulator ever has
-// to change lanes:
+// The same attention on the matrix cores, for head sizes 64 and 128: one workgroup of four wavefronts per
+// (head, block of 32 queries, sequence), key tiles of 32.  Everything is kept transposed so that no
+// accumulator ever has to change lanes:
 //   S^T = K Q^T      v_mfma_f32_32x32x8_f16 with A = key rows, B = query rows: lane l holds query l%32,
 //                    register i key 8(i/4) + 4(l/32) + i%4 of the tile;
 //   softmax          over registers and the two lane halves (one cross-lane exchange);
@@ -258,11 +259,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const __half *__restrict
 //                    block b (keys 8b + 4(l/32) + 0..3); A = V^T is read column-wise (2 bytes at a time)
 //                    from the value tile in LDS.
 // The running maximum, the running sum and the rescaling of O^T are per query, i.e. per lane.  The four
-// wavefronts of a workgroup take the key tiles in turn (tile t belongs to wavefront t % 4), so a sequence of
-// up to 128 keys costs one round of loads, and merge their partial (m, l, O^T) through LDS at the end: wavefront
-// w collects column tile w of the output from the other three.  The reduction
-// over the head dimension may visit it in any order as long as A and B agree: MFMA j takes elements
-// 16(j/2) + 8(l/32) + 4(j%2) + 0..3, so that each lane fetches 16 contiguous bytes per pair of MFMAs.
+// wavefronts take the key tiles in turn (tile t belongs to wavefront t % 4), so a sequence of up to 128
+// keys costs one round of loads, and merge their partial (m, l, O^T) through LDS at the end: wavefront w
+// collects column tile w of the output from the other three.  The reduction over the head dimension may
+// visit it in any order as long as A and B agree: MFMA j takes elements 16(j/2) + 8(l/32) + 4(j%2) + 0..3,
+// so that each lane fetches 16 contiguous bytes per pair of MFMAs.
 typedef _Float16 v4h __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
