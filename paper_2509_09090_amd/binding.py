@@ -23,7 +23,7 @@ EXPORTS = (
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
-    "sqap_attention", "sqap_residual_add", "sqap_rope_append",
+    "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares",
 )
 
 
@@ -85,6 +85,8 @@ def lib():
         L.sqap_group_free.argtypes = [vp]
         L.sqap_selftest_quotient.argtypes = [vp, vp]
         L.sqap_selftest_dispatch.argtypes = [ctypes.POINTER(u32), vp]
+        L.sqap_plan_linear_shares.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double),
+                                                                      ctypes.POINTER(ctypes.c_double)]
         for name in EXPORTS:
             if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
@@ -273,6 +275,15 @@ def sqap_selftest_dispatch(stream=None):
     table = (ctypes.c_uint32 * 256)()
     _check(lib().sqap_selftest_dispatch(table, _stream(stream)))
     return list(table)
+
+
+def sqap_plan_linear_shares(M, N, K, blocks_per_xcd=32):
+    """Host-only: (bounds[8][33], planned[8], even[8]) of the large-M linear's work split."""
+    bounds = (ctypes.c_uint32 * (8 * 33))()
+    planned = (ctypes.c_double * 8)()
+    even = (ctypes.c_double * 8)()
+    _check(lib().sqap_plan_linear_shares(M, N, K, blocks_per_xcd, bounds, planned, even))
+    return [list(bounds[x * 33:(x + 1) * 33]) for x in range(8)], list(planned), list(even)
 
 
 def sqap_workspace_bytes(M, N, K):

@@ -153,6 +153,8 @@ sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t
 // Checks once per device how a launch's workgroups are dealt to the XCDs (see gemm.hip); table_out
 // (host, 256 words, nullable) receives the XCC id of every workgroup and forces a fresh probe.
 sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out);
+sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
+                               double *even_out);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 
 }  // namespace sqap

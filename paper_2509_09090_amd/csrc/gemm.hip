@@ -12,7 +12,13 @@
 // the integer result is exact.
 #include <atomic>
 #include <cstdlib>
+#include <algorithm>
+#include <map>
+#include <mutex>
 #include <random>
+#include <tuple>
+#include <type_traits>
+#include <vector>
 
 #include "common.h"
 
@@ -38,6 +44,12 @@ constexpr int kDepartWord = 1024;
 constexpr int kStreamKMinM = 512;           // from this M on the persistent kernel is used
 constexpr long long kSpinLimit = 200000000; // bounded wait (about a minute of polling)
 
+// Shares of the stream-K kernel: workgroup j of XCD x runs main-loop steps [bounds[x][j], bounds[x][j + 1]) of
+// that XCD's tiles (numbered tile after tile).  Passed by value as a kernel argument.
+struct StreamKShares {
+    uint32_t bounds[kXcds][kMaxPersistentBlocks / kXcds + 1];
+};
+
 struct GemmParams {
     const uint8_t *Xq;     // [M, K/2] canonical
     const __half *sx;      // [M]
@@ -55,7 +67,6 @@ struct GemmParams {
     unsigned long long epoch;    // value that marks a flag as set by THIS launch
     uint8_t *partials;     // one BM x BN int32 slot per workgroup
     int blocks_per_xcd;
-    int epi_steps;         // cost of one epilogue, in main-loop steps (work split); 0 = even split
 };
 
 __device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
@@ -125,6 +136,10 @@ struct Cfg {
 // The MFMAs take the WEIGHT fragment first, so an accumulator tile is the
 // transpose of the output tile (see the epilogue).
 //
+// Rows: the wavefront in row wm of the wavefront grid owns row groups wm, wm + WAVES_M, wm + 2 WAVES_M,
+// ... of the tile (accumulator i = row group i * WAVES_M + wm), so the few valid row groups of a ragged
+// last tile are spread over all wavefronts (see mainloop_ragged).
+//
 // Loads are unguarded in M and N: rows past M re-read row M-1 and row groups
 // past the end exist as zero padding in the weight layout; what they produce
 // lands in accumulators that are never stored.  RAGGED_K = true guards the
@@ -133,6 +148,42 @@ struct Cfg {
 // Pipeline: while stage `cur` feeds the MFMAs, the registers loaded one step
 // ago are copied into the other stage and the loads for two steps ahead are
 // issued.  One barrier per step; a trailing barrier leaves LDS free.
+template <class C>
+struct OperandMover {
+    // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand (when the
+    // A fragments do not divide evenly, slots past the last fragment load it again and
+    // are not stored).
+    const v4i *a_src[C::A_LOADS];
+    int a_dst[C::A_LOADS], a_chunk[C::A_LOADS];
+    bool a_live[C::A_LOADS];
+    const v4i *b_src[C::B_LOADS];
+    int b_dst[C::B_LOADS], b_chunk[C::B_LOADS];
+
+    // groups: row groups of the tile that hold tokens (fragments of the others are not moved)
+    __device__ __forceinline__ OperandMover(const GemmParams &p, int m0, int ng0, int groups)
+    {
+        constexpr int CP = C::CP;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+        const int Kh = p.K >> 1;
+#pragma unroll
+        for (int i = 0; i < C::A_LOADS; ++i) {
+            const int f = min(wave * C::A_LOADS + i, C::A_FRAGS - 1), rg = f / CP, cp = f % CP;
+            a_live[i] = wave * C::A_LOADS + i < C::A_FRAGS && rg < groups;
+            const int grow = min(m0 + rg * 32 + (lane & 31), p.M - 1);
+            a_chunk[i] = 2 * cp + (lane >> 5);
+            a_src[i] = reinterpret_cast<const v4i *>(p.Xq + (size_t)grow * Kh) + a_chunk[i];
+            a_dst[i] = (f << 10) + (lane << 4);
+        }
+#pragma unroll
+        for (int i = 0; i < C::B_LOADS; ++i) {
+            const int f = wave * C::B_LOADS + i, rg = f / CP, cp = f % CP;
+            b_chunk[i] = 2 * cp + (lane >> 5);
+            b_src[i] = reinterpret_cast<const v4i *>(p.Wd + ((size_t)(ng0 + rg) * p.chunks + 2 * cp) * 512) + lane;
+            b_dst[i] = C::A_BYTES + (f << 10) + (lane << 4);
+        }
+    }
+};
+
 template <class C, bool RAGGED_K>
 __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int m0, int ng0, int step_begin,
                                          int step_end, v16i (&acc)[C::TM][C::TN])
@@ -140,32 +191,7 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     constexpr int TM = C::TM, TN = C::TN, CP = C::CP;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
-    const int Kh = p.K >> 1;
-
-    // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand (when the
-    // A fragments do not divide evenly, slots past the last fragment load it again and
-    // are not stored).
-    const v4i *a_src[C::A_LOADS];
-    int a_dst[C::A_LOADS], a_chunk[C::A_LOADS];
-    bool a_live[C::A_LOADS];
-#pragma unroll
-    for (int i = 0; i < C::A_LOADS; ++i) {
-        a_live[i] = wave * C::A_LOADS + i < C::A_FRAGS;
-        const int f = min(wave * C::A_LOADS + i, C::A_FRAGS - 1), rg = f / CP, cp = f % CP;
-        const int grow = min(m0 + rg * 32 + (lane & 31), p.M - 1);
-        a_chunk[i] = 2 * cp + (lane >> 5);
-        a_src[i] = reinterpret_cast<const v4i *>(p.Xq + (size_t)grow * Kh) + a_chunk[i];
-        a_dst[i] = (f << 10) + (lane << 4);
-    }
-    const v4i *b_src[C::B_LOADS];
-    int b_dst[C::B_LOADS], b_chunk[C::B_LOADS];
-#pragma unroll
-    for (int i = 0; i < C::B_LOADS; ++i) {
-        const int f = wave * C::B_LOADS + i, rg = f / CP, cp = f % CP;
-        b_chunk[i] = 2 * cp + (lane >> 5);
-        b_src[i] = reinterpret_cast<const v4i *>(p.Wd + ((size_t)(ng0 + rg) * p.chunks + 2 * cp) * 512) + lane;
-        b_dst[i] = C::A_BYTES + (f << 10) + (lane << 4);
-    }
+    const OperandMover<C> mv(p, m0, ng0, C::BM / 32);
 
     v4i ga[C::A_LOADS], gb[C::B_LOADS];
 
@@ -173,15 +199,15 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         const v4i zero4 = {0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < C::A_LOADS; ++i) {
-            if (!RAGGED_K || step * kChunksPerStep + a_chunk[i] < p.chunks)
-                ga[i] = a_src[i][step * kChunksPerStep];
+            if (!RAGGED_K || step * kChunksPerStep + mv.a_chunk[i] < p.chunks)
+                ga[i] = mv.a_src[i][step * kChunksPerStep];
             else
                 ga[i] = zero4;
         }
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) {
-            if (!RAGGED_K || step * kChunksPerStep + b_chunk[i] < p.chunks)
-                gb[i] = b_src[i][step * kChunksPerStep * 32];
+            if (!RAGGED_K || step * kChunksPerStep + mv.b_chunk[i] < p.chunks)
+                gb[i] = mv.b_src[i][step * kChunksPerStep * 32];
             else
                 gb[i] = zero4;
         }
@@ -190,19 +216,19 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         uint8_t *base = smem + stage * C::STAGE;
 #pragma unroll
         for (int i = 0; i < C::A_LOADS; ++i)
-            if (C::A_EVEN || a_live[i]) *reinterpret_cast<v4i *>(base + a_dst[i]) = ga[i];
+            if (C::A_EVEN || mv.a_live[i]) *reinterpret_cast<v4i *>(base + mv.a_dst[i]) = ga[i];
 #pragma unroll
-        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + b_dst[i]) = gb[i];
+        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + mv.b_dst[i]) = gb[i];
     };
     auto compute = [&](int stage) {
-        const uint8_t *sa = smem + stage * C::STAGE + ((wm * TM * CP) << 10) + (lane << 4);
+        const uint8_t *sa = smem + stage * C::STAGE + ((wm * CP) << 10) + (lane << 4);
         const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
 #pragma unroll
         for (int cp = 0; cp < CP; ++cp) {
             v4i alo[TM], ahi[TM], blo[TN], bhi[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                widen(*reinterpret_cast<const v4i *>(sa + ((i * CP + cp) << 10)), alo[i], ahi[i]);
+                widen(*reinterpret_cast<const v4i *>(sa + ((i * C::WAVES_M * CP + cp) << 10)), alo[i], ahi[i]);
 #pragma unroll
             for (int jn = 0; jn < TN; ++jn)
                 widen(*reinterpret_cast<const v4i *>(sb + ((jn * CP + cp) << 10)), blo[jn], bhi[jn]);
@@ -243,10 +269,123 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     __syncthreads();
 }
 
+// The same loop for a tile of the last tile row when only `groups` < BM / 32 of its row groups hold
+// tokens: every wavefront runs NI = ceil(groups / WAVES_M) of its TM accumulator rows (a wavefront
+// whose last one lies past `groups` multiplies stale LDS contents into an accumulator that is never
+// stored).  Such a step has a quarter to three quarters of the MFMAs of a full one and is shorter
+// than the round trip of a global load, so the operands travel in a ring of kRing register sets
+// (the unused accumulator rows leave room for them): a load has kRing steps to arrive before it is
+// copied to LDS.  Step s of the segment uses set (s - step_begin) % kRing; loads past the end of the
+// segment re-read its last step and are dropped, so every iteration issues the same loads and the
+// wait before a copy lets exactly the younger kRing - 1 steps stay in flight.
+constexpr int kRing = 4;
+
+template <class C, int NI>
+__device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *smem, int m0, int ng0, int step_begin,
+                                                int step_end, v16i (&acc)[C::TM][C::TN], int groups)
+{
+    constexpr int TN = C::TN, CP = C::CP;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
+    const OperandMover<C> mv(p, m0, ng0, groups);
+
+    v4i ga[kRing][C::A_LOADS], gb[kRing][C::B_LOADS];
+
+    auto load_global = [&](int step, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+#pragma unroll
+        for (int i = 0; i < C::A_LOADS; ++i) ga[set][i] = mv.a_src[i][step * kChunksPerStep];
+#pragma unroll
+        for (int i = 0; i < C::B_LOADS; ++i) gb[set][i] = mv.b_src[i][step * kChunksPerStep * 32];
+    };
+    auto store_lds = [&](int stage, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
+        uint8_t *base = smem + stage * C::STAGE;
+#pragma unroll
+        for (int i = 0; i < C::A_LOADS; ++i)
+            if (mv.a_live[i]) *reinterpret_cast<v4i *>(base + mv.a_dst[i]) = ga[set][i];
+#pragma unroll
+        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + mv.b_dst[i]) = gb[set][i];
+    };
+    auto compute = [&](int stage) {
+        const uint8_t *sa = smem + stage * C::STAGE + ((wm * CP) << 10) + (lane << 4);
+        const uint8_t *sb = smem + stage * C::STAGE + C::A_BYTES + ((wn * TN * CP) << 10) + (lane << 4);
+#pragma unroll
+        for (int cp = 0; cp < CP; ++cp) {
+            v4i alo[NI], ahi[NI], blo[TN], bhi[TN];
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                widen(*reinterpret_cast<const v4i *>(sa + ((i * C::WAVES_M * CP + cp) << 10)), alo[i], ahi[i]);
+#pragma unroll
+            for (int jn = 0; jn < TN; ++jn)
+                widen(*reinterpret_cast<const v4i *>(sb + ((jn * CP + cp) << 10)), blo[jn], bhi[jn]);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn) {
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[jn], alo[i], acc[i][jn], 0, 0, 0);
+                    acc[i][jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[jn], ahi[i], acc[i][jn], 0, 0, 0);
+                }
+        }
+    };
+
+    constexpr std::integral_constant<int, 0> set0{};
+    constexpr std::integral_constant<int, 1> set1{};
+    constexpr std::integral_constant<int, 2> set2{};
+    constexpr std::integral_constant<int, 3> set3{};
+    static_assert(kRing == 4, "the loop below is unrolled for four register sets");
+    const int last = step_end - 1;
+    load_global(step_begin, set0);
+    store_lds(0, set0);
+    load_global(min(step_begin + 1, last), set1);
+    load_global(min(step_begin + 2, last), set2);
+    load_global(min(step_begin + 3, last), set3);
+    load_global(min(step_begin + 4, last), set0);
+    __syncthreads();
+    int it = step_begin, stage = 0;
+    auto body = [&](auto set) {               // the set holds step it + 1
+        store_lds(stage ^ 1, set);
+        __builtin_amdgcn_sched_barrier(0);
+        load_global(min(it + 1 + kRing, last), set);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(stage);
+        __syncthreads();
+        stage ^= 1;
+        ++it;
+    };
+    while (it + kRing < step_end) {
+        body(set1);
+        body(set2);
+        body(set3);
+        body(set0);
+    }
+    const int rest = last - it;               // 0 .. kRing - 1 steps still to be staged
+    if (rest >= 1) body(set1);
+    if (rest >= 2) body(set2);
+    if (rest >= 3) body(set3);
+    compute(stage);
+    __syncthreads();
+}
+
+// Picks the loop for a tile with `groups` valid row groups.
+template <class C>
+__device__ __forceinline__ void mainloop_rows(const GemmParams &p, uint8_t *smem, int m0, int ng0, int step_begin,
+                                              int step_end, v16i (&acc)[C::TM][C::TN], int groups)
+{
+    if constexpr (C::WAVES_M > 1 && C::TM == 4) {
+        const int ni = (groups + C::WAVES_M - 1) / C::WAVES_M;
+        if (ni == 1) return mainloop_ragged<C, 1>(p, smem, m0, ng0, step_begin, step_end, acc, groups);
+        if (ni == 2) return mainloop_ragged<C, 2>(p, smem, m0, ng0, step_begin, step_end, acc, groups);
+        if (ni == 3) return mainloop_ragged<C, 3>(p, smem, m0, ng0, step_begin, step_end, acc, groups);
+    }
+    mainloop<C, false>(p, smem, m0, ng0, step_begin, step_end, acc);
+}
+
 // Epilogue: dequantise and store one wavefront's accumulators.  Called by every
 // wavefront of the block (it contains barriers); LDS must be free on entry and
 // is free again on return.
 //
+// Accumulator i of the wavefront in grid row wm is row group i * WAVES_M + wm of the block tile.
 // An accumulator tile is the transpose of the output tile: lane l holds token
 // row l%32 and, in register e, channel 8*(e/4) + 4*(l/32) + (e%4).  Four
 // consecutive registers are four consecutive channels of one token: 8 bytes of
@@ -256,7 +395,7 @@ template <class C>
 __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM][C::TN], uint8_t *smem, int m0,
                                          int ng0)
 {
-    constexpr int TM = C::TM, TN = C::TN, WM = C::WM, WN = C::WN, PITCH = C::EP_PITCH;
+    constexpr int TM = C::TM, TN = C::TN, WN = C::WN, PITCH = C::EP_PITCH;
     constexpr int LANES_PER_ROW = WN * 2 / 16;
     constexpr int ROWS_PER_PASS = 64 / LANES_PER_ROW;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -268,7 +407,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
         const bool vec = (p.N & 3) == 0 && (reinterpret_cast<uintptr_t>(p.acc_out) & 15u) == 0;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int row = m0 + wm * WM + i * 32 + tok;
+            const int row = m0 + (i * C::WAVES_M + wm) * 32 + tok;
 #pragma unroll
             for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
@@ -299,8 +438,9 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
     const bool vec_ok = p.y_vec_ok;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int row0 = m0 + wm * WM + i * 32;
-        const float sxf = sxs[wm * WM + i * 32 + tok];
+        const int row0 = m0 + (i * C::WAVES_M + wm) * 32;
+        if (row0 >= p.M) continue;                     // a row group without tokens (wave-uniform)
+        const float sxf = sxs[(i * C::WAVES_M + wm) * 32 + tok];
 #pragma unroll
         for (int jn = 0; jn < TN; ++jn)
 #pragma unroll
@@ -373,8 +513,9 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_tiled_kernel(const GemmPar
 
 // Persistent stream-K kernel.  The tiles are dealt to the 8 XCDs in whole
 // tiles (contiguous runs, as above); inside an XCD the run's main-loop steps
-// are split evenly over that XCD's workgroups, so a tile may be shared by
-// several workgroups.  The workgroup holding the LAST steps of a tile finishes
+// are split over that XCD's workgroups in consecutive shares (planned on the
+// host and passed as a kernel argument, see plan_shares), so a tile may be shared
+// by several workgroups.  The workgroup holding the LAST steps of a tile finishes
 // it: it adds the partial accumulators the others left in the workspace (exact:
 // integer sums commute) and runs the epilogue.  A workgroup computes a
 // segment it does not finish FIRST and publishes it at once; the segment it
@@ -383,27 +524,30 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_tiled_kernel(const GemmPar
 // before doing anything else, so the wait cannot deadlock; it is bounded all
 // the same, and a timeout raises the error word in the workspace header.
 template <class C>
-__global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmParams p)
+__global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmParams p, const StreamKShares sched)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int t = threadIdx.x;
     const int tiles = p.m_tiles * p.n_tiles;
     const int steps = p.chunks / kChunksPerStep;
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, nb = p.blocks_per_xcd;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
     // whole tiles of this XCD
     const int q = tiles >> 3, r = tiles & 7;
     const int tile0 = xcd * q + (xcd < r ? xcd : r);
-    const int ntile = q + (xcd < r ? 1 : 0);
-    // This workgroup's share [begin, end) of the XCD's work, measured in steps, with every
-    // tile counted as steps + epi_steps: the tail of each tile stands for its epilogue, so a
-    // workgroup that finishes more tiles gets fewer main-loop steps.  Positions of tile tl:
-    // [tl*V, tl*V + steps) are its steps, the rest is the epilogue share of whoever holds
-    // the last step.
-    const int V = steps + p.epi_steps;
-    const long long total = (long long)ntile * V;
-    const long long begin = total * j / nb, end = total * (j + 1) / nb;
+    // This workgroup's share [begin, end) of the XCD's main-loop steps (tile after tile, `steps` each):
+    // the host planned it (see plan_shares).
+    const int begin = (int)sched.bounds[xcd][j], end = (int)sched.bounds[xcd][j + 1];
     if (begin >= end) return;
-    const int t_first = (int)(begin / V), t_last = (int)((end - 1) / V);
+    const int mtl = p.m_tiles;
+    const int t_first = begin / steps, t_last = (end - 1) / steps;
+    // steps [s0, s1) of XCD-local tile tl that fall to the share [b, e); tb = the tile's first step
+    auto segment = [&](int b, int e, int tl, int &tb, int &s0, int &s1) {
+        tb = tl * steps;
+        s0 = min(max(b - tb, 0), steps);
+        s1 = min(max(e - tb, 0), steps);
+    };
+    // valid row groups of a tile: all of them except in a ragged last tile row
+    const int last_groups = (p.M - (mtl - 1) * C::BM + 31) >> 5;
     const int slot = blockIdx.x;
 
     // Visit order: downwards from t_last.  Only t_last can be left unfinished by
@@ -419,16 +563,17 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
     const int lane = t & 63, wave = t >> 6;
     const int my_off = wave * (C::TM * C::TN * 4096) + lane * 16;
     int tl = t_last;
-    if (end < (long long)t_last * V + steps) {
+    int tb, s0, s1;
+    segment(begin, end, tl, tb, s0, s1);
+    if (s1 < steps) {
         // not the finisher of t_last: compute the head segment and publish it
-        const long long tb = (long long)tl * V;
-        const int s0 = (int)((begin > tb ? begin : tb) - tb);
-        const int s1 = (int)(end - tb);
         const int tile = tile0 + tl;
-        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        const int nt = tile / mtl, mt = tile - nt * mtl;
+        --tl;
+        if (s0 < s1) {
         v16i acc[C::TM][C::TN];
         zero_acc<C>(acc);
-        mainloop<C, false>(p, smem, mt * C::BM, nt * (C::BN / 32), s0, s1, acc);
+        mainloop_rows<C>(p, smem, mt * C::BM, nt * (C::BN / 32), s0, s1, acc, mt == mtl - 1 ? last_groups : C::BM / 32);
         uint8_t *dst = p.partials + (size_t)slot * SLOT_BYTES + my_off;
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
@@ -447,31 +592,31 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (t == 0) __hip_atomic_store(&p.flags[slot], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        --tl;
+        }
     }
     for (; tl >= t_first; --tl) {
-        const long long tb = (long long)tl * V;
-        const int s0 = (int)((begin > tb ? begin : tb) - tb);
-        if (s0 >= steps) continue;          // only the epilogue share of this tile falls in the range
+        segment(begin, end, tl, tb, s0, s1);           // s1 == steps: the share reaches past this tile
+        if (s0 >= s1) continue;                        // no step of this tile starts inside the share
         const int tile = tile0 + tl;
-        const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
+        const int nt = tile / mtl, mt = tile - nt * mtl;
         const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
         v16i acc[C::TM][C::TN];
         zero_acc<C>(acc);
-        mainloop<C, false>(p, smem, m0, ng0, s0, steps, acc);
+        mainloop_rows<C>(p, smem, m0, ng0, s0, steps, acc, mt == mtl - 1 ? last_groups : C::BM / 32);
         if (s0 > 0) {
-            // finisher of a shared tile: steps [0, s0) were done by lower workgroups of this XCD
-            int first = (int)((tb * nb) / total);            // candidate for the workgroup holding step tb
-            while (total * (first + 1) / nb <= tb) ++first;  // (integer division: settle exactly)
-            while (total * first / nb > tb) --first;
-            // One lane per contributor (at most 31 of them) waits for that contributor's flag: the
-            // waits overlap instead of costing one memory round trip each.
+            // finisher of a shared tile: steps [0, s0) were done by lower workgroups of this XCD.
+            // One lane per workgroup of the XCD (at most 32) looks up whether that workgroup holds
+            // steps of this tile and waits for its flag: the waits overlap instead of costing one
+            // memory round trip each.
             unsigned *share = reinterpret_cast<unsigned *>(smem);       // LDS is free between main loop and epilogue
             if (t < 64) {
-                const int jj = first + t;
-                const bool live = jj < j && total * jj / nb < total * (jj + 1) / nb;   // else: no such workgroup, or no steps
+                bool live = false;
+                if (t < j) {
+                    const int jb = (int)sched.bounds[xcd][t], je = (int)sched.bounds[xcd][t + 1];
+                    live = jb < je && je > tb && jb < tb + s0;
+                }
                 if (live) {
-                    unsigned long long *f = &p.flags[jj * 8 + xcd];
+                    unsigned long long *f = &p.flags[t * 8 + xcd];
                     long long spins = 0;
                     while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
                         __builtin_amdgcn_s_sleep(8);
@@ -488,14 +633,14 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
                 if (t == 0) *share = (unsigned)mk;
             }
             __syncthreads();
-            const unsigned live_mask = *share;                // bit u: workgroup first + u left a partial
+            const unsigned live_mask = *share;                // bit u: workgroup u of this XCD left a partial
             __syncthreads();
             // Partials are read with agent-scope loads (sc1): they bypass this CU's L1 and
             // are served by the L2 the producer wrote through.
             constexpr int TILES = C::TM * C::TN;
             {
-                for (int jj = first; jj < j; ++jj) {
-                    if (!((live_mask >> (jj - first)) & 1u)) continue;
+                for (int jj = 0; jj < j; ++jj) {
+                    if (!((live_mask >> jj) & 1u)) continue;
                     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
                         p.partials + (size_t)(jj * 8 + xcd) * SLOT_BYTES, 0, SLOT_BYTES, 0x00020000);
                     // half of the accumulator at a time: up to 16 loads in flight per thread
@@ -675,7 +820,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
             for (int x = 0; x < UPT; ++x) {
                 const int u = u0 + x * C::THREADS;
                 const int l = u & 63, qd = (u >> 6) & 3, a = (u >> 8) % TILES, w = (u >> 8) / TILES;
-                row[x] = m0 + (w / C::WAVES_N) * C::WM + (a / C::TN) * 32 + (l & 31);
+                row[x] = m0 + ((a / C::TN) * C::WAVES_M + w / C::WAVES_N) * 32 + (l & 31);
                 col[x] = (ng0 << 5) + (w % C::WAVES_N) * C::WN + (a % C::TN) * 32 + qd * 8 + (l >> 5) * 4;
                 live[x] = u < ue && row[x] < p.M && col[x] < p.N;
                 sxf[x] = 0.f;
@@ -902,6 +1047,191 @@ static sqap_status launch_tiled(GemmParams &p, hipStream_t st)
     return launch_tiled_k<C, false>(p, st);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Shares of the stream-K launch.  Equal step counts do not give equal finishing times: a workgroup
+// that finishes two tiles runs two epilogues, a tile of a ragged last tile row has short steps, and a
+// finisher cannot start its reduction before the last contributor has published (a workgroup whose
+// whole share is one published segment publishes at the very end of its work).  The host therefore
+// plays the launch through with measured costs and looks for the smallest finishing time T for which
+// a sweep over the workgroups of an XCD, each taking the largest share it completes by T, uses up all
+// the steps.  A finisher only depends on lower-numbered workgroups, so one pass in index order knows
+// every publishing time it needs.  Costs are in units of one full main-loop step.
+struct SplitModel {
+    double step_last;      // a step of a tile of the last tile row (1 when that row is full)
+    double epi, epi_last;  // epilogue of a full tile / of a last-row tile
+    double ramp;           // entering a main loop: first loads, pipeline fill, bookkeeping around it
+    double publish;        // storing a partial and raising the flag
+    double reduce_fixed, reduce_each;   // flag look-up; reading and adding one contributor's partial
+};
+
+// Measured on MI355X with time stamps inside the kernel (256 x 256 tiles; one full step is about 1.4 us):
+// main-loop entry 1.5-1.7 us, partial store and flag 2.6-2.9 us, flag look-up 1.3 us, one partial read and
+// added 2.5-3.9 us, epilogue 4.1-5.0 us; a last-row tile that uses 1, 2 or 3 of the 4 accumulator rows
+// runs a step in 0.41 / 0.60 / 0.83 of a full one.
+constexpr SplitModel kBigTileModel = {1.0, 2.9, 2.9, 1.1, 1.8, 0.9, 2.3};
+constexpr double kRaggedStep[4] = {0.41, 0.60, 0.83, 1.0};
+constexpr double kRaggedEpilogue[4] = {1.1, 1.8, 2.4, 2.9};
+
+// Finishing time of a workgroup with share [b, e) of an XCD whose tiles start at global tile number tile0;
+// pub[jj] = publishing time of workgroup jj (lower numbers only are read); *my_pub receives this one's.
+static double play_share(int b, int e, int steps, int tile0, int mtl, const SplitModel &m, const uint32_t *bounds,
+                         const double *pub, int j, double *my_pub)
+{
+    *my_pub = 0.0;
+    if (b >= e) return 0.0;
+    double t = 0.0, chain = 0.0;
+    const int t_first = b / steps, t_last = (e - 1) / steps;
+    int tl = t_last;
+    auto is_last_row = [&](int tl_) { return (tile0 + tl_) % mtl == mtl - 1; };
+    {
+        const int tb = tl * steps, s0 = std::max(b - tb, 0), s1 = std::min(e - tb, steps);
+        if (s1 < steps) {
+            const bool lr = is_last_row(tl);
+            t += m.ramp + (s1 - s0) * (lr ? m.step_last : 1.0) + m.publish;
+            *my_pub = t;
+            // What this partial holds up: the tile's finisher still has to add the partials (this one,
+            // those of the lower workgroups in the tile, and one more if what is left of the tile is
+            // more than a share of average size) and to run the epilogue after it.
+            int n = 1;
+            for (int jj = 0; jj < j; ++jj)
+                if (bounds[jj] < bounds[jj + 1] && (int)bounds[jj + 1] > tb) ++n;
+            if (steps - s1 > (int)(bounds[j] / (j > 0 ? j : 1)) && j > 0) ++n;
+            chain = t + m.reduce_fixed + n * m.reduce_each + (lr ? m.epi_last : m.epi);
+            --tl;
+        }
+    }
+    for (; tl >= t_first; --tl) {
+        const int tb = tl * steps, s0 = std::max(b - tb, 0);
+        const bool lr = is_last_row(tl);
+        t += m.ramp + (steps - s0) * (lr ? m.step_last : 1.0);
+        if (s0 > 0) {
+            int n = 0;
+            for (int jj = 0; jj < j; ++jj) {
+                const int jb = (int)bounds[jj], je = (int)bounds[jj + 1];
+                if (jb < je && je > tb && jb < tb + s0) {
+                    t = std::max(t, pub[jj]);
+                    ++n;
+                }
+            }
+            t += m.reduce_fixed + n * m.reduce_each;
+        }
+        t += lr ? m.epi_last : m.epi;
+    }
+    return std::max(t, chain);
+}
+
+// Fills bounds[0 .. nb] for one XCD; returns false when no plan was found (the caller then splits evenly).
+static bool plan_xcd(int tile0, int ntile, int steps, int mtl, int nb, const SplitModel &m, uint32_t *bounds,
+                     double *t_out)
+{
+    const int total = ntile * steps;
+    double work = 0.0;
+    for (int tl = 0; tl < ntile; ++tl)
+        work += ((tile0 + tl) % mtl == mtl - 1) ? steps * m.step_last + m.epi_last : steps + m.epi;
+    double lo = work / nb, hi = 2.0 * work / nb + 4.0 * (m.epi + m.publish + m.reduce_fixed + m.reduce_each + m.ramp) + steps;
+    const int reach = 2 * steps + 2 * (total / nb) + 8;        // how far past its start a share may end
+    std::vector<uint32_t> trial(nb + 1), best;
+    std::vector<double> pub(nb);
+    double best_t = 0.0;
+    auto sweep = [&](double T) -> bool {
+        trial[0] = 0;
+        double worst = 0.0;
+        for (int j = 0; j < nb; ++j) {
+            const int b = (int)trial[j];
+            int pick = -1;
+            double pick_t = 0.0, pick_pub = 0.0;
+            if (j == nb - 1) {
+                trial[j + 1] = (uint32_t)total;
+                double pj;
+                const double t = play_share(b, total, steps, tile0, mtl, m, trial.data(), pub.data(), j, &pj);
+                if (t > T) return false;
+                worst = std::max(worst, t);
+                pub[j] = pj;
+                break;
+            }
+            const int e_max = std::min(total, b + reach);
+            for (int e = e_max; e >= b; --e) {                 // the largest share that is done by T
+                double pj;
+                trial[j + 1] = (uint32_t)e;
+                const double t = play_share(b, e, steps, tile0, mtl, m, trial.data(), pub.data(), j, &pj);
+                if (t <= T) {
+                    pick = e;
+                    pick_t = t;
+                    pick_pub = pj;
+                    break;
+                }
+            }
+            if (pick < 0) return false;
+            trial[j + 1] = (uint32_t)pick;
+            pub[j] = pick_pub;
+            worst = std::max(worst, pick_t);
+        }
+        best = trial;
+        best_t = worst;
+        return true;
+    };
+    if (!sweep(hi)) return false;
+    for (int it = 0; it < 24 && hi - lo > 0.05; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (sweep(mid)) hi = mid;
+        else lo = mid;
+    }
+    for (int j = 0; j <= nb; ++j) bounds[j] = best[j];
+    *t_out = best_t;
+    return true;
+}
+
+static void even_shares(int ntile, int steps, int nb, uint32_t *bounds)
+{
+    const long long total = (long long)ntile * steps;
+    for (int j = 0; j <= nb; ++j) bounds[j] = (uint32_t)(total * j / nb);
+}
+
+// Finishing time the model gives the slowest workgroup of an XCD under the shares `bounds`.
+static double predict_xcd(const uint32_t *bounds, int nb, int steps, int tile0, int mtl, const SplitModel &m)
+{
+    double pub[kMaxPersistentBlocks / kXcds], worst = 0.0;
+    for (int j = 0; j < nb; ++j)
+        worst = std::max(worst, play_share((int)bounds[j], (int)bounds[j + 1], steps, tile0, mtl, m, bounds, pub, j, &pub[j]));
+    return worst;
+}
+
+// Plans the shares of one launch (cached per shape: a plan takes a few milliseconds of host time).
+// model == nullptr: equal step counts.
+static void plan_shares(int tiles, int steps, int mtl, int nb, const SplitModel *model, StreamKShares *out)
+{
+    const int q = tiles / kXcds, r = tiles % kXcds;
+    for (int x = 0; x < kXcds; ++x) {
+        const int tile0 = x * q + std::min(x, r), ntile = q + (x < r ? 1 : 0);
+        double t;
+        for (int j = 0; j <= kMaxPersistentBlocks / kXcds; ++j) out->bounds[x][j] = (uint32_t)((long long)ntile * steps);
+        // XCDs whose runs of tiles look alike (same length, same place in the tile column) share a plan
+        int twin = -1;
+        for (int y = 0; y < x && twin < 0; ++y) {
+            const int tile0y = y * q + std::min(y, r), ntiley = q + (y < r ? 1 : 0);
+            if (ntiley == ntile && tile0y % mtl == tile0 % mtl) twin = y;
+        }
+        if (twin >= 0) {
+            for (int j = 0; j <= nb; ++j) out->bounds[x][j] = out->bounds[twin][j];
+            continue;
+        }
+        uint32_t even[kMaxPersistentBlocks / kXcds + 1];
+        even_shares(ntile, steps, nb, even);
+        // equal step counts when there is no model, no plan, or a plan the model itself rates no better
+        if (!model || !plan_xcd(tile0, ntile, steps, mtl, nb, *model, out->bounds[x], &t) ||
+            t >= predict_xcd(even, nb, steps, tile0, mtl, *model))
+            for (int j = 0; j <= nb; ++j) out->bounds[x][j] = even[j];
+    }
+}
+
+struct PlanKey {
+    int tiles, steps, mtl, nb, groups, kind;
+    bool operator<(const PlanKey &o) const
+    {
+        return std::tie(tiles, steps, mtl, nb, groups, kind) < std::tie(o.tiles, o.steps, o.mtl, o.nb, o.groups, o.kind);
+    }
+};
+
 template <class C, bool SPLITK>
 static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st)
 {
@@ -909,8 +1239,6 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     p.n_tiles = (p.N + C::BN - 1) / C::BN;
     const int blocks = persistent_blocks();
     p.blocks_per_xcd = blocks / kXcds;
-    p.epi_steps = 0;       // charging the measured cost (4 to 8 steps) did not shorten the launch: the tail is set by
-                           // the chain publish -> wait -> reduce -> epilogue, not by the epilogue count
     p.flags = reinterpret_cast<unsigned long long *>(workspace);
     p.epoch = next_epoch();
     p.partials = reinterpret_cast<uint8_t *>(workspace) + kFlagBytes;
@@ -923,11 +1251,71 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
         if (s != SQAP_OK) return s;
         configured[dslot].store(true, std::memory_order_release);
     }
-    if constexpr (SPLITK)
+    if constexpr (SPLITK) {
         hipLaunchKernelGGL((gemm_splitk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
-    else
-        hipLaunchKernelGGL((gemm_streamk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p);
+    } else {
+        const int steps = p.chunks / kChunksPerStep;
+        const int64_t tiles = (int64_t)p.m_tiles * p.n_tiles;
+        if ((tiles / kXcds + 1) * steps > 0x7fffffff) return launch_tiled<C>(p, st);    // shares are 32-bit step counts
+        const int groups = (p.M - (p.m_tiles - 1) * C::BM + 31) / 32;
+        const PlanKey key = {(int)tiles, steps, p.m_tiles, p.blocks_per_xcd, groups, C::BM * 1024 + C::BN};
+        static std::mutex mu;
+        static std::map<PlanKey, StreamKShares> plans;
+        StreamKShares shares;
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            auto it = plans.find(key);
+            if (it == plans.end()) {
+                StreamKShares fresh;
+                if constexpr (C::WAVES_M > 1) {
+                    const int rows_used = (groups + C::WAVES_M - 1) / C::WAVES_M;     // accumulator rows of a last-row tile
+                    SplitModel m = kBigTileModel;
+                    m.step_last = kRaggedStep[rows_used - 1];
+                    m.epi_last = kRaggedEpilogue[rows_used - 1];
+                    plan_shares((int)tiles, steps, p.m_tiles, p.blocks_per_xcd, &m, &fresh);
+                } else {
+                    plan_shares((int)tiles, steps, p.m_tiles, p.blocks_per_xcd, nullptr, &fresh);
+                }
+                if (plans.size() > 4096) plans.clear();
+                it = plans.emplace(key, fresh).first;
+            }
+            shares = it->second;
+        }
+        hipLaunchKernelGGL((gemm_streamk_kernel<C>), dim3(blocks), dim3(C::THREADS), C::LDS_BYTES, st, p, shares);
+    }
     SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// Host-only view of the planner for the 256 x 256 tiles (tests and diagnostics): the shares a launch of
+// shape (M, N, K) on blocks_per_xcd workgroups per XCD would get, and per XCD the finishing time the
+// model predicts for them and for equal step counts, in main-loop steps.
+sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
+                               double *even_out)
+{
+    using C = CfgBig;
+    if (M < kStreamKMinM || K % kBK != 0 || K > kMaxK)
+        return fail(SQAP_EUNSUPPORTED, "sqap_plan_linear_shares: M >= %d and K a multiple of %d only", kStreamKMinM, kBK);
+    if (blocks_per_xcd < 1 || blocks_per_xcd > kMaxPersistentBlocks / kXcds)
+        return fail(SQAP_EINVAL, "sqap_plan_linear_shares: 1 to %d workgroups per XCD", kMaxPersistentBlocks / kXcds);
+    const int m_tiles = (M + C::BM - 1) / C::BM, n_tiles = (N + C::BN - 1) / C::BN, steps = K / kBK;
+    const int64_t tiles = (int64_t)m_tiles * n_tiles;
+    if ((tiles / kXcds + 1) * steps > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_plan_linear_shares: too many steps");
+    const int groups = (M - (m_tiles - 1) * C::BM + 31) / 32;
+    const int rows_used = (groups + C::WAVES_M - 1) / C::WAVES_M;
+    SplitModel m = kBigTileModel;
+    m.step_last = kRaggedStep[rows_used - 1];
+    m.epi_last = kRaggedEpilogue[rows_used - 1];
+    StreamKShares planned, even;
+    plan_shares((int)tiles, steps, m_tiles, blocks_per_xcd, &m, &planned);
+    plan_shares((int)tiles, steps, m_tiles, blocks_per_xcd, nullptr, &even);
+    const int q = (int)(tiles / kXcds), r = (int)(tiles % kXcds), per = kMaxPersistentBlocks / kXcds + 1;
+    for (int x = 0; x < kXcds; ++x) {
+        const int tile0 = x * q + std::min(x, r);
+        planned_out[x] = predict_xcd(planned.bounds[x], blocks_per_xcd, steps, tile0, m_tiles, m);
+        even_out[x] = predict_xcd(even.bounds[x], blocks_per_xcd, steps, tile0, m_tiles, m);
+        for (int j = 0; j < per; ++j) bounds_out[x * per + j] = planned.bounds[x][j];
+    }
     return SQAP_OK;
 }
 

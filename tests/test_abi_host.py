@@ -191,3 +191,74 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "sqap_oracle" not in text, f
+
+
+# ------------------------------------------------------------------ work split of the large-M linear (host logic)
+def _play_protocol(bounds, nb, ntile, steps):
+    """Walks every workgroup of one XCD through the kernel's visit order; returns (owner of every step,
+    partials published, partials waited for)."""
+    owner, published, waited = {}, [], []
+    for j in range(nb):
+        b, e = bounds[j], bounds[j + 1]
+        if b >= e:
+            continue
+        t_first, t_last = b // steps, (e - 1) // steps
+        assert 0 <= t_first <= t_last < ntile
+        tl = t_last
+        seg = lambda tl: (tl * steps, min(max(b - tl * steps, 0), steps), min(max(e - tl * steps, 0), steps))
+        tb, s0, s1 = seg(tl)
+        if s1 < steps:
+            tl -= 1
+            if s0 < s1:
+                for s in range(s0, s1):
+                    assert (t_last, s) not in owner
+                    owner[(t_last, s)] = j
+                published.append((j, t_last))
+        while tl >= t_first:
+            tb, s0, s1 = seg(tl)
+            if s0 < s1:
+                assert s1 == steps
+                for s in range(s0, s1):
+                    assert (tl, s) not in owner
+                    owner[(tl, s)] = j
+                if s0 > 0:
+                    for jj in range(j):
+                        jb, je = bounds[jj], bounds[jj + 1]
+                        if jb < je and je > tb and jb < tb + s0:
+                            waited.append((jj, tl))
+            tl -= 1
+    return owner, published, waited
+
+
+@pytest.mark.parametrize("M,N,K,nb", [(2368, 11008, 4096, 32), (2368, 4096, 11008, 32), (2368, 22016, 4096, 32),
+                                      (2560, 11008, 4096, 32), (600, 768, 1024, 32), (513, 544, 640, 32),
+                                      (2368, 4096, 4096, 32), (700, 300, 128, 32), (5000, 512, 256, 13),
+                                      (1024, 32000, 4096, 32), (2432, 4096, 2048, 7), (736, 256, 12800, 32)])
+def test_planned_shares_follow_the_kernel_protocol(M, N, K, nb):
+    bounds, planned, even = B.sqap_plan_linear_shares(M, N, K, nb)
+    m_tiles, n_tiles, steps = -(-M // 256), -(-N // 256), K // 128
+    tiles = m_tiles * n_tiles
+    q, r = divmod(tiles, 8)
+    for x in range(8):
+        ntile = q + (1 if x < r else 0)
+        b = bounds[x]
+        assert b[0] == 0 and all(b[j] <= b[j + 1] for j in range(32)), b
+        assert all(v == ntile * steps for v in b[nb:]), b          # covers the run; unused entries repeat the total
+        owner, published, waited = _play_protocol(b, nb, ntile, steps)
+        assert len(owner) == ntile * steps                         # every step has exactly one owner
+        assert sorted(published) == sorted(waited)                 # every partial is consumed exactly once
+        assert len(set(waited)) == len(waited)
+        # a workgroup publishes at most one partial (it owns one slot), and a finisher's contributors number < 32
+        assert len({j for j, _ in published}) == len(published)
+    assert max(planned) <= max(even) + 1e-9                        # never worse than equal step counts, by the model
+
+
+def test_plan_linear_shares_validation():
+    ok = (ctypes.c_uint32 * 264)(), (ctypes.c_double * 8)(), (ctypes.c_double * 8)()
+    L = B.lib()
+    assert L.sqap_plan_linear_shares(2368, 4096, 4096, 32, None, ok[1], ok[2]) == B.EINVAL
+    assert L.sqap_plan_linear_shares(2368, 4096, 4096, 0, *ok) == B.EINVAL
+    assert L.sqap_plan_linear_shares(2368, 4096, 4096, 33, *ok) == B.EINVAL
+    assert L.sqap_plan_linear_shares(0, 4096, 4096, 32, *ok) == B.EINVAL
+    assert L.sqap_plan_linear_shares(148, 4096, 4096, 32, *ok) == B.EUNSUPPORTED
+    assert L.sqap_plan_linear_shares(2368, 4096, 4000, 32, *ok) == B.EUNSUPPORTED

@@ -301,7 +301,10 @@ def _random_packed(rng, R, K):
 
 @pytest.mark.parametrize("M,N,K", [(32, 512, 512), (1, 32, 32), (8, 4096, 4096), (148, 512, 1024),
                                    (300, 700, 352), (70, 33, 96), (257, 300, 128), (5, 1000, 11008),
-                                   (148, 1024, 11008), (513, 544, 640)])
+                                   (148, 1024, 11008), (513, 544, 640),
+                                   # ragged last tile row of the 256-row tiles: 2, 3, 5 and 7 of its 8 row groups hold tokens
+                                   (576, 1280, 4096), (608, 512, 2048), (672, 768, 1024), (736, 512, 512),
+                                   (2368, 512, 4096)])
 def test_linear_random_codes(G, oracle, M, N, K):
     """Uniform random codes (including -8) exercise every tile edge and the exact int32 sum."""
     rng = np.random.default_rng(M * 7 + N * 3 + K)
