@@ -1129,7 +1129,6 @@ static bool plan_xcd(int tile0, int ntile, int steps, int mtl, int nb, const Spl
     for (int tl = 0; tl < ntile; ++tl)
         work += ((tile0 + tl) % mtl == mtl - 1) ? steps * m.step_last + m.epi_last : steps + m.epi;
     double lo = work / nb, hi = 2.0 * work / nb + 4.0 * (m.epi + m.publish + m.reduce_fixed + m.reduce_each + m.ramp) + steps;
-    const int reach = 2 * steps + 2 * (total / nb) + 8;        // how far past its start a share may end
     std::vector<uint32_t> trial(nb + 1), best;
     std::vector<double> pub(nb);
     double best_t = 0.0;
@@ -1149,18 +1148,28 @@ static bool plan_xcd(int tile0, int ntile, int steps, int mtl, int nb, const Spl
                 pub[j] = pj;
                 break;
             }
-            const int e_max = std::min(total, b + reach);
-            for (int e = e_max; e >= b; --e) {                 // the largest share that is done by T
-                double pj;
+            // The largest share that is done by T.  The finishing time grows with the share except
+            // where the share crosses into another tile, so: bisect, then look one tile further.
+            auto fits = [&](int e, double *t, double *pj) {
                 trial[j + 1] = (uint32_t)e;
-                const double t = play_share(b, e, steps, tile0, mtl, m, trial.data(), pub.data(), j, &pj);
-                if (t <= T) {
+                *t = play_share(b, e, steps, tile0, mtl, m, trial.data(), pub.data(), j, pj);
+                return *t <= T;
+            };
+            const int e_max = std::min((long long)total, (long long)b + (long long)(T / std::min(1.0, m.step_last)) + 1);
+            int good = b, bad = e_max + 1;                     // an empty share always fits
+            double t, pj;
+            while (bad - good > 1) {
+                const int mid = good + (bad - good) / 2;
+                if (fits(mid, &t, &pj)) good = mid;
+                else bad = mid;
+            }
+            for (int e = std::min(e_max, good + steps + 1); e >= good; --e)
+                if (fits(e, &t, &pj)) {
                     pick = e;
                     pick_t = t;
                     pick_pub = pj;
                     break;
                 }
-            }
             if (pick < 0) return false;
             trial[j + 1] = (uint32_t)pick;
             pub[j] = pick_pub;
@@ -1218,7 +1227,8 @@ static void plan_shares(int tiles, int steps, int mtl, int nb, const SplitModel 
         uint32_t even[kMaxPersistentBlocks / kXcds + 1];
         even_shares(ntile, steps, nb, even);
         // equal step counts when there is no model, no plan, or a plan the model itself rates no better
-        if (!model || !plan_xcd(tile0, ntile, steps, mtl, nb, *model, out->bounds[x], &t) ||
+        // (with sixteen or more tiles per workgroup the differences are below two percent: not worth a plan)
+        if (!model || ntile >= 16 * nb || !plan_xcd(tile0, ntile, steps, mtl, nb, *model, out->bounds[x], &t) ||
             t >= predict_xcd(even, nb, steps, tile0, mtl, *model))
             for (int j = 0; j <= nb; ++j) out->bounds[x][j] = even[j];
     }
