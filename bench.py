@@ -213,7 +213,7 @@ def decode_leg(torch, B, wl, stack, steps_per_m=7):
         for gq in per_level:
             gq.free()
     best = out["M1"]
-    out["roofline"] = {"bound": "hbm", "kernel": "skinny_kernel<1>", "achieved": best["GBps"],
+    out["roofline"] = {"bound": "hbm", "kernel": "skinny_kernel<1, 16>", "achieved": best["GBps"],
                        "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["GBps"] / HBM_PEAK_GBS,
                        "traffic": None, "algorithmic_bytes_per_launch": stack.weight_bytes + stack.scale_bytes}
     out["weights_GB"] = stack.weight_bytes / 1e9

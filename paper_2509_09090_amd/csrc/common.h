@@ -53,6 +53,7 @@ constexpr int kSkinnyInline = 4;
 struct SkinnyArgs {
     const SkinnyEntry *table;   // device table, or null to use inline_entries
     int count, total_items, xs_bytes;
+    int out_off, out_cap;       // output slots in LDS: byte offset, slots per wavefront (0: outputs are stored at once)
     long long total_cost;
     SkinnyEntry inline_entries[kSkinnyInline];
 };

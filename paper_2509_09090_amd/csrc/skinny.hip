@@ -20,8 +20,8 @@ namespace sqap {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int kSkinnyWaves = 8;
-constexpr int kSkinnyThreads = kSkinnyWaves * 64;
+constexpr int kSkinnyWaves = 8;         // wavefronts per workgroup, two workgroups per CU ...
+constexpr int kSkinnyWavesBig = 16;     // ... or one workgroup of 16 for the launches that stream for long (see launch_skinny)
 constexpr int kSkinnyDepth = 8;          // 1 KiB weight loads in flight per wavefront
 constexpr int kSkinnyZeroBytes = 16;
 
@@ -130,15 +130,44 @@ __device__ __forceinline__ void inline_run(const SkinnyArgs &a, long long lo, lo
 // the caches' contents (a plain streaming read measures 6.1 TB/s on this part, a nontemporal one 6.8).
 __device__ __forceinline__ v4i stream_load(const v4i *p) { return __builtin_nontemporal_load(p); }
 
-template <int S>
-__global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyArgs a)
+template <int S, int W>
+__global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
 {
-    constexpr int R = kSkinnyWaves / S;          // items a block works on at a time
+    constexpr bool LATE = W == kSkinnyWavesBig;  // outputs wait in LDS (the 16-wavefront form)
+    constexpr int R = W / S;                     // items a block works on at a time
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);     // uniform: keeps item bookkeeping scalar
     uint8_t *xs = smem + kSkinnyZeroBytes;
     if (t < 4) reinterpret_cast<int *>(smem)[t] = 0;
+
+    // Outputs wait in LDS until the wavefront has no weights left to stream.  Vector-memory operations of
+    // a wavefront retire in order, so a ring slot loaded after an output store cannot be consumed before the
+    // store is acknowledged, and under this load that takes as long as the ring is deep; with 8 token rows
+    // (8 lines far apart per store) the stream stood still for about 8 % of the time.  Slot k of this
+    // wavefront: 8 rows x 64 bytes of halves at out_data + k * 512, its destination in out_meta[k].
+    struct OutMeta {
+        __half *Y;
+        long long ldy;
+        int M, N, rg, pad;
+    };
+    uint8_t *out_data = smem + (LATE ? a.out_off + (size_t)wave * a.out_cap * 512 : 0);
+    OutMeta *out_meta = reinterpret_cast<OutMeta *>(smem + (LATE ? a.out_off + (size_t)W * a.out_cap * 512 : 0)) + (LATE ? wave * a.out_cap : 0);
+    int out_n = 0;
+    auto flush_outputs = [&]() {
+        for (int k = 0; k < out_n; ++k) {
+            const OutMeta m = out_meta[k];
+            __half *Y = uni(m.Y);
+            const long long ldy = uni(m.ldy);
+            const int Mk = uni(m.M), Nk = uni(m.N), rgk = uni(m.rg);
+            const int row = lane >> 2, col = rgk * 32 + (lane & 3) * 8;
+            if (lane < 32 && row < Mk && col < Nk)
+                *reinterpret_cast<v4i *>(Y + (size_t)row * ldy + col) =
+                    *reinterpret_cast<const v4i *>(out_data + k * 512 + row * 64 + (lane & 3) * 16);
+        }
+        __builtin_amdgcn_wave_barrier();
+        out_n = 0;
+    };
 
     const SkinnyEntry *table = a.table;
     const bool inl = table == nullptr;             // the problems are in the kernel arguments
@@ -202,7 +231,7 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
 
         __syncthreads();                           // every wavefront is done with the previous problem's xs
         const int Kh = e.chunks * 16;
-        for (int u = t; u < cps * 16; u += kSkinnyThreads) {
+        for (int u = t; u < cps * 16; u += W * 64) {
             const int cp = u >> 4, hh = (u >> 3) & 1, rr = u & 7;
             v4i v = {0, 0, 0, 0};
             if (rr < e.M) v = reinterpret_cast<const v4i *>(e.Xq + (size_t)rr * Kh)[2 * cp + hh];
@@ -215,6 +244,9 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
         const int xstride = has_row ? 256 : 0;
         const float sxf = has_row ? __half2float(e.sx[r]) : 0.f;
         const bool y_vec = (e.N & 3) == 0 && (e.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(e.Y) & 7u) == 0;
+        // 16-byte stores possible: the output goes through the LDS slots (when the launch has any)
+        const bool y_late = LATE && a.out_cap > 0 && (e.N & 7) == 0 && (e.ldy & 7) == 0 &&
+                            (reinterpret_cast<uintptr_t>(e.Y) & 15u) == 0;
 
         for (int base = cur; base < seg_end; base += R, item += R) {
             const int rg = item - e.rg_begin;
@@ -288,7 +320,24 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
                 }
                 __syncthreads();
             }
-            if (has_row && active && ks == 0) {
+            if (y_late && active && ks == 0) {
+                if (out_n == a.out_cap) flush_outputs();
+                if (has_row) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        union { __half hv[4]; uint2 u; } pk, swq;
+                        swq.u = swraw[q];
+#pragma unroll
+                        for (int x = 0; x < 4; ++x)
+                            pk.hv[x] = dequant2(acc[4 * q + x] >> 8, sxf, __half2float(swq.hv[x]));
+                        *reinterpret_cast<uint2 *>(out_data + out_n * 512 + r * 64 + (q * 8 + h * 4) * 2) = pk.u;
+                    }
+                }
+                if (lane == 0) out_meta[out_n] = OutMeta{e.Y, e.ldy, e.M, e.N, rg, 0};
+                __builtin_amdgcn_wave_barrier();
+                ++out_n;
+            }
+            if (has_row && active && ks == 0 && (!y_late || e.acc_out)) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int n = rg * 32 + q * 8 + h * 4;
@@ -302,7 +351,9 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
                             pk.hv[x] = dequant2(v[x], sxf, __half2float(swq.hv[x]));
                         }
                         __half *dst = e.Y + (size_t)r * e.ldy + n;
-                        if (y_vec) {
+                        if (y_late) {
+                            // the halves are in the LDS slot; only the integer accumulators are stored here
+                        } else if (y_vec) {
                             *reinterpret_cast<uint2 *>(dst) = pk.u;
                         } else {
 #pragma unroll
@@ -320,27 +371,40 @@ __global__ __launch_bounds__(kSkinnyThreads, 4) void skinny_kernel(const SkinnyA
         }
         cur = seg_end;
     }
+    if (LATE) flush_outputs();
 }
 
-size_t skinny_lds_bytes(int max_chunks)
+// LDS of a launch: zero block, activations of one problem, 1 KiB per wavefront for the sliced reduction,
+// then (16-wavefront form only) the output slots, 512 + 32 bytes each, out_cap per wavefront, in what is
+// left of the CU's 160 KiB.
+constexpr int kSkinnyOutSlot = 512 + 32;
+constexpr int kSkinnyOutCapMax = 16;
+static size_t skinny_base_lds_bytes(int max_chunks, int waves)
 {
-    return kSkinnyZeroBytes + (size_t)(max_chunks / 2) * 256 + kSkinnyWaves * 1024;
+    return (kSkinnyZeroBytes + (size_t)(max_chunks / 2) * 256 + (size_t)waves * 1024 + 15) & ~(size_t)15;
 }
+static int skinny_out_cap(size_t base)
+{
+    const size_t room = base < 160 * 1024 ? 160 * 1024 - base : 0;
+    const int cap = (int)(room / ((size_t)kSkinnyWavesBig * kSkinnyOutSlot));
+    return cap > kSkinnyOutCapMax ? kSkinnyOutCapMax : cap;
+}
+size_t skinny_lds_bytes(int max_chunks) { return skinny_base_lds_bytes(max_chunks, kSkinnyWaves); }
 
-template <int S>
+template <int S, int W>
 static sqap_status launch_skinny_s(SkinnyArgs &a, size_t lds, int grid_cap, hipStream_t st)
 {
     static std::atomic<size_t> configured[kMaxDeviceSlots];
     const int dslot = device_slot();
     if (lds > configured[dslot].load(std::memory_order_acquire)) {
-        SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_kernel<S>),
+        SQAP_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(&skinny_kernel<S, W>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         configured[dslot].store(lds, std::memory_order_release);
     }
-    constexpr int R = kSkinnyWaves / S;
+    constexpr int R = W / S;
     const int want = (a.total_items + R - 1) / R;
     const int grid = want < grid_cap ? want : grid_cap;
-    hipLaunchKernelGGL(skinny_kernel<S>, dim3(grid), dim3(kSkinnyThreads), lds, st, a);
+    hipLaunchKernelGGL((skinny_kernel<S, W>), dim3(grid), dim3(W * 64), lds, st, a);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
@@ -349,15 +413,30 @@ sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st
 {
     const size_t lds = skinny_lds_bytes(max_chunks);
     if (lds > 160 * 1024) return fail(SQAP_EUNSUPPORTED, "small-M linear: K too large for the LDS staging");
-    const int grid_cap = 2 * device_cu_count();
+    const int cus = device_cu_count();
     SkinnyArgs a = args;
     a.xs_bytes = (max_chunks / 2) * 256;
+    a.out_off = 0;
+    a.out_cap = 0;
+    // Launches in which every wavefront streams several items (a whole model's linears in one group): one
+    // workgroup of 16 wavefronts per CU, whose outputs wait in LDS until the wavefront has streamed its
+    // last weight (see the kernel).  532 -> 527 us at M = 1 and 577 -> 541 us at M = 8 for the 225 linears of
+    // the 7B shape.  Shorter launches are bound by start-up and by how many CUs pull weights, not by the
+    // stores, and ran 15-30 % slower in this form: they keep two workgroups of 8 per CU and store at once.
+    const size_t big_base = skinny_base_lds_bytes(max_chunks, kSkinnyWavesBig);
+    const int cap = skinny_out_cap(big_base);
+    if ((long long)a.total_items >= 4ll * cus * kSkinnyWavesBig && cap >= 4) {
+        a.out_off = (int)big_base;
+        a.out_cap = cap;
+        return launch_skinny_s<1, kSkinnyWavesBig>(a, big_base + (size_t)cap * kSkinnyWavesBig * kSkinnyOutSlot, cus, st);
+    }
+    const int grid_cap = 2 * cus;
     // aim at about 4096 wavefronts: share an item between S of them when items are few
     const int waves = grid_cap * kSkinnyWaves;
-    if (a.total_items * 8 <= waves) return launch_skinny_s<8>(a, lds, grid_cap, st);
-    if (a.total_items * 4 <= waves) return launch_skinny_s<4>(a, lds, grid_cap, st);
-    if (a.total_items * 2 <= waves) return launch_skinny_s<2>(a, lds, grid_cap, st);
-    return launch_skinny_s<1>(a, lds, grid_cap, st);
+    if (a.total_items * 8 <= waves) return launch_skinny_s<8, kSkinnyWaves>(a, lds, grid_cap, st);
+    if (a.total_items * 4 <= waves) return launch_skinny_s<4, kSkinnyWaves>(a, lds, grid_cap, st);
+    if (a.total_items * 2 <= waves) return launch_skinny_s<2, kSkinnyWaves>(a, lds, grid_cap, st);
+    return launch_skinny_s<1, kSkinnyWaves>(a, lds, grid_cap, st);
 }
 
 }  // namespace sqap
