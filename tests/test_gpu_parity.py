@@ -481,6 +481,42 @@ def test_small_m_linear(G, oracle, M, N, K):
     assert G.assert_fp16_close(Y, Yo) == 0
 
 
+def test_group_with_many_row_groups_per_wavefront(G, oracle):
+    """A launch long enough for the form of the kernel that parks outputs in LDS (every wavefront gets
+    more row groups than it has slots, so the slots are also emptied mid-run), with problems of different
+    token counts, one whose N does not allow 16-byte stores (stored at once, inside the same launch), one
+    with the integer accumulators asked for, and an output pitch above N."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(78)
+    shapes = [(5, 262144, 64), (8, 262144, 64), (1, 262144, 64), (8, 262144, 64), (3, 131076, 64), (8, 262144, 64),
+              (2, 262144, 64), (8, 196608, 128), (7, 262144, 64), (4, 262144, 64)]
+    assert sum(-(-N // 32) for _, N, _ in shapes) > 17 * 4096        # more than 16 row groups per wavefront
+    problems, refs = [], []
+    for i, (M, N, K) in enumerate(shapes):
+        Xq = _random_packed(rng, M, K)
+        sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+        Wq = _random_packed(rng, N, K)
+        sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+        W = B.sqap_weight_pack(G.to_dev(Wq), G.to_dev(sw))
+        pitch = N + 16 if i % 2 else N
+        Y = torch.full((M, pitch), float("nan"), dtype=torch.float16, device="cuda")[:, :N]
+        acc = torch.full((M, N), -1, dtype=torch.int32, device="cuda") if i in (2, 4) else None
+        problems.append((G.to_dev(Xq), G.to_dev(sx), W, Y, acc))
+        refs.append(oracle.w4a4_linear(Xq, sx, Wq, sw))
+    g = B.sqap_group_create(problems)
+    for _ in range(2):
+        g.run()
+    torch.cuda.synchronize()
+    for (xq_d, sx_d, W, Y, acc), (Yo, acco) in zip(problems, refs):
+        if acc is not None:
+            assert np.array_equal(acc.cpu().numpy(), acco)
+        assert G.assert_fp16_close(Y.cpu().numpy(), Yo) == 0
+    g.free()
+    for pr in problems:
+        pr[2].free()
+
+
 def test_group_of_small_m_linears(G, oracle):
     """One launch over several independent problems of different shapes, two of them sharing an input."""
     import torch
