@@ -264,7 +264,6 @@ sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k,
 // (Eq. 5).  One wavefront per observation; lane l owns tokens l, l + 64, ...
 // (at most 1024 tokens, 16 per lane).  Everything after the projection is
 // integer work, so the result is exact.
-constexpr int kSelectMaxTokens = 1024;
 constexpr int kSelectCamera = 26;          // doubles per observation: K (9), [R|t] (12), point (3), patch w, h
 constexpr uint32_t kFarAway = 1u << 20;    // above any squared distance on a grid of <= 1024 tokens
 

@@ -5,7 +5,7 @@
 
 namespace sqap {
 
-constexpr int kQuantMaxGroups = 8;   // up to 8 groups of 8 elements per thread: K <= 16384
+// A thread holds up to 8 groups of 8 elements of its row: K <= 16384 (checked by the callers).
 
 // Correctly rounded binary32 quotient v / s for a divisor whose reciprocal r = RN(1/s)
 // was formed once per row (IEEE division).  q0 = RN(v r) is within one ulp of v/s, the

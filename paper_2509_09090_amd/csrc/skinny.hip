@@ -66,7 +66,6 @@ __device__ __forceinline__ void block_run(const SkinnyEntry *table, int count, i
                                           long long hi, bool to_the_end, int lane, int *beg, int *end, int *problem)
 {
     int n_lo = 0, n_hi = 0;
-#pragma unroll 4
     for (int base = 0; base < count; base += 64) {
         const int e = base + lane;
         const long long c = e < count ? table[e].cost_begin : 0x7fffffffffffffffll;
