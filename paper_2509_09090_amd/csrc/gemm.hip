@@ -193,32 +193,38 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     const int wm = wave / C::WAVES_N, wn = wave % C::WAVES_N;
     const OperandMover<C> mv(p, m0, ng0, C::BM / 32);
 
-    v4i ga[C::A_LOADS], gb[C::B_LOADS];
+    // Register sets for operands in flight.  The narrow tiles (one row of wavefronts; a few hundred token
+    // rows) have short steps and use two sets, so that a load has two steps to arrive (3-6 % faster at
+    // M = 84 and 276); the 256 x 256 tiles use one (two measured 2.5 % slower there).
+    constexpr int SETS = C::WAVES_M == 1 ? 2 : 1;
+    v4i ga[SETS][C::A_LOADS], gb[SETS][C::B_LOADS];
 
-    auto load_global = [&](int step) {
+    auto load_global = [&](int step, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
         const v4i zero4 = {0, 0, 0, 0};
 #pragma unroll
         for (int i = 0; i < C::A_LOADS; ++i) {
             if (!RAGGED_K || step * kChunksPerStep + mv.a_chunk[i] < p.chunks)
-                ga[i] = mv.a_src[i][step * kChunksPerStep];
+                ga[set][i] = mv.a_src[i][step * kChunksPerStep];
             else
-                ga[i] = zero4;
+                ga[set][i] = zero4;
         }
 #pragma unroll
         for (int i = 0; i < C::B_LOADS; ++i) {
             if (!RAGGED_K || step * kChunksPerStep + mv.b_chunk[i] < p.chunks)
-                gb[i] = mv.b_src[i][step * kChunksPerStep * 32];
+                gb[set][i] = mv.b_src[i][step * kChunksPerStep * 32];
             else
-                gb[i] = zero4;
+                gb[set][i] = zero4;
         }
     };
-    auto store_lds = [&](int stage) {
+    auto store_lds = [&](int stage, auto set_c) {
+        constexpr int set = decltype(set_c)::value;
         uint8_t *base = smem + stage * C::STAGE;
 #pragma unroll
         for (int i = 0; i < C::A_LOADS; ++i)
-            if (C::A_EVEN || mv.a_live[i]) *reinterpret_cast<v4i *>(base + mv.a_dst[i]) = ga[i];
+            if (C::A_EVEN || mv.a_live[i]) *reinterpret_cast<v4i *>(base + mv.a_dst[i]) = ga[set][i];
 #pragma unroll
-        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + mv.b_dst[i]) = gb[i];
+        for (int i = 0; i < C::B_LOADS; ++i) *reinterpret_cast<v4i *>(base + mv.b_dst[i]) = gb[set][i];
     };
     auto compute = [&](int stage) {
         const uint8_t *sa = smem + stage * C::STAGE + ((wm * CP) << 10) + (lane << 4);
@@ -245,25 +251,55 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         }
     };
 
-    load_global(step_begin);
-    store_lds(0);
-    if (step_begin + 1 < step_end) load_global(step_begin + 1);
-    __syncthreads();
+    constexpr std::integral_constant<int, 0> set0{};
     int it = step_begin, stage = 0;
-    for (; it + 2 < step_end; ++it) {
-        store_lds(stage ^ 1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_global(it + 2);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(stage);
+    if constexpr (SETS == 2) {
+        // Step s of the segment travels in set (s - step_begin) & 1.  Loads past the end of the segment
+        // re-read its last step (and are dropped): every iteration issues the same loads, so the wait
+        // before a copy to LDS lets exactly the one younger step stay in flight.  (Two steps per trip and
+        // a single loop exit: with an exit between the halves the accumulators get copied.)
+        constexpr std::integral_constant<int, 1> set1{};
+        const int last = step_end - 1;
+        load_global(step_begin, set0);
+        store_lds(0, set0);
+        load_global(min(step_begin + 1, last), set1);
+        load_global(min(step_begin + 2, last), set0);
         __syncthreads();
-        stage ^= 1;
-    }
-    if (it + 1 < step_end) {
-        store_lds(stage ^ 1);
-        compute(stage);
+        auto body = [&](auto set) {
+            store_lds(stage ^ 1, set);
+            __builtin_amdgcn_sched_barrier(0);
+            load_global(min(it + 3, last), set);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(stage);
+            __syncthreads();
+            stage ^= 1;
+            ++it;
+        };
+        while (it + 2 < step_end) {
+            body(set1);
+            body(set0);
+        }
+        if (it + 1 < step_end) body(set1);
+    } else {
+        load_global(step_begin, set0);
+        store_lds(0, set0);
+        if (step_begin + 1 < step_end) load_global(step_begin + 1, set0);
         __syncthreads();
-        stage ^= 1;
+        for (; it + 2 < step_end; ++it) {
+            store_lds(stage ^ 1, set0);
+            __builtin_amdgcn_sched_barrier(0);
+            load_global(it + 2, set0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(stage);
+            __syncthreads();
+            stage ^= 1;
+        }
+        if (it + 1 < step_end) {
+            store_lds(stage ^ 1, set0);
+            compute(stage);
+            __syncthreads();
+            stage ^= 1;
+        }
     }
     compute(stage);
     __syncthreads();
