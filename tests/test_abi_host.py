@@ -262,3 +262,27 @@ def test_plan_linear_shares_validation():
     assert L.sqap_plan_linear_shares(0, 4096, 4096, 32, *ok) == B.EINVAL
     assert L.sqap_plan_linear_shares(148, 4096, 4096, 32, *ok) == B.EUNSUPPORTED
     assert L.sqap_plan_linear_shares(2368, 4096, 4000, 32, *ok) == B.EUNSUPPORTED
+
+
+def test_planned_shares_random_shapes():
+    """The same walk over seeded random shapes (small, so that many fit in the time budget)."""
+    import random
+    rnd = random.Random(2024)
+    for _ in range(150):
+        M = rnd.choice([512, 513, 544, 600, 736, 768, 1000, 1025, 2368, 4096, rnd.randint(512, 6000)])
+        N = rnd.choice([32, 256, 300, 768, 4096, 11008, rnd.randint(1, 20000)])
+        K = 128 * rnd.choice([1, 2, 3, 5, 8, 32, 86, rnd.randint(1, 100)])
+        nb = rnd.choice([32, 32, 32, 1, 2, 7, 13, 31])
+        bounds, planned, even = B.sqap_plan_linear_shares(M, N, K, nb)
+        m_tiles, n_tiles, steps = -(-M // 256), -(-N // 256), K // 128
+        q, r = divmod(m_tiles * n_tiles, 8)
+        for x in range(8):
+            ntile = q + (1 if x < r else 0)
+            b = bounds[x]
+            assert b[0] == 0 and all(b[j] <= b[j + 1] for j in range(32)), (M, N, K, nb, b)
+            assert all(v == ntile * steps for v in b[nb:]), (M, N, K, nb, b)
+            owner, published, waited = _play_protocol(b, nb, ntile, steps)
+            assert len(owner) == ntile * steps, (M, N, K, nb)
+            assert sorted(published) == sorted(waited), (M, N, K, nb)
+            assert len({j for j, _ in published}) == len(published), (M, N, K, nb)
+        assert max(planned) <= max(even) + 1e-9, (M, N, K, nb)
