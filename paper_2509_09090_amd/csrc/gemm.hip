@@ -500,7 +500,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
                 const v4i v = *reinterpret_cast<const v4i *>(ep + rin * PITCH + cb);
                 __half *dst = p.Y + (size_t)row * p.ldy + col;
                 if (vec_ok && col + 8 <= p.N) {
-                    *reinterpret_cast<v4i *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst));
                 } else {
                     const __half *h = reinterpret_cast<const __half *>(&v);
 #pragma unroll
