@@ -472,6 +472,18 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
     __syncthreads();
     uint8_t *ep = smem + wave * (32 * PITCH);
     const bool vec_ok = p.y_vec_ok;
+    // This lane's channel scales are the same for every accumulator row: read once (the compiler cannot
+    // move these reads above the staging writes itself, and a read in the loop costs an LDS round trip
+    // per four channels).
+    float4 sw4[TN * 4];
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            sw4[jn * 4 + q] = *reinterpret_cast<const float4 *>(&sws[wn * WN + jn * 32 + q * 8 + ch4]);
+    // Whole tile inside the matrix and 16-byte stores possible (wave-uniform): no checks per store, and the
+    // four row passes of an accumulator row are read together before they are stored.
+    const bool inside = vec_ok && m0 + C::BM <= p.M && (ng0 << 5) + C::BN <= p.N;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row0 = m0 + (i * C::WAVES_M + wm) * 32;
@@ -482,7 +494,7 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int cin = jn * 32 + q * 8 + ch4;
-                const float4 s4 = *reinterpret_cast<const float4 *>(&sws[wn * WN + cin]);
+                const float4 s4 = sw4[jn * 4 + q];
                 uint2 pk;
                 pk.x = dequant2(acc[i][jn][4 * q + 0], acc[i][jn][4 * q + 1], sxf, s4.x, s4.y);
                 pk.y = dequant2(acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3], sxf, s4.z, s4.w);
@@ -491,21 +503,34 @@ __device__ __forceinline__ void epilogue(const GemmParams &p, v16i (&acc)[C::TM]
         // The staging area is private to the wavefront and LDS operations of one
         // wavefront complete in order, so no block barrier is needed around it.
         __builtin_amdgcn_wave_barrier();
+        if (inside) {
+            constexpr int PASSES = 32 / ROWS_PER_PASS;
+            const int rin0 = lane / LANES_PER_ROW, cb = (lane % LANES_PER_ROW) * 16;
+            __half *dst = p.Y + (size_t)(row0 + rin0) * p.ldy + wave_col0 + (cb >> 1);
+            v4i v[PASSES];
 #pragma unroll
-        for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
-            const int rin = ps * ROWS_PER_PASS + lane / LANES_PER_ROW;
-            const int cb = (lane % LANES_PER_ROW) * 16;
-            const int row = row0 + rin, col = wave_col0 + (cb >> 1);
-            if (row < p.M && col < p.N) {
-                const v4i v = *reinterpret_cast<const v4i *>(ep + rin * PITCH + cb);
-                __half *dst = p.Y + (size_t)row * p.ldy + col;
-                if (vec_ok && col + 8 <= p.N) {
-                    __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst));
-                } else {
-                    const __half *h = reinterpret_cast<const __half *>(&v);
+            for (int ps = 0; ps < PASSES; ++ps)
+                v[ps] = *reinterpret_cast<const v4i *>(ep + (ps * ROWS_PER_PASS + rin0) * PITCH + cb);
 #pragma unroll
-                    for (int x = 0; x < 8; ++x)
-                        if (col + x < p.N) dst[x] = h[x];
+            for (int ps = 0; ps < PASSES; ++ps)
+                __builtin_nontemporal_store(v[ps], reinterpret_cast<v4i *>(dst + (size_t)ps * ROWS_PER_PASS * p.ldy));
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < 32 / ROWS_PER_PASS; ++ps) {
+                const int rin = ps * ROWS_PER_PASS + lane / LANES_PER_ROW;
+                const int cb = (lane % LANES_PER_ROW) * 16;
+                const int row = row0 + rin, col = wave_col0 + (cb >> 1);
+                if (row < p.M && col < p.N) {
+                    const v4i v = *reinterpret_cast<const v4i *>(ep + rin * PITCH + cb);
+                    __half *dst = p.Y + (size_t)row * p.ldy + col;
+                    if (vec_ok && col + 8 <= p.N) {
+                        __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(dst));
+                    } else {
+                        const __half *h = reinterpret_cast<const __half *>(&v);
+#pragma unroll
+                        for (int x = 0; x < 8; ++x)
+                            if (col + x < p.N) dst[x] = h[x];
+                    }
                 }
             }
         }
