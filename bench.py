@@ -101,22 +101,23 @@ class Prefill:
 
 
 def time_gemm_launches(torch, wk, steps):
-    """Average duration of one prefill GEMM launch, from HIP events recorded on
-    the launch stream directly around each linear call inside whole steps."""
-    total_ms, launches = 0.0, 0
-    per = {"gate_up": 0.0, "down": 0.0}
+    """Average duration of one prefill GEMM launch, from HIP events recorded on the launch stream
+    directly around each linear call inside whole steps that run back to back (no synchronisation
+    between the steps, as in the timed region; one at the end)."""
+    all_ev = []
     for _ in range(steps):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
         wk.gemm_events = ev
         wk.step()
-        torch.cuda.synchronize()
-        a, b = ev[0].elapsed_time(ev[1]), ev[2].elapsed_time(ev[3])
-        per["gate_up"] += a
-        per["down"] += b
-        total_ms += a + b
-        launches += 2
+        all_ev.append(ev)
     wk.gemm_events = None
-    return total_ms / launches, {k: v / steps for k, v in per.items()}
+    torch.cuda.synchronize()
+    per = {"gate_up": 0.0, "down": 0.0}
+    for ev in all_ev:
+        per["gate_up"] += ev[0].elapsed_time(ev[1])
+        per["down"] += ev[2].elapsed_time(ev[3])
+    total_ms = per["gate_up"] + per["down"]
+    return total_ms / (2 * steps), {k: v / steps for k, v in per.items()}
 
 
 class Stack:
@@ -620,7 +621,7 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     tops = wk.ops / (dt / args.steps) / 1e12
 
-    gemm_ms, per_gemm = time_gemm_launches(torch, wk, min(args.steps, 50))
+    gemm_ms, per_gemm = time_gemm_launches(torch, wk, args.steps)
     gemm_ops = wk.ops / 2.0                                  # each of the two launches: 2*M*N*K
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
 
