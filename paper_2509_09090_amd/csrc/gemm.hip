@@ -769,10 +769,12 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
     const int q = tiles >> 3, r = tiles & 7;
     const int tile0 = xcd * q + (xcd < r ? xcd : r);
     const int ntile = q + (xcd < r ? 1 : 0);
-    const long long total = (long long)ntile * steps;
-    const long long begin = total * j / nb, end = total * (j + 1) / nb;
+    // (32-bit arithmetic: this kernel runs with at most 64 tiles, so ntile * steps * nb stays far below 2^31;
+    // 64-bit divisions cost about a microsecond at the start of a launch that takes fifteen)
+    const int total = ntile * steps;
+    const int begin = total * j / nb, end = total * (j + 1) / nb;
     if (begin >= end) return;
-    const int t_first = (int)(begin / steps), t_last = (int)((end - 1) / steps);
+    const int t_first = begin / steps, t_last = (end - 1) / steps;
     const int my_off = wave * (TILES * 4096) + lane * 16;
     int *cslot = reinterpret_cast<int *>(smem);            // [0, 32): slot numbers of the tile's contributors
     int *cinfo = cslot + 32;                               // [0]: how many, [1]: this workgroup's number among them
@@ -782,9 +784,9 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
     // workgroup is counted in, without waiting for anybody: a workgroup that waited here would
     // make its neighbour wait for everything the workgroup still has to do.
     for (int tl = t_last; tl >= t_first; --tl) {
-        const long long tb = (long long)tl * steps;
-        const int s0 = (int)((begin > tb ? begin : tb) - tb);
-        const int s1 = (int)((end < tb + steps ? end : tb + steps) - tb);
+        const int tb = tl * steps;
+        const int s0 = (begin > tb ? begin : tb) - tb;
+        const int s1 = (end < tb + steps ? end : tb + steps) - tb;
         const int tile = tile0 + tl;
         const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
         const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
@@ -823,27 +825,27 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
     for (int pass = 0; pass < 2; ++pass) {
         const int tl = pass == 0 ? t_last : t_first;
         if (pass == 1 && t_first == t_last) break;
-        const long long tb = (long long)tl * steps;
-        const int s0 = (int)((begin > tb ? begin : tb) - tb);
-        const int s1 = (int)((end < tb + steps ? end : tb + steps) - tb);
+        const int tb = tl * steps;
+        const int s0 = (begin > tb ? begin : tb) - tb;
+        const int s1 = (end < tb + steps ? end : tb + steps) - tb;
         if (s0 == 0 && s1 == steps) continue;              // was a whole tile
         const int tile = tile0 + tl;
         const int nt = tile / p.m_tiles, mt = tile - nt * p.m_tiles;
         const int m0 = mt * C::BM, ng0 = nt * (C::BN / 32);
         // who shares this tile: the workgroups of this XCD from the holder of its first step to
         // the holder of its last step (those with an empty share excepted)
-        int first = (int)((tb * nb) / total);
+        int first = (tb * nb) / total;
         while (total * (first + 1) / nb <= tb) ++first;
         while (total * first / nb > tb) --first;
         __syncthreads();                                   // cslot / cinfo of the previous pass are no longer read
         if (t < 64) {
             const int jj = first + t;
-            const long long jb = jj < nb ? total * jj / nb : 0, je = jj < nb ? total * (jj + 1) / nb : 0;
+            const int jb = jj < nb ? total * jj / nb : 0, je = jj < nb ? total * (jj + 1) / nb : 0;
             const bool live = jj < nb && jb < je && jb < tb + steps;          // has steps, and they start inside the tile
             const unsigned long long mk = __ballot(live);
             if (live) {
                 const int rank = __popcll(mk & ((1ull << t) - 1ull));
-                const int w2 = tl == (int)((je - 1) / steps) ? 0 : 1;          // the slot that workgroup used for this tile
+                const int w2 = tl == (je - 1) / steps ? 0 : 1;          // the slot that workgroup used for this tile
                 cslot[rank] = w2 * kMaxPersistentBlocks + jj * 8 + xcd;
                 if (jj == j) cinfo[1] = rank;
             }
@@ -867,7 +869,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
 
         // this workgroup's slice of the tile, 16 bytes (4 channels of one token) per thread at a time;
         // partials are read with agent-scope loads (sc1): they bypass this CU's L1
-        const int ub = (int)((long long)UNITS * rank / nc), ue = (int)((long long)UNITS * (rank + 1) / nc);
+        const int ub = UNITS * rank / nc, ue = UNITS * (rank + 1) / nc;
         const bool y_vec = (p.ldy & 3) == 0 && (reinterpret_cast<uintptr_t>(p.Y) & 7u) == 0;
         constexpr int UPT = 4;                             // units per thread per trip
         for (int u0 = ub + t; u0 < ue; u0 += UPT * C::THREADS) {
