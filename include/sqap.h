@@ -381,26 +381,30 @@ sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream);
 sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream);
 
 /*
- * The work split of the large-M linear (M >= 512, K a multiple of 128), as a
+ * The work split of the stream-K linear (M > 8, K a multiple of 128), as a
  * host-side computation: no GPU is touched.  A launch runs 8 x blocks_per_xcd
- * persistent workgroups; the 256 x 256 output tiles are dealt to the 8 XCDs in
- * contiguous runs and workgroup j of XCD x runs main-loop steps
+ * persistent workgroups; the output tiles (256 x 256 from M = 512 on, 96 or
+ * 160 rows x 128 columns below: *tile_rows_out, *tile_cols_out) are dealt to
+ * the 8 XCDs in contiguous runs and workgroup j of XCD x runs main-loop steps
  * [bounds[x][j], bounds[x][j + 1]) of its XCD's run (tile after tile, K / 128
  * steps each), so a tile can be shared along K; the workgroup holding a
  * tile's last step adds the others' partial sums and stores the tile.  The
  * bounds are planned from measured costs (epilogues, partial exchange, the
  * shorter steps of a ragged last tile row) so that the workgroups finish
- * together.  bounds_out: HOST, 8 x 33 words, row x = XCD x (entries past
- * blocks_per_xcd repeat the total).  planned_steps_out / even_steps_out:
- * HOST, 8 doubles each: the finishing time the cost model predicts for the
- * planned shares and for equal step counts, in units of one main-loop step.
- * blocks_per_xcd: 1 ... 32 (a 256-CU device uses 32).
+ * together.  (Launches with at most 64 narrow tiles use another kernel, whose
+ * contributors finish a tile jointly from equal step counts; the plan is
+ * reported for them all the same.)  bounds_out: HOST, 8 x 33 words, row x =
+ * XCD x (entries past blocks_per_xcd repeat the total).  planned_steps_out /
+ * even_steps_out: HOST, 8 doubles each: the finishing time the cost model
+ * predicts for the planned shares and for equal step counts, in units of one
+ * main-loop step.  blocks_per_xcd: 1 ... 32 (a 256-CU device uses 32).
  * EINVAL: null pointers, sizes <= 0, blocks_per_xcd out of range;
- * EUNSUPPORTED: M < 512, K not a multiple of 128 or above the K limit.
+ * EUNSUPPORTED: M <= 8, K not a multiple of 128 or above the K limit.
  */
 sqap_status sqap_plan_linear_shares(int32_t M, int32_t N, int32_t K, int32_t blocks_per_xcd,
                                     uint32_t *bounds_out, double *planned_steps_out,
-                                    double *even_steps_out);
+                                    double *even_steps_out, int32_t *tile_rows_out,
+                                    int32_t *tile_cols_out);
 
 /*
  * Grouped small-M linears (autoregressive decode, M <= 8).  Decode streams

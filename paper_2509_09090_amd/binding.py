@@ -86,7 +86,9 @@ def lib():
         L.sqap_selftest_quotient.argtypes = [vp, vp]
         L.sqap_selftest_dispatch.argtypes = [ctypes.POINTER(u32), vp]
         L.sqap_plan_linear_shares.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double),
-                                                                      ctypes.POINTER(ctypes.c_double)]
+                                                                      ctypes.POINTER(ctypes.c_double),
+                                                                      ctypes.POINTER(ctypes.c_int32),
+                                                                      ctypes.POINTER(ctypes.c_int32)]
         for name in EXPORTS:
             if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
@@ -278,12 +280,13 @@ def sqap_selftest_dispatch(stream=None):
 
 
 def sqap_plan_linear_shares(M, N, K, blocks_per_xcd=32):
-    """Host-only: (bounds[8][33], planned[8], even[8]) of the large-M linear's work split."""
+    """Host-only: (bounds[8][33], planned[8], even[8], (tile rows, tile columns)) of the stream-K linear's work split."""
     bounds = (ctypes.c_uint32 * (8 * 33))()
     planned = (ctypes.c_double * 8)()
     even = (ctypes.c_double * 8)()
-    _check(lib().sqap_plan_linear_shares(M, N, K, blocks_per_xcd, bounds, planned, even))
-    return [list(bounds[x * 33:(x + 1) * 33]) for x in range(8)], list(planned), list(even)
+    bm, bn = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().sqap_plan_linear_shares(M, N, K, blocks_per_xcd, bounds, planned, even, ctypes.byref(bm), ctypes.byref(bn)))
+    return [list(bounds[x * 33:(x + 1) * 33]) for x in range(8)], list(planned), list(even), (bm.value, bn.value)
 
 
 def sqap_workspace_bytes(M, N, K):

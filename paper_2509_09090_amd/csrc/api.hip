@@ -460,11 +460,14 @@ sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream)
 }
 
 sqap_status sqap_plan_linear_shares(int32_t M, int32_t N, int32_t K, int32_t blocks_per_xcd, uint32_t *bounds_out,
-                                    double *planned_steps_out, double *even_steps_out)
+                                    double *planned_steps_out, double *even_steps_out, int32_t *tile_rows_out,
+                                    int32_t *tile_cols_out)
 {
-    if (!bounds_out || !planned_steps_out || !even_steps_out) return fail(SQAP_EINVAL, "sqap_plan_linear_shares: null pointer");
+    if (!bounds_out || !planned_steps_out || !even_steps_out || !tile_rows_out || !tile_cols_out)
+        return fail(SQAP_EINVAL, "sqap_plan_linear_shares: null pointer");
     if (M <= 0 || N <= 0 || K <= 0) return fail(SQAP_EINVAL, "sqap_plan_linear_shares: M, N, K must be positive");
-    return plan_linear_shares(M, N, K, blocks_per_xcd, bounds_out, planned_steps_out, even_steps_out);
+    return plan_linear_shares(M, N, K, blocks_per_xcd, bounds_out, planned_steps_out, even_steps_out, tile_rows_out,
+                              tile_cols_out);
 }
 
 sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream)

@@ -155,7 +155,7 @@ sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t
 // (host, 256 words, nullable) receives the XCC id of every workgroup and forces a fresh probe.
 sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out);
 sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
-                               double *even_out);
+                               double *even_out, int *tile_rows_out, int *tile_cols_out);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 
 }  // namespace sqap

@@ -1132,6 +1132,9 @@ struct SplitModel {
 // added 2.5-3.9 us, epilogue 4.1-5.0 us; a last-row tile that uses 1, 2 or 3 of the 4 accumulator rows
 // runs a step in 0.41 / 0.60 / 0.83 of a full one.
 constexpr SplitModel kBigTileModel = {1.0, 2.9, 2.9, 1.1, 1.8, 0.9, 2.3};
+// The narrow tiles (96 or 160 rows x 128 columns; a step is about 0.35 us): costs set by trial, 1-3 % faster than equal
+// step counts at M = 84 and 148, no different at M = 276 (twice these values gain more at M = 148 and lose at M = 276).
+constexpr SplitModel kNarrowTileModel = {1.0, 3.0, 3.0, 4.0, 2.0, 2.0, 2.3};
 constexpr double kRaggedStep[4] = {0.41, 0.60, 0.83, 1.0};
 constexpr double kRaggedEpilogue[4] = {1.1, 1.8, 2.4, 2.9};
 
@@ -1347,7 +1350,7 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
                     m.epi_last = kRaggedEpilogue[rows_used - 1];
                     plan_shares((int)tiles, steps, p.m_tiles, p.blocks_per_xcd, &m, &fresh);
                 } else {
-                    plan_shares((int)tiles, steps, p.m_tiles, p.blocks_per_xcd, nullptr, &fresh);
+                    plan_shares((int)tiles, steps, p.m_tiles, p.blocks_per_xcd, &kNarrowTileModel, &fresh);
                 }
                 if (plans.size() > 4096) plans.clear();
                 it = plans.emplace(key, fresh).first;
@@ -1360,25 +1363,31 @@ static sqap_status launch_streamk(GemmParams &p, void *workspace, hipStream_t st
     return SQAP_OK;
 }
 
-// Host-only view of the planner for the 256 x 256 tiles (tests and diagnostics): the shares a launch of
+// Host-only view of the planner (tests and diagnostics): the shares a stream-K launch of
 // shape (M, N, K) on blocks_per_xcd workgroups per XCD would get, and per XCD the finishing time the
 // model predicts for them and for equal step counts, in main-loop steps.
 sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
-                               double *even_out)
+                               double *even_out, int *tile_rows_out, int *tile_cols_out)
 {
-    using C = CfgBig;
-    if (M < kStreamKMinM || K % kBK != 0 || K > kMaxK)
-        return fail(SQAP_EUNSUPPORTED, "sqap_plan_linear_shares: M >= %d and K a multiple of %d only", kStreamKMinM, kBK);
+    if (M <= kSkinnyMaxM || K % kBK != 0 || K > kMaxK)
+        return fail(SQAP_EUNSUPPORTED, "sqap_plan_linear_shares: M > %d and K a multiple of %d only", kSkinnyMaxM, kBK);
     if (blocks_per_xcd < 1 || blocks_per_xcd > kMaxPersistentBlocks / kXcds)
         return fail(SQAP_EINVAL, "sqap_plan_linear_shares: 1 to %d workgroups per XCD", kMaxPersistentBlocks / kXcds);
-    const int m_tiles = (M + C::BM - 1) / C::BM, n_tiles = (N + C::BN - 1) / C::BN, steps = K / kBK;
+    // tile shape and cost model as launch_w4a4_linear / launch_streamk choose them
+    const bool big = M >= kStreamKMinM;
+    const int BM = big ? CfgBig::BM : narrow_tile_is_mid(M) ? CfgMid::BM : CfgLow::BM;
+    const int BN = big ? CfgBig::BN : CfgMid::BN;
+    const int m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN, steps = K / kBK;
     const int64_t tiles = (int64_t)m_tiles * n_tiles;
     if ((tiles / kXcds + 1) * steps > 0x7fffffff) return fail(SQAP_EUNSUPPORTED, "sqap_plan_linear_shares: too many steps");
-    const int groups = (M - (m_tiles - 1) * C::BM + 31) / 32;
-    const int rows_used = (groups + C::WAVES_M - 1) / C::WAVES_M;
-    SplitModel m = kBigTileModel;
-    m.step_last = kRaggedStep[rows_used - 1];
-    m.epi_last = kRaggedEpilogue[rows_used - 1];
+    SplitModel m = kNarrowTileModel;
+    if (big) {
+        const int groups = (M - (m_tiles - 1) * BM + 31) / 32;
+        const int rows_used = (groups + CfgBig::WAVES_M - 1) / CfgBig::WAVES_M;
+        m = kBigTileModel;
+        m.step_last = kRaggedStep[rows_used - 1];
+        m.epi_last = kRaggedEpilogue[rows_used - 1];
+    }
     StreamKShares planned, even;
     plan_shares((int)tiles, steps, m_tiles, blocks_per_xcd, &m, &planned);
     plan_shares((int)tiles, steps, m_tiles, blocks_per_xcd, nullptr, &even);
@@ -1389,6 +1398,8 @@ sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t
         even_out[x] = predict_xcd(even.bounds[x], blocks_per_xcd, steps, tile0, m_tiles, m);
         for (int j = 0; j < per; ++j) bounds_out[x * per + j] = planned.bounds[x][j];
     }
+    *tile_rows_out = BM;
+    *tile_cols_out = BN;
     return SQAP_OK;
 }
 

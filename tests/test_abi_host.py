@@ -233,10 +233,14 @@ def _play_protocol(bounds, nb, ntile, steps):
 @pytest.mark.parametrize("M,N,K,nb", [(2368, 11008, 4096, 32), (2368, 4096, 11008, 32), (2368, 22016, 4096, 32),
                                       (2560, 11008, 4096, 32), (600, 768, 1024, 32), (513, 544, 640, 32),
                                       (2368, 4096, 4096, 32), (700, 300, 128, 32), (5000, 512, 256, 13),
-                                      (1024, 32000, 4096, 32), (2432, 4096, 2048, 7), (736, 256, 12800, 32)])
+                                      (1024, 32000, 4096, 32), (2432, 4096, 2048, 7), (736, 256, 12800, 32),
+                                      # narrow tiles (a few hundred token rows)
+                                      (84, 12288, 4096, 32), (276, 22016, 4096, 32), (148, 11008, 4096, 32),
+                                      (199, 4096, 11008, 32), (9, 64, 128, 32), (511, 4096, 4096, 5)])
 def test_planned_shares_follow_the_kernel_protocol(M, N, K, nb):
-    bounds, planned, even = B.sqap_plan_linear_shares(M, N, K, nb)
-    m_tiles, n_tiles, steps = -(-M // 256), -(-N // 256), K // 128
+    bounds, planned, even, (bm, bn) = B.sqap_plan_linear_shares(M, N, K, nb)
+    assert (bm, bn) == ((256, 256) if M >= 512 else (160 if -(-M // 160) * 160 <= -(-M // 96) * 96 else 96, 128))
+    m_tiles, n_tiles, steps = -(-M // bm), -(-N // bn), K // 128
     tiles = m_tiles * n_tiles
     q, r = divmod(tiles, 8)
     for x in range(8):
@@ -254,13 +258,14 @@ def test_planned_shares_follow_the_kernel_protocol(M, N, K, nb):
 
 
 def test_plan_linear_shares_validation():
-    ok = (ctypes.c_uint32 * 264)(), (ctypes.c_double * 8)(), (ctypes.c_double * 8)()
+    ok = ((ctypes.c_uint32 * 264)(), (ctypes.c_double * 8)(), (ctypes.c_double * 8)(), ctypes.byref(ctypes.c_int32(0)),
+          ctypes.byref(ctypes.c_int32(0)))
     L = B.lib()
-    assert L.sqap_plan_linear_shares(2368, 4096, 4096, 32, None, ok[1], ok[2]) == B.EINVAL
+    assert L.sqap_plan_linear_shares(2368, 4096, 4096, 32, None, *ok[1:]) == B.EINVAL
     assert L.sqap_plan_linear_shares(2368, 4096, 4096, 0, *ok) == B.EINVAL
     assert L.sqap_plan_linear_shares(2368, 4096, 4096, 33, *ok) == B.EINVAL
     assert L.sqap_plan_linear_shares(0, 4096, 4096, 32, *ok) == B.EINVAL
-    assert L.sqap_plan_linear_shares(148, 4096, 4096, 32, *ok) == B.EUNSUPPORTED
+    assert L.sqap_plan_linear_shares(8, 4096, 4096, 32, *ok) == B.EUNSUPPORTED
     assert L.sqap_plan_linear_shares(2368, 4096, 4000, 32, *ok) == B.EUNSUPPORTED
 
 
@@ -269,12 +274,12 @@ def test_planned_shares_random_shapes():
     import random
     rnd = random.Random(2024)
     for _ in range(150):
-        M = rnd.choice([512, 513, 544, 600, 736, 768, 1000, 1025, 2368, 4096, rnd.randint(512, 6000)])
+        M = rnd.choice([9, 84, 148, 276, 511, 512, 513, 544, 600, 736, 768, 1000, 1025, 2368, 4096, rnd.randint(9, 6000)])
         N = rnd.choice([32, 256, 300, 768, 4096, 11008, rnd.randint(1, 20000)])
         K = 128 * rnd.choice([1, 2, 3, 5, 8, 32, 86, rnd.randint(1, 100)])
         nb = rnd.choice([32, 32, 32, 1, 2, 7, 13, 31])
-        bounds, planned, even = B.sqap_plan_linear_shares(M, N, K, nb)
-        m_tiles, n_tiles, steps = -(-M // 256), -(-N // 256), K // 128
+        bounds, planned, even, (bm, bn) = B.sqap_plan_linear_shares(M, N, K, nb)
+        m_tiles, n_tiles, steps = -(-M // bm), -(-N // bn), K // 128
         q, r = divmod(m_tiles * n_tiles, 8)
         for x in range(8):
             ntile = q + (1 if x < r else 0)
