@@ -397,6 +397,78 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
     }
 }
 
+// The plain quantizer (no rotation, no channel scales, nothing fused in front) for many rows: one block
+// takes TWO rows and asks for both before it works on the first, so the second row's read is in flight
+// during the first row's reduction and arithmetic, and 2368 rows of K = 11008 fit the device in one
+// round of blocks instead of one and a sixth.  Same arithmetic, statement by statement, as the kernel above.
+template <int GPT>
+__global__ __launch_bounds__(256) void quantize_row_pairs_kernel(const __half *__restrict__ X, int64_t ldx,
+                                                                 const int32_t *__restrict__ rows, int M, int K,
+                                                                 uint8_t *__restrict__ Xq,
+                                                                 __half *__restrict__ scale_out)
+{
+    __shared__ float wave_max[2][4];
+    typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int groups = K >> 3;
+    const int row0 = 2 * blockIdx.x;
+    const int nrows = row0 + 1 < M ? 2 : 1;
+    v4u raw[2][GPT];
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const int row = min(row0 + r, M - 1);                       // (a missing second row re-reads the first)
+        const int64_t src = rows ? (int64_t)rows[row] : (int64_t)row;
+        const v4u *xrow = reinterpret_cast<const v4u *>(X + src * ldx);
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = t + gi * 256;
+            raw[r][gi] = g < groups ? __builtin_nontemporal_load(xrow + g) : v4u{0u, 0u, 0u, 0u};
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        if (r >= nrows) break;
+        const int row = row0 + r;
+        float v[GPT][8];
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            union { v4u v; uint4 u; } ld;
+            ld.v = raw[r][gi];
+            unpack8(ld.u, v[gi]);
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
+        for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+        if (lane == 0) wave_max[r][wave] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(wave_max[r][0], wave_max[r][1]), fmaxf(wave_max[r][2], wave_max[r][3]));
+
+        __half sh = __float2half_rn(amax / 7.0f);
+        if (__half_as_ushort(sh) == 0) sh = __ushort_as_half((unsigned short)1);
+        const float sf = __half2float(sh);
+        if (t == 0) scale_out[row] = sh;
+        const float rcp = 1.0f / sf;
+        uint32_t *qrow = reinterpret_cast<uint32_t *>(Xq + (size_t)row * (K >> 1));
+#pragma unroll
+        for (int gi = 0; gi < GPT; ++gi) {
+            const int g = t + gi * 256;
+            if (g < groups) {
+                uint32_t packed = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float q = rintf(quotient(v[gi][e], sf, rcp));
+                    q = fminf(fmaxf(q, -8.f), 7.f);
+                    packed |= ((uint32_t)(int)q & 15u) << (4 * e);
+                }
+                qrow[g] = packed;
+            }
+        }
+    }
+}
+
 // Static channel scales from calibration rows: each block walks rows blockIdx.x, + gridDim.x,
 // ... keeping the running maximum of its threads' columns in registers (the column layout of
 // load_row is the same for every row), then merges into amax[] with an integer atomic maximum
@@ -483,6 +555,8 @@ static sqap_status allow_rotation_lds(Kern kernel, size_t lds)
     return SQAP_OK;
 }
 
+constexpr int kPairsMinRows = 1024;      // from here on the plain quantizer takes two rows per block
+
 template <int MODE, int PRE>
 static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int32_t *rows, int M, int K,
                                         bool rotate, const __half *col_scales, uint8_t *Xq, __half *sx,
@@ -498,6 +572,13 @@ static sqap_status launch_quantize_mode(const __half *X, int64_t ldx, const int3
             if (s != SQAP_OK) return s;
             launch_quantize_gpt<true, MODE, PRE>(gpt, X, ldx, rows, M, K, lds, col_scales, Xq, sx, pre, st);
         }
+    } else if (MODE == kPerRow && PRE == kPreNone && Xq && M >= kPairsMinRows) {
+        const dim3 grid((M + 1) / 2), block(256);
+        if (gpt <= 1) hipLaunchKernelGGL(quantize_row_pairs_kernel<1>, grid, block, 0, st, X, ldx, rows, M, K, Xq, sx);
+        else if (gpt <= 2) hipLaunchKernelGGL(quantize_row_pairs_kernel<2>, grid, block, 0, st, X, ldx, rows, M, K, Xq, sx);
+        else if (gpt <= 4) hipLaunchKernelGGL(quantize_row_pairs_kernel<4>, grid, block, 0, st, X, ldx, rows, M, K, Xq, sx);
+        else if (gpt <= 6) hipLaunchKernelGGL(quantize_row_pairs_kernel<6>, grid, block, 0, st, X, ldx, rows, M, K, Xq, sx);
+        else hipLaunchKernelGGL(quantize_row_pairs_kernel<8>, grid, block, 0, st, X, ldx, rows, M, K, Xq, sx);
     } else {
         launch_quantize_gpt<false, MODE, PRE>(gpt, X, ldx, rows, M, K, 0, col_scales, Xq, sx, pre, st);
     }

@@ -92,7 +92,8 @@ def test_prune_rows_fused(G, oracle, batch, S, v0, nv, k):
 
 # ------------------------------------------------------------------ quantizer
 @pytest.mark.parametrize("M,K", [(64, 512), (148, 4096), (37, 11008), (5, 8), (3, 16), (9, 2056),
-                                 (2, 16384), (1, 4096), (8, 11008)])
+                                 (2, 16384), (1, 4096), (8, 11008),
+                                 (1025, 520), (1024, 4096), (1031, 11008)])       # two rows per block from 1024 rows on
 def test_quantize_act(G, oracle, M, K):
     X, _ = wl.activations(M, K, max(1, wl.n_outliers_for(K)), 30.0, wl.rng_for(92, M, wl.T_X, K))
     q, s = G.gpu_quantize(X)
