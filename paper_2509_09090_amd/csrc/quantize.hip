@@ -301,6 +301,16 @@ __device__ __forceinline__ void load_col_scales(const __half *col_scales, int g,
     }
 }
 
+// clamp(rint(q), -8, 7) as a 4-bit two's complement code.  Clamping first gives the same integer (both
+// bounds are integers and rounding is monotone), and adding 1.5 * 2^23 rounds a value of that size to
+// the nearest integer, ties to even like rint, and leaves it in the low mantissa bits: one addition
+// instead of a rounding and a conversion.  A NaN quotient clamps to -8 either way.
+__device__ __forceinline__ uint32_t code4(float q)
+{
+    const float c = fminf(fmaxf(q, -8.f), 7.f);
+    return __float_as_uint(c + 12582912.0f) & 15u;
+}
+
 // One block per output row; the row stays in registers from its single read to the packed
 // store.  Arithmetic (all binary32, IEEE, no contraction possible):
 //   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
@@ -341,9 +351,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    float r = rintf(v[gi][e] / c[e]);
-                    r = fminf(fmaxf(r, -8.f), 7.f);
-                    packed |= ((uint32_t)(int)r & 15u) << (4 * e);
+                    packed |= code4(v[gi][e] / c[e]) << (4 * e);
                 }
                 qrow[g] = packed;
             }
@@ -388,9 +396,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
             uint32_t packed = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                float r = rintf((ROTATE || MODE == kFolded) ? v[gi][e] / sf : quotient(v[gi][e], sf, rcp));
-                r = fminf(fmaxf(r, -8.f), 7.f);
-                packed |= ((uint32_t)(int)r & 15u) << (4 * e);
+                packed |= code4((ROTATE || MODE == kFolded) ? v[gi][e] / sf : quotient(v[gi][e], sf, rcp)) << (4 * e);
             }
             qrow[g] = packed;
         }
@@ -459,9 +465,7 @@ __global__ __launch_bounds__(256) void quantize_row_pairs_kernel(const __half *_
                 uint32_t packed = 0;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    float q = rintf(quotient(v[gi][e], sf, rcp));
-                    q = fminf(fmaxf(q, -8.f), 7.f);
-                    packed |= ((uint32_t)(int)q & 15u) << (4 * e);
+                    packed |= code4(quotient(v[gi][e], sf, rcp)) << (4 * e);
                 }
                 qrow[g] = packed;
             }
