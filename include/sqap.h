@@ -341,6 +341,19 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
  * EINVAL: null pointer, Sk < Sq, pitch < H*d.  EUNSUPPORTED: d not in
  * {16, 32, 64, 128}, operands or pitches not 16-byte aligned.
  *
+ * sqap_decode_attention: the attention of ONE new token of one sequence (a decode step) in a single
+ * launch: sqap_rope_append of the token's fused q|k|v row QKV [3*H*d] into cache row `past`
+ * (KV [>= past + 1, ldkv]: rotated key | value per position), sqap_attention of the rotated query
+ * over cache rows 0 .. past into O [H*d], and, when Xq is given, sqap_quantize_act of O (flags 0)
+ * into Xq [H*d/2], sx [1].  QKV is only read (the rotated query is not written back).  pos: [1]
+ * int32 device, the token's position.  The cache row and Xq, sx hold the same bits as the three
+ * separate calls give on the same O; O agrees with sqap_attention within the fp16 tolerance (the
+ * order of the binary32 sums differs).  counter: one device uint32 the quantizer needs (the
+ * workgroup that finishes last does it); zero before the first call, left zero by every call;
+ * calls that share it must not overlap.  EINVAL: null pointer, H, d <= 0, past < 0, pitch below
+ * 2*H*d, base <= 0, Xq without sx or counter.  EUNSUPPORTED: d not a multiple of 8 or above 128,
+ * KV, ldkv or O not 16-byte aligned, H*d > 8192 with Xq.
+ *
  * sqap_residual_add: X[i, :] <- binary16(float(X[i, :]) + float(delta[i, :])),
  * K a multiple of 8, 16-byte aligned rows.
  */
@@ -351,6 +364,9 @@ sqap_status sqap_rope_append(sqap_f16 *QKV, int64_t ld, const int32_t *pos, int3
 sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, int64_t ldk,
                            const sqap_f16 *V, int64_t ldv, int32_t batch, int32_t Sq, int32_t Sk, int32_t H,
                            int32_t d, sqap_f16 *O, int64_t ldo, void *stream);
+sqap_status sqap_decode_attention(const sqap_f16 *QKV, const int32_t *pos, int32_t H, int32_t d, double base,
+                                  sqap_f16 *KV, int64_t ldkv, int32_t past, sqap_f16 *O, uint8_t *Xq,
+                                  sqap_f16 *sx, uint32_t *counter, void *stream);
 sqap_status sqap_residual_add(sqap_f16 *X, int64_t ldx, const sqap_f16 *delta, int64_t ldd, int32_t M,
                               int32_t K, void *stream);
 

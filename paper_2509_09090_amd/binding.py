@@ -23,7 +23,7 @@ EXPORTS = (
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
-    "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares",
+    "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention",
 )
 
 
@@ -72,6 +72,7 @@ def lib():
         L.sqap_rope.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp]
         L.sqap_rope_append.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.c_double, vp, i64, vp]
         L.sqap_attention.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, i64, vp]
+        L.sqap_decode_attention.argtypes = [vp, vp, i32, i32, ctypes.c_double, vp, i64, i32, vp, vp, vp, vp, vp]
         L.sqap_residual_add.argtypes = [vp, i64, vp, i64, i32, i32, vp]
         L.sqap_quantize_weight.argtypes = [vp, i32, i32, u32, vp, vp, vp]
         L.sqap_weight_pack.argtypes = [vp, vp, i32, i32, ctypes.POINTER(vp), vp]
@@ -260,6 +261,14 @@ def sqap_attention(Q, K, V, H, d, O, batch=1, stream=None):
     _check(lib().sqap_attention(_ptr(Q), Q.stride(0), _ptr(K), K.stride(0), _ptr(V), V.stride(0), batch,
                                 Q.shape[0] // batch, K.shape[0] // batch, H, d, _ptr(O), O.stride(0),
                                 _stream(stream)))
+
+
+def sqap_decode_attention(qkv, pos, H, d, KV, past, O, Xq=None, sx=None, counter=None, base=10000.0, stream=None):
+    """One decode step's attention in one launch: qkv [3*H*d] (one token) rotated, key | value appended as
+    row `past` of the cache KV [>= past+1, 2*H*d], attention over rows 0..past into O [H*d]; with Xq
+    (and sx [1], counter: a zeroed uint32/int32 device word) O is also quantized as by sqap_quantize_act."""
+    _check(lib().sqap_decode_attention(_ptr(qkv), _ptr(pos), H, d, base, _ptr(KV), KV.stride(0), past, _ptr(O),
+                                       _ptr(Xq), _ptr(sx), _ptr(counter), _stream(stream)))
 
 
 def sqap_residual_add(X, delta, stream=None):

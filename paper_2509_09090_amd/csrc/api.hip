@@ -306,6 +306,28 @@ sqap_status sqap_attention(const sqap_f16 *Q, int64_t ldq, const sqap_f16 *K, in
                             as_stream(stream));
 }
 
+sqap_status sqap_decode_attention(const sqap_f16 *QKV, const int32_t *pos, int32_t H, int32_t d, double base,
+                                  sqap_f16 *KV, int64_t ldkv, int32_t past, sqap_f16 *O, uint8_t *Xq, sqap_f16 *sx,
+                                  uint32_t *counter, void *stream)
+{
+    if (H <= 0 || d <= 0 || past < 0) return fail(SQAP_EINVAL, "sqap_decode_attention: H %d, d %d, past %d", H, d, past);
+    if (ldkv < (int64_t)2 * H * d) return fail(SQAP_EINVAL, "sqap_decode_attention: cache pitch below 2 H d");
+    if (!(base > 0.0)) return fail(SQAP_EINVAL, "sqap_decode_attention: base must be positive");
+    if (!QKV || !pos || !KV || !O) return fail(SQAP_EINVAL, "sqap_decode_attention: null pointer");
+    if (Xq && (!sx || !counter)) return fail(SQAP_EINVAL, "sqap_decode_attention: Xq needs sx and counter");
+    if ((d & 7) || d > 128) return fail(SQAP_EUNSUPPORTED, "sqap_decode_attention: head size %d (multiple of 8, <= 128)", d);
+    if ((ldkv & 7) || !aligned16(KV) || !aligned16(O))
+        return fail(SQAP_EUNSUPPORTED, "sqap_decode_attention: cache, its pitch and the output must be 16-byte aligned");
+    if (Xq && (int64_t)H * d > 8192)
+        return fail(SQAP_EUNSUPPORTED, "sqap_decode_attention: H * d = %lld above 8192 with the quantizer folded in",
+                    (long long)H * d);
+    if (Xq && ((reinterpret_cast<uintptr_t>(Xq) | reinterpret_cast<uintptr_t>(counter)) & 3u))
+        return fail(SQAP_EUNSUPPORTED, "sqap_decode_attention: Xq and counter must be 4-byte aligned");
+    return launch_decode_attention(reinterpret_cast<const __half *>(QKV), pos, H, d, base, reinterpret_cast<__half *>(KV),
+                                   ldkv, past, reinterpret_cast<__half *>(O), Xq, reinterpret_cast<__half *>(sx), counter,
+                                   as_stream(stream));
+}
+
 sqap_status sqap_residual_add(sqap_f16 *X, int64_t ldx, const sqap_f16 *delta, int64_t ldd, int32_t M, int32_t K,
                               void *stream)
 {

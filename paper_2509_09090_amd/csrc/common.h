@@ -147,6 +147,9 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
 sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H, int d, double base, hipStream_t st);
 sqap_status launch_rope_append(__half *QKV, int64_t ld, const int32_t *pos, int S, int H, int d, double base,
                                __half *KV, int64_t ldkv, hipStream_t st);
+sqap_status launch_decode_attention(const __half *QKV, const int32_t *pos, int H, int d, double base, __half *KV,
+                                    int64_t ldkv, int past, __half *O, uint8_t *Xq, __half *sx,
+                                    unsigned int *counter, hipStream_t st);
 sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int64_t ldk, const __half *V,
                              int64_t ldv, int batch, int Sq, int Sk, int H, int d, __half *O, int64_t ldo, hipStream_t st);
 sqap_status launch_residual_add(__half *X, int64_t ldx, const __half *Dl, int64_t ldd, int M, int K, hipStream_t st);

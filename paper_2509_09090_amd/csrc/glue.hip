@@ -6,6 +6,7 @@
 // after), so attention is a small fraction of a layer and is written for low latency, not for
 // matrix-core throughput: binary32 FMAs over LDS tiles with an online softmax.
 #include "common.h"
+#include "quant_math.h"
 
 namespace sqap {
 
@@ -476,6 +477,217 @@ sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int
         return fail(SQAP_EUNSUPPORTED, "attention: head size %d (16, 32, 64 or 128)", d);
     }
 #undef SQAP_ATT_CASE
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
+// One decode step's attention in a single launch: the new token's query and key are rotated (same
+// arithmetic as rope_kernel), the rotated key and the value go into row `past` of the cache, and the
+// query attends to cache rows 0 .. past.  One workgroup per head.  At one token each of the three
+// launches this replaces (rotation + append, attention, activation quantizer) is a few microseconds
+// of latency and no work, so the quantizer of the following linear is folded in as well: the
+// workgroup that finishes last (a device-wide arrival counter) quantizes the whole output row.
+//
+// Scores: 16 lanes per key, lane c holding columns 8c .. 8c+7 (one 16-byte load per key row), four keys
+// per lane group in flight; softmax over chunks of 1024 keys with the usual running maximum and sum;
+// output: the same lane layout over the value rows, the 16 key groups added through LDS.  All binary32.
+constexpr int kDecChunk = 1024;            // keys per softmax chunk
+constexpr int kDecMaxD = 128;              // head size limit: 16 lanes x 8 columns
+constexpr int kDecMaxRow = 8192;           // H * d limit of the fused quantizer (row staged in LDS)
+
+__device__ __forceinline__ void unpack_halves(const uint4 raw, float (&f)[8])
+{
+    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float2 x = __half22float2(h2[p]);
+        f[2 * p] = x.x;
+        f[2 * p + 1] = x.y;
+    }
+}
+
+__global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__restrict__ QKV,
+                                                               const int32_t *__restrict__ pos, int H, int d,
+                                                               double base, __half *KV, int64_t ldkv, int past,
+                                                               __half *O, uint8_t *__restrict__ Xq,
+                                                               __half *__restrict__ sx, unsigned int *counter)
+{
+    __shared__ __attribute__((aligned(16))) float qf[kDecMaxD];
+    __shared__ __attribute__((aligned(16))) __half knew[kDecMaxD], vnew[kDecMaxD];
+    __shared__ float sc[kDecChunk];
+    constexpr int kRedFloats = 16 * kDecMaxD > kDecMaxRow / 2 ? 16 * kDecMaxD : kDecMaxRow / 2;
+    __shared__ __attribute__((aligned(16))) float ored[kRedFloats];        // later: the output row as halves
+    __shared__ float wred[4];
+    __shared__ int last_flag;
+    static_assert(sizeof(ored) >= kDecMaxRow * sizeof(__half), "the staged row must fit the reduction buffer");
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, h = blockIdx.x;
+    const int half_d = d >> 1, width = H * d;
+    const int Sk = past + 1;
+
+    // rotation of this head's query and key; the value is copied
+    if (t < half_d) {
+        const int i = t;
+        const double a = (double)pos[0] * pow(base, -2.0 * (double)i / (double)d);
+        double sn, cs;
+        sincos(a, &sn, &cs);
+        const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
+        __half *krow = KV + (int64_t)past * ldkv + (int64_t)h * d, *vrow = krow + width;
+        double lo = (double)__half2float(q[i]), hi = (double)__half2float(q[i + half_d]);
+        qf[i] = __half2float(__float2half_rn((float)(lo * cs - hi * sn)));
+        qf[i + half_d] = __half2float(__float2half_rn((float)(hi * cs + lo * sn)));
+        lo = (double)__half2float(k[i]);
+        hi = (double)__half2float(k[i + half_d]);
+        const __half k0 = __float2half_rn((float)(lo * cs - hi * sn));
+        const __half k1 = __float2half_rn((float)(hi * cs + lo * sn));
+        knew[i] = k0;
+        knew[i + half_d] = k1;
+        krow[i] = k0;
+        krow[i + half_d] = k1;
+        const __half v0 = v[i], v1 = v[i + half_d];
+        vnew[i] = v0;
+        vnew[i + half_d] = v1;
+        vrow[i] = v0;
+        vrow[i + half_d] = v1;
+    }
+    __syncthreads();
+
+    const int grp = t >> 4, c = t & 15;              // key group, column chunk
+    const bool col_ok = c * 8 < d;
+    float q8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q8[e] = col_ok ? qf[c * 8 + e] : 0.f;
+    const float inv_sqrt_d = 1.0f / sqrtf((float)d);
+    const __half *kbase = KV + (int64_t)h * d + c * 8, *vbase = kbase + width;
+    // row `key` of the cache, the new token's from LDS (its global copy was written by this workgroup just now)
+    auto fetch = [&](const __half *gbase, const __half *fresh, int key) {
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (col_ok && key < Sk)
+            raw = key == past ? *reinterpret_cast<const uint4 *>(fresh + c * 8)
+                              : *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
+        return raw;
+    };
+
+    float o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = 0.f;
+    float m = -INFINITY, l = 0.f;
+    for (int c0 = 0; c0 < Sk; c0 += kDecChunk) {
+        const int n = min(kDecChunk, Sk - c0);
+        for (int kb = 0; kb < n; kb += 64) {
+            uint4 raw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = fetch(kbase, knew, c0 + kb + 16 * j + grp);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float kf[8];
+                unpack_halves(raw[j], kf);
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
+                for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
+                const int key = kb + 16 * j + grp;
+                if (c == 0 && key < n) sc[key] = s * inv_sqrt_d;
+            }
+        }
+        __syncthreads();
+        float mx = -INFINITY;
+        for (int i = t; i < n; i += 256) mx = fmaxf(mx, sc[i]);
+        for (int x = 32; x > 0; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x));
+        if (lane == 0) wred[wave] = mx;
+        __syncthreads();
+        const float m_new = fmaxf(m, fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3])));
+        __syncthreads();                               // wred is reused for the sum
+        float sum = 0.f;
+        for (int i = t; i < n; i += 256) {
+            const float pj = expf(sc[i] - m_new);
+            sc[i] = pj;
+            sum += pj;
+        }
+        for (int x = 32; x > 0; x >>= 1) sum += __shfl_xor(sum, x);
+        if (lane == 0) wred[wave] = sum;
+        __syncthreads();
+        const float rescale = expf(m - m_new);         // m = -inf only before the first chunk: exp(-inf) = 0
+        l = l * rescale + ((wred[0] + wred[1]) + (wred[2] + wred[3]));
+        m = m_new;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] *= rescale;
+        for (int kb = 0; kb < n; kb += 64) {
+            uint4 raw[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) raw[j] = fetch(vbase, vnew, c0 + kb + 16 * j + grp);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int key = kb + 16 * j + grp;
+                const float pj = key < n ? sc[key] : 0.f;
+                float vf[8];
+                unpack_halves(raw[j], vf);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
+            }
+        }
+        __syncthreads();                               // sc and wred are rewritten by the next chunk
+    }
+    if (col_ok) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ored[grp * kDecMaxD + c * 8 + e] = o[e];
+    }
+    __syncthreads();
+    if (t < d) {
+        float acc = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) acc += ored[g * kDecMaxD + t];
+        O[(int64_t)h * d + t] = __float2half_rn(acc * (1.0f / l));
+    }
+    if (!Xq) return;
+
+    // the workgroup that arrives last quantizes the whole row (as quantize_rows_kernel does)
+    __threadfence();                                   // this head's outputs before the arrival
+    __syncthreads();
+    if (t == 0) {
+        const unsigned int before = atomicAdd(counter, 1u);
+        last_flag = before == (unsigned int)(H - 1);
+    }
+    __syncthreads();
+    if (!last_flag) return;
+    __threadfence();                                   // the other heads' outputs after the arrival
+    __half *row = reinterpret_cast<__half *>(ored);
+    const int groups = width >> 3;
+    float amax = 0.f;
+    for (int g = t; g < groups; g += 256) {
+        const uint4 raw = reinterpret_cast<const uint4 *>(O)[g];
+        reinterpret_cast<uint4 *>(row)[g] = raw;
+        float f[8];
+        unpack_halves(raw, f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
+    }
+    for (int x = 32; x > 0; x >>= 1) amax = fmaxf(amax, __shfl_xor(amax, x));
+    if (lane == 0) wred[wave] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3]));
+    const __half sh = row_scale(amax);
+    const float sf = __half2float(sh);
+    const float rcp = 1.0f / sf;
+    if (t == 0) {
+        sx[0] = sh;
+        atomicExch(counter, 0u);                       // the next call starts from zero again
+    }
+    for (int g = t; g < groups; g += 256) {
+        float f[8];
+        unpack_halves(reinterpret_cast<const uint4 *>(row)[g], f);
+        uint32_t packed = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed |= code4(quotient(f[e], sf, rcp)) << (4 * e);
+        reinterpret_cast<uint32_t *>(Xq)[g] = packed;
+    }
+}
+
+sqap_status launch_decode_attention(const __half *QKV, const int32_t *pos, int H, int d, double base, __half *KV,
+                                    int64_t ldkv, int past, __half *O, uint8_t *Xq, __half *sx,
+                                    unsigned int *counter, hipStream_t st)
+{
+    hipLaunchKernelGGL(decode_attention_kernel, dim3(H), dim3(256), 0, st, QKV, pos, H, d, base, KV, ldkv, past, O, Xq,
+                       sx, counter);
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }

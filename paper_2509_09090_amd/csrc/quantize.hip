@@ -2,24 +2,11 @@
 // one row per output channel), with the optional Hadamard rotation of Eq. 6,
 // and the re-layout of canonical packed weights into the streaming layout.
 #include "common.h"
+#include "quant_math.h"
 
 namespace sqap {
 
 // A thread holds up to 8 groups of 8 elements of its row: K <= 16384 (checked by the callers).
-
-// Correctly rounded binary32 quotient v / s for a divisor whose reciprocal r = RN(1/s)
-// was formed once per row (IEEE division).  q0 = RN(v r) is within one ulp of v/s, the
-// FMA gives the exact remainder, and the second FMA rounds q0 + rem * r to the
-// correctly rounded quotient (Markstein's correction; it can fail only for divisors whose
-// significand is all ones, which a half-precision scale widened to binary32 never is).
-// Three instructions instead of the ~15 of a full IEEE division per element; every
-// half / half pair is compared against the division operator by sqap_selftest_quotient.
-__device__ __forceinline__ float quotient(float v, float s, float r)
-{
-    const float q0 = v * r;
-    const float rem = fmaf(-q0, s, v);
-    return fmaf(rem, r, q0);
-}
 
 // How the scale enters (Section 3.3):
 //   kPerRow      one scale per row, from the row's own maximum (per token / per output channel)
@@ -301,16 +288,6 @@ __device__ __forceinline__ void load_col_scales(const __half *col_scales, int g,
     }
 }
 
-// clamp(rint(q), -8, 7) as a 4-bit two's complement code.  Clamping first gives the same integer (both
-// bounds are integers and rounding is monotone), and adding 1.5 * 2^23 rounds a value of that size to
-// the nearest integer, ties to even like rint, and leaves it in the low mantissa bits: one addition
-// instead of a rounding and a conversion.  A NaN quotient clamps to -8 either way.
-__device__ __forceinline__ uint32_t code4(float q)
-{
-    const float c = fminf(fmaxf(q, -8.f), 7.f);
-    return __float_as_uint(c + 12582912.0f) & 15u;
-}
-
 // One block per output row; the row stays in registers from its single read to the packed
 // store.  Arithmetic (all binary32, IEEE, no contraction possible):
 //   scale = half(max|v| / 7), 2^-24 if that is zero;  code = clamp(rint(v / scale), -8, 7)
@@ -381,8 +358,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
     __syncthreads();
     amax = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
 
-    __half sh = __float2half_rn(amax / 7.0f);
-    if (__half_as_ushort(sh) == 0) sh = __ushort_as_half((unsigned short)1);
+    const __half sh = row_scale(amax);
     const float sf = __half2float(sh);
     if (t == 0) scale_out[row] = sh;
 
@@ -452,8 +428,7 @@ __global__ __launch_bounds__(256) void quantize_row_pairs_kernel(const __half *_
         __syncthreads();
         amax = fmaxf(fmaxf(wave_max[r][0], wave_max[r][1]), fmaxf(wave_max[r][2], wave_max[r][3]));
 
-        __half sh = __float2half_rn(amax / 7.0f);
-        if (__half_as_ushort(sh) == 0) sh = __ushort_as_half((unsigned short)1);
+        const __half sh = row_scale(amax);
         const float sf = __half2float(sh);
         if (t == 0) scale_out[row] = sh;
         const float rcp = 1.0f / sf;

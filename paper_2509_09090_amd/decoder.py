@@ -9,6 +9,8 @@ published pre-normalisation layer:
                                              sqap_rope_append with a key/value cache: append folded in)
     a = causal attention(q, k, v)            sqap_attention
     o = W_o quant(a)                         sqap_quantize_act + sqap_w4a4_linear
+                                             (one token with a cache: rotation, append, attention and this
+                                             quantizer are one launch, sqap_decode_attention)
     y2 = RMSNorm(x + o) -> int4              sqap_rmsnorm_quantize_act   (residual add fused)
     g|u = W_gu y2                            sqap_w4a4_linear            (N = 2 * ffn)
     h = silu(g) * u -> int4                  sqap_swiglu_quantize_act
@@ -51,6 +53,7 @@ class LayerBuffers:
                      for (n, k) in ((3 * hidden, hidden), (hidden, hidden), (2 * ffn, hidden), (hidden, ffn)))
         self.ws = torch.zeros((max(nbytes, 256),), dtype=u8, device=device)
         self.iota = torch.arange(max_rows, dtype=torch.int32, device=device)
+        self.counter = torch.zeros((1,), dtype=torch.int32, device=device)     # arrival counter of sqap_decode_attention
 
 
 def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_out, eps=1e-5, rows=None,
@@ -73,6 +76,7 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
     B.sqap_rmsnorm_quantize_act(x, rows, w.gamma_attn, eps, xq, sx, delta=pending, flags=flags, xsum_out=x_out,
                                 stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.qkv, qkv, None, buf.ws, stream=stream)
+    one_launch = kv is not None and M == 1 and head_dim % 8 == 0 and head_dim <= 128 and hidden <= 8192
     if kv is None:
         B.sqap_rope(qkv[:, :2 * hidden], pos, 2 * n_heads, head_dim, stream=stream)  # queries and keys in one launch
         B.sqap_attention(qkv[:, :hidden], qkv[:, hidden:2 * hidden], qkv[:, 2 * hidden:], n_heads, head_dim, attn,
@@ -80,11 +84,16 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
     else:
         if batch != 1:
             raise ValueError("a key/value cache belongs to one sequence")
-        # rotation and cache append in one launch: rotated key | value rows land in the cache
-        B.sqap_rope_append(qkv, pos, n_heads, head_dim, kv[past:past + M], stream=stream)
-        B.sqap_attention(qkv[:, :hidden], kv[:past + M, :hidden], kv[:past + M, hidden:], n_heads, head_dim, attn,
-                         stream=stream)
-    B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
+        if one_launch:
+            # a decode step: rotation, cache append, attention and the quantizer of the next linear in one launch
+            B.sqap_decode_attention(qkv, pos, n_heads, head_dim, kv, past, attn, xq, sx, buf.counter, stream=stream)
+        else:
+            # rotation and cache append in one launch: rotated key | value rows land in the cache
+            B.sqap_rope_append(qkv, pos, n_heads, head_dim, kv[past:past + M], stream=stream)
+            B.sqap_attention(qkv[:, :hidden], kv[:past + M, :hidden], kv[:past + M, hidden:], n_heads, head_dim, attn,
+                             stream=stream)
+    if not one_launch:
+        B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.o, o, None, buf.ws, stream=stream)
     B.sqap_rmsnorm_quantize_act(x_out, None, w.gamma_mlp, eps, xq, sx, delta=o, xsum_out=x_out, stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.gate_up, gu, None, buf.ws, stream=stream)

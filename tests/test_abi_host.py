@@ -138,6 +138,20 @@ def test_glue_validation():
     assert L.sqap_attention(p, 48, p, 48, p, 48, 1, 4, 4, 1, 48, p, 48, None) == B.EUNSUPPORTED
     assert L.sqap_attention(None, 64, None, 64, None, 64, 2, 0, 4, 1, 64, None, 64, None) == B.OK
     assert L.sqap_attention(p, 64, p, 64, p, 64, -1, 4, 4, 1, 64, p, 64, None) == B.EINVAL
+    dbl = ctypes.c_double
+    args = lambda **kw: [kw.get(k, v) for k, v in (("QKV", p), ("pos", p), ("H", 2), ("d", 64), ("base", dbl(1e4)), ("KV", p),
+                                                    ("ldkv", 256), ("past", 3), ("O", p), ("Xq", None), ("sx", None),
+                                                    ("counter", None), ("stream", None))]
+    assert L.sqap_decode_attention(*args(H=0)) == B.EINVAL
+    assert L.sqap_decode_attention(*args(past=-1)) == B.EINVAL
+    assert L.sqap_decode_attention(*args(ldkv=248)) == B.EINVAL                               # pitch below 2 H d
+    assert L.sqap_decode_attention(*args(base=dbl(0.0))) == B.EINVAL
+    assert L.sqap_decode_attention(*args(O=None)) == B.EINVAL
+    assert L.sqap_decode_attention(*args(Xq=p, sx=p)) == B.EINVAL                             # quantizer without its counter
+    assert L.sqap_decode_attention(*args(d=60, ldkv=240)) == B.EUNSUPPORTED
+    assert L.sqap_decode_attention(*args(d=136, ldkv=544)) == B.EUNSUPPORTED
+    assert L.sqap_decode_attention(*args(KV=ctypes.c_void_p(4104))) == B.EUNSUPPORTED
+    assert L.sqap_decode_attention(*args(H=128, d=128, ldkv=32768, Xq=p, sx=p, counter=p)) == B.EUNSUPPORTED
     assert L.sqap_residual_add(p, 64, p, 32, 2, 64, None) == B.EINVAL
     assert L.sqap_residual_add(p, 68, p, 68, 2, 68, None) == B.EUNSUPPORTED
 

@@ -232,6 +232,74 @@ def test_attention_batch(G, oracle):
         assert G.assert_fp16_close(got[b * S:(b + 1) * S], want) >= 0
 
 
+@pytest.mark.parametrize("H,d,past,quantize", [(32, 128, 148, True), (4, 64, 0, True), (3, 16, 5, True),
+                                                (8, 128, 1100, True), (2, 96, 70, False), (32, 128, 63, False)])
+def test_decode_attention_in_one_launch(G, oracle, H, d, past, quantize):
+    """Rotation + cache append + attention (+ activation quantizer) of one new token in one launch:
+    the cache row against the oracle's rotation, the output against the oracle's attention over the
+    oracle's own rotated rows, the codes against the oracle's quantizer of the oracle's output within
+    one quantization step (the outputs differ within the fp16 tolerance, so codes may flip at
+    rounding boundaries) and, bit for bit, against the library's own quantizer on the same output."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(H * 1000 + d + past)
+    width = H * d
+    QKV = rng.standard_normal((1, 3 * width)).astype(np.float16)
+    QKV[:, :width] *= 2.0
+    prefix = rng.standard_normal((past, 2 * width)).astype(np.float16)          # rotated keys | values already cached
+    pos = np.array([past + 3], dtype=np.int32)
+    q_rot = oracle.rope(QKV[:, :width].reshape(1, H, d), pos)
+    k_rot = oracle.rope(QKV[:, width:2 * width].reshape(1, H, d), pos)
+    Kn = np.concatenate([prefix[:, :width].reshape(past, H, d), k_rot], axis=0)
+    Vn = np.concatenate([prefix[:, width:].reshape(past, H, d), QKV[:, 2 * width:].reshape(1, H, d)], axis=0)
+    want = oracle.attention(q_rot, Kn, Vn).reshape(1, width)
+
+    pitch = 2 * width + 16
+    cache = torch.full((past + 3, pitch), 7.0, dtype=torch.float16, device="cuda")
+    cache[:past, :2 * width] = G.to_dev(prefix)
+    qkv, p = G.to_dev(QKV), G.to_dev(pos)
+    O = torch.full((1, width), float("nan"), dtype=torch.float16, device="cuda")
+    Xq = torch.full((1, width // 2), 0x5a, dtype=torch.uint8, device="cuda") if quantize else None
+    sx = torch.full((1,), float("nan"), dtype=torch.float16, device="cuda") if quantize else None
+    counter = torch.zeros((1,), dtype=torch.int32, device="cuda") if quantize else None
+    for _ in range(2):                                                         # the second call finds the counter at zero again
+        B.sqap_decode_attention(qkv, p, H, d, cache[:, :2 * width], past, O, Xq, sx, counter)
+    torch.cuda.synchronize()
+    cn, got = cache.cpu().numpy(), O.cpu().numpy()
+    assert np.array_equal(qkv.cpu().numpy().view(np.uint16), QKV.view(np.uint16))                      # only read
+    assert np.array_equal(cn[:past, :2 * width].view(np.uint16), prefix.view(np.uint16))               # earlier rows untouched
+    assert np.all(cn[past + 1:] == 7.0) and np.all(cn[:, 2 * width:] == 7.0)
+    assert G.assert_fp16_close(cn[past:past + 1, :width], k_rot.reshape(1, width)) <= width // 100
+    assert np.array_equal(cn[past:past + 1, width:2 * width].view(np.uint16), QKV[:, 2 * width:].view(np.uint16))
+    assert G.assert_fp16_close(got, want) >= 0
+    # the separate calls give the same cache row (bits) and an output within the tolerance
+    qkv2 = G.to_dev(QKV)
+    cache2 = cache.clone()
+    cache2[past] = 7.0
+    O2 = torch.empty_like(O)
+    B.sqap_rope_append(qkv2, p, H, d, cache2[past:past + 1, :2 * width])
+    if d in (16, 32, 64, 128):
+        B.sqap_attention(qkv2[:, :width], cache2[:past + 1, :width], cache2[:past + 1, width:2 * width], H, d, O2)
+        torch.cuda.synchronize()
+        assert G.assert_fp16_close(got, O2.cpu().numpy()) >= 0
+    torch.cuda.synchronize()
+    assert np.array_equal(cache2.cpu().numpy().view(np.uint16), cn.view(np.uint16))
+    if quantize:
+        assert int(counter.item()) == 0
+        q_o, s_o, _ = oracle.quantize_rows(want)
+        step = float(np.asarray(s_o, dtype=np.float64)[0])
+        s_g = float(sx.cpu().numpy().astype(np.float64)[0])
+        assert abs(s_g - step) <= 2e-3 * step + 1e-6                          # scale = half(max / 7) of outputs 1e-3 apart
+        deq_g = oracle.unpack_int4(Xq.cpu().numpy()).astype(np.float64) * s_g
+        deq_o = oracle.unpack_int4(q_o).astype(np.float64) * step
+        assert np.all(np.abs(deq_g - deq_o) <= 1.02 * step + 1e-6)
+        q2 = torch.empty_like(Xq)
+        s2 = torch.empty_like(sx)
+        B.sqap_quantize_act(O, None, q2, s2)
+        torch.cuda.synchronize()
+        assert torch.equal(q2, Xq) and torch.equal(s2.view(torch.int16), sx.view(torch.int16))
+
+
 def test_residual_add(G, oracle):
     import torch
     from paper_2509_09090_amd import binding as B
