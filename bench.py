@@ -452,7 +452,7 @@ def decode_forward_leg(torch, B, wl, dev, layers, buf, g, prefix=148, new_tokens
     e1.record()
     torch.cuda.synchronize()
     us_eager = e0.elapsed_time(e1) * 1e3 / (3 * new_tokens)
-    res = {"us_per_token_eager": us_eager, "launches_per_token": nl * 8 + 2, "prefix": prefix,
+    res = {"us_per_token_eager": us_eager, "launches_per_token": nl * 9 + 2, "prefix": prefix,
            "new_tokens": new_tokens}
     try:
         res["us_per_token_graph"] = graph_time_us(torch, generate, 3, per_graph=1) / new_tokens

@@ -10,11 +10,31 @@
 
 namespace sqap {
 
+// The rotation frequencies base^(-2i/d), i < d/2, depend on the model alone: the host evaluates them (binary64
+// pow) and hands them over as a kernel argument, which takes the power out of the dependent chain
+// power -> angle -> sine and cosine that every pair used to walk (a third of a rotary launch's time at a few
+// hundred tokens).  Head sizes above 2 * kRopeTableMax evaluate the power on the device as before.
+constexpr int kRopeTableMax = 128;
+struct RopeFreq {
+    double f[kRopeTableMax];
+};
+static RopeFreq rope_frequencies(int d, double base)
+{
+    RopeFreq r = {};
+    for (int i = 0; i < d / 2 && i < kRopeTableMax; ++i) r.f[i] = std::pow(base, -2.0 * (double)i / (double)d);
+    return r;
+}
+__device__ __forceinline__ double rope_angle(const RopeFreq &freq, int pos, int i, int d, double base)
+{
+    const double f = (d >> 1) <= kRopeTableMax ? freq.f[i] : pow(base, -2.0 * (double)i / (double)d);
+    return (double)pos * f;
+}
+
 // v'_i = v_i cos a - v_{i+d/2} sin a,  v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a,
 // a = pos * base^(-2i/d); angle, sine and cosine in binary64, products in binary64, one rounding
 // to half.  One thread per (token, head, i); consecutive threads take consecutive i.
 __global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ X, int64_t ld, const int32_t *__restrict__ pos,
-                                                   int S, int H, int d, double base)
+                                                   int S, int H, int d, double base, const RopeFreq freq)
 {
     const int half_d = d >> 1;
     const int64_t total = (int64_t)S * H * half_d;
@@ -25,7 +45,7 @@ __global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ X, int64
     const int h = (int)(sh % H);
     const int s = (int)(sh / H);
     __half *v = X + (int64_t)s * ld + (int64_t)h * d;
-    const double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+    const double a = rope_angle(freq, pos[s], i, d, base);
     double sn, cs;
     sincos(a, &sn, &cs);
     const double lo = (double)__half2float(v[i]), hi = (double)__half2float(v[i + half_d]);
@@ -39,7 +59,7 @@ __global__ __launch_bounds__(256) void rope_kernel(__half *__restrict__ X, int64
 // One thread per (token, head-or-value slot, i): slots 0 .. H-1 queries, H .. 2H-1 keys, 2H .. 3H-1 values.
 __global__ __launch_bounds__(256) void rope_append_kernel(__half *__restrict__ QKV, int64_t ld,
                                                           const int32_t *__restrict__ pos, int S, int H, int d,
-                                                          double base, __half *__restrict__ KV, int64_t ldkv)
+                                                          double base, __half *__restrict__ KV, int64_t ldkv, const RopeFreq freq)
 {
     const int half_d = d >> 1;
     const int64_t total = (int64_t)S * 3 * H * half_d;
@@ -56,7 +76,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(__half *__restrict__ Q
         dst[i + half_d] = src[i + half_d];
         return;
     }
-    const double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+    const double a = rope_angle(freq, pos[s], i, d, base);
     double sn, cs;
     sincos(a, &sn, &cs);
     const double lo = (double)__half2float(src[i]), hi = (double)__half2float(src[i + half_d]);
@@ -73,7 +93,7 @@ sqap_status launch_rope_append(__half *QKV, int64_t ld, const int32_t *pos, int 
     const int64_t total = (int64_t)S * 3 * H * (d / 2);
     if (total == 0) return SQAP_OK;
     hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, QKV, ld, pos, S, H, d,
-                       base, KV, ldkv);
+                       base, KV, ldkv, rope_frequencies(d, base));
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
@@ -86,12 +106,13 @@ constexpr int kRopeMaxHalfD = 256;
 constexpr int kRopeTokenKernelFrom = 512;        // tokens
 
 __global__ __launch_bounds__(256) void rope_token_kernel(__half *__restrict__ X, int64_t ld,
-                                                         const int32_t *__restrict__ pos, int H, int d, double base)
+                                                         const int32_t *__restrict__ pos, int H, int d, double base,
+                                                         const RopeFreq freq)
 {
     __shared__ double cs[kRopeMaxHalfD], sn[kRopeMaxHalfD];
     const int half_d = d >> 1, s = blockIdx.x;
     for (int i = threadIdx.x; i < half_d; i += 256) {
-        const double a = (double)pos[s] * pow(base, -2.0 * (double)i / (double)d);
+        const double a = rope_angle(freq, pos[s], i, d, base);
         double sv, cv;
         sincos(a, &sv, &cv);
         sn[i] = sv;
@@ -113,11 +134,12 @@ sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H,
     const int64_t total = (int64_t)S * H * (d / 2);
     if (total == 0) return SQAP_OK;
     if (S >= kRopeTokenKernelFrom && d / 2 <= kRopeMaxHalfD) {
-        hipLaunchKernelGGL(rope_token_kernel, dim3(S), dim3(256), 0, st, X, ld, pos, H, d, base);
+        hipLaunchKernelGGL(rope_token_kernel, dim3(S), dim3(256), 0, st, X, ld, pos, H, d, base, rope_frequencies(d, base));
         SQAP_HIP_CHECK(hipGetLastError());
         return SQAP_OK;
     }
-    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, X, ld, pos, S, H, d, base);
+    hipLaunchKernelGGL(rope_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, X, ld, pos, S, H, d, base,
+                       rope_frequencies(d, base));
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }
@@ -488,10 +510,13 @@ sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int
 // of latency and no work, so the quantizer of the following linear is folded in as well: the
 // workgroup that finishes last (a device-wide arrival counter) quantizes the whole output row.
 //
-// Scores: 16 lanes per key, lane c holding columns 8c .. 8c+7 (one 16-byte load per key row), four keys
-// per lane group in flight; softmax over chunks of 1024 keys with the usual running maximum and sum;
-// output: the same lane layout over the value rows, the 16 key groups added through LDS.  All binary32.
-constexpr int kDecChunk = 1024;            // keys per softmax chunk
+// Scores: 16 lanes per key, lane c holding columns 8c .. 8c+7 (one 16-byte load per key row); softmax over
+// chunks of 192 keys with the usual running maximum and sum; output: the same lane layout over the value
+// rows, the 16 key groups added through LDS.  All binary32.  A chunk's key AND value rows (12 of each per
+// lane) are asked for at once, the first chunk's before the rotation, whose binary64 sine and cosine are a
+// longer dependent chain than the rest of the kernel: a prefix of up to 191 positions costs one round of loads.
+constexpr int kDecKeys = 12;              // keys per lane group and chunk: their key and value rows are in flight together
+constexpr int kDecChunk = 16 * kDecKeys;   // keys per softmax chunk
 constexpr int kDecMaxD = 128;              // head size limit: 16 lanes x 8 columns
 constexpr int kDecMaxRow = 8192;           // H * d limit of the fused quantizer (row staged in LDS)
 
@@ -510,7 +535,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
                                                                const int32_t *__restrict__ pos, int H, int d,
                                                                double base, __half *KV, int64_t ldkv, int past,
                                                                __half *O, uint8_t *__restrict__ Xq,
-                                                               __half *__restrict__ sx, unsigned int *counter)
+                                                               __half *__restrict__ sx, unsigned int *counter,
+                                                               const RopeFreq freq)
 {
     __shared__ __attribute__((aligned(16))) float qf[kDecMaxD];
     __shared__ __attribute__((aligned(16))) __half knew[kDecMaxD], vnew[kDecMaxD];
@@ -524,10 +550,26 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
     const int half_d = d >> 1, width = H * d;
     const int Sk = past + 1;
 
+    const int grp = t >> 4, c = t & 15;              // key group, column chunk
+    const bool col_ok = c * 8 < d;
+    const __half *kbase = KV + (int64_t)h * d + c * 8, *vbase = kbase + width;
+    // a cached row's 8 columns of this lane (zeros past the prefix; the new token's row comes from LDS later)
+    auto cached = [&](const __half *gbase, int key) {
+        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+        if (col_ok && key < past) raw = *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
+        return raw;
+    };
+    uint4 kraw[kDecKeys], vraw[kDecKeys];
+#pragma unroll
+    for (int j = 0; j < kDecKeys; ++j) {
+        kraw[j] = cached(kbase, 16 * j + grp);
+        vraw[j] = cached(vbase, 16 * j + grp);
+    }
+
     // rotation of this head's query and key; the value is copied
     if (t < half_d) {
         const int i = t;
-        const double a = (double)pos[0] * pow(base, -2.0 * (double)i / (double)d);
+        const double a = rope_angle(freq, pos[0], i, d, base);
         double sn, cs;
         sincos(a, &sn, &cs);
         const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
@@ -551,21 +593,10 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
     }
     __syncthreads();
 
-    const int grp = t >> 4, c = t & 15;              // key group, column chunk
-    const bool col_ok = c * 8 < d;
     float q8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) q8[e] = col_ok ? qf[c * 8 + e] : 0.f;
     const float inv_sqrt_d = 1.0f / sqrtf((float)d);
-    const __half *kbase = KV + (int64_t)h * d + c * 8, *vbase = kbase + width;
-    // row `key` of the cache, the new token's from LDS (its global copy was written by this workgroup just now)
-    auto fetch = [&](const __half *gbase, const __half *fresh, int key) {
-        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (col_ok && key < Sk)
-            raw = key == past ? *reinterpret_cast<const uint4 *>(fresh + c * 8)
-                              : *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
-        return raw;
-    };
 
     float o[8];
 #pragma unroll
@@ -573,21 +604,28 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
     float m = -INFINITY, l = 0.f;
     for (int c0 = 0; c0 < Sk; c0 += kDecChunk) {
         const int n = min(kDecChunk, Sk - c0);
-        for (int kb = 0; kb < n; kb += 64) {
-            uint4 raw[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = fetch(kbase, knew, c0 + kb + 16 * j + grp);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float kf[8];
-                unpack_halves(raw[j], kf);
-                float s = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
-                for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
-                const int key = kb + 16 * j + grp;
-                if (c == 0 && key < n) sc[key] = s * inv_sqrt_d;
+        for (int j = 0; j < kDecKeys; ++j) {
+            const int key = c0 + 16 * j + grp;
+            if (c0 > 0) {
+                kraw[j] = cached(kbase, key);
+                vraw[j] = cached(vbase, key);
             }
+            if (key == past && col_ok) {
+                kraw[j] = *reinterpret_cast<const uint4 *>(knew + c * 8);
+                vraw[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kDecKeys; ++j) {
+            float kf[8];
+            unpack_halves(kraw[j], kf);
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
+            for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
+            const int key = 16 * j + grp;
+            if (c == 0 && key < n) sc[key] = s * inv_sqrt_d;
         }
         __syncthreads();
         float mx = -INFINITY;
@@ -611,19 +649,14 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
         m = m_new;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] *= rescale;
-        for (int kb = 0; kb < n; kb += 64) {
-            uint4 raw[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) raw[j] = fetch(vbase, vnew, c0 + kb + 16 * j + grp);
+        for (int j = 0; j < kDecKeys; ++j) {
+            const int key = 16 * j + grp;
+            const float pj = key < n ? sc[key] : 0.f;
+            float vf[8];
+            unpack_halves(vraw[j], vf);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = kb + 16 * j + grp;
-                const float pj = key < n ? sc[key] : 0.f;
-                float vf[8];
-                unpack_halves(raw[j], vf);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
-            }
+            for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
         }
         __syncthreads();                               // sc and wred are rewritten by the next chunk
     }
@@ -687,7 +720,7 @@ sqap_status launch_decode_attention(const __half *QKV, const int32_t *pos, int H
                                     unsigned int *counter, hipStream_t st)
 {
     hipLaunchKernelGGL(decode_attention_kernel, dim3(H), dim3(256), 0, st, QKV, pos, H, d, base, KV, ldkv, past, O, Xq,
-                       sx, counter);
+                       sx, counter, rope_frequencies(d, base));
     SQAP_HIP_CHECK(hipGetLastError());
     return SQAP_OK;
 }

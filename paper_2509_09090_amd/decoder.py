@@ -9,8 +9,8 @@ published pre-normalisation layer:
                                              sqap_rope_append with a key/value cache: append folded in)
     a = causal attention(q, k, v)            sqap_attention
     o = W_o quant(a)                         sqap_quantize_act + sqap_w4a4_linear
-                                             (one token with a cache: rotation, append, attention and this
-                                             quantizer are one launch, sqap_decode_attention)
+                                             (one token with a cache: rotation, append and attention are one
+                                             launch, sqap_decode_attention, which can take this quantizer along)
     y2 = RMSNorm(x + o) -> int4              sqap_rmsnorm_quantize_act   (residual add fused)
     g|u = W_gu y2                            sqap_w4a4_linear            (N = 2 * ffn)
     h = silu(g) * u -> int4                  sqap_swiglu_quantize_act
@@ -57,7 +57,7 @@ class LayerBuffers:
 
 
 def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_out, eps=1e-5, rows=None,
-                  rotate=False, kv=None, past=0, stream=None):
+                  rotate=False, kv=None, past=0, stream=None, fold_quantizer=False):
     """Runs one layer on M token rows (batch sequences of M / batch tokens each).
 
     x: residual stream [*, hidden] fp16 (rows picks the M rows when given: the token gather is fused);
@@ -85,14 +85,19 @@ def layer_forward(w, buf, x, pending, pos, batch, n_heads, head_dim, x_out, d_ou
         if batch != 1:
             raise ValueError("a key/value cache belongs to one sequence")
         if one_launch:
-            # a decode step: rotation, cache append, attention and the quantizer of the next linear in one launch
-            B.sqap_decode_attention(qkv, pos, n_heads, head_dim, kv, past, attn, xq, sx, buf.counter, stream=stream)
+            # a decode step: rotation, cache append and attention in one launch.  The quantizer of the next
+            # linear can ride along (fold_quantizer: one launch fewer, which pays when the host's launch rate is
+            # the limit) but its device-wide arrival costs more GPU time than the separate launch (4.7 against 2.3 us)
+            if fold_quantizer:
+                B.sqap_decode_attention(qkv, pos, n_heads, head_dim, kv, past, attn, xq, sx, buf.counter, stream=stream)
+            else:
+                B.sqap_decode_attention(qkv, pos, n_heads, head_dim, kv, past, attn, stream=stream)
         else:
             # rotation and cache append in one launch: rotated key | value rows land in the cache
             B.sqap_rope_append(qkv, pos, n_heads, head_dim, kv[past:past + M], stream=stream)
             B.sqap_attention(qkv[:, :hidden], kv[:past + M, :hidden], kv[:past + M, hidden:], n_heads, head_dim, attn,
                              stream=stream)
-    if not one_launch:
+    if not (one_launch and fold_quantizer):
         B.sqap_quantize_act(attn, None, xq, sx, stream=stream)
     B.sqap_w4a4_linear(xq, sx, w.o, o, None, buf.ws, stream=stream)
     B.sqap_rmsnorm_quantize_act(x_out, None, w.gamma_mlp, eps, xq, sx, delta=o, xsum_out=x_out, stream=stream)

@@ -439,7 +439,8 @@ def test_decoder_layer_with_a_key_value_cache(G, oracle):
         x1 = torch.zeros((1, hidden), dtype=torch.float16, device="cuda")
         d1 = torch.zeros((1, hidden), dtype=torch.float16, device="cuda")
         before = kv.cpu().numpy()[:past]
-        decoder.layer_forward(w, buf, G.to_dev(xt), None, G.to_dev(pt), 1, H, d, x1, d1, kv=kv, past=past)
+        decoder.layer_forward(w, buf, G.to_dev(xt), None, G.to_dev(pt), 1, H, d, x1, d1, kv=kv, past=past,
+                              fold_quantizer=step % 2 == 1)        # the quantizer as its own launch, then folded in
         torch.cuda.synchronize()
         after = kv.cpu().numpy()
         assert np.array_equal(after[:past].view(np.uint16), before.view(np.uint16))          # earlier rows untouched
