@@ -360,7 +360,7 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
     e1.record()
     torch.cuda.synchronize()
     eager_us = e0.elapsed_time(e1) / reps * 1e3
-    res = {"us_forward_eager": eager_us, "launches": 2 * 11 + 4 + 30 * 11 + 2,
+    res = {"us_forward_eager": eager_us, "launches": 2 * 10 + 4 + 30 * 10 + 2,
            "note": "32 layers, 276 tokens for 2 layers then 84; includes the pruning step"}
     # the same forward replayed from a HIP graph (no host launch cost)
     try:
