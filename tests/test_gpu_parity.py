@@ -470,7 +470,9 @@ def test_linear_replayed_from_a_graph(G, oracle, M, N, K):
 # ------------------------------------------------------------------ small-M (decode) path
 @pytest.mark.parametrize("M,N,K", [(1, 4096, 4096), (2, 544, 640), (3, 33, 64), (4, 11008, 4096),
                                    (7, 4096, 11008), (8, 1000, 11008), (8, 32000, 4096), (1, 32, 128),
-                                   (8, 64, 64), (5, 96, 1088)])
+                                   (8, 64, 64), (5, 96, 1088),
+                                   # few row groups with long rows: every wavefront walks its ring two or three times
+                                   (1, 8192, 8192), (3, 2048, 16384), (2, 96, 8320), (8, 4096, 11008)])
 def test_small_m_linear(G, oracle, M, N, K):
     rng = np.random.default_rng(M * 11 + N * 5 + K)
     Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
