@@ -133,6 +133,14 @@ template <int S, int W>
 __global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
 {
     constexpr bool LATE = W == kSkinnyWavesBig;  // outputs wait in LDS (the 16-wavefront form)
+    // The 16-wavefront form also hands out a segment's items on demand.  With a fixed stride a block's run
+    // of about 170 items leaves some wavefronts one item more than others (a twelfth of their work), and a
+    // wavefront that gets less of the memory system than its neighbours cannot pass work on: the
+    // wavefronts of a block ended up to 60 us apart at 450 us.  The first W items of a segment are dealt
+    // by wavefront index; after that a wavefront takes the next one from a counter in LDS, one item ahead
+    // of its need so that the load ring runs on across the item boundary as before.
+    constexpr bool DYN = LATE && S == 1;
+    __shared__ int seg_next;
     constexpr int R = W / S;                     // items a block works on at a time
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int t = threadIdx.x, lane = t & 63;
@@ -220,8 +228,10 @@ __global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
         const int cn = (int)((long long)cps * (ks + 1) / S) - c0;
         const int rounds = (cn + kSkinnyDepth - 1) / kSkinnyDepth;
         const size_t item_stride = (size_t)R * e.chunks * 32;     // in v4i: R row groups on
-        const v4i *wsrc =
-            reinterpret_cast<const v4i *>(e.Wd + ((size_t)(item - e.rg_begin) * e.chunks + 2 * c0) * 512) + lane;
+        auto item_weights = [&](int it) {
+            return reinterpret_cast<const v4i *>(e.Wd + ((size_t)(it - e.rg_begin) * e.chunks + 2 * c0) * 512) + lane;
+        };
+        const v4i *wsrc = item_weights(item);
         v4i wbuf[kSkinnyDepth];
         if (item < seg_end) {
 #pragma unroll
@@ -236,6 +246,7 @@ __global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
             if (rr < e.M) v = reinterpret_cast<const v4i *>(e.Xq + (size_t)rr * Kh)[2 * cp + hh];
             *reinterpret_cast<v4i *>(xs + cp * 256 + hh * 128 + rr * 16) = v;
         }
+        if (DYN && t == 0) seg_next = cur + R;     // everybody has left the previous segment's loop (barrier above)
         __syncthreads();
         // lanes whose token row does not exist read the zero block, with stride 0
         const bool has_row = r < e.M;
@@ -247,11 +258,17 @@ __global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
         const bool y_late = LATE && a.out_cap > 0 && (e.N & 7) == 0 && (e.ldy & 7) == 0 &&
                             (reinterpret_cast<uintptr_t>(e.Y) & 15u) == 0;
 
-        for (int base = cur; base < seg_end; base += R, item += R) {
+        for (int base = cur; DYN ? item < seg_end : base < seg_end; base += R) {
             const int rg = item - e.rg_begin;
             const bool active = item < seg_end;
-            const bool has_next = item + R < seg_end;
-            const v4i *wnext = has_next ? wsrc + item_stride : wsrc;
+            int next_item = item + R;
+            if (DYN) {
+                int taken = 0;
+                if (lane == 0) taken = atomicAdd(&seg_next, 1);
+                next_item = __builtin_amdgcn_readfirstlane(taken);
+            }
+            const bool has_next = next_item < seg_end;
+            const v4i *wnext = has_next ? (DYN ? item_weights(next_item) : wsrc + item_stride) : wsrc;
             v16i acc;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0;
@@ -289,6 +306,7 @@ __global__ __launch_bounds__(W * 64, 4) void skinny_kernel(const SkinnyArgs a)
             }
             }
             wsrc = wnext;
+            item = next_item;
             // Accumulator layout: lane l holds token l%32 and, in register i, channel
             // 8*(i/4) + 4*(l/32) + (i%4) of the row group: four consecutive channels per quad.
             if (S > 1) {
@@ -384,7 +402,8 @@ static size_t skinny_base_lds_bytes(int max_chunks, int waves)
 }
 static int skinny_out_cap(size_t base)
 {
-    const size_t room = base < 160 * 1024 ? 160 * 1024 - base : 0;
+    const size_t limit = 160 * 1024 - 64;       // the kernel's few statically allocated bytes come on top
+    const size_t room = base < limit ? limit - base : 0;
     const int cap = (int)(room / ((size_t)kSkinnyWavesBig * kSkinnyOutSlot));
     return cap > kSkinnyOutCapMax ? kSkinnyOutCapMax : cap;
 }
