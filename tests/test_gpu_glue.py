@@ -300,6 +300,57 @@ def test_decode_attention_in_one_launch(G, oracle, H, d, past, quantize):
         assert torch.equal(q2, Xq) and torch.equal(s2.view(torch.int16), sx.view(torch.int16))
 
 
+def test_decode_attention_replayed_from_a_graph(G, oracle):
+    """The folded quantizer's arrival counter is put back to zero by the last workgroup, so a captured
+    launch replays: new inputs per replay, an eager call on the same counter in between, each result
+    against the oracle and the counter at zero afterwards."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    H, d, past = 8, 64, 37
+    width = H * d
+    rng = np.random.default_rng(977)
+    prefix = rng.standard_normal((past, 2 * width)).astype(np.float16)
+    cache = torch.zeros((past + 1, 2 * width), dtype=torch.float16, device="cuda")
+    cache[:past] = G.to_dev(prefix)
+    qkv = torch.zeros((1, 3 * width), dtype=torch.float16, device="cuda")
+    pos = G.to_dev(np.array([past], dtype=np.int32))
+    O = torch.zeros((1, width), dtype=torch.float16, device="cuda")
+    Xq = torch.zeros((1, width // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((1,), dtype=torch.float16, device="cuda")
+    counter = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()          # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.sqap_decode_attention(qkv, pos, H, d, cache, past, O, Xq, sx, counter)       # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.sqap_decode_attention(qkv, pos, H, d, cache, past, O, Xq, sx, counter)
+    for rep in range(4):
+        QKV = rng.standard_normal((1, 3 * width)).astype(np.float16)
+        qkv.copy_(G.to_dev(QKV))
+        O.fill_(float("nan"))
+        Xq.fill_(0x5a)
+        graph.replay()
+        torch.cuda.synchronize()
+        p = np.array([past], dtype=np.int32)
+        q_rot = oracle.rope(QKV[:, :width].reshape(1, H, d), p)
+        k_rot = oracle.rope(QKV[:, width:2 * width].reshape(1, H, d), p)
+        Kn = np.concatenate([prefix[:, :width].reshape(past, H, d), k_rot], axis=0)
+        Vn = np.concatenate([prefix[:, width:].reshape(past, H, d), QKV[:, 2 * width:].reshape(1, H, d)], axis=0)
+        assert G.assert_fp16_close(O.cpu().numpy(), oracle.attention(q_rot, Kn, Vn).reshape(1, width)) >= 0, rep
+        assert int(counter.item()) == 0, rep
+        q2, s2 = torch.empty_like(Xq), torch.empty_like(sx)
+        B.sqap_quantize_act(O, None, q2, s2)
+        torch.cuda.synchronize()
+        assert torch.equal(q2, Xq) and torch.equal(s2.view(torch.int16), sx.view(torch.int16)), rep
+        O3, q3, s3 = torch.empty_like(O), torch.empty_like(Xq), torch.empty_like(sx)
+        B.sqap_decode_attention(qkv, pos, H, d, cache, past, O3, q3, s3, counter)      # eager, same counter
+        torch.cuda.synchronize()
+        assert torch.equal(O3.view(torch.int16), O.view(torch.int16)) and torch.equal(q3, Xq), rep
+
+
 def test_residual_add(G, oracle):
     import torch
     from paper_2509_09090_amd import binding as B
