@@ -321,7 +321,8 @@ sqap_status sqap_swiglu_quantize_act(const sqap_f16 *G, int64_t ldg, const sqap_
  * Rotary position embedding, in place, half-split pairing: for token s, head h
  * and i < d/2, with a = pos[s] * base^(-2i/d),
  *   v'_i = v_i cos a - v_{i+d/2} sin a,   v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a,
- * evaluated in binary64 and rounded to half.  X: [S, H*d] with row pitch ld
+ * evaluated in binary64, rounded to binary32 and then to half (two roundings).
+ * X: [S, H*d] with row pitch ld
  * (elements), so a slice of a fused q/k/v output can be rotated where it lies.
  * pos: [S] int32 device.  EINVAL: null pointer, d odd, ld < H*d, base <= 0.
  *

@@ -387,6 +387,7 @@ int oracle_quantize_rows(const uint16_t *X, int64_t ldx, const int32_t *rows, in
     for (int i = 0; i < M; ++i) {
         float *v = (float *)malloc(sizeof(float) * (size_t)K);
         if (!v) {
+#pragma omp atomic write
             status = -4;
             continue;
         }
@@ -479,6 +480,7 @@ int oracle_quantize_rows_channelwise(const uint16_t *X, int64_t ldx, const int32
     for (int i = 0; i < M; ++i) {
         float *v = (float *)malloc(sizeof(float) * (size_t)K);
         if (!v) {
+#pragma omp atomic write
             status = -4;
             continue;
         }
@@ -516,6 +518,7 @@ int oracle_quantize_rows_folded(const uint16_t *W, int64_t ldw, int N, int K, in
     for (int i = 0; i < N; ++i) {
         float *v = (float *)malloc(sizeof(float) * (size_t)K);
         if (!v) {
+#pragma omp atomic write
             status = -4;
             continue;
         }
@@ -770,7 +773,8 @@ int oracle_swiglu(const uint16_t *G, int64_t ldg, const uint16_t *U, int64_t ldu
  * size d at position p and i < d/2, with angle a = p * base^(-2i/d),
  *   v'_i       = v_i cos a - v_{i+d/2} sin a
  *   v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a
- * in binary64, rounded to binary16.  X: [S, H, d] halves, in place.
+ * in binary64; each result is rounded to binary32 and that to binary16 (two
+ * roundings).  X: [S, H, d] halves, in place.
  */
 int oracle_rope(uint16_t *X, const int32_t *pos, int S, int H, int d, double base)
 {
@@ -794,7 +798,7 @@ int oracle_rope(uint16_t *X, const int32_t *pos, int S, int H, int d, double bas
  * queries are the last Sq positions of a sequence of Sk keys: query s sits at
  * position Sk - Sq + s and sees keys t <= Sk - Sq + s.
  *   l[s,t] = (q[s,h,:] . k[t,h,:]) / sqrt(d),   p[s,:] = softmax_t(l[s,:]),
- *   o[s,h,:] = sum_t p[s,t] v[t,h,:]  -> binary16.
+ *   o[s,h,:] = sum_t p[s,t] v[t,h,:]  -> binary32 -> binary16 (two roundings).
  * Q, O: [Sq, H, d] halves; K, V: [Sk, H, d].  Queries and keys are taken as
  * given (rotate them with oracle_rope first).
  */
