@@ -38,15 +38,16 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-layers", action="store_true")
+    ap.add_argument("--no-variants", action="store_true", help="skip the cold-weight / rotated / outlier-free GEMM timings")
     ap.add_argument("--only", default="", help="prefill|decode|decoder|calib: run just that loop --steps times (for profilers)")
     return ap.parse_args()
 
 
-def quantize_and_pack(torch, B, W):
+def quantize_and_pack(torch, B, W, flags=0):
     N, K = W.shape
     Wq = torch.empty((N, K // 2), dtype=torch.uint8, device=W.device)
     sw = torch.empty((N,), dtype=torch.float16, device=W.device)
-    B.sqap_quantize_weight(W, Wq, sw)
+    B.sqap_quantize_weight(W, Wq, sw, flags)
     h = B.sqap_weight_pack(Wq, sw)
     torch.cuda.synchronize()
     return h
@@ -55,9 +56,14 @@ def quantize_and_pack(torch, B, W):
 class Prefill:
     """Configuration 3 resident on the GPU."""
 
-    def __init__(self, torch, B, wl, dev):
+    def __init__(self, torch, B, wl, dev, variant="workload"):
+        """variant: "workload" (1 % outlier channels x30, no rotation: the configuration as defined), "rotated"
+        (same inputs, quantized with the Hadamard rotation: codes spread over the whole 4-bit range) or
+        "outlier_free" (plain N(0,1) inputs).  The GEMM's work is the same; its power draw, hence its clock, is not."""
         c = wl.CONFIGS[3]
         self.torch, self.B = torch, B
+        self.flags = B.ROTATE_HADAMARD if variant == "rotated" else 0
+        frac = 0.0 if variant == "outlier_free" else 0.01
         self.batch, self.keep = c["batch"], c["keep_k"]
         self.S, self.nv = wl.SEQ_LEN, wl.N_VISUAL
         self.M = self.batch * (self.keep + wl.N_TEXT)
@@ -65,10 +71,11 @@ class Prefill:
         self.H, self.F = H, F
         t = lambda a: torch.from_numpy(a).to(dev)
         self.scores = t(wl.scores(self.batch, self.nv, wl.rng_for(3, 0, wl.T_SCORES)))
-        self.X = t(wl.layer_input(3, 0, 4, self.batch * self.S))          # gate/up input, all tokens
-        self.Xd = t(wl.layer_input(3, 0, 6, self.M))                       # down input, kept tokens
-        self.W_gate = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 4)))
-        self.W_down = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 6)))
+        self.X = t(wl.layer_input(3, 0, 4, self.batch * self.S, outlier_frac=frac))   # gate/up input, all tokens
+        self.Xd = t(wl.layer_input(3, 0, 6, self.M, outlier_frac=frac))                # down input, kept tokens
+        self.W_gate = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 4)), self.flags)
+        self.W_down = quantize_and_pack(torch, B, t(wl.layer_weight(3, 0, 6)), self.flags)
+        self.cold = None                 # list of (W_gate, W_down) used in turn: see make_cold_weights
         i32, u8, f16 = torch.int32, torch.uint8, torch.float16
         self.idx = torch.empty((self.batch, self.keep), dtype=i32, device=dev)
         self.rows = torch.empty((self.M,), dtype=i32, device=dev)
@@ -83,27 +90,48 @@ class Prefill:
         self.ops = 2.0 * self.M * (F * H + H * F)
         self.gemm_events = None
 
+    def make_cold_weights(self, wl, total_bytes=1.1e9):
+        """Distinct weight pairs summing to more than a gigabyte (the last-level cache holds 256 MB), used in
+        turn by step(): every launch then streams its weights from HBM."""
+        torch, B = self.torch, self.B
+        g = torch.Generator(device=self.X.device)
+        g.manual_seed(wl.BASE_SEED + 3)
+        per_pair = self.F * self.H          # two weights of F x H codes, half a byte each
+        self.cold, self.turn = [], 0
+        for _ in range(int(total_bytes // per_pair) + 1):
+            mk = lambda N, K: quantize_and_pack(torch, B, (torch.randn((N, K), generator=g, device=self.X.device,
+                                                                       dtype=torch.float32) * 0.02).half())
+            self.cold.append((mk(self.F, self.H), mk(self.H, self.F)))
+
     def step(self):
         B, ev = self.B, self.gemm_events
+        Wg, Wd = self.W_gate, self.W_down
+        if self.cold:
+            Wg, Wd = self.cold[self.turn % len(self.cold)]
+            self.turn += 1
         B.sqap_prune_rows(self.scores, self.keep, self.S, 0, self.idx, self.rows)
-        B.sqap_quantize_act(self.X, self.rows, self.Xq, self.sx)
+        B.sqap_quantize_act(self.X, self.rows, self.Xq, self.sx, flags=self.flags)
         if ev is not None:
             ev[0].record()
-        B.sqap_w4a4_linear(self.Xq, self.sx, self.W_gate, self.Yg, None, self.ws)
+        B.sqap_w4a4_linear(self.Xq, self.sx, Wg, self.Yg, None, self.ws)
         if ev is not None:
             ev[1].record()
-        B.sqap_quantize_act(self.Xd, None, self.Xdq, self.sxd)
+        B.sqap_quantize_act(self.Xd, None, self.Xdq, self.sxd, flags=self.flags)
         if ev is not None:
             ev[2].record()
-        B.sqap_w4a4_linear(self.Xdq, self.sxd, self.W_down, self.Yd, None, self.ws)
+        B.sqap_w4a4_linear(self.Xdq, self.sxd, Wd, self.Yd, None, self.ws)
         if ev is not None:
             ev[3].record()
 
+    def free(self):
+        for w in [self.W_gate, self.W_down] + [w for pair in (self.cold or []) for w in pair]:
+            w.free()
+
 
 def time_gemm_launches(torch, wk, steps):
-    """Average duration of one prefill GEMM launch, from HIP events recorded on the launch stream
-    directly around each linear call inside whole steps that run back to back (no synchronisation
-    between the steps, as in the timed region; one at the end)."""
+    """Duration of the prefill GEMM launches, from HIP events recorded on the launch stream directly around
+    each linear call inside whole steps that run back to back (no synchronisation between the steps, as
+    in the timed region; one at the end).  Returns (mean ms per launch, per-GEMM mean ms, stats in us)."""
     all_ev = []
     for _ in range(steps):
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -112,12 +140,54 @@ def time_gemm_launches(torch, wk, steps):
         all_ev.append(ev)
     wk.gemm_events = None
     torch.cuda.synchronize()
-    per = {"gate_up": 0.0, "down": 0.0}
-    for ev in all_ev:
-        per["gate_up"] += ev[0].elapsed_time(ev[1])
-        per["down"] += ev[2].elapsed_time(ev[3])
-    total_ms = per["gate_up"] + per["down"]
-    return total_ms / (2 * steps), {k: v / steps for k, v in per.items()}
+    gate = [ev[0].elapsed_time(ev[1]) for ev in all_ev]
+    down = [ev[2].elapsed_time(ev[3]) for ev in all_ev]
+    both = sorted(gate + down)
+    stats = {"mean": 1e3 * sum(both) / len(both), "median": 1e3 * both[len(both) // 2], "min": 1e3 * both[0],
+             "max": 1e3 * both[-1], "launches": len(both)}
+    return sum(both) / len(both), {"gate_up": sum(gate) / steps, "down": sum(down) / steps}, stats
+
+
+def settle_clocks(torch, wk, max_steps=300, window=25, tol=0.01):
+    """Untimed pre-warm, whatever --warmup says: the first dozens of launches after an idle period run 5-10 %
+    slower (clocks and power management settle).  Runs whole steps in windows of `window` until the mean
+    step time of two consecutive windows differs by less than `tol`, or max_steps have run."""
+    prev, done, ms = None, 0, 0.0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    while done < max_steps:
+        e0.record()
+        for _ in range(window):
+            wk.step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / window
+        done += window
+        if prev is not None and abs(ms - prev) <= tol * prev:
+            break
+        prev = ms
+    return {"steps": done, "last_window_us_per_step": ms * 1e3}
+
+
+def read_sclk_mhz():
+    """Current shader clock of the first GPU that reports one (sysfs pp_dpm_sclk, the starred level), or None."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            for line in open(path):
+                if "*" in line:
+                    return int(line.split(":")[1].strip().lower().replace("mhz", "").replace("*", "").strip())
+        except (OSError, ValueError, IndexError):
+            continue
+    return None
+
+
+def sclk_under_load(torch, wk, steps=150):
+    """Shader clock read from the host while `steps` steps are in flight on the GPU (launches are asynchronous)."""
+    for _ in range(steps):
+        wk.step()
+    mhz = read_sclk_mhz()
+    torch.cuda.synchronize()
+    return mhz
 
 
 class Stack:
@@ -165,7 +235,7 @@ def decode_leg(torch, B, wl, stack, steps_per_m=7):
     out = {}
     dev = stack.dev
     H, F = wl.HIDDEN, wl.FFN
-    for M in (1, 8):
+    for M in (1, 2, 4, 8):
         xq_h = [stack.activation(M, H) for _ in range(3)]      # qkv input, o input, gate/up input
         xq_f = stack.activation(M, F)
         problems, levels = [], []
@@ -213,10 +283,22 @@ def decode_leg(torch, B, wl, stack, steps_per_m=7):
         whole.free()
         for gq in per_level:
             gq.free()
-    best = out["M1"]
-    out["roofline"] = {"bound": "hbm", "kernel": "skinny_kernel<1, 16>", "achieved": best["GBps"],
-                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": best["GBps"] / HBM_PEAK_GBS,
-                       "traffic": None, "algorithmic_bytes_per_launch": stack.weight_bytes + stack.scale_bytes}
+    # Two formulations of a step.  "whole_group": the 225 linears as independent problems in ONE launch (the
+    # workload definition has no glue between linears, so this is permitted, but no token generation could
+    # issue it: layer l + 1 consumes layer l's output): the ceiling of the weight stream.  "per_level": the
+    # linears that may run together (q|k|v, o, gate|up, down, head) as one launch each, in order: what a decode
+    # step's dependencies allow.  The roofline object is for the second; the first is kept beside it.
+    alg = stack.weight_bytes + stack.scale_bytes
+    dep, ceil_ = out["M1"]["per_level"], out["M1"]
+    out["roofline"] = {"bound": "hbm", "kernel": "skinny_kernel<S, 8> (129 launches per step, replayed from a HIP graph)",
+                       "formulation": "dependency-respecting: one launch per group of linears that can run together",
+                       "achieved": dep["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dep["GBps"] / HBM_PEAK_GBS,
+                       "target_frac": 0.70, "traffic": None, "algorithmic_bytes_per_step": alg}
+    out["weight_stream_ceiling"] = {"kernel": "skinny_kernel<1, 16>", "formulation": "all 225 linears as independent "
+                                    "problems in one launch (no dependencies: not a decode step)",
+                                    "achieved": ceil_["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": ceil_["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                                    "algorithmic_bytes_per_launch": alg}
     out["weights_GB"] = stack.weight_bytes / 1e9
     return out
 
@@ -260,6 +342,14 @@ def layer_leg(torch, B, wl, stack):
     total = 2 * us276 + 30 * us84
     res["cfg2_stack"] = {"us_per_layer_M276": us276, "us_per_layer_M84": us84, "us_total_32_layers": total,
                          "floor_us": 456.0, "TOPS": (2 * ops_layer(276) + 30 * ops_layer(84)) / total / 1e6}
+
+    # the vocabulary head (4096 -> 32000) at the stack's two token counts
+    for M in (84, 276):
+        xh = stack.activation(M, H)
+        yv = torch.empty((M, wl.LM_HEAD[1]), dtype=torch.float16, device=dev)
+        wsv = torch.zeros((max(B.sqap_workspace_bytes(M, wl.LM_HEAD[1], H), 256),), dtype=torch.uint8, device=dev)
+        res["cfg2_stack"]["us_lm_head_M%d" % M] = graph_time_us(
+            torch, lambda: B.sqap_w4a4_linear(xh[0], xh[1], stack.lm_head, yv, None, wsv), 20)
 
     # pruning-ratio sweep on the same layers: 256 visual tokens pruned by 0.3 .. 0.6, plus 20 text tokens
     few = range(min(4, n))
@@ -326,6 +416,7 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
     pos_full = torch.arange(S, dtype=torch.int32, device=dev)
     kdense = torch.empty((S, H), dtype=torch.float16, device=dev)
     scores = torch.empty((1, nv), dtype=torch.float32, device=dev)
+    score_ws = torch.zeros((B.sqap_attn_scores_workspace_bytes(1, S, nh, hd, nv),), dtype=torch.uint8, device=dev)
     idx = torch.empty((1, keep), dtype=torch.int32, device=dev)
     rows = torch.empty((Mk,), dtype=torch.int32, device=dev)
 
@@ -336,7 +427,7 @@ def decoder_leg(torch, B, wl, dev, distinct_layers=8):
         decoder.layer_forward(layers[1 % distinct_layers], buf, xa, da, pos_full, 1, nh, hd, xb, db)
         # retention score of the last (text) token from this layer's rotated q and k, then the kept rows
         B.sqap_gather_rows(buf.qkv[:S, H:2 * H], pos_full, kdense)
-        B.sqap_attn_scores(buf.qkv[S - 1, :H], kdense.view(S, nh, hd), 0, nv, scores[0])
+        B.sqap_attn_scores(buf.qkv[S - 1, :H], kdense.view(S, nh, hd), 0, nv, scores[0], score_ws)
         B.sqap_prune_rows(scores, keep, S, 0, idx, rows)
         B.sqap_residual_add(xb, db)                       # the pending update lands before the gather
         src, pend, use_rows, pos = xb, None, rows, rows
@@ -504,6 +595,36 @@ def graph_time_us(torch, fn, iters, per_graph=10):
     return e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
 
 
+def prefill_variants(torch, B, wl, dev, wk, steps=60):
+    """The two prefill GEMMs timed again (HIP events around each launch, back-to-back steps, clocks settled
+    first) with cold weights and with other input data: the work is the same, the power draw and so the
+    clock are not."""
+    res = {}
+
+    def measure(w):
+        settle_clocks(torch, w, max_steps=150)
+        ms, per, st = time_gemm_launches(torch, w, steps)
+        return {"avg_launch_us": ms * 1e3, "median_us": st["median"], "min_us": st["min"],
+                "gate_up_us": per["gate_up"] * 1e3, "down_us": per["down"] * 1e3,
+                "TOPs": wk.ops / 2.0 / (ms * 1e-3) / 1e12, "sclk_mhz_under_load": sclk_under_load(torch, w, 100)}
+
+    wk.make_cold_weights(wl)
+    res["cold_weights"] = measure(wk)
+    res["cold_weights"]["note"] = "%d distinct weight pairs (%.2f GB) used in turn: every launch streams its weights " \
+                                  "from HBM" % (len(wk.cold), len(wk.cold) * wk.F * wk.H / 1e9)
+    for pair in wk.cold:
+        for w in pair:
+            w.free()
+    wk.cold = None
+    for variant in ("rotated", "outlier_free"):
+        w = Prefill(torch, B, wl, dev, variant)
+        res[variant] = measure(w)
+        w.free()
+        del w
+    res["note"] = "rotated: activations and weights rotated (Eq. 6) before quantization; outlier_free: N(0,1) inputs"
+    return res
+
+
 def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
     """Microseconds per call of the selection and quantization kernels at configuration 3's sizes
     (back-to-back launches on one stream, HIP events around the run)."""
@@ -518,9 +639,11 @@ def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
     qb = q.unsqueeze(0).repeat(nb, 1, 1).contiguous()
     kb = k.unsqueeze(0).repeat(nb, 1, 1, 1).contiguous()
     a_qb = torch.empty((nb, wl.N_VISUAL), dtype=torch.float32, device=dev)
+    ws_a = torch.zeros((B.sqap_attn_scores_workspace_bytes(nb, wl.SEQ_LEN, wl.N_HEADS, wl.HEAD_DIM, wl.N_VISUAL),),
+                       dtype=torch.uint8, device=dev)
     out = {
-        "attn_scores_S276_H32_d128": timed(lambda: B.sqap_attn_scores(q, k, 0, wl.N_VISUAL, a_q)),
-        "attn_scores_batch16_S276_H32_d128": timed(lambda: B.sqap_attn_scores_batch(qb, kb, 0, wl.N_VISUAL, a_qb)),
+        "attn_scores_S276_H32_d128": timed(lambda: B.sqap_attn_scores(q, k, 0, wl.N_VISUAL, a_q, ws_a)),
+        "attn_scores_batch16_S276_H32_d128": timed(lambda: B.sqap_attn_scores_batch(qb, kb, 0, wl.N_VISUAL, a_qb, ws_a)),
         "prune_rows_16x256_to_128": timed(lambda: B.sqap_prune_rows(wk.scores, wk.keep, wk.S, 0, wk.idx, wk.rows)),
         "gather_rows_2368x4096": timed(lambda: B.sqap_gather_rows(wk.X, wk.rows, gathered)),
         "quantize_act_2368x4096_fused_gather": timed(lambda: B.sqap_quantize_act(wk.X, wk.rows, wk.Xq, wk.sx)),
@@ -536,9 +659,23 @@ def small_kernel_leg(torch, B, wl, wk, dev, iters=50):
     return out
 
 
-def cpu_baseline(wl):
-    """The oracle, as it stands, on the same step (all 16 observations)."""
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(wl, timed_outputs=None, n_samples=4000):
+    """The oracle, as it stands, on the same step (all 16 observations), all host threads; the same on one
+    observation's share with one thread; and, when the GPU's outputs of the timed buffers are given
+    (Yg, Yd as numpy arrays copied back after the timed region), a comparison of sampled outputs with
+    what the oracle computes for them one by one (bit equality of the fp16 values)."""
     import ctypes
+    import numpy as np
     import oracle
     H, F, S, nv = wl.HIDDEN, wl.FFN, wl.SEQ_LEN, wl.N_VISUAL
     keep, batch = wl.CONFIGS[3]["keep_k"], wl.CONFIGS[3]["batch"]
@@ -558,9 +695,37 @@ def cpu_baseline(wl):
     dt = time.perf_counter() - t0
     ops = 2.0 * M * (F * H + H * F)
     threads = ctypes.CDLL("libgomp.so.1").omp_get_max_threads()
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
-            "seconds": dt, "sample": "one whole step of the same workload (16 observations, M=%d): "
-                                     "prune, rows, quantize, gate/up, quantize, down" % M}
+    out = {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
+           "seconds": dt, "cpu_model": cpu_model(),
+           "sample": "one whole step of the same workload (16 observations, M=%d): "
+                     "prune, rows, quantize, gate/up, quantize, down" % M}
+    # one thread, one observation's 148 kept rows (a sixteenth of the step)
+    m1 = keep + wl.N_TEXT
+    old = oracle.set_threads(1)
+    t0 = time.perf_counter()
+    i1 = oracle.prune_topk(scores[:1], keep)
+    r1 = oracle.kept_rows(i1, S, 0, nv)
+    q1, s1, _ = oracle.quantize_rows(X, rows=r1)
+    oracle.w4a4_linear(q1, s1, Wg, sg)
+    qd1, sd1, _ = oracle.quantize_rows(Xd[:m1])
+    oracle.w4a4_linear(qd1, sd1, Wd, sd)
+    dt1 = time.perf_counter() - t0
+    oracle.set_threads(old)
+    out["single_thread"] = {"value": 2.0 * m1 * (F * H + H * F) / dt1 / 1e12, "unit": "TOPS", "cores": 1,
+                            "seconds": dt1, "sample": "one observation of the step (M=%d)" % m1}
+    if timed_outputs is not None:
+        Yg, Yd = timed_outputs
+        rng = np.random.default_rng(12345)
+        bad = 0
+        for (Y, xq, s_x, wq, s_w) in ((Yg, Xq, sx, Wg, sg), (Yd, Xdq, sxd, Wd, sd)):
+            ms = rng.integers(0, Y.shape[0], n_samples).astype(np.int32)
+            ns = rng.integers(0, Y.shape[1], n_samples).astype(np.int32)
+            ms[:4], ns[:4] = [0, Y.shape[0] - 1, 0, Y.shape[0] - 1], [0, 0, Y.shape[1] - 1, Y.shape[1] - 1]
+            _, y_o = oracle.linear_samples(xq, s_x, wq, s_w, ms, ns)
+            bad += int(np.count_nonzero(Y[ms, ns].view(np.uint16) != y_o.view(np.uint16)))
+        out["parity_samples"] = 2 * n_samples
+        out["parity_mismatches"] = bad
+    return out
 
 
 def stored_traffic(kernel):
@@ -610,6 +775,8 @@ def main():
         torch.cuda.synchronize()
         return
 
+    B.sqap_init()
+    settled = settle_clocks(torch, wk)
     for _ in range(args.warmup):
         wk.step()
     torch.cuda.synchronize()
@@ -621,9 +788,12 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     tops = wk.ops / (dt / args.steps) / 1e12
 
-    gemm_ms, per_gemm = time_gemm_launches(torch, wk, args.steps)
+    gemm_ms, per_gemm, launch_stats = time_gemm_launches(torch, wk, args.steps)
     gemm_ops = wk.ops / 2.0                                  # each of the two launches: 2*M*N*K
     achieved = gemm_ops / (gemm_ms * 1e-3) / 1e12
+    ws_error = B.workspace_error(wk.ws)
+    timed_outputs = (wk.Yg.cpu().numpy(), wk.Yd.cpu().numpy())      # the buffers the timed region wrote
+    sclk = sclk_under_load(torch, wk)
 
     out = {
         "metric": "W4A4 linear TOPS (prefill, pruned tokens) + decode GB/s, fraction of peak",
@@ -636,10 +806,15 @@ def main():
                    "M": wk.M, "step": "prune_rows(top-k+kept rows)+quantize_act+linear+quantize_act+linear"},
         "roofline": {"bound": "mfma", "kernel": "gemm_streamk_kernel<Cfg<256,256,2,4>>", "achieved": achieved,
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / INT8_MFMA_PEAK_TOPS,
-                     "avg_launch_ms": gemm_ms, "per_gemm_ms": per_gemm,
+                     "avg_launch_ms": gemm_ms, "per_gemm_ms": per_gemm, "launch_us": launch_stats,
                      "algorithmic_ops_per_launch": gemm_ops,
-                     "traffic": stored_traffic("gemm_streamk_kernel")},
+                     "traffic": stored_traffic("gemm_streamk_kernel"),
+                     "sclk_mhz_under_load": sclk, "workspace_error_word": ws_error,
+                     "operands": "warm: one layer's weights (45 MB) reused by every step"},
+        "prewarm": settled,
     }
+    if not args.no_variants:
+        out["roofline"]["variants"] = prefill_variants(torch, B, wl, dev, wk)
     out["kernels_us"] = small_kernel_leg(torch, B, wl, wk, dev)
     del wk
     torch.cuda.empty_cache()
@@ -656,7 +831,8 @@ def main():
         out["decoder_forward"] = decoder_leg(torch, B, wl, dev)
     out["selection"] = selection_leg(torch, B, wl, dev)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl)
+        out["cpu_baseline"] = cpu_baseline(wl, timed_outputs)
+        out["parity_checked"] = out["cpu_baseline"].get("parity_mismatches") == 0 and ws_error == 0
     print(json.dumps(out))
 
 

@@ -57,6 +57,21 @@ const char *sqap_last_error(void);
 const char *sqap_version(void);
 
 /*
+ * One-time set-up of the current device: finds out how the hardware deals the
+ * workgroups of a launch to the XCDs, which decides whether sqap_w4a4_linear
+ * may use its persistent kernels there (see sqap_selftest_dispatch).  This is
+ * the one call of the library that SYNCHRONISES the stream (a probe launch
+ * and a read-back of 1 KiB); later calls on the same device return at once.
+ * A device that has not been set up is set up by the first sqap_weight_pack
+ * on it, which then synchronises its stream once in the same way; when that
+ * stream is being captured into a graph the set-up is put off and
+ * sqap_w4a4_linear uses its slower one-tile-per-workgroup kernels on the
+ * device until a later sqap_init or sqap_weight_pack has probed it.
+ * EDEVICE: a HIP call failed.
+ */
+sqap_status sqap_init(void *stream);
+
+/*
  * Retention score a_q (Strategy 1, text under Eq. 1; Section 3.3 defines the
  * Q and K it is computed from).  For a task-query token with per-head query
  * q[H,d] and the key cache k[S,H,d] (both half, row-major), computes for each
@@ -66,26 +81,40 @@ const char *sqap_version(void);
  * Arithmetic in binary32.  scores_out: n_vis floats.  All pointers are device
  * pointers owned by the caller.  The heads are added in head order, so the
  * result is the same bits on every call.
- * The kernel keeps per-head weights in a scratch array that belongs to the
- * device (no workspace argument): calls of this function and of
- * sqap_attn_scores_batch that overlap in time on one device (two streams, two
- * host threads) race; calls in one stream do not.
- * EINVAL: null pointer, S/H/d <= 0, span outside [0,S).  EUNSUPPORTED: d > 256,
- * d odd or S > 16384.
+ * workspace: device scratch of at least sqap_attn_scores_workspace_bytes(1, S, H,
+ * d, n_vis) bytes, 16-byte aligned (may be NULL when that is 0): one workgroup
+ * per head leaves the head's weights there and the workgroup that finishes last,
+ * told by a counter at the start of the workspace, adds them.  The first
+ * 256 * batch bytes (the counters) must be ZERO before the first call that uses
+ * a workspace; every call leaves them zero, so clearing once is enough.  The
+ * rest needs no initialisation.  Calls that share a workspace must be ordered
+ * on one stream; calls on different streams need a workspace each.
+ * EINVAL: null pointer, S/H/d <= 0, span outside [0,S), workspace missing, too
+ * small or misaligned.  EUNSUPPORTED: d > 256, d odd or S > 16384.
  */
 sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
                              int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
-                             void *stream);
+                             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * The same score for `batch` observations in one launch: q[batch,H,d],
  * k[batch,S,H,d], scores_out[batch,n_vis] (row-major, dense); observation b
  * gets exactly what sqap_attn_scores gives for q[b], k[b].  batch = 0 is a
- * no-op.  Errors as above; EINVAL for batch < 0, EUNSUPPORTED for batch > 4096.
+ * no-op.  workspace: sqap_attn_scores_workspace_bytes(batch, ...) bytes, as above.
+ * Errors as above; EINVAL for batch < 0, EUNSUPPORTED for batch > 4096.
  */
 sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S,
                                    int32_t H, int32_t d, int32_t vis_begin, int32_t n_vis,
-                                   float *scores_out, void *stream);
+                                   float *scores_out, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
+/*
+ * Bytes of workspace the two calls above need for this shape: 256 per observation
+ * for the counters plus 4 * batch * H * n_vis for the per-head weights; 0 for
+ * shapes that run in a single workgroup and need none (head size not a power of
+ * two in 8 .. 256, or S > 4096) and for empty shapes.
+ */
+size_t sqap_attn_scores_workspace_bytes(int32_t batch, int32_t S, int32_t H, int32_t d, int32_t n_vis);
 
 /*
  * Eq. 1: K_attn = Top_k(a_q, k).  For each of `batch` rows of `scores`
@@ -239,6 +268,8 @@ sqap_status sqap_quantize_weight_folded(const sqap_f16 *W, int32_t N, int32_t K,
  * library's streaming layout and returns a handle that owns a device copy
  * (allocated with hipMalloc on the current device).  The inputs may be freed
  * once the stream has run past this call.  K must be a multiple of 32.
+ * The first call on a device that sqap_init has not set up does that set-up
+ * and so synchronises the stream once (see sqap_init).
  * EINVAL: null pointer, N/K <= 0.  EUNSUPPORTED: K % 32 != 0.  ENOMEM.
  */
 sqap_status sqap_weight_pack(const uint8_t *Wq, const sqap_f16 *sw, int32_t N, int32_t K,
@@ -269,9 +300,12 @@ size_t sqap_workspace_bytes(int32_t M, int32_t N, int32_t K);
  * that share a workspace must be ordered on one stream.  The large- and mid-M
  * kernels are persistent (one workgroup per compute unit) and split tiles
  * between workgroups, which exchange partial sums through the workspace; a
- * wait that does not end within about a minute gives up and writes a nonzero
- * value to the 64-bit word at byte 4000 of the workspace (the result is then
- * wrong).  A launch may be captured in a HIP graph and replayed: every flag it
+ * wait that does not end within a few seconds (two million polls) gives up, and
+ * the result is then wrong.  Such a launch can be told from a good one whatever
+ * the workspace held before: the launch's first workgroup clears the 64-bit
+ * word at byte 4000 of the workspace when it starts and a wait that gives up
+ * writes a nonzero value there, so after the launch the word is zero or the
+ * output is wrong.  A launch may be captured in a HIP graph and replayed: every flag it
  * raises in the workspace is cleared again before it ends.  One entry point
  * serves prefill (large M) and decode (M <= 8); the kernel is chosen from M
  * inside.
@@ -387,15 +421,20 @@ sqap_status sqap_selftest_quotient(uint64_t *mismatches_out, void *stream);
  * pass partial sums between workgroups b and b' of one launch with
  * b % 8 == b' % 8 through ordinary stores, which requires both to run behind
  * the same L2 (workgroup b on XCD b % 8, or a device with one L2).  The library
- * checks this once per device, in the first sqap_weight_pack on it, and uses
+ * checks this once per device (sqap_init, or the first sqap_weight_pack), and uses
  * one-tile-per-workgroup kernels on a device where it does not hold.  This call
  * repeats the probe and writes the XCC id of each of the 256 workgroups of a
  * probe launch to xcc_of_block_out (HOST memory, 256 words); it synchronises
  * the stream.  Expected: out[b] == out[b % 8] for every b.  EINVAL: null.
  * Setting SQAP_DISABLE_PERSISTENT=1 in the environment selects the fallback
- * kernels on any device (read at every sqap_w4a4_linear call).
+ * kernels on any device (read once per process, at the first sqap_w4a4_linear
+ * call that could use a persistent kernel).  sqap_set_persistent_kernels is
+ * the same switch at run time, process wide, for tests and diagnosis: 0 selects
+ * the fallback kernels, anything else lets the library choose per device again
+ * (and overrides the environment variable).  Always SQAP_OK.
  */
 sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream);
+sqap_status sqap_set_persistent_kernels(int32_t enabled);
 
 /*
  * The work split of the stream-K linear (M > 8, K a multiple of 128), as a
@@ -433,7 +472,10 @@ sqap_status sqap_plan_linear_shares(int32_t M, int32_t N, int32_t K, int32_t blo
  * sqap_w4a4_linear computes.  Build the group once, run it every step.
  *
  * descs is a HOST array; the device pointers inside it are captured, not
- * copied, and must stay valid while the group is used.  Outputs of different
+ * copied, and must stay valid while the group is used.  That includes the
+ * packed weights: a group keeps the device addresses of each problem's
+ * sqap_weight, not a reference to the handle, so every weight must outlive
+ * (not be freed before) every group built from it.  Outputs of different
  * problems must not overlap.
  * EINVAL: null pointers, count <= 0, M < 1, ldy < N, bad weight handle.
  * EUNSUPPORTED: some M > 8 or some K not a multiple of 64.  ENOMEM / EDEVICE.
@@ -454,6 +496,18 @@ sqap_status sqap_group_create(const sqap_linear_desc *descs, int32_t count, sqap
 
 /* Enqueues the whole group on `stream` as one launch.  No host synchronisation. */
 sqap_status sqap_group_run(const sqap_group *g, void *stream);
+
+/*
+ * How sqap_group_run will launch a group (host arithmetic only; no GPU work): the number of problems and of
+ * row groups (32 output channels each) in it, and the form of the small-M kernel the launch takes on a
+ * device with `compute_units` compute units (0: the current device): wavefronts that share one row
+ * group along K (1, 2, 4 or 8), wavefronts per workgroup (8, or 16 for launches in which every wavefront
+ * streams four or more row groups: outputs then wait in LDS slots, output_slots_out per wavefront, 0
+ * otherwise).  Any out pointer may be NULL.  EINVAL: not a group handle, compute_units < 0.
+ */
+sqap_status sqap_group_info(const sqap_group *g, int32_t compute_units, int32_t *problems_out,
+                            int32_t *row_groups_out, int32_t *wavefronts_per_row_group_out,
+                            int32_t *wavefronts_per_workgroup_out, int32_t *output_slots_out);
 
 /* Frees a group (NULL allowed); the caller makes sure no launch still uses it. */
 sqap_status sqap_group_free(sqap_group *g);

@@ -23,7 +23,8 @@ EXPORTS = (
     "sqap_group_create", "sqap_group_run", "sqap_group_free", "sqap_selftest_quotient", "sqap_selftest_dispatch",
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
-    "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention",
+    "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention", "sqap_group_info", "sqap_init",
+    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes",
 )
 
 
@@ -56,8 +57,10 @@ def lib():
         L.sqap_last_error.argtypes = []
         L.sqap_version.restype = ctypes.c_char_p
         L.sqap_version.argtypes = []
-        L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp]
-        L.sqap_attn_scores_batch.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
+        L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sqap_attn_scores_batch.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sqap_attn_scores_workspace_bytes.restype = sz
+        L.sqap_attn_scores_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.sqap_prune_topk.argtypes = [vp, i32, i32, i32, vp, vp]
         L.sqap_kept_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_prune_rows.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
@@ -84,14 +87,17 @@ def lib():
         L.sqap_group_create.argtypes = [ctypes.POINTER(LinearDesc), i32, ctypes.POINTER(vp)]
         L.sqap_group_run.argtypes = [vp, vp]
         L.sqap_group_free.argtypes = [vp]
+        L.sqap_group_info.argtypes = [vp, i32] + [ctypes.POINTER(i32)] * 5
         L.sqap_selftest_quotient.argtypes = [vp, vp]
+        L.sqap_init.argtypes = [vp]
+        L.sqap_set_persistent_kernels.argtypes = [i32]
         L.sqap_selftest_dispatch.argtypes = [ctypes.POINTER(u32), vp]
         L.sqap_plan_linear_shares.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double),
                                                                       ctypes.POINTER(ctypes.c_double),
                                                                       ctypes.POINTER(ctypes.c_int32),
                                                                       ctypes.POINTER(ctypes.c_int32)]
         for name in EXPORTS:
-            if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes"):
+            if name not in ("sqap_last_error", "sqap_version", "sqap_workspace_bytes", "sqap_attn_scores_workspace_bytes"):
                 getattr(L, name).restype = ctypes.c_int32
         _lib = L
     return _lib
@@ -112,22 +118,47 @@ def _stream(stream):
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
+def sqap_init(stream=None):
+    """One-time set-up of the current device (synchronises the stream once)."""
+    _check(lib().sqap_init(_stream(stream)))
+
+
+def sqap_set_persistent_kernels(enabled):
+    _check(lib().sqap_set_persistent_kernels(1 if enabled else 0))
+
+
+def workspace_error(workspace):
+    """Error word a persistent sqap_w4a4_linear launch leaves in its workspace (0: every wait ended).
+    Synchronises: reads 8 bytes back from the device."""
+    if workspace is None or workspace.numel() * workspace.element_size() < 4008:
+        return 0
+    return int(workspace.view(torch.uint8)[4000:4008].view(torch.int64).item())
+
+
 def sqap_version():
     return lib().sqap_version().decode()
 
 
-def sqap_attn_scores(q, k, vis_begin, n_vis, scores_out, stream=None):
-    """q [H,d] fp16, k [S,H,d] fp16 -> scores_out [n_vis] fp32."""
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def sqap_attn_scores_workspace_bytes(batch, S, H, d, n_vis):
+    return int(lib().sqap_attn_scores_workspace_bytes(batch, S, H, d, n_vis))
+
+
+def sqap_attn_scores(q, k, vis_begin, n_vis, scores_out, workspace=None, stream=None):
+    """q [H,d] fp16, k [S,H,d] fp16 -> scores_out [n_vis] fp32.  workspace: device bytes, first 256 zeroed once."""
     S, H, d = k.shape
     _check(lib().sqap_attn_scores(_ptr(q), _ptr(k), S, H, d, vis_begin, n_vis, _ptr(scores_out),
-                                  _stream(stream)))
+                                  _ptr(workspace), _nbytes(workspace), _stream(stream)))
 
 
-def sqap_attn_scores_batch(q, k, vis_begin, n_vis, scores_out, stream=None):
+def sqap_attn_scores_batch(q, k, vis_begin, n_vis, scores_out, workspace=None, stream=None):
     """q [batch,H,d] fp16, k [batch,S,H,d] fp16 -> scores_out [batch,n_vis] fp32."""
     batch, S, H, d = k.shape
     _check(lib().sqap_attn_scores_batch(_ptr(q), _ptr(k), batch, S, H, d, vis_begin, n_vis, _ptr(scores_out),
-                                        _stream(stream)))
+                                        _ptr(workspace), _nbytes(workspace), _stream(stream)))
 
 
 def sqap_prune_topk(scores, keep_k, idx_out, stream=None):
@@ -318,6 +349,12 @@ class Group:
 
     def run(self, stream=None):
         _check(lib().sqap_group_run(self.handle, _stream(stream)))
+
+    def info(self, compute_units=0):
+        """(problems, row groups, wavefronts per row group, wavefronts per workgroup, LDS output slots) of the launch."""
+        v = [ctypes.c_int32(0) for _ in range(5)]
+        _check(lib().sqap_group_info(self.handle, compute_units, *[ctypes.byref(x) for x in v]))
+        return tuple(x.value for x in v)
 
     def free(self):
         if self.handle:

@@ -38,9 +38,17 @@ const char *sqap_last_error(void) { return g_error; }
 
 const char *sqap_version(void) { return "sqap-gfx950 0.1"; }
 
+// workspace the fast kernel of the retention score needs for this shape (0: the shape takes the
+// one-workgroup kernel, which needs none)
+static size_t attn_scores_need(int32_t batch, int32_t S, int32_t H, int32_t d, int32_t n_vis)
+{
+    if (batch <= 0 || S <= 0 || S > 4096 || H <= 0 || d < 8 || d > 256 || (d & (d - 1)) || n_vis <= 0) return 0;
+    return attn_scores_workspace_bytes(batch, H, n_vis);
+}
+
 static sqap_status attn_scores_checked(const char *who, const sqap_f16 *q, const sqap_f16 *k, int32_t batch,
                                        int32_t S, int32_t H, int32_t d, int32_t vis_begin, int32_t n_vis,
-                                       float *scores_out, void *stream)
+                                       float *scores_out, void *workspace, size_t workspace_bytes, void *stream)
 {
     if (batch < 0) return fail(SQAP_EINVAL, "%s: batch %d < 0", who, batch);
     if (S <= 0 || H <= 0 || d <= 0)
@@ -54,22 +62,37 @@ static sqap_status attn_scores_checked(const char *who, const sqap_f16 *q, const
     if (d > 256 || (d & 1)) return fail(SQAP_EUNSUPPORTED, "%s: d = %d (even, <= 256)", who, d);
     if (S > 16384) return fail(SQAP_EUNSUPPORTED, "%s: S = %d > 16384", who, S);
     if (batch > 4096) return fail(SQAP_EUNSUPPORTED, "%s: batch = %d > 4096", who, batch);
+    const size_t need = aligned16(q) && aligned16(k) ? attn_scores_need(batch, S, H, d, n_vis) : 0;
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need)
+            return fail(SQAP_EINVAL, "%s: workspace of %zu bytes needed, %zu given", who, need,
+                        workspace ? workspace_bytes : (size_t)0);
+        if (!aligned16(workspace)) return fail(SQAP_EINVAL, "%s: workspace must be 16-byte aligned", who);
+    }
     return launch_attn_scores(reinterpret_cast<const __half *>(q), reinterpret_cast<const __half *>(k), batch, S, H,
-                              d, vis_begin, n_vis, scores_out, as_stream(stream));
+                              d, vis_begin, n_vis, scores_out, need > 0 ? workspace : nullptr, workspace_bytes,
+                              as_stream(stream));
+}
+
+size_t sqap_attn_scores_workspace_bytes(int32_t batch, int32_t S, int32_t H, int32_t d, int32_t n_vis)
+{
+    return attn_scores_need(batch, S, H, d, n_vis);
 }
 
 sqap_status sqap_attn_scores(const sqap_f16 *q, const sqap_f16 *k, int32_t S, int32_t H,
                              int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
-                             void *stream)
+                             void *workspace, size_t workspace_bytes, void *stream)
 {
-    return attn_scores_checked("sqap_attn_scores", q, k, 1, S, H, d, vis_begin, n_vis, scores_out, stream);
+    return attn_scores_checked("sqap_attn_scores", q, k, 1, S, H, d, vis_begin, n_vis, scores_out, workspace,
+                               workspace_bytes, stream);
 }
 
 sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S, int32_t H,
                                    int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out,
-                                   void *stream)
+                                   void *workspace, size_t workspace_bytes, void *stream)
 {
-    return attn_scores_checked("sqap_attn_scores_batch", q, k, batch, S, H, d, vis_begin, n_vis, scores_out, stream);
+    return attn_scores_checked("sqap_attn_scores_batch", q, k, batch, S, H, d, vis_begin, n_vis, scores_out, workspace,
+                               workspace_bytes, stream);
 }
 
 sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens,
@@ -473,6 +496,19 @@ sqap_status sqap_weight_info(const sqap_weight *w, int32_t *N, int32_t *K, size_
     return SQAP_OK;
 }
 
+sqap_status sqap_init(void *stream)
+{
+    int dev = 0;
+    SQAP_HIP_CHECK(hipGetDevice(&dev));
+    return probe_dispatch(dev, as_stream(stream), nullptr);
+}
+
+sqap_status sqap_set_persistent_kernels(int32_t enabled)
+{
+    set_persistent_kernels(enabled);
+    return SQAP_OK;
+}
+
 sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream)
 {
     if (!xcc_of_block_out) return fail(SQAP_EINVAL, "sqap_selftest_dispatch: null pointer");
@@ -625,6 +661,23 @@ sqap_status sqap_group_run(const sqap_group *g, void *stream)
     a.total_items = gg->total_items;
     a.total_cost = gg->total_cost;
     return launch_skinny(a, gg->max_chunks, as_stream(stream));
+}
+
+sqap_status sqap_group_info(const sqap_group *g, int32_t compute_units, int32_t *problems_out, int32_t *row_groups_out,
+                            int32_t *wavefronts_per_row_group_out, int32_t *wavefronts_per_workgroup_out,
+                            int32_t *output_slots_out)
+{
+    const Group *gg = reinterpret_cast<const Group *>(g);
+    if (!gg || gg->magic != kGroupMagic) return fail(SQAP_EINVAL, "sqap_group_info: not a group handle");
+    if (compute_units < 0) return fail(SQAP_EINVAL, "sqap_group_info: compute_units = %d", compute_units);
+    int S, W, cap;
+    skinny_plan(gg->total_items, gg->max_chunks, compute_units > 0 ? compute_units : device_cu_count(), &S, &W, &cap);
+    if (problems_out) *problems_out = gg->count;
+    if (row_groups_out) *row_groups_out = gg->total_items;
+    if (wavefronts_per_row_group_out) *wavefronts_per_row_group_out = S;
+    if (wavefronts_per_workgroup_out) *wavefronts_per_workgroup_out = W;
+    if (output_slots_out) *output_slots_out = cap;
+    return SQAP_OK;
 }
 
 sqap_status sqap_group_free(sqap_group *g)

@@ -104,7 +104,9 @@ static inline int device_cu_count()
 
 // kernel launchers (defined in the .hip files); all validation is done by the caller
 sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int S, int H, int d,
-                               int vis_begin, int n_vis, float *scores, hipStream_t st);
+                               int vis_begin, int n_vis, float *scores, void *workspace, size_t workspace_bytes,
+                               hipStream_t st);
+size_t attn_scores_workspace_bytes(int batch, int H, int n_vis);
 sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
                               hipStream_t st);
 sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,
@@ -157,8 +159,10 @@ sqap_status launch_quotient_selftest(unsigned long long *mismatches, hipStream_t
 // Checks once per device how a launch's workgroups are dealt to the XCDs (see gemm.hip); table_out
 // (host, 256 words, nullable) receives the XCC id of every workgroup and forces a fresh probe.
 sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out);
+void set_persistent_kernels(int enabled);
 sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
                                double *even_out, int *tile_rows_out, int *tile_cols_out);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
+void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *out_cap);
 
 }  // namespace sqap

@@ -42,7 +42,7 @@ constexpr int kErrWord = 500;
 constexpr int kArriveWord = 512;
 constexpr int kDepartWord = 1024;
 constexpr int kStreamKMinM = 512;           // from this M on the persistent kernel is used
-constexpr long long kSpinLimit = 200000000; // bounded wait (about a minute of polling)
+constexpr long long kSpinLimit = 2000000;   // bounded wait: a poll is a short sleep plus one L2 round trip, about 2 us, so a few seconds
 
 // Shares of the stream-K kernel: workgroup j of XCD x runs main-loop steps [bounds[x][j], bounds[x][j + 1]) of
 // that XCD's tiles (numbered tile after tile).  Passed by value as a kernel argument.
@@ -68,6 +68,20 @@ struct GemmParams {
     uint8_t *partials;     // one BM x BN int32 slot per workgroup
     int blocks_per_xcd;
 };
+
+// Error word of the workspace header.  The first workgroup of a persistent launch clears it when it starts and a
+// wait that gives up writes the launch's (nonzero) epoch, both as agent-scope stores (written through to
+// memory, so the later store is the one that stays whichever XCD issued it): after a launch the word is
+// zero, or that launch gave up a wait and its output is wrong, whatever the workspace held before.
+__device__ __forceinline__ void clear_error_word(const GemmParams &p)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        __hip_atomic_store(&p.flags[kErrWord], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void raise_error_word(const GemmParams &p)
+{
+    __hip_atomic_store(&p.flags[kErrWord], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 __device__ __forceinline__ void widen(const v4i p, v4i &lo, v4i &hi)
 {
@@ -598,6 +612,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
     // This workgroup's share [begin, end) of the XCD's main-loop steps (tile after tile, `steps` each):
     // the host planned it (see plan_shares).
     const int begin = (int)sched.bounds[xcd][j], end = (int)sched.bounds[xcd][j + 1];
+    clear_error_word(p);
     if (begin >= end) return;
     const int mtl = p.m_tiles;
     const int t_first = begin / steps, t_last = (end - 1) / steps;
@@ -682,7 +697,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_streamk_kernel(const GemmP
                     while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
                         __builtin_amdgcn_s_sleep(8);
                         if (++spins > kSpinLimit) {
-                            p.flags[kErrWord] = p.epoch;      // give up: the result of this tile is wrong
+                            raise_error_word(p);      // give up: the result of this tile is wrong
                             break;
                         }
                     }
@@ -773,6 +788,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
     // 64-bit divisions cost about a microsecond at the start of a launch that takes fifteen)
     const int total = ntile * steps;
     const int begin = total * j / nb, end = total * (j + 1) / nb;
+    clear_error_word(p);
     if (begin >= end) return;
     const int t_first = begin / steps, t_last = (end - 1) / steps;
     const int my_off = wave * (TILES * 4096) + lane * 16;
@@ -860,7 +876,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
             while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
                 __builtin_amdgcn_s_sleep(8);
                 if (++spins > kSpinLimit) {
-                    p.flags[kErrWord] = p.epoch;          // give up: the result of this tile is wrong
+                    raise_error_word(p);          // give up: the result of this tile is wrong
                     break;
                 }
             }
@@ -970,7 +986,7 @@ __global__ __launch_bounds__(C::THREADS, 1) void gemm_splitk_kernel(const GemmPa
             while (__hip_atomic_load(d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != p.epoch) {
                 __builtin_amdgcn_s_sleep(8);
                 if (++spins > kSpinLimit) {
-                    p.flags[kErrWord] = p.epoch;
+                    raise_error_word(p);
                     break;
                 }
             }
@@ -1019,6 +1035,13 @@ sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out)
 {
     if (device < 0 || device >= kMaxDevices) return fail(SQAP_EUNSUPPORTED, "device ordinal %d above %d", device, kMaxDevices - 1);
     if (g_dealing[device].load() != 0 && !table_out) return SQAP_OK;
+    // The probe synchronises the stream, which a capturing stream does not allow: leave the device unprobed
+    // (the one-tile-per-workgroup kernels are used until a later call probes it).
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+        if (table_out) return fail(SQAP_EUNSUPPORTED, "dispatch probe: the stream is capturing");
+        return SQAP_OK;
+    }
     unsigned int host[kMaxPersistentBlocks];
     hipLaunchKernelGGL(xcc_probe_kernel, dim3(kMaxPersistentBlocks), dim3(512), 0, st);
     SQAP_HIP_CHECK(hipGetLastError());
@@ -1032,11 +1055,19 @@ sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out)
     return SQAP_OK;
 }
 
+static std::atomic<int> g_persistent_switch{-1};      // -1: follow the environment, 0: off, 1: on
+
+void set_persistent_kernels(int enabled) { g_persistent_switch.store(enabled ? 1 : 0); }
+
 static bool persistent_allowed()
 {
-    // SQAP_DISABLE_PERSISTENT=1 in the environment selects the fallback kernels (read at every call)
-    const char *off = getenv("SQAP_DISABLE_PERSISTENT");
-    if (off && off[0] == '1') return false;
+    // SQAP_DISABLE_PERSISTENT=1 in the environment selects the fallback kernels; read once per process
+    static const bool disabled = [] {
+        const char *off = getenv("SQAP_DISABLE_PERSISTENT");
+        return off && off[0] == '1';
+    }();
+    const int sw = g_persistent_switch.load(std::memory_order_relaxed);
+    if (sw == 0 || (sw < 0 && disabled)) return false;
     int dev = 0;
     return hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices && g_dealing[dev].load() == 1;
 }

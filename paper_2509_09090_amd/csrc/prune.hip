@@ -586,17 +586,16 @@ __global__ __launch_bounds__(64 * kScoreWaves) void attn_scores_kernel(
 // Fast path of the retention score: one workgroup per head.  A group of d/8 lanes reads one
 // key row piece (16 bytes per lane: a coalesced run of 2d bytes), the logits of the head go to
 // LDS, the workgroup takes their maximum and the sum of exponentials, and writes the head's
-// softmax weights of the visual span to a device-resident scratch array.  The workgroup that
-// finishes last (a device counter tells) adds the heads in head order, so the result does not
-// depend on the order in which the workgroups ran.  The scratch array and the counter belong to
-// the device: calls that overlap on one device race.
+// softmax weights of the visual span to the workspace.  The workgroup that finishes last (a
+// counter in the workspace tells) adds the heads in head order, so the result does not depend on
+// the order in which the workgroups ran, and puts the counter back to zero.
 // A batch of observations runs as one launch (grid: heads x observations); each observation has
-// its own counter and its own piece of the scratch array.
-constexpr int kScoreMaxHeads = 128, kScoreMaxSpan = 4096, kScoreMaxSeq = 4096, kScoreMaxBatch = 1024;
-constexpr size_t kScoreScratchFloats = (size_t)kScoreMaxHeads * kScoreMaxSpan;
-__device__ float g_head_weights[kScoreScratchFloats];
-constexpr int kCounterStride = 64;                // one 256-byte line per counter: atomics on one line serialise
-__device__ unsigned int g_heads_done[kScoreMaxBatch * kCounterStride];
+// its own counter and its own piece of the weight array.
+// Workspace: [batch counters, one 256-byte line each (atomics on one line serialise)]
+//            [batch * H * n_vis floats].
+constexpr int kScoreMaxSeq = 4096;                // logits of one head sit in LDS
+constexpr int kCounterStride = 64;                // 32-bit words per counter line
+static size_t score_counter_bytes(int batch) { return (size_t)batch * kCounterStride * sizeof(unsigned int); }
 
 __device__ __forceinline__ float block_reduce_256(float v, bool take_max, float *scratch4)
 {
@@ -614,7 +613,8 @@ __device__ __forceinline__ float block_reduce_256(float v, bool take_max, float 
 
 __global__ __launch_bounds__(256) void attn_head_kernel(const __half *__restrict__ q, const __half *__restrict__ k,
                                                         int S, int H, int d, int vis_begin, int n_vis,
-                                                        float *__restrict__ scores)
+                                                        float *__restrict__ scores, unsigned int *heads_done,
+                                                        float *all_head_weights)
 {
     __shared__ float logits[kScoreMaxSeq];
     __shared__ float red[4];
@@ -623,7 +623,7 @@ __global__ __launch_bounds__(256) void attn_head_kernel(const __half *__restrict
     q += (size_t)b * H * d;
     k += (size_t)b * S * H * d;
     scores += (size_t)b * n_vis;
-    float *head_weights = g_head_weights + (size_t)b * H * n_vis;
+    float *head_weights = all_head_weights + (size_t)b * H * n_vis;
     const int lp = d >> 3;                        // lanes per key row: a power of two, 1 .. 32
     const int sub = t & (lp - 1), grp = t / lp, groups = 256 / lp;
     float qf[8];
@@ -679,11 +679,11 @@ __global__ __launch_bounds__(256) void attn_head_kernel(const __half *__restrict
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (t == 0) {
-        const unsigned done = __hip_atomic_fetch_add(&g_heads_done[b * kCounterStride], 1u, __ATOMIC_RELAXED,
+        const unsigned done = __hip_atomic_fetch_add(&heads_done[b * kCounterStride], 1u, __ATOMIC_RELAXED,
                                                      __HIP_MEMORY_SCOPE_AGENT);
         is_last = done + 1 == (unsigned)H;
         if (is_last)                              // ready for the next call
-            __hip_atomic_store(&g_heads_done[b * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&heads_done[b * kCounterStride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (is_last) {
@@ -698,15 +698,30 @@ __global__ __launch_bounds__(256) void attn_head_kernel(const __half *__restrict
     }
 }
 
-sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int S, int H, int d,
-                               int vis_begin, int n_vis, float *scores, hipStream_t st)
+// The fast path needs a power-of-two head size of 8 .. 256, 16-byte aligned operands and a sequence
+// whose logits fit LDS; everything else takes the one-workgroup kernel, which needs no workspace.
+static bool score_fast_path(const void *q, const void *k, int S, int d)
 {
     const bool pow2 = (d & (d - 1)) == 0;
     const bool aligned = ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k)) & 15u) == 0;
-    const bool fits = H <= kScoreMaxHeads && n_vis <= kScoreMaxSpan && S <= kScoreMaxSeq && batch <= kScoreMaxBatch &&
-                      (size_t)batch * H * n_vis <= kScoreScratchFloats;
-    if (pow2 && d >= 8 && d <= 256 && aligned && fits) {
-        hipLaunchKernelGGL(attn_head_kernel, dim3(H, batch), dim3(256), 0, st, q, k, S, H, d, vis_begin, n_vis, scores);
+    return pow2 && d >= 8 && d <= 256 && aligned && S <= kScoreMaxSeq;
+}
+
+size_t attn_scores_workspace_bytes(int batch, int H, int n_vis)
+{
+    if (batch <= 0 || H <= 0 || n_vis <= 0) return 0;
+    return score_counter_bytes(batch) + (size_t)batch * H * n_vis * sizeof(float);
+}
+
+sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int S, int H, int d,
+                               int vis_begin, int n_vis, float *scores, void *workspace, size_t workspace_bytes,
+                               hipStream_t st)
+{
+    if (score_fast_path(q, k, S, d) && workspace && workspace_bytes >= attn_scores_workspace_bytes(batch, H, n_vis)) {
+        unsigned int *counters = reinterpret_cast<unsigned int *>(workspace);
+        float *weights = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(workspace) + score_counter_bytes(batch));
+        hipLaunchKernelGGL(attn_head_kernel, dim3(H, batch), dim3(256), 0, st, q, k, S, H, d, vis_begin, n_vis, scores,
+                           counters, weights);
     } else {
         for (int b = 0; b < batch; ++b)
             hipLaunchKernelGGL(attn_scores_kernel, dim3(1), dim3(64 * kScoreWaves), n_vis * sizeof(float), st,

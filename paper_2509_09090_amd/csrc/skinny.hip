@@ -427,6 +427,30 @@ static sqap_status launch_skinny_s(SkinnyArgs &a, size_t lds, int grid_cap, hipS
     return SQAP_OK;
 }
 
+// Which form of the kernel a launch of total_items row groups (longest row: max_chunks pieces) takes on a
+// device with `cus` compute units: S wavefronts per row group, W wavefronts per workgroup, out_cap LDS
+// output slots per wavefront (0: outputs are stored at once).  Host arithmetic only.
+void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *out_cap)
+{
+    // Launches in which every wavefront streams several items (a whole model's linears in one group): one
+    // workgroup of 16 wavefronts per CU, whose outputs wait in LDS until the wavefront has streamed its
+    // last weight (see the kernel).  532 -> 527 us at M = 1 and 577 -> 541 us at M = 8 for the 225 linears of
+    // the 7B shape.  Shorter launches are bound by start-up and by how many CUs pull weights, not by the
+    // stores, and ran 15-30 % slower in this form: they keep two workgroups of 8 per CU and store at once.
+    const int cap = skinny_out_cap(skinny_base_lds_bytes(max_chunks, kSkinnyWavesBig));
+    if ((long long)total_items >= 4ll * cus * kSkinnyWavesBig && cap >= 4) {
+        *S = 1;
+        *W = kSkinnyWavesBig;
+        *out_cap = cap;
+        return;
+    }
+    // aim at about 4096 wavefronts: share an item between S of them when items are few
+    const long long waves = 2ll * cus * kSkinnyWaves;
+    *W = kSkinnyWaves;
+    *out_cap = 0;
+    *S = total_items * 8ll <= waves ? 8 : total_items * 4ll <= waves ? 4 : total_items * 2ll <= waves ? 2 : 1;
+}
+
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st)
 {
     const size_t lds = skinny_lds_bytes(max_chunks);
@@ -436,24 +460,18 @@ sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st
     a.xs_bytes = (max_chunks / 2) * 256;
     a.out_off = 0;
     a.out_cap = 0;
-    // Launches in which every wavefront streams several items (a whole model's linears in one group): one
-    // workgroup of 16 wavefronts per CU, whose outputs wait in LDS until the wavefront has streamed its
-    // last weight (see the kernel).  532 -> 527 us at M = 1 and 577 -> 541 us at M = 8 for the 225 linears of
-    // the 7B shape.  Shorter launches are bound by start-up and by how many CUs pull weights, not by the
-    // stores, and ran 15-30 % slower in this form: they keep two workgroups of 8 per CU and store at once.
-    const size_t big_base = skinny_base_lds_bytes(max_chunks, kSkinnyWavesBig);
-    const int cap = skinny_out_cap(big_base);
-    if ((long long)a.total_items >= 4ll * cus * kSkinnyWavesBig && cap >= 4) {
+    int S, W, cap;
+    skinny_plan(a.total_items, max_chunks, cus, &S, &W, &cap);
+    if (W == kSkinnyWavesBig) {
+        const size_t big_base = skinny_base_lds_bytes(max_chunks, kSkinnyWavesBig);
         a.out_off = (int)big_base;
         a.out_cap = cap;
         return launch_skinny_s<1, kSkinnyWavesBig>(a, big_base + (size_t)cap * kSkinnyWavesBig * kSkinnyOutSlot, cus, st);
     }
     const int grid_cap = 2 * cus;
-    // aim at about 4096 wavefronts: share an item between S of them when items are few
-    const int waves = grid_cap * kSkinnyWaves;
-    if (a.total_items * 8 <= waves) return launch_skinny_s<8, kSkinnyWaves>(a, lds, grid_cap, st);
-    if (a.total_items * 4 <= waves) return launch_skinny_s<4, kSkinnyWaves>(a, lds, grid_cap, st);
-    if (a.total_items * 2 <= waves) return launch_skinny_s<2, kSkinnyWaves>(a, lds, grid_cap, st);
+    if (S == 8) return launch_skinny_s<8, kSkinnyWaves>(a, lds, grid_cap, st);
+    if (S == 4) return launch_skinny_s<4, kSkinnyWaves>(a, lds, grid_cap, st);
+    if (S == 2) return launch_skinny_s<2, kSkinnyWaves>(a, lds, grid_cap, st);
     return launch_skinny_s<1, kSkinnyWaves>(a, lds, grid_cap, st);
 }
 

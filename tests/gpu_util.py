@@ -74,3 +74,9 @@ def assert_fp16_close(got, ref):
     r = ref.astype(np.float64)
     assert np.all(np.abs(g - r) <= 1e-2 + 1e-3 * np.abs(r)), float(np.abs(g - r).max())
     return int(np.count_nonzero(got.view(np.uint16) != ref.view(np.uint16)))
+
+
+def score_workspace(batch, S, H, d, n_vis):
+    """Zeroed workspace for sqap_attn_scores / sqap_attn_scores_batch (None when the shape needs none)."""
+    n = B.sqap_attn_scores_workspace_bytes(batch, S, H, d, n_vis)
+    return torch.zeros((n,), dtype=torch.uint8, device=DEV) if n else None

@@ -102,15 +102,27 @@ def test_weight_and_linear_validation():
 def test_attn_scores_validation():
     L = B.lib()
     p = ctypes.c_void_p(4096)
-    assert L.sqap_attn_scores(p, p, 0, 1, 8, 0, 0, p, None) == B.EINVAL
-    assert L.sqap_attn_scores(p, p, 10, 2, 8, 5, 6, p, None) == B.EINVAL
-    assert L.sqap_attn_scores(p, p, 10, 2, 512, 0, 4, p, None) == B.EUNSUPPORTED
-    assert L.sqap_attn_scores(p, p, 10, 2, 8, 0, 0, None, None) == B.OK
-    assert L.sqap_attn_scores_batch(p, p, -1, 10, 2, 8, 0, 4, p, None) == B.EINVAL
-    assert L.sqap_attn_scores_batch(None, None, 0, 10, 2, 8, 0, 4, None, None) == B.OK
-    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 8, 8, 4, p, None) == B.EINVAL
-    assert L.sqap_attn_scores_batch(p, p, 5000, 10, 2, 8, 0, 4, p, None) == B.EUNSUPPORTED
-    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 7, 0, 4, p, None) == B.EUNSUPPORTED
+    big = 1 << 30
+    assert L.sqap_attn_scores(p, p, 0, 1, 8, 0, 0, p, p, big, None) == B.EINVAL
+    assert L.sqap_attn_scores(p, p, 10, 2, 8, 5, 6, p, p, big, None) == B.EINVAL
+    assert L.sqap_attn_scores(p, p, 10, 2, 512, 0, 4, p, p, big, None) == B.EUNSUPPORTED
+    assert L.sqap_attn_scores(p, p, 10, 2, 8, 0, 0, None, None, 0, None) == B.OK
+    assert L.sqap_attn_scores_batch(p, p, -1, 10, 2, 8, 0, 4, p, p, big, None) == B.EINVAL
+    assert L.sqap_attn_scores_batch(None, None, 0, 10, 2, 8, 0, 4, None, None, 0, None) == B.OK
+    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 8, 8, 4, p, p, big, None) == B.EINVAL
+    assert L.sqap_attn_scores_batch(p, p, 5000, 10, 2, 8, 0, 4, p, p, big, None) == B.EUNSUPPORTED
+    assert L.sqap_attn_scores_batch(p, p, 3, 10, 2, 7, 0, 4, p, p, big, None) == B.EUNSUPPORTED
+    # the workspace: 256 bytes of counters per observation + the per-head weights; none for single-workgroup shapes
+    assert B.sqap_attn_scores_workspace_bytes(1, 276, 32, 128, 256) == 256 + 4 * 32 * 256
+    assert B.sqap_attn_scores_workspace_bytes(16, 276, 32, 128, 256) == 16 * (256 + 4 * 32 * 256)
+    assert B.sqap_attn_scores_workspace_bytes(1, 100, 3, 24, 60) == 0          # head size not a power of two
+    assert B.sqap_attn_scores_workspace_bytes(1, 5000, 2, 32, 4000) == 0       # logits do not fit LDS
+    assert B.sqap_attn_scores_workspace_bytes(0, 276, 32, 128, 256) == 0
+    need = B.sqap_attn_scores_workspace_bytes(1, 276, 32, 128, 256)
+    assert L.sqap_attn_scores(p, p, 276, 32, 128, 0, 256, p, None, 0, None) == B.EINVAL        # missing
+    assert b"workspace" in L.sqap_last_error()
+    assert L.sqap_attn_scores(p, p, 276, 32, 128, 0, 256, p, p, need - 1, None) == B.EINVAL    # too small
+    assert L.sqap_attn_scores(p, p, 276, 32, 128, 0, 256, p, ctypes.c_void_p(4104), need, None) == B.EINVAL   # misaligned
 
 
 def test_glue_validation():
@@ -154,6 +166,21 @@ def test_glue_validation():
     assert L.sqap_decode_attention(*args(H=128, d=128, ldkv=32768, Xq=p, sx=p, counter=p)) == B.EUNSUPPORTED
     assert L.sqap_residual_add(p, 64, p, 32, 2, 64, None) == B.EINVAL
     assert L.sqap_residual_add(p, 68, p, 68, 2, 68, None) == B.EUNSUPPORTED
+
+
+def test_group_info_validation():
+    L = B.lib()
+    v = ctypes.c_int32(0)
+    assert L.sqap_group_info(None, 0, ctypes.byref(v), None, None, None, None) == B.EINVAL
+    junk = (ctypes.c_uint8 * 64)()
+    assert L.sqap_group_info(ctypes.cast(junk, ctypes.c_void_p), 256, None, None, None, None, None) == B.EINVAL
+    assert b"group" in L.sqap_last_error()
+
+
+def test_persistent_switch_is_host_only():
+    L = B.lib()
+    assert L.sqap_set_persistent_kernels(0) == B.OK
+    assert L.sqap_set_persistent_kernels(1) == B.OK
 
 
 def test_selftest_dispatch_validation():

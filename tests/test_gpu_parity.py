@@ -326,16 +326,19 @@ def test_dispatch_order_selftest(G):
 
 
 @pytest.mark.parametrize("M,N,K", [(600, 768, 1024), (148, 1024, 2048), (84, 512, 1024)])
-def test_linear_fallback_kernels(G, oracle, M, N, K, monkeypatch):
+def test_linear_fallback_kernels(G, oracle, M, N, K):
     """With the persistent kernels switched off the one-tile-per-workgroup kernels give the same bits."""
     rng = np.random.default_rng(M + N + K)
     Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
     sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
     sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
     Y1, acc1 = G.gpu_linear(Xq, sx, Wq, sw)
-    monkeypatch.setenv("SQAP_DISABLE_PERSISTENT", "1")
-    Y2, acc2 = G.gpu_linear(Xq, sx, Wq, sw)
-    monkeypatch.delenv("SQAP_DISABLE_PERSISTENT")
+    from paper_2509_09090_amd import binding as B
+    B.sqap_set_persistent_kernels(False)
+    try:
+        Y2, acc2 = G.gpu_linear(Xq, sx, Wq, sw)
+    finally:
+        B.sqap_set_persistent_kernels(True)
     _, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
     assert np.array_equal(acc1, acco) and np.array_equal(acc2, acco)
     assert np.array_equal(Y1.view(np.uint16), Y2.view(np.uint16))
@@ -378,20 +381,44 @@ def test_config0_end_to_end(G, oracle):
 def test_attn_scores(G, oracle):
     import torch
     from paper_2509_09090_amd import binding as B
-    # the last three take the general kernel: head size not a power of two, a long sequence, many heads
+    # (100, 3, 24) and (5000, 2, 32) take the general kernel: head size not a power of two, a long sequence
     for (S, H, d, v0, nv) in [(276, 32, 128, 0, 256), (37, 4, 16, 3, 20), (1000, 5, 64, 10, 990), (300, 128, 8, 1, 299),
                               (4096, 2, 256, 0, 4096), (100, 3, 24, 5, 60), (5000, 2, 32, 100, 4000), (50, 130, 16, 0, 50)]:
         q, k = wl.query_and_keys(S, H, d, wl.rng_for(95, S, wl.T_Q))
         qd, kd = G.to_dev(q), G.to_dev(k)
         out = torch.zeros(nv, dtype=torch.float32, device="cuda")
-        B.sqap_attn_scores(qd, kd, v0, nv, out)
+        ws = G.score_workspace(1, S, H, d, nv)
+        B.sqap_attn_scores(qd, kd, v0, nv, out, ws)
         torch.cuda.synchronize()
         ref = oracle.attn_scores(q, k, v0, nv)
         assert np.allclose(out.cpu().numpy(), ref, rtol=2e-4, atol=1e-7), (S, H, d)
-        again = torch.zeros(nv, dtype=torch.float32, device="cuda")      # same bits on every call
-        B.sqap_attn_scores(qd, kd, v0, nv, again)
+        again = torch.zeros(nv, dtype=torch.float32, device="cuda")      # same bits on every call, same workspace
+        B.sqap_attn_scores(qd, kd, v0, nv, again, ws)
         torch.cuda.synchronize()
         assert torch.equal(out, again), (S, H, d)
+        if ws is not None:
+            assert int(ws[:256].view(torch.int32).abs().sum()) == 0     # the counter is back at zero
+
+
+def test_attn_scores_on_two_streams(G, oracle):
+    """Calls that overlap on two streams do not disturb each other when each has its own workspace."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    S, H, d, v0, nv = 276, 32, 128, 0, 256
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority
+    data = []
+    for i in range(2):
+        q, k = wl.query_and_keys(S, H, d, wl.rng_for(97, S, wl.T_Q, i))
+        data.append((q, k, G.to_dev(q), G.to_dev(k), torch.zeros(nv, dtype=torch.float32, device="cuda"),
+                     G.score_workspace(1, S, H, d, nv)))
+    torch.cuda.synchronize()
+    for rep in range(20):
+        for i in range(2):
+            q, k, qd, kd, out, ws = data[i]
+            B.sqap_attn_scores(qd, kd, v0, nv, out, ws, stream=streams[i].cuda_stream)
+    torch.cuda.synchronize()
+    for q, k, qd, kd, out, ws in data:
+        assert np.allclose(out.cpu().numpy(), oracle.attn_scores(q, k, v0, nv), rtol=2e-4, atol=1e-7)
 
 
 @pytest.mark.gpu
@@ -399,7 +426,7 @@ def test_attn_scores_batch(G, oracle):
     """One launch for a batch of observations gives each what the single call gives, and the oracle's values."""
     import torch
     from paper_2509_09090_amd import binding as B
-    # (batch, S, H, d, vis_begin, n_vis); the third does not fit the device scratch and takes the general kernel
+    # (batch, S, H, d, vis_begin, n_vis)
     for (nb, S, H, d, v0, nv) in [(16, 276, 32, 128, 0, 256), (3, 61, 5, 32, 7, 40), (5, 4096, 32, 16, 0, 4096)]:
         qs, ks = [], []
         for b in range(nb):
@@ -408,13 +435,14 @@ def test_attn_scores_batch(G, oracle):
             ks.append(k)
         qd, kd = G.to_dev(np.stack(qs)), G.to_dev(np.stack(ks))
         out = torch.zeros(nb, nv, dtype=torch.float32, device="cuda")
-        B.sqap_attn_scores_batch(qd, kd, v0, nv, out)
+        ws = G.score_workspace(nb, S, H, d, nv)
+        B.sqap_attn_scores_batch(qd, kd, v0, nv, out, ws)
         torch.cuda.synchronize()
         one = torch.zeros(nv, dtype=torch.float32, device="cuda")
         for b in ([0, nb - 1] if S > 1000 else range(nb)):
             ref = oracle.attn_scores(qs[b], ks[b], v0, nv)
             assert np.allclose(out[b].cpu().numpy(), ref, rtol=2e-4, atol=1e-7), (nb, S, H, d, b)
-            B.sqap_attn_scores(qd[b], kd[b], v0, nv, one)
+            B.sqap_attn_scores(qd[b], kd[b], v0, nv, one, ws)
             torch.cuda.synchronize()
             assert np.allclose(out[b].cpu().numpy(), one.cpu().numpy(), rtol=1e-6, atol=1e-9), (nb, S, H, d, b)
 
