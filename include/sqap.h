@@ -117,6 +117,30 @@ sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t
 size_t sqap_attn_scores_workspace_bytes(int32_t batch, int32_t S, int32_t H, int32_t d, int32_t n_vis);
 
 /*
+ * sqap_attn_scores_batch for callers that cannot allocate device memory or pass
+ * a workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments without the workspace, same kernels, same
+ * bits in scores_out.  The scratch memory is an array built into the library,
+ * 2 MiB + 16 KiB of device memory that every GPU the library runs on holds
+ * until the process ends; it serves at most 64 observations per call and
+ * batch * H * n_vis <= 524288 per-head weights (16 observations of 32 heads x
+ * 256 visual tokens use a quarter of it).  The call itself allocates and frees
+ * nothing, on the host or on the device; the array's device address is looked
+ * up at sqap_init, or else at the first call on a device.  All calls on one GPU
+ * share the array: calls that overlap in time there (two streams, two host
+ * threads) race, calls ordered on one stream do not.  What must be zero at the
+ * start of a call is zero when the library is loaded and is put back to zero by
+ * the kernel before it ends, so a call that runs to its end leaves the array
+ * ready for the next one whatever that one's size.  Shapes that run in a single
+ * workgroup (see sqap_attn_scores_workspace_bytes) use no scratch memory at all.
+ * EINVAL / EUNSUPPORTED as sqap_attn_scores_batch; EUNSUPPORTED also for
+ * batch > 64 or batch * H * n_vis > 524288 (the message says which).
+ */
+sqap_status sqap_attn_scores_noalloc(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S,
+                                     int32_t H, int32_t d, int32_t vis_begin, int32_t n_vis,
+                                     float *scores_out, void *stream);
+
+/*
  * Eq. 1: K_attn = Top_k(a_q, k).  For each of `batch` rows of `scores`
  * ([batch, n_tokens] floats) writes the indices of the keep_k largest values
  * to idx_out ([batch, keep_k] int32), in ascending index order.  The kept set

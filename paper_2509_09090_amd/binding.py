@@ -24,7 +24,7 @@ EXPORTS = (
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
     "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention", "sqap_group_info", "sqap_init",
-    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes",
+    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc",
 )
 
 
@@ -59,6 +59,7 @@ def lib():
         L.sqap_version.argtypes = []
         L.sqap_attn_scores.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, sz, vp]
         L.sqap_attn_scores_batch.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp, sz, vp]
+        L.sqap_attn_scores_noalloc.argtypes = [vp, vp, i32, i32, i32, i32, i32, i32, vp, vp]
         L.sqap_attn_scores_workspace_bytes.restype = sz
         L.sqap_attn_scores_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.sqap_prune_topk.argtypes = [vp, i32, i32, i32, vp, vp]
@@ -159,6 +160,13 @@ def sqap_attn_scores_batch(q, k, vis_begin, n_vis, scores_out, workspace=None, s
     batch, S, H, d = k.shape
     _check(lib().sqap_attn_scores_batch(_ptr(q), _ptr(k), batch, S, H, d, vis_begin, n_vis, _ptr(scores_out),
                                         _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+
+def sqap_attn_scores_noalloc(q, k, vis_begin, n_vis, scores_out, stream=None):
+    """sqap_attn_scores_batch on the library's built-in scratch array (no workspace, no allocation)."""
+    batch, S, H, d = k.shape
+    _check(lib().sqap_attn_scores_noalloc(_ptr(q), _ptr(k), batch, S, H, d, vis_begin, n_vis, _ptr(scores_out),
+                                          _stream(stream)))
 
 
 def sqap_prune_topk(scores, keep_k, idx_out, stream=None):

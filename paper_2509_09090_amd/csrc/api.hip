@@ -95,6 +95,32 @@ sqap_status sqap_attn_scores_batch(const sqap_f16 *q, const sqap_f16 *k, int32_t
                                workspace_bytes, stream);
 }
 
+sqap_status sqap_attn_scores_noalloc(const sqap_f16 *q, const sqap_f16 *k, int32_t batch, int32_t S, int32_t H,
+                                     int32_t d, int32_t vis_begin, int32_t n_vis, float *scores_out, void *stream)
+{
+    const char *who = "sqap_attn_scores_noalloc";
+    if (batch < 0) return fail(SQAP_EINVAL, "%s: batch %d < 0", who, batch);
+    if (S <= 0 || H <= 0 || d <= 0)
+        return fail(SQAP_EINVAL, "%s: S, H, d must be positive (%d, %d, %d)", who, S, H, d);
+    if (vis_begin < 0 || n_vis < 0 || (int64_t)vis_begin + n_vis > S)
+        return fail(SQAP_EINVAL, "%s: visual span [%d, %d+%d) outside [0, %d)", who, vis_begin, vis_begin, n_vis, S);
+    if (batch == 0) return SQAP_OK;
+    if (!q || !k) return fail(SQAP_EINVAL, "%s: null q or k", who);
+    if (n_vis == 0) return SQAP_OK;
+    if (!scores_out) return fail(SQAP_EINVAL, "%s: null scores_out", who);
+    if (d > 256 || (d & 1)) return fail(SQAP_EUNSUPPORTED, "%s: d = %d (even, <= 256)", who, d);
+    if (S > 16384) return fail(SQAP_EUNSUPPORTED, "%s: S = %d > 16384", who, S);
+    // what the file-scope scratch array holds
+    if (batch > noalloc_max_batch())
+        return fail(SQAP_EUNSUPPORTED, "%s: batch = %d above the %d observations the built-in scratch array holds", who,
+                    batch, noalloc_max_batch());
+    if ((uint64_t)batch * (uint64_t)H * (uint64_t)n_vis > noalloc_max_weights())
+        return fail(SQAP_EUNSUPPORTED, "%s: batch * H * n_vis = %llu above the %zu per-head weights the built-in scratch "
+                    "array holds", who, (unsigned long long)batch * H * n_vis, noalloc_max_weights());
+    return launch_attn_scores_noalloc(reinterpret_cast<const __half *>(q), reinterpret_cast<const __half *>(k), batch, S,
+                                      H, d, vis_begin, n_vis, scores_out, as_stream(stream));
+}
+
 sqap_status sqap_prune_topk(const float *scores, int32_t batch, int32_t n_tokens,
                             int32_t keep_k, int32_t *idx_out, void *stream)
 {
@@ -500,6 +526,9 @@ sqap_status sqap_init(void *stream)
 {
     int dev = 0;
     SQAP_HIP_CHECK(hipGetDevice(&dev));
+    void *scratch_ptr = nullptr;               // device address of the built-in scratch array, looked up once per device
+    sqap_status s = noalloc_scratch(&scratch_ptr);
+    if (s != SQAP_OK) return s;
     return probe_dispatch(dev, as_stream(stream), nullptr);
 }
 

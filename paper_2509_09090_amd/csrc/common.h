@@ -107,6 +107,12 @@ sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int 
                                int vis_begin, int n_vis, float *scores, void *workspace, size_t workspace_bytes,
                                hipStream_t st);
 size_t attn_scores_workspace_bytes(int batch, int H, int n_vis);
+// variant whose scratch is a file-scope device array (prune.hip); limits of that array
+sqap_status launch_attn_scores_noalloc(const __half *q, const __half *k, int batch, int S, int H, int d,
+                                       int vis_begin, int n_vis, float *scores, hipStream_t st);
+sqap_status noalloc_scratch(void **out);
+size_t noalloc_max_weights();
+int noalloc_max_batch();
 sqap_status launch_prune_topk(const float *scores, int batch, int n, int keep_k, int32_t *idx,
                               hipStream_t st);
 sqap_status launch_prune_rows(const float *scores, int batch, int n, int keep_k, int seq_len, int vis_begin,

@@ -732,4 +732,59 @@ sqap_status launch_attn_scores(const __half *q, const __half *k, int batch, int 
     return SQAP_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The retention score for callers that cannot allocate (a stream under graph capture, a serving loop
+// that forbids hipMalloc): the workspace of the fast kernel is this file-scope device array instead of
+// a caller's buffer.  Layout as above: kNoAllocMaxBatch counter lines, then the per-head weights.
+// The array's name is only a host-side handle: the device address is looked up once per device with
+// hipGetSymbolAddress (each device holds its own copy of the array at its own address) and host code
+// uses that address from then on.  The array is zero when the code object is loaded; what must be zero
+// at the start of a call (the counters) is put back to zero by the workgroup that finishes last, so
+// every call that runs to its end leaves the array ready for the next one.
+constexpr int kNoAllocMaxBatch = 64;
+constexpr size_t kNoAllocMaxWeights = 512 * 1024;                  // batch * H * n_vis floats: 2 MiB
+constexpr size_t kNoAllocCounterBytes = (size_t)kNoAllocMaxBatch * kCounterStride * sizeof(unsigned int);
+constexpr size_t kNoAllocScratchBytes = kNoAllocCounterBytes + kNoAllocMaxWeights * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
+static std::atomic<void *> g_scratch_of_device[kMaxDeviceSlots];
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+sqap_status noalloc_scratch(void **out)
+{
+    int dev = 0;
+    SQAP_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDeviceSlots)
+        return fail(SQAP_EUNSUPPORTED, "device ordinal %d above %d", dev, kMaxDeviceSlots - 1);
+    void *ptr = g_scratch_of_device[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        SQAP_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return fail(SQAP_EDEVICE, "hipGetSymbolAddress gave a null address for the scratch array");
+        g_scratch_of_device[dev].store(ptr, std::memory_order_release);      // racing host threads store the same value
+    }
+    *out = ptr;
+    return SQAP_OK;
+}
+
+size_t noalloc_max_weights() { return kNoAllocMaxWeights; }
+int noalloc_max_batch() { return kNoAllocMaxBatch; }
+
+sqap_status launch_attn_scores_noalloc(const __half *q, const __half *k, int batch, int S, int H, int d,
+                                       int vis_begin, int n_vis, float *scores, hipStream_t st)
+{
+    if (!score_fast_path(q, k, S, d))       // the one-workgroup kernel uses no scratch memory at all
+        return launch_attn_scores(q, k, batch, S, H, d, vis_begin, n_vis, scores, nullptr, 0, st);
+    void *ptr = nullptr;
+    sqap_status s = noalloc_scratch(&ptr);
+    if (s != SQAP_OK) return s;
+    // The kernel sees the array split as [batch counter lines][weights]; the weights start behind the
+    // counter lines of THIS call's batch, which all lie inside the kNoAllocMaxBatch lines that are kept zero.
+    unsigned int *counters = reinterpret_cast<unsigned int *>(ptr);
+    float *weights = reinterpret_cast<float *>(reinterpret_cast<uint8_t *>(ptr) + kNoAllocCounterBytes);
+    hipLaunchKernelGGL(attn_head_kernel, dim3(H, batch), dim3(256), 0, st, q, k, S, H, d, vis_begin, n_vis, scores,
+                       counters, weights);
+    SQAP_HIP_CHECK(hipGetLastError());
+    return SQAP_OK;
+}
+
 }  // namespace sqap
