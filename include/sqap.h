@@ -461,6 +461,16 @@ sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream);
 sqap_status sqap_set_persistent_kernels(int32_t enabled);
 
 /*
+ * Which kernel sqap_w4a4_linear uses for 8 < M < 512 with K a multiple of 256 (and at least 1024): 1, the
+ * default, the kernel in which every workgroup owns complete outputs and nothing passes between
+ * workgroups (it needs no workspace); 0 the tile kernels that split K between workgroups and exchange
+ * partial sums through the workspace (which other shapes always use).  Same results bit for bit; process
+ * wide; for tests and measurement.  sqap_workspace_bytes reports what the second kind needs either way.
+ * Always SQAP_OK.
+ */
+sqap_status sqap_set_mid_m_kernel(int32_t which);
+
+/*
  * The work split of the stream-K linear (M > 8, K a multiple of 128), as a
  * host-side computation: no GPU is touched.  A launch runs 8 x blocks_per_xcd
  * persistent workgroups; the output tiles (256 x 256 from M = 512 on, 96 or

@@ -24,7 +24,7 @@ EXPORTS = (
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
     "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention", "sqap_group_info", "sqap_init",
-    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc",
+    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc", "sqap_set_mid_m_kernel",
 )
 
 
@@ -92,6 +92,7 @@ def lib():
         L.sqap_selftest_quotient.argtypes = [vp, vp]
         L.sqap_init.argtypes = [vp]
         L.sqap_set_persistent_kernels.argtypes = [i32]
+        L.sqap_set_mid_m_kernel.argtypes = [i32]
         L.sqap_selftest_dispatch.argtypes = [ctypes.POINTER(u32), vp]
         L.sqap_plan_linear_shares.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(u32), ctypes.POINTER(ctypes.c_double),
                                                                       ctypes.POINTER(ctypes.c_double),
@@ -126,6 +127,10 @@ def sqap_init(stream=None):
 
 def sqap_set_persistent_kernels(enabled):
     _check(lib().sqap_set_persistent_kernels(1 if enabled else 0))
+
+
+def sqap_set_mid_m_kernel(which):
+    _check(lib().sqap_set_mid_m_kernel(int(which)))
 
 
 def workspace_error(workspace):

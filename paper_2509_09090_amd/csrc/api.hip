@@ -538,6 +538,12 @@ sqap_status sqap_set_persistent_kernels(int32_t enabled)
     return SQAP_OK;
 }
 
+sqap_status sqap_set_mid_m_kernel(int32_t which)
+{
+    set_mid_m_kernel(which);
+    return SQAP_OK;
+}
+
 sqap_status sqap_selftest_dispatch(uint32_t *xcc_of_block_out, void *stream)
 {
     if (!xcc_of_block_out) return fail(SQAP_EINVAL, "sqap_selftest_dispatch: null pointer");

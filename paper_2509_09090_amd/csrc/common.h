@@ -152,6 +152,12 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
                                __half *Y, int64_t ldy, int32_t *acc_out, void *workspace,
                                hipStream_t st);
 
+// Few hundred token rows, K a multiple of 256: every workgroup owns complete outputs (gemm_rows.hip)
+bool rows_kernel_applies(int M, int N, int K);
+sqap_status launch_rows_linear(const uint8_t *Xq, const __half *sx, int M, const Weight &w, __half *Y, int64_t ldy,
+                               int32_t *acc_out, hipStream_t st);
+void set_mid_m_kernel(int which);        // 0: tiles split along K between workgroups, 1: whole outputs per workgroup
+
 sqap_status launch_rope(__half *X, int64_t ld, const int32_t *pos, int S, int H, int d, double base, hipStream_t st);
 sqap_status launch_rope_append(__half *QKV, int64_t ld, const int32_t *pos, int S, int H, int d, double base,
                                __half *KV, int64_t ldkv, hipStream_t st);

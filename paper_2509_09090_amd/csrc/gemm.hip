@@ -1055,6 +1055,10 @@ sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out)
     return SQAP_OK;
 }
 
+static std::atomic<int> g_mid_m_kernel{1};            // 1: gemm_rows_kernel where it applies, 0: the split-K tile kernels
+
+void set_mid_m_kernel(int which) { g_mid_m_kernel.store(which ? 1 : 0); }
+
 static std::atomic<int> g_persistent_switch{-1};      // -1: follow the environment, 0: off, 1: on
 
 void set_persistent_kernels(int enabled) { g_persistent_switch.store(enabled ? 1 : 0); }
@@ -1452,6 +1456,9 @@ sqap_status launch_w4a4_linear(const uint8_t *Xq, const __half *sx, int M, const
     p.n_groups = w.n_groups;
     p.chunks = w.chunks;
     p.y_vec_ok = (reinterpret_cast<uintptr_t>(Y) & 15u) == 0 && (ldy & 7) == 0;
+    // A few hundred token rows: whole outputs per workgroup, nothing exchanged between workgroups
+    if (M < kStreamKMinM && g_mid_m_kernel.load(std::memory_order_relaxed) == 1 && rows_kernel_applies(M, w.N, w.K))
+        return launch_rows_linear(Xq, sx, M, w, Y, ldy, acc_out, st);
     if (w.K % kBK == 0 && persistent_allowed()) {
         if (M >= kStreamKMinM) return launch_streamk<CfgBig, false>(p, workspace, st);
         // Narrow tiles.  With few tiles, each is shared by many workgroups (256 / tiles of them) and

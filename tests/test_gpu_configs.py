@@ -218,13 +218,40 @@ def _linear_with_error_word(G, Xq, sx, Wq, sw, pitch_extra=0):
                           (84, 12288, 4096), (84, 22016, 4096), (276, 12288, 4096), (276, 22016, 4096),
                           (84, 32000, 4096), (276, 32000, 4096)])
 def test_ratio_sweep_and_head_shapes(G, oracle, M, N, K):
+    """Both kernels that serve this range: whole outputs per workgroup (the default) and K split between workgroups."""
+    from paper_2509_09090_amd import binding as B
     rng = np.random.default_rng(M * 7 + N * 3 + K)
     Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
     sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
     sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
-    Y, acc, err = _linear_with_error_word(G, Xq, sx, Wq, sw, pitch_extra=8 if N == 4096 else 0)
     Yo, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
-    assert err == 0
+    for which in (1, 0):
+        B.sqap_set_mid_m_kernel(which)
+        try:
+            Y, acc, err = _linear_with_error_word(G, Xq, sx, Wq, sw, pitch_extra=8 if N == 4096 else 0)
+        finally:
+            B.sqap_set_mid_m_kernel(1)
+        if which == 0:                   # the kernel with whole outputs per workgroup never touches the workspace
+            assert err == 0
+        assert np.array_equal(acc, acco), which
+        assert G.assert_fp16_close(Y, Yo) == 0, which
+
+
+# The kernel with whole outputs per workgroup at the edges of its range: token counts around the 16-row groups
+# and the 160-row blocks (one, two and four blocks), channel counts that are no multiple of 16 (guarded stores,
+# odd pitches), the shortest K it takes and a K with unequal shares for the four wavefronts.
+@pytest.mark.parametrize("M,N,K", [(9, 4096, 4096), (16, 512, 1024), (17, 1000, 2048), (33, 33, 1024), (160, 4096, 4096),
+                                   (161, 4096, 4096), (320, 2064, 2048), (321, 4096, 1024), (511, 1536, 2304),
+                                   (48, 16, 11008), (100, 12288, 1280), (148, 50, 4096), (640, 256, 1024)])
+def test_whole_output_kernel_edge_shapes(G, oracle, M, N, K):
+    rng = np.random.default_rng(M * 13 + N * 5 + K)
+    Xq, Wq = _random_packed(rng, M, K), _random_packed(rng, N, K)
+    sx = (rng.random(M) * 2 + 0.01).astype(np.float16)
+    sw = (rng.random(N) * 0.01 + 1e-4).astype(np.float16)
+    Y, acc, err = _linear_with_error_word(G, Xq, sx, Wq, sw, pitch_extra=0 if N % 8 else 24)
+    Yo, acco = oracle.w4a4_linear(Xq, sx, Wq, sw)
+    if M >= 512:                         # the stream-K kernel: it owns the workspace's error word
+        assert err == 0
     assert np.array_equal(acc, acco)
     assert G.assert_fp16_close(Y, Yo) == 0
 
