@@ -546,6 +546,53 @@ sqap_status sqap_group_info(const sqap_group *g, int32_t compute_units, int32_t 
 /* Frees a group (NULL allowed); the caller makes sure no launch still uses it. */
 sqap_status sqap_group_free(sqap_group *g);
 
+/*
+ * One decode step as ONE launch (autoregressive action-token decode at batch 1: the memory-bound
+ * regime of Section 4.3's linears, where every weight is streamed once per token).  A decoder is a device-
+ * resident description of a Llama-shaped model: per layer the packed q|k|v ([3 hidden, hidden]), o, gate|up
+ * ([2 ffn, hidden], gate rows first) and down weights, the two norm gains and the layer's key/value cache
+ * ([capacity, ldkv] halves: rotated key | value per position, as sqap_rope_append and
+ * sqap_decode_attention keep it); plus the final norm gain and the vocabulary head.  A step runs, for the
+ * token with embedding x [hidden] at position pos[0] and `past` positions already in the caches, exactly
+ * the chain
+ *   sqap_rmsnorm_quantize_act -> sqap_w4a4_linear(q|k|v) -> sqap_decode_attention (appends cache row `past`)
+ *   -> sqap_quantize_act -> sqap_w4a4_linear(o) -> sqap_rmsnorm_quantize_act (residual add fused)
+ *   -> sqap_w4a4_linear(gate|up) -> sqap_swiglu_quantize_act -> sqap_w4a4_linear(down)
+ * for every layer (each layer's trailing residual add fused into the next norm), then the final norm and the
+ * head, in one persistent kernel of 256 workgroups that hand the small rows between the linears to each
+ * other on the device and keep the weight stream running across those hand-overs.  Same bits as the chain
+ * wherever the chain is exact (everything but the attention output, which agrees within the fp16
+ * tolerance: the order of its binary32 sums is that of sqap_decode_attention).
+ *
+ * The handle owns a few KiB of device memory for the rows in flight and the barrier flags; the weights,
+ * gains and caches are captured by address and must outlive it.  One step at a time per decoder (steps are
+ * ordered on one stream).  logits: [vocab] halves.  attn_trace: NULL, or [n_layers, hidden] halves that
+ * receive every layer's attention output (tests feed it to the reference).  The kernel needs all its 256
+ * workgroups resident at once (a device with at least 256 compute units; EUNSUPPORTED otherwise).  A wait
+ * between workgroups that does not end within a few seconds gives up: sqap_decoder_status then reports a
+ * nonzero word (it copies 8 bytes back and SYNCHRONISES the stream; the word is cleared when a step starts).
+ * A captured step can be replayed from a HIP graph.
+ * EINVAL: null pointer, a handle that is not a weight, shapes that do not fit each other, negative
+ * past.  EUNSUPPORTED: head size not a multiple of 8 or above 128, hidden or ffn above 12288 or not a
+ * multiple of 128, more than 256 heads, a linear with more than 16 groups of 16 channels per compute unit
+ * (N above 65536), operands not 16-byte aligned.  ENOMEM / EDEVICE.
+ */
+typedef struct sqap_decoder sqap_decoder;
+typedef struct sqap_decoder_layer {
+    const sqap_weight *qkv, *o, *gate_up, *down;
+    const sqap_f16 *gamma_attn, *gamma_mlp;   /* device, [hidden] each, 16-byte aligned */
+    sqap_f16 *kv;                             /* device, this layer's cache */
+    int64_t ldkv;                             /* cache row pitch in elements, >= 2 * hidden */
+} sqap_decoder_layer;
+
+sqap_status sqap_decoder_create(const sqap_decoder_layer *layers, int32_t n_layers, int32_t n_heads,
+                                int32_t head_dim, const sqap_f16 *gamma_final, const sqap_weight *head,
+                                float eps, double rope_base, sqap_decoder **out);
+sqap_status sqap_decoder_step(sqap_decoder *d, const sqap_f16 *x, const int32_t *pos, int32_t past,
+                              sqap_f16 *logits, sqap_f16 *attn_trace, void *stream);
+sqap_status sqap_decoder_status(const sqap_decoder *d, uint64_t *error_word_out, void *stream);
+sqap_status sqap_decoder_free(sqap_decoder *d);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,8 @@ EXPORTS = (
     "sqap_prune_rows", "sqap_prune_select", "sqap_channel_scales", "sqap_quantize_act_channelwise",
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
     "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention", "sqap_group_info", "sqap_init",
-    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc", "sqap_set_mid_m_kernel",
+    "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc", "sqap_set_mid_m_kernel", "sqap_decoder_create", "sqap_decoder_step", "sqap_decoder_status",
+    "sqap_decoder_free",
 )
 
 
@@ -33,6 +34,13 @@ class LinearDesc(ctypes.Structure):
     _fields_ = [("Xq", ctypes.c_void_p), ("sx", ctypes.c_void_p), ("M", ctypes.c_int32),
                 ("W", ctypes.c_void_p), ("Y", ctypes.c_void_p), ("ldy", ctypes.c_int64),
                 ("acc_out", ctypes.c_void_p)]
+
+
+class DecoderLayer(ctypes.Structure):
+    """Mirror of sqap_decoder_layer."""
+    _fields_ = [("qkv", ctypes.c_void_p), ("o", ctypes.c_void_p), ("gate_up", ctypes.c_void_p), ("down", ctypes.c_void_p),
+                ("gamma_attn", ctypes.c_void_p), ("gamma_mlp", ctypes.c_void_p), ("kv", ctypes.c_void_p),
+                ("ldkv", ctypes.c_int64)]
 
 
 class SqapError(RuntimeError):
@@ -88,6 +96,11 @@ def lib():
         L.sqap_group_create.argtypes = [ctypes.POINTER(LinearDesc), i32, ctypes.POINTER(vp)]
         L.sqap_group_run.argtypes = [vp, vp]
         L.sqap_group_free.argtypes = [vp]
+        L.sqap_decoder_create.argtypes = [ctypes.POINTER(DecoderLayer), i32, i32, i32, vp, vp, ctypes.c_float,
+                                          ctypes.c_double, ctypes.POINTER(vp)]
+        L.sqap_decoder_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+        L.sqap_decoder_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), vp]
+        L.sqap_decoder_free.argtypes = [vp]
         L.sqap_group_info.argtypes = [vp, i32] + [ctypes.POINTER(i32)] * 5
         L.sqap_selftest_quotient.argtypes = [vp, vp]
         L.sqap_init.argtypes = [vp]
@@ -398,3 +411,46 @@ def sqap_group_create(problems):
 
 def sqap_group_run(group, stream=None):
     group.run(stream)
+
+
+class Decoder:
+    """Owns a sqap_decoder handle; keeps the tensors and weights it points to alive."""
+
+    def __init__(self, handle, keep):
+        self.handle, self._keep = handle, keep
+
+    def step(self, x, pos, past, logits, attn_trace=None, stream=None):
+        """x [hidden] fp16, pos [1] int32 (device), past: positions already in the caches, logits [vocab] fp16."""
+        _check(lib().sqap_decoder_step(self.handle, _ptr(x), _ptr(pos), past, _ptr(logits), _ptr(attn_trace),
+                                       _stream(stream)))
+
+    def status(self, stream=None):
+        """Error word of the last step (0: every wait between workgroups ended).  Synchronises the stream."""
+        w = ctypes.c_uint64(0)
+        _check(lib().sqap_decoder_status(self.handle, ctypes.byref(w), _stream(stream)))
+        return w.value
+
+    def free(self):
+        if self.handle:
+            _check(lib().sqap_decoder_free(self.handle))
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def sqap_decoder_create(layers, n_heads, head_dim, gamma_final, head, eps=1e-5, rope_base=10000.0):
+    """layers: list of (qkv, o, gate_up, down: Weight; gamma_attn, gamma_mlp: [hidden] fp16; kv: [capacity, >= 2 hidden] fp16)."""
+    n = len(layers)
+    arr = (DecoderLayer * n)()
+    for i, (qkv, o, gu, dn, g1, g2, kv) in enumerate(layers):
+        arr[i].qkv, arr[i].o, arr[i].gate_up, arr[i].down = qkv.handle.value, o.handle.value, gu.handle.value, dn.handle.value
+        arr[i].gamma_attn, arr[i].gamma_mlp = g1.data_ptr(), g2.data_ptr()
+        arr[i].kv, arr[i].ldkv = kv.data_ptr(), kv.stride(0)
+    h = ctypes.c_void_p()
+    _check(lib().sqap_decoder_create(arr, n, n_heads, head_dim, _ptr(gamma_final), head.handle, eps, rope_base,
+                                     ctypes.byref(h)))
+    return Decoder(h, (list(layers), gamma_final, head))

@@ -620,6 +620,50 @@ sqap_status sqap_w4a4_linear(const uint8_t *Xq, const sqap_f16 *sx, int32_t M,
                               as_stream(stream));
 }
 
+sqap_status sqap_decoder_create(const sqap_decoder_layer *layers, int32_t n_layers, int32_t n_heads, int32_t head_dim,
+                                const sqap_f16 *gamma_final, const sqap_weight *head, float eps, double rope_base,
+                                sqap_decoder **out)
+{
+    if (out) *out = nullptr;
+    if (!layers || !out) return fail(SQAP_EINVAL, "sqap_decoder_create: null pointer");
+    if (!(eps >= 0.0f) || !(rope_base > 0.0)) return fail(SQAP_EINVAL, "sqap_decoder_create: eps must be >= 0, rope_base > 0");
+    Decoder *d = nullptr;
+    sqap_status s = decoder_create(layers, n_layers, n_heads, head_dim, gamma_final, head, eps, rope_base, &d);
+    if (s == SQAP_OK) *out = reinterpret_cast<sqap_decoder *>(d);
+    return s;
+}
+
+sqap_status sqap_decoder_step(sqap_decoder *d, const sqap_f16 *x, const int32_t *pos, int32_t past, sqap_f16 *logits,
+                              sqap_f16 *attn_trace, void *stream)
+{
+    Decoder *dd = reinterpret_cast<Decoder *>(d);
+    if (!decoder_valid(dd)) return fail(SQAP_EINVAL, "sqap_decoder_step: not a decoder handle");
+    if (!x || !pos || !logits) return fail(SQAP_EINVAL, "sqap_decoder_step: null pointer");
+    if (past < 0) return fail(SQAP_EINVAL, "sqap_decoder_step: past = %d", past);
+    if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(attn_trace)) & 15u)
+        return fail(SQAP_EUNSUPPORTED, "sqap_decoder_step: x, logits and attn_trace must be 16-byte aligned");
+    return decoder_step(dd, x, pos, past, logits, attn_trace, as_stream(stream));
+}
+
+sqap_status sqap_decoder_status(const sqap_decoder *d, uint64_t *error_word_out, void *stream)
+{
+    const Decoder *dd = reinterpret_cast<const Decoder *>(d);
+    if (!decoder_valid(dd)) return fail(SQAP_EINVAL, "sqap_decoder_status: not a decoder handle");
+    if (!error_word_out) return fail(SQAP_EINVAL, "sqap_decoder_status: null pointer");
+    unsigned long long w = 0;
+    sqap_status s = decoder_error(dd, &w, as_stream(stream));
+    *error_word_out = w;
+    return s;
+}
+
+sqap_status sqap_decoder_free(sqap_decoder *d)
+{
+    if (!d) return SQAP_OK;
+    Decoder *dd = reinterpret_cast<Decoder *>(d);
+    if (!decoder_valid(dd)) return fail(SQAP_EINVAL, "sqap_decoder_free: not a decoder handle");
+    return decoder_free(dd);
+}
+
 sqap_status sqap_group_create(const sqap_linear_desc *descs, int32_t count, sqap_group **out)
 {
     if (out) *out = nullptr;

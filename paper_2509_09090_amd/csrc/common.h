@@ -174,6 +174,16 @@ sqap_status probe_dispatch(int device, hipStream_t st, uint32_t *table_out);
 void set_persistent_kernels(int enabled);
 sqap_status plan_linear_shares(int M, int N, int K, int blocks_per_xcd, uint32_t *bounds_out, double *planned_out,
                                double *even_out, int *tile_rows_out, int *tile_cols_out);
+// One decode step as one persistent launch (decoder_step.hip)
+struct Decoder;
+sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n_heads, int head_dim,
+                           const sqap_f16 *gamma_final, const sqap_weight *head, float eps, double rope_base,
+                           Decoder **out);
+sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int past, sqap_f16 *logits,
+                         sqap_f16 *attn_trace, hipStream_t st);
+sqap_status decoder_error(const Decoder *d, unsigned long long *word_out, hipStream_t st);
+sqap_status decoder_free(Decoder *d);
+bool decoder_valid(const Decoder *d);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *out_cap);
 

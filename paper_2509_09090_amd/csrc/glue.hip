@@ -7,28 +7,9 @@
 // matrix-core throughput: binary32 FMAs over LDS tiles with an online softmax.
 #include "common.h"
 #include "quant_math.h"
+#include "decode_attn.h"
 
 namespace sqap {
-
-// The rotation frequencies base^(-2i/d), i < d/2, depend on the model alone: the host evaluates them (binary64
-// pow) and hands them over as a kernel argument, which takes the power out of the dependent chain
-// power -> angle -> sine and cosine that every pair used to walk (a third of a rotary launch's time at a few
-// hundred tokens).  Head sizes above 2 * kRopeTableMax evaluate the power on the device as before.
-constexpr int kRopeTableMax = 128;
-struct RopeFreq {
-    double f[kRopeTableMax];
-};
-static RopeFreq rope_frequencies(int d, double base)
-{
-    RopeFreq r = {};
-    for (int i = 0; i < d / 2 && i < kRopeTableMax; ++i) r.f[i] = std::pow(base, -2.0 * (double)i / (double)d);
-    return r;
-}
-__device__ __forceinline__ double rope_angle(const RopeFreq &freq, int pos, int i, int d, double base)
-{
-    const double f = (d >> 1) <= kRopeTableMax ? freq.f[i] : pow(base, -2.0 * (double)i / (double)d);
-    return (double)pos * f;
-}
 
 // v'_i = v_i cos a - v_{i+d/2} sin a,  v'_{i+d/2} = v_{i+d/2} cos a + v_i sin a,
 // a = pos * base^(-2i/d); angle, sine and cosine in binary64, products in binary64, one rounding
@@ -515,22 +496,6 @@ sqap_status launch_attention(const __half *Q, int64_t ldq, const __half *Kc, int
 // rows, the 16 key groups added through LDS.  All binary32.  A chunk's key AND value rows (12 of each per
 // lane) are asked for at once, the first chunk's before the rotation, whose binary64 sine and cosine are a
 // longer dependent chain than the rest of the kernel: a prefix of up to 191 positions costs one round of loads.
-constexpr int kDecKeys = 12;              // keys per lane group and chunk: their key and value rows are in flight together
-constexpr int kDecChunk = 16 * kDecKeys;   // keys per softmax chunk
-constexpr int kDecMaxD = 128;              // head size limit: 16 lanes x 8 columns
-constexpr int kDecMaxRow = 8192;           // H * d limit of the fused quantizer (row staged in LDS)
-
-__device__ __forceinline__ void unpack_halves(const uint4 raw, float (&f)[8])
-{
-    const __half2 *h2 = reinterpret_cast<const __half2 *>(&raw);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const float2 x = __half22float2(h2[p]);
-        f[2 * p] = x.x;
-        f[2 * p + 1] = x.y;
-    }
-}
-
 __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__restrict__ QKV,
                                                                const int32_t *__restrict__ pos, int H, int d,
                                                                double base, __half *KV, int64_t ldkv, int past,
@@ -538,139 +503,12 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
                                                                __half *__restrict__ sx, unsigned int *counter,
                                                                const RopeFreq freq)
 {
-    __shared__ __attribute__((aligned(16))) float qf[kDecMaxD];
-    __shared__ __attribute__((aligned(16))) __half knew[kDecMaxD], vnew[kDecMaxD];
-    __shared__ float sc[kDecChunk];
-    constexpr int kRedFloats = 16 * kDecMaxD > kDecMaxRow / 2 ? 16 * kDecMaxD : kDecMaxRow / 2;
-    __shared__ __attribute__((aligned(16))) float ored[kRedFloats];        // later: the output row as halves
-    __shared__ float wred[4];
+    __shared__ DecodeAttnLds lds;
     __shared__ int last_flag;
-    static_assert(sizeof(ored) >= kDecMaxRow * sizeof(__half), "the staged row must fit the reduction buffer");
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, h = blockIdx.x;
-    const int half_d = d >> 1, width = H * d;
-    const int Sk = past + 1;
-
-    const int grp = t >> 4, c = t & 15;              // key group, column chunk
-    const bool col_ok = c * 8 < d;
-    const __half *kbase = KV + (int64_t)h * d + c * 8, *vbase = kbase + width;
-    // a cached row's 8 columns of this lane (zeros past the prefix; the new token's row comes from LDS later)
-    auto cached = [&](const __half *gbase, int key) {
-        uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (col_ok && key < past) raw = *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
-        return raw;
-    };
-    uint4 kraw[kDecKeys], vraw[kDecKeys];
-#pragma unroll
-    for (int j = 0; j < kDecKeys; ++j) {
-        kraw[j] = cached(kbase, 16 * j + grp);
-        vraw[j] = cached(vbase, 16 * j + grp);
-    }
-
-    // rotation of this head's query and key; the value is copied
-    if (t < half_d) {
-        const int i = t;
-        const double a = rope_angle(freq, pos[0], i, d, base);
-        double sn, cs;
-        sincos(a, &sn, &cs);
-        const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
-        __half *krow = KV + (int64_t)past * ldkv + (int64_t)h * d, *vrow = krow + width;
-        double lo = (double)__half2float(q[i]), hi = (double)__half2float(q[i + half_d]);
-        qf[i] = __half2float(__float2half_rn((float)(lo * cs - hi * sn)));
-        qf[i + half_d] = __half2float(__float2half_rn((float)(hi * cs + lo * sn)));
-        lo = (double)__half2float(k[i]);
-        hi = (double)__half2float(k[i + half_d]);
-        const __half k0 = __float2half_rn((float)(lo * cs - hi * sn));
-        const __half k1 = __float2half_rn((float)(hi * cs + lo * sn));
-        knew[i] = k0;
-        knew[i + half_d] = k1;
-        krow[i] = k0;
-        krow[i + half_d] = k1;
-        const __half v0 = v[i], v1 = v[i + half_d];
-        vnew[i] = v0;
-        vnew[i + half_d] = v1;
-        vrow[i] = v0;
-        vrow[i + half_d] = v1;
-    }
-    __syncthreads();
-
-    float q8[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) q8[e] = col_ok ? qf[c * 8 + e] : 0.f;
-    const float inv_sqrt_d = 1.0f / sqrtf((float)d);
-
-    float o[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-    for (int c0 = 0; c0 < Sk; c0 += kDecChunk) {
-        const int n = min(kDecChunk, Sk - c0);
-#pragma unroll
-        for (int j = 0; j < kDecKeys; ++j) {
-            const int key = c0 + 16 * j + grp;
-            if (c0 > 0) {
-                kraw[j] = cached(kbase, key);
-                vraw[j] = cached(vbase, key);
-            }
-            if (key == past && col_ok) {
-                kraw[j] = *reinterpret_cast<const uint4 *>(knew + c * 8);
-                vraw[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < kDecKeys; ++j) {
-            float kf[8];
-            unpack_halves(kraw[j], kf);
-            float s = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
-            for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
-            const int key = 16 * j + grp;
-            if (c == 0 && key < n) sc[key] = s * inv_sqrt_d;
-        }
-        __syncthreads();
-        float mx = -INFINITY;
-        for (int i = t; i < n; i += 256) mx = fmaxf(mx, sc[i]);
-        for (int x = 32; x > 0; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x));
-        if (lane == 0) wred[wave] = mx;
-        __syncthreads();
-        const float m_new = fmaxf(m, fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3])));
-        __syncthreads();                               // wred is reused for the sum
-        float sum = 0.f;
-        for (int i = t; i < n; i += 256) {
-            const float pj = expf(sc[i] - m_new);
-            sc[i] = pj;
-            sum += pj;
-        }
-        for (int x = 32; x > 0; x >>= 1) sum += __shfl_xor(sum, x);
-        if (lane == 0) wred[wave] = sum;
-        __syncthreads();
-        const float rescale = expf(m - m_new);         // m = -inf only before the first chunk: exp(-inf) = 0
-        l = l * rescale + ((wred[0] + wred[1]) + (wred[2] + wred[3]));
-        m = m_new;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] *= rescale;
-#pragma unroll
-        for (int j = 0; j < kDecKeys; ++j) {
-            const int key = 16 * j + grp;
-            const float pj = key < n ? sc[key] : 0.f;
-            float vf[8];
-            unpack_halves(vraw[j], vf);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
-        }
-        __syncthreads();                               // sc and wred are rewritten by the next chunk
-    }
-    if (col_ok) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ored[grp * kDecMaxD + c * 8 + e] = o[e];
-    }
-    __syncthreads();
-    if (t < d) {
-        float acc = 0.f;
-#pragma unroll
-        for (int g = 0; g < 16; ++g) acc += ored[g * kDecMaxD + t];
-        O[(int64_t)h * d + t] = __float2half_rn(acc * (1.0f / l));
-    }
+    float *ored = lds.ored, *wred = lds.wred;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int width = H * d;
+    decode_attention_head<false>(lds, blockIdx.x, QKV, pos[0], H, d, base, KV, ldkv, past, O, nullptr, freq);
     if (!Xq) return;
 
     // the workgroup that arrives last quantizes the whole row (as quantize_rows_kernel does)
