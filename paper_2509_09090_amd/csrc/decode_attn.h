@@ -79,10 +79,15 @@ __device__ __forceinline__ __half read_half(const __half *p, int64_t i)
 // workgroup barriers); the first 256 threads do the work, any others only keep step.  LDS in `lds`.
 // AGENT: QKV was written by other workgroups of this launch and O is read by others (agent-scope loads and
 // stores); d even, d <= 128.
+// In the AGENT form (the whole-step kernel) the value rows are asked for after the scores instead of together
+// with the key rows (half the registers; the kernel around it has few to spare), and `sincos_tab` (d / 2 pairs
+// of binary64 sine, cosine of the token's angles, evaluated once per step by the same sincos call) replaces
+// the evaluation per layer.  Neither changes a single operation on the data: same bits.
 template <bool AGENT>
 __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h, const __half *QKV, int pos0, int H,
                                                       int d, double base, __half *KV, int64_t ldkv, int past,
-                                                      __half *O, __half *trace, const RopeFreq &freq)
+                                                      __half *O, __half *trace, const RopeFreq &freq,
+                                                      const double2 *sincos_tab = nullptr)
 {
     float *qf = lds.qf, *sc = lds.sc, *ored = lds.ored, *wred = lds.wred;
     __half *knew = lds.knew, *vnew = lds.vnew;
@@ -101,19 +106,25 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         if (col_ok && key < past) raw = *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
         return raw;
     };
-    uint4 kraw[kDecKeys], vraw[kDecKeys];
+    constexpr bool V_LATE = AGENT;
+    uint4 kraw[kDecKeys], vraw[V_LATE ? 1 : kDecKeys];
 #pragma unroll
     for (int j = 0; j < kDecKeys; ++j) {
         kraw[j] = cached(kbase, 16 * j + grp);
-        vraw[j] = cached(vbase, 16 * j + grp);
+        if (!V_LATE) vraw[j] = cached(vbase, 16 * j + grp);
     }
 
     // rotation of this head's query and key; the value is copied
     if (t < half_d) {
         const int i = t;
-        const double a = rope_angle(freq, pos0, i, d, base);
         double sn, cs;
-        sincos(a, &sn, &cs);
+        if constexpr (AGENT) {                         // (the table is not optional in this form)
+            sn = sincos_tab[i].x;
+            cs = sincos_tab[i].y;
+        } else {
+            const double a = rope_angle(freq, pos0, i, d, base);
+            sincos(a, &sn, &cs);
+        }
         const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
         __half *krow = KV + (int64_t)past * ldkv + (int64_t)h * d, *vrow = krow + width;
         double lo = (double)__half2float(read_half<AGENT>(q, i)), hi = (double)__half2float(read_half<AGENT>(q, i + half_d));
@@ -151,11 +162,11 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             const int key = c0 + 16 * j + grp;
             if (c0 > 0) {
                 kraw[j] = cached(kbase, key);
-                vraw[j] = cached(vbase, key);
+                if (!V_LATE) vraw[j] = cached(vbase, key);
             }
             if (key == past && col_ok) {
                 kraw[j] = *reinterpret_cast<const uint4 *>(knew + c * 8);
-                vraw[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
+                if (!V_LATE) vraw[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
             }
         }
 #pragma unroll
@@ -168,6 +179,16 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
             const int key = 16 * j + grp;
             if (on && c == 0 && key < n) sc[key] = s * inv_sqrt_d;
+        }
+        // (late form: the key registers are free now; the value rows arrive during the softmax)
+        uint4 vlate[V_LATE ? kDecKeys : 1];
+        if (V_LATE) {
+#pragma unroll
+            for (int j = 0; j < kDecKeys; ++j) {
+                const int key = c0 + 16 * j + grp;
+                vlate[j] = cached(vbase, key);
+                if (key == past && col_ok) vlate[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
+            }
         }
         __syncthreads();
         float mx = -INFINITY;
@@ -196,7 +217,8 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             const int key = 16 * j + grp;
             const float pj = key < n ? sc[key] : 0.f;
             float vf[8];
-            unpack_halves(vraw[j], vf);
+            if (!V_LATE) unpack_halves(vraw[j], vf);
+            else unpack_halves(vlate[j], vf);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
         }

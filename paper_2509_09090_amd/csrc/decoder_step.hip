@@ -18,9 +18,12 @@
 //     token there is nothing for a matrix core to reuse: each lane multiplies 32 weight codes of its
 //     channel with the 32 activation codes by four v_dot8_i32_i4 (signed int4 x int4 -> int32, exact, no
 //     widening).  A 1 KiB wavefront load is 16 channels x 4 pieces in the packed weight layout.
-//   * Weights do not depend on activations: a wavefront asks for the first sixteen pieces of its share of the
-//     NEXT linear before it waits at the barrier, so the weight stream keeps running across the barrier and
-//     the glue (sixteen 1 KiB loads per wavefront, 128 KiB per compute unit in flight).
+//   * Weights do not depend on activations, so the weight stream never waits for them: every wavefront
+//     walks ITS pieces of all the linears of the step as one sequence, fifteen 1 KiB loads ahead of what
+//     it multiplies, whatever phase those pieces belong to.  The loads land in a ring in LDS
+//     (global_load_lds_dwordx4: no registers held, slots addressed at run time), 120 KiB per compute unit:
+//     while the workgroup waits at a barrier or rebuilds an input row, the next linear's weights, and
+//     often those of the one after, are arriving.
 //   * gate and up channels are dealt in pairs, so the workgroup that owns a pair applies SwiGLU to it and only
 //     h = silu(g) * u crosses to the down projection.
 //   * The barrier: every workgroup owns one 64-bit flag; arriving is a store of the launch's generation plus
@@ -39,7 +42,7 @@ namespace sqap {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kStepThreads = 512, kStepWaves = 8;
-constexpr int kStepRing = 16;              // 1 KiB weight loads in flight per wavefront
+constexpr int kStepRing = 15;              // 1 KiB weight loads in flight (or landed, not yet used) per wavefront
 constexpr int kStepMaxGroups = 16;         // 16-channel groups a workgroup owns in one phase
 constexpr int kStepGpt = 3;                // groups of 8 row elements per thread: K <= 12288
 constexpr int kStepMaxK = kStepThreads * 8 * kStepGpt;
@@ -83,8 +86,11 @@ struct StepLds {
     float wmax[kStepWaves];
     float sx;
     int dead;               // a wait gave up: later waits return at once (the step's result is wrong and says so)
+    double2 sincos_tab[kDecMaxD / 2];      // sine, cosine of the token's rotation angles (the same for every layer)
     DecodeAttnLds attn;
+    __attribute__((aligned(16))) uint8_t ring[kStepWaves][kStepRing][1024];         // weights asked for, per wavefront
 };
+static_assert(sizeof(StepLds) <= 160 * 1024, "one workgroup per compute unit: all of its LDS");
 
 // ---- small rows that cross workgroups: agent-scope accesses, 8 elements (two 64-bit words) at a time ----
 __device__ __forceinline__ void load8(const __half *p, int g, float (&f)[8])
@@ -270,11 +276,54 @@ __device__ __forceinline__ const v4i *step_item(const StepPhase &P, const StepSh
                                          ((g & 1) * 16 + (lane & 15)) * 16);
 }
 
-__device__ __forceinline__ void step_prefetch(const StepPhase &P, const StepShare &s, int lane, v4i (&wbuf)[kStepRing])
+// Where a wavefront is in the sequence of weight pieces it asks for: the pieces of its share of phase 0, then
+// of phase 1, ... (a phase in which it has none is skipped).  Everything but lane_ptr is wavefront-uniform.
+struct StepStream {
+    int ph;                    // phase of the next piece (n_phases: the sequence has ended)
+    int i, i1;                 // the piece's number within the wavefront's share of that phase; the share's end
+    int q, Q;                  // piece within its 16-channel group; pieces per group
+    int issued;                // pieces asked for so far
+    int slot;                  // ring slot of the next piece = issued % kStepRing
+    const uint8_t *lane_ptr;   // this lane's 16 bytes of the next piece
+};
+
+__device__ __forceinline__ void stream_enter(StepStream &c, const StepArgs &a, int block, int wave, int lane)
 {
-#pragma unroll
-    for (int d = 0; d < kStepRing; ++d)
-        if (s.i0 + d < s.i1) wbuf[d] = __builtin_nontemporal_load(step_item(P, s, s.i0 + d, lane));
+    while (c.ph < a.n_phases) {
+        const StepPhase &P = a.phases[c.ph];
+        const StepShare sh = step_share(P, block, a.blocks, wave);
+        if (sh.i0 < sh.i1) {
+            c.i = sh.i0;
+            c.i1 = sh.i1;
+            c.Q = sh.Q;
+            c.q = sh.i0 % sh.Q;
+            c.lane_ptr = reinterpret_cast<const uint8_t *>(step_item(P, sh, sh.i0, lane));
+            return;
+        }
+        ++c.ph;
+    }
+}
+
+// Asks for the next piece of the sequence (into the ring slot that the piece kStepRing before it has left).
+__device__ __forceinline__ void stream_issue(StepStream &c, const StepArgs &a, StepLds &lds, int block, int wave, int lane)
+{
+    if (c.ph >= a.n_phases) return;
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const v4i *>(c.lane_ptr),
+                                     (__attribute__((address_space(3))) void *)(&lds.ring[wave][c.slot][0]), 16, 0, 0);
+    ++c.issued;
+    c.slot = c.slot + 1 == kStepRing ? 0 : c.slot + 1;
+    ++c.i;
+    ++c.q;
+    c.lane_ptr += 4 * 512;                             // the next four chunks of the same 16 channels
+    if (c.i == c.i1) {
+        ++c.ph;
+        stream_enter(c, a, block, wave, lane);
+    } else if (c.q == c.Q) {                           // the next group of the share
+        c.q = 0;
+        const StepPhase &P = a.phases[c.ph];
+        const StepShare sh = step_share(P, block, a.blocks, wave);
+        c.lane_ptr = reinterpret_cast<const uint8_t *>(step_item(P, sh, c.i, lane));
+    }
 }
 
 __device__ __forceinline__ void step_arrive(const StepArgs &a, unsigned long long value)
@@ -301,6 +350,18 @@ __device__ __forceinline__ void step_wait(const StepArgs &a, unsigned long long 
     __syncthreads();
 }
 
+// Diagnostic builds (-DSQAP_STEP_STAMPS) record the 100 MHz wall clock of four workgroups at eight points of every
+// phase into the attention trace buffer; product builds compile the macro away.
+#ifdef SQAP_STEP_STAMPS
+#define STEP_STAMP(k)                                                                                       \
+    do {                                                                                                    \
+        if (t == 0 && (block & 63) == 0 && a.attn_trace)                                                    \
+            reinterpret_cast<unsigned long long *>(a.attn_trace + 262144)[((block >> 6) * 400 + ph) * 8 + (k)] = wall_clock64(); \
+    } while (0)
+#else
+#define STEP_STAMP(k) do { } while (0)
+#endif
+
 __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const StepArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -313,14 +374,22 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     const int pos0 = a.pos[0];
     if (block == 0 && t == 0) __hip_atomic_store(a.err, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (t == 0) lds.dead = 0;
+    if (block < a.H && t < (a.d >> 1)) {               // the rotation's sines and cosines: once per step instead of per layer
+        double sn, cs;
+        sincos(rope_angle(a.freq, pos0, t, a.d, a.base), &sn, &cs);
+        lds.sincos_tab[t] = double2{sn, cs};
+    }
     __syncthreads();
 
-    v4i wbuf[kStepRing];
-    StepShare share = step_share(a.phases[0], block, a.blocks, wave);
-    step_prefetch(a.phases[0], share, lane, wbuf);
+    StepStream stream = {};
+    stream_enter(stream, a, block, wave, lane);
+    for (int k = 0; k < kStepRing; ++k) stream_issue(stream, a, lds, block, wave, lane);
+    int consumed = 0, cslot = 0;                       // pieces multiplied so far; ring slot of the next one
 
     for (int ph = 0; ph < a.n_phases; ++ph) {
         const StepPhase P = a.phases[ph];
+        const StepShare share = step_share(P, block, a.blocks, wave);
+        STEP_STAMP(0);
         // ---- the linear's input row: built by every workgroup for itself ----
         {
             float v[kStepGpt][8];
@@ -356,41 +425,45 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             if (P.gamma) step_norm(v, K, delta, block == 0 ? xsum : nullptr, P.gamma, a.eps, lds);
             step_quantize(v, K, lds);
         }
+        STEP_STAMP(1);
         // ---- this workgroup's channels: the wavefronts split the reduction axis ----
         for (int i = t; i < kStepMaxGroups * kStepWaves * 16; i += kStepThreads) (&lds.partial[0][0][0])[i] = 0;
         __syncthreads();
         {
-            int acc = 0, cur = share.i0 < share.i1 ? share.i0 / share.Q : 0;
-            auto flush = [&](int j) {
-                int s = acc;
-                s += __shfl_xor(s, 16);
-                s += __shfl_xor(s, 32);
-                if (lane < 16) lds.partial[j][wave][lane] = s;
+            int acc = 0;
+            int j = share.i0 < share.i1 ? share.i0 / share.Q : 0, q = share.i0 < share.i1 ? share.i0 - j * share.Q : 0;
+            auto flush = [&]() {
+                int sum = acc;
+                sum += __shfl_xor(sum, 16);
+                sum += __shfl_xor(sum, 32);
+                if (lane < 16) lds.partial[j][wave][lane] = sum;
                 acc = 0;
             };
-            for (int base = share.i0; base < share.i1; base += kStepRing) {
-#pragma unroll
-                for (int d = 0; d < kStepRing; ++d) {
-                    const int i = base + d;
-                    if (i < share.i1) {
-                        const int j = i / share.Q, q = i - j * share.Q;
-                        if (j != cur) {
-                            flush(cur);
-                            cur = j;
-                        }
-                        const v4i w = wbuf[d];
-                        if (i + kStepRing < share.i1) wbuf[d] = __builtin_nontemporal_load(step_item(P, share, i + kStepRing, lane));
-                        const v4i x = *reinterpret_cast<const v4i *>(lds.xs + (4 * q + (lane >> 4)) * 16);
-                        acc = __builtin_amdgcn_sdot8(w.x, x.x, acc, false);
-                        acc = __builtin_amdgcn_sdot8(w.y, x.y, acc, false);
-                        acc = __builtin_amdgcn_sdot8(w.z, x.z, acc, false);
-                        acc = __builtin_amdgcn_sdot8(w.w, x.w, acc, false);
-                    }
+            for (int i = share.i0; i < share.i1; ++i) {
+                // The piece to multiply was asked for kStepRing pieces ago (fewer at the very end of the step): it
+                // has landed once at most the younger pieces are still on their way (loads return in order).
+                if (stream.issued - consumed == kStepRing) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kStepRing - 1) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
+                const v4i x = *reinterpret_cast<const v4i *>(lds.xs + (4 * q + (lane >> 4)) * 16);
+                acc = __builtin_amdgcn_sdot8(w.x, x.x, acc, false);
+                acc = __builtin_amdgcn_sdot8(w.y, x.y, acc, false);
+                acc = __builtin_amdgcn_sdot8(w.z, x.z, acc, false);
+                acc = __builtin_amdgcn_sdot8(w.w, x.w, acc, false);
+                // the slot is free (its contents are in registers: the products above needed them)
+                stream_issue(stream, a, lds, block, wave, lane);
+                ++consumed;
+                cslot = cslot + 1 == kStepRing ? 0 : cslot + 1;
+                if (++q == share.Q) {
+                    flush();
+                    q = 0;
+                    ++j;
                 }
             }
-            if (share.i0 < share.i1) flush(cur);
+            if (share.i0 < share.i1 && q != 0) flush();
         }
         __syncthreads();
+        STEP_STAMP(2);
         // ---- outputs: two adjacent channels per thread (one 32-bit agent-scope store) ----
         {
             const float sxf = lds.sx;
@@ -442,23 +515,23 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             }
         }
         // ---- barrier, with the next linear's first weights asked for before the wait ----
+        STEP_STAMP(3);
         ++bar;
         step_arrive(a, gen0 + bar);
+        STEP_STAMP(4);
         if (P.kind == kStepQkv) {
-            // attention of the new token over the layer's cache: one workgroup per head.  (The next linear's
-            // weights are asked for after it: the attention needs the registers they would wait in.)
+            // attention of the new token over the layer's cache: one workgroup per head
             step_wait(a, gen0 + bar, lds);
+            STEP_STAMP(5);
             if (block < a.H)
                 decode_attention_head<true>(lds.attn, block, a.qkv, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn,
-                                            a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq);
+                                            a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq, lds.sincos_tab);
+            STEP_STAMP(6);
             ++bar;
             step_arrive(a, gen0 + bar);
         }
-        if (ph + 1 < a.n_phases) {
-            share = step_share(a.phases[ph + 1], block, a.blocks, wave);
-            step_prefetch(a.phases[ph + 1], share, lane, wbuf);
-        }
         step_wait(a, gen0 + bar, lds);
+        STEP_STAMP(7);
     }
     // every workgroup has read the generation (it took part in a barrier since): move it on for the next launch
     if (block == 0 && t == 0) *a.gen = gen0 + bar;
