@@ -9,6 +9,22 @@
 
 namespace sqap {
 
+// A pointer that was loaded from memory (a table of per-layer pointers, say) is a generic pointer to the
+// compiler: loads through it become flat loads, each fenced by a full wait because it might address LDS.
+// Saying that it addresses global memory turns them back into global loads that overlap.
+// (Address-space pointers only take built-in types: halves travel as 16-bit integers, 16-byte pieces as vectors.)
+#define SQAP_GLOBAL __attribute__((address_space(1)))
+typedef unsigned int sqap_v4u __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 global_load16(const void *p)
+{
+    const sqap_v4u v = *(const SQAP_GLOBAL sqap_v4u *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void global_store_half(__half *p, __half v)
+{
+    *(SQAP_GLOBAL unsigned short *)p = __half_as_ushort(v);
+}
+
 // The rotation frequencies base^(-2i/d), i < d/2, depend on the model alone: the host evaluates them (binary64
 // pow) and hands them over as a kernel argument, which takes the power out of the dependent chain
 // power -> angle -> sine and cosine that every pair used to walk (a third of a rotary launch's time at a few
@@ -79,10 +95,10 @@ __device__ __forceinline__ __half read_half(const __half *p, int64_t i)
 // workgroup barriers); the first 256 threads do the work, any others only keep step.  LDS in `lds`.
 // AGENT: QKV was written by other workgroups of this launch and O is read by others (agent-scope loads and
 // stores); d even, d <= 128.
-// In the AGENT form (the whole-step kernel) the value rows are asked for after the scores instead of together
-// with the key rows (half the registers; the kernel around it has few to spare), and `sincos_tab` (d / 2 pairs
-// of binary64 sine, cosine of the token's angles, evaluated once per step by the same sincos call) replaces
-// the evaluation per layer.  Neither changes a single operation on the data: same bits.
+// In the AGENT form (the whole-step kernel) `sincos_tab` (d / 2 pairs of binary64 sine, cosine of the token's
+// angles, evaluated once per step by the same sincos call) replaces the evaluation per layer: same bits.
+// (V_LATE asks for the value rows after the scores instead of together with the key rows: half the
+// registers for one more memory round trip; not used at present.)
 template <bool AGENT>
 __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h, const __half *QKV, int pos0, int H,
                                                       int d, double base, __half *KV, int64_t ldkv, int past,
@@ -91,7 +107,12 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
 {
     float *qf = lds.qf, *sc = lds.sc, *ored = lds.ored, *wred = lds.wred;
     __half *knew = lds.knew, *vnew = lds.vnew;
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int t = threadIdx.x;
+    // Inside a loop over layers everything below that depends only on the lane is loop invariant; hoisted out, it
+    // would sit in registers (in practice: in scratch memory) for the whole step.  The empty asm makes the
+    // compiler take t as a new value here, so the addresses are formed where they are used.
+    if (AGENT) asm volatile("" : "+v"(t));
+    const int lane = t & 63, wave = t >> 6;
     const int half_d = d >> 1, width = H * d;
     const int Sk = past + 1;
 
@@ -103,10 +124,22 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
     // a cached row's 8 columns of this lane (zeros past the prefix; the new token's row comes from LDS later)
     auto cached = [&](const __half *gbase, int key) {
         uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-        if (col_ok && key < past) raw = *reinterpret_cast<const uint4 *>(gbase + (int64_t)key * ldkv);
+        if (col_ok && key < past) raw = global_load16(gbase + (int64_t)key * ldkv);
         return raw;
     };
-    constexpr bool V_LATE = AGENT;
+    // the new token's query, key and value elements of this lane (rotation pairs i and i + d / 2): asked for
+    // before the cache rows, because loads return in order and the rotation is the longer chain
+    const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
+    __half qkv_new[6] = {};
+    if (t < half_d) {
+        qkv_new[0] = read_half<AGENT>(q, t);
+        qkv_new[1] = read_half<AGENT>(q, t + half_d);
+        qkv_new[2] = read_half<AGENT>(k, t);
+        qkv_new[3] = read_half<AGENT>(k, t + half_d);
+        qkv_new[4] = read_half<AGENT>(v, t);
+        qkv_new[5] = read_half<AGENT>(v, t + half_d);
+    }
+    constexpr bool V_LATE = false;
     uint4 kraw[kDecKeys], vraw[V_LATE ? 1 : kDecKeys];
 #pragma unroll
     for (int j = 0; j < kDecKeys; ++j) {
@@ -125,24 +158,23 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             const double a = rope_angle(freq, pos0, i, d, base);
             sincos(a, &sn, &cs);
         }
-        const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
         __half *krow = KV + (int64_t)past * ldkv + (int64_t)h * d, *vrow = krow + width;
-        double lo = (double)__half2float(read_half<AGENT>(q, i)), hi = (double)__half2float(read_half<AGENT>(q, i + half_d));
+        double lo = (double)__half2float(qkv_new[0]), hi = (double)__half2float(qkv_new[1]);
         qf[i] = __half2float(__float2half_rn((float)(lo * cs - hi * sn)));
         qf[i + half_d] = __half2float(__float2half_rn((float)(hi * cs + lo * sn)));
-        lo = (double)__half2float(read_half<AGENT>(k, i));
-        hi = (double)__half2float(read_half<AGENT>(k, i + half_d));
+        lo = (double)__half2float(qkv_new[2]);
+        hi = (double)__half2float(qkv_new[3]);
         const __half k0 = __float2half_rn((float)(lo * cs - hi * sn));
         const __half k1 = __float2half_rn((float)(hi * cs + lo * sn));
         knew[i] = k0;
         knew[i + half_d] = k1;
-        krow[i] = k0;
-        krow[i + half_d] = k1;
-        const __half v0 = read_half<AGENT>(v, i), v1 = read_half<AGENT>(v, i + half_d);
+        global_store_half(krow + i, k0);
+        global_store_half(krow + i + half_d, k1);
+        const __half v0 = qkv_new[4], v1 = qkv_new[5];
         vnew[i] = v0;
         vnew[i + half_d] = v1;
-        vrow[i] = v0;
-        vrow[i + half_d] = v1;
+        global_store_half(vrow + i, v0);
+        global_store_half(vrow + i + half_d, v1);
     }
     __syncthreads();
 

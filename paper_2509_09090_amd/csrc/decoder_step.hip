@@ -192,7 +192,7 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
         const int g = t + gi * kStepThreads;
         if (g < groups) {
             float gm[8];
-            unpack_halves(reinterpret_cast<const uint4 *>(gamma)[g], gm);
+            unpack_halves(global_load16(reinterpret_cast<const uint4 *>(gamma) + g), gm);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float xr = v[gi][e] * r;
@@ -479,7 +479,8 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                         s1 += lds.partial[j][w][row + 1];
                     }
                     const int n = step_group(P, share, j) * 16 + row;
-                    const __half2 sw2 = *reinterpret_cast<const __half2 *>(P.sw + n);   // padded to whole row groups
+                    const unsigned swb = *(const SQAP_GLOBAL unsigned *)(P.sw + n);       // two scales; padded to whole row groups
+                    const __half2 sw2 = *reinterpret_cast<const __half2 *>(&swb);
                     float y0 = ((float)s0 * sxf) * __low2float(sw2), y1 = ((float)s1 * sxf) * __high2float(sw2);
                     asm volatile("" : "+v"(y0), "+v"(y1));            // two binary32 products, then one rounding to half
                     y[0] = __half2float(__float2half_rn(y0));
