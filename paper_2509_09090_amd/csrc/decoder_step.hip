@@ -23,7 +23,9 @@
 //     it multiplies, whatever phase those pieces belong to.  The loads land in a ring in LDS
 //     (global_load_lds_dwordx4: no registers held, slots addressed at run time), 120 KiB per compute unit:
 //     while the workgroup waits at a barrier or rebuilds an input row, the next linear's weights, and
-//     often those of the one after, are arriving.
+//     often those of the one after, are arriving.  A full ring would stop the stream for the rest of the
+//     wait (slots only free up when their pieces are multiplied), so on arriving at a barrier a wavefront
+//     moves the eight oldest landed pieces into registers and asks for eight more.
 //   * gate and up channels are dealt in pairs, so the workgroup that owns a pair applies SwiGLU to it and only
 //     h = silu(g) * u crosses to the down projection.
 //   * The barrier: every workgroup owns one 64-bit flag; arriving is a store of the launch's generation plus
@@ -43,6 +45,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kStepThreads = 512, kStepWaves = 8;
 constexpr int kStepRing = 15;              // 1 KiB weight loads in flight (or landed, not yet used) per wavefront
+constexpr int kStepPark = 8;               // landed pieces a wavefront moves from the ring into registers at a barrier
 constexpr int kStepMaxGroups = 16;         // 16-channel groups a workgroup owns in one phase
 constexpr int kStepGpt = 3;                // groups of 8 row elements per thread: K <= 12288
 constexpr int kStepMaxK = kStepThreads * 8 * kStepGpt;
@@ -384,7 +387,29 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     StepStream stream = {};
     stream_enter(stream, a, block, wave, lane);
     for (int k = 0; k < kStepRing; ++k) stream_issue(stream, a, lds, block, wave, lane);
-    int consumed = 0, cslot = 0;                       // pieces multiplied so far; ring slot of the next one
+    int consumed = 0, cslot = 0;                       // pieces that have left the ring so far; ring slot of the oldest one in it
+    v4i park[kStepPark];                               // the oldest pieces not yet multiplied, moved out of the ring
+    int park_c = 0, park_n = 0;                        // park[park_c .. park_n) are waiting
+    // moves landed pieces from the ring into the park registers (when those are empty) and asks for as many new ones
+    auto park_pieces = [&]() {
+        if (park_c != park_n) return;
+        const int avail = stream.issued - consumed;
+        const int n = avail < kStepPark ? avail : kStepPark;
+        park_c = 0;
+        park_n = n;
+#pragma unroll
+        for (int dd = 0; dd < kStepPark; ++dd)
+            if (dd < n) {
+                int sl = cslot + dd;
+                if (sl >= kStepRing) sl -= kStepRing;
+                park[dd] = *reinterpret_cast<const v4i *>(&lds.ring[wave][sl][lane * 16]);
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // the slots are read before new pieces may land in them
+        consumed += n;
+        cslot += n;
+        if (cslot >= kStepRing) cslot -= kStepRing;
+        for (int k = 0; k < n; ++k) stream_issue(stream, a, lds, block, wave, lane);
+    };
 
     for (int ph = 0; ph < a.n_phases; ++ph) {
         const StepPhase P = a.phases[ph];
@@ -439,26 +464,38 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 if (lane < 16) lds.partial[j][wave][lane] = sum;
                 acc = 0;
             };
-            for (int i = share.i0; i < share.i1; ++i) {
-                // The piece to multiply was asked for kStepRing pieces ago (fewer at the very end of the step): it
-                // has landed once at most the younger pieces are still on their way (loads return in order).
-                if (stream.issued - consumed == kStepRing) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kStepRing - 1) : "memory");
-                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
+            auto multiply = [&](const v4i w) {
                 const v4i x = *reinterpret_cast<const v4i *>(lds.xs + (4 * q + (lane >> 4)) * 16);
                 acc = __builtin_amdgcn_sdot8(w.x, x.x, acc, false);
                 acc = __builtin_amdgcn_sdot8(w.y, x.y, acc, false);
                 acc = __builtin_amdgcn_sdot8(w.z, x.z, acc, false);
                 acc = __builtin_amdgcn_sdot8(w.w, x.w, acc, false);
-                // the slot is free (its contents are in registers: the products above needed them)
-                stream_issue(stream, a, lds, block, wave, lane);
-                ++consumed;
-                cslot = cslot + 1 == kStepRing ? 0 : cslot + 1;
                 if (++q == share.Q) {
                     flush();
                     q = 0;
                     ++j;
                 }
+            };
+            int i = share.i0;
+            // first the pieces parked in registers (they are the oldest), then the ring
+#pragma unroll
+            for (int dd = 0; dd < kStepPark; ++dd)
+                if (dd >= park_c && dd < park_n && i < share.i1) {
+                    multiply(park[dd]);
+                    ++park_c;
+                    ++i;
+                }
+            for (; i < share.i1; ++i) {
+                // The piece to multiply was asked for kStepRing pieces ago (fewer at the very end of the step): it
+                // has landed once at most the younger pieces are still on their way (loads return in order).
+                if (stream.issued - consumed == kStepRing) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kStepRing - 1) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
+                multiply(w);
+                // the slot is free (its contents are in registers: the products above needed them)
+                stream_issue(stream, a, lds, block, wave, lane);
+                ++consumed;
+                cslot = cslot + 1 == kStepRing ? 0 : cslot + 1;
             }
             if (share.i0 < share.i1 && q != 0) flush();
         }
@@ -519,6 +556,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         STEP_STAMP(3);
         ++bar;
         step_arrive(a, gen0 + bar);
+        park_pieces();                                 // (everything in the ring has landed: the arrival waited for it)
         STEP_STAMP(4);
         if (P.kind == kStepQkv) {
             // attention of the new token over the layer's cache: one workgroup per head
