@@ -573,7 +573,7 @@ sqap_status sqap_group_free(sqap_group *g);
  * nonzero word (it copies 8 bytes back and SYNCHRONISES the stream; the word is cleared when a step starts).
  * A captured step can be replayed from a HIP graph.
  * EINVAL: null pointer, a handle that is not a weight, shapes that do not fit each other, negative
- * past.  EUNSUPPORTED: head size not a multiple of 8 or above 128, hidden or ffn above 12288 or not a
+ * past.  EUNSUPPORTED: head size not a multiple of 8 or above 128, hidden above 4096, ffn above 12288, either not a
  * multiple of 128, more than 256 heads, a linear with more than 16 groups of 16 channels per compute unit
  * (N above 65536), operands not 16-byte aligned.  ENOMEM / EDEVICE.
  */

@@ -78,33 +78,55 @@ struct DecodeAttnLds {
 };
 static_assert(sizeof(float) * kDecRedFloats >= kDecMaxRow * sizeof(__half), "the staged row must fit the reduction buffer");
 
-// One half of a buffer that another workgroup of the SAME launch wrote (agent-scope load of the 32-bit
-// word that holds it), or a plain load when the buffer was complete before the launch.
-template <bool AGENT>
-__device__ __forceinline__ __half read_half(const __half *p, int64_t i)
+// __syncthreads() is a release and an acquire fence around the barrier, and the release waits for every
+// load and store of the wavefront, global ones included.  A wavefront that keeps a stream of weight loads in
+// flight must not wait for those at every barrier: where the barrier only hands LDS contents from wavefront
+// to wavefront, waiting for the wavefront's own LDS operations is enough (they complete in order, and a completed
+// LDS write is visible to the whole workgroup).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// 16 bytes of LDS as a plain vector.  (Accesses typed as the uint4 class make the compiler wait for every load
+// in flight that lands in LDS, the weight stream included: it takes them as possibly the same memory.  The
+// kernels wait for what they read themselves.)
+typedef int sqap_v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 lds_load16(const void *p)
 {
-    if (!AGENT) return p[i];
-    const unsigned w = __hip_atomic_load(reinterpret_cast<const unsigned *>(p) + (i >> 1), __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
-    return __ushort_as_half((unsigned short)((i & 1) ? w >> 16 : w & 0xffffu));
+    const sqap_v4i v = *reinterpret_cast<const sqap_v4i *>(p);
+    return make_uint4((unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w);
 }
+__device__ __forceinline__ void lds_store16(void *p, const uint4 v)
+{
+    *reinterpret_cast<sqap_v4i *>(p) = sqap_v4i{(int)v.x, (int)v.y, (int)v.z, (int)v.w};
+}
+
+// The half in the low 16 bits of a tagged word (the whole-step kernel's rows: the high 16 bits say which
+// step and layer wrote the word).
+__device__ __forceinline__ __half untag(unsigned w) { return __ushort_as_half((unsigned short)(w & 0xffffu)); }
 
 // Rotation of head h's query and key of the new token (same arithmetic as rope_kernel), cache append (rotated
 // key | value into row `past` of KV), attention of the query over cache rows 0 .. past, output into
 // O[h * d .. h * d + d) (and into trace, when given).  Called by EVERY thread of the workgroup (it contains
 // workgroup barriers); the first 256 threads do the work, any others only keep step.  LDS in `lds`.
-// AGENT: QKV was written by other workgroups of this launch and O is read by others (agent-scope loads and
-// stores); d even, d <= 128.
-// In the AGENT form (the whole-step kernel) `sincos_tab` (d / 2 pairs of binary64 sine, cosine of the token's
-// angles, evaluated once per step by the same sincos call) replaces the evaluation per layer: same bits.
+// TAGGED (the whole-step kernel): the new token's q, k, v of this head were fetched by the caller as tagged
+// words into LDS (`staged`: q at word 0, k at 256, v at 512; QKV is not used); O is a row of tagged words
+// that other workgroups of the launch wait for (64-bit agent-scope stores, tag `tag`); `sincos_tab` (d / 2 pairs
+// of binary64 sine, cosine of the token's angles, evaluated once per step by the same sincos call) replaces the
+// evaluation per layer: same bits.  d even, d <= 128.
 // (V_LATE asks for the value rows after the scores instead of together with the key rows: half the
 // registers for one more memory round trip; not used at present.)
-template <bool AGENT>
+template <bool TAGGED>
 __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h, const __half *QKV, int pos0, int H,
                                                       int d, double base, __half *KV, int64_t ldkv, int past,
-                                                      __half *O, __half *trace, const RopeFreq &freq,
-                                                      const double2 *sincos_tab = nullptr)
+                                                      void *O, __half *trace, const RopeFreq &freq,
+                                                      const double2 *sincos_tab = nullptr, const unsigned *staged = nullptr,
+                                                      unsigned tag = 0)
 {
+    constexpr bool AGENT = TAGGED;
+    // (tagged form: the wavefronts have weight loads in flight; what the barriers below hand over is in LDS)
+    auto sync = [] {
+        if constexpr (TAGGED) lds_barrier();
+        else __syncthreads();
+    };
     float *qf = lds.qf, *sc = lds.sc, *ored = lds.ored, *wred = lds.wred;
     __half *knew = lds.knew, *vnew = lds.vnew;
     int t = threadIdx.x;
@@ -132,12 +154,21 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
     const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
     __half qkv_new[6] = {};
     if (t < half_d) {
-        qkv_new[0] = read_half<AGENT>(q, t);
-        qkv_new[1] = read_half<AGENT>(q, t + half_d);
-        qkv_new[2] = read_half<AGENT>(k, t);
-        qkv_new[3] = read_half<AGENT>(k, t + half_d);
-        qkv_new[4] = read_half<AGENT>(v, t);
-        qkv_new[5] = read_half<AGENT>(v, t + half_d);
+        if constexpr (TAGGED) {
+            qkv_new[0] = untag(staged[t]);
+            qkv_new[1] = untag(staged[t + half_d]);
+            qkv_new[2] = untag(staged[256 + t]);
+            qkv_new[3] = untag(staged[256 + t + half_d]);
+            qkv_new[4] = untag(staged[512 + t]);
+            qkv_new[5] = untag(staged[512 + t + half_d]);
+        } else {
+            qkv_new[0] = q[t];
+            qkv_new[1] = q[t + half_d];
+            qkv_new[2] = k[t];
+            qkv_new[3] = k[t + half_d];
+            qkv_new[4] = v[t];
+            qkv_new[5] = v[t + half_d];
+        }
     }
     constexpr bool V_LATE = false;
     uint4 kraw[kDecKeys], vraw[V_LATE ? 1 : kDecKeys];
@@ -176,7 +207,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         global_store_half(vrow + i, v0);
         global_store_half(vrow + i + half_d, v1);
     }
-    __syncthreads();
+    sync();
 
     float q8[8];
 #pragma unroll
@@ -197,8 +228,8 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
                 if (!V_LATE) vraw[j] = cached(vbase, key);
             }
             if (key == past && col_ok) {
-                kraw[j] = *reinterpret_cast<const uint4 *>(knew + c * 8);
-                if (!V_LATE) vraw[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
+                kraw[j] = lds_load16(knew + c * 8);
+                if (!V_LATE) vraw[j] = lds_load16(vnew + c * 8);
             }
         }
 #pragma unroll
@@ -219,17 +250,17 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             for (int j = 0; j < kDecKeys; ++j) {
                 const int key = c0 + 16 * j + grp;
                 vlate[j] = cached(vbase, key);
-                if (key == past && col_ok) vlate[j] = *reinterpret_cast<const uint4 *>(vnew + c * 8);
+                if (key == past && col_ok) vlate[j] = lds_load16(vnew + c * 8);
             }
         }
-        __syncthreads();
+        sync();
         float mx = -INFINITY;
         for (int i = t; i < n; i += 256) mx = fmaxf(mx, sc[i]);
         for (int x = 32; x > 0; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x));
         if (lane == 0 && wave < 4) wred[wave] = mx;
-        __syncthreads();
+        sync();
         const float m_new = fmaxf(m, fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3])));
-        __syncthreads();                               // wred is reused for the sum
+        sync();                               // wred is reused for the sum
         float sum = 0.f;
         for (int i = t; i < n; i += 256) {
             const float pj = expf(sc[i] - m_new);
@@ -238,7 +269,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         }
         for (int x = 32; x > 0; x >>= 1) sum += __shfl_xor(sum, x);
         if (lane == 0 && wave < 4) wred[wave] = sum;
-        __syncthreads();
+        sync();
         const float rescale = expf(m - m_new);         // m = -inf only before the first chunk: exp(-inf) = 0
         l = l * rescale + ((wred[0] + wred[1]) + (wred[2] + wred[3]));
         m = m_new;
@@ -254,13 +285,13 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
         }
-        __syncthreads();                               // sc and wred are rewritten by the next chunk
+        sync();                               // sc and wred are rewritten by the next chunk
     }
     if (col_ok) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) ored[grp * kDecMaxD + c * 8 + e] = o[e];
     }
-    __syncthreads();
+    sync();
     {
         float acc = 0.f;
         if (t < d) {
@@ -268,16 +299,16 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             for (int g = 0; g < 16; ++g) acc += ored[g * kDecMaxD + t];
         }
         const __half r = __float2half_rn(acc * (1.0f / l));
-        if (!AGENT) {
-            if (t < d) O[(int64_t)h * d + t] = r;
+        if constexpr (!TAGGED) {
+            if (t < d) reinterpret_cast<__half *>(O)[(int64_t)h * d + t] = r;
         } else {
-            // two halves per 32-bit agent-scope store (d is even, so a pair never leaves the head)
+            // two tagged words per 64-bit agent-scope store (d is even, so a pair never leaves the head)
             const unsigned mine = __half_as_ushort(r), next = __shfl_down(mine, 1);
             if (t < d && (t & 1) == 0) {
-                const unsigned w = mine | (next << 16);
-                __hip_atomic_store(reinterpret_cast<unsigned *>(O + (int64_t)h * d + t), w, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-                if (trace) *reinterpret_cast<unsigned *>(trace + (int64_t)h * d + t) = w;
+                const unsigned long long lo = (tag << 16) | mine, hi = (tag << 16) | next;
+                __hip_atomic_store(reinterpret_cast<unsigned long long *>(reinterpret_cast<unsigned *>(O) + (int64_t)h * d + t),
+                                   lo | (hi << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (trace) *reinterpret_cast<unsigned *>(trace + (int64_t)h * d + t) = mine | (next << 16);
             }
         }
     }

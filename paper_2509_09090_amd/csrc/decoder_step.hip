@@ -6,32 +6,49 @@
 // 7B shape against 0.52 ms for the weights alone.  Here one workgroup per compute unit stays resident for
 // the whole step and walks the linears in order:
 //
-//   phase  = [glue in front of the linear, redone by every workgroup] -> [its share of the linear] -> barrier
+//   phase  = [wait for the row the linear needs] -> [glue in front of the linear, redone by every workgroup]
+//            -> [its share of the linear] -> [its outputs, tagged]
 //   layer  = norm -> q|k|v | attention | quantize -> o | add, norm -> gate|up (+ SwiGLU) | quantize -> down
 //
-//   * The input of a linear is one row of at most 11008 values: every workgroup rebuilds it for itself (residual
+//   * The input of a linear is one row of at most 12288 values: every workgroup rebuilds it for itself (residual
 //     add, RMSNorm with the exact sum of squares, int4 quantization: the arithmetic of the fused quantizer
-//     kernels, statement by statement) and keeps the codes in LDS.  Nothing but the small rows between the
-//     linears crosses workgroups, through agent-scope stores and loads.
+//     kernels, statement by statement) and keeps the codes in LDS.  The residual stream never leaves the
+//     workgroups: each keeps its own copy of the row in LDS and adds every update to it.
 //   * A linear's output channels are dealt to the workgroups in runs of 16-channel groups; inside a
-//     workgroup the eight wavefronts split the run's reduction axis evenly and add through LDS.  With one
+//     workgroup the seven streaming wavefronts split the run's reduction axis evenly and add through LDS.  With one
 //     token there is nothing for a matrix core to reuse: each lane multiplies 32 weight codes of its
 //     channel with the 32 activation codes by four v_dot8_i32_i4 (signed int4 x int4 -> int32, exact, no
 //     widening).  A 1 KiB wavefront load is 16 channels x 4 pieces in the packed weight layout.
-//   * Weights do not depend on activations, so the weight stream never waits for them: every wavefront
-//     walks ITS pieces of all the linears of the step as one sequence, fifteen 1 KiB loads ahead of what
+//   * Weights do not depend on activations, so the weight stream never waits for them: every streaming wavefront
+//     walks ITS pieces of all the linears of the step as one sequence, twelve 1 KiB loads ahead of what
 //     it multiplies, whatever phase those pieces belong to.  The loads land in a ring in LDS
-//     (global_load_lds_dwordx4: no registers held, slots addressed at run time), 120 KiB per compute unit:
-//     while the workgroup waits at a barrier or rebuilds an input row, the next linear's weights, and
-//     often those of the one after, are arriving.  A full ring would stop the stream for the rest of the
-//     wait (slots only free up when their pieces are multiplied), so on arriving at a barrier a wavefront
-//     moves the eight oldest landed pieces into registers and asks for eight more.
+//     (global_load_lds_dwordx4: no registers held, slots addressed at run time), 84 KiB per compute unit:
+//     while the workgroup waits for a row or rebuilds it, the next linear's weights, and often those of the one
+//     after, are arriving.  A full ring would stop the stream for the rest of the wait (slots only free up
+//     when their pieces are multiplied), so before it waits a wavefront moves the eight oldest landed pieces
+//     into registers and asks for eight more.
 //   * gate and up channels are dealt in pairs, so the workgroup that owns a pair applies SwiGLU to it and only
 //     h = silu(g) * u crosses to the down projection.
-//   * The barrier: every workgroup owns one 64-bit flag; arriving is a store of the launch's generation plus
-//     the barrier's number, waiting is 256 lanes polling the 256 flags.  No read-modify-write atomics.  The
-//     generation lives in device memory and moves on with every launch, so a launch captured in a graph can
-//     be replayed.  All 256 workgroups must be resident at once: one per compute unit, checked at creation.
+//   * What crosses workgroups (q|k|v, the attention output, o, h, the down projection's output) travels as
+//     32-bit words: the half in the low 16 bits, a TAG in the high 16 bits that names the step and the place in
+//     it (generation + 5 * layer + 1 .. 5) where the row is produced.  A producer stores its words and goes on
+//     (nothing waits for a store); a consumer reads the row (straight into LDS, agent scope) and reads again
+//     the 1 KiB pieces in which some word does not carry the tag it expects.  One trip through the memory
+//     system per dependency, where a flag needs four (data complete, flag up, flag seen, data fetched); a word is
+//     written by one 32- or 64-bit store, so it is never half old.  There is no barrier: a workgroup only ever
+//     waits for the rows it needs.  A row buffer is rewritten one layer later; by then every workgroup that
+//     takes part in the linears in between has read it (each of those needs a complete row that depends on
+//     that read).  A workgroup that fell behind regardless finds a newer tag than it waits for, gives up after
+//     a bounded number of reads and raises the error word: late is reported, never computed with.
+//   * Loads of a wavefront return in order, and a store counts as a load: a wavefront with weight loads in
+//     flight would see the rows it polls only after all those loads have landed.  So the eighth wavefront
+//     of the workgroup streams no weights: it reads the rows (and the norm gains and weight scales) into
+//     LDS, where all eight work on them.
+//   * Barriers inside the workgroup wait for the wavefront's LDS operations only (lds_barrier): __syncthreads()
+//     would also wait for every weight load in flight, several times per phase.
+//   * The generation lives in device memory and moves on with every launch (the last workgroup to finish
+//     writes it), so a launch captured in a graph can be replayed.  All 256 workgroups must be resident at
+//     once: one per compute unit, checked at creation.
 #include <new>
 #include <vector>
 
@@ -44,14 +61,20 @@ namespace sqap {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kStepThreads = 512, kStepWaves = 8;
-constexpr int kStepRing = 15;              // 1 KiB weight loads in flight (or landed, not yet used) per wavefront
-constexpr int kStepPark = 8;               // landed pieces a wavefront moves from the ring into registers at a barrier
+constexpr int kStepStreamWaves = 7;        // wavefronts 0 .. 6 stream weights; wavefront 7 reads the rows
+constexpr int kStepGlueWave = 7;
+constexpr int kStepRing = 12;              // 1 KiB weight loads in flight (or landed, not yet used) per streaming wavefront
+constexpr int kStepPark = 8;               // landed pieces a wavefront moves from the ring into registers before it waits
 constexpr int kStepMaxGroups = 16;         // 16-channel groups a workgroup owns in one phase
 constexpr int kStepGpt = 3;                // groups of 8 row elements per thread: K <= 12288
 constexpr int kStepMaxK = kStepThreads * 8 * kStepGpt;
-constexpr long long kStepSpinLimit = 400000;      // polls of a flag before a wait gives up (about a second)
+constexpr int kStepMaxHidden = 4096;       // the residual row in LDS; a tagged row and the gains side by side
+constexpr int kStepTagsPerLayer = 5;       // q|k|v, attention, o, h, down
+constexpr int kStepRetryLimit = 100000;     // times a row is read again because a word was late
+constexpr long long kStepPollLimit = 200000;      // reads of a row before a wait gives up (a few tenths of a second)
 
 enum StepKind { kStepQkv = 0, kStepO = 1, kStepGateUp = 2, kStepDown = 3, kStepHead = 4 };
+enum StepTag { kTagQkv = 1, kTagAttn = 2, kTagO = 3, kTagH = 4, kTagDown = 5 };
 
 struct StepPhase {
     int kind;
@@ -67,55 +90,67 @@ struct StepPhase {
 
 struct StepArgs {
     const StepPhase *phases;
-    int n_phases, blocks;
+    int n_phases, blocks, n_layers;
     int hidden, ffn, H, d;
     float eps;
     double base;
     const __half *x_in;     // [hidden] the token's embedding
     const int32_t *pos;     // [1]
     int past;
-    __half *r1, *r2;        // residual stream after the attention block / after the feed-forward of the layer before
-    __half *qkv, *attn, *o, *h, *dn;
+    unsigned *qkv, *attn, *o, *h, *dn;     // tagged rows
     __half *logits;
     __half *attn_trace;     // nullable: [layers, hidden]
-    unsigned long long *flags, *gen, *err;
+    unsigned long long *flags, *gen, *err, *done;   // flags: one per workgroup
     RopeFreq freq;
 };
 
+constexpr int kStepStageWords = kStepMaxK;             // a tagged row of the longest kind
+constexpr int kStepStageNew = 10240;                   // word offset of the staged q, k, v of the new token (3 x 256 words)
 struct StepLds {
     __attribute__((aligned(16))) uint8_t xs[kStepMaxK / 2];                       // the linear's input row as int4 codes
     __attribute__((aligned(16))) int partial[kStepMaxGroups][kStepWaves][16];      // per wavefront sums of a group's 16 channels
+    __attribute__((aligned(16))) unsigned swl[kStepMaxGroups * 8];                 // weight scales of the workgroup's channels (pairs)
     unsigned long long wsum[2 * kStepWaves];
     float wmax[kStepWaves];
     float sx;
-    int dead;               // a wait gave up: later waits return at once (the step's result is wrong and says so)
+    int stale[2];           // some word of the row just read does not carry its tag yet (by attempt parity)
+    int dead;               // a wait gave up: later waits read once and return (the step's result is wrong and says so)
     double2 sincos_tab[kDecMaxD / 2];      // sine, cosine of the token's rotation angles (the same for every layer)
-    DecodeAttnLds attn;
-    __attribute__((aligned(16))) uint8_t ring[kStepWaves][kStepRing][1024];         // weights asked for, per wavefront
+    __attribute__((aligned(16))) __half resid[kStepMaxHidden];                    // the residual stream (this workgroup's copy)
+    union {                                // the attention runs between two fetches
+        __attribute__((aligned(16))) unsigned stage[kStepStageWords];             // rows as fetched: tagged words; the gains behind them
+        DecodeAttnLds attn;
+    };
+    __attribute__((aligned(16))) uint8_t ring[kStepStreamWaves][kStepRing][1024];   // weights asked for, per streaming wavefront
 };
 static_assert(sizeof(StepLds) <= 160 * 1024, "one workgroup per compute unit: all of its LDS");
+static_assert(sizeof(DecodeAttnLds) <= kStepStageNew * 4 && (kStepStageNew + 3 * 256) <= kStepStageWords,
+              "the new token's staged q, k, v sit behind the attention's own LDS");
+static_assert(kStepMaxHidden * 4 + kStepMaxHidden * 2 <= kStepStageWords * 4, "a tagged row and the gains");
 
-// ---- small rows that cross workgroups: agent-scope accesses, 8 elements (two 64-bit words) at a time ----
-__device__ __forceinline__ void load8(const __half *p, int g, float (&f)[8])
+// An entry of the phase table, read through the constant address space: the table is never written while the
+// kernel runs and the index is wavefront-uniform, so these become scalar loads, which do not queue behind the
+// weight loads in flight (a vector load would: the first use of its result waits for every older load).
+__device__ __forceinline__ StepPhase load_phase(const StepPhase *table, int ph)
 {
-    const unsigned long long *w = reinterpret_cast<const unsigned long long *>(p) + 2 * (size_t)g;
-    const unsigned long long a = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned long long b = __hip_atomic_load(w + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    uint4 raw = make_uint4((unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32));
-    unpack_halves(raw, f);
+    typedef const __attribute__((address_space(4))) unsigned long long *Words;
+    static_assert(sizeof(StepPhase) == 64, "eight 64-bit words");
+    const Words w = (Words)(unsigned long long)(table + __builtin_amdgcn_readfirstlane(ph));
+    unsigned long long v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = w[i];
+    StepPhase P;
+    __builtin_memcpy(&P, v, sizeof(P));
+    return P;
 }
 
-__device__ __forceinline__ void store8(__half *p, int g, const float (&f)[8])
+// 64 lanes x 16 bytes from global memory into 1 KiB of LDS at `to` (wavefront-uniform), no registers in between.
+// AGENT: the load is coherent at agent scope (sc1).  Completion: vmcnt.
+template <bool AGENT>
+__device__ __forceinline__ void fetch_piece(const void *lane_from, void *to)
 {
-    uint4 raw;
-    __half2 *h2 = reinterpret_cast<__half2 *>(&raw);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) h2[q] = __floats2half2_rn(f[2 * q], f[2 * q + 1]);
-    unsigned long long *w = reinterpret_cast<unsigned long long *>(p) + 2 * (size_t)g;
-    __hip_atomic_store(w, (unsigned long long)raw.x | ((unsigned long long)raw.y << 32), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(w + 1, (unsigned long long)raw.z | ((unsigned long long)raw.w << 32), __ATOMIC_RELAXED,
-                       __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_global_load_lds(reinterpret_cast<const SQAP_GLOBAL v4i *>((unsigned long long)lane_from),
+                                     (__attribute__((address_space(3))) void *)to, 16, 0, AGENT ? 16 : 0);
 }
 
 // The empty asm makes x exist as a binary32 value: otherwise the compiler folds the operation that produced it
@@ -126,11 +161,32 @@ __device__ __forceinline__ float to_half_value(float x)
     return __half2float(__float2half_rn(x));
 }
 
-// Residual update and RMSNorm of the row in v (thread t owns groups t, t + 512, ... of 8 elements), exactly as
-// the fused quantizer kernel does it:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (a half is an
+// eight tagged words -> their halves as floats
+__device__ __forceinline__ void untag8(const unsigned *w, float (&f)[8])
+{
+    const uint4 a = lds_load16(w), b = lds_load16(w + 4);
+    const unsigned x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = __half2float(__ushort_as_half((unsigned short)(x[e] & 0xffffu)));
+}
+
+// two adjacent outputs as tagged words, one 64-bit store (agent scope: written through to where every
+// workgroup reads)
+__device__ __forceinline__ void store_tagged_pair(unsigned *row, int n, float y0, float y1, unsigned tag)
+{
+    const unsigned long long lo = (tag << 16) | __half_as_ushort(__float2half_rn(y0));
+    const unsigned long long hi = (tag << 16) | __half_as_ushort(__float2half_rn(y1));
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(row + n), lo | (hi << 32), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Residual update and RMSNorm (thread t owns groups t, t + 512, ... of 8 elements), exactly as the fused
+// quantizer kernel does it:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (a half is an
 // integer below 2^11 times 2^e, e >= -24, so x^2 * 2^48 is an integer: the sum does not depend on the order);
-// r = (float)(1 / sqrt(S / K + eps)) in binary64;  v = half((x' * r) * gamma).  Contains a barrier.
-__device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const __half *delta, __half *xsum_out,
+// r = (float)(1 / sqrt(S / K + eps)) in binary64;  v = half((x' * r) * gamma).  x is the residual row in LDS,
+// which receives x'; delta (nullable) is a row of tagged words in LDS, gamma a row of halves in LDS.
+// Contains a barrier.
+__device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const unsigned *delta, __half *resid,
                                           const __half *gamma, float eps, StepLds &lds)
 {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6, groups = K >> 3;
@@ -139,13 +195,18 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
     for (int gi = 0; gi < kStepGpt; ++gi) {
         const int g = t + gi * kStepThreads;
         if (g < groups) {
+            unpack_halves(lds_load16(resid + 8 * g), v[gi]);
             if (delta) {
                 float dl[8];
-                load8(delta, g, dl);
+                untag8(delta + 8 * g, dl);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[gi][e] = to_half_value(v[gi][e] + dl[e]);
+                uint4 raw;
+                __half2 *h2 = reinterpret_cast<__half2 *>(&raw);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) h2[q] = __floats2half2_rn(v[gi][2 * q], v[gi][2 * q + 1]);
+                lds_store16(resid + 8 * g, raw);
             }
-            if (xsum_out) store8(xsum_out, g, v[gi]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const unsigned bits = __half_as_ushort(__float2half_rn(v[gi][e]));      // exact: v is a half value
@@ -158,6 +219,9 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
                 lo += add_lo;
                 hi += add_hi + (lo < add_lo ? 1ull : 0ull);
             }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
         }
     }
     for (int o = 32; o > 0; o >>= 1) {
@@ -169,7 +233,7 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
         lds.wsum[2 * wave] = hi;
         lds.wsum[2 * wave + 1] = lo;
     }
-    __syncthreads();
+    lds_barrier();
     hi = lds.wsum[0];
     lo = lds.wsum[1];
 #pragma unroll
@@ -195,7 +259,7 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
         const int g = t + gi * kStepThreads;
         if (g < groups) {
             float gm[8];
-            unpack_halves(global_load16(reinterpret_cast<const uint4 *>(gamma) + g), gm);
+            unpack_halves(lds_load16(gamma + 8 * g), gm);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float xr = v[gi][e] * r;
@@ -219,9 +283,9 @@ __device__ __forceinline__ void step_quantize(const float (&v)[kStepGpt][8], int
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
         }
     for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
-    __syncthreads();                                   // earlier readers of wmax and xs are done
+    lds_barrier();                                   // earlier readers of wmax and xs are done
     if (lane == 0) lds.wmax[wave] = amax;
-    __syncthreads();
+    lds_barrier();
     amax = lds.wmax[0];
 #pragma unroll
     for (int w = 1; w < kStepWaves; ++w) amax = fmaxf(amax, lds.wmax[w]);
@@ -239,7 +303,7 @@ __device__ __forceinline__ void step_quantize(const float (&v)[kStepGpt][8], int
             reinterpret_cast<uint32_t *>(lds.xs)[g] = packed;
         }
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 // ---- a workgroup's share of a linear ----
@@ -257,8 +321,12 @@ __device__ __forceinline__ StepShare step_share(const StepPhase &P, int block, i
     s.n_groups = (u1 - s.u0) * (P.kind == kStepGateUp ? 2 : 1);
     s.Q = P.chunks >> 2;
     const int total = s.n_groups * s.Q;
-    s.i0 = total * wave / kStepWaves;
-    s.i1 = total * (wave + 1) / kStepWaves;
+    if (wave < kStepStreamWaves) {
+        s.i0 = total * wave / kStepStreamWaves;
+        s.i1 = total * (wave + 1) / kStepStreamWaves;
+    } else {
+        s.i0 = s.i1 = 0;                               // the glue wavefront streams nothing
+    }
     return s;
 }
 
@@ -293,7 +361,7 @@ struct StepStream {
 __device__ __forceinline__ void stream_enter(StepStream &c, const StepArgs &a, int block, int wave, int lane)
 {
     while (c.ph < a.n_phases) {
-        const StepPhase &P = a.phases[c.ph];
+        const StepPhase P = load_phase(a.phases, c.ph);
         const StepShare sh = step_share(P, block, a.blocks, wave);
         if (sh.i0 < sh.i1) {
             c.i = sh.i0;
@@ -323,38 +391,75 @@ __device__ __forceinline__ void stream_issue(StepStream &c, const StepArgs &a, S
         stream_enter(c, a, block, wave, lane);
     } else if (c.q == c.Q) {                           // the next group of the share
         c.q = 0;
-        const StepPhase &P = a.phases[c.ph];
+        const StepPhase P = load_phase(a.phases, c.ph);
         const StepShare sh = step_share(P, block, a.blocks, wave);
         c.lane_ptr = reinterpret_cast<const uint8_t *>(step_item(P, sh, c.i, lane));
     }
 }
 
-__device__ __forceinline__ void step_arrive(const StepArgs &a, unsigned long long value)
+// Every workgroup says how far it has got (generation + 5 * layer + 1 .. 5: everything it produces up to
+// that point has been STORED, not necessarily arrived) in a flag of its own.  The glue wavefront reads the 256
+// flags, four per lane, until all have reached `value`: a cheap hint that the row is worth reading.  The tags
+// in the row decide.  False when it gave up.
+__device__ __forceinline__ bool poll_flags(const unsigned long long *flags, int blocks, unsigned long long value, int lane,
+                                           bool dead)
 {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores of the phase are complete
-    __syncthreads();
-    if (threadIdx.x == 0) __hip_atomic_store(&a.flags[blockIdx.x], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (dead) return false;
+    for (long long round = 0;; ++round) {
+        unsigned long long seen[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int f = lane + 64 * k;
+            seen[k] = __hip_atomic_load(&flags[f < blocks ? f : blocks - 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const int here = (int)(seen[0] >= value) & (int)(seen[1] >= value) & (int)(seen[2] >= value) & (int)(seen[3] >= value);
+        if (__all(here)) return true;
+        if (round > kStepPollLimit) return false;
+        __builtin_amdgcn_s_sleep(1);
+    }
 }
 
-__device__ __forceinline__ void step_wait(const StepArgs &a, unsigned long long value, StepLds &lds)
+// The glue wavefront waits for rows: `n` pieces of up to 1 KiB (piece(p, from, to, lanes): this lane's 16 bytes
+// in global memory, the piece's place in LDS, the lanes that take part) are read into LDS until every word of
+// every piece carries `tag` in its high half; pieces that do are not read again.  False when it gave up (or
+// gave up before: then one read, so that LDS holds something to go on with).
+template <class Piece>
+__device__ __forceinline__ bool poll_pieces(int n, Piece piece, unsigned tag, int lane, bool dead)
 {
-    const int t = threadIdx.x;
-    if (t < a.blocks && lds.dead == 0) {
-        long long spins = 0;
-        while (__hip_atomic_load(&a.flags[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < value) {
-            __builtin_amdgcn_s_sleep(2);
-            if (++spins > kStepSpinLimit) {            // give up: the step's result is wrong, and says so
-                __hip_atomic_store(a.err, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                lds.dead = 1;
-                break;
+    unsigned long long pending = n >= 64 ? ~0ull : (1ull << n) - 1ull;
+    const unsigned want = tag << 16;
+    const long long limit = dead ? 0 : kStepPollLimit;
+    for (long long round = 0; pending; ++round) {
+        if (round > limit) return false;
+        for (unsigned long long m = pending; m; m &= m - 1) {
+            const int p = __builtin_ctzll(m);
+            const unsigned *from;
+            unsigned *to;
+            int lanes;
+            piece(p, from, to, lanes);
+            if (lane < lanes) fetch_piece<true>(from, to);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (unsigned long long m = pending; m; m &= m - 1) {
+            const int p = __builtin_ctzll(m);
+            const unsigned *from;
+            unsigned *to;
+            int lanes;
+            piece(p, from, to, lanes);
+            int ok = 1;
+            if (lane < lanes) {
+                const uint4 w = lds_load16(to + 4 * lane);
+                ok = (int)((w.x & 0xffff0000u) == want) & (int)((w.y & 0xffff0000u) == want) &
+                     (int)((w.z & 0xffff0000u) == want) & (int)((w.w & 0xffff0000u) == want);
             }
+            if (__all(ok)) pending &= ~(1ull << p);
         }
     }
-    __syncthreads();
+    return true;
 }
 
 // Diagnostic builds (-DSQAP_STEP_STAMPS) record the 100 MHz wall clock of four workgroups at eight points of every
-// phase into the attention trace buffer; product builds compile the macro away.
+// phase behind the attention trace; product builds compile the macro away.
 #ifdef SQAP_STEP_STAMPS
 #define STEP_STAMP(k)                                                                                       \
     do {                                                                                                    \
@@ -371,28 +476,40 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     StepLds &lds = *reinterpret_cast<StepLds *>(smem);
     const int t = threadIdx.x, lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const bool glue = wave == kStepGlueWave;
     const int block = blockIdx.x;
     const unsigned long long gen0 = *a.gen;            // left by the launch before this one
-    unsigned long long bar = 0;
+    auto tag_of = [&](int layer, int what) { return (unsigned)((gen0 + (unsigned long long)(kStepTagsPerLayer * layer + what)) & 0xffffull); };
     const int pos0 = a.pos[0];
     if (block == 0 && t == 0) __hip_atomic_store(a.err, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (t == 0) lds.dead = 0;
+    if (t == 0) {
+        lds.dead = 0;
+        lds.stale[0] = lds.stale[1] = 0;
+    }
     if (block < a.H && t < (a.d >> 1)) {               // the rotation's sines and cosines: once per step instead of per layer
         double sn, cs;
         sincos(rope_angle(a.freq, pos0, t, a.d, a.base), &sn, &cs);
         lds.sincos_tab[t] = double2{sn, cs};
     }
-    __syncthreads();
+    if (glue) {                                        // the token's embedding starts the residual stream
+        for (int g0 = 0; g0 < (a.hidden >> 3); g0 += 64)
+            if (g0 + lane < (a.hidden >> 3))
+                fetch_piece<false>(reinterpret_cast<const uint4 *>(a.x_in) + g0 + lane, lds.resid + g0 * 8);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    lds_barrier();
 
     StepStream stream = {};
-    stream_enter(stream, a, block, wave, lane);
+    stream_enter(stream, a, block, wave, lane);        // (the glue wavefront's sequence is empty)
     for (int k = 0; k < kStepRing; ++k) stream_issue(stream, a, lds, block, wave, lane);
     int consumed = 0, cslot = 0;                       // pieces that have left the ring so far; ring slot of the oldest one in it
     v4i park[kStepPark];                               // the oldest pieces not yet multiplied, moved out of the ring
     int park_c = 0, park_n = 0;                        // park[park_c .. park_n) are waiting
-    // moves landed pieces from the ring into the park registers (when those are empty) and asks for as many new ones
+    // A streaming wavefront that is about to wait: once the pieces it asked for have landed it moves the oldest
+    // into the park registers (when those are empty) and asks for as many new ones.
     auto park_pieces = [&]() {
-        if (park_c != park_n) return;
+        if (glue || park_c != park_n) return;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const int avail = stream.issued - consumed;
         const int n = avail < kStepPark ? avail : kStepPark;
         park_c = 0;
@@ -410,51 +527,123 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         if (cslot >= kStepRing) cslot -= kStepRing;
         for (int k = 0; k < n; ++k) stream_issue(stream, a, lds, block, wave, lane);
     };
+    // the glue wavefront's wait gave up
+    auto give_up = [&](int ph, int what) {
+        if (!lds.dead) __hip_atomic_store(a.err, ((unsigned long long)(ph + 1) << 8) | (unsigned long long)what, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lds.dead = 1;
+    };
 
     for (int ph = 0; ph < a.n_phases; ++ph) {
-        const StepPhase P = a.phases[ph];
+        const StepPhase P = load_phase(a.phases, ph);
         const StepShare share = step_share(P, block, a.blocks, wave);
+        const StepShare all = step_share(P, block, a.blocks, 0);                  // (the group numbers do not depend on the wavefront)
+        const bool gate_up = P.kind == kStepGateUp;
+        const int n_out = gate_up ? all.n_groups >> 1 : all.n_groups;             // groups of 16 outputs
+        const int K = P.K, groups = K >> 3;
         STEP_STAMP(0);
-        // ---- the linear's input row: built by every workgroup for itself ----
-        {
-            float v[kStepGpt][8];
-            const int K = P.K, groups = K >> 3;
-            const __half *src = nullptr, *delta = nullptr;
-            __half *xsum = nullptr;
-            if (P.kind == kStepQkv) {
-                src = P.layer == 0 ? a.x_in : a.r2;
-                delta = P.layer == 0 ? nullptr : a.dn;
-                xsum = a.r1;
-            } else if (P.kind == kStepGateUp) {
-                src = a.r1;
-                delta = a.o;
-                xsum = a.r2;
-            } else if (P.kind == kStepHead) {
-                src = a.r2;
-                delta = a.dn;
-            } else if (P.kind == kStepO) {
-                src = a.attn;
-            } else {
-                src = a.h;
+        // ---- the row this linear needs: an update of the residual stream (q|k|v, gate|up, head) or its whole input ----
+        const unsigned *row = nullptr;
+        int row_at = 0;                                // where in the step the row is produced: 5 * layer + 1 .. 5
+        if (P.kind == kStepQkv) {
+            row = P.layer == 0 ? nullptr : a.dn;
+            row_at = kStepTagsPerLayer * (P.layer - 1) + kTagDown;
+        } else if (P.kind == kStepGateUp) {
+            row = a.o;
+            row_at = kStepTagsPerLayer * P.layer + kTagO;
+        } else if (P.kind == kStepHead) {
+            row = a.dn;
+            row_at = kStepTagsPerLayer * (P.layer - 1) + kTagDown;
+        } else if (P.kind == kStepO) {
+            row = all.n_groups ? a.attn : nullptr;     // (a workgroup with no channels of a linear skips its input)
+            row_at = kStepTagsPerLayer * P.layer + kTagAttn;
+        } else {
+            row = all.n_groups ? a.h : nullptr;
+            row_at = kStepTagsPerLayer * P.layer + kTagH;
+        }
+        __half *st_gamma = reinterpret_cast<__half *>(lds.stage + K);             // the gains, behind the tagged row
+        const unsigned row_tag = (unsigned)((gen0 + (unsigned long long)row_at) & 0xffffull);
+        // The glue wavefront waits for the flags, then reads the row once; every thread checks the tags of the words
+        // it is going to use.  A word that arrived later than its workgroup's flag is rare: then the row is read again.
+        for (int attempt = 0;; ++attempt) {
+            if (glue) {
+                // 1 KiB per instruction, straight into LDS (lane l's 16 bytes land at l * 16: the rows keep their layout)
+                if (P.gamma && attempt == 0)
+                    for (int g0 = 0; g0 < groups; g0 += 64)
+                        if (g0 + lane < groups)
+                            fetch_piece<false>(reinterpret_cast<const uint4 *>(P.gamma) + g0 + lane, st_gamma + g0 * 8);
+                if (row) {
+                    if (attempt == 0 && !poll_flags(a.flags, a.blocks, gen0 + (unsigned long long)row_at, lane, lds.dead != 0)) give_up(ph, 1);
+                    const unsigned *from = row + lane * 4;
+                    const int full = K >> 8;
+                    for (int p = 0; p < full; ++p) fetch_piece<true>(from + p * 256, lds.stage + p * 256);
+                    if ((K & 255) && lane < ((K & 255) >> 2)) fetch_piece<true>(from + full * 256, lds.stage + full * 256);
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            } else if (attempt == 0) {
+                park_pieces();
             }
+            lds_barrier();
+            if (!row) break;
+            if (t == 0) lds.stale[(attempt + 1) & 1] = 0;      // (last read before the barrier above)
+            unsigned bad = 0;
+            const unsigned want = row_tag << 16;
 #pragma unroll
             for (int gi = 0; gi < kStepGpt; ++gi) {
                 const int g = t + gi * kStepThreads;
                 if (g < groups) {
-                    load8(src, g, v[gi]);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
+                    const uint4 w0 = lds_load16(lds.stage + 8 * g), w1 = lds_load16(lds.stage + 8 * g + 4);
+                    bad |= (w0.x ^ want) | (w0.y ^ want) | (w0.z ^ want) | (w0.w ^ want) | (w1.x ^ want) | (w1.y ^ want) |
+                           (w1.z ^ want) | (w1.w ^ want);
                 }
             }
-            if (P.gamma) step_norm(v, K, delta, block == 0 ? xsum : nullptr, P.gamma, a.eps, lds);
-            step_quantize(v, K, lds);
+            if (__any((bad >> 16) != 0) && lane == 0) lds.stale[attempt & 1] = 1;
+            lds_barrier();
+            if (!lds.stale[attempt & 1] || lds.dead) break;
+            if (attempt >= kStepRetryLimit) {
+                if (glue) give_up(ph, 3);
+                lds_barrier();                         // (every wavefront has read `dead` above)
+                break;
+            }
+            if (glue) __builtin_amdgcn_s_sleep(8);
         }
         STEP_STAMP(1);
-        // ---- this workgroup's channels: the wavefronts split the reduction axis ----
-        for (int i = t; i < kStepMaxGroups * kStepWaves * 16; i += kStepThreads) (&lds.partial[0][0][0])[i] = 0;
-        __syncthreads();
         {
+            float v[kStepGpt][8];
+            if (P.gamma) {
+                step_norm(v, K, row ? lds.stage : nullptr, lds.resid, st_gamma, a.eps, lds);
+            } else {
+#pragma unroll
+                for (int gi = 0; gi < kStepGpt; ++gi) {
+                    const int g = t + gi * kStepThreads;
+                    if (g < groups && row) {
+                        untag8(lds.stage + 8 * g, v[gi]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
+                    }
+                }
+            }
+            step_quantize(v, K, lds);
+        }
+        STEP_STAMP(2);
+        // ---- this workgroup's channels: the streaming wavefronts split the reduction axis ----
+        for (int i = t; i < kStepMaxGroups * kStepWaves * 16; i += kStepThreads) (&lds.partial[0][0][0])[i] = 0;
+        lds_barrier();
+        if (glue) {
+            // meanwhile: the weight scales of the workgroup's channels, two per word (padded to whole groups)
+            unsigned sc[2] = {};
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int w = lane + 64 * it;
+                if (w < all.n_groups * 8) sc[it] = *(const SQAP_GLOBAL unsigned *)(P.sw + step_group(P, all, w >> 3) * 16 + (w & 7) * 2);
+            }
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+                if (lane + 64 * it < all.n_groups * 8) lds.swl[lane + 64 * it] = sc[it];
+            // (a wait the compiler can see: otherwise it takes the loads above as possibly in flight wherever the
+            // paths of the wavefronts meet again, and makes the streaming wavefronts wait there)
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+        } else {
             int acc = 0;
             int j = share.i0 < share.i1 ? share.i0 / share.Q : 0, q = share.i0 < share.i1 ? share.i0 - j * share.Q : 0;
             auto flush = [&]() {
@@ -487,7 +676,8 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 }
             for (; i < share.i1; ++i) {
                 // The piece to multiply was asked for kStepRing pieces ago (fewer at the very end of the step): it
-                // has landed once at most the younger pieces are still on their way (loads return in order).
+                // has landed once at most the younger pieces are still on their way (loads return in order; the
+                // wavefront's output stores are in the same queue and at worst make this wait a little longer).
                 if (stream.issued - consumed == kStepRing) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kStepRing - 1) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
@@ -499,81 +689,95 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             }
             if (share.i0 < share.i1 && q != 0) flush();
         }
-        __syncthreads();
-        STEP_STAMP(2);
-        // ---- outputs: two adjacent channels per thread (one 32-bit agent-scope store) ----
-        {
+        lds_barrier();
+        STEP_STAMP(3);
+        // ---- outputs: two adjacent channels per thread; nothing waits for the stores ----
+        if (t < n_out * 8) {
             const float sxf = lds.sx;
-            const bool gate_up = P.kind == kStepGateUp;
-            const int n_out = gate_up ? share.n_groups >> 1 : share.n_groups;        // groups of 16 outputs
-            if (t < n_out * 8) {
-                const int jo = t >> 3, row = (t & 7) * 2;
-                auto channel_pair = [&](int j, float (&y)[2]) {       // dequantised outputs of local group j, rows row, row + 1
-                    int s0 = 0, s1 = 0;
+            const int jo = t >> 3, row2 = (t & 7) * 2;
+            auto channel_pair = [&](int j, float (&y)[2]) {       // dequantised outputs of local group j, rows row2, row2 + 1
+                int s0 = 0, s1 = 0;
 #pragma unroll
-                    for (int w = 0; w < kStepWaves; ++w) {
-                        s0 += lds.partial[j][w][row];
-                        s1 += lds.partial[j][w][row + 1];
+                for (int w = 0; w < kStepStreamWaves; ++w) {
+                    s0 += lds.partial[j][w][row2];
+                    s1 += lds.partial[j][w][row2 + 1];
+                }
+                const unsigned swb = lds.swl[j * 8 + (t & 7)];
+                const __half2 sw2 = *reinterpret_cast<const __half2 *>(&swb);
+                float y0 = ((float)s0 * sxf) * __low2float(sw2), y1 = ((float)s1 * sxf) * __high2float(sw2);
+                asm volatile("" : "+v"(y0), "+v"(y1));            // two binary32 products, then one rounding to half
+                y[0] = __half2float(__float2half_rn(y0));
+                y[1] = __half2float(__float2half_rn(y1));
+            };
+            const int n = (all.u0 + jo) * 16 + row2;
+            float y[2];
+            if (!gate_up) {
+                channel_pair(jo, y);
+                if (n < P.N) {
+                    if (P.kind == kStepHead) {
+                        const __half2 pk = __floats2half2_rn(y[0], y[1]);
+                        *(SQAP_GLOBAL unsigned *)(a.logits + n) = *reinterpret_cast<const unsigned *>(&pk);
+                    } else if (P.kind == kStepQkv) {
+                        store_tagged_pair(a.qkv, n, y[0], y[1], tag_of(P.layer, kTagQkv));
+                    } else if (P.kind == kStepO) {
+                        store_tagged_pair(a.o, n, y[0], y[1], tag_of(P.layer, kTagO));
+                    } else {
+                        store_tagged_pair(a.dn, n, y[0], y[1], tag_of(P.layer, kTagDown));
                     }
-                    const int n = step_group(P, share, j) * 16 + row;
-                    const unsigned swb = *(const SQAP_GLOBAL unsigned *)(P.sw + n);       // two scales; padded to whole row groups
-                    const __half2 sw2 = *reinterpret_cast<const __half2 *>(&swb);
-                    float y0 = ((float)s0 * sxf) * __low2float(sw2), y1 = ((float)s1 * sxf) * __high2float(sw2);
-                    asm volatile("" : "+v"(y0), "+v"(y1));            // two binary32 products, then one rounding to half
-                    y[0] = __half2float(__float2half_rn(y0));
-                    y[1] = __half2float(__float2half_rn(y1));
-                };
-                float y[2];
-                int n;
-                __half *out;
-                if (!gate_up) {
-                    channel_pair(jo, y);
-                    n = (share.u0 + jo) * 16 + row;
-                    out = P.kind == kStepQkv ? a.qkv : P.kind == kStepO ? a.o : P.kind == kStepDown ? a.dn : a.logits;
-                } else {
-                    // h = half(silu(g) * u), silu(g) = (float)(g / (1 + exp(-g))) in binary64
-                    float g2[2], u2[2];
-                    channel_pair(2 * jo, g2);
-                    channel_pair(2 * jo + 1, u2);
+                }
+            } else {
+                // h = half(silu(g) * u), silu(g) = (float)(g / (1 + exp(-g))) in binary64
+                float g2[2], u2[2];
+                channel_pair(2 * jo, g2);
+                channel_pair(2 * jo + 1, u2);
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const double gd = (double)g2[e];
-                        const float sl = (float)(gd / (1.0 + exp(-gd)));
-                        y[e] = to_half_value(sl * u2[e]);
-                    }
-                    n = (share.u0 + jo) * 16 + row;
-                    out = a.h;
+                for (int e = 0; e < 2; ++e) {
+                    const double gd = (double)g2[e];
+                    const float sl = (float)(gd / (1.0 + exp(-gd)));
+                    y[e] = to_half_value(sl * u2[e]);
                 }
-                const int n_limit = gate_up ? P.N >> 1 : P.N;
-                if (n < n_limit) {
-                    const __half2 pk = __floats2half2_rn(y[0], y[1]);
-                    __hip_atomic_store(reinterpret_cast<unsigned *>(out + n), *reinterpret_cast<const unsigned *>(&pk),
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                if (n < (P.N >> 1)) store_tagged_pair(a.h, n, y[0], y[1], tag_of(P.layer, kTagH));
             }
         }
-        // ---- barrier, with the next linear's first weights asked for before the wait ----
-        STEP_STAMP(3);
-        ++bar;
-        step_arrive(a, gen0 + bar);
-        park_pieces();                                 // (everything in the ring has landed: the arrival waited for it)
-        STEP_STAMP(4);
-        if (P.kind == kStepQkv) {
-            // attention of the new token over the layer's cache: one workgroup per head
-            step_wait(a, gen0 + bar, lds);
-            STEP_STAMP(5);
-            if (block < a.H)
-                decode_attention_head<true>(lds.attn, block, a.qkv, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn,
-                                            a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq, lds.sincos_tab);
-            STEP_STAMP(6);
-            ++bar;
-            step_arrive(a, gen0 + bar);
+        // how far this workgroup has got (a workgroup without a head has nothing to add to the attention's row)
+        const bool attends = P.kind == kStepQkv && block < a.H;
+        if (P.kind != kStepHead && !attends && t == (n_out * 8 > 64 ? 64 : 0)) {
+            const int at = kStepTagsPerLayer * P.layer + (P.kind == kStepQkv ? kTagAttn : P.kind == kStepO ? kTagO : gate_up ? kTagH : kTagDown);
+            __hip_atomic_store(&a.flags[block], gen0 + (unsigned long long)at, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        step_wait(a, gen0 + bar, lds);
-        STEP_STAMP(7);
+        STEP_STAMP(4);
+        if (attends) {
+            // attention of the new token over the layer's cache: one workgroup per head; its q, k, v come as three
+            // pieces of d tagged words
+            if (glue) {
+                const bool ok = poll_pieces(3,
+                                            [&](int p, const unsigned *&from, unsigned *&to, int &lanes) {
+                                                from = a.qkv + (size_t)p * a.hidden + (size_t)block * a.d + lane * 4;
+                                                to = lds.stage + kStepStageNew + p * 256;
+                                                lanes = a.d >> 2;
+                                            },
+                                            tag_of(P.layer, kTagQkv), lane, lds.dead != 0);
+                if (!ok) give_up(ph, 2);
+            }
+            lds_barrier();
+            STEP_STAMP(5);
+            decode_attention_head<true>(lds.attn, block, nullptr, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn,
+                                        a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq, lds.sincos_tab,
+                                        lds.stage + kStepStageNew, tag_of(P.layer, kTagAttn));
+            if (t == 64)
+                __hip_atomic_store(&a.flags[block], gen0 + (unsigned long long)(kStepTagsPerLayer * P.layer + kTagAttn), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            lds_barrier();                           // its LDS is where the next row lands
+            STEP_STAMP(6);
+        }
     }
-    // every workgroup has read the generation (it took part in a barrier since): move it on for the next launch
-    if (block == 0 && t == 0) *a.gen = gen0 + bar;
+    // The last workgroup to get here moves the generation on for the next launch: by then every workgroup has
+    // read it.  (One read-modify-write per workgroup and launch.)
+    if (t == 0) {
+        const unsigned long long before = __hip_atomic_fetch_add(a.done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((before + 1ull) % (unsigned long long)a.blocks == 0ull)
+            __hip_atomic_store(a.gen, gen0 + (unsigned long long)(kStepTagsPerLayer * a.n_layers), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -583,9 +787,9 @@ struct Decoder {
     float eps;
     double base;
     StepPhase *phases;          // device
-    __half *rows;               // device: r1, r2, qkv, attn, o, h, dn
-    unsigned long long *sync;   // device: flags[256], generation, error word
-    size_t off_r2, off_qkv, off_attn, off_o, off_h, off_dn;
+    unsigned *rows;             // device, tagged words: qkv, attn, o, h, dn
+    unsigned long long *sync;   // device: generation, error word, count of finished workgroups, flags[256]
+    size_t off_attn, off_o, off_h, off_dn;
 };
 constexpr uint32_t kDecoderMagic = 0x53514443u;  // "SQDC"
 constexpr int kStepBlocks = 256;
@@ -608,6 +812,8 @@ sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n
     if (hw->K != hidden) return fail(SQAP_EINVAL, "sqap_decoder_create: head K = %d, hidden = %d", hw->K, hidden);
     if ((head_dim & 7) || head_dim > kDecMaxD) return fail(SQAP_EUNSUPPORTED, "sqap_decoder_create: head size %d (multiple of 8, <= %d)", head_dim, kDecMaxD);
     if (n_heads > kStepBlocks) return fail(SQAP_EUNSUPPORTED, "sqap_decoder_create: %d heads (at most %d)", n_heads, kStepBlocks);
+    if (hidden > kStepMaxHidden) return fail(SQAP_EUNSUPPORTED, "sqap_decoder_create: hidden = %d above %d", hidden, kStepMaxHidden);
+    if ((long long)kStepTagsPerLayer * n_layers >= 65536) return fail(SQAP_EUNSUPPORTED, "sqap_decoder_create: %d layers", n_layers);
     int ffn = 0;
     std::vector<StepPhase> ph;
     auto add = [&](int kind, int layer, const Weight *w, const sqap_f16 *gamma, sqap_f16 *kv, long long ldkv) {
@@ -681,14 +887,12 @@ sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n
     d->phases = nullptr;
     d->rows = nullptr;
     d->sync = nullptr;
-    auto round8 = [](size_t n) { return (n + 63) & ~(size_t)63; };
-    size_t off = round8(hidden);
-    d->off_r2 = off; off += round8(hidden);
-    d->off_qkv = off; off += round8(3 * (size_t)hidden);
-    d->off_attn = off; off += round8(hidden);
-    d->off_o = off; off += round8(hidden);
-    d->off_h = off; off += round8(d->ffn);
-    d->off_dn = off; off += round8(hidden);
+    auto round64 = [](size_t n) { return (n + 63) & ~(size_t)63; };
+    size_t off = round64(3 * (size_t)hidden);       // q|k|v first
+    d->off_attn = off; off += round64(hidden);
+    d->off_o = off; off += round64(hidden);
+    d->off_h = off; off += round64(d->ffn);
+    d->off_dn = off; off += round64(hidden);
     hipError_t e = hipGetDevice(&d->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d->device);
@@ -699,10 +903,13 @@ sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n
     }
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&d->phases), sizeof(StepPhase) * ph.size());
     if (e == hipSuccess) e = hipMemcpy(d->phases, ph.data(), sizeof(StepPhase) * ph.size(), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&d->rows), off * sizeof(__half));
-    if (e == hipSuccess) e = hipMemset(d->rows, 0, off * sizeof(__half));
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&d->sync), (kStepBlocks + 2) * sizeof(unsigned long long));
-    if (e == hipSuccess) e = hipMemset(d->sync, 0, (kStepBlocks + 2) * sizeof(unsigned long long));
+    // rows start with tag 0 everywhere, the generation at 1: the first step waits for tags from 2 on
+    std::vector<unsigned long long> sync0(3 + kStepBlocks, 0ull);
+    sync0[0] = 1ull;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&d->rows), off * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(d->rows, 0, off * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&d->sync), sync0.size() * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemcpy(d->sync, sync0.data(), sync0.size() * sizeof(unsigned long long), hipMemcpyHostToDevice);
     if (e == hipSuccess)
         e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decoder_step_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(StepLds));
@@ -724,6 +931,7 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
     a.phases = d->phases;
     a.n_phases = d->n_phases;
     a.blocks = d->blocks;
+    a.n_layers = d->n_layers;
     a.hidden = d->hidden;
     a.ffn = d->ffn;
     a.H = d->H;
@@ -733,18 +941,17 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
     a.x_in = reinterpret_cast<const __half *>(x);
     a.pos = pos;
     a.past = past;
-    a.r1 = d->rows;
-    a.r2 = d->rows + d->off_r2;
-    a.qkv = d->rows + d->off_qkv;
+    a.qkv = d->rows;
     a.attn = d->rows + d->off_attn;
     a.o = d->rows + d->off_o;
     a.h = d->rows + d->off_h;
     a.dn = d->rows + d->off_dn;
     a.logits = reinterpret_cast<__half *>(logits);
     a.attn_trace = reinterpret_cast<__half *>(attn_trace);
-    a.flags = d->sync;
-    a.gen = d->sync + kStepBlocks;
-    a.err = d->sync + kStepBlocks + 1;
+    a.gen = d->sync;
+    a.err = d->sync + 1;
+    a.done = d->sync + 2;
+    a.flags = d->sync + 3;
     a.freq = rope_frequencies(d->d, d->base);
     hipLaunchKernelGGL(decoder_step_kernel, dim3(d->blocks), dim3(kStepThreads), sizeof(StepLds), st, a);
     SQAP_HIP_CHECK(hipGetLastError());
@@ -753,7 +960,7 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
 
 sqap_status decoder_error(const Decoder *d, unsigned long long *word_out, hipStream_t st)
 {
-    SQAP_HIP_CHECK(hipMemcpyAsync(word_out, d->sync + kStepBlocks + 1, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
+    SQAP_HIP_CHECK(hipMemcpyAsync(word_out, d->sync + 1, sizeof(unsigned long long), hipMemcpyDeviceToHost, st));
     SQAP_HIP_CHECK(hipStreamSynchronize(st));
     return SQAP_OK;
 }
