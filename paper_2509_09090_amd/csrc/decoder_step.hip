@@ -70,6 +70,7 @@ constexpr int kStepGpt = 3;                // groups of 8 row elements per threa
 constexpr int kStepMaxK = kStepThreads * 8 * kStepGpt;
 constexpr int kStepMaxHidden = 4096;       // the residual row in LDS; a tagged row and the gains side by side
 constexpr int kStepTagsPerLayer = 5;       // q|k|v, attention, o, h, down
+constexpr int kStepWarmKeys = 2048;         // cached keys whose rows a workgroup warms the L2 cache with before its attention
 constexpr int kStepRetryLimit = 100000;     // times a row is read again because a word was late
 constexpr long long kStepPollLimit = 200000;      // reads of a row before a wait gives up (a few tenths of a second)
 
@@ -105,6 +106,7 @@ struct StepArgs {
 };
 
 constexpr int kStepStageWords = kStepMaxK;             // a tagged row of the longest kind
+constexpr int kStepStageWarm = 10240 + 3 * 256;       // word offset of 1 KiB that only receives the cache-warming loads
 constexpr int kStepStageNew = 10240;                   // word offset of the staged q, k, v of the new token (3 x 256 words)
 struct StepLds {
     __attribute__((aligned(16))) uint8_t xs[kStepMaxK / 2];                       // the linear's input row as int4 codes
@@ -124,7 +126,7 @@ struct StepLds {
     __attribute__((aligned(16))) uint8_t ring[kStepStreamWaves][kStepRing][1024];   // weights asked for, per streaming wavefront
 };
 static_assert(sizeof(StepLds) <= 160 * 1024, "one workgroup per compute unit: all of its LDS");
-static_assert(sizeof(DecodeAttnLds) <= kStepStageNew * 4 && (kStepStageNew + 3 * 256) <= kStepStageWords,
+static_assert(sizeof(DecodeAttnLds) <= kStepStageNew * 4 && (kStepStageWarm + 256) <= kStepStageWords,
               "the new token's staged q, k, v sit behind the attention's own LDS");
 static_assert(kStepMaxHidden * 4 + kStepMaxHidden * 2 <= kStepStageWords * 4, "a tagged row and the gains");
 
@@ -161,15 +163,6 @@ __device__ __forceinline__ float to_half_value(float x)
     return __half2float(__float2half_rn(x));
 }
 
-// eight tagged words -> their halves as floats
-__device__ __forceinline__ void untag8(const unsigned *w, float (&f)[8])
-{
-    const uint4 a = lds_load16(w), b = lds_load16(w + 4);
-    const unsigned x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = __half2float(__ushort_as_half((unsigned short)(x[e] & 0xffffu)));
-}
-
 // two adjacent outputs as tagged words, one 64-bit store (agent scope: written through to where every
 // workgroup reads)
 __device__ __forceinline__ void store_tagged_pair(unsigned *row, int n, float y0, float y1, unsigned tag)
@@ -180,67 +173,48 @@ __device__ __forceinline__ void store_tagged_pair(unsigned *row, int n, float y0
                        __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Residual update and RMSNorm (thread t owns groups t, t + 512, ... of 8 elements), exactly as the fused
-// quantizer kernel does it:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (a half is an
-// integer below 2^11 times 2^e, e >= -24, so x^2 * 2^48 is an integer: the sum does not depend on the order);
-// r = (float)(1 / sqrt(S / K + eps)) in binary64;  v = half((x' * r) * gamma).  x is the residual row in LDS,
-// which receives x'; delta (nullable) is a row of tagged words in LDS, gamma a row of halves in LDS.
-// Contains a barrier.
-__device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const unsigned *delta, __half *resid,
-                                          const __half *gamma, float eps, StepLds &lds)
+// ---- the pieces of the fused quantizer kernels' arithmetic, statement by statement ----
+// RMSNorm:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (a half is an integer below 2^11 times 2^e,
+// e >= -24, so x^2 * 2^48 is an integer: the sum does not depend on the order);  r = (float)(1 / sqrt(S / K + eps))
+// in binary64;  y = half((x' * r) * gamma).
+// Quantizer:  scale = half(max|y| / 7) (2^-24 when that is zero), code = clamp(rint(y / scale), -8, 7).
+
+// adds the squares of eight half values (times 2^48) to the 128-bit sum hi:lo
+__device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long long &hi, unsigned long long &lo)
 {
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, groups = K >> 3;
-    unsigned long long hi = 0, lo = 0;
 #pragma unroll
-    for (int gi = 0; gi < kStepGpt; ++gi) {
-        const int g = t + gi * kStepThreads;
-        if (g < groups) {
-            unpack_halves(lds_load16(resid + 8 * g), v[gi]);
-            if (delta) {
-                float dl[8];
-                untag8(delta + 8 * g, dl);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) v[gi][e] = to_half_value(v[gi][e] + dl[e]);
-                uint4 raw;
-                __half2 *h2 = reinterpret_cast<__half2 *>(&raw);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) h2[q] = __floats2half2_rn(v[gi][2 * q], v[gi][2 * q + 1]);
-                lds_store16(resid + 8 * g, raw);
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned bits = __half_as_ushort(__float2half_rn(v[gi][e]));      // exact: v is a half value
-                const unsigned ex = (bits >> 10) & 31u, man = bits & 1023u;
-                const unsigned long long m = ex ? man + 1024u : man;
-                const int sh = ex ? 2 * (int)ex - 2 : 0;                                // 2e + 48, at most 58
-                const unsigned long long m2 = m * m;                                    // below 2^22
-                const unsigned long long add_lo = m2 << sh;
-                const unsigned long long add_hi = sh > 42 ? m2 >> (64 - sh) : 0ull;
-                lo += add_lo;
-                hi += add_hi + (lo < add_lo ? 1ull : 0ull);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
-        }
+    for (int e = 0; e < 8; ++e) {
+        const unsigned bits = __half_as_ushort(__float2half_rn(v[e]));      // exact: v is a half value
+        const unsigned ex = (bits >> 10) & 31u, man = bits & 1023u;
+        const unsigned long long m = ex ? man + 1024u : man;
+        const int sh = ex ? 2 * (int)ex - 2 : 0;                                // 2e + 48, at most 58
+        const unsigned long long m2 = m * m;                                    // below 2^22
+        const unsigned long long add_lo = m2 << sh;
+        const unsigned long long add_hi = sh > 42 ? m2 >> (64 - sh) : 0ull;
+        lo += add_lo;
+        hi += add_hi + (lo < add_lo ? 1ull : 0ull);
     }
+}
+
+// the wavefront's 128-bit sum, in every lane
+__device__ __forceinline__ void wave_sum128(unsigned long long &hi, unsigned long long &lo)
+{
     for (int o = 32; o > 0; o >>= 1) {
         const unsigned long long ohi = __shfl_xor(hi, o), olo = __shfl_xor(lo, o);
         lo += olo;
         hi += ohi + (lo < olo ? 1ull : 0ull);
     }
-    if (lane == 0) {
-        lds.wsum[2 * wave] = hi;
-        lds.wsum[2 * wave + 1] = lo;
-    }
-    lds_barrier();
-    hi = lds.wsum[0];
-    lo = lds.wsum[1];
+}
+
+// r from the eight wavefronts' sums (hi, lo pairs)
+__device__ __forceinline__ float norm_factor(const unsigned long long *wsum, int K, float eps)
+{
+    unsigned long long hi = wsum[0], lo = wsum[1];
 #pragma unroll
     for (int w = 1; w < kStepWaves; ++w) {
-        const unsigned long long olo = lds.wsum[2 * w + 1];
+        const unsigned long long olo = wsum[2 * w + 1];
         lo += olo;
-        hi += lds.wsum[2 * w] + (lo < olo ? 1ull : 0ull);
+        hi += wsum[2 * w] + (lo < olo ? 1ull : 0ull);
     }
     double Sd;
     if (hi == 0) {
@@ -253,57 +227,7 @@ __device__ __forceinline__ void step_norm(float (&v)[kStepGpt][8], int K, const 
         Sd = ldexp((double)top, 64 - lz);
     }
     Sd = ldexp(Sd, -48);
-    const float r = (float)(1.0 / sqrt(Sd / (double)K + (double)eps));
-#pragma unroll
-    for (int gi = 0; gi < kStepGpt; ++gi) {
-        const int g = t + gi * kStepThreads;
-        if (g < groups) {
-            float gm[8];
-            unpack_halves(lds_load16(gamma + 8 * g), gm);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float xr = v[gi][e] * r;
-                v[gi][e] = to_half_value(xr * gm[e]);
-            }
-        }
-    }
-}
-
-// Per-token int4 quantization of the row in v into lds.xs (canonical packing) and lds.sx, as the quantizer
-// kernel does it: scale = half(max|v| / 7) (2^-24 when that is zero), code = clamp(rint(v / scale), -8, 7).
-// Contains barriers; on return every thread may read the codes.
-__device__ __forceinline__ void step_quantize(const float (&v)[kStepGpt][8], int K, StepLds &lds)
-{
-    const int t = threadIdx.x, lane = t & 63, wave = t >> 6, groups = K >> 3;
-    float amax = 0.f;
-#pragma unroll
-    for (int gi = 0; gi < kStepGpt; ++gi)
-        if (t + gi * kStepThreads < groups) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
-        }
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
-    lds_barrier();                                   // earlier readers of wmax and xs are done
-    if (lane == 0) lds.wmax[wave] = amax;
-    lds_barrier();
-    amax = lds.wmax[0];
-#pragma unroll
-    for (int w = 1; w < kStepWaves; ++w) amax = fmaxf(amax, lds.wmax[w]);
-    const __half sh = row_scale(amax);
-    const float sf = __half2float(sh);
-    const float rcp = 1.0f / sf;
-    if (t == 0) lds.sx = sf;
-#pragma unroll
-    for (int gi = 0; gi < kStepGpt; ++gi) {
-        const int g = t + gi * kStepThreads;
-        if (g < groups) {
-            uint32_t packed = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) packed |= code4(quotient(v[gi][e], sf, rcp)) << (4 * e);
-            reinterpret_cast<uint32_t *>(lds.xs)[g] = packed;
-        }
-    }
-    lds_barrier();
+    return (float)(1.0 / sqrt(Sd / (double)K + (double)eps));
 }
 
 // ---- a workgroup's share of a linear ----
@@ -561,9 +485,11 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             row_at = kStepTagsPerLayer * P.layer + kTagH;
         }
         __half *st_gamma = reinterpret_cast<__half *>(lds.stage + K);             // the gains, behind the tagged row
-        const unsigned row_tag = (unsigned)((gen0 + (unsigned long long)row_at) & 0xffffull);
+        const unsigned want = (unsigned)((gen0 + (unsigned long long)row_at) & 0xffffull) << 16;
         // The glue wavefront waits for the flags, then reads the row once; every thread checks the tags of the words
-        // it is going to use.  A word that arrived later than its workgroup's flag is rare: then the row is read again.
+        // it uses while it starts on the row.  A word that arrived later than its workgroup's flag is rare: then the
+        // row is read again (nothing has been written by then: the residual row is updated after the check).
+        float v[kStepGpt][8];
         for (int attempt = 0;; ++attempt) {
             if (glue) {
                 // 1 KiB per instruction, straight into LDS (lane l's 16 bytes land at l * 16: the rows keep their layout)
@@ -583,52 +509,111 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 park_pieces();
             }
             lds_barrier();
-            if (!row) break;
-            if (t == 0) lds.stale[(attempt + 1) & 1] = 0;      // (last read before the barrier above)
+            if (attempt == 0) STEP_STAMP(1);
             unsigned bad = 0;
-            const unsigned want = row_tag << 16;
+            unsigned long long hi = 0, lo = 0;
+            float amax = 0.f;
 #pragma unroll
             for (int gi = 0; gi < kStepGpt; ++gi) {
                 const int g = t + gi * kStepThreads;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
                 if (g < groups) {
-                    const uint4 w0 = lds_load16(lds.stage + 8 * g), w1 = lds_load16(lds.stage + 8 * g + 4);
-                    bad |= (w0.x ^ want) | (w0.y ^ want) | (w0.z ^ want) | (w0.w ^ want) | (w1.x ^ want) | (w1.y ^ want) |
-                           (w1.z ^ want) | (w1.w ^ want);
+                    float in[8] = {};
+                    if (row) {
+                        const uint4 w0 = lds_load16(lds.stage + 8 * g), w1 = lds_load16(lds.stage + 8 * g + 4);
+                        bad |= (w0.x ^ want) | (w0.y ^ want) | (w0.z ^ want) | (w0.w ^ want) | (w1.x ^ want) | (w1.y ^ want) |
+                               (w1.z ^ want) | (w1.w ^ want);
+                        const unsigned x[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) in[e] = __half2float(untag(x[e]));
+                    }
+                    if (P.gamma) {                     // the row is an update of the residual stream
+                        unpack_halves(lds_load16(lds.resid + 8 * g), v[gi]);
+                        if (row) {
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) v[gi][e] = to_half_value(v[gi][e] + in[e]);
+                        }
+                        add_squares8(v[gi], hi, lo);
+                    } else {                           // the row is the linear's input
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            v[gi][e] = in[e];
+                            amax = fmaxf(amax, fabsf(in[e]));
+                        }
+                    }
                 }
+            }
+            if (P.gamma) {
+                wave_sum128(hi, lo);
+                if (lane == 0) {
+                    lds.wsum[2 * wave] = hi;
+                    lds.wsum[2 * wave + 1] = lo;
+                }
+            } else {
+                for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+                if (lane == 0) lds.wmax[wave] = amax;
             }
             if (__any((bad >> 16) != 0) && lane == 0) lds.stale[attempt & 1] = 1;
             lds_barrier();
-            if (!lds.stale[attempt & 1] || lds.dead) break;
+            if (t == 0) lds.stale[(attempt + 1) & 1] = 0;      // (its last readers have passed the barrier before this one)
+            if (!row || !lds.stale[attempt & 1] || lds.dead) break;
             if (attempt >= kStepRetryLimit) {
                 if (glue) give_up(ph, 3);
-                lds_barrier();                         // (every wavefront has read `dead` above)
                 break;
             }
             if (glue) __builtin_amdgcn_s_sleep(8);
         }
-        STEP_STAMP(1);
-        {
-            float v[kStepGpt][8];
-            if (P.gamma) {
-                step_norm(v, K, row ? lds.stage : nullptr, lds.resid, st_gamma, a.eps, lds);
-            } else {
+        if (P.gamma) {
+            const float r = norm_factor(lds.wsum, K, a.eps);
+            float amax = 0.f;
 #pragma unroll
-                for (int gi = 0; gi < kStepGpt; ++gi) {
-                    const int g = t + gi * kStepThreads;
-                    if (g < groups && row) {
-                        untag8(lds.stage + 8 * g, v[gi]);
-                    } else {
+            for (int gi = 0; gi < kStepGpt; ++gi) {
+                const int g = t + gi * kStepThreads;
+                if (g < groups) {
+                    if (row) {                         // x' is the residual stream from here on
+                        uint4 raw;
+                        __half2 *h2 = reinterpret_cast<__half2 *>(&raw);
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) v[gi][e] = 0.f;
+                        for (int q = 0; q < 4; ++q) h2[q] = __floats2half2_rn(v[gi][2 * q], v[gi][2 * q + 1]);
+                        lds_store16(lds.resid + 8 * g, raw);
+                    }
+                    float gm[8];
+                    unpack_halves(lds_load16(st_gamma + 8 * g), gm);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float xr = v[gi][e] * r;
+                        v[gi][e] = to_half_value(xr * gm[e]);
+                        amax = fmaxf(amax, fabsf(v[gi][e]));
                     }
                 }
             }
-            step_quantize(v, K, lds);
+            for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+            if (lane == 0) lds.wmax[wave] = amax;
+            lds_barrier();
         }
-        STEP_STAMP(2);
+        {
+            float amax = lds.wmax[0];
+#pragma unroll
+            for (int w = 1; w < kStepWaves; ++w) amax = fmaxf(amax, lds.wmax[w]);
+            const float sf = __half2float(row_scale(amax));
+            const float rcp = 1.0f / sf;
+            if (t == 0) lds.sx = sf;
+#pragma unroll
+            for (int gi = 0; gi < kStepGpt; ++gi) {
+                const int g = t + gi * kStepThreads;
+                if (g < groups) {
+                    uint32_t packed = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) packed |= code4(quotient(v[gi][e], sf, rcp)) << (4 * e);
+                    reinterpret_cast<uint32_t *>(lds.xs)[g] = packed;
+                }
+            }
+        }
         // ---- this workgroup's channels: the streaming wavefronts split the reduction axis ----
         for (int i = t; i < kStepMaxGroups * kStepWaves * 16; i += kStepThreads) (&lds.partial[0][0][0])[i] = 0;
         lds_barrier();
+        STEP_STAMP(2);
         if (glue) {
             // meanwhile: the weight scales of the workgroup's channels, two per word (padded to whole groups)
             unsigned sc[2] = {};
@@ -643,6 +628,21 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             // (a wait the compiler can see: otherwise it takes the loads above as possibly in flight wherever the
             // paths of the wavefronts meet again, and makes the streaming wavefronts wait there)
             __builtin_amdgcn_s_waitcnt(0x0F70);
+            // A workgroup with a head: the cached keys and values it is about to attend over are known since the
+            // step began.  One word of every 128-byte line of them is asked for now (and dropped), so that the
+            // attention's own loads, which sit in the step's dependency chain, find the lines in the L2 cache.
+            if (P.kind == kStepQkv && block < a.H) {
+                const int lines_per_row = (a.d * 2 + 127) >> 7;                   // of the head's part of a key or value row
+                const int n_lines = min(a.past, kStepWarmKeys) * 2 * lines_per_row;
+                for (int i = lane; i < n_lines; i += 64) {
+                    const int key = i / (2 * lines_per_row), part = i - key * 2 * lines_per_row;
+                    const int kv = part / lines_per_row, line = part - kv * lines_per_row;
+                    const __half *at = P.kv + (size_t)key * P.ldkv + (size_t)kv * a.hidden + (size_t)block * a.d + line * 64;
+                    // (into a corner of LDS that nothing reads: a load into LDS holds no register, so nothing
+                    // has to be kept free until it returns)
+                    fetch_piece<false>(at, lds.stage + kStepStageWarm);
+                }
+            }
         } else {
             int acc = 0;
             int j = share.i0 < share.i1 ? share.i0 / share.Q : 0, q = share.i0 < share.i1 ? share.i0 - j * share.Q : 0;
