@@ -108,7 +108,8 @@ __device__ __forceinline__ __half untag(unsigned w) { return __ushort_as_half((u
 // O[h * d .. h * d + d) (and into trace, when given).  Called by EVERY thread of the workgroup (it contains
 // workgroup barriers); the first 256 threads do the work, any others only keep step.  LDS in `lds`.
 // TAGGED (the whole-step kernel): the new token's q, k, v of this head were fetched by the caller as tagged
-// words into LDS (`staged`: q at word 0, k at 256, v at 512; QKV is not used); O is a row of tagged words
+// words into LDS (`staged`: q at word 0, k at 256, v at 512, complete when every thread has reached the
+// function's first barrier; QKV is not used); O is a row of tagged words
 // that other workgroups of the launch wait for (64-bit agent-scope stores, tag `tag`); `sincos_tab` (d / 2 pairs
 // of binary64 sine, cosine of the token's angles, evaluated once per step by the same sincos call) replaces the
 // evaluation per layer: same bits.  d even, d <= 128.
@@ -150,18 +151,13 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         return raw;
     };
     // the new token's query, key and value elements of this lane (rotation pairs i and i + d / 2): asked for
-    // before the cache rows, because loads return in order and the rotation is the longer chain
+    // before the cache rows, because loads return in order and the rotation is the longer chain.  (Tagged form:
+    // they come from LDS, where the caller's fetching wavefront puts them; the cache rows do not depend on
+    // them and are asked for before the barrier that waits for that wavefront.)
     const __half *q = QKV + (int64_t)h * d, *k = QKV + width + (int64_t)h * d, *v = QKV + 2 * width + (int64_t)h * d;
     __half qkv_new[6] = {};
-    if (t < half_d) {
-        if constexpr (TAGGED) {
-            qkv_new[0] = untag(staged[t]);
-            qkv_new[1] = untag(staged[t + half_d]);
-            qkv_new[2] = untag(staged[256 + t]);
-            qkv_new[3] = untag(staged[256 + t + half_d]);
-            qkv_new[4] = untag(staged[512 + t]);
-            qkv_new[5] = untag(staged[512 + t + half_d]);
-        } else {
+    if constexpr (!TAGGED) {
+        if (t < half_d) {
             qkv_new[0] = q[t];
             qkv_new[1] = q[t + half_d];
             qkv_new[2] = k[t];
@@ -176,6 +172,17 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
     for (int j = 0; j < kDecKeys; ++j) {
         kraw[j] = cached(kbase, 16 * j + grp);
         if (!V_LATE) vraw[j] = cached(vbase, 16 * j + grp);
+    }
+    if constexpr (TAGGED) {
+        sync();                                        // the new token's q, k, v are in `staged`
+        if (t < half_d) {
+            qkv_new[0] = untag(staged[t]);
+            qkv_new[1] = untag(staged[t + half_d]);
+            qkv_new[2] = untag(staged[256 + t]);
+            qkv_new[3] = untag(staged[256 + t + half_d]);
+            qkv_new[4] = untag(staged[512 + t]);
+            qkv_new[5] = untag(staged[512 + t + half_d]);
+        }
     }
 
     // rotation of this head's query and key; the value is copied

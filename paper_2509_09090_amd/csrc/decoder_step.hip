@@ -432,7 +432,10 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     // A streaming wavefront that is about to wait: once the pieces it asked for have landed it moves the oldest
     // into the park registers (when those are empty) and asks for as many new ones.
     auto park_pieces = [&]() {
-        if (glue || park_c != park_n) return;
+        if (glue) return;
+        // (a wavefront that held its loads back for the attention asks for them now)
+        while (stream.issued - consumed < kStepRing && stream.ph < a.n_phases) stream_issue(stream, a, lds, block, wave, lane);
+        if (park_c != park_n) return;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const int avail = stream.issued - consumed;
         const int n = avail < kStepPark ? avail : kStepPark;
@@ -665,6 +668,10 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     ++j;
                 }
             };
+            // Loads return in order: the cached keys and values that the attention asks for would arrive behind every
+            // weight piece still on its way.  The wavefronts that will attend ask for no new pieces during this linear
+            // (what they multiply was asked for long ago) and catch up when they next wait.
+            const bool hold = P.kind == kStepQkv && block < a.H && wave < 4;
             int i = share.i0;
             // first the pieces parked in registers (they are the oldest), then the ring
 #pragma unroll
@@ -683,7 +690,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
                 multiply(w);
                 // the slot is free (its contents are in registers: the products above needed them)
-                stream_issue(stream, a, lds, block, wave, lane);
+                if (!hold) stream_issue(stream, a, lds, block, wave, lane);
                 ++consumed;
                 cslot = cslot + 1 == kStepRing ? 0 : cslot + 1;
             }
@@ -694,7 +701,11 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         // ---- outputs: two adjacent channels per thread; nothing waits for the stores ----
         if (t < n_out * 8) {
             const float sxf = lds.sx;
-            const int jo = t >> 3, row2 = (t & 7) * 2;
+            // (what depends on the thread alone is formed here, from a value the compiler takes as new: hoisted out
+            // of the loop over the phases it would sit in registers, in practice in scratch memory, for the whole step)
+            int te = t;
+            asm volatile("" : "+v"(te));
+            const int jo = te >> 3, row2 = (te & 7) * 2;
             auto channel_pair = [&](int j, float (&y)[2]) {       // dequantised outputs of local group j, rows row2, row2 + 1
                 int s0 = 0, s1 = 0;
 #pragma unroll
@@ -702,7 +713,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     s0 += lds.partial[j][w][row2];
                     s1 += lds.partial[j][w][row2 + 1];
                 }
-                const unsigned swb = lds.swl[j * 8 + (t & 7)];
+                const unsigned swb = lds.swl[j * 8 + (te & 7)];
                 const __half2 sw2 = *reinterpret_cast<const __half2 *>(&swb);
                 float y0 = ((float)s0 * sxf) * __low2float(sw2), y1 = ((float)s1 * sxf) * __high2float(sw2);
                 asm volatile("" : "+v"(y0), "+v"(y1));            // two binary32 products, then one rounding to half
@@ -759,7 +770,6 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                                             tag_of(P.layer, kTagQkv), lane, lds.dead != 0);
                 if (!ok) give_up(ph, 2);
             }
-            lds_barrier();
             STEP_STAMP(5);
             decode_attention_head<true>(lds.attn, block, nullptr, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn,
                                         a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq, lds.sincos_tab,
