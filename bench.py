@@ -551,6 +551,41 @@ def decode_forward_leg(torch, B, wl, dev, layers, buf, g, prefix=148, new_tokens
         res["graph_error"] = repr(exc)[:200]
     weight_bytes = nl * (3 * H * H + H * H + 2 * F * H + H * F) // 2 + V * H // 2
     res["GBps_weights_graph"] = weight_bytes / res.get("us_per_token_graph", us_eager) / 1e3
+    res["formulation"] = "chain of launches (nine per layer): every dependency of a real decode step"
+    chain_logits = logits.clone()                         # of the last token generated above
+    # The same step as ONE persistent launch (sqap_decoder_step): same caches, same weights, same token.
+    dec = B.sqap_decoder_create([(layers[l % nd].qkv, layers[l % nd].o, layers[l % nd].gate_up, layers[l % nd].down,
+                                  layers[l % nd].gamma_attn, layers[l % nd].gamma_mlp, caches[l]) for l in range(nl)],
+                                nh, hd, gamma_f, head)
+    logits1 = torch.empty((V,), dtype=torch.float16, device=dev)
+
+    def generate1():
+        for i in range(new_tokens):
+            dec.step(tok[0], p1[i], prefix + i, logits1)
+
+    generate1()
+    torch.cuda.synchronize()
+    one = {"launches_per_token": 1, "status": dec.status(),
+           "logits_equal_chain": bool(torch.equal(logits1.view(torch.int16), chain_logits[0].view(torch.int16)))}
+    e0.record()
+    for _ in range(3):
+        generate1()
+    e1.record()
+    torch.cuda.synchronize()
+    one["us_per_token_eager"] = e0.elapsed_time(e1) * 1e3 / (3 * new_tokens)
+    try:
+        one["us_per_token_graph"] = graph_time_us(torch, generate1, 3, per_graph=1) / new_tokens
+    except Exception as exc:
+        one["graph_error"] = repr(exc)[:200]
+    us1 = min(one["us_per_token_eager"], one.get("us_per_token_graph", float("inf")))
+    one["status_after"] = dec.status()
+    one["GBps_weights"] = weight_bytes / us1 / 1e3
+    one["frac_of_hbm_peak"] = one["GBps_weights"] / HBM_PEAK_GBS
+    one["weight_bytes_per_token"] = weight_bytes
+    one["formulation"] = ("one persistent launch per token (decoder_step_kernel): every dependency of a real decode step, "
+                          "rows between the linears handed from workgroup to workgroup inside the launch")
+    res["step_kernel"] = one
+    dec.free()
     head.free()
     return res
 
@@ -829,6 +864,18 @@ def main():
         torch.cuda.empty_cache()
     if not args.no_layers:
         out["decoder_forward"] = decoder_leg(torch, B, wl, dev)
+        if "decode" in out and "decode" in out["decoder_forward"]:
+            # the real decode step (attention, norms and caches included) beside the linears-only figures above
+            real = out["decoder_forward"]["decode"]
+            out["decode"]["real_step"] = {
+                "chain_of_launches_us_per_token": real.get("us_per_token_graph", real["us_per_token_eager"]),
+                "one_launch_us_per_token": min(real["step_kernel"]["us_per_token_eager"],
+                                               real["step_kernel"].get("us_per_token_graph", float("inf"))),
+                "one_launch_GBps_weights": real["step_kernel"]["GBps_weights"],
+                "one_launch_frac_of_hbm_peak": real["step_kernel"]["frac_of_hbm_peak"],
+                "logits_equal": real["step_kernel"]["logits_equal_chain"],
+                "formulation": "dependency-respecting, whole model: 32 layers with attention over the cache, norms, "
+                               "SwiGLU, cache append, final norm and head; batch 1, 148 cached tokens"}
     out["selection"] = selection_leg(torch, B, wl, dev)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, timed_outputs)

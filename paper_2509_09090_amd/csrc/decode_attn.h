@@ -46,10 +46,10 @@ __device__ __forceinline__ double rope_angle(const RopeFreq &freq, int pos, int 
 }
 
 // Scores: 16 lanes per key, lane c holding columns 8c .. 8c+7 (one 16-byte load per key row); softmax over
-// chunks of 192 keys with the usual running maximum and sum; output: the same lane layout over the value
-// rows, the 16 key groups added through LDS.  All binary32.  A chunk's key AND value rows (12 of each per
-// lane) are asked for at once, the first chunk's before the rotation, whose binary64 sine and cosine are a
-// longer dependent chain than the rest of the function.
+// chunks of 192 keys with the usual running maximum and sum, the probabilities kept in registers; output: the
+// same lane layout over the value rows, the 16 key groups added through LDS.  All binary32.  A chunk's key AND
+// value rows (12 of each per lane) are asked for at once, the first chunk's before the rotation, whose
+// binary64 sine and cosine are a longer dependent chain than the rest of the function.
 constexpr int kDecKeys = 12;              // keys per lane group and chunk: their key and value rows are in flight together
 constexpr int kDecChunk = 16 * kDecKeys;   // keys per softmax chunk
 constexpr int kDecMaxD = 128;              // head size limit: 16 lanes x 8 columns
@@ -72,9 +72,8 @@ constexpr int kDecRedFloats = 16 * kDecMaxD > kDecMaxRow / 2 ? 16 * kDecMaxD : k
 struct DecodeAttnLds {
     __attribute__((aligned(16))) float qf[kDecMaxD];
     __attribute__((aligned(16))) __half knew[kDecMaxD], vnew[kDecMaxD];
-    float sc[kDecChunk];
     __attribute__((aligned(16))) float ored[kDecRedFloats];
-    float wred[4];
+    float wred[12];            // chunk maxima of the four wavefronts (two sets, by chunk parity); their sums
 };
 static_assert(sizeof(float) * kDecRedFloats >= kDecMaxRow * sizeof(__half), "the staged row must fit the reduction buffer");
 
@@ -128,7 +127,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         if constexpr (TAGGED) lds_barrier();
         else __syncthreads();
     };
-    float *qf = lds.qf, *sc = lds.sc, *ored = lds.ored, *wred = lds.wred;
+    float *qf = lds.qf, *ored = lds.ored, *wred = lds.wred;
     __half *knew = lds.knew, *vnew = lds.vnew;
     int t = threadIdx.x;
     // Inside a loop over layers everything below that depends only on the lane is loop invariant; hoisted out, it
@@ -221,11 +220,17 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
     for (int e = 0; e < 8; ++e) q8[e] = col_ok ? qf[c * 8 + e] : 0.f;
     const float inv_sqrt_d = 1.0f / sqrtf((float)d);
 
+    // Softmax over chunks with a running maximum; the probabilities never leave the registers.  After the
+    // 16-lane sums a group's twelve scores are in all of its lanes; the chunk's maximum crosses the wavefronts
+    // through LDS (the only barrier of a chunk); lane c of a group exponentiates score c, the group's lanes
+    // exchange the results; every wavefront keeps the sum of ITS keys' probabilities, rescaled like the output
+    // (the four are added at the end, (w0 + w1) + (w2 + w3)).
     float o[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = 0.f;
-    float m = -INFINITY, l = 0.f;
-    for (int c0 = 0; c0 < Sk; c0 += kDecChunk) {
+    float m = -INFINITY, l_wave = 0.f;
+    int parity = 0;
+    for (int c0 = 0; c0 < Sk; c0 += kDecChunk, parity ^= 1) {
         const int n = min(kDecChunk, Sk - c0);
 #pragma unroll
         for (int j = 0; j < kDecKeys; ++j) {
@@ -239,6 +244,8 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
                 if (!V_LATE) vraw[j] = lds_load16(vnew + c * 8);
             }
         }
+        float sj[kDecKeys];
+        float mx = -INFINITY;
 #pragma unroll
         for (int j = 0; j < kDecKeys; ++j) {
             float kf[8];
@@ -247,8 +254,8 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
 #pragma unroll
             for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
             for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
-            const int key = 16 * j + grp;
-            if (on && c == 0 && key < n) sc[key] = s * inv_sqrt_d;
+            sj[j] = 16 * j + grp < n ? s * inv_sqrt_d : -INFINITY;
+            mx = fmaxf(mx, sj[j]);
         }
         // (late form: the key registers are free now; the value rows arrive during the softmax)
         uint4 vlate[V_LATE ? kDecKeys : 1];
@@ -260,40 +267,36 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
                 if (key == past && col_ok) vlate[j] = lds_load16(vnew + c * 8);
             }
         }
-        sync();
-        float mx = -INFINITY;
-        for (int i = t; i < n; i += 256) mx = fmaxf(mx, sc[i]);
-        for (int x = 32; x > 0; x >>= 1) mx = fmaxf(mx, __shfl_xor(mx, x));
-        if (lane == 0 && wave < 4) wred[wave] = mx;
-        sync();
-        const float m_new = fmaxf(m, fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3])));
-        sync();                               // wred is reused for the sum
-        float sum = 0.f;
-        for (int i = t; i < n; i += 256) {
-            const float pj = expf(sc[i] - m_new);
-            sc[i] = pj;
-            sum += pj;
-        }
-        for (int x = 32; x > 0; x >>= 1) sum += __shfl_xor(sum, x);
-        if (lane == 0 && wave < 4) wred[wave] = sum;
-        sync();
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (lane == 0 && wave < 4) wred[parity * 4 + wave] = mx;
+        sync();                                        // (the other parity's maxima were read before the barrier of the chunk before)
+        const float m_new = fmaxf(m, fmaxf(fmaxf(wred[parity * 4], wred[parity * 4 + 1]), fmaxf(wred[parity * 4 + 2], wred[parity * 4 + 3])));
+        // lane c's score (a chain of selects: the array stays in registers)
+        float mine = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < kDecKeys; ++j) mine = c == j ? sj[j] : mine;
+        const float pm = mine == -INFINITY ? 0.f : expf(mine - m_new);      // (a key past the end, or lanes 12 .. 15)
         const float rescale = expf(m - m_new);         // m = -inf only before the first chunk: exp(-inf) = 0
-        l = l * rescale + ((wred[0] + wred[1]) + (wred[2] + wred[3]));
         m = m_new;
+        float psum = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] *= rescale;
 #pragma unroll
         for (int j = 0; j < kDecKeys; ++j) {
-            const int key = 16 * j + grp;
-            const float pj = key < n ? sc[key] : 0.f;
+            const float pj = __shfl(pm, (lane & 48) | j);
+            psum += pj;
             float vf[8];
             if (!V_LATE) unpack_halves(vraw[j], vf);
             else unpack_halves(vlate[j], vf);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
         }
-        sync();                               // sc and wred are rewritten by the next chunk
+        psum += __shfl_xor(psum, 16);                  // the four groups of the wavefront
+        psum += __shfl_xor(psum, 32);
+        l_wave = l_wave * rescale + psum;
     }
+    if (lane == 0 && wave < 4) wred[8 + wave] = l_wave;
     if (col_ok) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) ored[grp * kDecMaxD + c * 8 + e] = o[e];
@@ -305,6 +308,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
 #pragma unroll
             for (int g = 0; g < 16; ++g) acc += ored[g * kDecMaxD + t];
         }
+        const float l = (wred[8] + wred[9]) + (wred[10] + wred[11]);
         const __half r = __float2half_rn(acc * (1.0f / l));
         if constexpr (!TAGGED) {
             if (t < d) reinterpret_cast<__half *>(O)[(int64_t)h * d + t] = r;
