@@ -564,13 +564,14 @@ sqap_status sqap_group_free(sqap_group *g);
  * wherever the chain is exact (everything but the attention output, which agrees within the fp16
  * tolerance: the order of its binary32 sums is that of sqap_decode_attention).
  *
- * The handle owns a few KiB of device memory for the rows in flight and the barrier flags; the weights,
- * gains and caches are captured by address and must outlive it.  One step at a time per decoder (steps are
+ * The handle owns the device memory of the rows in flight (4 * (7 hidden + ffn) bytes per layer) and of the
+ * workgroups' progress flags; the weights, gains and caches are captured by address and must outlive it.  One step at a time per decoder (steps are
  * ordered on one stream).  logits: [vocab] halves.  attn_trace: NULL, or [n_layers, hidden] halves that
  * receive every layer's attention output (tests feed it to the reference).  The kernel needs all its 256
- * workgroups resident at once (a device with at least 256 compute units; EUNSUPPORTED otherwise).  A wait
- * between workgroups that does not end within a few seconds gives up: sqap_decoder_status then reports a
- * nonzero word (it copies 8 bytes back and SYNCHRONISES the stream; the word is cleared when a step starts).
+ * workgroups resident at once (a device with at least 256 compute units; EUNSUPPORTED otherwise).  A
+ * workgroup's wait for another's output that does not end within a second or so gives up: the step's outputs
+ * are then wrong and sqap_decoder_status reports a nonzero word (it copies 8 bytes back and SYNCHRONISES the
+ * stream; the word is cleared when a step starts).  The decoder stays usable.
  * A captured step can be replayed from a HIP graph.
  * EINVAL: null pointer, a handle that is not a weight, shapes that do not fit each other, negative
  * past.  EUNSUPPORTED: head size not a multiple of 8 or above 128, hidden above 4096, ffn above 12288, either not a

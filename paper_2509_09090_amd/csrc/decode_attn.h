@@ -214,7 +214,6 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
         global_store_half(vrow + i + half_d, v1);
     }
     sync();
-
     float q8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) q8[e] = col_ok ? qf[c * 8 + e] : 0.f;

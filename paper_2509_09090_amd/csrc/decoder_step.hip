@@ -31,24 +31,34 @@
 //     h = silu(g) * u crosses to the down projection.
 //   * What crosses workgroups (q|k|v, the attention output, o, h, the down projection's output) travels as
 //     32-bit words: the half in the low 16 bits, a TAG in the high 16 bits that names the step and the place in
-//     it (generation + 5 * layer + 1 .. 5) where the row is produced.  A producer stores its words and goes on
-//     (nothing waits for a store); a consumer reads the row (straight into LDS, agent scope) and reads again
-//     the 1 KiB pieces in which some word does not carry the tag it expects.  One trip through the memory
-//     system per dependency, where a flag needs four (data complete, flag up, flag seen, data fetched); a word is
-//     written by one 32- or 64-bit store, so it is never half old.  There is no barrier: a workgroup only ever
-//     waits for the rows it needs.  A row buffer is rewritten one layer later; by then every workgroup that
-//     takes part in the linears in between has read it (each of those needs a complete row that depends on
-//     that read).  A workgroup that fell behind regardless finds a newer tag than it waits for, gives up after
-//     a bounded number of reads and raises the error word: late is reported, never computed with.
+//     it (generation + 5 * layer + 1 .. 5) where the row is produced.  A producer stores its words, then its
+//     progress flag, and goes on: nothing waits for a store.  A consumer polls the 256 flags (2 KiB, cheap) until
+//     all producers have got that far, reads the row once, straight into LDS, and every thread checks the tags of
+//     the words it uses; the flags say "stored", not "arrived", so a word can be late: then the row is read
+//     again.  The tags decide, the flags only say when reading is worth while.  Against a barrier (data
+//     complete, flag up, flag seen, data fetched) this saves the producer's wait for its stores; a word is
+//     written by one 64-bit store of two tagged words, so it is never half old.  There is no barrier between
+//     workgroups: a workgroup only ever waits for the rows it needs (the attention for its head's q, k, v: it
+//     polls those three pieces directly).
+//   * Every layer has row buffers of its own, so no address is written twice within a launch (caches are
+//     invalidated between launches).  The first read of a row therefore goes through the caches: one workgroup
+//     per chiplet pulls a line into the chiplet's L2, the other 31 hit there, instead of 256 reads past the
+//     caches.  A line read too early all the same would stay stale in the caches; the tags show it and the
+//     repeat reads past them (agent scope).  A workgroup that fell behind finds nothing newer than it waits for.
 //   * Loads of a wavefront return in order, and a store counts as a load: a wavefront with weight loads in
 //     flight would see the rows it polls only after all those loads have landed.  So the eighth wavefront
-//     of the workgroup streams no weights: it reads the rows (and the norm gains and weight scales) into
-//     LDS, where all eight work on them.
+//     of the workgroup streams no weights: it polls the flags and reads the rows, the norm gains and the weight
+//     scales into LDS, where all eight work on them (and, in a workgroup with a head, pulls the head's cached
+//     keys and values into L2 ahead of the attention).  The four wavefronts that will attend ask for no new
+//     weights during the q|k|v linear, so that the attention's cache rows are not queued behind them.
 //   * Barriers inside the workgroup wait for the wavefront's LDS operations only (lds_barrier): __syncthreads()
-//     would also wait for every weight load in flight, several times per phase.
+//     would also wait for every weight load in flight, several times per phase.  For the same reason LDS is
+//     read and written as plain vectors (lds_load16) and every load in a path of the fetching wavefront is
+//     waited for where the compiler can see it.
 //   * The generation lives in device memory and moves on with every launch (the last workgroup to finish
 //     writes it), so a launch captured in a graph can be replayed.  All 256 workgroups must be resident at
-//     once: one per compute unit, checked at creation.
+//     once: one per compute unit, checked at creation.  Every wait is bounded: a wait that gives up raises the
+//     error word, and the step's result is then wrong and says so.
 #include <new>
 #include <vector>
 
@@ -98,7 +108,8 @@ struct StepArgs {
     const __half *x_in;     // [hidden] the token's embedding
     const int32_t *pos;     // [1]
     int past;
-    unsigned *qkv, *attn, *o, *h, *dn;     // tagged rows
+    unsigned *qkv, *attn, *o, *h, *dn;     // tagged rows of layer 0; layer l's are l * row_stride words further on
+    size_t row_stride;
     __half *logits;
     __half *attn_trace;     // nullable: [layers, hidden]
     unsigned long long *flags, *gen, *err, *done;   // flags: one per workgroup
@@ -469,22 +480,25 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         const int K = P.K, groups = K >> 3;
         STEP_STAMP(0);
         // ---- the row this linear needs: an update of the residual stream (q|k|v, gate|up, head) or its whole input ----
+        // (a layer's rows have addresses of their own: within a launch no address is written twice, so a row can be
+        // read through the caches, and a workgroup that fell behind finds nothing newer than it waits for)
+        const size_t mine = (size_t)(P.kind == kStepHead ? P.layer - 1 : P.layer) * a.row_stride, before = (size_t)(P.layer > 0 ? P.layer - 1 : 0) * a.row_stride;
         const unsigned *row = nullptr;
         int row_at = 0;                                // where in the step the row is produced: 5 * layer + 1 .. 5
         if (P.kind == kStepQkv) {
-            row = P.layer == 0 ? nullptr : a.dn;
+            row = P.layer == 0 ? nullptr : a.dn + before;
             row_at = kStepTagsPerLayer * (P.layer - 1) + kTagDown;
         } else if (P.kind == kStepGateUp) {
-            row = a.o;
+            row = a.o + mine;
             row_at = kStepTagsPerLayer * P.layer + kTagO;
         } else if (P.kind == kStepHead) {
-            row = a.dn;
+            row = a.dn + before;
             row_at = kStepTagsPerLayer * (P.layer - 1) + kTagDown;
         } else if (P.kind == kStepO) {
-            row = all.n_groups ? a.attn : nullptr;     // (a workgroup with no channels of a linear skips its input)
+            row = all.n_groups ? a.attn + mine : nullptr;     // (a workgroup with no channels of a linear skips its input)
             row_at = kStepTagsPerLayer * P.layer + kTagAttn;
         } else {
-            row = all.n_groups ? a.h : nullptr;
+            row = all.n_groups ? a.h + mine : nullptr;
             row_at = kStepTagsPerLayer * P.layer + kTagH;
         }
         __half *st_gamma = reinterpret_cast<__half *>(lds.stage + K);             // the gains, behind the tagged row
@@ -504,8 +518,17 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     if (attempt == 0 && !poll_flags(a.flags, a.blocks, gen0 + (unsigned long long)row_at, lane, lds.dead != 0)) give_up(ph, 1);
                     const unsigned *from = row + lane * 4;
                     const int full = K >> 8;
-                    for (int p = 0; p < full; ++p) fetch_piece<true>(from + p * 256, lds.stage + p * 256);
-                    if ((K & 255) && lane < ((K & 255) >> 2)) fetch_piece<true>(from + full * 256, lds.stage + full * 256);
+                    // First through the caches (the first workgroup of a chiplet to ask brings a line into the chiplet's
+                    // L2 for the other 31): nobody has read these addresses in this launch, and the flags say that the
+                    // row has been stored.  A line that was read too early all the same stays stale in the caches: the
+                    // tags show it, and the row is read again past the caches (agent scope).
+                    if (attempt == 0) {
+                        for (int p = 0; p < full; ++p) fetch_piece<false>(from + p * 256, lds.stage + p * 256);
+                        if ((K & 255) && lane < ((K & 255) >> 2)) fetch_piece<false>(from + full * 256, lds.stage + full * 256);
+                    } else {
+                        for (int p = 0; p < full; ++p) fetch_piece<true>(from + p * 256, lds.stage + p * 256);
+                        if ((K & 255) && lane < ((K & 255) >> 2)) fetch_piece<true>(from + full * 256, lds.stage + full * 256);
+                    }
                 }
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             } else if (attempt == 0) {
@@ -729,11 +752,11 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                         const __half2 pk = __floats2half2_rn(y[0], y[1]);
                         *(SQAP_GLOBAL unsigned *)(a.logits + n) = *reinterpret_cast<const unsigned *>(&pk);
                     } else if (P.kind == kStepQkv) {
-                        store_tagged_pair(a.qkv, n, y[0], y[1], tag_of(P.layer, kTagQkv));
+                        store_tagged_pair(a.qkv + mine, n, y[0], y[1], tag_of(P.layer, kTagQkv));
                     } else if (P.kind == kStepO) {
-                        store_tagged_pair(a.o, n, y[0], y[1], tag_of(P.layer, kTagO));
+                        store_tagged_pair(a.o + mine, n, y[0], y[1], tag_of(P.layer, kTagO));
                     } else {
-                        store_tagged_pair(a.dn, n, y[0], y[1], tag_of(P.layer, kTagDown));
+                        store_tagged_pair(a.dn + mine, n, y[0], y[1], tag_of(P.layer, kTagDown));
                     }
                 }
             } else {
@@ -747,7 +770,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     const float sl = (float)(gd / (1.0 + exp(-gd)));
                     y[e] = to_half_value(sl * u2[e]);
                 }
-                if (n < (P.N >> 1)) store_tagged_pair(a.h, n, y[0], y[1], tag_of(P.layer, kTagH));
+                if (n < (P.N >> 1)) store_tagged_pair(a.h + mine, n, y[0], y[1], tag_of(P.layer, kTagH));
             }
         }
         // how far this workgroup has got (a workgroup without a head has nothing to add to the attention's row)
@@ -763,7 +786,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             if (glue) {
                 const bool ok = poll_pieces(3,
                                             [&](int p, const unsigned *&from, unsigned *&to, int &lanes) {
-                                                from = a.qkv + (size_t)p * a.hidden + (size_t)block * a.d + lane * 4;
+                                                from = a.qkv + mine + (size_t)p * a.hidden + (size_t)block * a.d + lane * 4;
                                                 to = lds.stage + kStepStageNew + p * 256;
                                                 lanes = a.d >> 2;
                                             },
@@ -771,7 +794,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 if (!ok) give_up(ph, 2);
             }
             STEP_STAMP(5);
-            decode_attention_head<true>(lds.attn, block, nullptr, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn,
+            decode_attention_head<true>(lds.attn, block, nullptr, pos0, a.H, a.d, a.base, P.kv, P.ldkv, a.past, a.attn + mine,
                                         a.attn_trace ? a.attn_trace + (size_t)P.layer * a.hidden : nullptr, a.freq, lds.sincos_tab,
                                         lds.stage + kStepStageNew, tag_of(P.layer, kTagAttn));
             if (t == 64)
@@ -799,7 +822,7 @@ struct Decoder {
     StepPhase *phases;          // device
     unsigned *rows;             // device, tagged words: qkv, attn, o, h, dn
     unsigned long long *sync;   // device: generation, error word, count of finished workgroups, flags[256]
-    size_t off_attn, off_o, off_h, off_dn;
+    size_t off_attn, off_o, off_h, off_dn, row_stride;
 };
 constexpr uint32_t kDecoderMagic = 0x53514443u;  // "SQDC"
 constexpr int kStepBlocks = 256;
@@ -903,6 +926,8 @@ sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n
     d->off_o = off; off += round64(hidden);
     d->off_h = off; off += round64(d->ffn);
     d->off_dn = off; off += round64(hidden);
+    d->row_stride = off;                            // every layer has rows of its own
+    off *= (size_t)n_layers;
     hipError_t e = hipGetDevice(&d->device);
     int cus = 0;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d->device);
@@ -956,6 +981,7 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
     a.o = d->rows + d->off_o;
     a.h = d->rows + d->off_h;
     a.dn = d->rows + d->off_dn;
+    a.row_stride = d->row_stride;
     a.logits = reinterpret_cast<__half *>(logits);
     a.attn_trace = reinterpret_cast<__half *>(attn_trace);
     a.gen = d->sync;
