@@ -183,6 +183,44 @@ def test_persistent_switch_is_host_only():
     assert L.sqap_set_persistent_kernels(1) == B.OK
 
 
+def test_mid_m_switch_is_host_only():
+    L = B.lib()
+    assert L.sqap_set_mid_m_kernel(0) == B.OK
+    assert L.sqap_set_mid_m_kernel(1) == B.OK
+
+
+def test_decoder_validation():
+    """Everything sqap_decoder_* can refuse without a device: null pointers, handles that are not handles."""
+    L = B.lib()
+    out = ctypes.c_void_p(1)
+    junk = (ctypes.c_uint8 * 256)()
+    jp = ctypes.cast(junk, ctypes.c_void_p)
+    layer = B.DecoderLayer()
+    assert L.sqap_decoder_create(None, 1, 4, 64, jp, jp, 1e-5, 10000.0, ctypes.byref(out)) == B.EINVAL
+    assert out.value is None                                                       # cleared on failure
+    assert L.sqap_decoder_create(ctypes.byref(layer), 1, 4, 64, jp, jp, 1e-5, 10000.0, None) == B.EINVAL
+    assert L.sqap_decoder_create(ctypes.byref(layer), 1, 4, 64, jp, jp, -1.0, 10000.0, ctypes.byref(out)) == B.EINVAL
+    assert L.sqap_decoder_create(ctypes.byref(layer), 1, 4, 64, jp, jp, 1e-5, 0.0, ctypes.byref(out)) == B.EINVAL
+    # the head is not a weight handle (zeroed memory carries no magic)
+    assert L.sqap_decoder_create(ctypes.byref(layer), 1, 4, 64, jp, jp, 1e-5, 10000.0, ctypes.byref(out)) == B.EINVAL
+    assert "head" in _err()
+    word = ctypes.c_uint64(0)
+    assert L.sqap_decoder_step(jp, jp, jp, 0, jp, None, None) == B.EINVAL and "decoder handle" in _err()
+    assert L.sqap_decoder_step(None, jp, jp, 0, jp, None, None) == B.EINVAL
+    assert L.sqap_decoder_status(jp, ctypes.byref(word), None) == B.EINVAL
+    assert L.sqap_decoder_free(jp) == B.EINVAL
+    assert L.sqap_decoder_free(None) == B.OK
+
+
+def test_attn_scores_noalloc_validation():
+    L = B.lib()
+    one = ctypes.c_void_p(16)
+    assert L.sqap_attn_scores_noalloc(None, None, 1, 8, 4, 64, 0, 4, None, None) == B.EINVAL
+    # beyond the fixed scratch: rejected before anything is launched
+    assert L.sqap_attn_scores_noalloc(one, one, 65, 8, 4, 64, 0, 4, one, None) == B.EUNSUPPORTED
+    assert L.sqap_attn_scores_noalloc(one, one, 64, 70000, 32, 128, 0, 65536, one, None) == B.EUNSUPPORTED
+
+
 def test_selftest_dispatch_validation():
     assert B.lib().sqap_selftest_dispatch(None, None) == B.EINVAL
 
