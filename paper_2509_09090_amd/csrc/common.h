@@ -187,4 +187,12 @@ bool decoder_valid(const Decoder *d);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *out_cap);
 
+// __syncthreads() is a release and an acquire fence around the barrier, and the release waits for every
+// load and store of the wavefront, global ones included.  A wavefront that keeps a stream of weight loads in
+// flight must not wait for those at every barrier: where the barrier only hands LDS contents from wavefront
+// to wavefront, waiting for the wavefront's own LDS operations is enough (they complete in order, and a completed
+// LDS write is visible to the whole workgroup).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+
 }  // namespace sqap

@@ -7,6 +7,8 @@
 #include <stdint.h>
 #include <cmath>
 
+#include "common.h"
+
 namespace sqap {
 
 // A pointer that was loaded from memory (a table of per-layer pointers, say) is a generic pointer to the
@@ -76,13 +78,6 @@ struct DecodeAttnLds {
     float wred[12];            // chunk maxima of the four wavefronts (two sets, by chunk parity); their sums
 };
 static_assert(sizeof(float) * kDecRedFloats >= kDecMaxRow * sizeof(__half), "the staged row must fit the reduction buffer");
-
-// __syncthreads() is a release and an acquire fence around the barrier, and the release waits for every
-// load and store of the wavefront, global ones included.  A wavefront that keeps a stream of weight loads in
-// flight must not wait for those at every barrier: where the barrier only hands LDS contents from wavefront
-// to wavefront, waiting for the wavefront's own LDS operations is enough (they complete in order, and a completed
-// LDS write is visible to the whole workgroup).
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 // 16 bytes of LDS as a plain vector.  (Accesses typed as the uint4 class make the compiler wait for every load
 // in flight that lands in LDS, the weight stream included: it takes them as possibly the same memory.  The

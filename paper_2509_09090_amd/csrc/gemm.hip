@@ -28,6 +28,9 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 128;            // codes of the reduction axis per main-loop step
+#ifndef SQAP_GEMM_SETS_WIDE
+#define SQAP_GEMM_SETS_WIDE 0
+#endif
 constexpr int kChunksPerStep = 4;   // = kBK / 32, 16-byte packed pieces per row per step
 constexpr int kMaxK = 131040;       // keeps 256 * 64 * K below 2^31
 
@@ -161,7 +164,9 @@ struct Cfg {
 //
 // Pipeline: while stage `cur` feeds the MFMAs, the registers loaded one step
 // ago are copied into the other stage and the loads for two steps ahead are
-// issued.  One barrier per step; a trailing barrier leaves LDS free.
+// issued.  One barrier per step; a trailing barrier leaves LDS free.  The barriers order LDS traffic only
+// (lds_barrier): __syncthreads() would also wait for the global loads just issued, every step, and a load
+// would never have more than one step to arrive, however many register sets hold loads in flight.
 template <class C>
 struct OperandMover {
     // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand (when the
@@ -210,7 +215,7 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     // Register sets for operands in flight.  The narrow tiles (one row of wavefronts; a few hundred token
     // rows) have short steps and use two sets, so that a load has two steps to arrive (3-6 % faster at
     // M = 84 and 276); the 256 x 256 tiles use one (two measured 2.5 % slower there).
-    constexpr int SETS = C::WAVES_M == 1 ? 2 : 1;
+    constexpr int SETS = SQAP_GEMM_SETS_WIDE && C::WAVES_M != 1 ? 2 : C::WAVES_M == 1 ? 2 : 1;
     v4i ga[SETS][C::A_LOADS], gb[SETS][C::B_LOADS];
 
     auto load_global = [&](int step, auto set_c) {
@@ -278,14 +283,14 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         store_lds(0, set0);
         load_global(min(step_begin + 1, last), set1);
         load_global(min(step_begin + 2, last), set0);
-        __syncthreads();
+        lds_barrier();
         auto body = [&](auto set) {
             store_lds(stage ^ 1, set);
             __builtin_amdgcn_sched_barrier(0);
             load_global(min(it + 3, last), set);
             __builtin_amdgcn_sched_barrier(0);
             compute(stage);
-            __syncthreads();
+            lds_barrier();
             stage ^= 1;
             ++it;
         };
@@ -298,25 +303,25 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         load_global(step_begin, set0);
         store_lds(0, set0);
         if (step_begin + 1 < step_end) load_global(step_begin + 1, set0);
-        __syncthreads();
+        lds_barrier();
         for (; it + 2 < step_end; ++it) {
             store_lds(stage ^ 1, set0);
             __builtin_amdgcn_sched_barrier(0);
             load_global(it + 2, set0);
             __builtin_amdgcn_sched_barrier(0);
             compute(stage);
-            __syncthreads();
+            lds_barrier();
             stage ^= 1;
         }
         if (it + 1 < step_end) {
             store_lds(stage ^ 1, set0);
             compute(stage);
-            __syncthreads();
+            lds_barrier();
             stage ^= 1;
         }
     }
     compute(stage);
-    __syncthreads();
+    lds_barrier();
 }
 
 // The same loop for a tile of the last tile row when only `groups` < BM / 32 of its row groups hold
@@ -391,7 +396,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
     load_global(min(step_begin + 2, last), set2);
     load_global(min(step_begin + 3, last), set3);
     load_global(min(step_begin + 4, last), set0);
-    __syncthreads();
+    lds_barrier();
     int it = step_begin, stage = 0;
     auto body = [&](auto set) {               // the set holds step it + 1
         store_lds(stage ^ 1, set);
@@ -399,7 +404,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
         load_global(min(it + 1 + kRing, last), set);
         __builtin_amdgcn_sched_barrier(0);
         compute(stage);
-        __syncthreads();
+        lds_barrier();
         stage ^= 1;
         ++it;
     };
@@ -414,7 +419,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
     if (rest >= 2) body(set2);
     if (rest >= 3) body(set3);
     compute(stage);
-    __syncthreads();
+    lds_barrier();
 }
 
 // Picks the loop for a tile with `groups` valid row groups.
