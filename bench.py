@@ -874,6 +874,11 @@ def main():
                 "one_launch_GBps_weights": real["step_kernel"]["GBps_weights"],
                 "one_launch_frac_of_hbm_peak": real["step_kernel"]["frac_of_hbm_peak"],
                 "logits_equal": real["step_kernel"]["logits_equal_chain"],
+                "roofline": {"bound": "hbm", "kernel": "decoder_step_kernel (one launch per token)",
+                             "achieved": real["step_kernel"]["GBps_weights"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": real["step_kernel"]["frac_of_hbm_peak"],
+                             "algorithmic_bytes_per_launch": real["step_kernel"]["weight_bytes_per_token"],
+                             "traffic": stored_traffic("decoder_step_kernel")},
                 "formulation": "dependency-respecting, whole model: 32 layers with attention over the cache, norms, "
                                "SwiGLU, cache append, final norm and head; batch 1, 148 cached tokens"}
     out["selection"] = selection_leg(torch, B, wl, dev)
