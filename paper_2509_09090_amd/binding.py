@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsqap.so")
+LIB_PATH = os.environ.get("SQAP_LIBRARY") or os.path.join(_HERE, "libsqap.so")      # (another build of the library: for A/B runs)
 
 OK, EINVAL, EUNSUPPORTED, EDEVICE, ENOMEM = 0, -1, -2, -3, -4
 ROTATE_HADAMARD = 1

@@ -28,9 +28,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kBK = 128;            // codes of the reduction axis per main-loop step
-#ifndef SQAP_GEMM_SETS_WIDE
-#define SQAP_GEMM_SETS_WIDE 0
-#endif
 constexpr int kChunksPerStep = 4;   // = kBK / 32, 16-byte packed pieces per row per step
 constexpr int kMaxK = 131040;       // keeps 256 * 64 * K below 2^31
 
@@ -215,7 +212,7 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
     // Register sets for operands in flight.  The narrow tiles (one row of wavefronts; a few hundred token
     // rows) have short steps and use two sets, so that a load has two steps to arrive (3-6 % faster at
     // M = 84 and 276); the 256 x 256 tiles use one (two measured 2.5 % slower there).
-    constexpr int SETS = SQAP_GEMM_SETS_WIDE && C::WAVES_M != 1 ? 2 : C::WAVES_M == 1 ? 2 : 1;
+    constexpr int SETS = C::WAVES_M == 1 ? 2 : 1;
     v4i ga[SETS][C::A_LOADS], gb[SETS][C::B_LOADS];
 
     auto load_global = [&](int step, auto set_c) {
