@@ -161,9 +161,7 @@ struct Cfg {
 //
 // Pipeline: while stage `cur` feeds the MFMAs, the registers loaded one step
 // ago are copied into the other stage and the loads for two steps ahead are
-// issued.  One barrier per step; a trailing barrier leaves LDS free.  The barriers order LDS traffic only
-// (lds_barrier): __syncthreads() would also wait for the global loads just issued, every step, and a load
-// would never have more than one step to arrive, however many register sets hold loads in flight.
+// issued.  One barrier per step; a trailing barrier leaves LDS free.
 template <class C>
 struct OperandMover {
     // Wavefront w moves fragments w*LOADS .. w*LOADS+LOADS-1 of each operand (when the
@@ -280,14 +278,14 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         store_lds(0, set0);
         load_global(min(step_begin + 1, last), set1);
         load_global(min(step_begin + 2, last), set0);
-        lds_barrier();
+        __syncthreads();
         auto body = [&](auto set) {
             store_lds(stage ^ 1, set);
             __builtin_amdgcn_sched_barrier(0);
             load_global(min(it + 3, last), set);
             __builtin_amdgcn_sched_barrier(0);
             compute(stage);
-            lds_barrier();
+            __syncthreads();
             stage ^= 1;
             ++it;
         };
@@ -300,25 +298,25 @@ __device__ __forceinline__ void mainloop(const GemmParams &p, uint8_t *smem, int
         load_global(step_begin, set0);
         store_lds(0, set0);
         if (step_begin + 1 < step_end) load_global(step_begin + 1, set0);
-        lds_barrier();
+        __syncthreads();
         for (; it + 2 < step_end; ++it) {
             store_lds(stage ^ 1, set0);
             __builtin_amdgcn_sched_barrier(0);
             load_global(it + 2, set0);
             __builtin_amdgcn_sched_barrier(0);
             compute(stage);
-            lds_barrier();
+            __syncthreads();
             stage ^= 1;
         }
         if (it + 1 < step_end) {
             store_lds(stage ^ 1, set0);
             compute(stage);
-            lds_barrier();
+            __syncthreads();
             stage ^= 1;
         }
     }
     compute(stage);
-    lds_barrier();
+    __syncthreads();
 }
 
 // The same loop for a tile of the last tile row when only `groups` < BM / 32 of its row groups hold
@@ -393,7 +391,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
     load_global(min(step_begin + 2, last), set2);
     load_global(min(step_begin + 3, last), set3);
     load_global(min(step_begin + 4, last), set0);
-    lds_barrier();
+    __syncthreads();
     int it = step_begin, stage = 0;
     auto body = [&](auto set) {               // the set holds step it + 1
         store_lds(stage ^ 1, set);
@@ -401,7 +399,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
         load_global(min(it + 1 + kRing, last), set);
         __builtin_amdgcn_sched_barrier(0);
         compute(stage);
-        lds_barrier();
+        __syncthreads();
         stage ^= 1;
         ++it;
     };
@@ -416,7 +414,7 @@ __device__ __forceinline__ void mainloop_ragged(const GemmParams &p, uint8_t *sm
     if (rest >= 2) body(set2);
     if (rest >= 3) body(set3);
     compute(stage);
-    lds_barrier();
+    __syncthreads();
 }
 
 // Picks the loop for a tile with `groups` valid row groups.
