@@ -69,6 +69,7 @@ def _oracle_step(oracle, host, head_host, gf, x_tok, pos, caches_before, attn_tr
 
 @pytest.mark.parametrize("hidden,H,d,F,L,vocab,S", [(256, 4, 64, 512, 3, 1000, 21),       # most workgroups idle in every phase
                                                     (1024, 8, 128, 2816, 2, 5008, 40),   # several groups per workgroup, ragged shares
+                                                    (512, 4, 128, 1408, 2, 3008, 300),   # a cache longer than one attention chunk
                                                     (4096, 32, 128, 11008, 1, 32000, 148)])   # the 7B layer shape and head
 def test_decoder_step_matches_the_oracle_and_the_launch_chain(G, oracle, hidden, H, d, F, L, vocab, S):
     import torch
