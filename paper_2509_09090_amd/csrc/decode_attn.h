@@ -162,10 +162,12 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
     }
     constexpr bool V_LATE = false;
     uint4 kraw[kDecKeys], vraw[V_LATE ? 1 : kDecKeys];
+    // (all key rows first: loads return in order, and the scores need the keys only)
 #pragma unroll
-    for (int j = 0; j < kDecKeys; ++j) {
-        kraw[j] = cached(kbase, 16 * j + grp);
-        if (!V_LATE) vraw[j] = cached(vbase, 16 * j + grp);
+    for (int j = 0; j < kDecKeys; ++j) kraw[j] = cached(kbase, 16 * j + grp);
+    if (!V_LATE) {
+#pragma unroll
+        for (int j = 0; j < kDecKeys; ++j) vraw[j] = cached(vbase, 16 * j + grp);
     }
     if constexpr (TAGGED) {
         sync();                                        // the new token's q, k, v are in `staged`
