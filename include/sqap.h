@@ -592,6 +592,11 @@ sqap_status sqap_decoder_create(const sqap_decoder_layer *layers, int32_t n_laye
 sqap_status sqap_decoder_step(sqap_decoder *d, const sqap_f16 *x, const int32_t *pos, int32_t past,
                               sqap_f16 *logits, sqap_f16 *attn_trace, void *stream);
 sqap_status sqap_decoder_status(const sqap_decoder *d, uint64_t *error_word_out, void *stream);
+/* How many times a workgroup of the step kernel looks for another's output before it gives up (default: a
+ * negative value restores it; about 200 000 looks, a few tenths of a second).  Applies to the steps enqueued
+ * afterwards.  With 0 a step never waits: it ends at once with a nonzero status word and wrong outputs, which
+ * is how the tests exercise the give-up path without a kernel that waits for long.  EINVAL: not a decoder. */
+sqap_status sqap_decoder_set_wait_limit(sqap_decoder *d, int64_t polls);
 sqap_status sqap_decoder_free(sqap_decoder *d);
 
 #ifdef __cplusplus

@@ -25,7 +25,7 @@ EXPORTS = (
     "sqap_quantize_weight_folded", "sqap_rmsnorm_quantize_act", "sqap_swiglu_quantize_act", "sqap_rope",
     "sqap_attention", "sqap_residual_add", "sqap_rope_append", "sqap_plan_linear_shares", "sqap_decode_attention", "sqap_group_info", "sqap_init",
     "sqap_set_persistent_kernels", "sqap_attn_scores_workspace_bytes", "sqap_attn_scores_noalloc", "sqap_set_mid_m_kernel", "sqap_decoder_create", "sqap_decoder_step", "sqap_decoder_status",
-    "sqap_decoder_free",
+    "sqap_decoder_set_wait_limit", "sqap_decoder_free",
 )
 
 
@@ -101,6 +101,7 @@ def lib():
         L.sqap_decoder_step.argtypes = [vp, vp, vp, i32, vp, vp, vp]
         L.sqap_decoder_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64), vp]
         L.sqap_decoder_free.argtypes = [vp]
+        L.sqap_decoder_set_wait_limit.argtypes = [vp, i64]
         L.sqap_group_info.argtypes = [vp, i32] + [ctypes.POINTER(i32)] * 5
         L.sqap_selftest_quotient.argtypes = [vp, vp]
         L.sqap_init.argtypes = [vp]
@@ -429,6 +430,10 @@ class Decoder:
         w = ctypes.c_uint64(0)
         _check(lib().sqap_decoder_status(self.handle, ctypes.byref(w), _stream(stream)))
         return w.value
+
+    def set_wait_limit(self, polls):
+        """Looks for another workgroup's output before a wait gives up (negative: the default)."""
+        _check(lib().sqap_decoder_set_wait_limit(self.handle, int(polls)))
 
     def free(self):
         if self.handle:

@@ -656,6 +656,14 @@ sqap_status sqap_decoder_status(const sqap_decoder *d, uint64_t *error_word_out,
     return s;
 }
 
+sqap_status sqap_decoder_set_wait_limit(sqap_decoder *d, int64_t polls)
+{
+    Decoder *dd = reinterpret_cast<Decoder *>(d);
+    if (!decoder_valid(dd)) return fail(SQAP_EINVAL, "sqap_decoder_set_wait_limit: not a decoder handle");
+    decoder_set_wait_limit(dd, (long long)polls);
+    return SQAP_OK;
+}
+
 sqap_status sqap_decoder_free(sqap_decoder *d)
 {
     if (!d) return SQAP_OK;

@@ -184,6 +184,7 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
 sqap_status decoder_error(const Decoder *d, unsigned long long *word_out, hipStream_t st);
 sqap_status decoder_free(Decoder *d);
 bool decoder_valid(const Decoder *d);
+void decoder_set_wait_limit(Decoder *d, long long polls);
 sqap_status launch_skinny(const SkinnyArgs &args, int max_chunks, hipStream_t st);
 void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *out_cap);
 

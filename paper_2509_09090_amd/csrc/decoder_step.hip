@@ -81,8 +81,7 @@ constexpr int kStepMaxK = kStepThreads * 8 * kStepGpt;
 constexpr int kStepMaxHidden = 4096;       // the residual row in LDS; a tagged row and the gains side by side
 constexpr int kStepTagsPerLayer = 5;       // q|k|v, attention, o, h, down
 constexpr int kStepWarmKeys = 2048;         // cached keys whose rows a workgroup warms the L2 cache with before its attention
-constexpr int kStepRetryLimit = 100000;     // times a row is read again because a word was late
-constexpr long long kStepPollLimit = 200000;      // reads of a row before a wait gives up (a few tenths of a second)
+constexpr long long kStepPollLimit = 200000;      // polls, or repeated reads of a row, before a wait gives up (a few tenths of a second)
 
 enum StepKind { kStepQkv = 0, kStepO = 1, kStepGateUp = 2, kStepDown = 3, kStepHead = 4 };
 enum StepTag { kTagQkv = 1, kTagAttn = 2, kTagO = 3, kTagH = 4, kTagDown = 5 };
@@ -113,6 +112,7 @@ struct StepArgs {
     __half *logits;
     __half *attn_trace;     // nullable: [layers, hidden]
     unsigned long long *flags, *gen, *err, *done;   // flags: one per workgroup
+    long long poll_limit;   // polls (and repeated reads of a row) before a wait gives up
     RopeFreq freq;
 };
 
@@ -337,7 +337,7 @@ __device__ __forceinline__ void stream_issue(StepStream &c, const StepArgs &a, S
 // flags, four per lane, until all have reached `value`: a cheap hint that the row is worth reading.  The tags
 // in the row decide.  False when it gave up.
 __device__ __forceinline__ bool poll_flags(const unsigned long long *flags, int blocks, unsigned long long value, int lane,
-                                           bool dead)
+                                           bool dead, long long poll_limit)
 {
     if (dead) return false;
     for (long long round = 0;; ++round) {
@@ -349,7 +349,7 @@ __device__ __forceinline__ bool poll_flags(const unsigned long long *flags, int 
         }
         const int here = (int)(seen[0] >= value) & (int)(seen[1] >= value) & (int)(seen[2] >= value) & (int)(seen[3] >= value);
         if (__all(here)) return true;
-        if (round > kStepPollLimit) return false;
+        if (round >= poll_limit) return false;
         __builtin_amdgcn_s_sleep(1);
     }
 }
@@ -359,11 +359,11 @@ __device__ __forceinline__ bool poll_flags(const unsigned long long *flags, int 
 // every piece carries `tag` in its high half; pieces that do are not read again.  False when it gave up (or
 // gave up before: then one read, so that LDS holds something to go on with).
 template <class Piece>
-__device__ __forceinline__ bool poll_pieces(int n, Piece piece, unsigned tag, int lane, bool dead)
+__device__ __forceinline__ bool poll_pieces(int n, Piece piece, unsigned tag, int lane, bool dead, long long poll_limit)
 {
     unsigned long long pending = n >= 64 ? ~0ull : (1ull << n) - 1ull;
     const unsigned want = tag << 16;
-    const long long limit = dead ? 0 : kStepPollLimit;
+    const long long limit = dead ? 0 : poll_limit;
     for (long long round = 0; pending; ++round) {
         if (round > limit) return false;
         for (unsigned long long m = pending; m; m &= m - 1) {
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                         if (g0 + lane < groups)
                             fetch_piece<false>(reinterpret_cast<const uint4 *>(P.gamma) + g0 + lane, st_gamma + g0 * 8);
                 if (row) {
-                    if (attempt == 0 && !poll_flags(a.flags, a.blocks, gen0 + (unsigned long long)row_at, lane, lds.dead != 0)) give_up(ph, 1);
+                    if (attempt == 0 && !poll_flags(a.flags, a.blocks, gen0 + (unsigned long long)row_at, lane, lds.dead != 0, a.poll_limit)) give_up(ph, 1);
                     const unsigned *from = row + lane * 4;
                     const int full = K >> 8;
                     // First through the caches (the first workgroup of a chiplet to ask brings a line into the chiplet's
@@ -584,7 +584,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             lds_barrier();
             if (t == 0) lds.stale[(attempt + 1) & 1] = 0;      // (its last readers have passed the barrier before this one)
             if (!row || !lds.stale[attempt & 1] || lds.dead) break;
-            if (attempt >= kStepRetryLimit) {
+            if (attempt >= a.poll_limit) {
                 if (glue) give_up(ph, 3);
                 break;
             }
@@ -790,7 +790,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                                                 to = lds.stage + kStepStageNew + p * 256;
                                                 lanes = a.d >> 2;
                                             },
-                                            tag_of(P.layer, kTagQkv), lane, lds.dead != 0);
+                                            tag_of(P.layer, kTagQkv), lane, lds.dead != 0, a.poll_limit);
                 if (!ok) give_up(ph, 2);
             }
             STEP_STAMP(5);
@@ -823,6 +823,7 @@ struct Decoder {
     unsigned *rows;             // device, tagged words: qkv, attn, o, h, dn
     unsigned long long *sync;   // device: generation, error word, count of finished workgroups, flags[256]
     size_t off_attn, off_o, off_h, off_dn, row_stride;
+    long long poll_limit;
 };
 constexpr uint32_t kDecoderMagic = 0x53514443u;  // "SQDC"
 constexpr int kStepBlocks = 256;
@@ -917,6 +918,7 @@ sqap_status decoder_create(const sqap_decoder_layer *layers, int n_layers, int n
     d->base = rope_base;
     d->n_phases = (int)ph.size();
     d->blocks = kStepBlocks;
+    d->poll_limit = kStepPollLimit;
     d->phases = nullptr;
     d->rows = nullptr;
     d->sync = nullptr;
@@ -982,6 +984,7 @@ sqap_status decoder_step(Decoder *d, const sqap_f16 *x, const int32_t *pos, int 
     a.h = d->rows + d->off_h;
     a.dn = d->rows + d->off_dn;
     a.row_stride = d->row_stride;
+    a.poll_limit = d->poll_limit;
     a.logits = reinterpret_cast<__half *>(logits);
     a.attn_trace = reinterpret_cast<__half *>(attn_trace);
     a.gen = d->sync;
@@ -1012,6 +1015,7 @@ sqap_status decoder_free(Decoder *d)
 }
 
 bool decoder_valid(const Decoder *d) { return d && d->magic == kDecoderMagic; }
+void decoder_set_wait_limit(Decoder *d, long long polls) { d->poll_limit = polls < 0 ? kStepPollLimit : polls; }
 int decoder_hidden(const Decoder *d) { return d->hidden; }
 
 }  // namespace sqap

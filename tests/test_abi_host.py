@@ -208,6 +208,7 @@ def test_decoder_validation():
     assert L.sqap_decoder_step(jp, jp, jp, 0, jp, None, None) == B.EINVAL and "decoder handle" in _err()
     assert L.sqap_decoder_step(None, jp, jp, 0, jp, None, None) == B.EINVAL
     assert L.sqap_decoder_status(jp, ctypes.byref(word), None) == B.EINVAL
+    assert L.sqap_decoder_set_wait_limit(jp, 0) == B.EINVAL
     assert L.sqap_decoder_free(jp) == B.EINVAL
     assert L.sqap_decoder_free(None) == B.OK
 

@@ -179,3 +179,39 @@ def test_decoder_step_replayed_from_a_graph(G, oracle):
     head.free()
     for (w, _) in dev:
         w.free()
+
+
+def test_decoder_step_gives_up_instead_of_waiting(G, oracle):
+    """With a wait limit of zero a step never waits for another workgroup: it ends, says so in the status word,
+    and the decoder is as good as new afterwards (the next step with the default limit gives the reference)."""
+    import torch
+    from paper_2509_09090_amd import binding as B
+    rng = np.random.default_rng(11)
+    hidden, H, d, F, L, vocab, S = 512, 4, 128, 1408, 3, 3008, 25
+    host, dev, head_host, gf, head = _model(oracle, G, rng, hidden, H, d, F, L, vocab, S + 1)
+    for (_, kv) in dev:
+        kv[:S] = G.to_dev((0.5 * rng.standard_normal((S, 2 * hidden))).astype(np.float16))
+    gf_d = G.to_dev(gf)
+    dec = B.sqap_decoder_create([(w.qkv, w.o, w.gate_up, w.down, w.gamma_attn, w.gamma_mlp, kv) for (w, kv) in dev],
+                                H, d, gf_d, head)
+    x_d, p_d = G.to_dev(_acts(rng, 1, hidden))[0], G.to_dev(np.array([40], np.int32))
+    ref = torch.zeros((vocab,), dtype=torch.float16, device="cuda")
+    out = torch.zeros_like(ref)
+    dec.step(x_d, p_d, S, ref)
+    torch.cuda.synchronize()
+    assert dec.status() == 0
+    dec.set_wait_limit(0)
+    dec.step(x_d, p_d, S, out)
+    torch.cuda.synchronize()                 # the launch ends although nobody waited for anybody
+    assert dec.status() != 0
+    dec.set_wait_limit(-1)
+    for _ in range(2):
+        out.fill_(float("nan"))
+        dec.step(x_d, p_d, S, out)
+        torch.cuda.synchronize()
+        assert dec.status() == 0
+        assert torch.equal(out.view(torch.int16), ref.view(torch.int16))
+    dec.free()
+    head.free()
+    for (w, _) in dev:
+        w.free()
