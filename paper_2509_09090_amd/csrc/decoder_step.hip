@@ -314,8 +314,10 @@ __device__ __forceinline__ void stream_enter(StepStream &c, const StepArgs &a, i
 __device__ __forceinline__ void stream_issue(StepStream &c, const StepArgs &a, StepLds &lds, int block, int wave, int lane)
 {
     if (c.ph >= a.n_phases) return;
+    // (nontemporal: every weight byte is used once, and the stream should not push the rows, the flags and the
+    // cached keys and values out of the L2)
     __builtin_amdgcn_global_load_lds(reinterpret_cast<const v4i *>(c.lane_ptr),
-                                     (__attribute__((address_space(3))) void *)(&lds.ring[wave][c.slot][0]), 16, 0, 0);
+                                     (__attribute__((address_space(3))) void *)(&lds.ring[wave][c.slot][0]), 16, 0, 2);
     ++c.issued;
     c.slot = c.slot + 1 == kStepRing ? 0 : c.slot + 1;
     ++c.i;
