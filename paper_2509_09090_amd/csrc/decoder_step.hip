@@ -352,7 +352,6 @@ __device__ __forceinline__ bool poll_flags(const unsigned long long *flags, int 
         const int here = (int)(seen[0] >= value) & (int)(seen[1] >= value) & (int)(seen[2] >= value) & (int)(seen[3] >= value);
         if (__all(here)) return true;
         if (round >= poll_limit) return false;
-        __builtin_amdgcn_s_sleep(1);
     }
 }
 
@@ -446,8 +445,6 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     // into the park registers (when those are empty) and asks for as many new ones.
     auto park_pieces = [&]() {
         if (glue) return;
-        // (a wavefront that held its loads back for the attention asks for them now)
-        while (stream.issued - consumed < kStepRing && stream.ph < a.n_phases) stream_issue(stream, a, lds, block, wave, lane);
         if (park_c != park_n) return;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         const int avail = stream.issued - consumed;
@@ -693,10 +690,6 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     ++j;
                 }
             };
-            // Loads return in order: the cached keys and values that the attention asks for would arrive behind every
-            // weight piece still on its way.  The wavefronts that will attend ask for no new pieces during this linear
-            // (what they multiply was asked for long ago) and catch up when they next wait.
-            const bool hold = P.kind == kStepQkv && block < a.H && wave < 4;
             int i = share.i0;
             // first the pieces parked in registers (they are the oldest), then the ring
 #pragma unroll
@@ -715,7 +708,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                 const v4i w = *reinterpret_cast<const v4i *>(&lds.ring[wave][cslot][lane * 16]);
                 multiply(w);
                 // the slot is free (its contents are in registers: the products above needed them)
-                if (!hold) stream_issue(stream, a, lds, block, wave, lane);
+                stream_issue(stream, a, lds, block, wave, lane);
                 ++consumed;
                 cslot = cslot + 1 == kStepRing ? 0 : cslot + 1;
             }
