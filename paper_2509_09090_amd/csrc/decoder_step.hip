@@ -49,8 +49,8 @@
 //     flight would see the rows it polls only after all those loads have landed.  So the eighth wavefront
 //     of the workgroup streams no weights: it polls the flags and reads the rows, the norm gains and the weight
 //     scales into LDS, where all eight work on them (and, in a workgroup with a head, pulls the head's cached
-//     keys and values into L2 ahead of the attention).  The four wavefronts that will attend ask for no new
-//     weights during the q|k|v linear, so that the attention's cache rows are not queued behind them.
+//     keys and values into L2 ahead of the attention).  The weight stream is read with nontemporal loads, so
+//     that it does not push those lines, the rows and the flags out of the L2 again.
 //   * Barriers inside the workgroup wait for the wavefront's LDS operations only (lds_barrier): __syncthreads()
 //     would also wait for every weight load in flight, several times per phase.  For the same reason LDS is
 //     read and written as plain vectors (lds_load16) and every load in a path of the fetching wavefront is
