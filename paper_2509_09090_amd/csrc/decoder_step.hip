@@ -207,14 +207,58 @@ __device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long 
     }
 }
 
+// Reductions over the wavefront with data-parallel-primitive moves instead of LDS permutes: inside a row of
+// 16 lanes the partner is reached by quad permutes (xor 1, xor 2) and the two mirrors (7 - i within 8 lanes,
+// 15 - i within 16), each a modifier on the instruction's operand, so after four steps every lane of a row
+// holds the row's result; the four rows are read out as scalars.  A step costs a few cycles against the
+// LDS round trip of a permute.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_move(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+// the wavefront's maximum of non-negative values, in every lane
+__device__ __forceinline__ float wave_max(float v)
+{
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor1>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor2>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppHalfMirror>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppMirror>(__float_as_uint(v))));
+    const unsigned b = __float_as_uint(v);
+    const float r0 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 0)), r1 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 16));
+    const float r2 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 32)), r3 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
 // the wavefront's 128-bit sum, in every lane
 __device__ __forceinline__ void wave_sum128(unsigned long long &hi, unsigned long long &lo)
 {
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long ohi = __shfl_xor(hi, o), olo = __shfl_xor(lo, o);
+    auto step = [&](auto ctrl_c) {
+        constexpr int CTRL = decltype(ctrl_c)::value;
+        const unsigned long long olo = (unsigned long long)dpp_move<CTRL>((unsigned)lo) | ((unsigned long long)dpp_move<CTRL>((unsigned)(lo >> 32)) << 32);
+        const unsigned long long ohi = (unsigned long long)dpp_move<CTRL>((unsigned)hi) | ((unsigned long long)dpp_move<CTRL>((unsigned)(hi >> 32)) << 32);
         lo += olo;
         hi += ohi + (lo < olo ? 1ull : 0ull);
+    };
+    step(std::integral_constant<int, kDppXor1>{});
+    step(std::integral_constant<int, kDppXor2>{});
+    step(std::integral_constant<int, kDppHalfMirror>{});
+    step(std::integral_constant<int, kDppMirror>{});
+    auto lane64 = [](unsigned long long v, int l) {
+        return (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, l) |
+               ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), l) << 32);
+    };
+    unsigned long long h = lane64(hi, 0), l = lane64(lo, 0);
+#pragma unroll
+    for (int r = 1; r < 4; ++r) {
+        const unsigned long long ol = lane64(lo, 16 * r);
+        l += ol;
+        h += lane64(hi, 16 * r) + (l < ol ? 1ull : 0ull);
     }
+    hi = h;
+    lo = l;
 }
 
 // r from the eight wavefronts' sums (hi, lo pairs)
@@ -238,7 +282,11 @@ __device__ __forceinline__ float norm_factor(const unsigned long long *wsum, int
         Sd = ldexp((double)top, 64 - lz);
     }
     Sd = ldexp(Sd, -48);
-    return (float)(1.0 / sqrt(Sd / (double)K + (double)eps));
+    // (eps widened here: hoisted out of the loop over the phases the double would sit in registers, in practice in
+    // scratch memory, for the whole step)
+    float e = eps;
+    asm volatile("" : "+v"(e));
+    return (float)(1.0 / sqrt(Sd / (double)K + (double)e));
 }
 
 // ---- a workgroup's share of a linear ----
@@ -576,7 +624,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     lds.wsum[2 * wave + 1] = lo;
                 }
             } else {
-                for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+                amax = wave_max(amax);
                 if (lane == 0) lds.wmax[wave] = amax;
             }
             if (__any((bad >> 16) != 0) && lane == 0) lds.stale[attempt & 1] = 1;
@@ -613,7 +661,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     }
                 }
             }
-            for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+            amax = wave_max(amax);
             if (lane == 0) lds.wmax[wave] = amax;
             lds_barrier();
         }
