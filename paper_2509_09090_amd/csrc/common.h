@@ -196,4 +196,24 @@ void skinny_plan(int total_items, int max_chunks, int cus, int *S, int *W, int *
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 
+// Reductions over the wavefront with data-parallel-primitive moves instead of LDS permutes: inside a row of
+// 16 lanes the partner is reached by quad permutes (xor 1, xor 2) and the two mirrors (7 - i within 8 lanes,
+// 15 - i within 16), each a modifier on the instruction's operand, so after four steps every lane of a row
+// holds the row's result; the four rows are read out as scalars.  A step costs a few cycles against the
+// LDS round trip of a permute.
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_move(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
+
+// the same for a float, and a row's value (the same in its 16 lanes) of each of the four rows as scalars
+template <int CTRL>
+__device__ __forceinline__ float dpp_move_f(float v) { return __uint_as_float(dpp_move<CTRL>(__float_as_uint(v))); }
+__device__ __forceinline__ float row_value(float v, int row)
+{
+    return __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(v), 16 * row));
+}
+
 }  // namespace sqap

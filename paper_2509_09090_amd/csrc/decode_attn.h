@@ -249,7 +249,11 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
             float s = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) s = fmaf(q8[e], kf[e], s);
-            for (int x = 1; x < 16; x <<= 1) s += __shfl_xor(s, x);
+            // the 16 lanes' sum in all of them (quad permutes, then the mirrors: operand modifiers, no LDS permute)
+            s += dpp_move_f<kDppXor1>(s);
+            s += dpp_move_f<kDppXor2>(s);
+            s += dpp_move_f<kDppHalfMirror>(s);
+            s += dpp_move_f<kDppMirror>(s);
             sj[j] = 16 * j + grp < n ? s * inv_sqrt_d : -INFINITY;
             mx = fmaxf(mx, sj[j]);
         }
@@ -263,8 +267,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
                 if (key == past && col_ok) vlate[j] = lds_load16(vnew + c * 8);
             }
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = fmaxf(fmaxf(row_value(mx, 0), row_value(mx, 1)), fmaxf(row_value(mx, 2), row_value(mx, 3)));      // (the same in a group's lanes)
         if (lane == 0 && wave < 4) wred[parity * 4 + wave] = mx;
         sync();                                        // (the other parity's maxima were read before the barrier of the chunk before)
         const float m_new = fmaxf(m, fmaxf(fmaxf(wred[parity * 4], wred[parity * 4 + 1]), fmaxf(wred[parity * 4 + 2], wred[parity * 4 + 3])));
@@ -288,8 +291,7 @@ __device__ __forceinline__ void decode_attention_head(DecodeAttnLds &lds, int h,
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] = fmaf(pj, vf[e], o[e]);
         }
-        psum += __shfl_xor(psum, 16);                  // the four groups of the wavefront
-        psum += __shfl_xor(psum, 32);
+        psum = (row_value(psum, 0) + row_value(psum, 1)) + (row_value(psum, 2) + row_value(psum, 3));       // the four groups of the wavefront
         l_wave = l_wave * rescale + psum;
     }
     if (lane == 0 && wave < 4) wred[8 + wave] = l_wave;

@@ -207,18 +207,6 @@ __device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long 
     }
 }
 
-// Reductions over the wavefront with data-parallel-primitive moves instead of LDS permutes: inside a row of
-// 16 lanes the partner is reached by quad permutes (xor 1, xor 2) and the two mirrors (7 - i within 8 lanes,
-// 15 - i within 16), each a modifier on the instruction's operand, so after four steps every lane of a row
-// holds the row's result; the four rows are read out as scalars.  A step costs a few cycles against the
-// LDS round trip of a permute.
-template <int CTRL>
-__device__ __forceinline__ unsigned dpp_move(unsigned v)
-{
-    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
-
 // the wavefront's maximum of non-negative values, in every lane
 __device__ __forceinline__ float wave_max(float v)
 {
