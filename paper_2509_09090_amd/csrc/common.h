@@ -216,4 +216,15 @@ __device__ __forceinline__ float row_value(float v, int row)
     return __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(v), 16 * row));
 }
 
+// The sum of an integer over the four rows of 16 lanes (lanes l, l + 16, l + 32, l + 48), in every lane: the
+// upper 32 lanes are exchanged with the lower (v_permlane32_swap), then the odd rows with the even
+// (v_permlane16_swap); two vector-ALU instructions each, no LDS permute.
+__device__ __forceinline__ int rows_sum(int v)
+{
+    const auto a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    v = (int)a[0] + (int)a[1];
+    const auto b = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (int)b[0] + (int)b[1];
+}
+
 }  // namespace sqap

@@ -708,9 +708,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             int acc = 0;
             int j = share.i0 < share.i1 ? share.i0 / share.Q : 0, q = share.i0 < share.i1 ? share.i0 - j * share.Q : 0;
             auto flush = [&]() {
-                int sum = acc;
-                sum += __shfl_xor(sum, 16);
-                sum += __shfl_xor(sum, 32);
+                const int sum = rows_sum(acc);
                 if (lane < 16) lds.partial[j][wave][lane] = sum;
                 acc = 0;
             };
