@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <type_traits>
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
@@ -214,6 +215,48 @@ __device__ __forceinline__ float dpp_move_f(float v) { return __uint_as_float(dp
 __device__ __forceinline__ float row_value(float v, int row)
 {
     return __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)__float_as_uint(v), 16 * row));
+}
+
+// the wavefront's maximum of non-negative values, in every lane
+__device__ __forceinline__ float wavefront_max(float v)
+{
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor1>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor2>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppHalfMirror>(__float_as_uint(v))));
+    v = fmaxf(v, __uint_as_float(dpp_move<kDppMirror>(__float_as_uint(v))));
+    const unsigned b = __float_as_uint(v);
+    const float r0 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 0)), r1 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 16));
+    const float r2 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 32)), r3 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 48));
+    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// the wavefront's 128-bit sum, in every lane
+__device__ __forceinline__ void wave_sum128(unsigned long long &hi, unsigned long long &lo)
+{
+    auto step = [&](auto ctrl_c) {
+        constexpr int CTRL = decltype(ctrl_c)::value;
+        const unsigned long long olo = (unsigned long long)dpp_move<CTRL>((unsigned)lo) | ((unsigned long long)dpp_move<CTRL>((unsigned)(lo >> 32)) << 32);
+        const unsigned long long ohi = (unsigned long long)dpp_move<CTRL>((unsigned)hi) | ((unsigned long long)dpp_move<CTRL>((unsigned)(hi >> 32)) << 32);
+        lo += olo;
+        hi += ohi + (lo < olo ? 1ull : 0ull);
+    };
+    step(std::integral_constant<int, kDppXor1>{});
+    step(std::integral_constant<int, kDppXor2>{});
+    step(std::integral_constant<int, kDppHalfMirror>{});
+    step(std::integral_constant<int, kDppMirror>{});
+    auto lane64 = [](unsigned long long v, int l) {
+        return (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, l) |
+               ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), l) << 32);
+    };
+    unsigned long long h = lane64(hi, 0), l = lane64(lo, 0);
+#pragma unroll
+    for (int r = 1; r < 4; ++r) {
+        const unsigned long long ol = lane64(lo, 16 * r);
+        l += ol;
+        h += lane64(hi, 16 * r) + (l < ol ? 1ull : 0ull);
+    }
+    hi = h;
+    lo = l;
 }
 
 // The sum of an integer over the four rows of 16 lanes (lanes l, l + 16, l + 32, l + 48), in every lane: the

@@ -207,48 +207,6 @@ __device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long 
     }
 }
 
-// the wavefront's maximum of non-negative values, in every lane
-__device__ __forceinline__ float wave_max(float v)
-{
-    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor1>(__float_as_uint(v))));
-    v = fmaxf(v, __uint_as_float(dpp_move<kDppXor2>(__float_as_uint(v))));
-    v = fmaxf(v, __uint_as_float(dpp_move<kDppHalfMirror>(__float_as_uint(v))));
-    v = fmaxf(v, __uint_as_float(dpp_move<kDppMirror>(__float_as_uint(v))));
-    const unsigned b = __float_as_uint(v);
-    const float r0 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 0)), r1 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 16));
-    const float r2 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 32)), r3 = __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)b, 48));
-    return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
-}
-
-// the wavefront's 128-bit sum, in every lane
-__device__ __forceinline__ void wave_sum128(unsigned long long &hi, unsigned long long &lo)
-{
-    auto step = [&](auto ctrl_c) {
-        constexpr int CTRL = decltype(ctrl_c)::value;
-        const unsigned long long olo = (unsigned long long)dpp_move<CTRL>((unsigned)lo) | ((unsigned long long)dpp_move<CTRL>((unsigned)(lo >> 32)) << 32);
-        const unsigned long long ohi = (unsigned long long)dpp_move<CTRL>((unsigned)hi) | ((unsigned long long)dpp_move<CTRL>((unsigned)(hi >> 32)) << 32);
-        lo += olo;
-        hi += ohi + (lo < olo ? 1ull : 0ull);
-    };
-    step(std::integral_constant<int, kDppXor1>{});
-    step(std::integral_constant<int, kDppXor2>{});
-    step(std::integral_constant<int, kDppHalfMirror>{});
-    step(std::integral_constant<int, kDppMirror>{});
-    auto lane64 = [](unsigned long long v, int l) {
-        return (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, l) |
-               ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), l) << 32);
-    };
-    unsigned long long h = lane64(hi, 0), l = lane64(lo, 0);
-#pragma unroll
-    for (int r = 1; r < 4; ++r) {
-        const unsigned long long ol = lane64(lo, 16 * r);
-        l += ol;
-        h += lane64(hi, 16 * r) + (l < ol ? 1ull : 0ull);
-    }
-    hi = h;
-    lo = l;
-}
-
 // r from the eight wavefronts' sums (hi, lo pairs)
 __device__ __forceinline__ float norm_factor(const unsigned long long *wsum, int K, float eps)
 {
@@ -612,7 +570,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     lds.wsum[2 * wave + 1] = lo;
                 }
             } else {
-                amax = wave_max(amax);
+                amax = wavefront_max(amax);
                 if (lane == 0) lds.wmax[wave] = amax;
             }
             if (__any((bad >> 16) != 0) && lane == 0) lds.stale[attempt & 1] = 1;
@@ -649,7 +607,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     }
                 }
             }
-            amax = wave_max(amax);
+            amax = wavefront_max(amax);
             if (lane == 0) lds.wmax[wave] = amax;
             lds_barrier();
         }

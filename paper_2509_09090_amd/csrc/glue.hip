@@ -532,7 +532,7 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(const __half *__r
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(f[e]));
     }
-    for (int x = 32; x > 0; x >>= 1) amax = fmaxf(amax, __shfl_xor(amax, x));
+    amax = wavefront_max(amax);
     if (lane == 0) wred[wave] = amax;
     __syncthreads();
     amax = fmaxf(fmaxf(wred[0], wred[1]), fmaxf(wred[2], wred[3]));

@@ -203,11 +203,7 @@ __device__ __forceinline__ void norm_row(float (&v)[GPT][8], int row, int K, con
             }
         }
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long ohi = __shfl_xor(hi, o), olo = __shfl_xor(lo, o);
-        lo += olo;
-        hi += ohi + (lo < olo ? 1ull : 0ull);
-    }
+    wave_sum128(hi, lo);
     if (lane == 0) {
         wsum[2 * wave] = hi;
         wsum[2 * wave + 1] = lo;
@@ -353,7 +349,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const __half *X, int
     for (int gi = 0; gi < GPT; ++gi)
 #pragma unroll
         for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
-    for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    amax = wavefront_max(amax);
     if (lane == 0) wave_max[wave] = amax;
     __syncthreads();
     amax = fmaxf(fmaxf(wave_max[0], wave_max[1]), fmaxf(wave_max[2], wave_max[3]));
@@ -423,7 +419,7 @@ __global__ __launch_bounds__(256) void quantize_row_pairs_kernel(const __half *_
         for (int gi = 0; gi < GPT; ++gi)
 #pragma unroll
             for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[gi][e]));
-        for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+        amax = wavefront_max(amax);
         if (lane == 0) wave_max[r][wave] = amax;
         __syncthreads();
         amax = fmaxf(fmaxf(wave_max[r][0], wave_max[r][1]), fmaxf(wave_max[r][2], wave_max[r][3]));
