@@ -566,7 +566,8 @@ sqap_status sqap_group_free(sqap_group *g);
  *
  * The handle owns the device memory of the rows in flight (4 * (7 hidden + ffn) bytes per layer) and of the
  * workgroups' progress flags; the weights, gains and caches are captured by address and must outlive it.  One step at a time per decoder (steps are
- * ordered on one stream).  logits: [vocab] halves.  attn_trace: NULL, or [n_layers, hidden] halves that
+ * ordered on one stream).  A step writes row `past` of every layer's cache: the caller makes sure that
+ * past < capacity (the library does not know the caches' sizes).  logits: [vocab] halves.  attn_trace: NULL, or [n_layers, hidden] halves that
  * receive every layer's attention output (tests feed it to the reference).  The kernel needs all its 256
  * workgroups resident at once (a device with at least 256 compute units; EUNSUPPORTED otherwise).  A
  * workgroup's wait for another's output that does not end within a second or so gives up: the step's outputs
