@@ -122,7 +122,7 @@ constexpr int kStepStageNew = 10240;                   // word offset of the sta
 struct StepLds {
     __attribute__((aligned(16))) uint8_t xs[kStepMaxK / 2];                       // the linear's input row as int4 codes
     __attribute__((aligned(16))) int partial[kStepMaxGroups][kStepWaves][16];      // per wavefront sums of a group's 16 channels
-    __attribute__((aligned(16))) unsigned swl[kStepMaxGroups * 8];                 // weight scales of the workgroup's channels (pairs)
+    __attribute__((aligned(16))) unsigned swl[2][kStepMaxGroups * 8];              // weight scales of the workgroup's channels (pairs), by phase parity
     unsigned long long wsum[2 * kStepWaves];
     float wmax[kStepWaves];
     float sx;
@@ -503,6 +503,16 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         for (int attempt = 0;; ++attempt) {
             if (glue) {
                 // 1 KiB per instruction, straight into LDS (lane l's 16 bytes land at l * 16: the rows keep their layout)
+                // The weight scales of the workgroup's channels, two per word (padded to whole groups), are not in any
+                // cache yet: asked for now, they arrive while the row is waited for.  (The outputs of the phase
+                // before may still be reading theirs: two places, by phase parity.)
+                if (attempt == 0)
+                    for (int it = 0; it < 2; ++it) {
+                        const int w = lane + 64 * it;
+                        if (w < all.n_groups * 8)
+                            __builtin_amdgcn_global_load_lds((const SQAP_GLOBAL unsigned *)(P.sw + step_group(P, all, w >> 3) * 16 + (w & 7) * 2),
+                                                             (__attribute__((address_space(3))) void *)(&lds.swl[ph & 1][64 * it]), 4, 0, 0);
+                    }
                 if (P.gamma && attempt == 0)
                     for (int g0 = 0; g0 < groups; g0 += 64)
                         if (g0 + lane < groups)
@@ -634,19 +644,6 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
         lds_barrier();
         STEP_STAMP(2);
         if (glue) {
-            // meanwhile: the weight scales of the workgroup's channels, two per word (padded to whole groups)
-            unsigned sc[2] = {};
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int w = lane + 64 * it;
-                if (w < all.n_groups * 8) sc[it] = *(const SQAP_GLOBAL unsigned *)(P.sw + step_group(P, all, w >> 3) * 16 + (w & 7) * 2);
-            }
-#pragma unroll
-            for (int it = 0; it < 2; ++it)
-                if (lane + 64 * it < all.n_groups * 8) lds.swl[lane + 64 * it] = sc[it];
-            // (a wait the compiler can see: otherwise it takes the loads above as possibly in flight wherever the
-            // paths of the wavefronts meet again, and makes the streaming wavefronts wait there)
-            __builtin_amdgcn_s_waitcnt(0x0F70);
             // A workgroup with a head: the cached keys and values it is about to attend over are known since the
             // step began.  One word of every 128-byte line of them is asked for now (and dropped), so that the
             // attention's own loads, which sit in the step's dependency chain, find the lines in the L2 cache.
@@ -723,7 +720,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
                     s0 += lds.partial[j][w][row2];
                     s1 += lds.partial[j][w][row2 + 1];
                 }
-                const unsigned swb = lds.swl[j * 8 + (te & 7)];
+                const unsigned swb = lds.swl[ph & 1][j * 8 + (te & 7)];
                 const __half2 sw2 = *reinterpret_cast<const __half2 *>(&swb);
                 float y0 = ((float)s0 * sxf) * __low2float(sw2), y1 = ((float)s1 * sxf) * __high2float(sw2);
                 asm volatile("" : "+v"(y0), "+v"(y1));            // two binary32 products, then one rounding to half
