@@ -70,6 +70,7 @@ namespace sqap {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
+constexpr int kStepBlocks = 256;           // workgroups: one per compute unit, all resident at once
 constexpr int kStepThreads = 512, kStepWaves = 8;
 constexpr int kStepStreamWaves = 7;        // wavefronts 0 .. 6 stream weights; wavefront 7 reads the rows
 constexpr int kStepGlueWave = 7;
@@ -242,11 +243,14 @@ struct StepShare {
     int Q;                  // items per group = chunks / 4
 };
 
-__device__ __forceinline__ StepShare step_share(const StepPhase &P, int block, int blocks, int wave)
+__device__ __forceinline__ StepShare step_share(const StepPhase &P, int block, int wave)
 {
     StepShare s;
-    s.u0 = (int)((long long)P.units * block / blocks);
-    const int u1 = (int)((long long)P.units * (block + 1) / blocks);
+    // (the number of workgroups is a constant power of two: a shift, where a division by a launch argument would
+    // be some hundred scalar instructions every time a wavefront's stream of pieces changes group)
+    static_assert((kStepBlocks & (kStepBlocks - 1)) == 0, "power of two");
+    s.u0 = (int)(((long long)P.units * block) / kStepBlocks);
+    const int u1 = (int)(((long long)P.units * (block + 1)) / kStepBlocks);
     s.n_groups = (u1 - s.u0) * (P.kind == kStepGateUp ? 2 : 1);
     s.Q = P.chunks >> 2;
     const int total = s.n_groups * s.Q;
@@ -291,7 +295,7 @@ __device__ __forceinline__ void stream_enter(StepStream &c, const StepArgs &a, i
 {
     while (c.ph < a.n_phases) {
         const StepPhase P = load_phase(a.phases, c.ph);
-        const StepShare sh = step_share(P, block, a.blocks, wave);
+        const StepShare sh = step_share(P, block, wave);
         if (sh.i0 < sh.i1) {
             c.i = sh.i0;
             c.i1 = sh.i1;
@@ -323,7 +327,7 @@ __device__ __forceinline__ void stream_issue(StepStream &c, const StepArgs &a, S
     } else if (c.q == c.Q) {                           // the next group of the share
         c.q = 0;
         const StepPhase P = load_phase(a.phases, c.ph);
-        const StepShare sh = step_share(P, block, a.blocks, wave);
+        const StepShare sh = step_share(P, block, wave);
         c.lane_ptr = reinterpret_cast<const uint8_t *>(step_item(P, sh, c.i, lane));
     }
 }
@@ -466,8 +470,8 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
 
     for (int ph = 0; ph < a.n_phases; ++ph) {
         const StepPhase P = load_phase(a.phases, ph);
-        const StepShare share = step_share(P, block, a.blocks, wave);
-        const StepShare all = step_share(P, block, a.blocks, 0);                  // (the group numbers do not depend on the wavefront)
+        const StepShare share = step_share(P, block, wave);
+        const StepShare all = step_share(P, block, 0);                  // (the group numbers do not depend on the wavefront)
         const bool gate_up = P.kind == kStepGateUp;
         const int n_out = gate_up ? all.n_groups >> 1 : all.n_groups;             // groups of 16 outputs
         const int K = P.K, groups = K >> 3;
@@ -792,7 +796,7 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
     // read it.  (One read-modify-write per workgroup and launch.)
     if (t == 0) {
         const unsigned long long before = __hip_atomic_fetch_add(a.done, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((before + 1ull) % (unsigned long long)a.blocks == 0ull)
+        if ((before + 1ull) % (unsigned long long)kStepBlocks == 0ull)
             __hip_atomic_store(a.gen, gen0 + (unsigned long long)(kStepTagsPerLayer * a.n_layers), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
@@ -810,8 +814,6 @@ struct Decoder {
     long long poll_limit;
 };
 constexpr uint32_t kDecoderMagic = 0x53514443u;  // "SQDC"
-constexpr int kStepBlocks = 256;
-
 static const Weight *as_weight(const sqap_weight *w)
 {
     const Weight *ww = reinterpret_cast<const Weight *>(w);
