@@ -685,13 +685,22 @@ __global__ __launch_bounds__(kStepThreads, 1) void decoder_step_kernel(const Ste
             };
             int i = share.i0;
             // first the pieces parked in registers (they are the oldest), then the ring
+            if (park_c == 0) {                         // (the usual case: one comparison per piece)
+                const int left = share.i1 - i, n_use = park_n < left ? park_n : left;
 #pragma unroll
-            for (int dd = 0; dd < kStepPark; ++dd)
-                if (dd >= park_c && dd < park_n && i < share.i1) {
-                    multiply(park[dd]);
-                    ++park_c;
-                    ++i;
-                }
+                for (int dd = 0; dd < kStepPark; ++dd)
+                    if (dd < n_use) multiply(park[dd]);
+                park_c = n_use;
+                i += n_use;
+            } else {
+#pragma unroll
+                for (int dd = 0; dd < kStepPark; ++dd)
+                    if (dd >= park_c && dd < park_n && i < share.i1) {
+                        multiply(park[dd]);
+                        ++park_c;
+                        ++i;
+                    }
+            }
             for (; i < share.i1; ++i) {
                 // The piece to multiply was asked for kStepRing pieces ago (fewer at the very end of the step): it
                 // has landed once at most the younger pieces are still on their way (loads return in order; the
