@@ -186,27 +186,10 @@ __device__ __forceinline__ void store_tagged_pair(unsigned *row, int n, float y0
 }
 
 // ---- the pieces of the fused quantizer kernels' arithmetic, statement by statement ----
-// RMSNorm:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (a half is an integer below 2^11 times 2^e,
-// e >= -24, so x^2 * 2^48 is an integer: the sum does not depend on the order);  r = (float)(1 / sqrt(S / K + eps))
+// RMSNorm:  x' = half(x + delta);  S = sum x'^2 as a 128-bit integer (add_squares8: the sum does not depend on
+// the order);  r = (float)(1 / sqrt(S / K + eps))
 // in binary64;  y = half((x' * r) * gamma).
 // Quantizer:  scale = half(max|y| / 7) (2^-24 when that is zero), code = clamp(rint(y / scale), -8, 7).
-
-// adds the squares of eight half values (times 2^48) to the 128-bit sum hi:lo
-__device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long long &hi, unsigned long long &lo)
-{
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const unsigned bits = __half_as_ushort(__float2half_rn(v[e]));      // exact: v is a half value
-        const unsigned ex = (bits >> 10) & 31u, man = bits & 1023u;
-        const unsigned long long m = ex ? man + 1024u : man;
-        const int sh = ex ? 2 * (int)ex - 2 : 0;                                // 2e + 48, at most 58
-        const unsigned long long m2 = m * m;                                    // below 2^22
-        const unsigned long long add_lo = m2 << sh;
-        const unsigned long long add_hi = sh > 42 ? m2 >> (64 - sh) : 0ull;
-        lo += add_lo;
-        hi += add_hi + (lo < add_lo ? 1ull : 0ull);
-    }
-}
 
 // r from the eight wavefronts' sums (hi, lo pairs)
 __device__ __forceinline__ float norm_factor(const unsigned long long *wsum, int K, float eps)

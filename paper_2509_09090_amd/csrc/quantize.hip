@@ -189,18 +189,7 @@ __device__ __forceinline__ void norm_row(float (&v)[GPT][8], int row, int K, con
                 for (int e = 0; e < 8; ++e) v[gi][e] = round_to_half(v[gi][e] + d[e]);
             }
             if (pre.xsum_out) reinterpret_cast<uint4 *>(pre.xsum_out + (size_t)row * K)[g] = pack8(v[gi]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned bits = __half_as_ushort(__float2half_rn(v[gi][e]));      // exact: v is a half value
-                const unsigned ex = (bits >> 10) & 31u, man = bits & 1023u;
-                const unsigned long long m = ex ? man + 1024u : man;
-                const int sh = ex ? 2 * (int)ex - 2 : 0;                                // 2e + 48, at most 58
-                const unsigned long long m2 = m * m;                                    // below 2^22
-                const unsigned long long add_lo = m2 << sh;
-                const unsigned long long add_hi = sh > 42 ? m2 >> (64 - sh) : 0ull;
-                lo += add_lo;
-                hi += add_hi + (lo < add_lo ? 1ull : 0ull);
-            }
+            add_squares8(v[gi], hi, lo);
         }
     }
     wave_sum128(hi, lo);
