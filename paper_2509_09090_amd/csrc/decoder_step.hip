@@ -216,7 +216,7 @@ __device__ __forceinline__ float norm_factor(const unsigned long long *wsum, int
     // scratch memory, for the whole step)
     float e = eps;
     asm volatile("" : "+v"(e));
-    return (float)(1.0 / sqrt(Sd / (double)K + (double)e));
+    return (float)(1.0 / sqrt(mean_of(Sd, K) + (double)e));
 }
 
 // ---- a workgroup's share of a linear ----

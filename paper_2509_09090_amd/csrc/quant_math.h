@@ -91,4 +91,12 @@ __device__ __forceinline__ void add_squares8(const float (&v)[8], unsigned long 
     }
 }
 
+// S / K in binary64.  For a power of two the quotient is S with a smaller exponent (S is zero or at least 2^-48,
+// so nothing underflows): one instruction instead of the division's forty, the same bits.
+__device__ __forceinline__ double mean_of(double S, int K)
+{
+    if ((K & (K - 1)) == 0) return ldexp(S, -__builtin_ctz((unsigned)K));
+    return S / (double)K;
+}
+
 }  // namespace sqap

@@ -217,7 +217,7 @@ __device__ __forceinline__ void norm_row(float (&v)[GPT][8], int row, int K, con
         Sd = ldexp((double)top, 64 - lz);
     }
     Sd = ldexp(Sd, -48);
-    const float r = (float)(1.0 / sqrt(Sd / (double)K + (double)pre.eps));
+    const float r = (float)(1.0 / sqrt(mean_of(Sd, K) + (double)pre.eps));
 #pragma unroll
     for (int gi = 0; gi < GPT; ++gi) {
         const int g = t + gi * 256;
