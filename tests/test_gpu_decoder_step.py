@@ -67,11 +67,19 @@ def _oracle_step(oracle, host, head_host, gf, x_tok, pos, caches_before, attn_tr
     return states, logits
 
 
-@pytest.mark.parametrize("hidden,H,d,F,L,vocab,S", [(256, 4, 64, 512, 3, 1000, 21),       # most workgroups idle in every phase
-                                                    (1024, 8, 128, 2816, 2, 5008, 40),   # several groups per workgroup, ragged shares
-                                                    (512, 4, 128, 1408, 2, 3008, 300),   # a cache longer than one attention chunk
-                                                    (4096, 32, 128, 11008, 1, 32000, 148)])   # the 7B layer shape and head
-def test_decoder_step_matches_the_oracle_and_the_launch_chain(G, oracle, hidden, H, d, F, L, vocab, S):
+def _wide_token(rng, K):
+    """A token whose elements span thirty binary orders: neighbours differ by more than 2^14 in most groups of
+    eight, which is where the norm's sum of squares leaves its binary64 path."""
+    x = rng.standard_normal((1, K)) * np.exp2(rng.uniform(-20, 10, (1, K)))
+    return np.clip(x, -6e4, 6e4).astype(np.float16)
+
+
+@pytest.mark.parametrize("hidden,H,d,F,L,vocab,S,wide", [(256, 4, 64, 512, 3, 1000, 21, False),       # most workgroups idle in every phase
+                                                         (256, 4, 64, 512, 2, 1000, 9, True),         # tokens of wide dynamic range
+                                                         (1024, 8, 128, 2816, 2, 5008, 40, False),   # several groups per workgroup, ragged shares
+                                                         (512, 4, 128, 1408, 2, 3008, 300, False),   # a cache longer than one attention chunk
+                                                         (4096, 32, 128, 11008, 1, 32000, 148, False)])   # the 7B layer shape and head
+def test_decoder_step_matches_the_oracle_and_the_launch_chain(G, oracle, hidden, H, d, F, L, vocab, S, wide):
     import torch
     from paper_2509_09090_amd import binding as B, decoder
     rng = np.random.default_rng(hidden + L)
@@ -98,7 +106,7 @@ def test_decoder_step_matches_the_oracle_and_the_launch_chain(G, oracle, hidden,
     chain_logits = torch.zeros((1, vocab), dtype=torch.float16, device="cuda")
     past = S
     for step in range(steps):
-        x_tok = _acts(rng, 1, hidden)
+        x_tok = _wide_token(rng, hidden) if wide else _acts(rng, 1, hidden)
         pt = np.array([int(pos[-1]) + 1 + 2 * step], np.int32)
         x_d, p_d = G.to_dev(x_tok), G.to_dev(pt)
         before = [kv.cpu().numpy()[:past].copy() for (_, kv) in dev]
